@@ -1,0 +1,241 @@
+"""ctypes front end of the CPU oracle (oracle/oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+bench's cpu_baseline leg.  The product package never imports this module.
+It marshals numpy arrays into the C functions and holds a host copy of a KV
+pool; it contains no attention arithmetic of its own.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SO = os.path.join(_HERE, "liboracle.so")
+_SRC = os.path.join(_HERE, "oracle.c")
+
+BF16, FP8_E4M3, FP32 = 0, 1, 2
+PAGE, D = 16, 128
+
+
+def build(force: bool = False) -> str:
+    """Compile oracle.c with gcc (double precision, OpenMP over independent rows)."""
+    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+                               "-o", _SO, _SRC, "-lm"])
+    return _SO
+
+
+class _Pool(C.Structure):
+    _fields_ = [("num_pages", C.c_int32), ("num_kv_heads", C.c_int32), ("dtype", C.c_int32),
+                ("k_pages", C.c_void_p), ("v_pages", C.c_void_p),
+                ("k_scale", C.c_void_p), ("v_scale", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        L = C.CDLL(_SO)
+        L.orc_e4m3_value.restype = C.c_double
+        L.orc_e4m3_value.argtypes = [C.c_uint8]
+        L.orc_e4m3_encode.restype = C.c_uint8
+        L.orc_e4m3_encode.argtypes = [C.c_float]
+        L.oracle_num_threads.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    if a is None:
+        return None
+    assert a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _elem_np(dtype: int):
+    return {BF16: np.uint16, FP8_E4M3: np.uint8, FP32: np.float32}[dtype]
+
+
+def _src_dtype(a: np.ndarray) -> int:
+    if a.dtype == np.uint16:
+        return BF16
+    if a.dtype == np.float32:
+        return FP32
+    raise TypeError(f"expected uint16 (bf16 bits) or float32, got {a.dtype}")
+
+
+class HostPool:
+    """Host copy of a KV page pool in the library's documented storage format.
+
+    Unused pages and slots are filled with NaN so that anything read by mistake shows."""
+
+    def __init__(self, num_pages: int, num_kv_heads: int, dtype: int, poison: bool = True):
+        self.num_pages, self.num_kv_heads, self.dtype = num_pages, num_kv_heads, dtype
+        n = num_pages * num_kv_heads * PAGE * D
+        et = _elem_np(dtype)
+        if dtype == BF16:
+            fill = 0x7FC0 if poison else 0
+        elif dtype == FP8_E4M3:
+            fill = 0x7F if poison else 0
+        else:
+            fill = np.nan if poison else 0.0
+        self.k = np.full(n, fill, dtype=et)
+        self.v = np.full(n, fill, dtype=et)
+        self.k_scale = self.v_scale = None
+        if dtype == FP8_E4M3:
+            self.k_scale = np.full(num_pages * num_kv_heads, np.nan if poison else 1.0, dtype=np.float32)
+            self.v_scale = np.full(num_pages * num_kv_heads, np.nan if poison else 1.0, dtype=np.float32)
+
+    def _c(self) -> _Pool:
+        return _Pool(self.num_pages, self.num_kv_heads, self.dtype, _p(self.k), _p(self.v),
+                     _p(self.k_scale), _p(self.v_scale))
+
+    def write(self, page_ids, first_slot: int, k_src: np.ndarray, v_src: np.ndarray) -> None:
+        page_ids = _i32(page_ids)
+        k_src, v_src = np.ascontiguousarray(k_src), np.ascontiguousarray(v_src)
+        n_tokens = k_src.shape[0]
+        assert k_src.shape == v_src.shape == (n_tokens, self.num_kv_heads, D)
+        assert len(page_ids) >= (first_slot + n_tokens + PAGE - 1) // PAGE
+        pc = self._c()
+        rc = lib().oracle_kv_write(C.byref(pc), _p(self.k), _p(self.v), _p(self.k_scale), _p(self.v_scale),
+                                   _p(page_ids), C.c_int32(first_slot), C.c_int32(n_tokens), _p(k_src),
+                                   _p(v_src), C.c_int32(_src_dtype(k_src)))
+        if rc:
+            raise ValueError(f"oracle_kv_write failed: {rc}")
+
+    def fill_from(self, workload) -> None:
+        """Write every node's own tokens into the node's pages."""
+        f = workload.forest
+        for v in range(f.n_nodes):
+            if f.n_tokens[v] == 0:
+                continue
+            k, vv = workload.node_kv(v)
+            self.write(f.node_pages[f.page_begin[v]: f.page_begin[v] + f.n_pages[v]], 0, k, vv)
+
+
+def flatten_tree(nodes, node_pages, req_leaf, max_pages: int):
+    nodes, node_pages, req_leaf = _i32(nodes).reshape(-1, 4), _i32(node_pages), _i32(req_leaf)
+    n_nodes, n_req = nodes.shape[0], req_leaf.shape[0]
+    bt = np.empty((n_req, max_pages), dtype=np.int32)
+    kv_len = np.empty(n_req, dtype=np.int32)
+    indptr = np.empty(n_nodes + 1, dtype=np.int32)
+    idx = np.empty(max(1, n_nodes * max(1, n_req)), dtype=np.int32)
+    tok_start = np.empty(n_nodes, dtype=np.int32)
+    rc = lib().oracle_flatten_tree(_p(nodes), C.c_int32(n_nodes), _p(node_pages), C.c_int32(len(node_pages)),
+                                   _p(req_leaf), C.c_int32(n_req), C.c_int32(max_pages), _p(bt), _p(kv_len),
+                                   _p(indptr), _p(idx), _p(tok_start))
+    if rc:
+        raise ValueError(f"oracle_flatten_tree failed: {rc}")
+    return bt, kv_len, indptr, idx[: indptr[-1]].copy(), tok_start
+
+
+def prefill_usage(nodes, calls) -> np.ndarray:
+    nodes, calls = _i32(nodes).reshape(-1, 4), _i32(calls)
+    out = np.empty(len(calls), dtype=np.int64)
+    rc = lib().oracle_prefill_usage(_p(nodes), C.c_int32(nodes.shape[0]), _p(calls), C.c_int32(len(calls)), _p(out))
+    if rc:
+        raise ValueError(f"oracle_prefill_usage failed: {rc}")
+    return out
+
+
+def attn_decode(pool: HostPool, q: np.ndarray, block_table, kv_len, scale: float,
+                seg: Optional[Tuple[np.ndarray, np.ndarray]] = None):
+    q = np.ascontiguousarray(q)
+    block_table, kv_len = _i32(block_table), _i32(kv_len)
+    n_req, Hq = q.shape[0], q.shape[1]
+    assert q.shape[2] == D and block_table.shape[0] == n_req
+    out = np.empty((n_req, Hq, D), dtype=np.float64)
+    lse = np.empty((n_req, Hq), dtype=np.float64)
+    sb = se = None
+    if seg is not None:
+        sb, se = _i32(seg[0]), _i32(seg[1])
+    pc = pool._c()
+    rc = lib().oracle_attn_decode(C.byref(pc), _p(q), C.c_int32(_src_dtype(q)), _p(block_table),
+                                  C.c_int32(block_table.shape[1]), _p(kv_len), _p(sb), _p(se), C.c_int32(n_req),
+                                  C.c_int32(Hq), C.c_float(scale), _p(out), _p(lse))
+    if rc:
+        raise ValueError(f"oracle_attn_decode failed: {rc}")
+    return out, lse
+
+
+def attn_prefill(pool: HostPool, q: np.ndarray, cu_q, block_table, kv_len, scale: float):
+    q = np.ascontiguousarray(q)
+    cu_q, block_table, kv_len = _i32(cu_q), _i32(block_table), _i32(kv_len)
+    total, Hq = q.shape[0], q.shape[1]
+    n_req = len(kv_len)
+    assert int(cu_q[-1]) == total
+    out = np.empty((total, Hq, D), dtype=np.float64)
+    lse = np.empty((total, Hq), dtype=np.float64)
+    pc = pool._c()
+    rc = lib().oracle_attn_prefill(C.byref(pc), _p(q), C.c_int32(_src_dtype(q)), _p(cu_q), _p(block_table),
+                                   C.c_int32(block_table.shape[1]), _p(kv_len), C.c_int32(n_req), C.c_int32(Hq),
+                                   C.c_float(scale), _p(out), _p(lse))
+    if rc:
+        raise ValueError(f"oracle_attn_prefill failed: {rc}")
+    return out, lse
+
+
+def attn_probs(pool: HostPool, q_row: np.ndarray, pages, kv_len: int, q_head: int, num_q_heads: int, scale: float):
+    """q_row: [Hq][128] of one token; returns the softmax weights over the kv_len tokens."""
+    q_row, pages = np.ascontiguousarray(q_row), _i32(pages)
+    probs = np.empty(kv_len, dtype=np.float64)
+    pc = pool._c()
+    lib().oracle_attn_probs(C.byref(pc), _p(q_row), C.c_int32(_src_dtype(q_row)), _p(pages), C.c_int32(kv_len),
+                            C.c_int32(q_head), C.c_int32(num_q_heads), C.c_float(scale), _p(probs))
+    return probs
+
+
+def lse_merge(o_parts, lse_parts, row_indptr, part_idx):
+    o_parts = np.ascontiguousarray(o_parts, dtype=np.float64)
+    lse_parts = np.ascontiguousarray(lse_parts, dtype=np.float64)
+    row_indptr, part_idx = _i32(row_indptr), _i32(part_idx)
+    n_rows = len(row_indptr) - 1
+    out = np.empty((n_rows, D), dtype=np.float64)
+    lse = np.empty(n_rows, dtype=np.float64)
+    lib().oracle_lse_merge(_p(o_parts), _p(lse_parts), _p(row_indptr), _p(part_idx), C.c_int32(n_rows), _p(out), _p(lse))
+    return out, lse
+
+
+def e4m3_value(code: int) -> float:
+    return float(lib().orc_e4m3_value(C.c_uint8(code)))
+
+
+def e4m3_encode(x: float) -> int:
+    return int(lib().orc_e4m3_encode(C.c_float(x)))
+
+
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())
+
+
+def flatten_workload(workload):
+    f = workload.forest
+    mp = max(1, f.max_pages_per_req())
+    return flatten_tree(f.nodes, f.node_pages, f.req_leaf, mp)
+
+
+def run_workload(workload, pool: Optional[HostPool] = None, req_subset=None):
+    """Whole-workload oracle result (out, lse).  req_subset (decode only) restricts to some requests."""
+    if pool is None:
+        pool = HostPool(workload.num_pages, workload.num_kv_heads, workload.kv_dtype)
+        pool.fill_from(workload)
+    bt, kv_len, _, _, _ = flatten_workload(workload)
+    q = workload.q()
+    if workload.mode == "decode":
+        if req_subset is not None:
+            idx = np.asarray(req_subset)
+            return attn_decode(pool, q[idx], bt[idx], kv_len[idx], float(workload.scale))
+        return attn_decode(pool, q, bt, kv_len, float(workload.scale))
+    return attn_prefill(pool, q, workload.cu_q(), bt, kv_len, float(workload.scale))

@@ -1,0 +1,341 @@
+"""Seeded synthetic prefix-forest workloads.
+
+This module only *draws inputs*: tree shapes, page-id permutations and N(0,1)
+tensors rounded to bf16 bit patterns.  It holds none of the attention
+arithmetic, none of the pool-layout indexing and no quantisation: both the
+HIP path and the CPU oracle consume what it returns through their own code.
+
+The shapes mirror the prompt structure the paper schedules (a static system
+prompt at the root, a per-query context below it, a per-operator suffix at
+the leaf: the templated radix tree of Section 5 and the nested sequences of
+Algorithm 1) with Llama-3 / Qwen3 class grouped-query head shapes
+(Section 7.1, "Models and Testbed").  No dataset item is reproduced; every
+tensor is drawn from a fixed-seed generator.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+PAGE_SIZE = 16
+HEAD_DIM = 128
+BASE_SEED = 20260316
+
+KV_BF16 = 0
+KV_FP8_E4M3 = 1
+KV_FP32 = 2
+
+BF16_NAN_BITS = 0x7FC0
+FP8_NAN_BITS = 0x7F
+
+
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round float32 to bfloat16 (round-to-nearest-even), returned as uint16 bit patterns."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    r = (u + np.uint32(0x7FFF) + lsb) >> np.uint32(16)
+    return r.astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    """Widen bfloat16 bit patterns (uint16) to float32 exactly."""
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+@dataclass
+class PrefixForest:
+    """Call-level prefix forest: node v holds the tokens of its own prompt segment
+    (omega(v) = n_tokens[v]); a request's sequence is the concatenation along root->leaf."""
+
+    parent: np.ndarray       # int32 [n_nodes], -1 for a root; parents precede children
+    n_tokens: np.ndarray     # int32 [n_nodes]
+    page_begin: np.ndarray   # int32 [n_nodes], offset of the node's first page in node_pages
+    n_pages: np.ndarray      # int32 [n_nodes] = ceil(n_tokens / 16)
+    node_pages: np.ndarray   # int32 [sum n_pages], pool page ids
+    req_leaf: np.ndarray     # int32 [n_req]
+
+    @property
+    def n_nodes(self) -> int:
+        return int(self.parent.shape[0])
+
+    @property
+    def n_req(self) -> int:
+        return int(self.req_leaf.shape[0])
+
+    @property
+    def nodes(self) -> np.ndarray:
+        """[n_nodes][4] int32 rows (parent, page_begin, n_pages, n_tokens)."""
+        return np.ascontiguousarray(
+            np.stack([self.parent, self.page_begin, self.n_pages, self.n_tokens], axis=1), dtype=np.int32
+        )
+
+    def path(self, leaf: int) -> List[int]:
+        out = []
+        v = int(leaf)
+        while v >= 0:
+            out.append(v)
+            v = int(self.parent[v])
+        return out[::-1]
+
+    def kv_len(self, r: int) -> int:
+        return int(sum(int(self.n_tokens[v]) for v in self.path(int(self.req_leaf[r]))))
+
+    def max_pages_per_req(self) -> int:
+        m = 0
+        for r in range(self.n_req):
+            m = max(m, sum(int(self.n_pages[v]) for v in self.path(int(self.req_leaf[r]))))
+        return m
+
+    def unique_tokens(self) -> int:
+        """Tokens stored once in the pool and reachable from some request."""
+        used = np.zeros(self.n_nodes, dtype=bool)
+        for r in range(self.n_req):
+            for v in self.path(int(self.req_leaf[r])):
+                used[v] = True
+        return int(self.n_tokens[used].sum())
+
+    def attended_tokens(self) -> int:
+        return int(sum(self.kv_len(r) for r in range(self.n_req)))
+
+
+def make_forest(parent: Sequence[int], n_tokens: Sequence[int], req_leaf: Sequence[int],
+                page_ids: np.ndarray) -> PrefixForest:
+    """Lay the nodes' pages out consecutively over the given (already permuted) pool page ids."""
+    parent = np.asarray(parent, dtype=np.int32)
+    n_tokens = np.asarray(n_tokens, dtype=np.int32)
+    n_pages = ((n_tokens + (PAGE_SIZE - 1)) // PAGE_SIZE).astype(np.int32)
+    page_begin = np.zeros_like(n_pages)
+    if len(n_pages):
+        page_begin[1:] = np.cumsum(n_pages)[:-1]
+    total = int(n_pages.sum())
+    if total > len(page_ids):
+        raise ValueError(f"forest needs {total} pages, only {len(page_ids)} given")
+    return PrefixForest(parent, n_tokens, page_begin.astype(np.int32), n_pages,
+                        np.ascontiguousarray(page_ids[:total], dtype=np.int32),
+                        np.asarray(req_leaf, dtype=np.int32))
+
+
+@dataclass
+class Workload:
+    name: str
+    num_q_heads: int
+    num_kv_heads: int
+    kv_dtype: int
+    num_pages: int
+    seed: int
+    forest: PrefixForest
+    mode: str                      # "decode" or "prefill"
+    q_len: Optional[np.ndarray] = None   # prefill: int32 [n_req] new tokens (= leaf n_tokens)
+    src_dtype: str = "bf16"        # dtype of Q and of the K/V handed to the pool writer
+    notes: str = ""
+
+    @property
+    def group(self) -> int:
+        return self.num_q_heads // self.num_kv_heads
+
+    @property
+    def scale(self) -> np.float32:
+        return np.float32(1.0 / np.sqrt(np.float32(HEAD_DIM)))
+
+    def _draw(self, tag: Tuple[int, ...], shape) -> np.ndarray:
+        rng = np.random.default_rng([self.seed, *tag])
+        x = rng.standard_normal(size=shape, dtype=np.float32)
+        if self.src_dtype == "fp32":
+            return x
+        return f32_to_bf16_bits(x)
+
+    def node_kv(self, node: int) -> Tuple[np.ndarray, np.ndarray]:
+        """K and V of the node's own tokens, each [n_tokens][Hkv][128] (uint16 bf16 bits or float32)."""
+        n = int(self.forest.n_tokens[node])
+        shape = (n, self.num_kv_heads, HEAD_DIM)
+        return self._draw((1, node), shape), self._draw((2, node), shape)
+
+    def total_q(self) -> int:
+        if self.mode == "decode":
+            return self.forest.n_req
+        return int(self.q_len.sum())
+
+    def cu_q(self) -> np.ndarray:
+        cu = np.zeros(self.forest.n_req + 1, dtype=np.int32)
+        if self.mode == "decode":
+            cu[1:] = np.arange(1, self.forest.n_req + 1)
+        else:
+            cu[1:] = np.cumsum(self.q_len)
+        return cu
+
+    def q(self) -> np.ndarray:
+        """[total_q][Hq][128] query tokens."""
+        return self._draw((3,), (self.total_q(), self.num_q_heads, HEAD_DIM))
+
+    def kv_bytes_per_token(self) -> int:
+        es = {KV_BF16: 2, KV_FP8_E4M3: 1, KV_FP32: 4}[self.kv_dtype]
+        return 2 * self.num_kv_heads * HEAD_DIM * es
+
+    def unique_kv_bytes(self) -> int:
+        return self.forest.unique_tokens() * self.kv_bytes_per_token()
+
+    def pair_count(self) -> int:
+        """Causally visible (query token, key token) pairs, per q-head."""
+        f = self.forest
+        if self.mode == "decode":
+            return f.attended_tokens()
+        tot = 0
+        for r in range(f.n_req):
+            s = int(self.q_len[r])
+            p = f.kv_len(r) - s
+            tot += s * p + s * (s + 1) // 2
+        return tot
+
+    def useful_flop(self) -> int:
+        return 4 * HEAD_DIM * self.num_q_heads * self.pair_count()
+
+
+def _perm(seed: int, num_pages: int) -> np.ndarray:
+    return np.random.default_rng([seed, 0]).permutation(num_pages).astype(np.int32)
+
+
+def config1(seed: int = BASE_SEED + 1) -> Tuple[Workload, Workload]:
+    """Tiny prefix tree: returns (prefill workload, decode workload) over the same pool pages.
+
+    root 256 tokens -> 4 private branches of 32 -> 4 new-token segments of 16 (prefilled)
+    -> 4 single decode tokens, each alone in a fresh page.
+    """
+    parent = [-1] + [0] * 4 + [1, 2, 3, 4] + [5, 6, 7, 8]
+    ntok = [256] + [32] * 4 + [16] * 4 + [1] * 4
+    pages = _perm(seed, 128)
+    f_dec = make_forest(parent, ntok, [9, 10, 11, 12], pages)
+    f_pre = make_forest(parent[:9], ntok[:9], [5, 6, 7, 8], pages)
+    common = dict(num_q_heads=8, num_kv_heads=2, kv_dtype=KV_BF16, num_pages=128, seed=seed)
+    pre = Workload(name="c1_tiny_prefill", forest=f_pre, mode="prefill",
+                   q_len=np.full(4, 16, dtype=np.int32), **common)
+    dec = Workload(name="c1_tiny_decode", forest=f_dec, mode="decode", **common)
+    return pre, dec
+
+
+def _pool_pages(n_used: int) -> int:
+    return int(n_used + n_used // 4)
+
+
+def config2(seed: int = BASE_SEED + 2, n_req: int = 64, root_tokens: int = 2048,
+            private_tokens: int = 512) -> Workload:
+    """Llama-3-8B-shaped decode: one shared system-prompt root, one private context per request."""
+    parent = [-1] + [0] * n_req
+    ntok = [root_tokens] + [private_tokens] * n_req
+    n_used = sum((t + 15) // 16 for t in ntok)
+    num_pages = _pool_pages(n_used)
+    f = make_forest(parent, ntok, list(range(1, n_req + 1)), _perm(seed, num_pages))
+    return Workload(name="c2_llama8b_decode", num_q_heads=32, num_kv_heads=8, kv_dtype=KV_BF16,
+                    num_pages=num_pages, seed=seed, forest=f, mode="decode")
+
+
+def config3(seed: int = BASE_SEED + 3) -> Workload:
+    """Speculative fan-out tree: 4096 -> 8 x 1024 -> 128 x 256."""
+    parent = [-1] + [0] * 8
+    ntok = [4096] + [1024] * 8
+    leaves = []
+    for c in range(8):
+        for _ in range(16):
+            parent.append(1 + c)
+            ntok.append(256)
+            leaves.append(len(parent) - 1)
+    n_used = sum((t + 15) // 16 for t in ntok)
+    num_pages = _pool_pages(n_used)
+    f = make_forest(parent, ntok, leaves, _perm(seed, num_pages))
+    return Workload(name="c3_fanout_decode", num_q_heads=32, num_kv_heads=8, kv_dtype=KV_BF16,
+                    num_pages=num_pages, seed=seed, forest=f, mode="decode")
+
+
+def config4(seed: int = BASE_SEED + 4, n_req: int = 32, prefix_tokens: int = 8192,
+            lo: int = 768, hi: int = 1024) -> Workload:
+    """Prefix-hit prefill: every request prefills s_r ~ U{lo..hi} new tokens over a shared cached prefix."""
+    s = np.random.default_rng([seed, 7]).integers(lo, hi + 1, size=n_req).astype(np.int32)
+    parent = [-1] + [0] * n_req
+    ntok = [prefix_tokens] + [int(x) for x in s]
+    n_used = sum((t + 15) // 16 for t in ntok)
+    num_pages = _pool_pages(n_used)
+    f = make_forest(parent, ntok, list(range(1, n_req + 1)), _perm(seed, num_pages))
+    return Workload(name="c4_prefix_hit_prefill", num_q_heads=32, num_kv_heads=8, kv_dtype=KV_BF16,
+                    num_pages=num_pages, seed=seed, forest=f, mode="prefill", q_len=s)
+
+
+def config5(seed: int = BASE_SEED + 5, n_roots: int = 16, children: int = 32,
+            root_tokens: int = 8192, child_tokens: int = 2048) -> Workload:
+    """Large forest, 70B-shaped layer, KV stored as fp8 e4m3 with per-page per-head scales."""
+    parent, ntok, leaves = [], [], []
+    for _ in range(n_roots):
+        parent.append(-1)
+        ntok.append(root_tokens)
+    for r in range(n_roots):
+        for _ in range(children):
+            parent.append(r)
+            ntok.append(child_tokens)
+            leaves.append(len(parent) - 1)
+    n_used = sum((t + 15) // 16 for t in ntok)
+    num_pages = _pool_pages(n_used)
+    f = make_forest(parent, ntok, leaves, _perm(seed, num_pages))
+    return Workload(name="c5_forest_fp8_decode", num_q_heads=64, num_kv_heads=8, kv_dtype=KV_FP8_E4M3,
+                    num_pages=num_pages, seed=seed, forest=f, mode="decode")
+
+
+def random_forest_workload(seed: int, *, n_roots: int = 2, depth: int = 3, fanout: int = 3,
+                           max_node_pages: int = 5, num_q_heads: int = 8, num_kv_heads: int = 2,
+                           kv_dtype: int = KV_BF16, mode: str = "decode", ragged: bool = True,
+                           zero_weight_nodes: bool = True, src_dtype: str = "bf16",
+                           extra_pages: int = 7) -> Workload:
+    """Small random forest for tests: internal nodes are page aligned, leaves may be ragged,
+    and (as in the paper's tree, where the root and the leaves carry no tokens) some nodes are empty."""
+    rng = np.random.default_rng([seed, 11])
+    parent: List[int] = []
+    ntok: List[int] = []
+    leaves: List[int] = []
+
+    def grow(par: int, level: int) -> None:
+        idx = len(parent)
+        parent.append(par)
+        is_leaf = level == depth - 1 or (level > 0 and rng.random() < 0.25)
+        if is_leaf:
+            if zero_weight_nodes and rng.random() < 0.15:
+                t = 0
+            elif ragged:
+                t = int(rng.integers(1, max_node_pages * PAGE_SIZE + 1))
+            else:
+                t = int(rng.integers(1, max_node_pages + 1)) * PAGE_SIZE
+            ntok.append(t)
+            leaves.append(idx)
+            return
+        if zero_weight_nodes and rng.random() < 0.2:
+            ntok.append(0)
+        else:
+            ntok.append(int(rng.integers(1, max_node_pages + 1)) * PAGE_SIZE)
+        for _ in range(int(rng.integers(1, fanout + 1))):
+            grow(idx, level + 1)
+
+    # Nodes must be parent-first: grow() appends a node before its children.
+    for _ in range(n_roots):
+        grow(-1, 0)
+    # Some requests may stop at an internal (page-aligned) node as well.
+    req_leaf = list(leaves)
+    internal = [v for v in range(len(parent)) if v not in set(leaves)]
+    for v in internal:
+        if rng.random() < 0.3:
+            req_leaf.append(v)
+    order = rng.permutation(len(req_leaf))
+    req_leaf = [req_leaf[i] for i in order]
+    n_used = sum((t + 15) // 16 for t in ntok)
+    num_pages = n_used + extra_pages
+    f = make_forest(parent, ntok, req_leaf, _perm(seed, num_pages))
+    q_len = None
+    if mode == "prefill":
+        # new tokens = the request's last node; everything above it is the cached prefix
+        q_len = np.asarray([ntok[v] for v in req_leaf], dtype=np.int32)
+    return Workload(name=f"random_{seed}", num_q_heads=num_q_heads, num_kv_heads=num_kv_heads,
+                    kv_dtype=kv_dtype, num_pages=num_pages, seed=seed, forest=f, mode=mode,
+                    q_len=q_len, src_dtype=src_dtype)
+
+
+def all_configs():
+    c1p, c1d = config1()
+    return {"c1_prefill": c1p, "c1_decode": c1d, "c2": config2(), "c3": config3(),
+            "c4": config4(), "c5": config5()}
