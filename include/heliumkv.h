@@ -1,0 +1,269 @@
+/*
+ * heliumkv: attention over a paged KV pool whose pages are shared through a prefix forest.
+ *
+ * C ABI of the MI355X (gfx950) library.  Every step behind these calls runs in hand-written
+ * HIP kernels; there is no CPU fallback.  The operations are the GPU side of the proactive KV
+ * caching and cache-aware scheduling of the Helium paper:
+ *   - Section 5, "Proactive Cache Management": the KV cache of a prompt prefix shared by many
+ *     LLM calls is computed once, kept in GPU memory block by block, and reused.
+ *   - Section 5, "Token usage" (equation for u_p): a call processes only the tokens below the
+ *     part of its root-to-leaf path that is already cached.
+ *   - Section 5, templated radix tree T = (V, E, E'): prompts form a prefix tree; omega(v) is
+ *     the number of tokens of node v's own segment and may be zero.
+ *   - Section 2, "Scope": the optimised execution must return what naive execution returns, so
+ *     every result here equals plain softmax attention of a query over its request's whole
+ *     key/value sequence (up to floating-point rounding).
+ *
+ * Conventions
+ *   - Every function returns HKV_OK (0) or a negative HKV_E* code and never throws.
+ *     hkv_last_error() returns a thread-local message for the last failure on this thread.
+ *   - "host" pointers are ordinary CPU memory read during the call; the caller may free or
+ *     reuse them as soon as the call returns.  "device" pointers are HIP device memory of the
+ *     current device, owned by the caller, and must stay valid until the work queued on
+ *     `stream` has finished.  The library never frees caller memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Kernel launches are
+ *     asynchronous on it.  All argument validation happens on the host before anything is
+ *     queued, so a failing call has no effect on device memory.
+ *   - Fixed geometry: page size 16 tokens, head dimension 128.  Anything else is HKV_ESHAPE.
+ *   - Grouped-query attention: query head h reads KV head h / (num_q_heads / num_kv_heads).
+ *
+ * Pool storage format (device memory owned by the caller, layout fixed by this library).
+ *   For page p and KV head h, the K block and the V block each hold 16*128 elements and start
+ *   at element (p*num_kv_heads + h)*2048 of k_pages / v_pages.
+ *     K block: the 128 dimensions are cut into chunks of 64 bytes (C = 64/sizeof(element)
+ *              dimensions: 32 for bf16, 64 for fp8, 16 for fp32); element (slot t, dim d) is at
+ *              (d / C)*16*C + t*C + d % C.
+ *     V block: dimension-major; element (slot t, dim d) is at d*16 + t.
+ *   Both orders hand a 64-lane wavefront its matrix-core operands as 16-byte contiguous loads
+ *   and make every (page, head) block one contiguous 4 KiB (bf16) / 2 KiB (fp8) burst.
+ *   fp8 pools (OCP e4m3, no infinities, max 448) carry k_scale and v_scale, float
+ *   [num_pages][num_kv_heads]; the stored value is code * scale.
+ *   Slots past the end of a sequence and unreferenced pages may hold anything, NaN included.
+ */
+#ifndef HELIUMKV_H
+#define HELIUMKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HKV_PAGE_SIZE 16
+#define HKV_HEAD_DIM 128
+
+enum {
+    HKV_OK = 0,
+    HKV_EINVAL = -1, /* null pointer, negative size, inconsistent lengths */
+    HKV_ERANGE = -2, /* page id, node id or request id outside its range */
+    HKV_ESHAPE = -3, /* unsupported geometry or dtype combination */
+    HKV_ETREE = -4,  /* malformed forest: parent after child, page count != ceil(tokens/16),
+                        node with children whose token count is not a multiple of 16 */
+    HKV_ENOMEM = -5, /* pool exhausted, workspace or output table too small */
+    HKV_EHIP = -6    /* a HIP runtime call failed (message holds the HIP error string) */
+};
+
+enum { HKV_BF16 = 0, HKV_FP8_E4M3 = 1, HKV_FP32 = 2 };
+
+typedef struct hkv_pool hkv_pool;
+typedef struct hkv_decode_plan hkv_decode_plan;
+typedef struct hkv_prefill_plan hkv_prefill_plan;
+
+/* Thread-local text of the last error returned on the calling thread ("" if none). */
+const char *hkv_last_error(void);
+
+/* ------------------------------------------------------------------------------------------
+ * KV page pool (Section 5, "Proactive Cache Management"; Section 6, pinned prefix blocks).
+ * The pool object is host metadata over caller-owned device buffers: a free list, a
+ * reference count per page (the number of holders that pin it) and the buffer addresses.
+ */
+typedef struct {
+    int32_t num_pages;
+    int32_t page_size;    /* must be 16 */
+    int32_t num_kv_heads;
+    int32_t head_dim;     /* must be 128 */
+    int32_t dtype;        /* HKV_BF16 or HKV_FP8_E4M3 */
+    void *k_pages;        /* device, num_pages*num_kv_heads*2048 elements, format above */
+    void *v_pages;        /* device, same size */
+    float *k_scale;       /* device, [num_pages][num_kv_heads]; fp8 pools only, else NULL */
+    float *v_scale;       /* device, same */
+    const int32_t *free_order; /* host, optional permutation of 0..num_pages-1: the order in
+                                  which kv_pool_alloc hands pages out; NULL = ascending */
+} hkv_pool_desc;
+
+/* Creates the host-side pool object.  Borrows the device pointers; copies free_order.
+ * EINVAL: null desc/out or buffers, num_pages <= 0, free_order not a permutation.
+ * ESHAPE: page_size != 16, head_dim != 128, dtype not storable, scales missing for fp8. */
+int kv_pool_create(const hkv_pool_desc *desc, hkv_pool **out);
+
+/* Frees host metadata and any cached plan.  Waits for the device to be idle first if a cached
+ * plan holds device index buffers.  Never touches the caller's page buffers. */
+int kv_pool_destroy(hkv_pool *pool);
+
+/* Pops n pages from the free list in free_order (deterministic), sets their reference count to
+ * 1 and writes their ids to ids_out (host, n entries).  ENOMEM (nothing allocated) if fewer
+ * than n pages are free. */
+int kv_pool_alloc(hkv_pool *pool, int32_t n, int32_t *ids_out);
+
+/* Adds one reference to each listed page (a further request or tree node pins it).
+ * ERANGE: id outside the pool; EINVAL: page not allocated.  Nothing changes on error. */
+int kv_pool_retain(hkv_pool *pool, int32_t n, const int32_t *ids /* host */);
+
+/* Drops one reference from each listed page; a page whose count reaches 0 returns to the
+ * tail of the free list in the order listed.  Errors as kv_pool_retain. */
+int kv_pool_release(hkv_pool *pool, int32_t n, const int32_t *ids /* host */);
+
+/* Number of free pages, or a negative error code. */
+int32_t kv_pool_num_free(const hkv_pool *pool);
+
+/* Reference count of one page (0 = free), or a negative error code. */
+int32_t kv_pool_refcount(const hkv_pool *pool, int32_t page_id);
+
+/* Stores the K/V of n_tokens consecutive tokens of one sequence into the pool: token i goes to
+ * page page_ids[(first_slot + i) / 16], slot (first_slot + i) % 16.  This is the "compute the
+ * prefix KV once and keep it" step seen from the pool.
+ *   page_ids: host, ceil((first_slot + n_tokens)/16) entries (at most 65536).
+ *   k_src, v_src: device, [n_tokens][num_kv_heads][128] bf16.
+ * bf16 pools: plain scatter into the block format.  fp8 pools: first_slot must be 0; every
+ * (page, head) block written gets scale = amax/448 over the tokens written into it by this
+ * call (1 if amax == 0) and code = round-to-nearest-even(x / scale), saturated to +-448, all in
+ * float; a later call that writes the same page recomputes its scale from that call's tokens
+ * only, so fp8 pages are written whole (or as the sequence's last, partial page).
+ * Slots not written keep their contents.  n_tokens == 0 is a no-op.
+ * EINVAL / ERANGE / ESHAPE as above; the ids are checked before anything is queued. */
+int kv_pool_write(hkv_pool *pool, const int32_t *page_ids, int32_t first_slot, int32_t n_tokens,
+                  const void *k_src, const void *v_src, void *stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Prefix forest (the call-level templated radix tree of Section 5: every leaf is one LLM
+ * call, a call's prompt is the concatenation of the token segments on path(root, leaf)).
+ */
+typedef struct {
+    int32_t parent;     /* index of the parent node, -1 for a root; must be < own index */
+    int32_t page_begin; /* offset of this node's first page id in node_pages */
+    int32_t n_pages;    /* == ceil(n_tokens / 16) */
+    int32_t n_tokens;   /* omega(v) >= 0; must be a multiple of 16 if the node has children */
+} hkv_node;
+
+/* Host-only, integer-only.  Expands the forest into what the kernels index with:
+ *   block_table     [n_req][max_pages]  page ids along root -> leaf, padded with -1
+ *   kv_len          [n_req]             sum of n_tokens along the path
+ *   node_req_indptr [n_nodes + 1], node_req_idx [<= n_nodes*n_req]
+ *                                       CSR: the requests whose path contains the node,
+ *                                       ascending request index
+ *   node_tok_start  [n_nodes]           token offset of the node's segment within such a path
+ * Any output pointer may be NULL to skip it.  All pointers are host memory.
+ * ETREE / ERANGE as documented on the codes; ENOMEM if a path needs more than max_pages. */
+int prefix_tree_flatten(const hkv_node *nodes, int32_t n_nodes, const int32_t *node_pages,
+                        int32_t n_node_pages, const int32_t *req_leaf, int32_t n_req, int32_t max_pages,
+                        int32_t *block_table, int32_t *kv_len, int32_t *node_req_indptr,
+                        int32_t *node_req_idx, int32_t *node_tok_start);
+
+/* Prefill token usage u_p of Section 5 for a sequence of calls on one worker: calls[0]
+ * processes every token on path(root, calls[0]); calls[j] only the tokens on the path from the
+ * lowest common ancestor of calls[j-1] and calls[j] (exclusive) down to calls[j].  Host-only.
+ * u_p[j] is the number of new tokens attn_prefill_with_prefix has to be given for call j when
+ * the previous call's pages are still cached. */
+int prefix_tree_prefill_usage(const hkv_node *nodes, int32_t n_nodes, const int32_t *calls,
+                              int32_t n_calls, int64_t *u_p);
+
+/* ------------------------------------------------------------------------------------------
+ * Log-sum-exp combine of partial attention results (natural logarithm).
+ * Output row i owns the partials part_idx[row_indptr[i] .. row_indptr[i+1]):
+ *   lse_i = ln sum_n exp(lse_parts[n]),   out_i = sum_n exp(lse_parts[n] - lse_i) * o_parts[n].
+ * A partial with lse = -inf contributes nothing (its o may hold anything); a row with no
+ * finite partial gives out = 0, lse = -inf.  Never produces NaN from finite inputs.
+ *   o_parts [n_parts][128] float, lse_parts [n_parts] float, row_indptr [n_rows+1] int32,
+ *   part_idx int32: all device.  out: device [n_rows][128] of out_dtype (HKV_BF16, rounded to
+ *   nearest even, or HKV_FP32).  lse_out: device [n_rows] float, may be NULL.
+ * The index arrays are trusted (they live on the device); only the arguments are validated. */
+int lse_merge(const float *o_parts, const float *lse_parts, const int32_t *row_indptr,
+              const int32_t *part_idx, int32_t n_rows, void *out, int32_t out_dtype, float *lse_out,
+              void *stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Batched decode over a prefix forest: one query token per request.  Every node's pages are
+ * read from HBM once and applied to all requests below the node; the per-node partial results
+ * (o, lse) are then combined along each request's path by the kernel behind lse_merge.
+ *
+ * A plan holds the flattened topology (work list, page ids, merge CSR) on host and device so
+ * that a serving loop pays for the tree walk once per topology, not once per step.
+ */
+enum { HKV_PLAN_HOST_ONLY = 1 /* build and validate on the host, allocate nothing on the device */ };
+
+/* nodes, node_pages, req_leaf: host.  Validates the forest (ETREE/ERANGE, page ids against the
+ * pool), builds the work list and uploads it (blocking).  ESHAPE unless num_q_heads is a
+ * multiple of the pool's num_kv_heads with a ratio of at most 16. */
+int hkv_decode_plan_create(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes, const int32_t *node_pages,
+                           int32_t n_node_pages, const int32_t *req_leaf, int32_t n_req, int32_t num_q_heads,
+                           uint32_t flags, hkv_decode_plan **out);
+int hkv_decode_plan_destroy(hkv_decode_plan *plan);
+/* Bytes of device workspace attn_decode_plan_run needs (partial o and lse), 0 on a null plan. */
+size_t hkv_decode_plan_workspace_bytes(const hkv_decode_plan *plan);
+/* Introspection for tests and tools (host copies).  Work item layout, 8 int32 each:
+ * (page_off, n_tokens, kv_head, req_off, n_req, part_base, tok_begin, node).  page_off indexes
+ * the plan's page list (= node_pages), req_off its node->request CSR values. */
+int32_t hkv_decode_plan_num_items(const hkv_decode_plan *plan);
+int32_t hkv_decode_plan_num_parts(const hkv_decode_plan *plan);
+int hkv_decode_plan_items(const hkv_decode_plan *plan, int32_t *items_out /* [n_items][8] */);
+/* Merge CSR over output rows (request*num_q_heads + head): row_indptr [n_req*Hq + 1], part_idx
+ * [row_indptr[last]] (pass NULL to query sizes only via the return of ..._num_merge_entries). */
+int32_t hkv_decode_plan_num_merge_entries(const hkv_decode_plan *plan);
+int hkv_decode_plan_merge_csr(const hkv_decode_plan *plan, int32_t *row_indptr, int32_t *part_idx);
+
+/* Runs one decode step.  q: device [n_req][num_q_heads][128] bf16.  out: device, same shape,
+ * bf16.  lse_out: device [n_req][num_q_heads] float or NULL.  workspace: device, at least
+ * hkv_decode_plan_workspace_bytes(plan) bytes, 256-byte aligned; its contents are scratch.
+ * A request whose path holds no token gets out = 0, lse = -inf.
+ * EINVAL (null/unaligned), ENOMEM (workspace too small), EHIP. */
+int attn_decode_plan_run(hkv_decode_plan *plan, const void *q, float scale, void *out, float *lse_out,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/* One-shot form: plans (or reuses the plan cached in the pool when the forest is unchanged) and
+ * runs.  Same arguments as the two calls above. */
+int attn_decode_prefix_tree(hkv_pool *pool, const void *q, const hkv_node *nodes, int32_t n_nodes,
+                            const int32_t *node_pages, int32_t n_node_pages, const int32_t *req_leaf,
+                            int32_t n_req, int32_t num_q_heads, float scale, void *out, float *lse_out,
+                            void *workspace, size_t workspace_bytes, void *stream);
+/* Workspace bytes the one-shot call needs for this forest (0 on error; see hkv_last_error). */
+size_t attn_decode_workspace_bytes(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes,
+                                   const int32_t *node_pages, int32_t n_node_pages, const int32_t *req_leaf,
+                                   int32_t n_req, int32_t num_q_heads);
+
+/* ------------------------------------------------------------------------------------------
+ * Prefill of the uncached suffix (Section 5, u_p): request r brings s_r = cu_q[r+1] - cu_q[r]
+ * new tokens whose K/V have already been written to the pool (kv_pool_write) at positions
+ * prefix_len_r .. kv_len_r - 1, prefix_len_r = kv_len_r - s_r >= 0.  New token i sits at
+ * absolute position a = prefix_len_r + i and attends keys t <= a of the request's block table:
+ * all cached prefix tokens plus the causal part of its own suffix, itself included.
+ *   cu_q [n_req+1], block_table [n_req][max_pages], kv_len [n_req]: host.  Entries of
+ *   block_table beyond ceil(kv_len/16) are ignored.  ERANGE if a used page id is outside the pool.
+ * ESHAPE unless num_q_heads / num_kv_heads is 1, 2, 4 or 8.
+ */
+int hkv_prefill_plan_create(hkv_pool *pool, const int32_t *cu_q, const int32_t *block_table, int32_t max_pages,
+                            const int32_t *kv_len, int32_t n_req, int32_t num_q_heads, uint32_t flags,
+                            hkv_prefill_plan **out);
+int hkv_prefill_plan_destroy(hkv_prefill_plan *plan);
+/* Number of (request, query tile, kv head) workgroups the plan launches. */
+int32_t hkv_prefill_plan_num_tiles(const hkv_prefill_plan *plan);
+/* Tile layout for tests, 8 int32 each: (req, q_begin, n_q, kv_head, q_row0, prefix_len, kv_len, bt_off). */
+int hkv_prefill_plan_tiles(const hkv_prefill_plan *plan, int32_t *tiles_out);
+
+/* q: device [cu_q[n_req]][num_q_heads][128] bf16; out: device, same shape, bf16; lse_out: device
+ * [cu_q[n_req]][num_q_heads] float or NULL. */
+int attn_prefill_plan_run(hkv_prefill_plan *plan, const void *q, float scale, void *out, float *lse_out,
+                          void *stream);
+
+/* One-shot form; workspace may be NULL (attn_prefill_workspace_bytes is 0 in this version: a
+ * query tile reads its whole key range itself). */
+int attn_prefill_with_prefix(hkv_pool *pool, const void *q, const int32_t *cu_q, const int32_t *block_table,
+                             int32_t max_pages, const int32_t *kv_len, int32_t n_req, int32_t num_q_heads,
+                             float scale, void *out, float *lse_out, void *workspace, size_t workspace_bytes,
+                             void *stream);
+size_t attn_prefill_workspace_bytes(int32_t total_q, int32_t num_q_heads);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HELIUMKV_H */

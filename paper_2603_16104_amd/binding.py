@@ -1,0 +1,283 @@
+"""Thin ctypes binding of libheliumkv.so: argument marshalling only.
+
+Function names match the C ABI in include/heliumkv.h.  Device buffers are passed as
+torch tensors (their data_ptr() is used) or as raw integer addresses; host arrays as
+numpy int32 arrays.  Every step of the path runs inside the library's HIP kernels;
+there is no Python or CPU fallback, and loading fails loudly when the library has
+not been built.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libheliumkv.so")
+
+OK, EINVAL, ERANGE, ESHAPE, ETREE, ENOMEM, EHIP = 0, -1, -2, -3, -4, -5, -6
+BF16, FP8_E4M3, FP32 = 0, 1, 2
+PLAN_HOST_ONLY = 1
+PAGE_SIZE, HEAD_DIM = 16, 128
+
+EXPORTS = [
+    "hkv_last_error", "kv_pool_create", "kv_pool_destroy", "kv_pool_alloc", "kv_pool_retain", "kv_pool_release",
+    "kv_pool_num_free", "kv_pool_refcount", "kv_pool_write", "prefix_tree_flatten", "prefix_tree_prefill_usage",
+    "lse_merge", "hkv_decode_plan_create", "hkv_decode_plan_destroy", "hkv_decode_plan_workspace_bytes",
+    "hkv_decode_plan_num_items", "hkv_decode_plan_num_parts", "hkv_decode_plan_items",
+    "hkv_decode_plan_num_merge_entries", "hkv_decode_plan_merge_csr", "attn_decode_plan_run",
+    "attn_decode_prefix_tree", "attn_decode_workspace_bytes", "hkv_prefill_plan_create", "hkv_prefill_plan_destroy",
+    "hkv_prefill_plan_num_tiles", "hkv_prefill_plan_tiles", "attn_prefill_plan_run", "attn_prefill_with_prefix",
+    "attn_prefill_workspace_bytes",
+]
+
+
+class HkvError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"heliumkv error {code}: {msg}")
+        self.code = code
+
+
+class PoolDesc(C.Structure):
+    _fields_ = [("num_pages", C.c_int32), ("page_size", C.c_int32), ("num_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("dtype", C.c_int32), ("k_pages", C.c_void_p), ("v_pages", C.c_void_p),
+                ("k_scale", C.c_void_p), ("v_scale", C.c_void_p), ("free_order", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib():
+    """Loads the built library; raises if it is missing (build it with __graft_entry__.build())."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build the HIP library first "
+                               "(python -c 'import __graft_entry__ as g; g.build()'); there is no fallback path")
+        L = C.CDLL(LIB_PATH)
+        L.hkv_last_error.restype = C.c_char_p
+        for name in ("hkv_decode_plan_workspace_bytes", "attn_decode_workspace_bytes", "attn_prefill_workspace_bytes"):
+            getattr(L, name).restype = C.c_size_t
+        _lib = L
+    return _lib
+
+
+def last_error() -> str:
+    return lib().hkv_last_error().decode()
+
+
+def _check(rc: int) -> int:
+    if rc < 0:
+        raise HkvError(rc, last_error())
+    return rc
+
+
+def _dev(t) -> C.c_void_p:
+    """Device address of a torch tensor, a raw int address, or None."""
+    if t is None:
+        return C.c_void_p(None)
+    if isinstance(t, int):
+        return C.c_void_p(t)
+    return C.c_void_p(t.data_ptr())
+
+
+def _host_i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _hp(a: Optional[np.ndarray]) -> C.c_void_p:
+    return C.c_void_p(None) if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _stream(stream) -> C.c_void_p:
+    if stream is None:
+        import torch
+        return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return C.c_void_p(stream)
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _nodes(nodes) -> np.ndarray:
+    n = np.ascontiguousarray(nodes, dtype=np.int32).reshape(-1, 4)
+    return n
+
+
+# ----------------------------------------------------------------------------------------- pool
+def kv_pool_create(num_pages: int, num_kv_heads: int, dtype: int, k_pages, v_pages, k_scale=None, v_scale=None,
+                   free_order=None, page_size: int = PAGE_SIZE, head_dim: int = HEAD_DIM) -> C.c_void_p:
+    fo = None if free_order is None else _host_i32(free_order)
+    d = PoolDesc(num_pages, page_size, num_kv_heads, head_dim, dtype, _dev(k_pages), _dev(v_pages), _dev(k_scale),
+                 _dev(v_scale), _hp(fo))
+    out = C.c_void_p()
+    _check(lib().kv_pool_create(C.byref(d), C.byref(out)))
+    return out
+
+
+def kv_pool_destroy(pool) -> None:
+    _check(lib().kv_pool_destroy(pool))
+
+
+def kv_pool_alloc(pool, n: int) -> np.ndarray:
+    ids = np.empty(max(n, 0), dtype=np.int32)
+    _check(lib().kv_pool_alloc(pool, C.c_int32(n), _hp(ids)))
+    return ids
+
+
+def kv_pool_retain(pool, ids) -> None:
+    ids = _host_i32(ids)
+    _check(lib().kv_pool_retain(pool, C.c_int32(len(ids)), _hp(ids)))
+
+
+def kv_pool_release(pool, ids) -> None:
+    ids = _host_i32(ids)
+    _check(lib().kv_pool_release(pool, C.c_int32(len(ids)), _hp(ids)))
+
+
+def kv_pool_num_free(pool) -> int:
+    return _check(lib().kv_pool_num_free(pool))
+
+
+def kv_pool_refcount(pool, page_id: int) -> int:
+    return _check(lib().kv_pool_refcount(pool, C.c_int32(page_id)))
+
+
+def kv_pool_write(pool, page_ids, first_slot: int, n_tokens: int, k_src, v_src, stream=None) -> None:
+    ids = _host_i32(page_ids)
+    need = (first_slot + n_tokens + PAGE_SIZE - 1) // PAGE_SIZE if n_tokens > 0 else 0
+    if len(ids) < need:
+        raise HkvError(EINVAL, f"kv_pool_write: {need} page ids needed, {len(ids)} given")
+    _check(lib().kv_pool_write(pool, _hp(ids), C.c_int32(first_slot), C.c_int32(n_tokens), _dev(k_src), _dev(v_src),
+                               _stream(stream) if n_tokens > 0 else C.c_void_p(None)))
+
+
+# ----------------------------------------------------------------------------------------- forest
+def prefix_tree_flatten(nodes, node_pages, req_leaf, max_pages: int):
+    nodes, node_pages, req_leaf = _nodes(nodes), _host_i32(node_pages), _host_i32(req_leaf)
+    n_nodes, n_req = nodes.shape[0], req_leaf.shape[0]
+    bt = np.empty((n_req, max_pages), dtype=np.int32)
+    kv_len = np.empty(n_req, dtype=np.int32)
+    indptr = np.empty(n_nodes + 1, dtype=np.int32)
+    idx = np.empty(max(1, n_nodes * max(1, n_req)), dtype=np.int32)
+    tok_start = np.empty(n_nodes, dtype=np.int32)
+    _check(lib().prefix_tree_flatten(_hp(nodes), C.c_int32(n_nodes), _hp(node_pages), C.c_int32(len(node_pages)),
+                                     _hp(req_leaf), C.c_int32(n_req), C.c_int32(max_pages), _hp(bt), _hp(kv_len),
+                                     _hp(indptr), _hp(idx), _hp(tok_start)))
+    return bt, kv_len, indptr, idx[: indptr[-1]].copy(), tok_start
+
+
+def prefix_tree_prefill_usage(nodes, calls) -> np.ndarray:
+    nodes, calls = _nodes(nodes), _host_i32(calls)
+    out = np.empty(len(calls), dtype=np.int64)
+    _check(lib().prefix_tree_prefill_usage(_hp(nodes), C.c_int32(nodes.shape[0]), _hp(calls), C.c_int32(len(calls)),
+                                           _hp(out)))
+    return out
+
+
+# ----------------------------------------------------------------------------------------- merge
+def lse_merge(o_parts, lse_parts, row_indptr, part_idx, n_rows: int, out, out_dtype: int, lse_out=None,
+              stream=None) -> None:
+    _check(lib().lse_merge(_dev(o_parts), _dev(lse_parts), _dev(row_indptr), _dev(part_idx), C.c_int32(n_rows),
+                           _dev(out), C.c_int32(out_dtype), _dev(lse_out),
+                           _stream(stream) if n_rows > 0 else C.c_void_p(None)))
+
+
+# ----------------------------------------------------------------------------------------- decode
+def hkv_decode_plan_create(pool, nodes, node_pages, req_leaf, num_q_heads: int, flags: int = 0) -> C.c_void_p:
+    nodes, node_pages, req_leaf = _nodes(nodes), _host_i32(node_pages), _host_i32(req_leaf)
+    out = C.c_void_p()
+    _check(lib().hkv_decode_plan_create(pool, _hp(nodes), C.c_int32(nodes.shape[0]), _hp(node_pages),
+                                        C.c_int32(len(node_pages)), _hp(req_leaf), C.c_int32(len(req_leaf)),
+                                        C.c_int32(num_q_heads), C.c_uint32(flags), C.byref(out)))
+    return out
+
+
+def hkv_decode_plan_destroy(plan) -> None:
+    _check(lib().hkv_decode_plan_destroy(plan))
+
+
+def hkv_decode_plan_workspace_bytes(plan) -> int:
+    return int(lib().hkv_decode_plan_workspace_bytes(plan))
+
+
+def hkv_decode_plan_items(plan) -> np.ndarray:
+    n = _check(lib().hkv_decode_plan_num_items(plan))
+    items = np.empty((n, 8), dtype=np.int32)
+    _check(lib().hkv_decode_plan_items(plan, _hp(items)))
+    return items
+
+
+def hkv_decode_plan_num_parts(plan) -> int:
+    return _check(lib().hkv_decode_plan_num_parts(plan))
+
+
+def hkv_decode_plan_merge_csr(plan, n_rows: int):
+    n = _check(lib().hkv_decode_plan_num_merge_entries(plan))
+    indptr = np.empty(n_rows + 1, dtype=np.int32)
+    idx = np.empty(n, dtype=np.int32)
+    _check(lib().hkv_decode_plan_merge_csr(plan, _hp(indptr), _hp(idx)))
+    return indptr, idx
+
+
+def attn_decode_plan_run(plan, q, scale: float, out, lse_out, workspace, workspace_bytes: int, stream=None) -> None:
+    _check(lib().attn_decode_plan_run(plan, _dev(q), C.c_float(scale), _dev(out), _dev(lse_out), _dev(workspace),
+                                      C.c_size_t(workspace_bytes), _stream(stream)))
+
+
+def attn_decode_prefix_tree(pool, q, nodes, node_pages, req_leaf, num_q_heads: int, scale: float, out, lse_out,
+                            workspace, workspace_bytes: int, stream=None) -> None:
+    nodes, node_pages, req_leaf = _nodes(nodes), _host_i32(node_pages), _host_i32(req_leaf)
+    _check(lib().attn_decode_prefix_tree(pool, _dev(q), _hp(nodes), C.c_int32(nodes.shape[0]), _hp(node_pages),
+                                         C.c_int32(len(node_pages)), _hp(req_leaf), C.c_int32(len(req_leaf)),
+                                         C.c_int32(num_q_heads), C.c_float(scale), _dev(out), _dev(lse_out),
+                                         _dev(workspace), C.c_size_t(workspace_bytes), _stream(stream)))
+
+
+def attn_decode_workspace_bytes(pool, nodes, node_pages, req_leaf, num_q_heads: int) -> int:
+    nodes, node_pages, req_leaf = _nodes(nodes), _host_i32(node_pages), _host_i32(req_leaf)
+    n = int(lib().attn_decode_workspace_bytes(pool, _hp(nodes), C.c_int32(nodes.shape[0]), _hp(node_pages),
+                                              C.c_int32(len(node_pages)), _hp(req_leaf), C.c_int32(len(req_leaf)),
+                                              C.c_int32(num_q_heads)))
+    return n
+
+
+# ----------------------------------------------------------------------------------------- prefill
+def hkv_prefill_plan_create(pool, cu_q, block_table, kv_len, num_q_heads: int, flags: int = 0) -> C.c_void_p:
+    cu_q, kv_len = _host_i32(cu_q), _host_i32(kv_len)
+    bt = _host_i32(block_table).reshape(len(kv_len), -1) if len(kv_len) else _host_i32(block_table).reshape(0, 0)
+    out = C.c_void_p()
+    _check(lib().hkv_prefill_plan_create(pool, _hp(cu_q), _hp(bt), C.c_int32(bt.shape[1] if bt.ndim == 2 else 0),
+                                         _hp(kv_len), C.c_int32(len(kv_len)), C.c_int32(num_q_heads),
+                                         C.c_uint32(flags), C.byref(out)))
+    return out
+
+
+def hkv_prefill_plan_destroy(plan) -> None:
+    _check(lib().hkv_prefill_plan_destroy(plan))
+
+
+def hkv_prefill_plan_tiles(plan) -> np.ndarray:
+    n = _check(lib().hkv_prefill_plan_num_tiles(plan))
+    tiles = np.empty((n, 8), dtype=np.int32)
+    _check(lib().hkv_prefill_plan_tiles(plan, _hp(tiles)))
+    return tiles
+
+
+def attn_prefill_plan_run(plan, q, scale: float, out, lse_out=None, stream=None) -> None:
+    _check(lib().attn_prefill_plan_run(plan, _dev(q), C.c_float(scale), _dev(out), _dev(lse_out), _stream(stream)))
+
+
+def attn_prefill_with_prefix(pool, q, cu_q, block_table, kv_len, num_q_heads: int, scale: float, out, lse_out=None,
+                             workspace=None, workspace_bytes: int = 0, stream=None) -> None:
+    cu_q, kv_len = _host_i32(cu_q), _host_i32(kv_len)
+    bt = _host_i32(block_table).reshape(len(kv_len), -1) if len(kv_len) else _host_i32(block_table).reshape(0, 0)
+    _check(lib().attn_prefill_with_prefix(pool, _dev(q), _hp(cu_q), _hp(bt), C.c_int32(bt.shape[1]), _hp(kv_len),
+                                          C.c_int32(len(kv_len)), C.c_int32(num_q_heads), C.c_float(scale), _dev(out),
+                                          _dev(lse_out), _dev(workspace), C.c_size_t(workspace_bytes),
+                                          _stream(stream)))
+
+
+def attn_prefill_workspace_bytes(total_q: int, num_q_heads: int) -> int:
+    return int(lib().attn_prefill_workspace_bytes(C.c_int32(total_q), C.c_int32(num_q_heads)))

@@ -1,0 +1,768 @@
+// Host side of the heliumkv C ABI: pool bookkeeping, forest validation and flattening, work
+// planning, argument checks, kernel launches.  All arithmetic on K/V/Q lives in the kernels.
+#include "../../include/heliumkv.h"
+#include "hkv_internal.h"
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <deque>
+#include <new>
+#include <numeric>
+#include <string>
+#include <vector>
+
+using namespace hkv;
+
+// ---------------------------------------------------------------------------------------------
+// errors
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char *fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+int fail_hip(hipError_t e, const char *what) {
+    return fail(HKV_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+#define HKV_HIP(call)                                  \
+    do {                                               \
+        hipError_t e_ = (call);                        \
+        if (e_ != hipSuccess) return fail_hip(e_, #call); \
+    } while (0)
+
+size_t elem_bytes(int dtype) { return dtype == HKV_BF16 ? 2 : dtype == HKV_FP8_E4M3 ? 1 : 4; }
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+int env_int(const char *name, int dflt) {
+    const char *s = getenv(name);
+    if (!s || !*s) return dflt;
+    int v = atoi(s);
+    return v > 0 ? v : dflt;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------
+// opaque objects
+struct hkv_decode_plan {
+    hkv_pool *pool = nullptr;
+    int32_t n_req = 0, num_q_heads = 0, group = 0, n_parts = 0;
+    std::vector<hkv_node> nodes;            // key of the one-shot cache
+    std::vector<int32_t> node_pages, req_leaf;
+    std::vector<DecodeItem> items;
+    std::vector<int32_t> node_req_indptr, node_req_idx, row_indptr, part_idx;
+    // one device allocation holding items | pages | node_req_idx | row_indptr | part_idx
+    void *dev = nullptr;
+    DecodeItem *d_items = nullptr;
+    int32_t *d_pages = nullptr, *d_node_req_idx = nullptr, *d_row_indptr = nullptr, *d_part_idx = nullptr;
+};
+
+struct hkv_prefill_plan {
+    hkv_pool *pool = nullptr;
+    int32_t n_req = 0, num_q_heads = 0, max_pages = 0, total_q = 0;
+    std::vector<int32_t> cu_q, block_table, kv_len;   // key of the one-shot cache
+    std::vector<PrefillTile> tiles;
+    void *dev = nullptr;
+    PrefillTile *d_tiles = nullptr;
+    int32_t *d_block_table = nullptr;
+};
+
+struct hkv_pool {
+    hkv_pool_desc d{};
+    std::vector<int32_t> refcnt;
+    std::deque<int32_t> free_list;
+    // staging of page ids for kv_pool_write
+    static constexpr int kMaxWritePages = 65536;
+    int32_t *h_ids = nullptr;  // pinned host
+    int32_t *d_ids = nullptr;  // device
+    hipEvent_t ids_free = nullptr;
+    bool ids_in_flight = false;
+    hkv_decode_plan *cached_decode = nullptr;
+    hkv_prefill_plan *cached_prefill = nullptr;
+};
+
+// ---------------------------------------------------------------------------------------------
+extern "C" const char *hkv_last_error(void) { return g_err.c_str(); }
+
+// ---------------------------------------------------------------------------------------------
+// pool
+extern "C" int kv_pool_create(const hkv_pool_desc *desc, hkv_pool **out) {
+    if (!desc || !out) return fail(HKV_EINVAL, "kv_pool_create: null argument");
+    *out = nullptr;
+    if (desc->page_size != HKV_PAGE_SIZE || desc->head_dim != HKV_HEAD_DIM)
+        return fail(HKV_ESHAPE, "kv_pool_create: page_size must be 16 and head_dim 128 (got %d, %d)",
+                    desc->page_size, desc->head_dim);
+    if (desc->dtype != HKV_BF16 && desc->dtype != HKV_FP8_E4M3)
+        return fail(HKV_ESHAPE, "kv_pool_create: pool dtype %d is not storable (bf16 or fp8 e4m3)", desc->dtype);
+    if (desc->num_pages <= 0 || desc->num_kv_heads <= 0)
+        return fail(HKV_EINVAL, "kv_pool_create: num_pages and num_kv_heads must be positive");
+    if (!desc->k_pages || !desc->v_pages) return fail(HKV_EINVAL, "kv_pool_create: null page buffer");
+    if (desc->dtype == HKV_FP8_E4M3 && (!desc->k_scale || !desc->v_scale))
+        return fail(HKV_ESHAPE, "kv_pool_create: fp8 pools need k_scale and v_scale");
+    if ((reinterpret_cast<uintptr_t>(desc->k_pages) | reinterpret_cast<uintptr_t>(desc->v_pages)) & 15)
+        return fail(HKV_EINVAL, "kv_pool_create: page buffers must be 16-byte aligned");
+    hkv_pool *p = new (std::nothrow) hkv_pool;
+    if (!p) return fail(HKV_ENOMEM, "kv_pool_create: out of host memory");
+    p->d = *desc;
+    p->d.free_order = nullptr;
+    p->refcnt.assign(desc->num_pages, 0);
+    if (desc->free_order) {
+        std::vector<char> seen(desc->num_pages, 0);
+        for (int i = 0; i < desc->num_pages; ++i) {
+            int32_t id = desc->free_order[i];
+            if (id < 0 || id >= desc->num_pages || seen[id]) {
+                delete p;
+                return fail(HKV_EINVAL, "kv_pool_create: free_order is not a permutation (entry %d = %d)", i, id);
+            }
+            seen[id] = 1;
+            p->free_list.push_back(id);
+        }
+    } else {
+        for (int i = 0; i < desc->num_pages; ++i) p->free_list.push_back(i);
+    }
+    *out = p;
+    return HKV_OK;
+}
+
+extern "C" int kv_pool_destroy(hkv_pool *pool) {
+    if (!pool) return HKV_OK;
+    if (pool->cached_decode) hkv_decode_plan_destroy(pool->cached_decode);
+    if (pool->cached_prefill) hkv_prefill_plan_destroy(pool->cached_prefill);
+    if (pool->ids_free) {
+        (void)hipEventSynchronize(pool->ids_free);
+        (void)hipEventDestroy(pool->ids_free);
+    }
+    if (pool->d_ids) (void)hipFree(pool->d_ids);
+    if (pool->h_ids) (void)hipHostFree(pool->h_ids);
+    delete pool;
+    return HKV_OK;
+}
+
+extern "C" int kv_pool_alloc(hkv_pool *pool, int32_t n, int32_t *ids_out) {
+    if (!pool || n < 0 || (n > 0 && !ids_out)) return fail(HKV_EINVAL, "kv_pool_alloc: bad argument");
+    if ((size_t)n > pool->free_list.size())
+        return fail(HKV_ENOMEM, "kv_pool_alloc: %d pages requested, %zu free", n, pool->free_list.size());
+    for (int i = 0; i < n; ++i) {
+        int32_t id = pool->free_list.front();
+        pool->free_list.pop_front();
+        pool->refcnt[id] = 1;
+        ids_out[i] = id;
+    }
+    return HKV_OK;
+}
+
+static int check_held(const hkv_pool *pool, int32_t n, const int32_t *ids, const char *who) {
+    if (!pool || n < 0 || (n > 0 && !ids)) return fail(HKV_EINVAL, "%s: bad argument", who);
+    for (int i = 0; i < n; ++i) {
+        if (ids[i] < 0 || ids[i] >= pool->d.num_pages)
+            return fail(HKV_ERANGE, "%s: page id %d (entry %d) outside pool of %d pages", who, ids[i], i,
+                        pool->d.num_pages);
+    }
+    // a page listed k times needs at least k references for a release; at least 1 for a retain
+    return HKV_OK;
+}
+
+extern "C" int kv_pool_retain(hkv_pool *pool, int32_t n, const int32_t *ids) {
+    if (int rc = check_held(pool, n, ids, "kv_pool_retain")) return rc;
+    for (int i = 0; i < n; ++i)
+        if (pool->refcnt[ids[i]] <= 0) return fail(HKV_EINVAL, "kv_pool_retain: page %d is not allocated", ids[i]);
+    for (int i = 0; i < n; ++i) ++pool->refcnt[ids[i]];
+    return HKV_OK;
+}
+
+extern "C" int kv_pool_release(hkv_pool *pool, int32_t n, const int32_t *ids) {
+    if (int rc = check_held(pool, n, ids, "kv_pool_release")) return rc;
+    std::vector<int32_t> drop(n ? pool->d.num_pages : 0, 0);
+    for (int i = 0; i < n; ++i)
+        if (++drop[ids[i]] > pool->refcnt[ids[i]])
+            return fail(HKV_EINVAL, "kv_pool_release: page %d released more often than it is held", ids[i]);
+    for (int i = 0; i < n; ++i)
+        if (--pool->refcnt[ids[i]] == 0) pool->free_list.push_back(ids[i]);
+    return HKV_OK;
+}
+
+extern "C" int32_t kv_pool_num_free(const hkv_pool *pool) {
+    if (!pool) return fail(HKV_EINVAL, "kv_pool_num_free: null pool");
+    return (int32_t)pool->free_list.size();
+}
+
+extern "C" int32_t kv_pool_refcount(const hkv_pool *pool, int32_t page_id) {
+    if (!pool) return fail(HKV_EINVAL, "kv_pool_refcount: null pool");
+    if (page_id < 0 || page_id >= pool->d.num_pages) return fail(HKV_ERANGE, "kv_pool_refcount: page id %d", page_id);
+    return pool->refcnt[page_id];
+}
+
+static PoolView view_of(const hkv_pool *p) {
+    return PoolView{p->d.k_pages, p->d.v_pages, p->d.k_scale, p->d.v_scale, p->d.num_kv_heads, p->d.dtype};
+}
+
+extern "C" int kv_pool_write(hkv_pool *pool, const int32_t *page_ids, int32_t first_slot, int32_t n_tokens,
+                             const void *k_src, const void *v_src, void *stream) {
+    if (!pool) return fail(HKV_EINVAL, "kv_pool_write: null pool");
+    if (n_tokens < 0 || first_slot < 0 || first_slot >= HKV_PAGE_SIZE)
+        return fail(HKV_EINVAL, "kv_pool_write: n_tokens %d, first_slot %d", n_tokens, first_slot);
+    if (n_tokens == 0) return HKV_OK;
+    if (!page_ids || !k_src || !v_src) return fail(HKV_EINVAL, "kv_pool_write: null argument");
+    if ((reinterpret_cast<uintptr_t>(k_src) | reinterpret_cast<uintptr_t>(v_src)) & 15)
+        return fail(HKV_EINVAL, "kv_pool_write: k_src and v_src must be 16-byte aligned");
+    if (pool->d.dtype == HKV_FP8_E4M3 && first_slot != 0)
+        return fail(HKV_EINVAL, "kv_pool_write: fp8 pools are written from slot 0 of a page (first_slot %d)", first_slot);
+    int64_t n_pg = ((int64_t)first_slot + n_tokens + HKV_PAGE_SIZE - 1) / HKV_PAGE_SIZE;
+    if (n_pg > hkv_pool::kMaxWritePages)
+        return fail(HKV_EINVAL, "kv_pool_write: %lld pages in one call (limit %d)", (long long)n_pg,
+                    hkv_pool::kMaxWritePages);
+    for (int64_t i = 0; i < n_pg; ++i)
+        if (page_ids[i] < 0 || page_ids[i] >= pool->d.num_pages)
+            return fail(HKV_ERANGE, "kv_pool_write: page id %d (entry %lld) outside pool of %d pages", page_ids[i],
+                        (long long)i, pool->d.num_pages);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!pool->h_ids) {
+        HKV_HIP(hipHostMalloc((void **)&pool->h_ids, sizeof(int32_t) * hkv_pool::kMaxWritePages, hipHostMallocDefault));
+        HKV_HIP(hipMalloc((void **)&pool->d_ids, sizeof(int32_t) * hkv_pool::kMaxWritePages));
+        HKV_HIP(hipEventCreateWithFlags(&pool->ids_free, hipEventDisableTiming));
+    }
+    if (pool->ids_in_flight) HKV_HIP(hipEventSynchronize(pool->ids_free));  // previous write done with the staging
+    memcpy(pool->h_ids, page_ids, sizeof(int32_t) * (size_t)n_pg);
+    HKV_HIP(hipMemcpyAsync(pool->d_ids, pool->h_ids, sizeof(int32_t) * (size_t)n_pg, hipMemcpyHostToDevice, s));
+    PoolWriteLaunch a{pool->d.k_pages, pool->d.v_pages, pool->d.k_scale, pool->d.v_scale, pool->d.num_kv_heads,
+                      pool->d.dtype, pool->d_ids, (int32_t)n_pg, first_slot, n_tokens, k_src, v_src};
+    HKV_HIP(launch_pool_write(a, s));
+    HKV_HIP(hipEventRecord(pool->ids_free, s));
+    pool->ids_in_flight = true;
+    return HKV_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// forest
+static int validate_forest(const hkv_node *nodes, int32_t n_nodes, const int32_t *node_pages, int32_t n_node_pages,
+                           const char *who) {
+    if (n_nodes < 0 || n_node_pages < 0 || (n_nodes > 0 && !nodes) || (n_node_pages > 0 && !node_pages))
+        return fail(HKV_EINVAL, "%s: bad forest arguments", who);
+    std::vector<char> has_child(n_nodes, 0);
+    for (int v = 0; v < n_nodes; ++v) {
+        const hkv_node &nd = nodes[v];
+        if (nd.parent < -1 || nd.parent >= v)
+            return fail(HKV_ETREE, "%s: node %d has parent %d (parents must come first)", who, v, nd.parent);
+        if (nd.n_tokens < 0 || nd.n_pages != (nd.n_tokens + HKV_PAGE_SIZE - 1) / HKV_PAGE_SIZE)
+            return fail(HKV_ETREE, "%s: node %d has %d tokens but %d pages", who, v, nd.n_tokens, nd.n_pages);
+        if (nd.page_begin < 0 || (int64_t)nd.page_begin + nd.n_pages > n_node_pages)
+            return fail(HKV_ERANGE, "%s: node %d pages [%d, %d) outside node_pages of %d", who, v, nd.page_begin,
+                        nd.page_begin + nd.n_pages, n_node_pages);
+        if (nd.parent >= 0) has_child[nd.parent] = 1;
+    }
+    for (int v = 0; v < n_nodes; ++v)
+        if (has_child[v] && nodes[v].n_tokens % HKV_PAGE_SIZE)
+            return fail(HKV_ETREE, "%s: node %d has children but %d tokens (not a multiple of 16)", who, v,
+                        nodes[v].n_tokens);
+    return HKV_OK;
+}
+
+static int build_node_req_csr(const hkv_node *nodes, int32_t n_nodes, const int32_t *req_leaf, int32_t n_req,
+                              std::vector<int32_t> &indptr, std::vector<int32_t> &idx, const char *who) {
+    if (n_req < 0 || (n_req > 0 && !req_leaf)) return fail(HKV_EINVAL, "%s: bad request list", who);
+    indptr.assign((size_t)n_nodes + 1, 0);
+    for (int r = 0; r < n_req; ++r) {
+        if (req_leaf[r] < 0 || req_leaf[r] >= n_nodes)
+            return fail(HKV_ERANGE, "%s: request %d ends at node %d of %d", who, r, req_leaf[r], n_nodes);
+        for (int v = req_leaf[r]; v >= 0; v = nodes[v].parent) ++indptr[v + 1];
+    }
+    for (int v = 0; v < n_nodes; ++v) indptr[v + 1] += indptr[v];
+    idx.assign((size_t)indptr[n_nodes], 0);
+    std::vector<int32_t> fill(indptr.begin(), indptr.end() - 1);
+    for (int r = 0; r < n_req; ++r)  // ascending r keeps every node's list sorted
+        for (int v = req_leaf[r]; v >= 0; v = nodes[v].parent) idx[fill[v]++] = r;
+    return HKV_OK;
+}
+
+extern "C" int prefix_tree_flatten(const hkv_node *nodes, int32_t n_nodes, const int32_t *node_pages,
+                                   int32_t n_node_pages, const int32_t *req_leaf, int32_t n_req, int32_t max_pages,
+                                   int32_t *block_table, int32_t *kv_len, int32_t *node_req_indptr,
+                                   int32_t *node_req_idx, int32_t *node_tok_start) {
+    if (max_pages < 0) return fail(HKV_EINVAL, "prefix_tree_flatten: max_pages %d", max_pages);
+    if (int rc = validate_forest(nodes, n_nodes, node_pages, n_node_pages, "prefix_tree_flatten")) return rc;
+    std::vector<int32_t> indptr, idx;
+    if (int rc = build_node_req_csr(nodes, n_nodes, req_leaf, n_req, indptr, idx, "prefix_tree_flatten")) return rc;
+    std::vector<int32_t> tok_start(n_nodes, 0), pages_before(n_nodes, 0);
+    for (int v = 0; v < n_nodes; ++v) {
+        int par = nodes[v].parent;
+        if (par >= 0) {
+            tok_start[v] = tok_start[par] + nodes[par].n_tokens;
+            pages_before[v] = pages_before[par] + nodes[par].n_pages;
+        }
+    }
+    for (int r = 0; r < n_req; ++r) {
+        int leaf = req_leaf[r];
+        int total_pages = pages_before[leaf] + nodes[leaf].n_pages;
+        if (total_pages > max_pages)
+            return fail(HKV_ENOMEM, "prefix_tree_flatten: request %d needs %d pages, max_pages is %d", r, total_pages,
+                        max_pages);
+    }
+    for (int r = 0; r < n_req; ++r) {
+        int leaf = req_leaf[r];
+        if (kv_len) kv_len[r] = tok_start[leaf] + nodes[leaf].n_tokens;
+        if (!block_table) continue;
+        int32_t *row = block_table + (size_t)r * max_pages;
+        int total_pages = pages_before[leaf] + nodes[leaf].n_pages;
+        for (int i = total_pages; i < max_pages; ++i) row[i] = -1;
+        for (int v = leaf; v >= 0; v = nodes[v].parent)
+            for (int j = 0; j < nodes[v].n_pages; ++j) row[pages_before[v] + j] = node_pages[nodes[v].page_begin + j];
+    }
+    if (node_req_indptr) memcpy(node_req_indptr, indptr.data(), sizeof(int32_t) * indptr.size());
+    if (node_req_idx && !idx.empty()) memcpy(node_req_idx, idx.data(), sizeof(int32_t) * idx.size());
+    if (node_tok_start && n_nodes) memcpy(node_tok_start, tok_start.data(), sizeof(int32_t) * n_nodes);
+    return HKV_OK;
+}
+
+extern "C" int prefix_tree_prefill_usage(const hkv_node *nodes, int32_t n_nodes, const int32_t *calls,
+                                         int32_t n_calls, int64_t *u_p) {
+    if (n_nodes < 0 || n_calls < 0 || (n_nodes > 0 && !nodes) || (n_calls > 0 && (!calls || !u_p)))
+        return fail(HKV_EINVAL, "prefix_tree_prefill_usage: bad argument");
+    for (int v = 0; v < n_nodes; ++v)
+        if (nodes[v].parent < -1 || nodes[v].parent >= v || nodes[v].n_tokens < 0)
+            return fail(HKV_ETREE, "prefix_tree_prefill_usage: node %d malformed", v);
+    // depth and token count from the root let two leaves meet at their lowest common ancestor
+    std::vector<int32_t> depth(n_nodes, 0);
+    std::vector<int64_t> tok_end(n_nodes, 0);
+    for (int v = 0; v < n_nodes; ++v) {
+        int par = nodes[v].parent;
+        depth[v] = par < 0 ? 0 : depth[par] + 1;
+        tok_end[v] = (par < 0 ? 0 : tok_end[par]) + nodes[v].n_tokens;
+    }
+    for (int j = 0; j < n_calls; ++j) {
+        if (calls[j] < 0 || calls[j] >= n_nodes)
+            return fail(HKV_ERANGE, "prefix_tree_prefill_usage: call %d names node %d of %d", j, calls[j], n_nodes);
+        int64_t shared = 0;
+        if (j > 0) {
+            int a = calls[j - 1], b = calls[j];
+            while (a >= 0 && b >= 0 && a != b) {
+                if (depth[a] >= depth[b]) a = nodes[a].parent; else b = nodes[b].parent;
+            }
+            if (a >= 0 && a == b) shared = tok_end[a];
+        }
+        u_p[j] = tok_end[calls[j]] - shared;
+    }
+    return HKV_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// lse_merge
+extern "C" int lse_merge(const float *o_parts, const float *lse_parts, const int32_t *row_indptr,
+                         const int32_t *part_idx, int32_t n_rows, void *out, int32_t out_dtype, float *lse_out,
+                         void *stream) {
+    if (n_rows < 0) return fail(HKV_EINVAL, "lse_merge: n_rows %d", n_rows);
+    if (out_dtype != HKV_BF16 && out_dtype != HKV_FP32) return fail(HKV_ESHAPE, "lse_merge: out_dtype %d", out_dtype);
+    if (n_rows == 0) return HKV_OK;
+    if (!o_parts || !lse_parts || !row_indptr || !part_idx || !out) return fail(HKV_EINVAL, "lse_merge: null argument");
+    if ((reinterpret_cast<uintptr_t>(o_parts) & 7) || (reinterpret_cast<uintptr_t>(out) & 7))
+        return fail(HKV_EINVAL, "lse_merge: o_parts and out must be 8-byte aligned");
+    HKV_HIP(launch_lse_merge(o_parts, lse_parts, row_indptr, part_idx, n_rows, out, out_dtype, lse_out,
+                             static_cast<hipStream_t>(stream)));
+    return HKV_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// decode planning
+//
+// A node with T tokens that R requests pass through is cut into work items of at most 64 query
+// rows (R_item * G) and a token chunk each.  Every item yields one partial result per row, so the
+// chunk length trades parallelism (more items) against partial-result traffic (516 B per row and
+// item, written once and read once).  The chunk lengths below keep every item's HBM read at or
+// above 128 KiB for the node sizes of the target workloads while giving the 256 CUs several
+// items each.
+static void plan_items(hkv_decode_plan &pl) {
+    const int G = pl.group;
+    const int Hkv = pl.pool->d.num_kv_heads;
+    const int max_req_per_item = std::max(1, 64 / G);
+    const int leaf_chunk = env_int("HKV_DECODE_LEAF_CHUNK", 512) / 16 * 16;
+    const int shared_chunk = env_int("HKV_DECODE_SHARED_CHUNK", 512) / 16 * 16;
+    struct Proto { DecodeItem it; int64_t cost; };
+    std::vector<Proto> protos;
+    for (int v = 0; v < (int)pl.nodes.size(); ++v) {
+        const hkv_node &nd = pl.nodes[v];
+        int R = pl.node_req_indptr[v + 1] - pl.node_req_indptr[v];
+        if (nd.n_tokens == 0 || R == 0) continue;
+        int chunk = std::max(16, R * G > 16 ? shared_chunk : leaf_chunk);
+        // equal chunks of whole pages
+        int n_chunks = (nd.n_tokens + chunk - 1) / chunk;
+        int pages_per_chunk = (nd.n_pages + n_chunks - 1) / n_chunks;
+        for (int r0 = 0; r0 < R; r0 += max_req_per_item) {
+            int nr = std::min(max_req_per_item, R - r0);
+            for (int pg = 0; pg < nd.n_pages; pg += pages_per_chunk) {
+                int tb = pg * 16;
+                int nt = std::min(pages_per_chunk * 16, nd.n_tokens - tb);
+                for (int h = 0; h < Hkv; ++h) {
+                    DecodeItem it{nd.page_begin + pg, nt, h, pl.node_req_indptr[v] + r0, nr, 0, tb, v};
+                    int rows = nr * G;
+                    protos.push_back({it, (int64_t)nt * std::max(16, (rows + 15) / 16 * 16)});
+                }
+            }
+        }
+    }
+    std::stable_sort(protos.begin(), protos.end(), [](const Proto &a, const Proto &b) { return a.cost > b.cost; });
+    int32_t part = 0;
+    pl.items.clear();
+    for (auto &p : protos) {
+        p.it.part_base = part;
+        part += p.it.n_req * G;
+        pl.items.push_back(p.it);
+    }
+    pl.n_parts = part;
+    // merge CSR: output row (request, q head) -> its partials
+    const int Hq = pl.num_q_heads;
+    std::vector<int32_t> cnt((size_t)pl.n_req * Hq + 1, 0);
+    for (const DecodeItem &it : pl.items)
+        for (int j = 0; j < it.n_req; ++j) {
+            int r = pl.node_req_idx[it.req_off + j];
+            for (int g = 0; g < G; ++g) ++cnt[(size_t)r * Hq + it.kv_head * G + g + 1];
+        }
+    pl.row_indptr.assign(cnt.size(), 0);
+    std::partial_sum(cnt.begin(), cnt.end(), pl.row_indptr.begin());
+    pl.part_idx.assign((size_t)pl.row_indptr.back(), 0);
+    std::vector<int32_t> fill(pl.row_indptr.begin(), pl.row_indptr.end() - 1);
+    for (const DecodeItem &it : pl.items)
+        for (int j = 0; j < it.n_req; ++j) {
+            int r = pl.node_req_idx[it.req_off + j];
+            for (int g = 0; g < G; ++g)
+                pl.part_idx[fill[(size_t)r * Hq + it.kv_head * G + g]++] = it.part_base + j * G + g;
+        }
+}
+
+static int upload_decode_plan(hkv_decode_plan &pl) {
+    size_t off_items = 0;
+    size_t off_pages = align_up(off_items + sizeof(DecodeItem) * pl.items.size(), 256);
+    size_t off_nri = align_up(off_pages + sizeof(int32_t) * pl.node_pages.size(), 256);
+    size_t off_indptr = align_up(off_nri + sizeof(int32_t) * pl.node_req_idx.size(), 256);
+    size_t off_pidx = align_up(off_indptr + sizeof(int32_t) * pl.row_indptr.size(), 256);
+    size_t total = align_up(off_pidx + sizeof(int32_t) * pl.part_idx.size(), 256) + 256;
+    HKV_HIP(hipMalloc(&pl.dev, total));
+    char *base = static_cast<char *>(pl.dev);
+    pl.d_items = reinterpret_cast<DecodeItem *>(base + off_items);
+    pl.d_pages = reinterpret_cast<int32_t *>(base + off_pages);
+    pl.d_node_req_idx = reinterpret_cast<int32_t *>(base + off_nri);
+    pl.d_row_indptr = reinterpret_cast<int32_t *>(base + off_indptr);
+    pl.d_part_idx = reinterpret_cast<int32_t *>(base + off_pidx);
+    auto up = [&](void *dst, const void *src, size_t n) -> hipError_t {
+        return n ? hipMemcpy(dst, src, n, hipMemcpyHostToDevice) : hipSuccess;
+    };
+    HKV_HIP(up(pl.d_items, pl.items.data(), sizeof(DecodeItem) * pl.items.size()));
+    HKV_HIP(up(pl.d_pages, pl.node_pages.data(), sizeof(int32_t) * pl.node_pages.size()));
+    HKV_HIP(up(pl.d_node_req_idx, pl.node_req_idx.data(), sizeof(int32_t) * pl.node_req_idx.size()));
+    HKV_HIP(up(pl.d_row_indptr, pl.row_indptr.data(), sizeof(int32_t) * pl.row_indptr.size()));
+    HKV_HIP(up(pl.d_part_idx, pl.part_idx.data(), sizeof(int32_t) * pl.part_idx.size()));
+    return HKV_OK;
+}
+
+extern "C" int hkv_decode_plan_create(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes,
+                                      const int32_t *node_pages, int32_t n_node_pages, const int32_t *req_leaf,
+                                      int32_t n_req, int32_t num_q_heads, uint32_t flags, hkv_decode_plan **out) {
+    if (!pool || !out) return fail(HKV_EINVAL, "hkv_decode_plan_create: null argument");
+    *out = nullptr;
+    const int Hkv = pool->d.num_kv_heads;
+    if (num_q_heads <= 0 || num_q_heads % Hkv || num_q_heads / Hkv > 16)
+        return fail(HKV_ESHAPE, "hkv_decode_plan_create: %d query heads over %d KV heads", num_q_heads, Hkv);
+    if (int rc = validate_forest(nodes, n_nodes, node_pages, n_node_pages, "hkv_decode_plan_create")) return rc;
+    for (int v = 0; v < n_nodes; ++v)
+        for (int j = 0; j < nodes[v].n_pages; ++j) {
+            int32_t id = node_pages[nodes[v].page_begin + j];
+            if (id < 0 || id >= pool->d.num_pages)
+                return fail(HKV_ERANGE, "hkv_decode_plan_create: node %d page %d has id %d outside pool of %d", v, j,
+                            id, pool->d.num_pages);
+        }
+    hkv_decode_plan *pl = new (std::nothrow) hkv_decode_plan;
+    if (!pl) return fail(HKV_ENOMEM, "hkv_decode_plan_create: out of host memory");
+    pl->pool = pool;
+    pl->n_req = n_req;
+    pl->num_q_heads = num_q_heads;
+    pl->group = num_q_heads / Hkv;
+    if (int rc = build_node_req_csr(nodes, n_nodes, req_leaf, n_req, pl->node_req_indptr, pl->node_req_idx,
+                                    "hkv_decode_plan_create")) {
+        delete pl;
+        return rc;
+    }
+    pl->nodes.assign(nodes, nodes + n_nodes);
+    pl->node_pages.assign(node_pages, node_pages + n_node_pages);
+    pl->req_leaf.assign(req_leaf, req_leaf + n_req);
+    plan_items(*pl);
+    if (!(flags & HKV_PLAN_HOST_ONLY)) {
+        if (int rc = upload_decode_plan(*pl)) {
+            if (pl->dev) (void)hipFree(pl->dev);
+            delete pl;
+            return rc;
+        }
+    }
+    *out = pl;
+    return HKV_OK;
+}
+
+extern "C" int hkv_decode_plan_destroy(hkv_decode_plan *plan) {
+    if (!plan) return HKV_OK;
+    if (plan->dev) (void)hipFree(plan->dev);  // hipFree waits for work that may still read it
+    delete plan;
+    return HKV_OK;
+}
+
+extern "C" size_t hkv_decode_plan_workspace_bytes(const hkv_decode_plan *plan) {
+    if (!plan) return 0;
+    return align_up((size_t)plan->n_parts * HKV_HEAD_DIM * sizeof(float), 256) +
+           align_up((size_t)plan->n_parts * sizeof(float), 256);
+}
+
+extern "C" int32_t hkv_decode_plan_num_items(const hkv_decode_plan *plan) {
+    return plan ? (int32_t)plan->items.size() : fail(HKV_EINVAL, "null plan");
+}
+extern "C" int32_t hkv_decode_plan_num_parts(const hkv_decode_plan *plan) {
+    return plan ? plan->n_parts : fail(HKV_EINVAL, "null plan");
+}
+extern "C" int hkv_decode_plan_items(const hkv_decode_plan *plan, int32_t *items_out) {
+    if (!plan || !items_out) return fail(HKV_EINVAL, "hkv_decode_plan_items: null argument");
+    static_assert(sizeof(DecodeItem) == 32, "item layout is part of the introspection contract");
+    if (!plan->items.empty()) memcpy(items_out, plan->items.data(), sizeof(DecodeItem) * plan->items.size());
+    return HKV_OK;
+}
+extern "C" int32_t hkv_decode_plan_num_merge_entries(const hkv_decode_plan *plan) {
+    return plan ? (int32_t)plan->part_idx.size() : fail(HKV_EINVAL, "null plan");
+}
+extern "C" int hkv_decode_plan_merge_csr(const hkv_decode_plan *plan, int32_t *row_indptr, int32_t *part_idx) {
+    if (!plan) return fail(HKV_EINVAL, "hkv_decode_plan_merge_csr: null plan");
+    if (row_indptr) memcpy(row_indptr, plan->row_indptr.data(), sizeof(int32_t) * plan->row_indptr.size());
+    if (part_idx && !plan->part_idx.empty())
+        memcpy(part_idx, plan->part_idx.data(), sizeof(int32_t) * plan->part_idx.size());
+    return HKV_OK;
+}
+
+extern "C" int attn_decode_plan_run(hkv_decode_plan *plan, const void *q, float scale, void *out, float *lse_out,
+                                    void *workspace, size_t workspace_bytes, void *stream) {
+    if (!plan) return fail(HKV_EINVAL, "attn_decode_plan_run: null plan");
+    if (plan->n_req == 0) return HKV_OK;
+    if (!q || !out) return fail(HKV_EINVAL, "attn_decode_plan_run: null q or out");
+    if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(out)) & 15)
+        return fail(HKV_EINVAL, "attn_decode_plan_run: q and out must be 16-byte aligned");
+    if (!plan->dev) return fail(HKV_EINVAL, "attn_decode_plan_run: plan was built host-only");
+    size_t need = hkv_decode_plan_workspace_bytes(plan);
+    if (need && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)))
+        return fail(HKV_EINVAL, "attn_decode_plan_run: workspace must be non-null and 256-byte aligned");
+    if (workspace_bytes < need)
+        return fail(HKV_ENOMEM, "attn_decode_plan_run: workspace has %zu bytes, %zu needed", workspace_bytes, need);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float *o_parts = static_cast<float *>(workspace);
+    float *lse_parts = reinterpret_cast<float *>(static_cast<char *>(workspace) +
+                                                 align_up((size_t)plan->n_parts * HKV_HEAD_DIM * sizeof(float), 256));
+    if (!plan->items.empty()) {
+        DecodeLaunch a{view_of(plan->pool), q, plan->d_items, plan->d_pages, plan->d_node_req_idx, o_parts, lse_parts,
+                       (int32_t)plan->items.size(), plan->num_q_heads, scale};
+        HKV_HIP(launch_decode(a, s));
+    }
+    HKV_HIP(launch_lse_merge(o_parts, lse_parts, plan->d_row_indptr, plan->d_part_idx, plan->n_req * plan->num_q_heads,
+                             out, HKV_BF16, lse_out, s));
+    return HKV_OK;
+}
+
+static bool same_forest(const hkv_decode_plan *pl, const hkv_node *nodes, int32_t n_nodes, const int32_t *node_pages,
+                        int32_t n_node_pages, const int32_t *req_leaf, int32_t n_req, int32_t num_q_heads) {
+    return pl && pl->num_q_heads == num_q_heads && (int32_t)pl->nodes.size() == n_nodes &&
+           (int32_t)pl->node_pages.size() == n_node_pages && (int32_t)pl->req_leaf.size() == n_req &&
+           (n_nodes == 0 || !memcmp(pl->nodes.data(), nodes, sizeof(hkv_node) * n_nodes)) &&
+           (n_node_pages == 0 || !memcmp(pl->node_pages.data(), node_pages, sizeof(int32_t) * n_node_pages)) &&
+           (n_req == 0 || !memcmp(pl->req_leaf.data(), req_leaf, sizeof(int32_t) * n_req));
+}
+
+static int cached_decode_plan(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes, const int32_t *node_pages,
+                              int32_t n_node_pages, const int32_t *req_leaf, int32_t n_req, int32_t num_q_heads,
+                              uint32_t flags, hkv_decode_plan **out) {
+    if (!pool) return fail(HKV_EINVAL, "null pool");
+    if (n_nodes < 0 || n_node_pages < 0 || n_req < 0 || (n_nodes > 0 && !nodes) || (n_node_pages > 0 && !node_pages) ||
+        (n_req > 0 && !req_leaf))
+        return fail(HKV_EINVAL, "bad forest arguments");
+    hkv_decode_plan *c = pool->cached_decode;
+    if (same_forest(c, nodes, n_nodes, node_pages, n_node_pages, req_leaf, n_req, num_q_heads) &&
+        (c->dev || (flags & HKV_PLAN_HOST_ONLY))) {
+        *out = c;
+        return HKV_OK;
+    }
+    hkv_decode_plan *fresh = nullptr;
+    if (int rc = hkv_decode_plan_create(pool, nodes, n_nodes, node_pages, n_node_pages, req_leaf, n_req, num_q_heads,
+                                        flags, &fresh))
+        return rc;
+    if (c) hkv_decode_plan_destroy(c);
+    pool->cached_decode = fresh;
+    *out = fresh;
+    return HKV_OK;
+}
+
+extern "C" int attn_decode_prefix_tree(hkv_pool *pool, const void *q, const hkv_node *nodes, int32_t n_nodes,
+                                       const int32_t *node_pages, int32_t n_node_pages, const int32_t *req_leaf,
+                                       int32_t n_req, int32_t num_q_heads, float scale, void *out, float *lse_out,
+                                       void *workspace, size_t workspace_bytes, void *stream) {
+    hkv_decode_plan *pl = nullptr;
+    // validate everything that does not need the device before touching it
+    if (n_req > 0 && (!q || !out)) return fail(HKV_EINVAL, "attn_decode_prefix_tree: null q or out");
+    if (int rc = cached_decode_plan(pool, nodes, n_nodes, node_pages, n_node_pages, req_leaf, n_req, num_q_heads, 0,
+                                    &pl))
+        return rc;
+    return attn_decode_plan_run(pl, q, scale, out, lse_out, workspace, workspace_bytes, stream);
+}
+
+extern "C" size_t attn_decode_workspace_bytes(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes,
+                                              const int32_t *node_pages, int32_t n_node_pages, const int32_t *req_leaf,
+                                              int32_t n_req, int32_t num_q_heads) {
+    hkv_decode_plan *pl = nullptr;
+    uint32_t flags = (pool && pool->cached_decode && pool->cached_decode->dev) ? 0u : (uint32_t)HKV_PLAN_HOST_ONLY;
+    if (cached_decode_plan(pool, nodes, n_nodes, node_pages, n_node_pages, req_leaf, n_req, num_q_heads, flags, &pl))
+        return 0;
+    return hkv_decode_plan_workspace_bytes(pl);
+}
+
+// ---------------------------------------------------------------------------------------------
+// prefill planning
+extern "C" int hkv_prefill_plan_create(hkv_pool *pool, const int32_t *cu_q, const int32_t *block_table,
+                                       int32_t max_pages, const int32_t *kv_len, int32_t n_req, int32_t num_q_heads,
+                                       uint32_t flags, hkv_prefill_plan **out) {
+    if (!pool || !out) return fail(HKV_EINVAL, "hkv_prefill_plan_create: null argument");
+    *out = nullptr;
+    const int Hkv = pool->d.num_kv_heads;
+    if (num_q_heads <= 0 || num_q_heads % Hkv) return fail(HKV_ESHAPE, "hkv_prefill_plan_create: %d query heads over %d KV heads", num_q_heads, Hkv);
+    const int G = num_q_heads / Hkv;
+    if (G != 1 && G != 2 && G != 4 && G != 8)
+        return fail(HKV_ESHAPE, "hkv_prefill_plan_create: query/KV head ratio %d (supported: 1, 2, 4, 8)", G);
+    if (pool->d.dtype != HKV_BF16) return fail(HKV_ESHAPE, "hkv_prefill_plan_create: prefill reads bf16 pools only");
+    if (n_req < 0 || max_pages < 0 || (n_req > 0 && (!cu_q || !kv_len || (max_pages > 0 && !block_table))))
+        return fail(HKV_EINVAL, "hkv_prefill_plan_create: bad argument");
+    if (n_req > 0 && cu_q[0] != 0) return fail(HKV_EINVAL, "hkv_prefill_plan_create: cu_q[0] must be 0");
+    for (int r = 0; r < n_req; ++r) {
+        int64_t s = (int64_t)cu_q[r + 1] - cu_q[r];
+        if (s < 0) return fail(HKV_EINVAL, "hkv_prefill_plan_create: cu_q decreases at request %d", r);
+        if (kv_len[r] < s) return fail(HKV_EINVAL, "hkv_prefill_plan_create: request %d has kv_len %d < %lld new tokens", r, kv_len[r], (long long)s);
+        int64_t need = ((int64_t)kv_len[r] + HKV_PAGE_SIZE - 1) / HKV_PAGE_SIZE;
+        if (need > max_pages) return fail(HKV_ENOMEM, "hkv_prefill_plan_create: request %d needs %lld pages, max_pages is %d", r, (long long)need, max_pages);
+        if (s == 0) continue;  // nothing of this request is read
+        for (int64_t i = 0; i < need; ++i) {
+            int32_t id = block_table[(size_t)r * max_pages + i];
+            if (id < 0 || id >= pool->d.num_pages)
+                return fail(HKV_ERANGE, "hkv_prefill_plan_create: request %d page %lld has id %d outside pool of %d", r, (long long)i, id, pool->d.num_pages);
+        }
+    }
+    hkv_prefill_plan *pl = new (std::nothrow) hkv_prefill_plan;
+    if (!pl) return fail(HKV_ENOMEM, "hkv_prefill_plan_create: out of host memory");
+    pl->pool = pool;
+    pl->n_req = n_req;
+    pl->num_q_heads = num_q_heads;
+    pl->max_pages = max_pages;
+    pl->total_q = n_req ? cu_q[n_req] : 0;
+    pl->cu_q.assign(cu_q, cu_q + (n_req ? n_req + 1 : 0));
+    pl->kv_len.assign(kv_len, kv_len + n_req);
+    if (n_req && max_pages) pl->block_table.assign(block_table, block_table + (size_t)n_req * max_pages);
+    const int TQ = prefill_tile_tokens(G);
+    struct Proto { int32_t req, q_begin, n_q; int64_t extent; };
+    std::vector<Proto> protos;
+    for (int r = 0; r < n_req; ++r) {
+        int s = cu_q[r + 1] - cu_q[r];
+        int prefix = kv_len[r] - s;
+        for (int q0 = 0; q0 < s; q0 += TQ) {
+            int nq = std::min(TQ, s - q0);
+            protos.push_back({r, q0, nq, (int64_t)prefix + q0 + nq});
+        }
+    }
+    // longest key range first; the KV heads of one query tile sit next to each other so that
+    // workgroup index mod num_kv_heads is the KV head (one head per XCD when there are 8)
+    std::stable_sort(protos.begin(), protos.end(), [](const Proto &a, const Proto &b) { return a.extent > b.extent; });
+    for (const Proto &p : protos)
+        for (int h = 0; h < Hkv; ++h) {
+            int s = cu_q[p.req + 1] - cu_q[p.req];
+            pl->tiles.push_back(PrefillTile{p.req, p.q_begin, p.n_q, h, cu_q[p.req] + p.q_begin, kv_len[p.req] - s,
+                                            kv_len[p.req], p.req * max_pages});
+        }
+    if (!(flags & HKV_PLAN_HOST_ONLY) && !pl->tiles.empty()) {
+        size_t off_bt = align_up(sizeof(PrefillTile) * pl->tiles.size(), 256);
+        size_t total = off_bt + align_up(sizeof(int32_t) * pl->block_table.size(), 256) + 256;
+        hipError_t e = hipMalloc(&pl->dev, total);
+        if (e == hipSuccess) {
+            pl->d_tiles = static_cast<PrefillTile *>(pl->dev);
+            pl->d_block_table = reinterpret_cast<int32_t *>(static_cast<char *>(pl->dev) + off_bt);
+            e = hipMemcpy(pl->d_tiles, pl->tiles.data(), sizeof(PrefillTile) * pl->tiles.size(), hipMemcpyHostToDevice);
+        }
+        if (e == hipSuccess)
+            e = hipMemcpy(pl->d_block_table, pl->block_table.data(), sizeof(int32_t) * pl->block_table.size(),
+                          hipMemcpyHostToDevice);
+        if (e != hipSuccess) {
+            if (pl->dev) (void)hipFree(pl->dev);
+            delete pl;
+            return fail_hip(e, "hkv_prefill_plan_create: device upload");
+        }
+    }
+    *out = pl;
+    return HKV_OK;
+}
+
+extern "C" int hkv_prefill_plan_destroy(hkv_prefill_plan *plan) {
+    if (!plan) return HKV_OK;
+    if (plan->dev) (void)hipFree(plan->dev);
+    delete plan;
+    return HKV_OK;
+}
+
+extern "C" int32_t hkv_prefill_plan_num_tiles(const hkv_prefill_plan *plan) {
+    return plan ? (int32_t)plan->tiles.size() : fail(HKV_EINVAL, "null plan");
+}
+
+extern "C" int hkv_prefill_plan_tiles(const hkv_prefill_plan *plan, int32_t *tiles_out) {
+    if (!plan || !tiles_out) return fail(HKV_EINVAL, "hkv_prefill_plan_tiles: null argument");
+    static_assert(sizeof(PrefillTile) == 32, "tile layout is part of the introspection contract");
+    if (!plan->tiles.empty()) memcpy(tiles_out, plan->tiles.data(), sizeof(PrefillTile) * plan->tiles.size());
+    return HKV_OK;
+}
+
+extern "C" int attn_prefill_plan_run(hkv_prefill_plan *plan, const void *q, float scale, void *out, float *lse_out,
+                                     void *stream) {
+    if (!plan) return fail(HKV_EINVAL, "attn_prefill_plan_run: null plan");
+    if (plan->tiles.empty()) return HKV_OK;
+    if (!q || !out) return fail(HKV_EINVAL, "attn_prefill_plan_run: null q or out");
+    if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(out)) & 15)
+        return fail(HKV_EINVAL, "attn_prefill_plan_run: q and out must be 16-byte aligned");
+    if (!plan->dev) return fail(HKV_EINVAL, "attn_prefill_plan_run: plan was built host-only");
+    PrefillLaunch a{view_of(plan->pool), q, plan->d_tiles, plan->d_block_table, out, lse_out,
+                    (int32_t)plan->tiles.size(), plan->num_q_heads, scale};
+    HKV_HIP(launch_prefill(a, static_cast<hipStream_t>(stream)));
+    return HKV_OK;
+}
+
+extern "C" int attn_prefill_with_prefix(hkv_pool *pool, const void *q, const int32_t *cu_q, const int32_t *block_table,
+                                        int32_t max_pages, const int32_t *kv_len, int32_t n_req, int32_t num_q_heads,
+                                        float scale, void *out, float *lse_out, void *workspace, size_t workspace_bytes,
+                                        void *stream) {
+    (void)workspace;
+    (void)workspace_bytes;
+    if (!pool) return fail(HKV_EINVAL, "attn_prefill_with_prefix: null pool");
+    hkv_prefill_plan *c = pool->cached_prefill;
+    bool same = c && c->dev && c->n_req == n_req && c->num_q_heads == num_q_heads && c->max_pages == max_pages &&
+                n_req > 0 && cu_q && kv_len && block_table &&
+                !memcmp(c->cu_q.data(), cu_q, sizeof(int32_t) * (n_req + 1)) &&
+                !memcmp(c->kv_len.data(), kv_len, sizeof(int32_t) * n_req) &&
+                !memcmp(c->block_table.data(), block_table, sizeof(int32_t) * (size_t)n_req * max_pages);
+    if (!same) {
+        hkv_prefill_plan *fresh = nullptr;
+        if (int rc = hkv_prefill_plan_create(pool, cu_q, block_table, max_pages, kv_len, n_req, num_q_heads, 0, &fresh))
+            return rc;
+        if (c) hkv_prefill_plan_destroy(c);
+        pool->cached_prefill = c = fresh;
+    }
+    return attn_prefill_plan_run(c, q, scale, out, lse_out, stream);
+}
+
+extern "C" size_t attn_prefill_workspace_bytes(int32_t total_q, int32_t num_q_heads) {
+    (void)total_q;
+    (void)num_q_heads;
+    return 0;
+}

@@ -1,0 +1,68 @@
+// Device-side helpers shared by the gfx950 kernels: matrix-core operand types, bf16/fp8
+// conversions and cross-lane reductions for 64-wide wavefronts.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "hkv_internal.h"
+
+namespace hkv {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// 16-byte global load of matrix-core operand data (8 bf16 or 16 fp8).
+__device__ __forceinline__ u32x4 ld16(const void *p) { return *reinterpret_cast<const u32x4 *>(p); }
+
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// float -> bf16 bits, round to nearest even (inputs here are finite or +-inf, never NaN payloads
+// that matter).  The compiler turns the pair form into the packed convert of gfx950.
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+    bf16x2 v;
+    v[0] = (__bf16)lo;
+    v[1] = (__bf16)hi;
+    return __builtin_bit_cast(uint32_t, v);
+}
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// Eight e4m3 codes (two dwords) -> eight bf16 (exact: every e4m3 value is a bf16 value).
+__device__ __forceinline__ bf16x8 fp8x8_to_bf16x8(uint32_t w0, uint32_t w1) {
+    auto a = __builtin_amdgcn_cvt_pk_f32_fp8(w0, false);
+    auto b = __builtin_amdgcn_cvt_pk_f32_fp8(w0, true);
+    auto c = __builtin_amdgcn_cvt_pk_f32_fp8(w1, false);
+    auto d = __builtin_amdgcn_cvt_pk_f32_fp8(w1, true);
+    u32x4 r;
+    r[0] = pack_bf16(a[0], a[1]);
+    r[1] = pack_bf16(b[0], b[1]);
+    r[2] = pack_bf16(c[0], c[1]);
+    r[3] = pack_bf16(d[0], d[1]);
+    return as_bf16x8(r);
+}
+
+// Reductions across the four 16-lane rows of a wavefront (lanes l, l^16, l^32, l^48 hold the
+// same matrix column): after the call every lane holds the result.
+__device__ __forceinline__ float rows_max(float v) {
+    v = fmaxf(v, __shfl_xor(v, 16));
+    v = fmaxf(v, __shfl_xor(v, 32));
+    return v;
+}
+__device__ __forceinline__ float rows_sum(float v) {
+    v += __shfl_xor(v, 16);
+    v += __shfl_xor(v, 32);
+    return v;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+}  // namespace hkv

@@ -1,0 +1,99 @@
+// Internal interface between the host side of the library (api.cpp) and its gfx950 kernels.
+// Not part of the C ABI.
+#pragma once
+
+#include <hip/hip_runtime_api.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace hkv {
+
+constexpr int kPage = 16;
+constexpr int kHeadDim = 128;
+constexpr int kBlockElems = kPage * kHeadDim;  // elements of one (page, head) K or V block
+
+// One decode workgroup: the tokens [tok_begin, tok_begin + n_tokens) of one tree node, one KV
+// head, applied to n_req of the requests below the node (n_req * G query rows, at most 64).
+struct DecodeItem {
+    int32_t page_off;   // index of the item's first page in the plan's page list
+    int32_t n_tokens;   // tokens of this item; only the node's last item may end inside a page
+    int32_t kv_head;
+    int32_t req_off;    // index of the item's first request in the node->request CSR values
+    int32_t n_req;
+    int32_t part_base;  // partial-result slot of row 0; row (j, g) -> part_base + j*G + g
+    int32_t tok_begin;  // first token within the node (multiple of 16)
+    int32_t node;
+};
+
+// One prefill workgroup: n_q consecutive new tokens of one request, all G query heads of one KV head.
+struct PrefillTile {
+    int32_t req;
+    int32_t q_begin;    // first new token of the tile within the request's suffix
+    int32_t n_q;
+    int32_t kv_head;
+    int32_t q_row0;     // row of that token in q / out: cu_q[req] + q_begin
+    int32_t prefix_len; // cached tokens in front of the request's suffix
+    int32_t kv_len;
+    int32_t bt_off;     // offset of the request's row in the uploaded block table
+};
+
+struct PoolView {
+    const void *k_pages;
+    const void *v_pages;
+    const float *k_scale;
+    const float *v_scale;
+    int32_t num_kv_heads;
+    int32_t dtype;
+};
+
+struct DecodeLaunch {
+    PoolView pool;
+    const void *q;               // [n_req][Hq][128] bf16
+    const DecodeItem *items;     // device
+    const int32_t *pages;        // device: the plan's page list
+    const int32_t *node_req_idx; // device: node->request CSR values
+    float *o_parts;              // [n_parts][128]
+    float *lse_parts;            // [n_parts]
+    int32_t n_items;
+    int32_t num_q_heads;
+    float scale;
+};
+
+struct PrefillLaunch {
+    PoolView pool;
+    const void *q;
+    const PrefillTile *tiles;    // device
+    const int32_t *block_table;  // device
+    void *out;
+    float *lse_out;              // may be null
+    int32_t n_tiles;
+    int32_t num_q_heads;
+    float scale;
+};
+
+struct PoolWriteLaunch {
+    void *k_pages;
+    void *v_pages;
+    float *k_scale;
+    float *v_scale;
+    int32_t num_kv_heads;
+    int32_t dtype;
+    const int32_t *page_ids;     // device
+    int32_t n_pages;
+    int32_t first_slot;
+    int32_t n_tokens;
+    const void *k_src;
+    const void *v_src;
+};
+
+// Query tokens per prefill workgroup for a given group size G (rows per workgroup / G).
+int prefill_tile_tokens(int group);
+
+hipError_t launch_pool_write(const PoolWriteLaunch &a, hipStream_t s);
+hipError_t launch_decode(const DecodeLaunch &a, hipStream_t s);
+hipError_t launch_prefill(const PrefillLaunch &a, hipStream_t s);
+hipError_t launch_lse_merge(const float *o_parts, const float *lse_parts, const int32_t *row_indptr,
+                            const int32_t *part_idx, int32_t n_rows, void *out, int32_t out_dtype,
+                            float *lse_out, hipStream_t s);
+
+}  // namespace hkv

@@ -1,0 +1,140 @@
+// Scatter of new tokens' K/V into the pool's block format (one workgroup per touched page and KV
+// head).  bf16 pools: plain re-ordering.  fp8 pools: per-block amax, scale = amax/448, codes =
+// round-to-nearest-even(x / scale) saturated to +-448 (OCP e4m3), all in float.
+// (The "compute a prefix's KV once and keep it in GPU memory" step of Section 5, "Proactive Cache
+// Management", seen from the pool.)
+#include "hkv_device.h"
+
+namespace hkv {
+
+namespace {
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+
+__device__ __forceinline__ uint32_t quant4(float a, float b, float c, float d, float scale) {
+    auto q = [scale](float x) { return fminf(fmaxf(x / scale, -448.0f), 448.0f); };
+    int p = 0;
+    p = __builtin_amdgcn_cvt_pk_fp8_f32(q(a), q(b), p, false);
+    p = __builtin_amdgcn_cvt_pk_fp8_f32(q(c), q(d), p, true);
+    return (uint32_t)p;
+}
+
+template <int DT>
+__global__ __launch_bounds__(256) void pool_write_kernel(PoolWriteLaunch a) {
+    __shared__ uint16_t sV[kPage][kHeadDim + 8];
+    __shared__ float sRed[2][4];
+    __shared__ float sScale[2];
+
+    const int pi = blockIdx.x, h = blockIdx.y;
+    const int tid = threadIdx.x;
+    const int slot = tid >> 4, d0 = (tid & 15) * 8;
+    const int tok = pi * kPage + slot - a.first_slot;
+    const bool valid = tok >= 0 && tok < a.n_tokens;
+    const int page = a.page_ids[pi];
+    const size_t blk = ((size_t)page * a.num_kv_heads + h) * kBlockElems;
+
+    u32x4 kw = {0u, 0u, 0u, 0u}, vw = {0u, 0u, 0u, 0u};
+    if (valid) {
+        const size_t src = (((size_t)tok * a.num_kv_heads + h) * kHeadDim + d0) * 2;
+        kw = ld16(static_cast<const char *>(a.k_src) + src);
+        vw = ld16(static_cast<const char *>(a.v_src) + src);
+    }
+    *reinterpret_cast<u32x4 *>(&sV[slot][d0]) = vw;
+
+    // which slots of this page does the call write?  (contiguous range)
+    const int s_lo = max(0, a.first_slot - pi * kPage);
+    const int s_hi = min(kPage, a.first_slot + a.n_tokens - pi * kPage);  // exclusive
+
+    if (DT == 0) {
+        if (valid) {
+            uint16_t *kdst = static_cast<uint16_t *>(a.k_pages) + blk + (d0 >> 5) * (kPage * 32) + slot * 32 + (d0 & 31);
+            *reinterpret_cast<u32x4 *>(kdst) = kw;
+        }
+        __syncthreads();
+        const int d = tid >> 1, half = tid & 1;
+        uint16_t *vdst = static_cast<uint16_t *>(a.v_pages) + blk + d * kPage + half * 8;
+        if (s_lo <= half * 8 && s_hi >= half * 8 + 8) {
+            u32x4 w;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                w[j] = (uint32_t)sV[half * 8 + 2 * j][d] | ((uint32_t)sV[half * 8 + 2 * j + 1][d] << 16);
+            *reinterpret_cast<u32x4 *>(vdst) = w;
+        } else {
+            for (int j = 0; j < 8; ++j) {
+                const int sl = half * 8 + j;
+                if (sl >= s_lo && sl < s_hi) vdst[j] = sV[sl][d];
+            }
+        }
+    } else {
+        float kf[8], vf[8];
+        float ka = 0.f, va = 0.f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            kf[2 * j] = __uint_as_float(kw[j] << 16);
+            kf[2 * j + 1] = __uint_as_float(kw[j] & 0xFFFF0000u);
+            vf[2 * j] = __uint_as_float(vw[j] << 16);
+            vf[2 * j + 1] = __uint_as_float(vw[j] & 0xFFFF0000u);
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            ka = fmaxf(ka, fabsf(kf[j]));
+            va = fmaxf(va, fabsf(vf[j]));
+        }
+        ka = wave_max(ka);
+        va = wave_max(va);
+        if ((tid & 63) == 0) {
+            sRed[0][tid >> 6] = ka;
+            sRed[1][tid >> 6] = va;
+        }
+        __syncthreads();
+        if (tid < 2) {
+            const float am = fmaxf(fmaxf(sRed[tid][0], sRed[tid][1]), fmaxf(sRed[tid][2], sRed[tid][3]));
+            const float sc = am > 0.f ? am / 448.0f : 1.0f;
+            sScale[tid] = sc;
+            (tid ? a.v_scale : a.k_scale)[(size_t)page * a.num_kv_heads + h] = sc;
+        }
+        __syncthreads();
+        const float ksc = sScale[0], vsc = sScale[1];
+        if (valid) {
+            u32x2 c;
+            c[0] = quant4(kf[0], kf[1], kf[2], kf[3], ksc);
+            c[1] = quant4(kf[4], kf[5], kf[6], kf[7], ksc);
+            uint8_t *kdst = static_cast<uint8_t *>(a.k_pages) + blk + (d0 >> 6) * (kPage * 64) + slot * 64 + (d0 & 63);
+            *reinterpret_cast<u32x2 *>(kdst) = c;
+        }
+        const int d = tid >> 1, half = tid & 1;
+        float x[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) x[j] = bf16_bits_to_float(sV[half * 8 + j][d]);
+        u32x2 c;
+        c[0] = quant4(x[0], x[1], x[2], x[3], vsc);
+        c[1] = quant4(x[4], x[5], x[6], x[7], vsc);
+        uint8_t *vdst = static_cast<uint8_t *>(a.v_pages) + blk + d * kPage + half * 8;
+        if (s_lo <= half * 8 && s_hi >= half * 8 + 8) {
+            *reinterpret_cast<u32x2 *>(vdst) = c;
+        } else {
+            for (int j = 0; j < 8; ++j) {
+                const int sl = half * 8 + j;
+                if (sl >= s_lo && sl < s_hi) vdst[j] = (uint8_t)(c[j >> 2] >> (8 * (j & 3)));
+            }
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_pool_write(const PoolWriteLaunch &a, hipStream_t s) {
+    if (a.n_pages <= 0) return hipSuccess;
+    dim3 grid(a.n_pages, a.num_kv_heads), block(256);
+    if (a.dtype == 0)
+        hipLaunchKernelGGL(pool_write_kernel<0>, grid, block, 0, s, a);
+    else
+        hipLaunchKernelGGL(pool_write_kernel<1>, grid, block, 0, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace hkv

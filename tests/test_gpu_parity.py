@@ -1,0 +1,276 @@
+"""GPU parity: the HIP library, called through its C ABI, against the fp64 CPU oracle on the same
+seeded inputs.  Integer and byte outputs must be bit-exact; attention outputs (bf16 inputs, fp32
+accumulation) must meet max-abs <= 2e-2 and relative-L2 <= 5e-3."""
+import numpy as np
+import pytest
+
+from paper_2603_16104_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS, REL_L2 = 2e-2, 5e-3
+LSE_ABS = 2e-3   # fp32 log-sum-exp of scores of magnitude ~10: 1e-3 relative headroom over fp32 rounding
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need an MI355X"
+    from paper_2603_16104_amd import binding, runtime
+    binding.lib()
+    return runtime
+
+
+def check_close(got, exp, what=""):
+    got, exp = np.asarray(got, dtype=np.float64), np.asarray(exp, dtype=np.float64)
+    assert got.shape == exp.shape
+    assert np.isfinite(got).all(), f"{what}: non-finite output"
+    max_abs = np.abs(got - exp).max() if got.size else 0.0
+    den = np.linalg.norm(exp.ravel())
+    rel = np.linalg.norm((got - exp).ravel()) / den if den > 0 else np.linalg.norm((got - exp).ravel())
+    assert max_abs <= MAX_ABS, f"{what}: max_abs {max_abs:.3e}"
+    assert rel <= REL_L2, f"{what}: rel_l2 {rel:.3e}"
+    return max_abs, rel
+
+
+def check_lse(got, exp, what=""):
+    got, exp = np.asarray(got, dtype=np.float64), np.asarray(exp, dtype=np.float64)
+    fin = np.isfinite(exp)
+    assert np.array_equal(np.isneginf(got), np.isneginf(exp)), f"{what}: -inf pattern"
+    if fin.any():
+        assert np.abs(got[fin] - exp[fin]).max() <= LSE_ABS, f"{what}: lse {np.abs(got[fin] - exp[fin]).max():.3e}"
+
+
+def both_pools(gpu, oracle, w):
+    hp = oracle.HostPool(w.num_pages, w.num_kv_heads, w.kv_dtype)
+    hp.fill_from(w)
+    dp = gpu.DevicePool(w.num_pages, w.num_kv_heads, w.kv_dtype)
+    dp.fill_from(w)
+    return hp, dp
+
+
+def assert_pool_bytes_equal(hp, dp, w):
+    f = w.forest
+    used = np.zeros(w.num_pages, dtype=bool)
+    for v in range(f.n_nodes):
+        used[f.node_pages[f.page_begin[v]: f.page_begin[v] + f.n_pages[v]]] = True
+    H = w.num_kv_heads
+    for name in ("k", "v"):
+        g = getattr(dp, name).cpu().numpy().view(getattr(hp, name).dtype).reshape(w.num_pages, -1)
+        o = getattr(hp, name).reshape(w.num_pages, -1)
+        assert np.array_equal(g, o), f"pool {name} bytes differ"     # poison included: untouched slots stay untouched
+    if w.kv_dtype == wl.KV_FP8_E4M3:
+        for name in ("k_scale", "v_scale"):
+            g = getattr(dp, name).cpu().numpy().reshape(w.num_pages, H)[used]
+            o = getattr(hp, name).reshape(w.num_pages, H)[used]
+            assert np.array_equal(g.view(np.uint32), o.view(np.uint32)), f"pool {name} differs"
+
+
+# ------------------------------------------------------------------------------ pool writer (bytes: bit-exact)
+
+@pytest.mark.parametrize("kv_dtype", [wl.KV_BF16, wl.KV_FP8_E4M3])
+@pytest.mark.parametrize("seed", [41, 42])
+def test_pool_write_bit_exact(gpu, oracle, kv_dtype, seed):
+    w = wl.random_forest_workload(seed, kv_dtype=kv_dtype, depth=3, fanout=3, max_node_pages=6)
+    hp, dp = both_pools(gpu, oracle, w)
+    assert_pool_bytes_equal(hp, dp, w)
+    dp.close()
+
+
+def test_pool_write_slot_offsets_bit_exact(gpu, oracle):
+    import torch
+    rng = np.random.default_rng(5)
+    H, T = 2, 53
+    k = wl.f32_to_bf16_bits(rng.standard_normal((T, H, 128)).astype(np.float32))
+    v = wl.f32_to_bf16_bits(rng.standard_normal((T, H, 128)).astype(np.float32))
+    pages = np.array([6, 2, 9, 0, 4], dtype=np.int32)
+    hp = oracle.HostPool(11, H, oracle.BF16)
+    dp = gpu.DevicePool(11, H, oracle.BF16)
+    # three appends: 5 tokens, then 20 starting mid page, then the rest
+    cuts = [0, 5, 25, T]
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        hp.write(pages[a // 16:], a % 16, k[a:b], v[a:b])
+        dp.write(pages[a // 16:], a % 16, gpu.to_device_bits(k[a:b]), gpu.to_device_bits(v[a:b]))
+    torch.cuda.synchronize()
+    assert np.array_equal(dp.k.cpu().numpy().view(hp.k.dtype), hp.k) and np.array_equal(dp.v.cpu().numpy().view(hp.v.dtype), hp.v)
+    dp.close()
+
+
+def test_fp8_quantisation_edge_values_bit_exact(gpu, oracle):
+    """Ties, subnormal codes, zeros, negative zero and a block whose amax maps exactly to 448."""
+    import torch
+    H, T = 1, 16
+    x = np.zeros((T, H, 128), dtype=np.float32)
+    grid = np.array([oracle.e4m3_value(c) for c in range(0x7F)], dtype=np.float64)
+    mids = 0.5 * (grid[:-1] + grid[1:])
+    vals = np.concatenate([grid, mids, -grid, -mids, [0.0, -0.0, 448.0]])
+    x.reshape(-1)[: len(vals)] = vals.astype(np.float32)      # amax 448 -> scale exactly 1
+    kb = wl.f32_to_bf16_bits(x)
+    hp = oracle.HostPool(2, H, oracle.FP8_E4M3)
+    dp = gpu.DevicePool(2, H, oracle.FP8_E4M3)
+    hp.write([1], 0, kb, kb)
+    dp.write([1], 0, gpu.to_device_bits(kb), gpu.to_device_bits(kb))
+    torch.cuda.synchronize()
+    assert np.array_equal(dp.k.cpu().numpy().view(hp.k.dtype), hp.k) and np.array_equal(dp.v.cpu().numpy().view(hp.v.dtype), hp.v)
+    assert dp.k_scale.cpu().numpy()[1] == hp.k_scale[1] == 1.0
+    dp.close()
+
+
+# ------------------------------------------------------------------------------ lse_merge
+
+def test_lse_merge_kernel(gpu, oracle):
+    import torch
+    from paper_2603_16104_amd import binding as hkv
+    rng = np.random.default_rng(7)
+    n_parts, n_rows = 700, 150
+    o = rng.standard_normal((n_parts, 128)).astype(np.float32)
+    lse = (rng.standard_normal(n_parts) * 4).astype(np.float32)
+    lse[rng.random(n_parts) < 0.1] = -np.inf
+    o[np.isneginf(lse)] = np.nan                       # ignored partials may hold anything
+    counts = rng.integers(0, 9, size=n_rows)
+    counts[3] = 0
+    indptr = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    pidx = rng.integers(0, n_parts, size=indptr[-1]).astype(np.int32)
+    first = indptr[7]
+    if counts[7]:
+        lse[pidx[first: first + counts[7]]] = -np.inf      # a row whose partials are all empty
+        o[pidx[first: first + counts[7]]] = np.nan
+    exp_o, exp_l = oracle.lse_merge(np.nan_to_num(o.astype(np.float64)), lse.astype(np.float64), indptr, pidx)
+    d = lambda a: torch.from_numpy(a).cuda()
+    do, dl, di, dp = d(o), d(lse), d(indptr), d(pidx)
+    for out_dtype in (hkv.FP32, hkv.BF16):
+        out = torch.empty((n_rows, 128), dtype=torch.float32 if out_dtype == hkv.FP32 else torch.int16, device="cuda")
+        lout = torch.empty(n_rows, dtype=torch.float32, device="cuda")
+        hkv.lse_merge(do, dl, di, dp, n_rows, out, out_dtype, lout)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().astype(np.float64) if out_dtype == hkv.FP32 else gpu.bf16_tensor_to_f64(out)
+        tol = 1e-5 if out_dtype == hkv.FP32 else 2e-2
+        assert np.abs(got - exp_o).max() <= tol
+        check_lse(lout.cpu().numpy(), exp_l, "lse_merge")
+        assert (got[3] == 0).all() and (got[7] == 0).all()
+
+
+# ------------------------------------------------------------------------------ decode
+
+def run_decode(gpu, oracle, w, one_shot=False):
+    import torch
+    from paper_2603_16104_amd import binding as hkv
+    hp, dp = both_pools(gpu, oracle, w)
+    exp_o, exp_l = oracle.run_workload(w, hp)
+    if one_shot:
+        f = w.forest
+        nbytes = hkv.attn_decode_workspace_bytes(dp.handle, f.nodes, f.node_pages, f.req_leaf, w.num_q_heads)
+        ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
+        q = gpu.to_device_bits(w.q())
+        out = torch.zeros((f.n_req, w.num_q_heads, 128), dtype=torch.int16, device="cuda")
+        lse = torch.zeros((f.n_req, w.num_q_heads), dtype=torch.float32, device="cuda")
+        for _ in range(2):      # second call reuses the cached plan
+            hkv.attn_decode_prefix_tree(dp.handle, q, f.nodes, f.node_pages, f.req_leaf, w.num_q_heads,
+                                        float(w.scale), out, lse, ws, nbytes)
+        torch.cuda.synchronize()
+        got_o, got_l = gpu.bf16_tensor_to_f64(out), lse.cpu().numpy()
+    else:
+        r = gpu.DecodeRunner(dp, w)
+        r.run()
+        torch.cuda.synchronize()
+        got_o, got_l = gpu.bf16_tensor_to_f64(r.out), r.lse.cpu().numpy()
+        r.close()
+    dp.close()
+    res = check_close(got_o, exp_o, w.name)
+    check_lse(got_l, exp_l, w.name)
+    return res
+
+
+@pytest.mark.parametrize("seed", [51, 52, 53, 54])
+@pytest.mark.parametrize("kv_dtype", [wl.KV_BF16, wl.KV_FP8_E4M3])
+def test_decode_random_forests(gpu, oracle, seed, kv_dtype):
+    hq, hkv_ = [(8, 2), (8, 1), (4, 4), (16, 1)][seed % 4]
+    w = wl.random_forest_workload(seed, kv_dtype=kv_dtype, num_q_heads=hq, num_kv_heads=hkv_, depth=4, fanout=3,
+                                  max_node_pages=9, n_roots=2)
+    run_decode(gpu, oracle, w)
+
+
+def test_decode_many_requests_per_node(gpu, oracle):
+    """More than 64 query rows under one node: row groups and token chunks are both split."""
+    w = wl.config2(seed=77, n_req=40, root_tokens=1200 // 16 * 16, private_tokens=100)
+    run_decode(gpu, oracle, w)
+
+
+def test_decode_config1_one_shot(gpu, oracle):
+    _, dec = wl.config1()
+    run_decode(gpu, oracle, dec, one_shot=True)
+
+
+def test_decode_empty_and_degenerate(gpu, oracle):
+    import torch
+    from paper_2603_16104_amd import binding as hkv
+    # requests whose whole path is empty give zeros and -inf; a forest without requests is a no-op
+    parent, ntok = [-1, 0, 0], [0, 0, 5]
+    f = wl.make_forest(parent, ntok, [1, 2, 0], np.arange(4, dtype=np.int32))
+    w = wl.Workload(name="degenerate", num_q_heads=4, num_kv_heads=2, kv_dtype=wl.KV_BF16, num_pages=4, seed=3,
+                    forest=f, mode="decode")
+    hp, dp = both_pools(gpu, oracle, w)
+    exp_o, exp_l = oracle.run_workload(w, hp)
+    r = gpu.DecodeRunner(dp, w)
+    r.out.fill_(12345)
+    r.run()
+    torch.cuda.synchronize()
+    got_o, got_l = gpu.bf16_tensor_to_f64(r.out), r.lse.cpu().numpy()
+    check_close(got_o, exp_o, "degenerate")
+    check_lse(got_l, exp_l, "degenerate")
+    assert (got_o[0] == 0).all() and np.isneginf(got_l[0]).all()
+    r.close()
+    plan = hkv.hkv_decode_plan_create(dp.handle, f.nodes, f.node_pages, np.zeros(0, dtype=np.int32), 4)
+    hkv.attn_decode_plan_run(plan, None, 1.0, None, None, None, 0)
+    hkv.hkv_decode_plan_destroy(plan)
+    dp.close()
+
+
+# ------------------------------------------------------------------------------ prefill
+
+def run_prefill(gpu, oracle, w, one_shot=False):
+    import torch
+    from paper_2603_16104_amd import binding as hkv
+    hp, dp = both_pools(gpu, oracle, w)
+    exp_o, exp_l = oracle.run_workload(w, hp)
+    r = gpu.PrefillRunner(dp, w)
+    if one_shot:
+        for _ in range(2):
+            hkv.attn_prefill_with_prefix(dp.handle, r.q, r.cu_q, r.block_table, r.kv_len, w.num_q_heads, r.scale,
+                                         r.out, r.lse)
+    else:
+        r.run()
+    torch.cuda.synchronize()
+    got_o, got_l = gpu.bf16_tensor_to_f64(r.out), r.lse.cpu().numpy()
+    r.close()
+    dp.close()
+    res = check_close(got_o, exp_o, w.name)
+    check_lse(got_l, exp_l, w.name)
+    return res
+
+
+def test_prefill_config1(gpu, oracle):
+    pre, _ = wl.config1()
+    run_prefill(gpu, oracle, pre, one_shot=True)
+
+
+@pytest.mark.parametrize("seed", [61, 62, 63, 64])
+def test_prefill_random_forests(gpu, oracle, seed):
+    hq, hkv_ = [(8, 2), (8, 1), (4, 4), (4, 2)][seed % 4]
+    w = wl.random_forest_workload(seed, mode="prefill", num_q_heads=hq, num_kv_heads=hkv_, depth=3, fanout=3,
+                                  max_node_pages=12, n_roots=2)
+    run_prefill(gpu, oracle, w)
+
+
+def test_prefill_ragged_medium(gpu, oracle):
+    """Several query tiles per request, ragged suffix lengths, prefix spanning many 64-token blocks."""
+    w = wl.config4(seed=99, n_req=3, prefix_tokens=400 // 16 * 16, lo=70, hi=200)
+    run_prefill(gpu, oracle, w)
+
+
+def test_prefill_without_prefix(gpu, oracle):
+    parent, ntok = [-1, -1], [77, 130]
+    f = wl.make_forest(parent, ntok, [0, 1], np.random.default_rng(1).permutation(20).astype(np.int32))
+    w = wl.Workload(name="no_prefix", num_q_heads=8, num_kv_heads=2, kv_dtype=wl.KV_BF16, num_pages=20, seed=8,
+                    forest=f, mode="prefill", q_len=np.array(ntok, dtype=np.int32))
+    run_prefill(gpu, oracle, w)
