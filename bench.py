@@ -1,0 +1,273 @@
+#!/usr/bin/env python3
+"""Benchmark of the prefix-tree paged-attention hot path on one MI355X.
+
+A step is one pass of the hot path over one batch of the headline workload: the Llama-3-8B
+shaped decode (64 requests sharing a 2048-token prefix, 512 private tokens each, one query token
+per request) = per-node decode kernel + log-sum-exp merge kernel behind attn_decode_plan_run.
+All inputs are resident in HBM before the timed region; the plan (tree walk, work list) is built
+once per topology outside it.  Steps rotate over several identical pools so that the 256 MB
+last-level cache cannot serve the KV bytes.
+
+Prints one JSON line: the headline metric (unique-KV bytes per second), the roofline of the
+dominant kernel measured with HIP events, the CPU oracle timed on the host cores, and (unless
+--no-extras) the other single-GPU workloads as context.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix-core peak
+
+
+def log(msg: str) -> None:
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def time_steps(fn, steps: int, warmup: int):
+    import torch
+    for i in range(warmup):
+        fn(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        fn(warmup + i)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def make_pools(runtime, w, n_pools: int):
+    """n_pools identical pools (same page ids, distinct HBM), each with its own plan and buffers."""
+    first = runtime.DevicePool(w.num_pages, w.num_kv_heads, w.kv_dtype)
+    first.fill_from(w)
+    pools = [first]
+    for _ in range(n_pools - 1):
+        p = runtime.DevicePool(w.num_pages, w.num_kv_heads, w.kv_dtype, poison=False)
+        p.k.copy_(first.k)
+        p.v.copy_(first.v)
+        if first.k_scale is not None:
+            p.k_scale.copy_(first.k_scale)
+            p.v_scale.copy_(first.v_scale)
+        pools.append(p)
+    return pools
+
+
+def bench_decode(runtime, hkv, w, steps: int, warmup: int, n_pools: int, profile_steps: int):
+    import torch
+    pools = make_pools(runtime, w, n_pools)
+    runners = [runtime.DecodeRunner(p, w) for p in pools]
+    sec = time_steps(lambda i: runners[i % n_pools].run(), steps, warmup)
+    # same steps again with HIP events around each kernel (on the launch stream)
+    node_ms = merge_ms = 0.0
+    for r in runners:
+        hkv.hkv_decode_plan_set_profiling(r.plan, True)
+    for i in range(profile_steps):
+        r = runners[i % n_pools]
+        r.run()
+        a, b = hkv.hkv_decode_plan_elapsed_ms(r.plan)
+        node_ms += a
+        merge_ms += b
+    for r in runners:
+        hkv.hkv_decode_plan_set_profiling(r.plan, False)
+    node_ms /= max(1, profile_steps)
+    merge_ms /= max(1, profile_steps)
+    # cache-resident variant for context (always the same pool)
+    sec_hot = time_steps(lambda i: runners[0].run(), steps, warmup)
+    info = {
+        "items": int(len(hkv.hkv_decode_plan_items(runners[0].plan))),
+        "partials": int(hkv.hkv_decode_plan_num_parts(runners[0].plan)),
+        "workspace_bytes": int(runners[0].ws_bytes),
+    }
+    for r in runners:
+        r.close()
+    for p in pools:
+        p.close()
+    del runners, pools
+    torch.cuda.empty_cache()
+    return sec, node_ms, merge_ms, sec_hot, info
+
+
+def bench_prefill(runtime, hkv, w, steps: int, warmup: int):
+    import torch
+    pool = runtime.DevicePool(w.num_pages, w.num_kv_heads, w.kv_dtype)
+    pool.fill_from(w)
+    r = runtime.PrefillRunner(pool, w)
+    sec = time_steps(lambda i: r.run(), steps, warmup)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(steps):
+        r.run()
+    ev1.record()
+    torch.cuda.synchronize()
+    kern_ms = ev0.elapsed_time(ev1) / steps
+    tiles = int(len(hkv.hkv_prefill_plan_tiles(r.plan)))
+    r.close()
+    pool.close()
+    torch.cuda.empty_cache()
+    return sec, kern_ms, tiles
+
+
+def bench_pool_write(runtime, w, steps: int):
+    """KV write of new tokens (timed apart from attention): one call writing 8192 tokens."""
+    import numpy as np
+    import torch
+    n_tok = 8192
+    pool = runtime.DevicePool(n_tok // 16, w.num_kv_heads, w.kv_dtype, poison=False)
+    k = torch.randn((n_tok, w.num_kv_heads, 128), device="cuda").to(torch.bfloat16).view(torch.int16)
+    v = torch.randn((n_tok, w.num_kv_heads, 128), device="cuda").to(torch.bfloat16).view(torch.int16)
+    ids = np.random.default_rng(0).permutation(n_tok // 16).astype(np.int32)
+    sec = time_steps(lambda i: pool.write(ids, 0, k, v), steps, 3)
+    pool.close()
+    src_bytes = 2 * n_tok * w.num_kv_heads * 128 * 2
+    return src_bytes / sec / 1e9
+
+
+def cpu_baseline_decode(w, budget_s: float = 20.0):
+    """The fp64 oracle as it stands on the host cores: whole workload, repeated within the budget."""
+    from oracle import oracle as orc
+    hp = orc.HostPool(w.num_pages, w.num_kv_heads, w.kv_dtype)
+    hp.fill_from(w)
+    bt, kv_len, *_ = orc.flatten_workload(w)
+    q = w.q()
+    reps, t_total = 0, 0.0
+    while reps < 1 or (t_total < budget_s / 2 and reps < 20):
+        t0 = time.perf_counter()
+        orc.attn_decode(hp, q, bt, kv_len, float(w.scale))
+        t_total += time.perf_counter() - t0
+        reps += 1
+    sec = t_total / reps
+    return {
+        "value": w.unique_kv_bytes() / sec / 1e9,
+        "unit": "GB/s",
+        "cores": orc.num_threads(),
+        "kind": "oracle",
+        "sample": f"whole workload ({w.forest.n_req} requests, {w.forest.attended_tokens()} attended tokens), "
+                  f"mean of {reps} runs, {sec:.3f} s each; the oracle gathers every request's full sequence, "
+                  "so it reads attended rather than unique bytes",
+        "attended_tokens_per_s": w.forest.attended_tokens() / sec,
+        "seconds_per_step": sec,
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--pools", type=int, default=4, help="identical pools to rotate over (cache defeat)")
+    ap.add_argument("--no-extras", action="store_true", help="skip the context workloads (c3, c4, pool write)")
+    ap.add_argument("--c5", action="store_true", help="also time the fp8 forest (2.4 GB pool, slow to generate)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (every box has one GPU); "
+              "run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2603_16104_amd import binding as hkv, runtime, workloads as wl
+    if not torch.cuda.is_available():
+        print("bench.py needs an MI355X; no GPU is visible", file=sys.stderr)
+        return 2
+    hkv.lib()
+
+    w = wl.config2()
+    log(f"workload {w.name}: {w.forest.n_req} requests, unique KV {w.unique_kv_bytes() / 1e6:.1f} MB")
+    sec, node_ms, merge_ms, sec_hot, info = bench_decode(runtime, hkv, w, args.steps, args.warmup, args.pools,
+                                                        min(args.steps, 100))
+    uniq = w.unique_kv_bytes()
+    value = uniq / sec / 1e9
+    achieved = uniq / (node_ms * 1e-3) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "decode_c2_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+        except Exception:
+            traffic = None
+    result = {
+        "metric": "decode_unique_kv_bandwidth",
+        "value": round(value, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(sec * 1e3, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": "c2_llama8b_decode: 64 requests, 2048-token shared prefix + 512 private tokens each, "
+                        "32 q / 8 kv heads, head_dim 128, page 16, bf16 KV, 1 query token per request",
+            "unique_kv_bytes": uniq,
+            "attended_tokens": w.forest.attended_tokens(),
+            "attended_tokens_per_s": round(w.forest.attended_tokens() / sec, 1),
+            "pools_rotated": args.pools,
+            "step": "attn_decode_plan_run = per-node decode kernel + lse merge kernel; plan built once outside",
+            **info,
+        },
+        "roofline": {
+            "bound": "hbm",
+            "kernel": "decode_node_kernel<bf16>",
+            "achieved": round(achieved, 2),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "traffic": traffic,
+            "kernel_ms": round(node_ms, 5),
+            "merge_kernel_ms": round(merge_ms, 5),
+            "whole_step_frac": round(value / HBM_PEAK_GBS, 4),
+        },
+        "paper_context": "the paper reports end-to-end speedups only (up to 1.56x over KVFlow on 2x H100 NVL); "
+                         "no attention-kernel number exists to compare with",
+    }
+    result["extra"] = {"c2_cache_resident_GBps": round(uniq / sec_hot / 1e9, 2)}
+
+    if not args.no_extras:
+        w3 = wl.config3()
+        s3, n3, m3, h3, i3 = bench_decode(runtime, hkv, w3, max(20, args.steps // 2), args.warmup, args.pools, 50)
+        result["extra"]["c3_fanout_decode"] = {
+            "unique_kv_GBps": round(w3.unique_kv_bytes() / s3 / 1e9, 2),
+            "attended_tokens_per_s": round(w3.forest.attended_tokens() / s3, 1),
+            "ms_per_step": round(s3 * 1e3, 5), "node_kernel_ms": round(n3, 5), "merge_kernel_ms": round(m3, 5),
+            "hbm_frac_whole_step": round(w3.unique_kv_bytes() / s3 / 1e9 / HBM_PEAK_GBS, 4), **i3}
+        log("c3 done")
+        w4 = wl.config4()
+        s4, k4, t4 = bench_prefill(runtime, hkv, w4, 5, 2)
+        tflops = w4.useful_flop() / (k4 * 1e-3) / 1e12
+        result["extra"]["c4_prefix_hit_prefill"] = {
+            "new_tokens_per_s": round(w4.total_q() / s4, 1), "ms_per_step": round(s4 * 1e3, 4),
+            "kernel_ms": round(k4, 4), "useful_TFLOPs": round(tflops, 2),
+            "mfma_bf16_frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4), "new_tokens": int(w4.total_q()),
+            "useful_flop": int(w4.useful_flop()), "tiles": t4}
+        log("c4 done")
+        result["extra"]["kv_pool_write_src_GBps"] = round(bench_pool_write(runtime, w, 20), 1)
+    if args.c5:
+        w5 = wl.config5()
+        s5, n5, m5, h5, i5 = bench_decode(runtime, hkv, w5, 20, 3, 1, 10)
+        result["extra"]["c5_forest_fp8_decode"] = {
+            "unique_kv_GBps": round(w5.unique_kv_bytes() / s5 / 1e9, 2),
+            "attended_tokens_per_s": round(w5.forest.attended_tokens() / s5, 1),
+            "ms_per_step": round(s5 * 1e3, 5), "node_kernel_ms": round(n5, 5), "merge_kernel_ms": round(m5, 5),
+            "hbm_frac_whole_step": round(w5.unique_kv_bytes() / s5 / 1e9 / HBM_PEAK_GBS, 4), **i5}
+    if not args.no_cpu:
+        log("timing the CPU oracle")
+        result["cpu_baseline"] = cpu_baseline_decode(w)
+    else:
+        result["cpu_baseline"] = None
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

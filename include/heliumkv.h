@@ -220,6 +220,14 @@ int hkv_decode_plan_merge_csr(const hkv_decode_plan *plan, int32_t *row_indptr, 
 int attn_decode_plan_run(hkv_decode_plan *plan, const void *q, float scale, void *out, float *lse_out,
                          void *workspace, size_t workspace_bytes, void *stream);
 
+/* Profiling aid.  While enabled, attn_decode_plan_run brackets its two kernels with HIP events
+ * on the stream it is given (this adds a few microseconds between them).
+ * hkv_decode_plan_elapsed_ms waits for the most recent profiled run to finish and returns the
+ * GPU time of the per-node kernel and of the merge kernel in milliseconds.
+ * EINVAL if no profiled run has been queued. */
+int hkv_decode_plan_set_profiling(hkv_decode_plan *plan, int32_t enable);
+int hkv_decode_plan_elapsed_ms(hkv_decode_plan *plan, float *node_ms /* host */, float *merge_ms /* host */);
+
 /* One-shot form: plans (or reuses the plan cached in the pool when the forest is unchanged) and
  * runs.  Same arguments as the two calls above. */
 int attn_decode_prefix_tree(hkv_pool *pool, const void *q, const hkv_node *nodes, int32_t n_nodes,

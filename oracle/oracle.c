@@ -81,22 +81,31 @@ double orc_e4m3_value(uint8_t c) {
     return s ? -v : v;
 }
 
-/* Round-to-nearest-even onto the e4m3 grid, saturating at +-448. */
+/* Round-to-nearest-even onto the e4m3 grid, saturating at +-448.  The grid spacing around a is
+ * 2^(e-3) with e = floor(log2 a), but never finer than the subnormal spacing 2^-9; a / spacing is
+ * rounded to the nearest integer with ties to even (rint under the default rounding mode), which
+ * may carry into the next binade, and the code is read off the rounded value. */
 uint8_t orc_e4m3_encode(float y) {
     if (isnan(y)) return 0x7F;
     uint8_t sign = signbit(y) ? 0x80 : 0x00;
     double a = fabs((double)y);
     if (a >= 448.0) return (uint8_t)(sign | 0x7E);
-    int best = 0;
-    double best_err = INFINITY;
-    for (int c = 0; c <= 0x7E; ++c) {
-        double err = fabs(orc_e4m3_value((uint8_t)c) - a);
-        if (err < best_err || (err == best_err && (c & 1) == 0)) {
-            best_err = err;
-            best = c;
-        }
+    int e;
+    (void)frexp(a, &e); /* a = f * 2^e with f in [0.5, 1)  ->  floor(log2 a) = e - 1 */
+    e -= 1;
+    if (a == 0.0 || e < -6) e = -6;
+    double spacing = ldexp(1.0, e - 3);
+    double v = rint(a / spacing) * spacing; /* exact: a / spacing < 16 has few significant bits */
+    if (v > 448.0) v = 448.0;
+    int code;
+    if (v < ldexp(1.0, -6)) {
+        code = (int)(v / ldexp(1.0, -9)); /* subnormal: mantissa in units of 2^-9 */
+    } else {
+        int e2;
+        double f = frexp(v, &e2); /* v = f * 2^e2, f in [0.5, 1) -> v = (2f) * 2^(e2-1) */
+        code = ((e2 - 1 + 7) << 3) | (int)((2.0 * f - 1.0) * 8.0);
     }
-    return (uint8_t)(sign | best);
+    return (uint8_t)(sign | code);
 }
 
 static size_t elem_size(int dtype) { return dtype == ORC_BF16 ? 2 : dtype == ORC_FP8_E4M3 ? 1 : 4; }

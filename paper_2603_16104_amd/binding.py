@@ -28,6 +28,7 @@ EXPORTS = [
     "lse_merge", "hkv_decode_plan_create", "hkv_decode_plan_destroy", "hkv_decode_plan_workspace_bytes",
     "hkv_decode_plan_num_items", "hkv_decode_plan_num_parts", "hkv_decode_plan_items",
     "hkv_decode_plan_num_merge_entries", "hkv_decode_plan_merge_csr", "attn_decode_plan_run",
+    "hkv_decode_plan_set_profiling", "hkv_decode_plan_elapsed_ms",
     "attn_decode_prefix_tree", "attn_decode_workspace_bytes", "hkv_prefill_plan_create", "hkv_prefill_plan_destroy",
     "hkv_prefill_plan_num_tiles", "hkv_prefill_plan_tiles", "attn_prefill_plan_run", "attn_prefill_with_prefix",
     "attn_prefill_workspace_bytes",
@@ -224,6 +225,16 @@ def hkv_decode_plan_merge_csr(plan, n_rows: int):
 def attn_decode_plan_run(plan, q, scale: float, out, lse_out, workspace, workspace_bytes: int, stream=None) -> None:
     _check(lib().attn_decode_plan_run(plan, _dev(q), C.c_float(scale), _dev(out), _dev(lse_out), _dev(workspace),
                                       C.c_size_t(workspace_bytes), _stream(stream)))
+
+
+def hkv_decode_plan_set_profiling(plan, enable: bool) -> None:
+    _check(lib().hkv_decode_plan_set_profiling(plan, C.c_int32(1 if enable else 0)))
+
+
+def hkv_decode_plan_elapsed_ms(plan):
+    a, b = C.c_float(), C.c_float()
+    _check(lib().hkv_decode_plan_elapsed_ms(plan, C.byref(a), C.byref(b)))
+    return float(a.value), float(b.value)
 
 
 def attn_decode_prefix_tree(pool, q, nodes, node_pages, req_leaf, num_q_heads: int, scale: float, out, lse_out,

@@ -68,6 +68,8 @@ struct hkv_decode_plan {
     void *dev = nullptr;
     DecodeItem *d_items = nullptr;
     int32_t *d_pages = nullptr, *d_node_req_idx = nullptr, *d_row_indptr = nullptr, *d_part_idx = nullptr;
+    bool profiling = false, profiled_run = false;
+    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
 };
 
 struct hkv_prefill_plan {
@@ -510,6 +512,8 @@ extern "C" int hkv_decode_plan_create(hkv_pool *pool, const hkv_node *nodes, int
 extern "C" int hkv_decode_plan_destroy(hkv_decode_plan *plan) {
     if (!plan) return HKV_OK;
     if (plan->dev) (void)hipFree(plan->dev);  // hipFree waits for work that may still read it
+    for (hipEvent_t e : plan->ev)
+        if (e) (void)hipEventDestroy(e);
     delete plan;
     return HKV_OK;
 }
@@ -560,13 +564,37 @@ extern "C" int attn_decode_plan_run(hkv_decode_plan *plan, const void *q, float 
     float *o_parts = static_cast<float *>(workspace);
     float *lse_parts = reinterpret_cast<float *>(static_cast<char *>(workspace) +
                                                  align_up((size_t)plan->n_parts * HKV_HEAD_DIM * sizeof(float), 256));
+    const bool prof = plan->profiling;
+    if (prof) HKV_HIP(hipEventRecord(plan->ev[0], s));
     if (!plan->items.empty()) {
         DecodeLaunch a{view_of(plan->pool), q, plan->d_items, plan->d_pages, plan->d_node_req_idx, o_parts, lse_parts,
                        (int32_t)plan->items.size(), plan->num_q_heads, scale};
         HKV_HIP(launch_decode(a, s));
     }
+    if (prof) HKV_HIP(hipEventRecord(plan->ev[1], s));
     HKV_HIP(launch_lse_merge(o_parts, lse_parts, plan->d_row_indptr, plan->d_part_idx, plan->n_req * plan->num_q_heads,
                              out, HKV_BF16, lse_out, s));
+    if (prof) {
+        HKV_HIP(hipEventRecord(plan->ev[2], s));
+        plan->profiled_run = true;
+    }
+    return HKV_OK;
+}
+
+extern "C" int hkv_decode_plan_set_profiling(hkv_decode_plan *plan, int32_t enable) {
+    if (!plan) return fail(HKV_EINVAL, "hkv_decode_plan_set_profiling: null plan");
+    if (enable && !plan->ev[0])
+        for (hipEvent_t &e : plan->ev) HKV_HIP(hipEventCreate(&e));
+    plan->profiling = enable != 0;
+    return HKV_OK;
+}
+
+extern "C" int hkv_decode_plan_elapsed_ms(hkv_decode_plan *plan, float *node_ms, float *merge_ms) {
+    if (!plan || !node_ms || !merge_ms) return fail(HKV_EINVAL, "hkv_decode_plan_elapsed_ms: null argument");
+    if (!plan->profiled_run) return fail(HKV_EINVAL, "hkv_decode_plan_elapsed_ms: no profiled run has been queued");
+    HKV_HIP(hipEventSynchronize(plan->ev[2]));
+    HKV_HIP(hipEventElapsedTime(node_ms, plan->ev[0], plan->ev[1]));
+    HKV_HIP(hipEventElapsedTime(merge_ms, plan->ev[1], plan->ev[2]));
     return HKV_OK;
 }
 
