@@ -182,6 +182,16 @@ int lse_merge(const float *o_parts, const float *lse_parts, const int32_t *row_i
               const int32_t *part_idx, int32_t n_rows, void *out, int32_t out_dtype, float *lse_out,
               void *stream);
 
+/* The same combine for partials stored densely: output row i owns the partials i*max_parts + k,
+ * k < part_count[i / rows_per_count] (part_count: device int32 [ceil(n_rows / rows_per_count)],
+ * each entry in 0..max_parts).  This is the layout attn_decode_plan_run uses: the prefix above a
+ * tree node is common to all requests below it, so a node's chunks take the same positions k in
+ * every one of those requests' lists, and rows_per_count is the number of query heads.
+ * o_parts and out must be 16-byte aligned. */
+int lse_merge_dense(const float *o_parts, const float *lse_parts, const int32_t *part_count,
+                    int32_t rows_per_count, int32_t max_parts, int32_t n_rows, void *out, int32_t out_dtype,
+                    float *lse_out, void *stream);
+
 /* ------------------------------------------------------------------------------------------
  * Batched decode over a prefix forest: one query token per request.  Every node's pages are
  * read from HBM once and applied to all requests below the node; the per-node partial results
@@ -202,15 +212,17 @@ int hkv_decode_plan_destroy(hkv_decode_plan *plan);
 /* Bytes of device workspace attn_decode_plan_run needs (partial o and lse), 0 on a null plan. */
 size_t hkv_decode_plan_workspace_bytes(const hkv_decode_plan *plan);
 /* Introspection for tests and tools (host copies).  Work item layout, 8 int32 each:
- * (page_off, n_tokens, kv_head, req_off, n_req, part_base, tok_begin, node).  page_off indexes
- * the plan's page list (= node_pages), req_off its node->request CSR values. */
+ * (page_off, n_tokens, kv_head, req_off, n_req, part_slot, tok_begin, node).  page_off indexes
+ * the plan's page list (= node_pages), req_off the node->request CSR values that
+ * prefix_tree_flatten returns.  An item applies the tokens [tok_begin, tok_begin + n_tokens) of
+ * `node` to n_req requests x (num_q_heads / num_kv_heads) heads of kv_head; row (request r, head
+ * h) of the item writes partial (r*num_q_heads + h)*max_parts + part_slot. */
 int32_t hkv_decode_plan_num_items(const hkv_decode_plan *plan);
-int32_t hkv_decode_plan_num_parts(const hkv_decode_plan *plan);
+int32_t hkv_decode_plan_num_parts(const hkv_decode_plan *plan); /* n_req*num_q_heads*max_parts */
 int hkv_decode_plan_items(const hkv_decode_plan *plan, int32_t *items_out /* [n_items][8] */);
-/* Merge CSR over output rows (request*num_q_heads + head): row_indptr [n_req*Hq + 1], part_idx
- * [row_indptr[last]] (pass NULL to query sizes only via the return of ..._num_merge_entries). */
-int32_t hkv_decode_plan_num_merge_entries(const hkv_decode_plan *plan);
-int hkv_decode_plan_merge_csr(const hkv_decode_plan *plan, int32_t *row_indptr, int32_t *part_idx);
+int32_t hkv_decode_plan_max_parts(const hkv_decode_plan *plan);
+/* part_count [n_req]: number of partials each row of the request owns. */
+int hkv_decode_plan_part_counts(const hkv_decode_plan *plan, int32_t *part_count);
 
 /* Runs one decode step.  q: device [n_req][num_q_heads][128] bf16.  out: device, same shape,
  * bf16.  lse_out: device [n_req][num_q_heads] float or NULL.  workspace: device, at least

@@ -27,7 +27,7 @@ EXPORTS = [
     "kv_pool_num_free", "kv_pool_refcount", "kv_pool_write", "prefix_tree_flatten", "prefix_tree_prefill_usage",
     "lse_merge", "hkv_decode_plan_create", "hkv_decode_plan_destroy", "hkv_decode_plan_workspace_bytes",
     "hkv_decode_plan_num_items", "hkv_decode_plan_num_parts", "hkv_decode_plan_items",
-    "hkv_decode_plan_num_merge_entries", "hkv_decode_plan_merge_csr", "attn_decode_plan_run",
+    "hkv_decode_plan_max_parts", "hkv_decode_plan_part_counts", "lse_merge_dense", "attn_decode_plan_run",
     "hkv_decode_plan_set_profiling", "hkv_decode_plan_elapsed_ms",
     "attn_decode_prefix_tree", "attn_decode_workspace_bytes", "hkv_prefill_plan_create", "hkv_prefill_plan_destroy",
     "hkv_prefill_plan_num_tiles", "hkv_prefill_plan_tiles", "attn_prefill_plan_run", "attn_prefill_with_prefix",
@@ -185,6 +185,13 @@ def lse_merge(o_parts, lse_parts, row_indptr, part_idx, n_rows: int, out, out_dt
                            _stream(stream) if n_rows > 0 else C.c_void_p(None)))
 
 
+def lse_merge_dense(o_parts, lse_parts, part_count, rows_per_count: int, max_parts: int, n_rows: int, out,
+                    out_dtype: int, lse_out=None, stream=None) -> None:
+    _check(lib().lse_merge_dense(_dev(o_parts), _dev(lse_parts), _dev(part_count), C.c_int32(rows_per_count),
+                                 C.c_int32(max_parts), C.c_int32(n_rows), _dev(out), C.c_int32(out_dtype),
+                                 _dev(lse_out), _stream(stream) if n_rows > 0 else C.c_void_p(None)))
+
+
 # ----------------------------------------------------------------------------------------- decode
 def hkv_decode_plan_create(pool, nodes, node_pages, req_leaf, num_q_heads: int, flags: int = 0) -> C.c_void_p:
     nodes, node_pages, req_leaf = _nodes(nodes), _host_i32(node_pages), _host_i32(req_leaf)
@@ -214,12 +221,14 @@ def hkv_decode_plan_num_parts(plan) -> int:
     return _check(lib().hkv_decode_plan_num_parts(plan))
 
 
-def hkv_decode_plan_merge_csr(plan, n_rows: int):
-    n = _check(lib().hkv_decode_plan_num_merge_entries(plan))
-    indptr = np.empty(n_rows + 1, dtype=np.int32)
-    idx = np.empty(n, dtype=np.int32)
-    _check(lib().hkv_decode_plan_merge_csr(plan, _hp(indptr), _hp(idx)))
-    return indptr, idx
+def hkv_decode_plan_max_parts(plan) -> int:
+    return _check(lib().hkv_decode_plan_max_parts(plan))
+
+
+def hkv_decode_plan_part_counts(plan, n_req: int) -> np.ndarray:
+    cnt = np.empty(n_req, dtype=np.int32)
+    _check(lib().hkv_decode_plan_part_counts(plan, _hp(cnt)))
+    return cnt
 
 
 def attn_decode_plan_run(plan, q, scale: float, out, lse_out, workspace, workspace_bytes: int, stream=None) -> None:

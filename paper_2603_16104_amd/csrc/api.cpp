@@ -59,15 +59,15 @@ int env_int(const char *name, int dflt) {
 // opaque objects
 struct hkv_decode_plan {
     hkv_pool *pool = nullptr;
-    int32_t n_req = 0, num_q_heads = 0, group = 0, n_parts = 0;
+    int32_t n_req = 0, num_q_heads = 0, group = 0, n_parts = 0, max_parts = 1;
     std::vector<hkv_node> nodes;            // key of the one-shot cache
     std::vector<int32_t> node_pages, req_leaf;
     std::vector<DecodeItem> items;
-    std::vector<int32_t> node_req_indptr, node_req_idx, row_indptr, part_idx;
-    // one device allocation holding items | pages | node_req_idx | row_indptr | part_idx
+    std::vector<int32_t> node_req_indptr, node_req_idx, part_count;
+    // one device allocation holding items | pages | node_req_idx | part_count
     void *dev = nullptr;
     DecodeItem *d_items = nullptr;
-    int32_t *d_pages = nullptr, *d_node_req_idx = nullptr, *d_row_indptr = nullptr, *d_part_idx = nullptr;
+    int32_t *d_pages = nullptr, *d_node_req_idx = nullptr, *d_part_count = nullptr;
     bool profiling = false, profiled_run = false;
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
 };
@@ -375,38 +375,85 @@ extern "C" int lse_merge(const float *o_parts, const float *lse_parts, const int
     return HKV_OK;
 }
 
+extern "C" int lse_merge_dense(const float *o_parts, const float *lse_parts, const int32_t *part_count,
+                               int32_t rows_per_count, int32_t max_parts, int32_t n_rows, void *out, int32_t out_dtype,
+                               float *lse_out, void *stream) {
+    if (n_rows < 0 || rows_per_count <= 0 || max_parts <= 0)
+        return fail(HKV_EINVAL, "lse_merge_dense: n_rows %d, rows_per_count %d, max_parts %d", n_rows, rows_per_count,
+                    max_parts);
+    if (out_dtype != HKV_BF16 && out_dtype != HKV_FP32) return fail(HKV_ESHAPE, "lse_merge_dense: out_dtype %d", out_dtype);
+    if (n_rows == 0) return HKV_OK;
+    if (!o_parts || !lse_parts || !part_count || !out) return fail(HKV_EINVAL, "lse_merge_dense: null argument");
+    if ((reinterpret_cast<uintptr_t>(o_parts) | reinterpret_cast<uintptr_t>(out)) & 15)
+        return fail(HKV_EINVAL, "lse_merge_dense: o_parts and out must be 16-byte aligned");
+    HKV_HIP(launch_lse_merge_dense(o_parts, lse_parts, part_count, rows_per_count, max_parts, n_rows, out, out_dtype,
+                                   lse_out, static_cast<hipStream_t>(stream)));
+    return HKV_OK;
+}
+
 // ---------------------------------------------------------------------------------------------
 // decode planning
 //
 // A node with T tokens that R requests pass through is cut into work items of at most 64 query
 // rows (R_item * G) and a token chunk each.  Every item yields one partial result per row, so the
 // chunk length trades parallelism (more items) against partial-result traffic (516 B per row and
-// item, written once and read once).  The chunk lengths below keep every item's HBM read at or
-// above 128 KiB for the node sizes of the target workloads while giving the 256 CUs several
-// items each.
+// item, written once and read once).
+//
+// Partials are stored densely: the path above a node is common to every request below it, so the
+// chunks of a node get the same positions k in the partial lists of all those requests, and row
+// (r, h) keeps its partials at (r*Hq + h)*max_parts + k.  The merge then needs no index lists,
+// only the number of partials per request.
 static void plan_items(hkv_decode_plan &pl) {
     const int G = pl.group;
     const int Hkv = pl.pool->d.num_kv_heads;
-    const int max_req_per_item = std::max(1, 64 / G);
-    const int leaf_chunk = env_int("HKV_DECODE_LEAF_CHUNK", 512) / 16 * 16;
-    const int shared_chunk = env_int("HKV_DECODE_SHARED_CHUNK", 512) / 16 * 16;
+    const int n_nodes = (int)pl.nodes.size();
+    const int max_req_per_item = std::max(1, std::min(64, env_int("HKV_DECODE_MAX_ROWS", 64)) / G);
+    // Chunk lengths.  Nodes read by at most 16 rows ("leaf type") stay whole unless the forest has
+    // fewer (node, head) units than workgroups fit on the chip at once; then they are cut, but not
+    // below 256 tokens.  Nodes shared by more rows run one row tile per wavefront over all tokens
+    // of the item, so their chunks are kept near the typical leaf-type item to finish together.
+    const int kResidentGroups = 768;  // 256 CUs x 3 workgroups
+    int64_t leaf_units = 0, leaf_tokens = 0, shared_units = 0;
+    for (int v = 0; v < n_nodes; ++v) {
+        int R = pl.node_req_indptr[v + 1] - pl.node_req_indptr[v];
+        if (pl.nodes[v].n_tokens == 0 || R == 0) continue;
+        if (R * G > 16) {  // counted at the smallest chunk length used for such nodes
+            shared_units += (int64_t)((R + max_req_per_item - 1) / max_req_per_item) * Hkv *
+                            ((pl.nodes[v].n_tokens + 511) / 512);
+        } else {
+            leaf_units += Hkv;
+            leaf_tokens += pl.nodes[v].n_tokens;
+        }
+    }
+    int leaf_split = 1;
+    if (leaf_units > 0 && leaf_units + shared_units < kResidentGroups / 2)
+        leaf_split = (int)((kResidentGroups / 2 + leaf_units - 1) / leaf_units);
+    const int mean_leaf = leaf_units ? (int)(leaf_tokens * Hkv / leaf_units) : 512;
+    int leaf_chunk = std::max(256, (mean_leaf / leaf_split + 15) / 16 * 16);
+    if (leaf_split == 1) leaf_chunk = 1 << 30;  // whole nodes
+    int shared_chunk = std::min(kMaxSharedItemTokens, std::max(512, std::min(mean_leaf, leaf_chunk) / 16 * 16));
+    leaf_chunk = env_int("HKV_DECODE_LEAF_CHUNK", leaf_chunk) / 16 * 16;
+    shared_chunk = std::min(kMaxSharedItemTokens, env_int("HKV_DECODE_SHARED_CHUNK", shared_chunk)) / 16 * 16;
     struct Proto { DecodeItem it; int64_t cost; };
     std::vector<Proto> protos;
-    for (int v = 0; v < (int)pl.nodes.size(); ++v) {
+    std::vector<int32_t> node_chunks(n_nodes, 0), slot_base(n_nodes, 0);
+    for (int v = 0; v < n_nodes; ++v) {
         const hkv_node &nd = pl.nodes[v];
+        if (nd.parent >= 0) slot_base[v] = slot_base[nd.parent] + node_chunks[nd.parent];
         int R = pl.node_req_indptr[v + 1] - pl.node_req_indptr[v];
         if (nd.n_tokens == 0 || R == 0) continue;
         int chunk = std::max(16, R * G > 16 ? shared_chunk : leaf_chunk);
         // equal chunks of whole pages
         int n_chunks = (nd.n_tokens + chunk - 1) / chunk;
         int pages_per_chunk = (nd.n_pages + n_chunks - 1) / n_chunks;
+        node_chunks[v] = (nd.n_pages + pages_per_chunk - 1) / pages_per_chunk;
         for (int r0 = 0; r0 < R; r0 += max_req_per_item) {
             int nr = std::min(max_req_per_item, R - r0);
-            for (int pg = 0; pg < nd.n_pages; pg += pages_per_chunk) {
+            for (int pg = 0, ci = 0; pg < nd.n_pages; pg += pages_per_chunk, ++ci) {
                 int tb = pg * 16;
                 int nt = std::min(pages_per_chunk * 16, nd.n_tokens - tb);
                 for (int h = 0; h < Hkv; ++h) {
-                    DecodeItem it{nd.page_begin + pg, nt, h, pl.node_req_indptr[v] + r0, nr, 0, tb, v};
+                    DecodeItem it{nd.page_begin + pg, nt, h, pl.node_req_indptr[v] + r0, nr, slot_base[v] + ci, tb, v};
                     int rows = nr * G;
                     protos.push_back({it, (int64_t)nt * std::max(16, (rows + 15) / 16 * 16)});
                 }
@@ -414,56 +461,37 @@ static void plan_items(hkv_decode_plan &pl) {
         }
     }
     std::stable_sort(protos.begin(), protos.end(), [](const Proto &a, const Proto &b) { return a.cost > b.cost; });
-    int32_t part = 0;
     pl.items.clear();
-    for (auto &p : protos) {
-        p.it.part_base = part;
-        part += p.it.n_req * G;
-        pl.items.push_back(p.it);
+    for (auto &p : protos) pl.items.push_back(p.it);
+    pl.part_count.assign(pl.n_req, 0);
+    pl.max_parts = 1;
+    for (int r = 0; r < pl.n_req; ++r) {
+        int leaf = pl.req_leaf[r];
+        pl.part_count[r] = slot_base[leaf] + node_chunks[leaf];
+        pl.max_parts = std::max(pl.max_parts, pl.part_count[r]);
     }
-    pl.n_parts = part;
-    // merge CSR: output row (request, q head) -> its partials
-    const int Hq = pl.num_q_heads;
-    std::vector<int32_t> cnt((size_t)pl.n_req * Hq + 1, 0);
-    for (const DecodeItem &it : pl.items)
-        for (int j = 0; j < it.n_req; ++j) {
-            int r = pl.node_req_idx[it.req_off + j];
-            for (int g = 0; g < G; ++g) ++cnt[(size_t)r * Hq + it.kv_head * G + g + 1];
-        }
-    pl.row_indptr.assign(cnt.size(), 0);
-    std::partial_sum(cnt.begin(), cnt.end(), pl.row_indptr.begin());
-    pl.part_idx.assign((size_t)pl.row_indptr.back(), 0);
-    std::vector<int32_t> fill(pl.row_indptr.begin(), pl.row_indptr.end() - 1);
-    for (const DecodeItem &it : pl.items)
-        for (int j = 0; j < it.n_req; ++j) {
-            int r = pl.node_req_idx[it.req_off + j];
-            for (int g = 0; g < G; ++g)
-                pl.part_idx[fill[(size_t)r * Hq + it.kv_head * G + g]++] = it.part_base + j * G + g;
-        }
+    pl.n_parts = pl.n_req * pl.num_q_heads * pl.max_parts;
 }
 
 static int upload_decode_plan(hkv_decode_plan &pl) {
     size_t off_items = 0;
     size_t off_pages = align_up(off_items + sizeof(DecodeItem) * pl.items.size(), 256);
     size_t off_nri = align_up(off_pages + sizeof(int32_t) * pl.node_pages.size(), 256);
-    size_t off_indptr = align_up(off_nri + sizeof(int32_t) * pl.node_req_idx.size(), 256);
-    size_t off_pidx = align_up(off_indptr + sizeof(int32_t) * pl.row_indptr.size(), 256);
-    size_t total = align_up(off_pidx + sizeof(int32_t) * pl.part_idx.size(), 256) + 256;
+    size_t off_cnt = align_up(off_nri + sizeof(int32_t) * pl.node_req_idx.size(), 256);
+    size_t total = align_up(off_cnt + sizeof(int32_t) * pl.part_count.size(), 256) + 256;
     HKV_HIP(hipMalloc(&pl.dev, total));
     char *base = static_cast<char *>(pl.dev);
     pl.d_items = reinterpret_cast<DecodeItem *>(base + off_items);
     pl.d_pages = reinterpret_cast<int32_t *>(base + off_pages);
     pl.d_node_req_idx = reinterpret_cast<int32_t *>(base + off_nri);
-    pl.d_row_indptr = reinterpret_cast<int32_t *>(base + off_indptr);
-    pl.d_part_idx = reinterpret_cast<int32_t *>(base + off_pidx);
+    pl.d_part_count = reinterpret_cast<int32_t *>(base + off_cnt);
     auto up = [&](void *dst, const void *src, size_t n) -> hipError_t {
         return n ? hipMemcpy(dst, src, n, hipMemcpyHostToDevice) : hipSuccess;
     };
     HKV_HIP(up(pl.d_items, pl.items.data(), sizeof(DecodeItem) * pl.items.size()));
     HKV_HIP(up(pl.d_pages, pl.node_pages.data(), sizeof(int32_t) * pl.node_pages.size()));
     HKV_HIP(up(pl.d_node_req_idx, pl.node_req_idx.data(), sizeof(int32_t) * pl.node_req_idx.size()));
-    HKV_HIP(up(pl.d_row_indptr, pl.row_indptr.data(), sizeof(int32_t) * pl.row_indptr.size()));
-    HKV_HIP(up(pl.d_part_idx, pl.part_idx.data(), sizeof(int32_t) * pl.part_idx.size()));
+    HKV_HIP(up(pl.d_part_count, pl.part_count.data(), sizeof(int32_t) * pl.part_count.size()));
     return HKV_OK;
 }
 
@@ -536,14 +564,12 @@ extern "C" int hkv_decode_plan_items(const hkv_decode_plan *plan, int32_t *items
     if (!plan->items.empty()) memcpy(items_out, plan->items.data(), sizeof(DecodeItem) * plan->items.size());
     return HKV_OK;
 }
-extern "C" int32_t hkv_decode_plan_num_merge_entries(const hkv_decode_plan *plan) {
-    return plan ? (int32_t)plan->part_idx.size() : fail(HKV_EINVAL, "null plan");
+extern "C" int32_t hkv_decode_plan_max_parts(const hkv_decode_plan *plan) {
+    return plan ? plan->max_parts : fail(HKV_EINVAL, "null plan");
 }
-extern "C" int hkv_decode_plan_merge_csr(const hkv_decode_plan *plan, int32_t *row_indptr, int32_t *part_idx) {
-    if (!plan) return fail(HKV_EINVAL, "hkv_decode_plan_merge_csr: null plan");
-    if (row_indptr) memcpy(row_indptr, plan->row_indptr.data(), sizeof(int32_t) * plan->row_indptr.size());
-    if (part_idx && !plan->part_idx.empty())
-        memcpy(part_idx, plan->part_idx.data(), sizeof(int32_t) * plan->part_idx.size());
+extern "C" int hkv_decode_plan_part_counts(const hkv_decode_plan *plan, int32_t *part_count) {
+    if (!plan || (plan->n_req > 0 && !part_count)) return fail(HKV_EINVAL, "hkv_decode_plan_part_counts: null argument");
+    if (plan->n_req) memcpy(part_count, plan->part_count.data(), sizeof(int32_t) * plan->n_req);
     return HKV_OK;
 }
 
@@ -568,12 +594,12 @@ extern "C" int attn_decode_plan_run(hkv_decode_plan *plan, const void *q, float 
     if (prof) HKV_HIP(hipEventRecord(plan->ev[0], s));
     if (!plan->items.empty()) {
         DecodeLaunch a{view_of(plan->pool), q, plan->d_items, plan->d_pages, plan->d_node_req_idx, o_parts, lse_parts,
-                       (int32_t)plan->items.size(), plan->num_q_heads, scale};
+                       (int32_t)plan->items.size(), plan->num_q_heads, plan->max_parts, scale, nullptr};
         HKV_HIP(launch_decode(a, s));
     }
     if (prof) HKV_HIP(hipEventRecord(plan->ev[1], s));
-    HKV_HIP(launch_lse_merge(o_parts, lse_parts, plan->d_row_indptr, plan->d_part_idx, plan->n_req * plan->num_q_heads,
-                             out, HKV_BF16, lse_out, s));
+    HKV_HIP(launch_lse_merge_dense(o_parts, lse_parts, plan->d_part_count, plan->num_q_heads, plan->max_parts,
+                                   plan->n_req * plan->num_q_heads, out, HKV_BF16, lse_out, s));
     if (prof) {
         HKV_HIP(hipEventRecord(plan->ev[2], s));
         plan->profiled_run = true;

@@ -22,6 +22,19 @@
 
 #include "hkv_device.h"
 
+// Development aid: with -DHKV_TRACE every wavefront records wall-clock stamps at a few points.
+#ifdef HKV_TRACE
+#define HKV_STAMP(slot)                                                                              \
+    do {                                                                                             \
+        if (a.trace && (threadIdx.x & 63) == 0)                                                      \
+            a.trace[((size_t)blockIdx.x * kWaves + (threadIdx.x >> 6)) * 8 + (slot)] = wall_clock64(); \
+    } while (0)
+#else
+#define HKV_STAMP(slot) \
+    do {                \
+    } while (0)
+#endif
+
 namespace hkv {
 
 namespace {
@@ -29,6 +42,17 @@ namespace {
 constexpr int kWaves = 4;
 constexpr int kThreads = kWaves * 64;
 constexpr int kORow = kHeadDim + 4;  // padded LDS row: 16 rows x 132 floats do not collide in banks
+constexpr int kStageBytes = 16 * 1024;  // one step's 16 operand fragments x 64 lanes x 16 bytes
+constexpr int kStages = 3;
+constexpr int kIdRegs = 2;  // LDS-staged items hold their page ids in registers: at most 64*kIdRegs pages
+static_assert(kMaxSharedItemTokens <= 64 * kIdRegs * kPage, "planner limit exceeds what the kernel can index");
+
+#define HKV_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
+#define HKV_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
+
+// s_waitcnt immediate that waits for vmcnt <= n only (gfx9 encoding: vmcnt in bits 3:0 and 15:14,
+// expcnt 6:4 and lgkmcnt 11:8 left at their maxima)
+constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
 template <int DT>
 struct Traits;
@@ -78,31 +102,35 @@ __device__ __forceinline__ void load_step_pages(StepPages<DT> &sp, const DecodeL
     }
 }
 
-template <int N>
-__device__ __forceinline__ int pick(const int (&v)[N], int sel) {
-    int r = v[0];
-#pragma unroll
-    for (int i = 1; i < N; ++i) r = (sel == i) ? v[i] : r;
-    return r;
+// Per-lane choice among a step's wavefront-uniform values (scalars in, one v_cndmask tree out).
+template <typename T>
+__device__ __forceinline__ T pick(const T (&v)[2], int sel) {
+    const T v0 = v[0], v1 = v[1];
+    return (sel & 1) ? v1 : v0;
 }
-template <int N>
-__device__ __forceinline__ float pickf(const float (&v)[N], int sel) {
-    float r = v[0];
-#pragma unroll
-    for (int i = 1; i < N; ++i) r = (sel == i) ? v[i] : r;
-    return r;
+template <typename T>
+__device__ __forceinline__ T pick(const T (&v)[4], int sel) {
+    const T v0 = v[0], v1 = v[1], v2 = v[2], v3 = v[3];
+    const T lo = (sel & 1) ? v1 : v0, hi = (sel & 1) ? v3 : v2;
+    return (sel & 2) ? hi : lo;
 }
 
 template <int DT>
-__global__ __launch_bounds__(kThreads, 2) void decode_node_kernel(DecodeLaunch a) {
-    __shared__ float sO[kWaves][16][kORow];
-    __shared__ float sM[kWaves][16];
-    __shared__ float sL[kWaves][16];
+__global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(DecodeLaunch a) {
+    // LDS: a ring of kStages K/V stages for items shared by many query rows; items with at most 16
+    // rows use the same bytes for the cross-wavefront combine instead.
+    __shared__ __attribute__((aligned(16))) char smem[kStages * kStageBytes];
+    float(*sO)[16][kORow] = reinterpret_cast<float(*)[16][kORow]>(smem);
+    float(*sM)[16] = reinterpret_cast<float(*)[16]>(smem + sizeof(float) * kWaves * 16 * kORow);
+    float(*sL)[16] = sM + kWaves;
+    int *sPart = reinterpret_cast<int *>(sL + kWaves);  // partial index of each of the 16 rows
+    static_assert(sizeof(float) * (kWaves * 16 * kORow + 2 * kWaves * 16 + 16) <= kStages * kStageBytes, "LDS overlay");
 
     constexpr int TB = Traits<DT>::kTokBlock;
     constexpr int NS = TB / 4;  // scores per lane (16 query rows x TB tokens over 64 lanes)
     constexpr int BB = Traits<DT>::kBlockBytes;
 
+    HKV_STAMP(0);
     const DecodeItem it = a.items[blockIdx.x];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -110,31 +138,37 @@ __global__ __launch_bounds__(kThreads, 2) void decode_node_kernel(DecodeLaunch a
     const int Hkv = a.pool.num_kv_heads;
     const int G = a.num_q_heads / Hkv;
     const int rows = it.n_req * G;
-    const int n_rt = rows <= 16 ? 1 : rows <= 32 ? 2 : 4;  // 16-row tiles, one or more wavefronts each
-    const int n_ts = kWaves / n_rt;                         // wavefronts sharing a row tile split the tokens
+    // Up to 16 rows: the four wavefronts split the tokens and read K/V straight into registers.
+    // More rows: each wavefront owns a 16-row tile, all tokens, and K/V are staged once in LDS.
+    const bool shared = rows > 16;
+    const int n_rt = shared ? kWaves : 1;
+    const int n_ts = kWaves / n_rt;
     const int rt = wave % n_rt, ts = wave / n_rt;
     const float c = a.scale * kLog2e;
 
-    // Q^T operands of this wavefront's 16 rows; rows past the item's end are zero
-    bf16x8 qf[4];
-    {
-        const int row = rt * 16 + m;
-        u32x4 z = {0u, 0u, 0u, 0u};
+    // Q^T operands of this wavefront's 16 rows; rows past the item's end are zero.  The loads are
+    // unconditional (row clamped) so that they can stay in flight next to the first K/V requests.
+    const int row = rt * 16 + m;
+    const int rowc = min(row, rows - 1);
+    auto load_req = [&]() {
+        int req = a.node_req_idx[it.req_off];  // wavefront-uniform: scalar load
+        if (it.n_req > 1) req = a.node_req_idx[it.req_off + rowc / G];
+        return req;
+    };
+    auto load_q = [&](bf16x8 (&qf)[4], int req) {
+        const int head = it.kv_head * G + rowc % G;
+        const char *qp = static_cast<const char *>(a.q) + ((size_t)req * a.num_q_heads + head) * (kHeadDim * 2);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) qf[i] = as_bf16x8(z);
-        if (row < rows) {
-            const int req = a.node_req_idx[it.req_off + row / G];
-            const int head = it.kv_head * G + row % G;
-            const char *qp = static_cast<const char *>(a.q) + ((size_t)req * a.num_q_heads + head) * (kHeadDim * 2);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                // bf16 pool: k-step i covers dims 32*i + 8*g ..; fp8 pool: k-step (i/2, i%2) covers
-                // dims 64*(i/2) + 16*g + 8*(i%2) ..
-                const int d0 = (DT == 0) ? 32 * i + 8 * g : 64 * (i >> 1) + 16 * g + 8 * (i & 1);
-                qf[i] = as_bf16x8(ld16(qp + d0 * 2));
-            }
+        for (int i = 0; i < 4; ++i) {
+            // bf16 pool: k-step i covers dims 32*i + 8*g ..; fp8 pool: k-step (i/2, i%2) covers
+            // dims 64*(i/2) + 16*g + 8*(i%2) ..
+            const int d0 = (DT == 0) ? 32 * i + 8 * g : 64 * (i >> 1) + 16 * g + 8 * (i & 1);
+            u32x4 w = ld16(qp + d0 * 2);
+            if (row >= rows) w = u32x4{0u, 0u, 0u, 0u};
+            qf[i] = as_bf16x8(w);
         }
-    }
+    };
+    bf16x8 qf[4];
 
     // Loop-invariant byte offsets of this lane inside a (page, head) block and the page of the step
     // it reads.  bf16: score tile a holds tokens 8*(m/4) + m%4 of the 32-token step, tile b those + 4;
@@ -199,7 +233,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_node_kernel(DecodeLaunch a
                 s[4 + i] = sb[i];
             }
         } else {
-            const float ksc = pickf(cur.ksc, g);
+            const float ksc = pick(cur.ksc, g);
 #pragma unroll
             for (int t4 = 0; t4 < 4; ++t4) {
                 f32x4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -213,7 +247,11 @@ __global__ __launch_bounds__(kThreads, 2) void decode_node_kernel(DecodeLaunch a
                 for (int i = 0; i < 4; ++i) s[t4 * 4 + i] = acc[i] * ksc;
             }
         }
-        if constexpr (MORE) issue_k(nxt);  // the K registers are free again
+        if constexpr (MORE) {  // the K registers are free again; keep the request exactly here
+            __builtin_amdgcn_sched_barrier(0);
+            issue_k(nxt);
+            __builtin_amdgcn_sched_barrier(0);
+        }
 
         // ---- online softmax; lane-local score j belongs to token tok0 + j of the item
         const int tok0 = b * TB + g * NS;
@@ -246,7 +284,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_node_kernel(DecodeLaunch a
         }
 
         // ---- O^T += V^T P^T
-        const float vs = (DT == 0) ? 1.0f : pickf(cur.vsc, g);
+        const float vs = (DT == 0) ? 1.0f : pick(cur.vsc, g);
 #pragma unroll
         for (int ks = 0; ks < NS / 8; ++ks) {
             u32x4 pw;
@@ -264,23 +302,142 @@ __global__ __launch_bounds__(kThreads, 2) void decode_node_kernel(DecodeLaunch a
                 o[dt] = mfma16(va, pb, o[dt]);
             }
         }
-        if constexpr (MORE) issue_v(nxt);  // the V registers are free again
+        if constexpr (MORE) {  // the V registers are free again
+            __builtin_amdgcn_sched_barrier(0);
+            issue_v(nxt);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     };
 
+    if (shared) {
+        // ---- K/V staged in LDS, fetched once for all row tiles of the item (LDS-direct loads: the
+        // data in flight occupies no registers, so two further steps are kept in flight).  A stage
+        // holds the 16 operand fragments of a step in lane order; wavefront w fetches fragments
+        // w, 4+w (K) and 8+w, 12+w (V) with exactly the addresses the register path uses.
+        const bool active = rt * 16 < rows;
+        // page ids (and fp8 scales) of the whole item, kIdRegs pages per lane (the planner keeps such
+        // items at 64*kIdRegs pages or fewer); a step's entries are then read across lanes, so no
+        // global load sits between the LDS-direct loads
+        int id_lane[kIdRegs];
+        float ksc_lane[kIdRegs], vsc_lane[kIdRegs];
+#pragma unroll
+        for (int r = 0; r < kIdRegs; ++r) {
+            id_lane[r] = a.pages[it.page_off + min(lane + 64 * r, last_page)];
+            if constexpr (DT == 1) {
+                ksc_lane[r] = a.pool.k_scale[(size_t)id_lane[r] * Hkv + it.kv_head];
+                vsc_lane[r] = a.pool.v_scale[(size_t)id_lane[r] * Hkv + it.kv_head];
+            }
+        }
+        auto step_pages = [&](StepPages<DT> &sp, int blk) {
+#pragma unroll
+            for (int i = 0; i < StepPages<DT>::N; ++i) {
+                const int pg = min(blk * StepPages<DT>::N + i, last_page);
+                const int hi = pg >> 6, lo = pg & 63;  // wavefront-uniform
+                int idv = id_lane[0];
+                float kv = ksc_lane[0], vv = vsc_lane[0];
+#pragma unroll
+                for (int r = 1; r < kIdRegs; ++r)
+                    if (hi == r) {
+                        idv = id_lane[r];
+                        kv = ksc_lane[r];
+                        vv = vsc_lane[r];
+                    }
+                sp.id[i] = __builtin_amdgcn_readlane(idv, lo);
+                if constexpr (DT == 1) {
+                    sp.ksc[i] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, kv), lo));
+                    sp.vsc[i] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, vv), lo));
+                }
+            }
+        };
+        auto issue_stage = [&](int blk) {
+            StepPages<DT> sp;
+            step_pages(sp, blk);
+            char *stage = smem + (blk % kStages) * kStageBytes;
+            const char *pk = kb + (size_t)pick(sp.id, k_sel) * page_stride;
+            const char *pv = vb + (size_t)pick(sp.id, v_sel) * page_stride;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int f = 4 * j + wave;
+                const int koff = (DT == 0) ? (f & 3) * 1024 + (f >> 2) * 256 : (f & 1) * 1024 + (f >> 1) * 256;
+                __builtin_amdgcn_global_load_lds(HKV_GLOBAL_PTR(pk + koff), HKV_LDS_PTR(stage + f * 1024), 16, 0, 0);
+            }
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int dt = 4 * j + wave;
+                __builtin_amdgcn_global_load_lds(HKV_GLOBAL_PTR(pv + dt * ((DT == 0) ? 512 : 256)),
+                                                 HKV_LDS_PTR(stage + (8 + dt) * 1024), 16, 0, 0);
+            }
+        };
+        const int req = load_req();
+        load_q(qf, req);
+        issue_stage(0);
+        if (n_blk > 1) issue_stage(1);
+        HKV_STAMP(1);
+        for (int b = 0; b < n_blk; ++b) {
+            StepPages<DT> cur;
+            step_pages(cur, b);  // fp8 scales of this step
+            // this wavefront's share of step b has landed once at most the next step's 4 loads are pending
+            __builtin_amdgcn_sched_barrier(0);
+            if (b + 1 < n_blk)
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(4));
+            else
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+            __builtin_amdgcn_s_barrier();  // everyone's share landed; everyone is done with step b-1
+            __builtin_amdgcn_sched_barrier(0);
+            if (b + 2 < n_blk) issue_stage(b + 2);  // overwrites the stage of step b-1
+            __builtin_amdgcn_sched_barrier(0);
+            if (active) {
+                const char *stage = smem + (b % kStages) * kStageBytes + lane * 16;
+#pragma unroll
+                for (int f = 0; f < 8; ++f) {
+                    kf[f] = *reinterpret_cast<const u32x4 *>(stage + f * 1024);
+                    vf[f] = *reinterpret_cast<const u32x4 *>(stage + (8 + f) * 1024);
+                }
+                step(std::false_type{}, b, cur, cur);
+            }
+            if (b == 0) HKV_STAMP(2);
+        }
+        HKV_STAMP(4);
+        if (active) {
+            const float l_row = rows_sum(l_run);
+            if (row < rows) {
+                const float inv = 1.0f / l_row;
+                const size_t part = (size_t)(req * a.num_q_heads + it.kv_head * G + row % G) * a.max_parts + it.part_slot;
+                float *op = a.o_parts + part * kHeadDim + 4 * g;
+#pragma unroll
+                for (int dt = 0; dt < 8; ++dt) *reinterpret_cast<f32x4 *>(op + 16 * dt) = o[dt] * inv;
+                if (g == 0) a.lse_parts[part] = (m_run * c + fast_log2(l_row)) * kLn2;
+            }
+        }
+        HKV_STAMP(6);
+        return;
+    }
+
     int b = ts;
+    int req = 0;
     if (b < n_blk) {
         StepPages<DT> cur, nxt;
         load_step_pages<DT>(cur, a, it, b, last_page);
+        req = load_req();  // requested before K/V so that waiting for it does not wait for them
         issue_k(cur);
         issue_v(cur);
+        load_q(qf, req);
         load_step_pages<DT>(nxt, a, it, b + n_ts, last_page);  // clamped: always in bounds
+        HKV_STAMP(1);
+        bool first = true;
         while (b + n_ts < n_blk) {
             step(std::true_type{}, b, cur, nxt);
+            if (first) {
+                HKV_STAMP(2);
+                first = false;
+            }
             b += n_ts;
             cur = nxt;
             load_step_pages<DT>(nxt, a, it, b + n_ts, last_page);
         }
+        HKV_STAMP(3);
         step(std::false_type{}, b, cur, nxt);
+        HKV_STAMP(4);
     }
 
     // combine the wavefronts that split the tokens of a row tile, normalise, write the partials
@@ -290,8 +447,11 @@ __global__ __launch_bounds__(kThreads, 2) void decode_node_kernel(DecodeLaunch a
     if (g == 0) {
         sM[wave][m] = m_run;
         sL[wave][m] = l_row;
+        // wavefront 0 always has a step (the item holds at least one token), so its req is loaded
+        if (wave == 0 && row < rows) sPart[m] = (req * a.num_q_heads + it.kv_head * G + row % G) * a.max_parts + it.part_slot;
     }
     __syncthreads();
+    HKV_STAMP(5);
     for (int idx = tid; idx < rows * kHeadDim; idx += kThreads) {
         const int row = idx >> 7, d = idx & 127;
         const int r_t = row >> 4, r_c = row & 15;
@@ -304,9 +464,16 @@ __global__ __launch_bounds__(kThreads, 2) void decode_node_kernel(DecodeLaunch a
             L += sL[w][r_c] * wgt;
             acc += sO[w][r_c][d] * wgt;
         }
-        a.o_parts[(size_t)(it.part_base + row) * kHeadDim + d] = acc / L;
-        if (d == 0) a.lse_parts[it.part_base + row] = (M * c + fast_log2(L)) * kLn2;
+        const size_t part = (size_t)sPart[row];
+        a.o_parts[part * kHeadDim + d] = acc / L;
+        if (d == 0) a.lse_parts[part] = (M * c + fast_log2(L)) * kLn2;
     }
+    HKV_STAMP(6);
+#ifdef HKV_TRACE
+    if (a.trace && (threadIdx.x & 63) == 0)
+        a.trace[((size_t)blockIdx.x * kWaves + (threadIdx.x >> 6)) * 8 + 7] =
+            ((unsigned long long)__builtin_amdgcn_s_getreg((31 << 11) | 20) << 32) | __builtin_amdgcn_s_getreg((31 << 11) | 4);
+#endif
 }
 
 }  // namespace

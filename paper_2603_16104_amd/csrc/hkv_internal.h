@@ -20,7 +20,8 @@ struct DecodeItem {
     int32_t kv_head;
     int32_t req_off;    // index of the item's first request in the node->request CSR values
     int32_t n_req;
-    int32_t part_base;  // partial-result slot of row 0; row (j, g) -> part_base + j*G + g
+    int32_t part_slot;  // position of this item among the partials of every row below the node:
+                        // row (request r, q head h) writes partial (r*Hq + h)*max_parts + part_slot
     int32_t tok_begin;  // first token within the node (multiple of 16)
     int32_t node;
 };
@@ -52,11 +53,13 @@ struct DecodeLaunch {
     const DecodeItem *items;     // device
     const int32_t *pages;        // device: the plan's page list
     const int32_t *node_req_idx; // device: node->request CSR values
-    float *o_parts;              // [n_parts][128]
-    float *lse_parts;            // [n_parts]
+    float *o_parts;              // [n_req*Hq*max_parts][128]
+    float *lse_parts;            // [n_req*Hq*max_parts]
     int32_t n_items;
     int32_t num_q_heads;
+    int32_t max_parts;
     float scale;
+    unsigned long long *trace;   // development builds only (HKV_TRACE): 8 timestamps per wavefront, else null
 };
 
 struct PrefillLaunch {
@@ -86,6 +89,9 @@ struct PoolWriteLaunch {
     const void *v_src;
 };
 
+// Largest token count of a decode item that is shared by more than 16 query rows.
+constexpr int kMaxSharedItemTokens = 2048;
+
 // Query tokens per prefill workgroup for a given group size G (rows per workgroup / G).
 int prefill_tile_tokens(int group);
 
@@ -95,5 +101,8 @@ hipError_t launch_prefill(const PrefillLaunch &a, hipStream_t s);
 hipError_t launch_lse_merge(const float *o_parts, const float *lse_parts, const int32_t *row_indptr,
                             const int32_t *part_idx, int32_t n_rows, void *out, int32_t out_dtype,
                             float *lse_out, hipStream_t s);
+hipError_t launch_lse_merge_dense(const float *o_parts, const float *lse_parts, const int32_t *part_count,
+                                  int32_t rows_per_count, int32_t max_parts, int32_t n_rows, void *out,
+                                  int32_t out_dtype, float *lse_out, hipStream_t s);
 
 }  // namespace hkv

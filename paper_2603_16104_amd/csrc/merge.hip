@@ -47,7 +47,84 @@ __global__ __launch_bounds__(64 * kRowsPerBlock) void lse_merge_kernel(const flo
     if (lse_out && lane == 0) lse_out[row] = (M == -INFINITY) ? -INFINITY : M + fast_log2(z) * kLn2;
 }
 
+// Dense variant: row i owns partials i*max_parts + k, k < part_count[i / rows_per_count].  Half a
+// wavefront per row (32 lanes x 4 dims); the first kUnroll partials and their lse values are
+// requested together, so a row costs one memory round trip after its count.
+constexpr int kDenseRowsPerBlock = 8;
+constexpr int kUnroll = 8;
+
+template <int OUT_DT>
+__global__ __launch_bounds__(32 * kDenseRowsPerBlock) void lse_merge_dense_kernel(
+    const float *__restrict__ o_parts, const float *__restrict__ lse_parts, const int32_t *__restrict__ part_count,
+    int32_t rows_per_count, int32_t max_parts, int32_t n_rows, void *__restrict__ out, float *__restrict__ lse_out) {
+    const int row = blockIdx.x * kDenseRowsPerBlock + (threadIdx.x >> 5);
+    const int l = threadIdx.x & 31;
+    if (row >= n_rows) return;
+    const int cnt = min(part_count[row / rows_per_count], max_parts);
+    const size_t base = (size_t)row * max_parts;
+    const float *lp = lse_parts + base;
+    const f32x4 *op = reinterpret_cast<const f32x4 *>(o_parts + base * kHeadDim) + l;
+    float ls[kUnroll];
+    f32x4 ov[kUnroll];
+#pragma unroll
+    for (int k = 0; k < kUnroll; ++k) {
+        ls[k] = -INFINITY;
+        ov[k] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (k < cnt) {
+            ls[k] = lp[k];
+            ov[k] = op[(size_t)k * (kHeadDim / 4)];
+        }
+    }
+    float M = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < kUnroll; ++k) M = fmaxf(M, ls[k]);
+    for (int k = kUnroll; k < cnt; ++k) M = fmaxf(M, lp[k]);
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    float z = 0.f;
+    if (M != -INFINITY) {
+#pragma unroll
+        for (int k = 0; k < kUnroll; ++k) {
+            if (ls[k] != -INFINITY) {  // an empty partial may hold anything in o
+                const float w = fast_exp2((ls[k] - M) * kLog2e);
+                z += w;
+                acc += ov[k] * w;
+            }
+        }
+        for (int k = kUnroll; k < cnt; ++k) {
+            const float lk = lp[k];
+            if (lk == -INFINITY) continue;
+            const float w = fast_exp2((lk - M) * kLog2e);
+            z += w;
+            acc += op[(size_t)k * (kHeadDim / 4)] * w;
+        }
+        acc *= 1.0f / z;
+    }
+    if (OUT_DT == 0) {
+        u32x2 w;
+        w[0] = pack_bf16(acc[0], acc[1]);
+        w[1] = pack_bf16(acc[2], acc[3]);
+        reinterpret_cast<u32x2 *>(out)[(size_t)row * (kHeadDim / 4) + l] = w;
+    } else {
+        reinterpret_cast<f32x4 *>(out)[(size_t)row * (kHeadDim / 4) + l] = acc;
+    }
+    if (lse_out && l == 0) lse_out[row] = (M == -INFINITY) ? -INFINITY : M + fast_log2(z) * kLn2;
+}
+
 }  // namespace
+
+hipError_t launch_lse_merge_dense(const float *o_parts, const float *lse_parts, const int32_t *part_count,
+                                  int32_t rows_per_count, int32_t max_parts, int32_t n_rows, void *out,
+                                  int32_t out_dtype, float *lse_out, hipStream_t s) {
+    if (n_rows <= 0) return hipSuccess;
+    dim3 grid((n_rows + kDenseRowsPerBlock - 1) / kDenseRowsPerBlock), block(32 * kDenseRowsPerBlock);
+    if (out_dtype == 0)
+        hipLaunchKernelGGL(lse_merge_dense_kernel<0>, grid, block, 0, s, o_parts, lse_parts, part_count, rows_per_count,
+                           max_parts, n_rows, out, lse_out);
+    else
+        hipLaunchKernelGGL(lse_merge_dense_kernel<2>, grid, block, 0, s, o_parts, lse_parts, part_count, rows_per_count,
+                           max_parts, n_rows, out, lse_out);
+    return hipGetLastError();
+}
 
 hipError_t launch_lse_merge(const float *o_parts, const float *lse_parts, const int32_t *row_indptr,
                             const int32_t *part_idx, int32_t n_rows, void *out, int32_t out_dtype, float *lse_out,
