@@ -150,6 +150,45 @@ def test_lse_merge_kernel(gpu, oracle):
         assert (got[3] == 0).all() and (got[7] == 0).all()
 
 
+def test_lse_merge_dense_kernel(gpu, oracle):
+    import torch
+    from paper_2603_16104_amd import binding as hkv
+    rng = np.random.default_rng(8)
+    rows_per_count, n_groups, max_parts = 4, 37, 11        # more partials than the kernel's unrolled prefix
+    n_rows = rows_per_count * n_groups - 2                 # last group is ragged
+    counts = rng.integers(0, max_parts + 1, size=n_groups).astype(np.int32)
+    counts[0], counts[1] = 0, max_parts
+    n_parts = n_rows * max_parts
+    o = rng.standard_normal((n_parts, 128)).astype(np.float32)
+    lse = (rng.standard_normal(n_parts) * 4).astype(np.float32)
+    lse[rng.random(n_parts) < 0.15] = -np.inf
+    o[np.isneginf(lse)] = np.nan
+    indptr = np.zeros(n_rows + 1, dtype=np.int32)
+    pidx = []
+    for i in range(n_rows):
+        c = counts[i // rows_per_count]
+        pidx += list(range(i * max_parts, i * max_parts + c))
+        indptr[i + 1] = len(pidx)
+    # slots past a row's count hold garbage that must never be read into the result
+    for i in range(n_rows):
+        c = counts[i // rows_per_count]
+        o[i * max_parts + c: (i + 1) * max_parts] = np.nan
+        lse[i * max_parts + c: (i + 1) * max_parts] = np.nan
+    exp_o, exp_l = oracle.lse_merge(np.nan_to_num(o.astype(np.float64)), np.nan_to_num(lse.astype(np.float64), neginf=-np.inf),
+                                    indptr, np.array(pidx, dtype=np.int32))
+    d = lambda a: torch.from_numpy(a).cuda()
+    do, dl, dc = d(o), d(lse), d(counts)
+    for out_dtype in (hkv.FP32, hkv.BF16):
+        out = torch.empty((n_rows, 128), dtype=torch.float32 if out_dtype == hkv.FP32 else torch.int16, device="cuda")
+        lout = torch.empty(n_rows, dtype=torch.float32, device="cuda")
+        hkv.lse_merge_dense(do, dl, dc, rows_per_count, max_parts, n_rows, out, out_dtype, lout)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().astype(np.float64) if out_dtype == hkv.FP32 else gpu.bf16_tensor_to_f64(out)
+        assert np.isfinite(got).all()
+        assert np.abs(got - exp_o).max() <= (1e-5 if out_dtype == hkv.FP32 else 2e-2)
+        check_lse(lout.cpu().numpy(), exp_l, "lse_merge_dense")
+
+
 # ------------------------------------------------------------------------------ decode
 
 def run_decode(gpu, oracle, w, one_shot=False):

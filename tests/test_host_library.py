@@ -1,0 +1,334 @@
+"""CPU-only tests of the C-ABI library: it loads, exports what the header declares, and its host
+logic (pool bookkeeping, forest flattening, token usage, work planning, argument validation) is
+right.  Integer outputs are compared bit-exactly with the oracle.  No kernel is launched."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2603_16104_amd import binding as hkv
+from paper_2603_16104_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE_K, FAKE_V = 0x10000, 0x20000     # never dereferenced on the host
+
+
+@pytest.fixture(scope="module", autouse=True)
+def built():
+    if not os.path.exists(hkv.LIB_PATH):
+        from paper_2603_16104_amd import build
+        build.build(force=True)
+    hkv.lib()
+
+
+def fake_pool(num_pages=64, num_kv_heads=2, dtype=hkv.BF16, **kw):
+    scales = dict(k_scale=0x30000, v_scale=0x40000) if dtype == hkv.FP8_E4M3 else {}
+    return hkv.kv_pool_create(num_pages, num_kv_heads, dtype, FAKE_K, FAKE_V, **scales, **kw)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "heliumkv.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b([a-z_0-9]+)\s*\(", header)) - {"defined", "sizeof"}
+    declared = {d for d in declared if d.startswith(("kv_pool", "hkv_", "prefix_tree", "attn_", "lse_merge"))}
+    assert len(declared) >= 30
+    L = hkv.lib()
+    for name in sorted(declared):
+        assert hasattr(L, name), f"{name} is declared in heliumkv.h but not exported"
+    assert declared == set(hkv.EXPORTS), declared ^ set(hkv.EXPORTS)
+
+
+# ------------------------------------------------------------------------------ pool bookkeeping
+
+def test_pool_create_validation():
+    with pytest.raises(hkv.HkvError) as e:
+        hkv.kv_pool_create(8, 2, hkv.BF16, FAKE_K, FAKE_V, page_size=32)
+    assert e.value.code == hkv.ESHAPE
+    with pytest.raises(hkv.HkvError) as e:
+        hkv.kv_pool_create(8, 2, hkv.BF16, FAKE_K, FAKE_V, head_dim=64)
+    assert e.value.code == hkv.ESHAPE
+    with pytest.raises(hkv.HkvError) as e:
+        hkv.kv_pool_create(8, 2, hkv.FP8_E4M3, FAKE_K, FAKE_V)          # scales missing
+    assert e.value.code == hkv.ESHAPE
+    with pytest.raises(hkv.HkvError) as e:
+        hkv.kv_pool_create(8, 2, hkv.FP32, FAKE_K, FAKE_V)
+    assert e.value.code == hkv.ESHAPE
+    with pytest.raises(hkv.HkvError) as e:
+        hkv.kv_pool_create(8, 2, hkv.BF16, None, FAKE_V)
+    assert e.value.code == hkv.EINVAL
+    with pytest.raises(hkv.HkvError) as e:
+        hkv.kv_pool_create(4, 2, hkv.BF16, FAKE_K, FAKE_V, free_order=[0, 1, 1, 3])
+    assert e.value.code == hkv.EINVAL
+    assert "permutation" in str(e.value)
+    hkv.kv_pool_destroy(fake_pool())
+
+
+def test_pool_alloc_retain_release_matches_model():
+    rng = np.random.default_rng(0)
+    n = 40
+    order = rng.permutation(n).astype(np.int32)
+    pool = fake_pool(n, free_order=order)
+    free = list(order)
+    ref = [0] * n
+    held = []
+    for step in range(300):
+        op = rng.integers(0, 3)
+        if op == 0:
+            k = int(rng.integers(0, 6))
+            if k > len(free):
+                with pytest.raises(hkv.HkvError) as e:
+                    hkv.kv_pool_alloc(pool, k)
+                assert e.value.code == hkv.ENOMEM
+                continue
+            got = hkv.kv_pool_alloc(pool, k)
+            exp = [free.pop(0) for _ in range(k)]
+            assert list(got) == exp                     # deterministic, bit-exact page ids
+            for p in exp:
+                ref[p] = 1
+            held += exp
+        elif op == 1 and held:
+            ids = list(rng.choice(held, size=min(3, len(held)), replace=False))
+            hkv.kv_pool_retain(pool, ids)
+            for p in ids:
+                ref[p] += 1
+            held += ids
+        elif op == 2 and held:
+            k = int(rng.integers(1, min(4, len(held)) + 1))
+            idx = sorted(rng.choice(len(held), size=k, replace=False), reverse=True)
+            ids = [held.pop(i) for i in idx]
+            hkv.kv_pool_release(pool, ids)
+            for p in ids:
+                ref[p] -= 1
+                if ref[p] == 0:
+                    free.append(p)
+        assert hkv.kv_pool_num_free(pool) == len(free)
+    for p in range(n):
+        assert hkv.kv_pool_refcount(pool, p) == ref[p]
+    with pytest.raises(hkv.HkvError) as e:
+        hkv.kv_pool_retain(pool, [n])
+    assert e.value.code == hkv.ERANGE
+    if free:
+        with pytest.raises(hkv.HkvError) as e:
+            hkv.kv_pool_release(pool, [int(free[0])])
+        assert e.value.code == hkv.EINVAL
+    hkv.kv_pool_destroy(pool)
+
+
+def test_pool_write_validates_before_touching_the_device():
+    pool = fake_pool(8)
+    for args, code in (((np.array([9], dtype=np.int32), 0, 4), hkv.ERANGE),
+                       ((np.array([-1], dtype=np.int32), 0, 4), hkv.ERANGE),
+                       ((np.array([1], dtype=np.int32), 16, 4), hkv.EINVAL),
+                       ((np.array([1], dtype=np.int32), 0, -1), hkv.EINVAL)):
+        with pytest.raises(hkv.HkvError) as e:
+            hkv.kv_pool_write(pool, args[0], args[1], args[2], 0x50000, 0x60000, stream=0)
+        assert e.value.code == code
+    hkv.kv_pool_write(pool, np.zeros(0, dtype=np.int32), 0, 0, None, None, stream=0)    # empty write is a no-op
+    p8 = fake_pool(8, dtype=hkv.FP8_E4M3)
+    with pytest.raises(hkv.HkvError) as e:
+        hkv.kv_pool_write(p8, np.array([1], dtype=np.int32), 3, 4, 0x50000, 0x60000, stream=0)
+    assert e.value.code == hkv.EINVAL and "slot 0" in str(e.value)
+    hkv.kv_pool_destroy(pool)
+    hkv.kv_pool_destroy(p8)
+
+
+# ------------------------------------------------------------------------------ forest indexing (bit-exact vs oracle)
+
+def _all_forests():
+    out = [wl.random_forest_workload(s, depth=4, fanout=3, n_roots=3).forest for s in range(100, 112)]
+    c1p, c1d = wl.config1()
+    out += [c1p.forest, c1d.forest, wl.config2().forest, wl.config3().forest, wl.config4().forest,
+            wl.config5().forest]
+    return out
+
+
+def test_flatten_bit_exact_against_oracle(oracle):
+    for f in _all_forests():
+        mp = max(1, f.max_pages_per_req()) + 1
+        got = hkv.prefix_tree_flatten(f.nodes, f.node_pages, f.req_leaf, mp)
+        exp = oracle.flatten_tree(f.nodes, f.node_pages, f.req_leaf, mp)
+        for g, e, name in zip(got, exp, ("block_table", "kv_len", "node_req_indptr", "node_req_idx", "node_tok_start")):
+            assert np.array_equal(g, e), name
+
+
+def test_flatten_error_codes():
+    pages = np.arange(8, dtype=np.int32)
+    ok = np.array([[-1, 0, 1, 16], [0, 1, 1, 5]], dtype=np.int32)
+    hkv.prefix_tree_flatten(ok, pages, [1], 4)
+    cases = [(np.array([[0, 0, 1, 16]], dtype=np.int32), [0], 4, hkv.ETREE),
+             (np.array([[-1, 0, 1, 12], [0, 1, 1, 5]], dtype=np.int32), [1], 4, hkv.ETREE),
+             (np.array([[-1, 0, 2, 16]], dtype=np.int32), [0], 4, hkv.ETREE),
+             (np.array([[-1, 7, 2, 32]], dtype=np.int32), [0], 4, hkv.ERANGE),
+             (ok, [2], 4, hkv.ERANGE),
+             (ok, [1], 1, hkv.ENOMEM)]
+    for nodes, leaves, mp, code in cases:
+        with pytest.raises(hkv.HkvError) as e:
+            hkv.prefix_tree_flatten(nodes, pages, leaves, mp)
+        assert e.value.code == code, (nodes, code, str(e.value))
+
+
+def test_prefill_usage_bit_exact_against_oracle(oracle):
+    rng = np.random.default_rng(1)
+    for f in _all_forests()[:14]:
+        calls = rng.integers(0, f.n_nodes, size=25).astype(np.int32)
+        assert np.array_equal(hkv.prefix_tree_prefill_usage(f.nodes, calls), oracle.prefill_usage(f.nodes, calls))
+    pre, _ = wl.config1()
+    assert list(hkv.prefix_tree_prefill_usage(pre.forest.nodes, [5, 6, 7, 8])) == [304, 48, 48, 48]
+
+
+# ------------------------------------------------------------------------------ decode planning
+
+def _check_decode_plan(w, oracle):
+    f = w.forest
+    pool = fake_pool(w.num_pages, w.num_kv_heads, w.kv_dtype)
+    plan = hkv.hkv_decode_plan_create(pool, f.nodes, f.node_pages, f.req_leaf, w.num_q_heads, hkv.PLAN_HOST_ONLY)
+    items = hkv.hkv_decode_plan_items(plan)
+    G = w.group
+    _, kv_len, indptr, idx, tok_start = oracle.flatten_tree(f.nodes, f.node_pages, f.req_leaf,
+                                                            max(1, f.max_pages_per_req()))
+    max_parts = hkv.hkv_decode_plan_max_parts(plan)
+    counts = hkv.hkv_decode_plan_part_counts(plan, f.n_req)
+    assert hkv.hkv_decode_plan_num_parts(plan) == f.n_req * w.num_q_heads * max_parts
+    assert hkv.hkv_decode_plan_workspace_bytes(plan) >= hkv.hkv_decode_plan_num_parts(plan) * 516
+    covered = [np.zeros((w.num_kv_heads, int(kv_len[r])), dtype=np.int32) for r in range(f.n_req)]
+    slots = [np.zeros((w.num_kv_heads, max_parts), dtype=np.int32) for _ in range(f.n_req)]
+    for page_off, n_tok, kv_head, req_off, n_req, slot, tok_begin, node in items:
+        assert 1 <= n_tok and tok_begin % 16 == 0 and tok_begin + n_tok <= f.n_tokens[node]
+        assert page_off == f.page_begin[node] + tok_begin // 16
+        assert 1 <= n_req and n_req * G <= 64
+        if n_req * G > 16:
+            assert n_tok <= 2048                       # what the LDS-staged path can index
+        assert indptr[node] <= req_off and req_off + n_req <= indptr[node + 1]
+        if tok_begin + n_tok < f.n_tokens[node]:
+            assert n_tok % 16 == 0                     # only a node's last chunk may end inside a page
+        for r in idx[req_off: req_off + n_req]:
+            a = tok_start[node] + tok_begin
+            covered[r][kv_head, a: a + n_tok] += 1
+            slots[r][kv_head, slot] += 1
+    for r in range(f.n_req):
+        assert (covered[r] == 1).all(), "every (request, kv head, token) is read by exactly one item"
+        assert (slots[r][:, :counts[r]] == 1).all() and (slots[r][:, counts[r]:] == 0).all()
+    hkv.hkv_decode_plan_destroy(plan)
+    hkv.kv_pool_destroy(pool)
+    return items
+
+
+def test_decode_plan_covers_every_token_once(oracle):
+    for seed in range(120, 128):
+        hq, hk = [(8, 2), (8, 1), (4, 4), (16, 1)][seed % 4]
+        _check_decode_plan(wl.random_forest_workload(seed, depth=4, fanout=3, n_roots=2, max_node_pages=40,
+                                                     num_q_heads=hq, num_kv_heads=hk), oracle)
+    _, c1d = wl.config1()
+    for w in (c1d, wl.config2(), wl.config3(), wl.config5()):
+        _check_decode_plan(w, oracle)
+
+
+def test_decode_plan_sizes_of_benchmark_configs(oracle):
+    items = _check_decode_plan(wl.config2(), oracle)
+    assert len(items) == 640            # 64 leaves x 8 heads + 4 chunks x 4 row groups x 8 heads of the root
+    # heavy items first
+    cost = items[:, 1] * np.maximum(16, items[:, 4] * 4)
+    assert (np.diff(cost) <= 0).all()
+
+
+def test_decode_plan_error_codes():
+    pool = fake_pool(16, 2)
+    nodes = np.array([[-1, 0, 1, 16], [0, 1, 1, 5]], dtype=np.int32)
+    pages = np.array([3, 4], dtype=np.int32)
+    cases = [(nodes, pages, [1], 3, hkv.ESHAPE),                                    # 3 q heads over 2 kv heads
+             (nodes, np.array([3, 16], dtype=np.int32), [1], 4, hkv.ERANGE),        # page id outside the pool
+             (nodes, pages, [5], 4, hkv.ERANGE),
+             (np.array([[-1, 0, 1, 10], [0, 1, 1, 5]], dtype=np.int32), pages, [1], 4, hkv.ETREE)]
+    for n, p, leaves, hq, code in cases:
+        with pytest.raises(hkv.HkvError) as e:
+            hkv.hkv_decode_plan_create(pool, n, p, leaves, hq, hkv.PLAN_HOST_ONLY)
+        assert e.value.code == code, str(e.value)
+    plan = hkv.hkv_decode_plan_create(pool, nodes, pages, [1], 4, hkv.PLAN_HOST_ONLY)
+    with pytest.raises(hkv.HkvError) as e:          # a host-only plan cannot run
+        hkv.attn_decode_plan_run(plan, 0x1000, 1.0, 0x2000, None, 0x3000, 1 << 20, stream=0)
+    assert e.value.code == hkv.EINVAL and "host-only" in str(e.value)
+    with pytest.raises(hkv.HkvError) as e:
+        hkv.attn_decode_plan_run(plan, 0x1001, 1.0, 0x2000, None, 0x3000, 1 << 20, stream=0)   # unaligned q
+    assert e.value.code == hkv.EINVAL
+    assert hkv.attn_decode_workspace_bytes(pool, nodes, pages, [1], 4) == hkv.hkv_decode_plan_workspace_bytes(plan)
+    hkv.hkv_decode_plan_destroy(plan)
+    hkv.kv_pool_destroy(pool)
+
+
+# ------------------------------------------------------------------------------ prefill planning
+
+def _check_prefill_plan(w, oracle):
+    f = w.forest
+    bt, kv_len, *_ = oracle.flatten_tree(f.nodes, f.node_pages, f.req_leaf, max(1, f.max_pages_per_req()))
+    cu = w.cu_q()
+    pool = fake_pool(w.num_pages, w.num_kv_heads, w.kv_dtype)
+    plan = hkv.hkv_prefill_plan_create(pool, cu, bt, kv_len, w.num_q_heads, hkv.PLAN_HOST_ONLY)
+    tiles = hkv.hkv_prefill_plan_tiles(plan)
+    tq = 256 // w.group
+    covered = np.zeros((w.num_kv_heads, int(cu[-1])), dtype=np.int32)
+    for req, q_begin, n_q, kv_head, q_row0, prefix_len, kvl, bt_off in tiles:
+        assert 1 <= n_q <= tq and q_begin % tq == 0
+        assert q_row0 == cu[req] + q_begin and q_begin + n_q <= cu[req + 1] - cu[req]
+        assert kvl == kv_len[req] and prefix_len == kv_len[req] - (cu[req + 1] - cu[req])
+        assert bt_off == req * bt.shape[1]
+        covered[kv_head, q_row0: q_row0 + n_q] += 1
+    assert (covered == 1).all()
+    # longest key range first
+    ext = tiles[:, 5] + tiles[:, 1] + tiles[:, 2]
+    assert (np.diff(ext[::w.num_kv_heads]) <= 0).all()
+    hkv.hkv_prefill_plan_destroy(plan)
+    hkv.kv_pool_destroy(pool)
+    return tiles
+
+
+def test_prefill_plan_covers_every_new_token_once(oracle):
+    for seed in range(130, 136):
+        hq, hk = [(8, 2), (8, 1), (4, 4), (4, 2)][seed % 4]
+        _check_prefill_plan(wl.random_forest_workload(seed, mode="prefill", num_q_heads=hq, num_kv_heads=hk,
+                                                      max_node_pages=30), oracle)
+    c1p, _ = wl.config1()
+    _check_prefill_plan(c1p, oracle)
+    tiles = _check_prefill_plan(wl.config4(), oracle)
+    assert len(tiles) == 3712
+
+
+def test_prefill_plan_error_codes():
+    pool = fake_pool(16, 2)
+    bt = np.array([[1, 2, 3, -1]], dtype=np.int32)
+    cases = [([0, 8], bt, [40], 4, hkv.OK),
+             ([0, 8], bt, [4], 4, hkv.EINVAL),              # fewer keys than new tokens
+             ([1, 8], bt, [40], 4, hkv.EINVAL),             # cu_q must start at 0
+             ([0, 8], bt, [80], 4, hkv.ENOMEM),             # needs 5 pages, table has 4
+             ([0, 8], bt, [60], 4, hkv.ERANGE),             # reaches the -1 entry
+             ([0, 8], bt, [40], 6, hkv.ESHAPE)]             # group of 3 heads
+    for cu, b, kvl, hq, code in cases:
+        if code == hkv.OK:
+            hkv.hkv_prefill_plan_destroy(hkv.hkv_prefill_plan_create(pool, cu, b, kvl, hq, hkv.PLAN_HOST_ONLY))
+            continue
+        with pytest.raises(hkv.HkvError) as e:
+            hkv.hkv_prefill_plan_create(pool, cu, b, kvl, hq, hkv.PLAN_HOST_ONLY)
+        assert e.value.code == code, str(e.value)
+    p8 = fake_pool(16, 2, dtype=hkv.FP8_E4M3)
+    with pytest.raises(hkv.HkvError) as e:
+        hkv.hkv_prefill_plan_create(p8, [0, 8], bt, [40], 4, hkv.PLAN_HOST_ONLY)
+    assert e.value.code == hkv.ESHAPE
+    hkv.kv_pool_destroy(pool)
+    hkv.kv_pool_destroy(p8)
+
+
+def test_merge_argument_validation():
+    with pytest.raises(hkv.HkvError) as e:
+        hkv.lse_merge(0x1000, 0x2000, 0x3000, 0x4000, 4, 0x5000, 7, stream=0)
+    assert e.value.code == hkv.ESHAPE
+    with pytest.raises(hkv.HkvError) as e:
+        hkv.lse_merge(None, 0x2000, 0x3000, 0x4000, 4, 0x5000, hkv.BF16, stream=0)
+    assert e.value.code == hkv.EINVAL
+    hkv.lse_merge(None, None, None, None, 0, None, hkv.BF16, stream=0)              # nothing to do
+    with pytest.raises(hkv.HkvError) as e:
+        hkv.lse_merge_dense(0x1000, 0x2000, 0x3000, 0, 4, 8, 0x5000, hkv.BF16, stream=0)
+    assert e.value.code == hkv.EINVAL
+    with pytest.raises(hkv.HkvError) as e:
+        hkv.lse_merge_dense(0x1004, 0x2000, 0x3000, 4, 4, 8, 0x5000, hkv.BF16, stream=0)
+    assert e.value.code == hkv.EINVAL
+    assert hkv.attn_prefill_workspace_bytes(1000, 32) == 0
