@@ -232,12 +232,15 @@ int hkv_decode_plan_part_counts(const hkv_decode_plan *plan, int32_t *part_count
 int attn_decode_plan_run(hkv_decode_plan *plan, const void *q, float scale, void *out, float *lse_out,
                          void *workspace, size_t workspace_bytes, void *stream);
 
-/* Profiling aid.  While enabled, attn_decode_plan_run brackets its two kernels with HIP events
- * on the stream it is given (this adds a few microseconds between them).
- * hkv_decode_plan_elapsed_ms waits for the most recent profiled run to finish and returns the
- * GPU time of the per-node kernel and of the merge kernel in milliseconds.
+/* Profiling aid.  mode 0: off.  mode 1: attn_decode_plan_run brackets its two kernels with HIP
+ * events on the stream it is given (each event costs a few microseconds of dispatch latency that
+ * end up inside the intervals).  mode 2: attn_decode_plan_run launches only the per-node kernel
+ * and leaves `out` untouched, so that a caller can time a batch of back-to-back launches of that
+ * kernel with two events of its own.
+ * hkv_decode_plan_elapsed_ms (mode 1) waits for the most recent profiled run to finish and returns
+ * the GPU time of the per-node kernel and of the merge kernel in milliseconds.
  * EINVAL if no profiled run has been queued. */
-int hkv_decode_plan_set_profiling(hkv_decode_plan *plan, int32_t enable);
+int hkv_decode_plan_set_profiling(hkv_decode_plan *plan, int32_t mode);
 int hkv_decode_plan_elapsed_ms(hkv_decode_plan *plan, float *node_ms /* host */, float *merge_ms /* host */);
 
 /* One-shot form: plans (or reuses the plan cached in the pool when the forest is unchanged) and

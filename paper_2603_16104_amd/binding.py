@@ -236,8 +236,9 @@ def attn_decode_plan_run(plan, q, scale: float, out, lse_out, workspace, workspa
                                       C.c_size_t(workspace_bytes), _stream(stream)))
 
 
-def hkv_decode_plan_set_profiling(plan, enable: bool) -> None:
-    _check(lib().hkv_decode_plan_set_profiling(plan, C.c_int32(1 if enable else 0)))
+def hkv_decode_plan_set_profiling(plan, mode) -> None:
+    """mode: 0/False off, 1/True events around both kernels, 2 launch the per-node kernel only."""
+    _check(lib().hkv_decode_plan_set_profiling(plan, C.c_int32(int(mode))))
 
 
 def hkv_decode_plan_elapsed_ms(plan):

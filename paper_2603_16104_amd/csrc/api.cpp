@@ -68,7 +68,7 @@ struct hkv_decode_plan {
     void *dev = nullptr;
     DecodeItem *d_items = nullptr;
     int32_t *d_pages = nullptr, *d_node_req_idx = nullptr, *d_part_count = nullptr;
-    bool profiling = false, profiled_run = false;
+    bool profiling = false, profiled_run = false, node_only = false;
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
 };
 
@@ -597,6 +597,7 @@ extern "C" int attn_decode_plan_run(hkv_decode_plan *plan, const void *q, float 
                        (int32_t)plan->items.size(), plan->num_q_heads, plan->max_parts, scale, nullptr};
         HKV_HIP(launch_decode(a, s));
     }
+    if (plan->node_only) return HKV_OK;
     if (prof) HKV_HIP(hipEventRecord(plan->ev[1], s));
     HKV_HIP(launch_lse_merge_dense(o_parts, lse_parts, plan->d_part_count, plan->num_q_heads, plan->max_parts,
                                    plan->n_req * plan->num_q_heads, out, HKV_BF16, lse_out, s));
@@ -607,11 +608,13 @@ extern "C" int attn_decode_plan_run(hkv_decode_plan *plan, const void *q, float 
     return HKV_OK;
 }
 
-extern "C" int hkv_decode_plan_set_profiling(hkv_decode_plan *plan, int32_t enable) {
+extern "C" int hkv_decode_plan_set_profiling(hkv_decode_plan *plan, int32_t mode) {
     if (!plan) return fail(HKV_EINVAL, "hkv_decode_plan_set_profiling: null plan");
-    if (enable && !plan->ev[0])
+    if (mode < 0 || mode > 2) return fail(HKV_EINVAL, "hkv_decode_plan_set_profiling: mode %d", mode);
+    if (mode == 1 && !plan->ev[0])
         for (hipEvent_t &e : plan->ev) HKV_HIP(hipEventCreate(&e));
-    plan->profiling = enable != 0;
+    plan->profiling = mode == 1;
+    plan->node_only = mode == 2;
     return HKV_OK;
 }
 
