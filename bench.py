@@ -180,6 +180,9 @@ def main() -> int:
     ap.add_argument("--no-extras", action="store_true", help="skip the context workloads (c3, c4, pool write)")
     ap.add_argument("--c5", action="store_true", help="also time the fp8 forest (2.4 GB pool, slow to generate)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--profile-workload", choices=["c3", "c4", "c5"], default=None,
+                    help="run only this context workload for a few steps and print its figures (for rocprofv3 runs "
+                         "of the other kernels; not the headline line)")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
                     help="also run a plain elementwise copy kernel over this many MiB three times (a known-size "
                          "kernel to calibrate rocprofv3's FETCH_SIZE / WRITE_SIZE counters against)")
@@ -206,6 +209,23 @@ def main() -> int:
         log(f"copy probe: 3 x elementwise add over {n * 4} bytes read + {n * 4} bytes written")
         del src, dst
         torch.cuda.empty_cache()
+
+    if args.profile_workload:
+        name = args.profile_workload
+        if name == "c4":
+            w4 = wl.config4()
+            s4, k4, t4 = bench_prefill(runtime, hkv, w4, max(1, min(args.steps, 10)), 2)
+            tf = w4.useful_flop() / (k4 * 1e-3) / 1e12
+            print(json.dumps({"workload": w4.name, "kernel_ms": round(k4, 4), "useful_TFLOPs": round(tf, 2),
+                              "mfma_bf16_frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
+                              "new_tokens_per_s": round(w4.total_q() / s4, 1), "tiles": t4}), flush=True)
+        else:
+            wx = wl.config3() if name == "c3" else wl.config5()
+            sx, nx, mx, hx, ix = bench_decode(runtime, hkv, wx, max(1, min(args.steps, 20)), 3,
+                                              1 if name == "c5" else args.pools, 5)
+            print(json.dumps({"workload": wx.name, "ms_per_step": round(sx * 1e3, 5),
+                              "unique_kv_GBps": round(wx.unique_kv_bytes() / sx / 1e9, 2), **ix}), flush=True)
+        return 0
 
     w = wl.config2()
     log(f"workload {w.name}: {w.forest.n_req} requests, unique KV {w.unique_kv_bytes() / 1e6:.1f} MB")

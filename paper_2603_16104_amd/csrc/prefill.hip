@@ -5,7 +5,8 @@
 // One workgroup (4 wavefronts) owns 256 query rows = 256/G consecutive new tokens x the G query
 // heads of one KV head, so every K/V tile staged in LDS is used by all G heads.  Each wavefront
 // owns 64 rows (two 32-row tiles) and keeps Q^T and the O^T accumulators in registers; K/V
-// stream through LDS in 64-token blocks, double buffered.
+// stream through LDS in 64-token blocks, triple buffered, fetched by LDS-direct loads
+// (global_load_lds_dwordx4) two blocks ahead so that the data in flight occupies no registers.
 //
 // Matrix-core mapping (v_mfma_f32_32x32x16_bf16):
 //   S^T = K * Q^T   A = 32 tokens x 16 dims (LDS), B = 16 dims x 32 rows (registers)
@@ -13,6 +14,18 @@
 // The token order of the score tile's M index is permuted (groups of four: 0,2,1,3) so that a lane
 // of the result holds eight consecutive tokens of a page per half, i.e. a ready B operand for the
 // second product and a 16-byte read of the dimension-major V page for its A operand.
+//
+// Softmax.  The exponentials of a block cost about as many VALU cycles as its two products cost
+// matrix-core cycles, so the main loop does as little else as possible and overlaps the two:
+//   - every row keeps ONE reference value m_ref, the maximum of its first 32 scores, for the whole
+//     key range: p = exp2((s - m_ref) * scale * log2 e).  Softmax is invariant to the reference, and
+//     fp32 / bf16 carry 8 exponent bits, so p may range over 2^-126 .. 2^90 without loss; there is
+//     no running maximum, no cross-lane traffic and no rescaling of O^T in the loop.  Should a row
+//     sum pass 2^90 (a later score more than ~60 above the first 32 ones), the workgroup abandons
+//     the result and recomputes its tile with the classic running-maximum loop further down.
+//   - the loop is software-pipelined inside each wavefront at 32-token steps: while the VALU turns
+//     the scores of step t into probabilities, the matrix core computes the scores of step t+1 into
+//     a second set of registers; the two instruction streams are interleaved explicitly.
 #include "hkv_device.h"
 
 namespace hkv {
@@ -21,21 +34,40 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kRowsPerGroup = 256;
-constexpr int KB = 64;                    // tokens per LDS stage (4 pages)
+constexpr int KB = 64;                         // tokens per LDS stage (4 pages)
 constexpr int kTileBytes = KB * kHeadDim * 2;  // 16 KiB for K, same for V
+constexpr float kSumLimit = 1.2379400392853803e27f;  // 2^90
+constexpr int kIdSlots = 2048;                 // page ids kept in LDS at a time (32768 tokens)
+
+#define HKV_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
+#define HKV_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
+// s_waitcnt immediate that waits for vmcnt <= n only (gfx9 encoding)
+constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
-__device__ __forceinline__ float half_swap_max(float v) { return fmaxf(v, __shfl_xor(v, 32)); }
+__device__ __forceinline__ f32x16 zero16() {
+    f32x16 z;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) z[i] = 0.f;
+    return z;
+}
+
+struct Step {
+    f32x16 t[2];  // scores of one 32-token step: [row tile nt]
+};
 
 __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillLaunch a) {
-    __shared__ __attribute__((aligned(16))) char sK[2][kTileBytes];
-    __shared__ __attribute__((aligned(16))) char sV[2][kTileBytes];
+    __shared__ __attribute__((aligned(16))) char sK[3][kTileBytes];
+    __shared__ __attribute__((aligned(16))) char sV[3][kTileBytes];
+    __shared__ int sIds[kIdSlots];  // page ids of the keys in use (a window of the block table row)
+    __shared__ int sBail;
 
     const PrefillTile tl = a.tiles[blockIdx.x];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, h = lane >> 5;
     const int Hq = a.num_q_heads, Hkv = a.pool.num_kv_heads;
     const int G = Hq / Hkv;
@@ -58,18 +90,6 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillLaunch a) {
     // wavefront-uniform: smallest absolute position among this wavefront's rows
     const int wave_min_pos = tl.prefix_len + tl.q_begin + 32 * ((2 * wave) % tbh);
 
-    f32x16 o[2][4];
-    float m_run[2], l_run[2];
-#pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
-#pragma unroll
-        for (int dm = 0; dm < 4; ++dm)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) o[nt][dm][i] = 0.f;
-        m_run[nt] = -INFINITY;
-        l_run[nt] = 0.f;
-    }
-
     const int kv_end = tl.prefix_len + tl.q_begin + tl.n_q;  // keys any row of the tile can see
     const int n_blk = (kv_end + KB - 1) / KB;
     const int last_page = (tl.kv_len - 1) >> 4;
@@ -78,41 +98,52 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillLaunch a) {
     const size_t page_stride = (size_t)Hkv * (kBlockElems * 2);
     const int32_t *bt = a.block_table + tl.bt_off;
 
-    // LDS offsets of this thread's 16-byte pieces within a page (bank-conflict swizzles):
-    //   K page: [chunk][slot][4 units of 16 B], unit ^= (slot / 4) % 4
-    //   V page: [d][2 units of 16 B],            unit ^= (d / 8) % 2
-    const int k_slot = (tid & 63) >> 2, k_unit = tid & 3;
-    const int k_lds = (tid >> 6) * 1024 + k_slot * 64 + ((k_unit ^ ((k_slot >> 2) & 3)) << 4);
-    const int v_d = tid >> 1, v_unit = tid & 1;
-    const int v_lds = v_d * 32 + ((v_unit ^ ((v_d >> 3) & 1)) << 4);
-
-    u32x4 kreg[4], vreg[4];
-    auto load_global = [&](int blk) {
+    // LDS-direct loads: a wavefront-level load writes 1 KiB, lane l at byte 16*l.  The LDS image of a
+    // page carries bank-conflict swizzles, so each lane fetches the 16-byte piece that belongs at
+    // its LDS position:
+    //   K page: [chunk = wavefront][slot][4 units of 16 B], unit ^= (slot / 4) % 4
+    //   V page: [d][2 units of 16 B],                        unit ^= (d / 8) % 2
+    const int k_slot = lane >> 2, k_unit = lane & 3;
+    const int k_src = wave * 1024 + k_slot * 64 + ((k_unit ^ ((k_slot >> 2) & 3)) << 4);
+    const int v_d = wave * 32 + (lane >> 1), v_unit = lane & 1;
+    const int v_src = v_d * 32 + ((v_unit ^ ((v_d >> 3) & 1)) << 4);
+    int id_base = 0;  // first page held in sIds
+    auto fill_ids = [&](int first_page) {  // all threads; the caller separates it from readers by barriers
+        for (int i = tid; i < kIdSlots; i += kThreads) sIds[i] = bt[min(first_page + i, last_page)];
+    };
+    // queue the 8 loads of block blk into stage `st` (pages past the sequence are clamped: in bounds)
+    auto issue_block = [&](int blk, int st) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int id = bt[min(blk * 4 + i, last_page)];
-            kreg[i] = ld16(kbase + (size_t)id * page_stride + tid * 16);
-            vreg[i] = ld16(vbase + (size_t)id * page_stride + tid * 16);
+            const int id = __builtin_amdgcn_readfirstlane(sIds[min(blk * 4 + i, last_page) - id_base]);
+            const size_t page = (size_t)id * page_stride;
+            __builtin_amdgcn_global_load_lds(HKV_GLOBAL_PTR(kbase + page + k_src),
+                                             HKV_LDS_PTR(sK[st] + i * 4096 + wave * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(HKV_GLOBAL_PTR(vbase + page + v_src),
+                                             HKV_LDS_PTR(sV[st] + i * 4096 + wave * 1024), 16, 0, 0);
         }
     };
-    auto store_lds = [&](int blk, int buf) {
-        const bool tail = blk * KB + KB > tl.kv_len;  // block holds slots past the sequence end
+    // V of slots past the sequence end may be anything (NaN included): overwrite with zeros.  Called
+    // by all threads between two barriers, only for the block that holds the sequence end.
+    auto zero_tail = [&](int blk, int st) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            u32x4 vv = vreg[i];
-            if (tail) {  // V of slots past the end may be anything (NaN included): store zeros
-                const int t0 = blk * KB + i * 16 + v_unit * 8;
+            u32x4 *pv = reinterpret_cast<u32x4 *>(sV[st] + i * 4096 + wave * 1024 + lane * 16);
+            u32x4 vv = *pv;
+            // the piece at this LDS position holds slots 8*u .. 8*u+7 of dim v_d, u = the un-swizzled unit
+            const int t0 = blk * KB + i * 16 + (v_unit ^ ((v_d >> 3) & 1)) * 8;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const uint32_t keep = (t0 + 2 * j + 1 < tl.kv_len) ? 0xFFFFFFFFu
-                                          : (t0 + 2 * j < tl.kv_len)   ? 0x0000FFFFu
-                                                                       : 0u;
-                    vv[j] &= keep;
-                }
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t keep = (t0 + 2 * j + 1 < tl.kv_len) ? 0xFFFFFFFFu : (t0 + 2 * j < tl.kv_len) ? 0x0000FFFFu : 0u;
+                vv[j] &= keep;
             }
-            *reinterpret_cast<u32x4 *>(&sK[buf][i * 4096 + k_lds]) = kreg[i];
-            *reinterpret_cast<u32x4 *>(&sV[buf][i * 4096 + v_lds]) = vv;
+            *pv = vv;
         }
+    };
+    // everything queued by this wavefront has landed; then everyone's has
+    auto land = [&]() {
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        __builtin_amdgcn_s_barrier();
     };
 
     // A-operand LDS offsets of this lane.
@@ -120,104 +151,224 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillLaunch a) {
     const int grp = n >> 2;
     const int grp_p = ((grp & 3) == 1) ? grp + 1 : ((grp & 3) == 2) ? grp - 1 : grp;
     const int tau = 4 * grp_p + (n & 3);
-    const int ka_page = tau >> 4, ka_slot = tau & 15;
+    const int ka_slot = tau & 15;
     const int ka_swz = (ka_slot >> 2) & 3;
-    const int ka_base = ka_page * 4096 + ka_slot * 64;
+    const int ka_base = (tau >> 4) * 4096 + ka_slot * 64;
     //   V: M index n -> dim 32*dm + n; unit h (slots 8h..8h+7), swizzled by (d/8)%2
     const int va_base = n * 32 + ((h ^ ((n >> 3) & 1)) << 4);
 
-    load_global(0);
-    store_lds(0, 0);
-    __syncthreads();
-
-    for (int blk = 0; blk < n_blk; ++blk) {
-        const int buf = blk & 1;
-        const bool more = blk + 1 < n_blk;
-        if (more) load_global(blk + 1);
-
-        // ---- S^T = K Q^T for 64 tokens x 64 rows
-        f32x16 s[2][2];
+    // S^T = K Q^T for one 32-token step (token tile mt of the block in kbuf) x this wavefront's 64 rows
+    auto scores = [&](Step &s, const char *kbuf, int mt) {
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
+        for (int kk = 0; kk < 8; ++kk) {
+            const int unit = 2 * (kk & 1) + h;
+            const bf16x8 ka = as_bf16x8(*reinterpret_cast<const u32x4 *>(
+                kbuf + mt * 8192 + ka_base + (kk >> 1) * 1024 + ((unit ^ ka_swz) << 4)));
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) s[nt][mt][i] = 0.f;
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-            for (int kk = 0; kk < 8; ++kk) {
-                const int unit = 2 * (kk & 1) + h;
-                const bf16x8 ka = as_bf16x8(*reinterpret_cast<const u32x4 *>(
-                    &sK[buf][mt * 8192 + ka_base + (kk >> 1) * 1024 + ((unit ^ ka_swz) << 4)]));
-#pragma unroll
-                for (int nt = 0; nt < 2; ++nt) s[nt][mt] = mfma32(ka, qf[nt][kk], s[nt][mt]);
-            }
-
-        // ---- online softmax per row; lane-local score (mt, i) is token blk*64 + mt*32 + (i/8)*16 + 8h + i%8
-        const bool need_mask = blk * KB + KB - 1 > wave_min_pos;
-        bf16x8 pb[2][4];
+            for (int nt = 0; nt < 2; ++nt) s.t[nt] = mfma32(ka, qf[nt][kk], kk == 0 ? zero16() : s.t[nt]);
+        }
+    };
+    // lane-local score i of step st is token st*32 + (i/8)*16 + 8h + i%8
+    auto mask_scores = [&](Step &s, int st) {
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt) {
-            if (need_mask) {
-                const int pos = tl.prefix_len + tl.q_begin + tok[nt];  // absolute position of this lane's row
+            // absolute position of this lane's row; rows past the tile's end behave like its last row,
+            // so they never see the garbage slots behind the sequence
+            const int pos = tl.prefix_len + tl.q_begin + min(tok[nt], tl.n_q - 1);
 #pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int t = blk * KB + mt * 32 + (i >> 3) * 16 + 8 * h + (i & 7);
-                        if (t > pos) s[nt][mt][i] = -INFINITY;
-                    }
-            }
-            float mx = s[nt][0][0];
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[nt][mt][i]);
-            mx = half_swap_max(mx);
-            const float m_new = fmaxf(m_run[nt], mx);
-            const float mc = m_new * c;
-            const float alpha = fast_exp2(m_run[nt] * c - mc);
-            float sum = 0.f;
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt) {
-                float p[16];
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    p[i] = fast_exp2(__builtin_fmaf(s[nt][mt][i], c, -mc));
-                    sum += p[i];
-                }
-#pragma unroll
-                for (int hf = 0; hf < 2; ++hf) {
-                    u32x4 w;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) w[j] = pack_bf16(p[hf * 8 + 2 * j], p[hf * 8 + 2 * j + 1]);
-                    pb[nt][mt * 2 + hf] = as_bf16x8(w);
-                }
-            }
-            l_run[nt] = l_run[nt] * alpha + sum;
-            m_run[nt] = m_new;
-            if (__builtin_amdgcn_ballot_w64(alpha != 1.0f)) {
-#pragma unroll
-                for (int dm = 0; dm < 4; ++dm)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) o[nt][dm][i] *= alpha;
+            for (int i = 0; i < 16; ++i) {
+                const int t = st * 32 + (i >> 3) * 16 + 8 * h + (i & 7);
+                if (t > pos) s.t[nt][i] = -INFINITY;
             }
         }
+    };
 
-        // ---- O^T += V^T P^T
+    f32x16 o[2][4];
+    float m_ref[2], l_run[2];
+    bf16x8 pb[2][2];
+    // O^T += V^T P^T for one step: pages 2*mt and 2*mt + 1 of the block in vbuf
+    auto accumulate = [&](const char *vbuf, int mt) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
             for (int dm = 0; dm < 4; ++dm) {
                 const bf16x8 va = as_bf16x8(
-                    *reinterpret_cast<const u32x4 *>(&sV[buf][u * 4096 + dm * 1024 + va_base]));
+                    *reinterpret_cast<const u32x4 *>(vbuf + (2 * mt + hf) * 4096 + dm * 1024 + va_base));
 #pragma unroll
-                for (int nt = 0; nt < 2; ++nt) o[nt][dm] = mfma32(va, pb[nt][u], o[nt][dm]);
+                for (int nt = 0; nt < 2; ++nt) o[nt][dm] = mfma32(va, pb[nt][hf], o[nt][dm]);
             }
+    };
+    auto pack_probs = [&](int nt, const float (&p)[16]) {
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf) {
+            u32x4 w;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) w[j] = pack_bf16(p[hf * 8 + 2 * j], p[hf * 8 + 2 * j + 1]);
+            pb[nt][hf] = as_bf16x8(w);
+        }
+    };
 
-        if (more) store_lds(blk + 1, buf ^ 1);
+    // =========================================================================================
+    // main path: one reference value per row, pipelined steps
+    // =========================================================================================
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+#pragma unroll
+        for (int dm = 0; dm < 4; ++dm) o[nt][dm] = zero16();
+        l_run[nt] = 0.f;
+    }
+    if (tid == 0) sBail = 0;
+    fill_ids(0);
+    __syncthreads();
+    issue_block(0, 0);
+    issue_block(1, 1);
+    land();
+    if (KB > tl.kv_len || 2 * KB > tl.kv_len) {  // the sequence ends inside block 0 or 1
+        if (KB > tl.kv_len) zero_tail(0, 0);
+        zero_tail(1, 1);
         __syncthreads();
+    }
+    Step sa, sb;  // even and odd steps
+    scores(sa, sK[0], 0);
+    if (31 > wave_min_pos) mask_scores(sa, 0);
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {  // reference = maximum of the row's first 32 scores (token 0 is visible)
+        float mx = sa.t[nt][0];
+#pragma unroll
+        for (int i = 1; i < 16; ++i) mx = fmaxf(mx, sa.t[nt][i]);
+        m_ref[nt] = fmaxf(mx, __shfl_xor(mx, 32));
+    }
+    const float mc[2] = {m_ref[0] * c, m_ref[1] * c};
+
+    // probabilities of one step against the fixed reference; branch-free
+    auto exponentials = [&](const Step &s) {
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+            float p[16];
+            float sum = 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                p[i] = fast_exp2(__builtin_fmaf(s.t[nt][i], c, -mc[nt]));
+                sum += p[i];
+            }
+            l_run[nt] += sum;
+            pack_probs(nt, p);
+        }
+    };
+    // the exponentials of one step and the scores of the next are independent: alternate one matrix
+    // instruction (32 cycles of the matrix core) with VALU instructions and operand reads
+    auto interleave = [&]() {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
+            __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);  // VALU
+        }
+    };
+
+    // Block j = steps 2j and 2j+1, held in stage j % 3; block j+2 is in flight into stage (j+2) % 3,
+    // which was last read during block j-1.
+    bool bail = false;
+    for (int j = 0; j < n_blk; ++j) {
+        const char *kcur = sK[j % 3], *knext = sK[(j + 1) % 3], *vcur = sV[j % 3];
+        if ((j + 2) * 4 + 3 - id_base >= kIdSlots && (j + 2) * 4 <= last_page) {  // id window exhausted (rare)
+            __syncthreads();
+            id_base = (j + 2) * 4;
+            fill_ids(id_base);
+            __syncthreads();
+        }
+        issue_block(j + 2, (j + 2) % 3);
+        if (j > 0 && j * KB + 31 > wave_min_pos) mask_scores(sa, 2 * j);
+        scores(sb, kcur, 1);
+        exponentials(sa);
+        interleave();
+        accumulate(vcur, 0);
+        if (j * KB + 63 > wave_min_pos) mask_scores(sb, 2 * j + 1);
+        scores(sa, knext, 0);  // step 2j+2 (stale data after the last block: never used)
+        exponentials(sb);
+        interleave();
+        accumulate(vcur, 1);
+        // a row sum beyond 2^90 (or inf/NaN) means the reference was far too low: give up this path
+        if (__builtin_amdgcn_ballot_w64(!(l_run[0] < kSumLimit) || !(l_run[1] < kSumLimit))) {
+            sBail = 1;
+        }
+        land();  // block j+2 is in LDS; stage j % 3 is no longer read; the flag is visible
+        if (sBail) {
+            bail = true;
+            break;
+        }
+        if ((j + 2) * KB + KB > tl.kv_len && (j + 2) * KB < tl.kv_len) {  // block j+2 holds the sequence end
+            zero_tail(j + 2, (j + 2) % 3);
+            __syncthreads();
+        }
+    }
+    float m_fin[2] = {m_ref[0], m_ref[1]};
+
+    // =========================================================================================
+    // fallback: classic online softmax with a running maximum, one 64-token block at a time.
+    // Only taken when a row's later scores exceed its first ones by more than the exponent range
+    // allows; always correct, not tuned.
+    // =========================================================================================
+    if (bail) {
+        float m_run[2];
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+#pragma unroll
+            for (int dm = 0; dm < 4; ++dm) o[nt][dm] = zero16();
+            m_run[nt] = -INFINITY;
+            l_run[nt] = 0.f;
+        }
+        __syncthreads();
+        id_base = 0;
+        fill_ids(0);
+        __syncthreads();
+        for (int j = 0; j < n_blk; ++j) {
+            if (j * 4 + 3 - id_base >= kIdSlots) {
+                id_base = j * 4;
+                fill_ids(id_base);
+                __syncthreads();
+            }
+            issue_block(j, 0);
+            land();
+            if (j * KB + KB > tl.kv_len) {
+                zero_tail(j, 0);
+                __syncthreads();
+            }
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt) {
+                Step s;
+                scores(s, sK[0], mt);
+                if (j * KB + mt * 32 + 31 > wave_min_pos) mask_scores(s, 2 * j + mt);
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt) {
+                    float mx = s.t[nt][0];
+#pragma unroll
+                    for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s.t[nt][i]);
+                    mx = fmaxf(mx, __shfl_xor(mx, 32));
+                    const float m_new = fmaxf(m_run[nt], mx);
+                    const float mcn = m_new * c;
+                    const float alpha = fast_exp2(m_run[nt] * c - mcn);
+                    float p[16];
+                    float sum = 0.f;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        p[i] = fast_exp2(__builtin_fmaf(s.t[nt][i], c, -mcn));
+                        sum += p[i];
+                    }
+                    pack_probs(nt, p);
+                    l_run[nt] = l_run[nt] * alpha + sum;
+                    m_run[nt] = m_new;
+#pragma unroll
+                    for (int dm = 0; dm < 4; ++dm)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) o[nt][dm][i] *= alpha;
+                }
+                accumulate(sV[0], mt);
+            }
+            __syncthreads();
+        }
+        m_fin[0] = m_run[0];
+        m_fin[1] = m_run[1];
     }
 
     // ---- normalise and store; lane (n, h) holds dims 32*dm + 8*(i/4) + 4*h + i%4 of its row
@@ -237,7 +388,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillLaunch a) {
                 w[1] = pack_bf16(o[nt][dm][4 * q4 + 2] * inv, o[nt][dm][4 * q4 + 3] * inv);
                 *reinterpret_cast<u32x2 *>(op + 32 * dm + 8 * q4 + 4 * h) = w;
             }
-        if (a.lse_out && h == 0) a.lse_out[row] = (m_run[nt] * c + fast_log2(l_tot)) * kLn2;
+        if (a.lse_out && h == 0) a.lse_out[row] = (m_fin[nt] * c + fast_log2(l_tot)) * kLn2;
     }
 }
 

@@ -313,3 +313,51 @@ def test_prefill_without_prefix(gpu, oracle):
     w = wl.Workload(name="no_prefix", num_q_heads=8, num_kv_heads=2, kv_dtype=wl.KV_BF16, num_pages=20, seed=8,
                     forest=f, mode="prefill", q_len=np.array(ntok, dtype=np.int32))
     run_prefill(gpu, oracle, w)
+
+
+class _FixedWorkload(wl.Workload):
+    """A workload whose tensors are given explicitly instead of drawn."""
+
+    def __init__(self, base, kv, q):
+        super().__init__(**base.__dict__)
+        self._kv, self._q = kv, q
+
+    def node_kv(self, node):
+        return self._kv[node]
+
+    def q(self):
+        return self._q
+
+
+@pytest.mark.parametrize("beta", [4.9, 8.0, 30.0])
+def test_prefill_late_dominant_key(gpu, oracle, beta):
+    """A key far down the sequence whose score exceeds everything before it by 55 / 90 / 340 nats.
+    The main prefill loop keeps one softmax reference per row (the maximum of the row's first 32
+    scores); the first case stays inside its exponent range, the others must take the
+    running-maximum fallback.  Rows behind the dominant key must return (almost exactly) its V."""
+    rng = np.random.default_rng(77)
+    n_tok, hot = 200, 150
+    f = wl.make_forest([-1], [n_tok], [0], np.random.default_rng(2).permutation(20).astype(np.int32))
+    base = wl.Workload(name=f"late_key_{beta}", num_q_heads=8, num_kv_heads=2, kv_dtype=wl.KV_BF16, num_pages=20,
+                       seed=1, forest=f, mode="prefill", q_len=np.array([n_tok], dtype=np.int32))
+    u = rng.standard_normal(128).astype(np.float32)
+    u *= np.sqrt(128.0) / np.linalg.norm(u)
+    k = (0.05 * rng.standard_normal((n_tok, 2, 128))).astype(np.float32)
+    v = rng.standard_normal((n_tok, 2, 128)).astype(np.float32)
+    k[hot] = beta * u                                  # score = beta * |u|^2 / sqrt(128) = 11.3 * beta nats
+    q = np.broadcast_to(u, (n_tok, 8, 128)).astype(np.float32) + 0.05 * rng.standard_normal((n_tok, 8, 128)).astype(np.float32)
+    w = _FixedWorkload(base, {0: (wl.f32_to_bf16_bits(k), wl.f32_to_bf16_bits(v))}, wl.f32_to_bf16_bits(q))
+    hp, dp = both_pools(gpu, oracle, w)
+    exp_o, exp_l = oracle.run_workload(w, hp)
+    r = gpu.PrefillRunner(dp, w)
+    r.run()
+    import torch
+    torch.cuda.synchronize()
+    got_o, got_l = gpu.bf16_tensor_to_f64(r.out), r.lse.cpu().numpy()
+    r.close()
+    dp.close()
+    check_close(got_o, exp_o, w.name)
+    # lse grows to hundreds here: compare relative to its magnitude (fp32 has 24 bits)
+    assert np.abs(got_l - exp_l).max() <= 2e-3 + 1e-6 * np.abs(exp_l).max()
+    vb = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(v))
+    assert np.abs(got_o[hot:, 0] - vb[hot, 0]).max() <= 2e-2
