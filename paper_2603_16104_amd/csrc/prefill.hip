@@ -85,7 +85,11 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillLaunch a) {
         const int qrow = tl.q_row0 + min(tok[nt], tl.n_q - 1);
         const char *qp = static_cast<const char *>(a.q) + ((size_t)qrow * Hq + head[nt]) * (kHeadDim * 2);
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk) qf[nt][kk] = as_bf16x8(ld16(qp + (16 * kk + 8 * h) * 2));
+        for (int kk = 0; kk < 8; ++kk) {
+            u32x4 w = ld16(qp + (16 * kk + 8 * h) * 2);
+            asm volatile("" : "+a"(w));  // Q^T is only read by matrix instructions: park it in the accumulation file
+            qf[nt][kk] = as_bf16x8(w);
+        }
     }
     // wavefront-uniform: smallest absolute position among this wavefront's rows
     const int wave_min_pos = tl.prefix_len + tl.q_begin + 32 * ((2 * wave) % tbh);
@@ -186,6 +190,16 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillLaunch a) {
     f32x16 o[2][4];
     float m_ref[2], l_run[2];
     bf16x8 pb[2][2];
+    // The O^T tiles are only ever touched by matrix instructions inside the loop.  Telling the
+    // register allocator that they belong in the accumulation registers (an empty asm with an "a"
+    // constraint) keeps it from parking them in the VALU registers and shuffling them back and
+    // forth around every softmax.
+    auto pin_accumulators = [&]() {
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+            for (int dm = 0; dm < 4; ++dm) asm volatile("" : "+a"(o[nt][dm]));
+    };
     // O^T += V^T P^T for one step: pages 2*mt and 2*mt + 1 of the block in vbuf
     auto accumulate = [&](const char *vbuf, int mt) {
 #pragma unroll
@@ -258,22 +272,27 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillLaunch a) {
     // the exponentials of one step and the scores of the next are independent: alternate one matrix
     // instruction (32 cycles of the matrix core) with VALU instructions and operand reads
     auto interleave = [&]() {
+#ifndef HKV_NO_INTERLEAVE
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
             __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);  // VALU
         }
+#endif
     };
 
-    // Block j = steps 2j and 2j+1, held in stage j % 3; block j+2 is in flight into stage (j+2) % 3,
-    // which was last read during block j-1.
+    // Block j = steps 2j and 2j+1, held in stage j % 3.  Block j+2 is requested at the top of
+    // iteration j (its stage was last read during block j-1) and has to be complete only in the
+    // middle of iteration j+1, when the scores of its first step are computed: the loads get one and
+    // a half iterations, and nothing ever waits for all outstanding loads.
     bool bail = false;
     for (int j = 0; j < n_blk; ++j) {
         const char *kcur = sK[j % 3], *knext = sK[(j + 1) % 3], *vcur = sV[j % 3];
         if ((j + 2) * 4 + 3 - id_base >= kIdSlots && (j + 2) * 4 <= last_page) {  // id window exhausted (rare)
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
             __syncthreads();
-            id_base = (j + 2) * 4;
+            id_base = (j + 1) * 4;  // block j+1 may still have to be named by zero_tail's caller
             fill_ids(id_base);
             __syncthreads();
         }
@@ -282,26 +301,35 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillLaunch a) {
         scores(sb, kcur, 1);
         exponentials(sa);
         interleave();
+        pin_accumulators();
         accumulate(vcur, 0);
+        pin_accumulators();
+        // block j+1 (requested one iteration ago) must be complete now; block j+2's 8 loads may fly on
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(8));
+        __builtin_amdgcn_s_barrier();
+        if ((j + 1) * KB + KB > tl.kv_len && (j + 1) * KB < tl.kv_len && j + 1 >= 2) {  // block j+1 holds the sequence end
+            zero_tail(j + 1, (j + 1) % 3);
+            __syncthreads();
+        }
         if (j * KB + 63 > wave_min_pos) mask_scores(sb, 2 * j + 1);
         scores(sa, knext, 0);  // step 2j+2 (stale data after the last block: never used)
         exponentials(sb);
         interleave();
+        pin_accumulators();
         accumulate(vcur, 1);
+        pin_accumulators();
         // a row sum beyond 2^90 (or inf/NaN) means the reference was far too low: give up this path
         if (__builtin_amdgcn_ballot_w64(!(l_run[0] < kSumLimit) || !(l_run[1] < kSumLimit))) {
             sBail = 1;
         }
-        land();  // block j+2 is in LDS; stage j % 3 is no longer read; the flag is visible
+        __syncthreads();  // stage j % 3 is no longer read; the flag is visible
         if (sBail) {
             bail = true;
             break;
         }
-        if ((j + 2) * KB + KB > tl.kv_len && (j + 2) * KB < tl.kv_len) {  // block j+2 holds the sequence end
-            zero_tail(j + 2, (j + 2) % 3);
-            __syncthreads();
-        }
     }
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // nothing of this path is in flight any more
+    __syncthreads();
     float m_fin[2] = {m_ref[0], m_ref[1]};
 
     // =========================================================================================
