@@ -32,8 +32,13 @@ namespace hkv {
 
 namespace {
 
-constexpr int kThreads = 256;
 constexpr int kRowsPerGroup = 256;
+#ifndef HKV_PREFILL_NT
+#define HKV_PREFILL_NT 1
+#endif
+constexpr int NT = HKV_PREFILL_NT;            // 32-row tiles per wavefront
+constexpr int kWaves = 8 / NT;                // 8 row tiles per workgroup
+constexpr int kThreads = 64 * kWaves;
 constexpr int KB = 64;                         // tokens per LDS stage (4 pages)
 constexpr int kTileBytes = KB * kHeadDim * 2;  // 16 KiB for K, same for V
 constexpr float kSumLimit = 1.2379400392853803e27f;  // 2^90
@@ -56,10 +61,10 @@ __device__ __forceinline__ f32x16 zero16() {
 }
 
 struct Step {
-    f32x16 t[2];  // scores of one 32-token step: [row tile nt]
+    f32x16 t[NT];  // scores of one 32-token step: [row tile nt]
 };
 
-__global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillLaunch a) {
+__global__ __launch_bounds__(kThreads, 2 / NT) void prefill_kernel(PrefillLaunch a) {
     __shared__ __attribute__((aligned(16))) char sK[3][kTileBytes];
     __shared__ __attribute__((aligned(16))) char sV[3][kTileBytes];
     __shared__ int sIds[kIdSlots];  // page ids of the keys in use (a window of the block table row)
@@ -75,11 +80,11 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillLaunch a) {
     const float c = a.scale * kLog2e;
 
     // the two 32-row tiles of this wavefront
-    int head[2], tok[2];  // query head; token index of this lane's row within the tile's new tokens
-    bf16x8 qf[2][8];
+    int head[NT], tok[NT];  // query head; token index of this lane's row within the tile's new tokens
+    bf16x8 qf[NT][8];
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
-        const int T = 2 * wave + nt;
+    for (int nt = 0; nt < NT; ++nt) {
+        const int T = NT * wave + nt;
         head[nt] = tl.kv_head * G + T / tbh;
         tok[nt] = 32 * (T % tbh) + n;
         const int qrow = tl.q_row0 + min(tok[nt], tl.n_q - 1);
@@ -87,12 +92,14 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillLaunch a) {
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) {
             u32x4 w = ld16(qp + (16 * kk + 8 * h) * 2);
+#if HKV_PREFILL_NT == 2
             asm volatile("" : "+a"(w));  // Q^T is only read by matrix instructions: park it in the accumulation file
+#endif
             qf[nt][kk] = as_bf16x8(w);
         }
     }
     // wavefront-uniform: smallest absolute position among this wavefront's rows
-    const int wave_min_pos = tl.prefix_len + tl.q_begin + 32 * ((2 * wave) % tbh);
+    const int wave_min_pos = tl.prefix_len + tl.q_begin + 32 * ((NT * wave) % tbh);
 
     const int kv_end = tl.prefix_len + tl.q_begin + tl.n_q;  // keys any row of the tile can see
     const int n_blk = (kv_end + KB - 1) / KB;
@@ -107,10 +114,11 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillLaunch a) {
     // its LDS position:
     //   K page: [chunk = wavefront][slot][4 units of 16 B], unit ^= (slot / 4) % 4
     //   V page: [d][2 units of 16 B],                        unit ^= (d / 8) % 2
+    // Per block 32 wavefront-level loads: (page i, 1 KiB quarter c) for K and for V; wavefront w takes
+    // the pairs with (4*i + c) % kWaves == w.
     const int k_slot = lane >> 2, k_unit = lane & 3;
-    const int k_src = wave * 1024 + k_slot * 64 + ((k_unit ^ ((k_slot >> 2) & 3)) << 4);
-    const int v_d = wave * 32 + (lane >> 1), v_unit = lane & 1;
-    const int v_src = v_d * 32 + ((v_unit ^ ((v_d >> 3) & 1)) << 4);
+    const int k_in_quarter = k_slot * 64 + ((k_unit ^ ((k_slot >> 2) & 3)) << 4);  // + c*1024
+    const int v_unit = lane & 1;
     int id_base = 0;  // first page held in sIds
     auto fill_ids = [&](int first_page) {  // all threads; the caller separates it from readers by barriers
         for (int i = tid; i < kIdSlots; i += kThreads) sIds[i] = bt[min(first_page + i, last_page)];
@@ -118,21 +126,28 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillLaunch a) {
     // queue the 8 loads of block blk into stage `st` (pages past the sequence are clamped: in bounds)
     auto issue_block = [&](int blk, int st) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int u = 0; u < 16 / kWaves; ++u) {
+            const int pc = u * kWaves + wave;  // 4*page + quarter
+            const int i = pc >> 2, cq = pc & 3;
             const int id = __builtin_amdgcn_readfirstlane(sIds[min(blk * 4 + i, last_page) - id_base]);
             const size_t page = (size_t)id * page_stride;
-            __builtin_amdgcn_global_load_lds(HKV_GLOBAL_PTR(kbase + page + k_src),
-                                             HKV_LDS_PTR(sK[st] + i * 4096 + wave * 1024), 16, 0, 0);
+            const int v_d = cq * 32 + (lane >> 1);
+            const int v_src = v_d * 32 + ((v_unit ^ ((v_d >> 3) & 1)) << 4);
+            __builtin_amdgcn_global_load_lds(HKV_GLOBAL_PTR(kbase + page + cq * 1024 + k_in_quarter),
+                                             HKV_LDS_PTR(sK[st] + i * 4096 + cq * 1024), 16, 0, 0);
             __builtin_amdgcn_global_load_lds(HKV_GLOBAL_PTR(vbase + page + v_src),
-                                             HKV_LDS_PTR(sV[st] + i * 4096 + wave * 1024), 16, 0, 0);
+                                             HKV_LDS_PTR(sV[st] + i * 4096 + cq * 1024), 16, 0, 0);
         }
     };
     // V of slots past the sequence end may be anything (NaN included): overwrite with zeros.  Called
     // by all threads between two barriers, only for the block that holds the sequence end.
     auto zero_tail = [&](int blk, int st) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            u32x4 *pv = reinterpret_cast<u32x4 *>(sV[st] + i * 4096 + wave * 1024 + lane * 16);
+        for (int u = 0; u < 16 / kWaves; ++u) {
+            const int pc = u * kWaves + wave;
+            const int i = pc >> 2, cq = pc & 3;
+            const int v_d = cq * 32 + (lane >> 1);
+            u32x4 *pv = reinterpret_cast<u32x4 *>(sV[st] + i * 4096 + cq * 1024 + lane * 16);
             u32x4 vv = *pv;
             // the piece at this LDS position holds slots 8*u .. 8*u+7 of dim v_d, u = the un-swizzled unit
             const int t0 = blk * KB + i * 16 + (v_unit ^ ((v_d >> 3) & 1)) * 8;
@@ -169,13 +184,13 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillLaunch a) {
             const bf16x8 ka = as_bf16x8(*reinterpret_cast<const u32x4 *>(
                 kbuf + mt * 8192 + ka_base + (kk >> 1) * 1024 + ((unit ^ ka_swz) << 4)));
 #pragma unroll
-            for (int nt = 0; nt < 2; ++nt) s.t[nt] = mfma32(ka, qf[nt][kk], kk == 0 ? zero16() : s.t[nt]);
+            for (int nt = 0; nt < NT; ++nt) s.t[nt] = mfma32(ka, qf[nt][kk], kk == 0 ? zero16() : s.t[nt]);
         }
     };
     // lane-local score i of step st is token st*32 + (i/8)*16 + 8h + i%8
     auto mask_scores = [&](Step &s, int st) {
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
+        for (int nt = 0; nt < NT; ++nt) {
             // absolute position of this lane's row; rows past the tile's end behave like its last row,
             // so they never see the garbage slots behind the sequence
             const int pos = tl.prefix_len + tl.q_begin + min(tok[nt], tl.n_q - 1);
@@ -187,18 +202,20 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillLaunch a) {
         }
     };
 
-    f32x16 o[2][4];
-    float m_ref[2], l_run[2];
-    bf16x8 pb[2][2];
+    f32x16 o[NT][4];
+    float m_ref[NT], l_run[NT];
+    bf16x8 pb[NT][2];
     // The O^T tiles are only ever touched by matrix instructions inside the loop.  Telling the
     // register allocator that they belong in the accumulation registers (an empty asm with an "a"
     // constraint) keeps it from parking them in the VALU registers and shuffling them back and
     // forth around every softmax.
     auto pin_accumulators = [&]() {
+#if HKV_PREFILL_NT == 2
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
+        for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
             for (int dm = 0; dm < 4; ++dm) asm volatile("" : "+a"(o[nt][dm]));
+#endif
     };
     // O^T += V^T P^T for one step: pages 2*mt and 2*mt + 1 of the block in vbuf
     auto accumulate = [&](const char *vbuf, int mt) {
@@ -209,7 +226,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillLaunch a) {
                 const bf16x8 va = as_bf16x8(
                     *reinterpret_cast<const u32x4 *>(vbuf + (2 * mt + hf) * 4096 + dm * 1024 + va_base));
 #pragma unroll
-                for (int nt = 0; nt < 2; ++nt) o[nt][dm] = mfma32(va, pb[nt][hf], o[nt][dm]);
+                for (int nt = 0; nt < NT; ++nt) o[nt][dm] = mfma32(va, pb[nt][hf], o[nt][dm]);
             }
     };
     auto pack_probs = [&](int nt, const float (&p)[16]) {
@@ -226,7 +243,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillLaunch a) {
     // main path: one reference value per row, pipelined steps
     // =========================================================================================
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
+    for (int nt = 0; nt < NT; ++nt) {
 #pragma unroll
         for (int dm = 0; dm < 4; ++dm) o[nt][dm] = zero16();
         l_run[nt] = 0.f;
@@ -246,18 +263,20 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillLaunch a) {
     scores(sa, sK[0], 0);
     if (31 > wave_min_pos) mask_scores(sa, 0);
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {  // reference = maximum of the row's first 32 scores (token 0 is visible)
+    for (int nt = 0; nt < NT; ++nt) {  // reference = maximum of the row's first 32 scores (token 0 is visible)
         float mx = sa.t[nt][0];
 #pragma unroll
         for (int i = 1; i < 16; ++i) mx = fmaxf(mx, sa.t[nt][i]);
         m_ref[nt] = fmaxf(mx, __shfl_xor(mx, 32));
     }
-    const float mc[2] = {m_ref[0] * c, m_ref[1] * c};
+    float mc[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) mc[nt] = m_ref[nt] * c;
 
     // probabilities of one step against the fixed reference; branch-free
     auto exponentials = [&](const Step &s) {
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
+        for (int nt = 0; nt < NT; ++nt) {
             float p[16];
             float sum = 0.f;
 #pragma unroll
@@ -274,7 +293,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillLaunch a) {
     auto interleave = [&]() {
 #ifndef HKV_NO_INTERLEAVE
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
+        for (int i = 0; i < 8 * NT; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
             __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);  // VALU
@@ -305,7 +324,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillLaunch a) {
         accumulate(vcur, 0);
         pin_accumulators();
         // block j+1 (requested one iteration ago) must be complete now; block j+2's 8 loads may fly on
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm(8));
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(32 / kWaves));
         __builtin_amdgcn_s_barrier();
         if ((j + 1) * KB + KB > tl.kv_len && (j + 1) * KB < tl.kv_len && j + 1 >= 2) {  // block j+1 holds the sequence end
             zero_tail(j + 1, (j + 1) % 3);
@@ -319,9 +338,10 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillLaunch a) {
         accumulate(vcur, 1);
         pin_accumulators();
         // a row sum beyond 2^90 (or inf/NaN) means the reference was far too low: give up this path
-        if (__builtin_amdgcn_ballot_w64(!(l_run[0] < kSumLimit) || !(l_run[1] < kSumLimit))) {
-            sBail = 1;
-        }
+        bool over = false;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) over |= !(l_run[nt] < kSumLimit);
+        if (__builtin_amdgcn_ballot_w64(over)) sBail = 1;
         __syncthreads();  // stage j % 3 is no longer read; the flag is visible
         if (sBail) {
             bail = true;
@@ -330,7 +350,9 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillLaunch a) {
     }
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // nothing of this path is in flight any more
     __syncthreads();
-    float m_fin[2] = {m_ref[0], m_ref[1]};
+    float m_fin[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) m_fin[nt] = m_ref[nt];
 
     // =========================================================================================
     // fallback: classic online softmax with a running maximum, one 64-token block at a time.
@@ -338,9 +360,9 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillLaunch a) {
     // allows; always correct, not tuned.
     // =========================================================================================
     if (bail) {
-        float m_run[2];
+        float m_run[NT];
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
+        for (int nt = 0; nt < NT; ++nt) {
 #pragma unroll
             for (int dm = 0; dm < 4; ++dm) o[nt][dm] = zero16();
             m_run[nt] = -INFINITY;
@@ -368,7 +390,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillLaunch a) {
                 scores(s, sK[0], mt);
                 if (j * KB + mt * 32 + 31 > wave_min_pos) mask_scores(s, 2 * j + mt);
 #pragma unroll
-                for (int nt = 0; nt < 2; ++nt) {
+                for (int nt = 0; nt < NT; ++nt) {
                     float mx = s.t[nt][0];
 #pragma unroll
                     for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s.t[nt][i]);
@@ -395,13 +417,13 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillLaunch a) {
             }
             __syncthreads();
         }
-        m_fin[0] = m_run[0];
-        m_fin[1] = m_run[1];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) m_fin[nt] = m_run[nt];
     }
 
     // ---- normalise and store; lane (n, h) holds dims 32*dm + 8*(i/4) + 4*h + i%4 of its row
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
+    for (int nt = 0; nt < NT; ++nt) {
         const float l_tot = l_run[nt] + __shfl_xor(l_run[nt], 32);
         if (tok[nt] >= tl.n_q) continue;
         const float inv = 1.0f / l_tot;
