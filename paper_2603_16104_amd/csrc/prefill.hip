@@ -43,11 +43,24 @@ constexpr int KB = 64;                         // tokens per LDS stage (4 pages)
 constexpr int kTileBytes = KB * kHeadDim * 2;  // 16 KiB for K, same for V
 constexpr float kSumLimit = 1.2379400392853803e27f;  // 2^90
 constexpr int kIdSlots = 2048;                 // page ids kept in LDS at a time (32768 tokens)
+constexpr int kStages = 4;                     // K/V blocks resident in LDS (4 x 32 KiB)
+constexpr int kLoadsPerBlock = 32 / kWaves;    // LDS-direct loads each wavefront issues per block
 
 #define HKV_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 #define HKV_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
 // s_waitcnt immediate that waits for vmcnt <= n only (gfx9 encoding)
 constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
+
+// LDS-direct load of 16 bytes per lane: lane l's piece lands at LDS byte lds_base + 16*l.  Issued as
+// inline assembly on purpose: the compiler makes every LDS read wait for ALL outstanding loads of
+// this kind that it knows of (it cannot tell the stages apart), which would drain the prefetch queue
+// at the top of every iteration.  Completion is tracked by hand (vmcnt waits + barriers) instead.
+__device__ __forceinline__ void load_to_lds16(const void *gptr, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory", "m0");
+}
+__device__ __forceinline__ uint32_t lds_address(const void *p) {
+    return (uint32_t)(size_t)HKV_LDS_PTR(p);
+}
 
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
@@ -65,8 +78,8 @@ struct Step {
 };
 
 __global__ __launch_bounds__(kThreads, 2 / NT) void prefill_kernel(PrefillLaunch a) {
-    __shared__ __attribute__((aligned(16))) char sK[3][kTileBytes];
-    __shared__ __attribute__((aligned(16))) char sV[3][kTileBytes];
+    __shared__ __attribute__((aligned(16))) char sK[kStages][kTileBytes];
+    __shared__ __attribute__((aligned(16))) char sV[kStages][kTileBytes];
     __shared__ int sIds[kIdSlots];  // page ids of the keys in use (a window of the block table row)
     __shared__ int sBail;
 
@@ -133,10 +146,8 @@ __global__ __launch_bounds__(kThreads, 2 / NT) void prefill_kernel(PrefillLaunch
             const size_t page = (size_t)id * page_stride;
             const int v_d = cq * 32 + (lane >> 1);
             const int v_src = v_d * 32 + ((v_unit ^ ((v_d >> 3) & 1)) << 4);
-            __builtin_amdgcn_global_load_lds(HKV_GLOBAL_PTR(kbase + page + cq * 1024 + k_in_quarter),
-                                             HKV_LDS_PTR(sK[st] + i * 4096 + cq * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds(HKV_GLOBAL_PTR(vbase + page + v_src),
-                                             HKV_LDS_PTR(sV[st] + i * 4096 + cq * 1024), 16, 0, 0);
+            load_to_lds16(kbase + page + cq * 1024 + k_in_quarter, lds_address(sK[st] + i * 4096 + cq * 1024));
+            load_to_lds16(vbase + page + v_src, lds_address(sV[st] + i * 4096 + cq * 1024));
         }
     };
     // V of slots past the sequence end may be anything (NaN included): overwrite with zeros.  Called
@@ -253,8 +264,10 @@ __global__ __launch_bounds__(kThreads, 2 / NT) void prefill_kernel(PrefillLaunch
     __syncthreads();
     issue_block(0, 0);
     issue_block(1, 1);
-    land();
-    if (KB > tl.kv_len || 2 * KB > tl.kv_len) {  // the sequence ends inside block 0 or 1
+    issue_block(2, 2);
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(kLoadsPerBlock));  // blocks 0 and 1 are complete, block 2 may fly on
+    __builtin_amdgcn_s_barrier();
+    if (2 * KB > tl.kv_len) {  // the sequence ends inside block 0 or 1
         if (KB > tl.kv_len) zero_tail(0, 0);
         zero_tail(1, 1);
         __syncthreads();
@@ -273,79 +286,83 @@ __global__ __launch_bounds__(kThreads, 2 / NT) void prefill_kernel(PrefillLaunch
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) mc[nt] = m_ref[nt] * c;
 
-    // probabilities of one step against the fixed reference; branch-free
-    auto exponentials = [&](const Step &s) {
+    // One pipeline phase = one 32-token step t, written in issue order and fenced so that the
+    // compiler keeps it:
+    //   1. request the eight V^T operands of step t from LDS;
+    //   2. eight matrix instructions S^T(t+1) = K(t+1) Q^T on the K operands already in registers,
+    //      each followed by the VALU work that turns two scores of step t into probabilities
+    //      (they run in the shadow of the matrix instruction; the V^T reads land meanwhile);
+    //   3. request the eight K operands of step t+2;
+    //   4. eight matrix instructions O^T += V^T(t) P^T(t) (the K reads land meanwhile).
+    static_assert(NT == 1, "the pipelined path is written for one row tile per wavefront");
+    bf16x8 kf[8];
+    auto load_k = [&](const char *ktile) {
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            float p[16];
-            float sum = 0.f;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                p[i] = fast_exp2(__builtin_fmaf(s.t[nt][i], c, -mc[nt]));
-                sum += p[i];
-            }
-            l_run[nt] += sum;
-            pack_probs(nt, p);
+        for (int kk = 0; kk < 8; ++kk) {
+            const int unit = 2 * (kk & 1) + h;
+            kf[kk] = as_bf16x8(*reinterpret_cast<const u32x4 *>(ktile + ka_base + (kk >> 1) * 1024 + ((unit ^ ka_swz) << 4)));
         }
     };
-    // the exponentials of one step and the scores of the next are independent: alternate one matrix
-    // instruction (32 cycles of the matrix core) with VALU instructions and operand reads
-    auto interleave = [&]() {
-#ifndef HKV_NO_INTERLEAVE
+    auto phase = [&](const f32x16 &sp, f32x16 &sn, const char *vtile, const char *knext) {
+        bf16x8 vf[8];
 #pragma unroll
-        for (int i = 0; i < 8 * NT; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
-            __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);  // VALU
+        for (int i = 0; i < 8; ++i)
+            vf[i] = as_bf16x8(*reinterpret_cast<const u32x4 *>(vtile + (i >> 2) * 4096 + (i & 3) * 1024 + va_base));
+        __builtin_amdgcn_sched_barrier(0);
+        u32x4 w[2];
+        float sum = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+            sn = mfma32(kf[kk], qf[0][kk], kk == 0 ? zero16() : sn);
+            const float p0 = fast_exp2(__builtin_fmaf(sp[2 * kk], c, -mc[0]));
+            const float p1 = fast_exp2(__builtin_fmaf(sp[2 * kk + 1], c, -mc[0]));
+            sum += p0 + p1;
+            w[kk >> 2][kk & 3] = pack_bf16(p0, p1);
+            __builtin_amdgcn_sched_barrier(0);
         }
-#endif
+        l_run[0] += sum;
+        load_k(knext);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[0][i & 3] = mfma32(vf[i], as_bf16x8(w[i >> 2]), o[0][i & 3]);
+        __builtin_amdgcn_sched_barrier(0);
     };
 
-    // Block j = steps 2j and 2j+1, held in stage j % 3.  Block j+2 is requested at the top of
-    // iteration j (its stage was last read during block j-1) and has to be complete only in the
-    // middle of iteration j+1, when the scores of its first step are computed: the loads get one and
-    // a half iterations, and nothing ever waits for all outstanding loads.
+    // Block j = steps 2j and 2j+1, held in stage j % kStages.  At the top of iteration j block j+3
+    // is requested into the stage that block j-1 has just left; blocks j and j+1 are complete (the
+    // wait at the end of iteration j-1 allows only the youngest request to be outstanding), so a
+    // request has two iterations to land and one barrier per iteration suffices.
+    load_k(sK[0] + 8192);  // step 1
     bool bail = false;
     for (int j = 0; j < n_blk; ++j) {
-        const char *kcur = sK[j % 3], *knext = sK[(j + 1) % 3], *vcur = sV[j % 3];
-        if ((j + 2) * 4 + 3 - id_base >= kIdSlots && (j + 2) * 4 <= last_page) {  // id window exhausted (rare)
+        const char *knext = sK[(j + 1) % kStages], *vcur = sV[j % kStages];
+        if ((j + 3) * 4 + 3 - id_base >= kIdSlots && (j + 3) * 4 <= last_page) {  // id window exhausted (rare)
             __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
             __syncthreads();
-            id_base = (j + 1) * 4;  // block j+1 may still have to be named by zero_tail's caller
+            id_base = (j + 2) * 4;
             fill_ids(id_base);
             __syncthreads();
         }
-        issue_block(j + 2, (j + 2) % 3);
+        issue_block(j + 3, (j + 3) % kStages);
         if (j > 0 && j * KB + 31 > wave_min_pos) mask_scores(sa, 2 * j);
-        scores(sb, kcur, 1);
-        exponentials(sa);
-        interleave();
-        pin_accumulators();
-        accumulate(vcur, 0);
-        pin_accumulators();
-        // block j+1 (requested one iteration ago) must be complete now; block j+2's 8 loads may fly on
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm(32 / kWaves));
-        __builtin_amdgcn_s_barrier();
-        if ((j + 1) * KB + KB > tl.kv_len && (j + 1) * KB < tl.kv_len && j + 1 >= 2) {  // block j+1 holds the sequence end
-            zero_tail(j + 1, (j + 1) % 3);
-            __syncthreads();
-        }
+        phase(sa.t[0], sb.t[0], vcur, knext);  // step 2j; scores of 2j+1; K of 2j+2
         if (j * KB + 63 > wave_min_pos) mask_scores(sb, 2 * j + 1);
-        scores(sa, knext, 0);  // step 2j+2 (stale data after the last block: never used)
-        exponentials(sb);
-        interleave();
-        pin_accumulators();
-        accumulate(vcur, 1);
-        pin_accumulators();
+        phase(sb.t[0], sa.t[0], vcur + 8192, knext + 8192);  // step 2j+1; scores of 2j+2; K of 2j+3
+        // (after the last block these read stale stages: in bounds, never used)
         // a row sum beyond 2^90 (or inf/NaN) means the reference was far too low: give up this path
-        bool over = false;
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) over |= !(l_run[nt] < kSumLimit);
+        const bool over = !(l_run[0] < kSumLimit);
         if (__builtin_amdgcn_ballot_w64(over)) sBail = 1;
-        __syncthreads();  // stage j % 3 is no longer read; the flag is visible
+        // blocks up to j+2 are complete (only the request of this iteration may be outstanding);
+        // stage j % kStages is no longer read; the flag is visible
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(kLoadsPerBlock));
+        __syncthreads();
         if (sBail) {
             bail = true;
             break;
+        }
+        if ((j + 2) * KB + KB > tl.kv_len && (j + 2) * KB < tl.kv_len) {  // block j+2 holds the sequence end
+            zero_tail(j + 2, (j + 2) % kStages);
+            __syncthreads();
         }
     }
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // nothing of this path is in flight any more
