@@ -25,8 +25,8 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast
 
 // float -> bf16 bits, round to nearest even (inputs here are finite or +-inf, never NaN payloads
 // that matter).  The compiler turns the pair form into the packed convert of gfx950.
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
     bf16x2 v;
     v[0] = (__bf16)lo;
     v[1] = (__bf16)hi;

@@ -2,10 +2,10 @@
 // prefix pages plus the causal part of their own suffix, all read through the block table.
 // (Section 5, "Token usage": a call processes only the tokens that are not already cached.)
 //
-// One workgroup (4 wavefronts) owns 256 query rows = 256/G consecutive new tokens x the G query
-// heads of one KV head, so every K/V tile staged in LDS is used by all G heads.  Each wavefront
-// owns 64 rows (two 32-row tiles) and keeps Q^T and the O^T accumulators in registers; K/V
-// stream through LDS in 64-token blocks, triple buffered, fetched by LDS-direct loads
+// One workgroup (8 wavefronts, two per SIMD) owns 256 query rows = 256/G consecutive new tokens x
+// the G query heads of one KV head, so every K/V tile staged in LDS is used by all G heads.  Each
+// wavefront owns one 32-row tile and keeps Q^T and the O^T accumulators in registers; K/V stream
+// through LDS in 64-token blocks, four stages each, fetched by LDS-direct loads
 // (global_load_lds_dwordx4) two blocks ahead so that the data in flight occupies no registers.
 //
 // Matrix-core mapping (v_mfma_f32_32x32x16_bf16):
@@ -23,9 +23,13 @@
 //     no running maximum, no cross-lane traffic and no rescaling of O^T in the loop.  Should a row
 //     sum pass 2^90 (a later score more than ~60 above the first 32 ones), the workgroup abandons
 //     the result and recomputes its tile with the classic running-maximum loop further down.
-//   - the loop is software-pipelined inside each wavefront at 32-token steps: while the VALU turns
-//     the scores of step t into probabilities, the matrix core computes the scores of step t+1 into
-//     a second set of registers; the two instruction streams are interleaved explicitly.
+//   - the loop is software-pipelined inside each wavefront at 32-token steps.  Phase t issues three
+//     mutually independent instruction streams, interleaved one to one:
+//         S^T(t+1) = K(t+1) Q^T      8 matrix instructions
+//         P(t)     = exp2(...S(t))    VALU
+//         O^T     += V^T(t-1) P^T(t-1) 8 matrix instructions
+//     so every matrix instruction has about three VALU instructions in its shadow and neither of
+//     the two wavefronts of a SIMD ever runs a VALU-only or matrix-only stretch.
 #include "hkv_device.h"
 
 namespace hkv {
@@ -33,21 +37,17 @@ namespace hkv {
 namespace {
 
 constexpr int kRowsPerGroup = 256;
-#ifndef HKV_PREFILL_NT
-#define HKV_PREFILL_NT 1
-#endif
-constexpr int NT = HKV_PREFILL_NT;            // 32-row tiles per wavefront
-constexpr int kWaves = 8 / NT;                // 8 row tiles per workgroup
+constexpr int kWaves = 8;                      // one 32-row tile each
 constexpr int kThreads = 64 * kWaves;
 constexpr int KB = 64;                         // tokens per LDS stage (4 pages)
 constexpr int kTileBytes = KB * kHeadDim * 2;  // 16 KiB for K, same for V
 constexpr float kSumLimit = 1.2379400392853803e27f;  // 2^90
 constexpr int kIdSlots = 2048;                 // page ids kept in LDS at a time (32768 tokens)
-constexpr int kStages = 4;                     // K/V blocks resident in LDS (4 x 32 KiB)
-constexpr int kLoadsPerBlock = 32 / kWaves;    // LDS-direct loads each wavefront issues per block
+constexpr int kStages = 4;                     // K blocks and V blocks resident in LDS (4 x 16 KiB each)
+constexpr int kParts = 16 / kWaves;            // (page, quarter) pairs of a block per wavefront
+constexpr int kLoadsPerBlock = 2 * kParts;     // LDS-direct loads each wavefront issues per iteration
 
 #define HKV_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
-#define HKV_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
 // s_waitcnt immediate that waits for vmcnt <= n only (gfx9 encoding)
 constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
@@ -56,11 +56,9 @@ constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) |
 // this kind that it knows of (it cannot tell the stages apart), which would drain the prefetch queue
 // at the top of every iteration.  Completion is tracked by hand (vmcnt waits + barriers) instead.
 __device__ __forceinline__ void load_to_lds16(const void *gptr, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory");
 }
-__device__ __forceinline__ uint32_t lds_address(const void *p) {
-    return (uint32_t)(size_t)HKV_LDS_PTR(p);
-}
+__device__ __forceinline__ uint32_t lds_address(const void *p) { return (uint32_t)(size_t)HKV_LDS_PTR(p); }
 
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
@@ -73,11 +71,7 @@ __device__ __forceinline__ f32x16 zero16() {
     return z;
 }
 
-struct Step {
-    f32x16 t[NT];  // scores of one 32-token step: [row tile nt]
-};
-
-__global__ __launch_bounds__(kThreads, 2 / NT) void prefill_kernel(PrefillLaunch a) {
+__global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillLaunch a) {
     __shared__ __attribute__((aligned(16))) char sK[kStages][kTileBytes];
     __shared__ __attribute__((aligned(16))) char sV[kStages][kTileBytes];
     __shared__ int sIds[kIdSlots];  // page ids of the keys in use (a window of the block table row)
@@ -92,27 +86,18 @@ __global__ __launch_bounds__(kThreads, 2 / NT) void prefill_kernel(PrefillLaunch
     const int tbh = 8 / G;  // 32-token blocks per head inside the workgroup's rows
     const float c = a.scale * kLog2e;
 
-    // the two 32-row tiles of this wavefront
-    int head[NT], tok[NT];  // query head; token index of this lane's row within the tile's new tokens
-    bf16x8 qf[NT][8];
+    // the 32-row tile of this wavefront
+    const int head = tl.kv_head * G + wave / tbh;  // query head
+    const int tok = 32 * (wave % tbh) + n;         // token index of this lane's row within the tile's new tokens
+    bf16x8 qf[8];
+    {
+        const int qrow = tl.q_row0 + min(tok, tl.n_q - 1);
+        const char *qp = static_cast<const char *>(a.q) + ((size_t)qrow * Hq + head) * (kHeadDim * 2);
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        const int T = NT * wave + nt;
-        head[nt] = tl.kv_head * G + T / tbh;
-        tok[nt] = 32 * (T % tbh) + n;
-        const int qrow = tl.q_row0 + min(tok[nt], tl.n_q - 1);
-        const char *qp = static_cast<const char *>(a.q) + ((size_t)qrow * Hq + head[nt]) * (kHeadDim * 2);
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-            u32x4 w = ld16(qp + (16 * kk + 8 * h) * 2);
-#if HKV_PREFILL_NT == 2
-            asm volatile("" : "+a"(w));  // Q^T is only read by matrix instructions: park it in the accumulation file
-#endif
-            qf[nt][kk] = as_bf16x8(w);
-        }
+        for (int kk = 0; kk < 8; ++kk) qf[kk] = as_bf16x8(ld16(qp + (16 * kk + 8 * h) * 2));
     }
     // wavefront-uniform: smallest absolute position among this wavefront's rows
-    const int wave_min_pos = tl.prefix_len + tl.q_begin + 32 * ((NT * wave) % tbh);
+    const int wave_min_pos = tl.prefix_len + tl.q_begin + 32 * (wave % tbh);
 
     const int kv_end = tl.prefix_len + tl.q_begin + tl.n_q;  // keys any row of the tile can see
     const int n_blk = (kv_end + KB - 1) / KB;
@@ -125,36 +110,51 @@ __global__ __launch_bounds__(kThreads, 2 / NT) void prefill_kernel(PrefillLaunch
     // LDS-direct loads: a wavefront-level load writes 1 KiB, lane l at byte 16*l.  The LDS image of a
     // page carries bank-conflict swizzles, so each lane fetches the 16-byte piece that belongs at
     // its LDS position:
-    //   K page: [chunk = wavefront][slot][4 units of 16 B], unit ^= (slot / 4) % 4
-    //   V page: [d][2 units of 16 B],                        unit ^= (d / 8) % 2
-    // Per block 32 wavefront-level loads: (page i, 1 KiB quarter c) for K and for V; wavefront w takes
-    // the pairs with (4*i + c) % kWaves == w.
+    //   K page: [chunk = 1 KiB quarter][slot][4 units of 16 B], unit ^= (slot / 4) % 4
+    //   V page: [d][2 units of 16 B],                            unit ^= (d / 8) % 2
+    // A block is 16 (page i, quarter cq) pairs for K and 16 for V; wavefront w takes the pairs
+    // 4*i + cq = u * kWaves + w, u < kParts.
     const int k_slot = lane >> 2, k_unit = lane & 3;
-    const int k_in_quarter = k_slot * 64 + ((k_unit ^ ((k_slot >> 2) & 3)) << 4);  // + c*1024
+    const int k_in_quarter = k_slot * 64 + ((k_unit ^ ((k_slot >> 2) & 3)) << 4);  // + cq*1024
     const int v_unit = lane & 1;
     int id_base = 0;  // first page held in sIds
     auto fill_ids = [&](int first_page) {  // all threads; the caller separates it from readers by barriers
         for (int i = tid; i < kIdSlots; i += kThreads) sIds[i] = bt[min(first_page + i, last_page)];
     };
-    // queue the 8 loads of block blk into stage `st` (pages past the sequence are clamped: in bounds)
+    auto k_source = [&](int id, int cq) { return kbase + (size_t)id * page_stride + cq * 1024 + k_in_quarter; };
+    auto v_source = [&](int id, int cq) {
+        const int v_d = cq * 32 + (lane >> 1);
+        return vbase + (size_t)id * page_stride + v_d * 32 + ((v_unit ^ ((v_d >> 3) & 1)) << 4);
+    };
+    // Main path: lane l of a window register holds the id of page 64 * (blk / 16) + l (pages past the
+    // sequence are clamped: in bounds), so a request costs a lane read instead of a memory access.
+    auto window = [&](int blk) { return sIds[min((blk & ~15) * 4 + lane, last_page) - id_base]; };
+    int kwin = 0, vwin = 0;
+    auto issue_k_part = [&](int blk, int u) {  // K of block blk -> stage blk % kStages
+        const int pc = u * kWaves + wave, i = pc >> 2, cq = pc & 3;
+        const int id = __builtin_amdgcn_readlane(kwin, (blk * 4 + i) & 63);
+        load_to_lds16(k_source(id, cq), lds_address(sK[blk % kStages] + i * 4096 + cq * 1024));
+    };
+    auto issue_v_part = [&](int blk, int u) {  // V of block blk -> stage blk % kStages
+        const int pc = u * kWaves + wave, i = pc >> 2, cq = pc & 3;
+        const int id = __builtin_amdgcn_readlane(vwin, (blk * 4 + i) & 63);
+        load_to_lds16(v_source(id, cq), lds_address(sV[blk % kStages] + i * 4096 + cq * 1024));
+    };
+    // Fallback path: K and V of block blk -> stage st, ids straight from LDS
     auto issue_block = [&](int blk, int st) {
 #pragma unroll
-        for (int u = 0; u < 16 / kWaves; ++u) {
-            const int pc = u * kWaves + wave;  // 4*page + quarter
-            const int i = pc >> 2, cq = pc & 3;
+        for (int u = 0; u < kParts; ++u) {
+            const int pc = u * kWaves + wave, i = pc >> 2, cq = pc & 3;
             const int id = __builtin_amdgcn_readfirstlane(sIds[min(blk * 4 + i, last_page) - id_base]);
-            const size_t page = (size_t)id * page_stride;
-            const int v_d = cq * 32 + (lane >> 1);
-            const int v_src = v_d * 32 + ((v_unit ^ ((v_d >> 3) & 1)) << 4);
-            load_to_lds16(kbase + page + cq * 1024 + k_in_quarter, lds_address(sK[st] + i * 4096 + cq * 1024));
-            load_to_lds16(vbase + page + v_src, lds_address(sV[st] + i * 4096 + cq * 1024));
+            load_to_lds16(k_source(id, cq), lds_address(sK[st] + i * 4096 + cq * 1024));
+            load_to_lds16(v_source(id, cq), lds_address(sV[st] + i * 4096 + cq * 1024));
         }
     };
     // V of slots past the sequence end may be anything (NaN included): overwrite with zeros.  Called
     // by all threads between two barriers, only for the block that holds the sequence end.
     auto zero_tail = [&](int blk, int st) {
 #pragma unroll
-        for (int u = 0; u < 16 / kWaves; ++u) {
+        for (int u = 0; u < kParts; ++u) {
             const int pc = u * kWaves + wave;
             const int i = pc >> 2, cq = pc & 3;
             const int v_d = cq * 32 + (lane >> 1);
@@ -170,11 +170,6 @@ __global__ __launch_bounds__(kThreads, 2 / NT) void prefill_kernel(PrefillLaunch
             *pv = vv;
         }
     };
-    // everything queued by this wavefront has landed; then everyone's has
-    auto land = [&]() {
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-        __builtin_amdgcn_s_barrier();
-    };
 
     // A-operand LDS offsets of this lane.
     //   K: M index n -> token sigma(n) of the 32-token tile (groups of four permuted 0,2,1,3)
@@ -186,190 +181,179 @@ __global__ __launch_bounds__(kThreads, 2 / NT) void prefill_kernel(PrefillLaunch
     const int ka_base = (tau >> 4) * 4096 + ka_slot * 64;
     //   V: M index n -> dim 32*dm + n; unit h (slots 8h..8h+7), swizzled by (d/8)%2
     const int va_base = n * 32 + ((h ^ ((n >> 3) & 1)) << 4);
+    // operand kk (dims 16kk .. 16kk+15) of the 32-token K tile at ktile
+    auto lds_k = [&](const char *ktile, int kk) {
+        const int unit = 2 * (kk & 1) + h;
+        return as_bf16x8(*reinterpret_cast<const u32x4 *>(ktile + ka_base + (kk >> 1) * 1024 + ((unit ^ ka_swz) << 4)));
+    };
+    // operand i (page i / 4 of the tile, dims 32 * (i % 4) ..) of the 32-token V tile at vtile
+    auto lds_v = [&](const char *vtile, int i) {
+        return as_bf16x8(*reinterpret_cast<const u32x4 *>(vtile + (i >> 2) * 4096 + (i & 3) * 1024 + va_base));
+    };
+    // tiles of step s (32 tokens): block s / 2, half s % 2
+    auto k_tile = [&](int s) { return sK[(s >> 1) % kStages] + (s & 1) * 8192; };
+    auto v_tile = [&](int s) { return sV[(s >> 1) % kStages] + (s & 1) * 8192; };
 
-    // S^T = K Q^T for one 32-token step (token tile mt of the block in kbuf) x this wavefront's 64 rows
-    auto scores = [&](Step &s, const char *kbuf, int mt) {
+    // S^T = K Q^T for one 32-token step, straight from LDS (prologue and fallback)
+    auto scores = [&](f32x16 &s, const char *ktile) {
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-            const int unit = 2 * (kk & 1) + h;
-            const bf16x8 ka = as_bf16x8(*reinterpret_cast<const u32x4 *>(
-                kbuf + mt * 8192 + ka_base + (kk >> 1) * 1024 + ((unit ^ ka_swz) << 4)));
+        for (int kk = 0; kk < 8; ++kk) s = mfma32(lds_k(ktile, kk), qf[kk], kk == 0 ? zero16() : s);
+    };
+    // lane-local score i of step st is token st*32 + (i/8)*16 + 8h + i%8.  Rows past the tile's end
+    // behave like its last row, so they never see the garbage slots behind the sequence.
+    const int pos = tl.prefix_len + tl.q_begin + min(tok, tl.n_q - 1);
+    auto mask_scores = [&](f32x16 &s, int st) {
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) s.t[nt] = mfma32(ka, qf[nt][kk], kk == 0 ? zero16() : s.t[nt]);
+        for (int i = 0; i < 16; ++i) {
+            const int t = st * 32 + (i >> 3) * 16 + 8 * h + (i & 7);
+            if (t > pos) s[i] = -INFINITY;
         }
     };
-    // lane-local score i of step st is token st*32 + (i/8)*16 + 8h + i%8
-    auto mask_scores = [&](Step &s, int st) {
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            // absolute position of this lane's row; rows past the tile's end behave like its last row,
-            // so they never see the garbage slots behind the sequence
-            const int pos = tl.prefix_len + tl.q_begin + min(tok[nt], tl.n_q - 1);
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int t = st * 32 + (i >> 3) * 16 + 8 * h + (i & 7);
-                if (t > pos) s.t[nt][i] = -INFINITY;
-            }
-        }
-    };
 
-    f32x16 o[NT][4];
-    float m_ref[NT], l_run[NT];
-    bf16x8 pb[NT][2];
-    // The O^T tiles are only ever touched by matrix instructions inside the loop.  Telling the
-    // register allocator that they belong in the accumulation registers (an empty asm with an "a"
-    // constraint) keeps it from parking them in the VALU registers and shuffling them back and
-    // forth around every softmax.
-    auto pin_accumulators = [&]() {
-#if HKV_PREFILL_NT == 2
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-            for (int dm = 0; dm < 4; ++dm) asm volatile("" : "+a"(o[nt][dm]));
-#endif
-    };
-    // O^T += V^T P^T for one step: pages 2*mt and 2*mt + 1 of the block in vbuf
-    auto accumulate = [&](const char *vbuf, int mt) {
+    f32x16 o[4];
+    float l_run = 0.f;
+    auto pack_probs = [&](u32x4 (&w)[2], const float (&p)[16]) {
 #pragma unroll
         for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
-            for (int dm = 0; dm < 4; ++dm) {
-                const bf16x8 va = as_bf16x8(
-                    *reinterpret_cast<const u32x4 *>(vbuf + (2 * mt + hf) * 4096 + dm * 1024 + va_base));
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt) o[nt][dm] = mfma32(va, pb[nt][hf], o[nt][dm]);
-            }
-    };
-    auto pack_probs = [&](int nt, const float (&p)[16]) {
-#pragma unroll
-        for (int hf = 0; hf < 2; ++hf) {
-            u32x4 w;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) w[j] = pack_bf16(p[hf * 8 + 2 * j], p[hf * 8 + 2 * j + 1]);
-            pb[nt][hf] = as_bf16x8(w);
-        }
+            for (int j = 0; j < 4; ++j) w[hf][j] = pack_bf16(p[hf * 8 + 2 * j], p[hf * 8 + 2 * j + 1]);
     };
 
     // =========================================================================================
     // main path: one reference value per row, pipelined steps
     // =========================================================================================
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-#pragma unroll
-        for (int dm = 0; dm < 4; ++dm) o[nt][dm] = zero16();
-        l_run[nt] = 0.f;
-    }
+    for (int dm = 0; dm < 4; ++dm) o[dm] = zero16();
     if (tid == 0) sBail = 0;
     fill_ids(0);
     __syncthreads();
-    issue_block(0, 0);
-    issue_block(1, 1);
-    issue_block(2, 2);
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(kLoadsPerBlock));  // blocks 0 and 1 are complete, block 2 may fly on
+    // Request schedule: K runs one block ahead of V (phase t multiplies K(t+1) but V(t-1)).  The
+    // prologue requests K(0); {K(1), V(0)}; {K(2), V(1)}; iteration j requests {K(j+3), V(j+2)}.
+    kwin = window(0);
+    vwin = kwin;
+#pragma unroll
+    for (int u = 0; u < kParts; ++u) issue_k_part(0, u);
+#pragma unroll
+    for (int u = 0; u < kParts; ++u) {
+        issue_k_part(1, u);
+        issue_v_part(0, u);
+    }
+#pragma unroll
+    for (int u = 0; u < kParts; ++u) {
+        issue_k_part(2, u);
+        issue_v_part(1, u);
+    }
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(kLoadsPerBlock));  // all but the last group: K(0), K(1), V(0) are here
     __builtin_amdgcn_s_barrier();
-    if (2 * KB > tl.kv_len) {  // the sequence ends inside block 0 or 1
-        if (KB > tl.kv_len) zero_tail(0, 0);
-        zero_tail(1, 1);
+    if (KB > tl.kv_len) {  // the sequence ends inside block 0
+        zero_tail(0, 0);
         __syncthreads();
     }
-    Step sa, sb;  // even and odd steps
-    scores(sa, sK[0], 0);
+    f32x16 sa, sb;  // scores of even and odd steps
+    scores(sa, k_tile(0));
     if (31 > wave_min_pos) mask_scores(sa, 0);
+    float m_ref;  // reference = maximum of the row's first 32 scores (token 0 is visible)
+    {
+        float mx = sa[0];
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {  // reference = maximum of the row's first 32 scores (token 0 is visible)
-        float mx = sa.t[nt][0];
-#pragma unroll
-        for (int i = 1; i < 16; ++i) mx = fmaxf(mx, sa.t[nt][i]);
-        m_ref[nt] = fmaxf(mx, __shfl_xor(mx, 32));
+        for (int i = 1; i < 16; ++i) mx = fmaxf(mx, sa[i]);
+        m_ref = fmaxf(mx, __shfl_xor(mx, 32));
     }
-    float mc[NT];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) mc[nt] = m_ref[nt] * c;
+    const float mc = m_ref * c;
 
-    // One pipeline phase = one 32-token step t, written in issue order and fenced so that the
-    // compiler keeps it:
-    //   1. request the eight V^T operands of step t from LDS;
-    //   2. eight matrix instructions S^T(t+1) = K(t+1) Q^T on the K operands already in registers,
-    //      each followed by the VALU work that turns two scores of step t into probabilities
-    //      (they run in the shadow of the matrix instruction; the V^T reads land meanwhile);
-    //   3. request the eight K operands of step t+2;
-    //   4. eight matrix instructions O^T += V^T(t) P^T(t) (the K reads land meanwhile).
-    static_assert(NT == 1, "the pipelined path is written for one row tile per wavefront");
-    bf16x8 kf[8];
-    auto load_k = [&](const char *ktile) {
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-            const int unit = 2 * (kk & 1) + h;
-            kf[kk] = as_bf16x8(*reinterpret_cast<const u32x4 *>(ktile + ka_base + (kk >> 1) * 1024 + ((unit ^ ka_swz) << 4)));
-        }
-    };
-    auto phase = [&](const f32x16 &sp, f32x16 &sn, const char *vtile, const char *knext) {
-        bf16x8 vf[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-            vf[i] = as_bf16x8(*reinterpret_cast<const u32x4 *>(vtile + (i >> 2) * 4096 + (i & 3) * 1024 + va_base));
-        __builtin_amdgcn_sched_barrier(0);
-        u32x4 w[2];
+    // One phase, written in issue order and fenced so that the compiler keeps it.  Operands live in
+    // two rings of four registers sets: each set is reloaded right after the matrix instruction
+    // that read it, four slots (eight matrix instructions) before its next use.
+    //   on entry  kf = operands 0-3 of K(t+1),  vf = operands 0-3 of V(t-1)
+    //   on exit   kf = operands 0-3 of K(t+2),  vf = operands 0-3 of V(t)
+    // dma_u >= 0: this wavefront's part dma_u of the requests {K(dma_k), V(dma_v)} goes out in slot 2.
+    bf16x8 kf[4], vf[4];
+    auto phase = [&](const f32x16 &sp, f32x16 &sn, const u32x4 (&wp)[2], u32x4 (&wn)[2], const char *k1,
+                     const char *k2, const char *v0, const char *v1, int dma_k, int dma_v, int dma_u) {
         float sum = 0.f;
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-            sn = mfma32(kf[kk], qf[0][kk], kk == 0 ? zero16() : sn);
-            const float p0 = fast_exp2(__builtin_fmaf(sp[2 * kk], c, -mc[0]));
-            const float p1 = fast_exp2(__builtin_fmaf(sp[2 * kk + 1], c, -mc[0]));
+        for (int i = 0; i < 8; ++i) {
+            // The empty asm statements are ordered like the fences; they pin each VALU group between
+            // the two matrix instructions it is meant to follow (its inputs become available at the
+            // first, its results are consumed at the second).
+            float x0 = sp[2 * i], x1 = sp[2 * i + 1];
+            sn = mfma32(kf[i & 3], qf[i], i == 0 ? zero16() : sn);
+            kf[i & 3] = i < 4 ? lds_k(k1, i + 4) : lds_k(k2, i - 4);
+            asm volatile("" : "+v"(x0));
+            float p0 = fast_exp2(__builtin_fmaf(x0, c, -mc));
+            asm volatile("" : "+v"(p0));
+            __builtin_amdgcn_sched_barrier(0);
+            o[i & 3] = mfma32(vf[i & 3], as_bf16x8(wp[i >> 2]), o[i & 3]);
+            vf[i & 3] = i < 4 ? lds_v(v0, i + 4) : lds_v(v1, i - 4);
+            asm volatile("" : "+v"(x1));
+            const float p1 = fast_exp2(__builtin_fmaf(x1, c, -mc));
             sum += p0 + p1;
-            w[kk >> 2][kk & 3] = pack_bf16(p0, p1);
+            uint32_t pk = pack_bf16(p0, p1);
+            asm volatile("" : "+v"(pk), "+v"(sum));
+            wn[i >> 2][i & 3] = pk;
+            if (i == 2 && dma_u >= 0) {
+                issue_k_part(dma_k, dma_u);
+                issue_v_part(dma_v, dma_u);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
-        l_run[0] += sum;
-        load_k(knext);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) o[0][i & 3] = mfma32(vf[i], as_bf16x8(w[i >> 2]), o[0][i & 3]);
-        __builtin_amdgcn_sched_barrier(0);
+        l_run += sum;
     };
 
-    // Block j = steps 2j and 2j+1, held in stage j % kStages.  At the top of iteration j block j+3
-    // is requested into the stage that block j-1 has just left; blocks j and j+1 are complete (the
-    // wait at the end of iteration j-1 allows only the youngest request to be outstanding), so a
-    // request has two iterations to land and one barrier per iteration suffices.
-    load_k(sK[0] + 8192);  // step 1
-    bool bail = false;
+    u32x4 wa[2], wb[2];  // probabilities (packed bf16) of even and odd steps
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) wb[hf] = u32x4{0u, 0u, 0u, 0u};  // "P(-1)" = 0: phase 0 adds nothing to O^T
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        kf[i] = lds_k(k_tile(1), i);
+        vf[i] = lds_v(v_tile(0), i);  // stands in for V(-1): finite data, multiplied by zeros
+    }
+    // Iteration j = phases 2j and 2j+1: reads K of blocks j, j+1, j+2 and V of blocks j-1, j.  The
+    // wait at its end allows only its own requests to be outstanding, so K(j+2) and V(j+1) are
+    // complete before iteration j+1 and a request has two iterations to land; K stage (j-1) % 4 and
+    // V stage (j-2) % 4 are free from the barrier at the end of iteration j-1 on, which is where
+    // iteration j's requests go.  One barrier per iteration.
     for (int j = 0; j < n_blk; ++j) {
-        const char *knext = sK[(j + 1) % kStages], *vcur = sV[j % kStages];
-        if ((j + 3) * 4 + 3 - id_base >= kIdSlots && (j + 3) * 4 <= last_page) {  // id window exhausted (rare)
-            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-            __syncthreads();
-            id_base = (j + 2) * 4;
-            fill_ids(id_base);
-            __syncthreads();
+        if (((j + 3) & 15) == 0) {
+            if ((j + 3) * 4 - id_base >= kIdSlots && (j + 3) * 4 <= last_page) {  // id slots exhausted (rare)
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+                __syncthreads();
+                id_base = (j + 3) * 4;  // a multiple of 64: the windows stay aligned
+                fill_ids(id_base);
+                __syncthreads();
+            }
+            kwin = window(j + 3);
         }
-        issue_block(j + 3, (j + 3) % kStages);
-        if (j > 0 && j * KB + 31 > wave_min_pos) mask_scores(sa, 2 * j);
-        phase(sa.t[0], sb.t[0], vcur, knext);  // step 2j; scores of 2j+1; K of 2j+2
-        if (j * KB + 63 > wave_min_pos) mask_scores(sb, 2 * j + 1);
-        phase(sb.t[0], sa.t[0], vcur + 8192, knext + 8192);  // step 2j+1; scores of 2j+2; K of 2j+3
-        // (after the last block these read stale stages: in bounds, never used)
-        // a row sum beyond 2^90 (or inf/NaN) means the reference was far too low: give up this path
-        const bool over = !(l_run[0] < kSumLimit);
-        if (__builtin_amdgcn_ballot_w64(over)) sBail = 1;
-        // blocks up to j+2 are complete (only the request of this iteration may be outstanding);
-        // stage j % kStages is no longer read; the flag is visible
+        if (((j + 2) & 15) == 0) vwin = window(j + 2);
+        const int t = 2 * j;
+        if (j > 0 && j * KB + 31 > wave_min_pos) mask_scores(sa, t);
+        phase(sa, sb, wb, wa, k_tile(t + 1), k_tile(t + 2), v_tile(t > 0 ? t - 1 : 0), v_tile(t), j + 3, j + 2, 0);
+        if (j * KB + 63 > wave_min_pos) mask_scores(sb, t + 1);
+        phase(sb, sa, wa, wb, k_tile(t + 2), k_tile(t + 3), v_tile(t), v_tile(t + 1), j + 3, j + 2, kParts - 1);
+        // (after the last block the K operands come from stale stages: in bounds, never used)
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(kLoadsPerBlock));
         __syncthreads();
-        if (sBail) {
-            bail = true;
-            break;
-        }
-        if ((j + 2) * KB + KB > tl.kv_len && (j + 2) * KB < tl.kv_len) {  // block j+2 holds the sequence end
-            zero_tail(j + 2, (j + 2) % kStages);
+        if ((j + 1) * KB + KB > tl.kv_len && (j + 1) * KB < tl.kv_len) {  // V(j+1) holds the sequence end
+            zero_tail(j + 1, (j + 1) % kStages);
             __syncthreads();
+        }
+    }
+    // drain: O^T += V^T P^T of the last step (vf holds its operands 0-3, wb its probabilities)
+    {
+        const char *vl = v_tile(2 * n_blk - 1);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            o[i & 3] = mfma32(vf[i & 3], as_bf16x8(wb[i >> 2]), o[i & 3]);
+            if (i < 4) vf[i & 3] = lds_v(vl, i + 4);
         }
     }
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // nothing of this path is in flight any more
+    // A row sum beyond 2^90, inf or NaN (all of them sticky) means that the reference was far too low
+    // for some row: the whole workgroup then repeats its tile with the running-maximum loop.
+    if (__builtin_amdgcn_ballot_w64(!(l_run < kSumLimit))) sBail = 1;
     __syncthreads();
-    float m_fin[NT];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) m_fin[nt] = m_ref[nt];
+    const bool bail = sBail != 0;
+    float m_fin = m_ref;
 
     // =========================================================================================
     // fallback: classic online softmax with a running maximum, one 64-token block at a time.
@@ -377,14 +361,10 @@ __global__ __launch_bounds__(kThreads, 2 / NT) void prefill_kernel(PrefillLaunch
     // allows; always correct, not tuned.
     // =========================================================================================
     if (bail) {
-        float m_run[NT];
+        float m_run = -INFINITY;
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-#pragma unroll
-            for (int dm = 0; dm < 4; ++dm) o[nt][dm] = zero16();
-            m_run[nt] = -INFINITY;
-            l_run[nt] = 0.f;
-        }
+        for (int dm = 0; dm < 4; ++dm) o[dm] = zero16();
+        l_run = 0.f;
         __syncthreads();
         id_base = 0;
         fill_ids(0);
@@ -396,66 +376,63 @@ __global__ __launch_bounds__(kThreads, 2 / NT) void prefill_kernel(PrefillLaunch
                 __syncthreads();
             }
             issue_block(j, 0);
-            land();
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+            __syncthreads();
             if (j * KB + KB > tl.kv_len) {
                 zero_tail(j, 0);
                 __syncthreads();
             }
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt) {
-                Step s;
-                scores(s, sK[0], mt);
+                f32x16 s;
+                scores(s, sK[0] + mt * 8192);
                 if (j * KB + mt * 32 + 31 > wave_min_pos) mask_scores(s, 2 * j + mt);
+                float mx = s[0];
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    float mx = s.t[nt][0];
+                for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[i]);
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                const float m_new = fmaxf(m_run, mx);
+                const float mcn = m_new * c;
+                const float alpha = fast_exp2(m_run * c - mcn);
+                float p[16];
+                float sum = 0.f;
 #pragma unroll
-                    for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s.t[nt][i]);
-                    mx = fmaxf(mx, __shfl_xor(mx, 32));
-                    const float m_new = fmaxf(m_run[nt], mx);
-                    const float mcn = m_new * c;
-                    const float alpha = fast_exp2(m_run[nt] * c - mcn);
-                    float p[16];
-                    float sum = 0.f;
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        p[i] = fast_exp2(__builtin_fmaf(s.t[nt][i], c, -mcn));
-                        sum += p[i];
-                    }
-                    pack_probs(nt, p);
-                    l_run[nt] = l_run[nt] * alpha + sum;
-                    m_run[nt] = m_new;
-#pragma unroll
-                    for (int dm = 0; dm < 4; ++dm)
-#pragma unroll
-                        for (int i = 0; i < 16; ++i) o[nt][dm][i] *= alpha;
+                for (int i = 0; i < 16; ++i) {
+                    p[i] = fast_exp2(__builtin_fmaf(s[i], c, -mcn));
+                    sum += p[i];
                 }
-                accumulate(sV[0], mt);
+                u32x4 w[2];
+                pack_probs(w, p);
+                l_run = l_run * alpha + sum;
+                m_run = m_new;
+#pragma unroll
+                for (int dm = 0; dm < 4; ++dm)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) o[dm][i] *= alpha;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) o[i & 3] = mfma32(lds_v(sV[0] + mt * 8192, i), as_bf16x8(w[i >> 2]), o[i & 3]);
             }
             __syncthreads();
         }
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) m_fin[nt] = m_run[nt];
+        m_fin = m_run;
     }
 
     // ---- normalise and store; lane (n, h) holds dims 32*dm + 8*(i/4) + 4*h + i%4 of its row
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        const float l_tot = l_run[nt] + __shfl_xor(l_run[nt], 32);
-        if (tok[nt] >= tl.n_q) continue;
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    if (tok < tl.n_q) {
         const float inv = 1.0f / l_tot;
-        const size_t row = (size_t)(tl.q_row0 + tok[nt]) * Hq + head[nt];
+        const size_t row = (size_t)(tl.q_row0 + tok) * Hq + head;
         uint16_t *op = static_cast<uint16_t *>(a.out) + row * kHeadDim;
 #pragma unroll
         for (int dm = 0; dm < 4; ++dm)
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
                 u32x2 w;
-                w[0] = pack_bf16(o[nt][dm][4 * q4] * inv, o[nt][dm][4 * q4 + 1] * inv);
-                w[1] = pack_bf16(o[nt][dm][4 * q4 + 2] * inv, o[nt][dm][4 * q4 + 3] * inv);
+                w[0] = pack_bf16(o[dm][4 * q4] * inv, o[dm][4 * q4 + 1] * inv);
+                w[1] = pack_bf16(o[dm][4 * q4 + 2] * inv, o[dm][4 * q4 + 3] * inv);
                 *reinterpret_cast<u32x2 *>(op + 32 * dm + 8 * q4 + 4 * h) = w;
             }
-        if (a.lse_out && h == 0) a.lse_out[row] = (m_fin[nt] * c + fast_log2(l_tot)) * kLn2;
+        if (a.lse_out && h == 0) a.lse_out[row] = (m_fin * c + fast_log2(l_tot)) * kLn2;
     }
 }
 
