@@ -284,6 +284,13 @@ def main() -> int:
                          "no attention-kernel number exists to compare with",
     }
     result["extra"] = {"c2_cache_resident_GBps": round(uniq / sec_hot / 1e9, 2)}
+    # what a kernel that only reads the same number of bytes reaches, same rotation, same launch cadence
+    bufs = [torch.zeros(uniq // 4, dtype=torch.int32, device="cuda") for _ in range(args.pools)]
+    read_gbps = hkv.hkv_hbm_read_probe(bufs, uniq, 100)
+    del bufs
+    torch.cuda.empty_cache()
+    result["roofline"]["plain_read_same_bytes_GBps"] = round(read_gbps, 1)
+    result["roofline"]["frac_of_plain_read"] = round(achieved / read_gbps, 4)
 
     if not args.no_extras:
         w3 = wl.config3()
@@ -302,6 +309,14 @@ def main() -> int:
             "kernel_ms": round(k4, 4), "useful_TFLOPs": round(tflops, 2),
             "mfma_bf16_frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4), "new_tokens": int(w4.total_q()),
             "useful_flop": int(w4.useful_flop()), "tiles": t4}
+        # matrix-core ceiling with nothing else running: zero operands (nominal clock) and random ones
+        # (the clock settles under the power limit), two wavefronts per SIMD as in the prefill kernel
+        tf0, ghz0 = hkv.hkv_mfma_probe(100000, False, 2)
+        tf1, ghz1 = hkv.hkv_mfma_probe(100000, True, 2)
+        result["extra"]["mfma_probe_bf16"] = {
+            "zero_operands_TFLOPs": round(tf0, 1), "zero_operands_clock_GHz": round(ghz0, 3),
+            "random_operands_TFLOPs": round(tf1, 1), "random_operands_clock_GHz": round(ghz1, 3)}
+        result["extra"]["c4_prefix_hit_prefill"]["frac_of_random_operand_probe"] = round(tflops / tf1, 4)
         log("c4 done")
         result["extra"]["kv_pool_write_src_GBps"] = round(bench_pool_write(runtime, w, 20), 1)
     if args.c5:

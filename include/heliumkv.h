@@ -286,6 +286,29 @@ int attn_prefill_with_prefix(hkv_pool *pool, const void *q, const int32_t *cu_q,
                              void *stream);
 size_t attn_prefill_workspace_bytes(int32_t total_q, int32_t num_q_heads);
 
+/* ------------------------------------------------------------------------------------------
+ * Diagnostics (no part of the attention path; for callers that report a roofline).
+ * Runs a register-only stream of bf16 matrix-core instructions (v_mfma_f32_32x32x16_bf16, the
+ * one the prefill kernel is built on) on every compute unit of the current device,
+ * waves_per_simd in {1, 2} wavefronts per SIMD, iters x 4 instructions per wavefront, with
+ * all-zero operands (random_operands = 0) or random ones (1: realistic switching activity, the
+ * clock settles under the power limit).  Blocks until done.  tflops (host): dense bf16 TFLOP/s by
+ * HIP event time; clock_ghz (host): core clock during the run, from the core-cycle and 100 MHz
+ * counters read inside the kernel.  Allocates and frees a few KiB of device memory.
+ * EINVAL (null pointers, iters < 1, waves_per_simd not 1 or 2), EHIP. */
+int hkv_mfma_probe(int32_t iters, int32_t random_operands, int32_t waves_per_simd, float *tflops,
+                   float *clock_ghz, void *stream);
+
+/* Plain streaming-read ceiling: a kernel that does nothing but read `bytes` bytes (a multiple of
+ * 16; 16-byte loads, four in flight per lane, 8 workgroups of 256 threads per compute unit) is
+ * launched `reps` times back to back, launch i over bufs[i % n_buf], so that with buffers larger
+ * in sum than the last-level cache every launch reads HBM, exactly as a decode step over rotating
+ * pools does.  bufs: host array of n_buf device pointers, 16-byte aligned, owned by the caller.
+ * gbps (host): bytes * reps / time between two HIP events around the launches (launch gaps
+ * included, as in a real step).  Blocks until done.  EINVAL, EHIP. */
+int hkv_hbm_read_probe(const void *const *bufs, int32_t n_buf, size_t bytes, int32_t reps, float *gbps,
+                       void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -823,3 +823,32 @@ extern "C" size_t attn_prefill_workspace_bytes(int32_t total_q, int32_t num_q_he
     (void)num_q_heads;
     return 0;
 }
+
+// ---------------------------------------------------------------------------------------------
+// diagnostics
+extern "C" int hkv_mfma_probe(int32_t iters, int32_t random_operands, int32_t waves_per_simd, float *tflops,
+                              float *clock_ghz, void *stream) {
+    if (!tflops || !clock_ghz) return fail(HKV_EINVAL, "hkv_mfma_probe: null output pointer");
+    if (iters < 1 || (waves_per_simd != 1 && waves_per_simd != 2))
+        return fail(HKV_EINVAL, "hkv_mfma_probe: iters %d, waves_per_simd %d", iters, waves_per_simd);
+    int dev = 0, n_cu = 0;
+    HKV_HIP(hipGetDevice(&dev));
+    HKV_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+    HKV_HIP(run_mfma_probe(n_cu, 4 * waves_per_simd, iters, random_operands != 0, tflops, clock_ghz,
+                           static_cast<hipStream_t>(stream)));
+    return HKV_OK;
+}
+
+extern "C" int hkv_hbm_read_probe(const void *const *bufs, int32_t n_buf, size_t bytes, int32_t reps, float *gbps,
+                                  void *stream) {
+    if (!bufs || !gbps || n_buf < 1 || reps < 1 || bytes < 16 || bytes % 16)
+        return fail(HKV_EINVAL, "hkv_hbm_read_probe: bad argument (n_buf %d, reps %d, bytes %zu)", n_buf, reps, bytes);
+    for (int i = 0; i < n_buf; ++i)
+        if (!bufs[i] || (reinterpret_cast<uintptr_t>(bufs[i]) & 15))
+            return fail(HKV_EINVAL, "hkv_hbm_read_probe: buffer %d is null or not 16-byte aligned", i);
+    int dev = 0, n_cu = 0;
+    HKV_HIP(hipGetDevice(&dev));
+    HKV_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+    HKV_HIP(run_read_probe(bufs, n_buf, bytes, reps, n_cu, gbps, static_cast<hipStream_t>(stream)));
+    return HKV_OK;
+}

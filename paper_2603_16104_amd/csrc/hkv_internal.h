@@ -105,4 +105,9 @@ hipError_t launch_lse_merge_dense(const float *o_parts, const float *lse_parts, 
                                   int32_t rows_per_count, int32_t max_parts, int32_t n_rows, void *out,
                                   int32_t out_dtype, float *lse_out, hipStream_t s);
 
+hipError_t run_read_probe(const void *const *bufs, int n_buf, size_t bytes, int reps, int n_cu, float *gbps,
+                          hipStream_t s);
+hipError_t run_mfma_probe(int n_cu, int waves, int iters, int random_operands, float *tflops, float *clock_ghz,
+                          hipStream_t s);
+
 }  // namespace hkv

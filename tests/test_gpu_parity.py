@@ -361,3 +361,21 @@ def test_prefill_late_dominant_key(gpu, oracle, beta):
     assert np.abs(got_l - exp_l).max() <= 2e-3 + 1e-6 * np.abs(exp_l).max()
     vb = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(v))
     assert np.abs(got_o[hot:, 0] - vb[hot, 0]).max() <= 2e-2
+
+
+@pytest.mark.gpu
+def test_diagnostic_probes(gpu):
+    """The ceiling probes run and report figures of the right order (no attention result involved)."""
+    import torch
+    from paper_2603_16104_amd import binding as hkv
+    tf0, ghz0 = hkv.hkv_mfma_probe(20000, False, 2)
+    tf1, ghz1 = hkv.hkv_mfma_probe(20000, True, 2)
+    assert 500.0 < tf1 <= tf0 * 1.05 < 2700.0          # never above the 2.5 PFLOP/s data-sheet peak (+ timer slack)
+    assert 0.5 < ghz1 <= ghz0 * 1.05 < 2.6
+    bufs = [torch.zeros(1 << 24, dtype=torch.int32, device="cuda") for _ in range(4)]   # 4 x 64 MiB
+    gbps = hkv.hkv_hbm_read_probe(bufs, 1 << 26, 40)
+    assert 1000.0 < gbps < 8000.0 * 1.6                # cache hits may lift it above the HBM peak
+    with pytest.raises(hkv.HkvError):
+        hkv.hkv_mfma_probe(0, False, 2)
+    with pytest.raises(hkv.HkvError):
+        hkv.hkv_hbm_read_probe(bufs, 24, 1)
