@@ -287,6 +287,61 @@ int attn_prefill_with_prefix(hkv_pool *pool, const void *q, const int32_t *cu_q,
 size_t attn_prefill_workspace_bytes(int32_t total_q, int32_t num_q_heads);
 
 /* ------------------------------------------------------------------------------------------
+ * Scheduling layer (host only, integers only): templated radix tree, token-step cost model and
+ * cache-aware scheduling (Section 5: "Modeling Prompt Structure with a Templated Radix Tree",
+ * "Scheduling Problem Formulation" with its token-usage and precedence-delay equations, the
+ * scheduling algorithm; appendix "Templated Radix Tree Construction").
+ *
+ * A call's prefix template is a list of int32 symbols: s >= 0 is a static token id, s < 0 stands
+ * for the output of call -(s + 1) (a placeholder; it makes this call depend on that one).
+ * omega(v) of a tree node = static tokens of its segment + len_out of every placeholder in it;
+ * the root and the leaves (one per call, child of the node where its template ends) weigh 0.
+ * Workers are identical, alpha = 1 / capacity; every time below is an integer scaled by the
+ * capacity M:  U = len_out * u_p + len_out (len_out + 1) / 2  (= M u),  delay = M * len_out  (= M d).
+ * A worker runs its calls one after another in schedule order.
+ * Nodes are numbered in depth-first preorder from the root (node 0), children in order of
+ * creation (a node created by a split takes the place of the node it was split from); this makes
+ * `parent` a valid parent-first forest for the attention entry points, with omega as n_tokens. */
+typedef struct hkv_trt hkv_trt;
+
+/* Builds the tree: calls are inserted in topological order of their dependencies (smallest index
+ * first among the ready ones) by radix-tree insertion with node splitting.
+ * tmpl_indptr [n_calls+1], tmpl_syms, len_out [n_calls], worker [n_calls] (NULL: all on worker 0):
+ * host.  ETREE if a placeholder names a missing call, the call itself, or the dependencies form a
+ * cycle; ERANGE for negative len_out / worker; EINVAL; ENOMEM. */
+int trt_build(const int32_t *tmpl_indptr, const int32_t *tmpl_syms, const int32_t *len_out,
+              const int32_t *worker, int32_t n_calls, hkv_trt **out);
+int trt_destroy(hkv_trt *tree);
+int32_t trt_num_nodes(const hkv_trt *tree);
+int32_t trt_num_syms(const hkv_trt *tree);  /* total length of all node segments */
+int32_t trt_num_calls(const hkv_trt *tree);
+/* Copies the flat tree out (host arrays; any pointer may be NULL): parent, omega (int64), the
+ * call of a leaf (-1 for other nodes), each node's segment as [seg_begin, seg_begin + seg_len)
+ * of syms, and the leaf of every call. */
+int trt_nodes(const hkv_trt *tree, int32_t *parent, int64_t *weight, int32_t *call, int32_t *seg_begin,
+              int32_t *seg_len, int32_t *syms, int32_t *leaf_of_call);
+/* u_p of a sequence of calls run back to back on one worker: u_p[0] sums omega over path(root,
+ * leaf of calls[0]], u_p[j] over the path from the lowest common ancestor of the leaves of
+ * calls[j-1] and calls[j] (exclusive) down to the latter.  ERANGE for a call index out of range. */
+int trt_prefill_usage(const hkv_trt *tree, const int32_t *calls, int32_t n, int64_t *u_p);
+/* Start B and completion C of every call (indexed by call, may be NULL) and the total token step
+ * T = max C under schedule sigma (worker i runs sigma[sigma_indptr[i] .. sigma_indptr[i+1])):
+ * B = max(previous completion on the worker, C' + capacity * len_out' over the dependencies),
+ * C = B + U.  ERANGE if sigma is no partition of the calls, ETREE if it contradicts the
+ * dependencies (a worker's next call waits for one that can never run). */
+int trt_evaluate(const hkv_trt *tree, const int32_t *sigma_indptr, const int32_t *sigma, int32_t n_workers,
+                 int64_t capacity, int64_t *B, int64_t *C, int64_t *T);
+/* Cache-aware scheduling: depth-first descent over the tree, at every node taking the remaining
+ * children by greatest dependency depth (longest chain of dependents below any unscheduled leaf of
+ * the subtree), then earliest schedulable step, then node number; a leaf is placed when its
+ * dependencies are scheduled and it opens no idle gap on its worker; when a whole pass places
+ * nothing more, a forced pass places the ready call with the earliest start.  Calls stay on the
+ * worker given at trt_build.  Outputs: sigma_indptr [n_workers+1], sigma [n_calls], B, C (may be
+ * NULL), T.  ERANGE if a call's worker is >= n_workers. */
+int trt_schedule(const hkv_trt *tree, int32_t n_workers, int64_t capacity, int32_t *sigma_indptr,
+                 int32_t *sigma, int64_t *B, int64_t *C, int64_t *T);
+
+/* ------------------------------------------------------------------------------------------
  * Diagnostics (no part of the attention path; for callers that report a roofline).
  * Runs a register-only stream of bf16 matrix-core instructions (v_mfma_f32_32x32x16_bf16, the
  * one the prefill kernel is built on) on every compute unit of the current device,

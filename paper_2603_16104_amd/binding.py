@@ -32,6 +32,8 @@ EXPORTS = [
     "attn_decode_prefix_tree", "attn_decode_workspace_bytes", "hkv_prefill_plan_create", "hkv_prefill_plan_destroy",
     "hkv_prefill_plan_num_tiles", "hkv_prefill_plan_tiles", "attn_prefill_plan_run", "attn_prefill_with_prefix",
     "attn_prefill_workspace_bytes", "hkv_mfma_probe", "hkv_hbm_read_probe",
+    "trt_build", "trt_destroy", "trt_num_nodes", "trt_num_syms", "trt_num_calls", "trt_nodes", "trt_prefill_usage",
+    "trt_evaluate", "trt_schedule",
 ]
 
 
@@ -319,3 +321,73 @@ def hkv_hbm_read_probe(bufs, nbytes: int, reps: int, stream=None) -> float:
     _check(lib().hkv_hbm_read_probe(ptrs, C.c_int32(len(bufs)), C.c_size_t(nbytes), C.c_int32(reps), C.byref(gbps),
                                     _stream(stream)))
     return float(gbps.value)
+
+
+# ---------------------------------------------------------------------------------------------
+# scheduling layer (host only)
+
+
+def _host_i64(n: int) -> np.ndarray:
+    return np.zeros(max(n, 0), dtype=np.int64)
+
+
+def trt_build(templates, len_out, worker=None) -> C.c_void_p:
+    """templates: list of int sequences (symbols); returns the tree handle."""
+    indptr = np.zeros(len(templates) + 1, dtype=np.int32)
+    for i, t in enumerate(templates):
+        indptr[i + 1] = indptr[i] + len(t)
+    syms = _host_i32([s for t in templates for s in t])
+    lo = _host_i32(len_out)
+    wk = _host_i32(worker) if worker is not None else None
+    out = C.c_void_p()
+    _check(lib().trt_build(_hp(indptr), _hp(syms), _hp(lo), _hp(wk) if wk is not None else None,
+                           C.c_int32(len(templates)), C.byref(out)))
+    return out
+
+
+def trt_destroy(tree) -> None:
+    _check(lib().trt_destroy(tree))
+
+
+def trt_nodes(tree) -> dict:
+    n, ns, nc = (_check(lib().trt_num_nodes(tree)), _check(lib().trt_num_syms(tree)), _check(lib().trt_num_calls(tree)))
+    parent, call, sb, sl = (np.zeros(n, dtype=np.int32) for _ in range(4))
+    weight = _host_i64(n)
+    syms, leaf = np.zeros(ns, dtype=np.int32), np.zeros(nc, dtype=np.int32)
+    _check(lib().trt_nodes(tree, _hp(parent), _hp(weight), _hp(call), _hp(sb), _hp(sl), _hp(syms), _hp(leaf)))
+    return {"parent": parent, "weight": weight, "call": call, "seg_begin": sb, "seg_len": sl, "syms": syms,
+            "leaf_of_call": leaf}
+
+
+def trt_prefill_usage(tree, calls) -> np.ndarray:
+    calls = _host_i32(calls)
+    u = _host_i64(len(calls))
+    _check(lib().trt_prefill_usage(tree, _hp(calls), C.c_int32(len(calls)), _hp(u)))
+    return u
+
+
+def _sigma_arrays(sigma):
+    indptr = np.zeros(len(sigma) + 1, dtype=np.int32)
+    for i, s in enumerate(sigma):
+        indptr[i + 1] = indptr[i] + len(s)
+    return indptr, _host_i32([c for s in sigma for c in s])
+
+
+def trt_evaluate(tree, sigma, capacity: int):
+    """sigma: one list of calls per worker.  Returns (B, C, T)."""
+    nc = _check(lib().trt_num_calls(tree))
+    indptr, flat = _sigma_arrays(sigma)
+    B, Cc, T = _host_i64(nc), _host_i64(nc), C.c_int64(0)
+    _check(lib().trt_evaluate(tree, _hp(indptr), _hp(flat), C.c_int32(len(sigma)), C.c_int64(capacity), _hp(B),
+                              _hp(Cc), C.byref(T)))
+    return B, Cc, int(T.value)
+
+
+def trt_schedule(tree, n_workers: int, capacity: int):
+    """Returns (sigma as a list of lists, B, C, T)."""
+    nc = _check(lib().trt_num_calls(tree))
+    indptr, flat = np.zeros(n_workers + 1, dtype=np.int32), np.zeros(nc, dtype=np.int32)
+    B, Cc, T = _host_i64(nc), _host_i64(nc), C.c_int64(0)
+    _check(lib().trt_schedule(tree, C.c_int32(n_workers), C.c_int64(capacity), _hp(indptr), _hp(flat), _hp(B), _hp(Cc),
+                              C.byref(T)))
+    return [flat[indptr[i]:indptr[i + 1]].tolist() for i in range(n_workers)], B, Cc, int(T.value)

@@ -19,9 +19,11 @@ using namespace hkv;
 // ---------------------------------------------------------------------------------------------
 // errors
 namespace {
-
 thread_local std::string g_err;
+}
 
+namespace hkv {
+// records the thread-local message and returns the code (shared with the other host files)
 int fail(int code, const char *fmt, ...) {
     char buf[512];
     va_list ap;
@@ -31,6 +33,9 @@ int fail(int code, const char *fmt, ...) {
     g_err = buf;
     return code;
 }
+}  // namespace hkv
+
+namespace {
 
 int fail_hip(hipError_t e, const char *what) {
     return fail(HKV_EHIP, "%s: %s", what, hipGetErrorString(e));

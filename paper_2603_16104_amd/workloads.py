@@ -339,3 +339,107 @@ def all_configs():
     c1p, c1d = config1()
     return {"c1_prefill": c1p, "c1_decode": c1d, "c2": config2(), "c3": config3(),
             "c4": config4(), "c5": config5()}
+
+
+# ---------------------------------------------------------------------------------------------
+# Workflow shapes for the scheduling layer: lists of LLM calls with prefix templates.
+# A template is a list of int symbols: s >= 0 static token id, s < 0 the output of call -(s+1).
+# Only the structure of the paper's primitive workflows is used (Section 7, "Workloads": map-reduce,
+# multi-agent debate, reflection); token ids and lengths are synthetic.
+
+
+class Workflow:
+    def __init__(self, name: str):
+        self.name = name
+        self.templates: List[List[int]] = []
+        self.len_out: List[int] = []
+        self.worker: List[int] = []
+        self._next_token = 0
+
+    def fresh_tokens(self, n: int) -> List[int]:
+        """n static token ids that occur nowhere else (so that only intended prefixes are shared)."""
+        t = list(range(self._next_token, self._next_token + n))
+        self._next_token += n
+        return t
+
+    def add(self, template: List[int], len_out: int, worker: int = 0) -> int:
+        self.templates.append(list(template))
+        self.len_out.append(int(len_out))
+        self.worker.append(int(worker))
+        return len(self.templates) - 1
+
+    @staticmethod
+    def out(call: int) -> int:
+        return -(call + 1)
+
+    @property
+    def n_calls(self) -> int:
+        return len(self.templates)
+
+
+def workflow_map_reduce(n_queries: int = 4, n_mappers: int = 3, sys_len: int = 64, ctx_len: int = 128,
+                        len_out: int = 32, n_workers: int = 1) -> Workflow:
+    """Per query: n_mappers calls [mapper system prompt | query context], one reducer
+    [reducer system prompt | query context | all mapper outputs]."""
+    w = Workflow("map_reduce")
+    map_sys = [w.fresh_tokens(sys_len) for _ in range(n_mappers)]
+    red_sys = w.fresh_tokens(sys_len)
+    for q in range(n_queries):
+        ctx = w.fresh_tokens(ctx_len)
+        wk = q % n_workers
+        ms = [w.add(map_sys[m] + ctx, len_out, wk) for m in range(n_mappers)]
+        w.add(red_sys + ctx + [Workflow.out(m) for m in ms], len_out, wk)
+    return w
+
+
+def workflow_debate(n_queries: int = 3, n_agents: int = 3, rounds: int = 2, sys_len: int = 64, q_len: int = 48,
+                    len_out: int = 32, n_workers: int = 1) -> Workflow:
+    """Round 1: every agent answers [agent system prompt | question]; every later round appends the
+    answers of all agents in all earlier rounds."""
+    w = Workflow("debate")
+    sys_p = [w.fresh_tokens(sys_len) for _ in range(n_agents)]
+    for q in range(n_queries):
+        question = w.fresh_tokens(q_len)
+        wk = q % n_workers
+        history: List[int] = []               # answers of all earlier rounds, in order
+        for _ in range(rounds):
+            cur = [w.add(sys_p[a] + question + [Workflow.out(c) for c in history], len_out, wk)
+                   for a in range(n_agents)]
+            history = history + cur
+    return w
+
+
+def workflow_reflect(n_queries: int = 4, sys_len: int = 64, q_len: int = 48, len_out: int = 32,
+                     n_workers: int = 1) -> Workflow:
+    """answer -> critique of the answer -> revised answer, per query; the three roles have their own
+    system prompts."""
+    w = Workflow("reflect")
+    s_ans, s_crit, s_rev = (w.fresh_tokens(sys_len) for _ in range(3))
+    for q in range(n_queries):
+        question = w.fresh_tokens(q_len)
+        wk = q % n_workers
+        a = w.add(s_ans + question, len_out, wk)
+        c = w.add(s_crit + question + [Workflow.out(a)], len_out, wk)
+        w.add(s_rev + question + [Workflow.out(a), Workflow.out(c)], len_out, wk)
+    return w
+
+
+def random_workflow(seed: int, n_calls: int = 12, vocab: int = 6, max_len: int = 10, max_out: int = 9,
+                    n_workers: int = 1, p_placeholder: float = 0.2) -> Workflow:
+    """Small random templates over a tiny vocabulary (many accidental shared prefixes, splits at every
+    depth), placeholders only to earlier calls (acyclic by construction, then shuffled)."""
+    rng = np.random.default_rng([seed, 13])
+    w = Workflow(f"random_{seed}")
+    perm = rng.permutation(n_calls)           # call i of the build order gets index perm[i]
+    tmpl = [None] * n_calls
+    for i in range(n_calls):
+        t = []
+        for _ in range(int(rng.integers(0, max_len + 1))):
+            if i > 0 and rng.random() < p_placeholder:
+                t.append(-(int(perm[int(rng.integers(0, i))]) + 1))
+            else:
+                t.append(int(rng.integers(0, vocab)))
+        tmpl[int(perm[i])] = t
+    for i in range(n_calls):
+        w.add(tmpl[i], int(rng.integers(0, max_out + 1)), int(rng.integers(0, n_workers)))
+    return w
