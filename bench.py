@@ -144,6 +144,50 @@ def bench_pool_write(runtime, w, steps: int):
     return src_bytes / sec / 1e9
 
 
+def bench_workflow(runtime, hkv, wl, shape: str):
+    """Call orders of one worker compared on the cost model (prefill usage, total token step) and on
+    the GPU (kv_pool_write of the new tokens + suffix-only prefill attention per call)."""
+    import torch
+    if shape == "map_reduce":
+        wf = wl.workflow_map_reduce(n_queries=6, n_mappers=4, sys_len=2048, ctx_len=8192, len_out=256)
+        per_query = 5
+    elif shape == "debate":
+        wf = wl.workflow_debate(n_queries=6, n_agents=3, rounds=3, sys_len=4096, q_len=2048, len_out=512)
+        per_query = 9
+    else:
+        wf = wl.workflow_reflect(n_queries=12, sys_len=4096, q_len=4096, len_out=512)
+        per_query = 3
+    r = runtime.WorkflowRunner(wf)
+    capacity = 1 << 16
+    n = wf.n_calls
+    helium = hkv.trt_schedule(r.tree, 1, capacity)[0][0]
+    orders = {
+        "cache_aware_schedule": (helium, True),
+        "query_by_query": (list(range(n)), True),
+        "operator_by_operator": ([q * per_query + o for o in range(per_query) for q in range(n // per_query)], True),
+        "no_prefix_reuse": (helium, False),
+    }
+    res = {"workflow": wf.name, "calls": n, "tree_nodes": int(len(r.nodes["parent"])), "capacity_M": capacity,
+           "layer": "32 q / 8 kv heads, head_dim 128, bf16", "orders": {}}
+    for name, (seq, cache) in orders.items():
+        usage = r.prepare(seq, cache)
+        T = hkv.trt_evaluate(r.tree, [seq], capacity)[2] if cache else None
+        r.run()
+        torch.cuda.synchronize()
+        ms = []
+        for _ in range(3):
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            ev0.record()
+            r.run()
+            ev1.record()
+            torch.cuda.synchronize()
+            ms.append(ev0.elapsed_time(ev1))
+        res["orders"][name] = {"prefill_usage_tokens": int(sum(usage)),
+                               "total_token_step_times_M": T, "gpu_ms": round(min(ms), 3)}
+    r.close()
+    return res
+
+
 def cpu_baseline_decode(w, budget_s: float = 20.0):
     """The fp64 oracle as it stands on the host cores: whole workload, repeated within the budget."""
     from oracle import oracle as orc
@@ -183,6 +227,9 @@ def main() -> int:
     ap.add_argument("--profile-workload", choices=["c3", "c4", "c5"], default=None,
                     help="run only this context workload for a few steps and print its figures (for rocprofv3 runs "
                          "of the other kernels; not the headline line)")
+    ap.add_argument("--workflow", choices=["map_reduce", "debate", "reflect"], default=None,
+                    help="scheduling-layer experiment: run the prefill side of a synthetic workflow on one worker "
+                         "under several call orders and print token steps beside measured GPU time (not the headline line)")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
                     help="also run a plain elementwise copy kernel over this many MiB three times (a known-size "
                          "kernel to calibrate rocprofv3's FETCH_SIZE / WRITE_SIZE counters against)")
@@ -209,6 +256,10 @@ def main() -> int:
         log(f"copy probe: 3 x elementwise add over {n * 4} bytes read + {n * 4} bytes written")
         del src, dst
         torch.cuda.empty_cache()
+
+    if args.workflow:
+        print(json.dumps(bench_workflow(runtime, hkv, wl, args.workflow)), flush=True)
+        return 0
 
     if args.profile_workload:
         name = args.profile_workload

@@ -91,12 +91,16 @@ struct hkv_pool {
     hkv_pool_desc d{};
     std::vector<int32_t> refcnt;
     std::deque<int32_t> free_list;
-    // staging of page ids for kv_pool_write
+    // Staging of page ids for kv_pool_write: a ring of slots (pinned host + device, one allocation
+    // each), so that back-to-back writes on a stream do not wait for one another; a slot is reused
+    // only after the event recorded behind its last write has completed.
     static constexpr int kMaxWritePages = 65536;
-    int32_t *h_ids = nullptr;  // pinned host
-    int32_t *d_ids = nullptr;  // device
-    hipEvent_t ids_free = nullptr;
-    bool ids_in_flight = false;
+    static constexpr int kWriteSlots = 8;
+    int32_t *h_ids = nullptr;  // pinned host, kWriteSlots x kMaxWritePages
+    int32_t *d_ids = nullptr;  // device, same shape
+    hipEvent_t slot_free[kWriteSlots] = {};
+    bool slot_in_flight[kWriteSlots] = {};
+    int next_slot = 0;
     hkv_decode_plan *cached_decode = nullptr;
     hkv_prefill_plan *cached_prefill = nullptr;
 };
@@ -148,10 +152,11 @@ extern "C" int kv_pool_destroy(hkv_pool *pool) {
     if (!pool) return HKV_OK;
     if (pool->cached_decode) hkv_decode_plan_destroy(pool->cached_decode);
     if (pool->cached_prefill) hkv_prefill_plan_destroy(pool->cached_prefill);
-    if (pool->ids_free) {
-        (void)hipEventSynchronize(pool->ids_free);
-        (void)hipEventDestroy(pool->ids_free);
-    }
+    for (hipEvent_t e : pool->slot_free)
+        if (e) {
+            (void)hipEventSynchronize(e);
+            (void)hipEventDestroy(e);
+        }
     if (pool->d_ids) (void)hipFree(pool->d_ids);
     if (pool->h_ids) (void)hipHostFree(pool->h_ids);
     delete pool;
@@ -237,18 +242,23 @@ extern "C" int kv_pool_write(hkv_pool *pool, const int32_t *page_ids, int32_t fi
                         (long long)i, pool->d.num_pages);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (!pool->h_ids) {
-        HKV_HIP(hipHostMalloc((void **)&pool->h_ids, sizeof(int32_t) * hkv_pool::kMaxWritePages, hipHostMallocDefault));
-        HKV_HIP(hipMalloc((void **)&pool->d_ids, sizeof(int32_t) * hkv_pool::kMaxWritePages));
-        HKV_HIP(hipEventCreateWithFlags(&pool->ids_free, hipEventDisableTiming));
+        const size_t bytes = sizeof(int32_t) * hkv_pool::kMaxWritePages * hkv_pool::kWriteSlots;
+        HKV_HIP(hipHostMalloc((void **)&pool->h_ids, bytes, hipHostMallocDefault));
+        HKV_HIP(hipMalloc((void **)&pool->d_ids, bytes));
+        for (hipEvent_t &e : pool->slot_free) HKV_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
     }
-    if (pool->ids_in_flight) HKV_HIP(hipEventSynchronize(pool->ids_free));  // previous write done with the staging
-    memcpy(pool->h_ids, page_ids, sizeof(int32_t) * (size_t)n_pg);
-    HKV_HIP(hipMemcpyAsync(pool->d_ids, pool->h_ids, sizeof(int32_t) * (size_t)n_pg, hipMemcpyHostToDevice, s));
+    const int slot = pool->next_slot;
+    pool->next_slot = (slot + 1) % hkv_pool::kWriteSlots;
+    if (pool->slot_in_flight[slot]) HKV_HIP(hipEventSynchronize(pool->slot_free[slot]));  // its last write is done
+    int32_t *h = pool->h_ids + (size_t)slot * hkv_pool::kMaxWritePages;
+    int32_t *d = pool->d_ids + (size_t)slot * hkv_pool::kMaxWritePages;
+    memcpy(h, page_ids, sizeof(int32_t) * (size_t)n_pg);
+    HKV_HIP(hipMemcpyAsync(d, h, sizeof(int32_t) * (size_t)n_pg, hipMemcpyHostToDevice, s));
     PoolWriteLaunch a{pool->d.k_pages, pool->d.v_pages, pool->d.k_scale, pool->d.v_scale, pool->d.num_kv_heads,
-                      pool->d.dtype, pool->d_ids, (int32_t)n_pg, first_slot, n_tokens, k_src, v_src};
+                      pool->d.dtype, d, (int32_t)n_pg, first_slot, n_tokens, k_src, v_src};
     HKV_HIP(launch_pool_write(a, s));
-    HKV_HIP(hipEventRecord(pool->ids_free, s));
-    pool->ids_in_flight = true;
+    HKV_HIP(hipEventRecord(pool->slot_free[slot], s));
+    pool->slot_in_flight[slot] = true;
     return HKV_OK;
 }
 

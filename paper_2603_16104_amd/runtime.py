@@ -126,3 +126,98 @@ class PrefillRunner:
         if self.plan is not None:
             hkv.hkv_prefill_plan_destroy(self.plan)
             self.plan = None
+
+
+class WorkflowRunner:
+    """Runs the prefill side of a scheduled workflow on one worker through the library: the tree of
+    the workflow's prompt templates is the prefix forest, the KV pages of the previous call's path
+    stay in the pool, every call allocates and writes pages only for the nodes that are new on its
+    path (their token count is the call's prefill usage) and runs suffix-only prefill attention of
+    those tokens against the whole path.  Everything a call needs (page ids, plan, source tensors)
+    is prepared by `prepare`; `run` only queues GPU work, so that it can be timed."""
+
+    def __init__(self, wf: wl.Workflow, num_q_heads: int = 32, num_kv_heads: int = 8, seed: int = wl.BASE_SEED + 9,
+                 device: str = "cuda:0"):
+        self.wf, self.Hq, self.Hkv, self.seed, self.device = wf, num_q_heads, num_kv_heads, seed, device
+        self.tree = hkv.trt_build(wf.templates, wf.len_out, wf.worker)
+        self.nodes = hkv.trt_nodes(self.tree)
+        nd = self.nodes
+        for v in range(len(nd["parent"])):
+            if nd["weight"][v] % hkv.PAGE_SIZE:
+                raise ValueError(f"node {v} holds {nd['weight'][v]} tokens: sharing is page-granular, every "
+                                 "template segment (and output length) must be a multiple of 16 tokens")
+        self.paths = []          # per call: nodes with tokens from the root down to the leaf's parent
+        for c in range(wf.n_calls):
+            p, v = [], int(nd["parent"][nd["leaf_of_call"][c]])
+            while v > 0:
+                if nd["weight"][v] > 0:
+                    p.append(v)
+                v = int(nd["parent"][v])
+            self.paths.append(p[::-1])
+        longest = max((sum(int(nd["weight"][v]) for v in p) for p in self.paths), default=16)
+        self.pool = DevicePool(2 * longest // hkv.PAGE_SIZE + 8, num_kv_heads, hkv.BF16, device)
+        self.scale = float(1.0 / np.sqrt(np.float32(hkv.HEAD_DIM)))
+        self.steps = []
+        self._kv_cache = {}
+
+    def _node_tensors(self, v: int):
+        if v not in self._kv_cache:
+            n = int(self.nodes["weight"][v])
+            k, vv = wl.workflow_node_kv(self.seed, v, n, self.Hkv)
+            q = wl.workflow_node_q(self.seed, v, n, self.Hq)
+            self._kv_cache[v] = (to_device_bits(k, self.device), to_device_bits(vv, self.device),
+                                 to_device_bits(q, self.device))
+        return self._kv_cache[v]
+
+    def prepare(self, sequence, cache: bool = True) -> list:
+        """Fixes page ids and builds one prefill plan per call of `sequence`.  cache = False models an
+        engine without prefix reuse: every call starts from an empty pool.  Returns the calls'
+        prefill usage (new tokens)."""
+        self.release_steps()
+        resident = {}            # node -> page ids
+        usage = []
+        for c in sequence:
+            path = self.paths[c]
+            for v in [v for v in resident if (not cache) or v not in path]:
+                hkv.kv_pool_release(self.pool.handle, resident.pop(v))
+            new = [v for v in path if v not in resident]
+            for v in new:
+                resident[v] = hkv.kv_pool_alloc(self.pool.handle, int(self.nodes["weight"][v]) // hkv.PAGE_SIZE)
+            n_new = sum(int(self.nodes["weight"][v]) for v in new)
+            usage.append(n_new)
+            step = {"call": c, "new": new, "pages": {v: resident[v].copy() for v in new}, "n_new": n_new, "plan": None}
+            if n_new:
+                bt = np.concatenate([resident[v] for v in path]).astype(np.int32)
+                kv_len = sum(int(self.nodes["weight"][v]) for v in path)
+                # the new nodes are the tail of the path (everything below the lowest common ancestor)
+                assert path[len(path) - len(new):] == new
+                step["plan"] = hkv.hkv_prefill_plan_create(self.pool.handle, np.array([0, n_new], dtype=np.int32),
+                                                           bt[None, :], np.array([kv_len], dtype=np.int32), self.Hq)
+                step["q"] = torch.cat([self._node_tensors(v)[2] for v in new], dim=0)
+                step["out"] = torch.zeros((n_new, self.Hq, hkv.HEAD_DIM), dtype=torch.int16, device=self.device)
+                step["block_table"], step["kv_len"] = bt, kv_len
+            self.steps.append(step)
+        for v in list(resident):
+            hkv.kv_pool_release(self.pool.handle, resident.pop(v))
+        return usage
+
+    def run(self, stream=None) -> None:
+        for st in self.steps:
+            for v in st["new"]:
+                k, vv, _ = self._node_tensors(v)
+                self.pool.write(st["pages"][v], 0, k, vv, stream)
+            if st["plan"] is not None:
+                hkv.attn_prefill_plan_run(st["plan"], st["q"], self.scale, st["out"], None, stream)
+
+    def release_steps(self) -> None:
+        for st in self.steps:
+            if st["plan"] is not None:
+                hkv.hkv_prefill_plan_destroy(st["plan"])
+        self.steps = []
+
+    def close(self) -> None:
+        self.release_steps()
+        if self.tree is not None:
+            hkv.trt_destroy(self.tree)
+            self.tree = None
+        self.pool.close()

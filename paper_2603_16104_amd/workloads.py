@@ -443,3 +443,18 @@ def random_workflow(seed: int, n_calls: int = 12, vocab: int = 6, max_len: int =
     for i in range(n_calls):
         w.add(tmpl[i], int(rng.integers(0, max_out + 1)), int(rng.integers(0, n_workers)))
     return w
+
+
+def workflow_node_kv(seed: int, node: int, n_tokens: int, num_kv_heads: int) -> Tuple[np.ndarray, np.ndarray]:
+    """K and V (bf16 bits, [n_tokens][Hkv][128]) of the tokens of one tree node of a workflow: the same
+    node always yields the same bits, whichever call brings it into the cache."""
+    shape = (n_tokens, num_kv_heads, HEAD_DIM)
+    k = np.random.default_rng([seed, 21, node]).standard_normal(size=shape, dtype=np.float32)
+    v = np.random.default_rng([seed, 22, node]).standard_normal(size=shape, dtype=np.float32)
+    return f32_to_bf16_bits(k), f32_to_bf16_bits(v)
+
+
+def workflow_node_q(seed: int, node: int, n_tokens: int, num_q_heads: int) -> np.ndarray:
+    """Query rows (bf16 bits, [n_tokens][Hq][128]) of the tokens of one tree node."""
+    x = np.random.default_rng([seed, 23, node]).standard_normal(size=(n_tokens, num_q_heads, HEAD_DIM), dtype=np.float32)
+    return f32_to_bf16_bits(x)

@@ -379,3 +379,42 @@ def test_diagnostic_probes(gpu):
         hkv.hkv_mfma_probe(0, False, 2)
     with pytest.raises(hkv.HkvError):
         hkv.hkv_hbm_read_probe(bufs, 24, 1)
+
+
+@pytest.mark.gpu
+def test_workflow_prefix_reuse_equals_naive(gpu, oracle):
+    """Scheduling layer driving the kernels: calls of a small debate workflow run in the order the
+    cache-aware scheduler picks, each prefilling only the nodes that are new on its path against the
+    pages the previous call left in the pool.  Every call's output must equal plain attention over
+    its whole prompt (Section 2, "Scope": same result as naive execution), and the number of
+    tokens each call processes must be its prefill usage u_p."""
+    import torch
+    from oracle import trt as otrt
+    from paper_2603_16104_amd import binding as hkv
+    wf = wl.workflow_debate(n_queries=2, n_agents=2, rounds=2, sys_len=32, q_len=48, len_out=16)
+    r = gpu.WorkflowRunner(wf, num_q_heads=8, num_kv_heads=2)
+    try:
+        sigma, _, _, _ = hkv.trt_schedule(r.tree, 1, 4096)
+        seq = sigma[0]
+        t = otrt.build_trt([otrt.Call(a, b, c) for a, b, c in zip(wf.templates, wf.len_out, wf.worker)])
+        usage = r.prepare(seq)
+        assert usage == [otrt.prefill_usage(t, seq[j - 1] if j else -1, c) for j, c in enumerate(seq)]
+        assert sum(usage) < sum(otrt.prefill_usage(t, -1, c) for c in seq)       # something was reused
+        r.run()
+        torch.cuda.synchronize()
+        for st in r.steps:
+            if st["plan"] is None:
+                continue
+            path = r.paths[st["call"]]
+            k = np.concatenate([wl.workflow_node_kv(r.seed, v, int(r.nodes["weight"][v]), 2)[0] for v in path])
+            v_ = np.concatenate([wl.workflow_node_kv(r.seed, v, int(r.nodes["weight"][v]), 2)[1] for v in path])
+            q = np.concatenate([wl.workflow_node_q(r.seed, v, int(r.nodes["weight"][v]), 8) for v in st["new"]])
+            n_pages = len(k) // 16
+            hp = oracle.HostPool(n_pages, 2, wl.KV_BF16)
+            hp.write(np.arange(n_pages, dtype=np.int32), 0, k, v_)
+            exp_o, _ = oracle.attn_prefill(hp, q, np.array([0, len(q)], dtype=np.int32),
+                                           np.arange(n_pages, dtype=np.int32)[None, :], np.array([len(k)], dtype=np.int32),
+                                           float(r.scale))
+            check_close(gpu.bf16_tensor_to_f64(st["out"]), exp_o, f"workflow call {st['call']}")
+    finally:
+        r.close()
