@@ -707,8 +707,7 @@ extern "C" int hkv_prefill_plan_create(hkv_pool *pool, const int32_t *cu_q, cons
     const int Hkv = pool->d.num_kv_heads;
     if (num_q_heads <= 0 || num_q_heads % Hkv) return fail(HKV_ESHAPE, "hkv_prefill_plan_create: %d query heads over %d KV heads", num_q_heads, Hkv);
     const int G = num_q_heads / Hkv;
-    if (G != 1 && G != 2 && G != 4 && G != 8)
-        return fail(HKV_ESHAPE, "hkv_prefill_plan_create: query/KV head ratio %d (supported: 1, 2, 4, 8)", G);
+    if (G > 8) return fail(HKV_ESHAPE, "hkv_prefill_plan_create: query/KV head ratio %d (supported: 1..8)", G);
     if (pool->d.dtype != HKV_BF16) return fail(HKV_ESHAPE, "hkv_prefill_plan_create: prefill reads bf16 pools only");
     if (n_req < 0 || max_pages < 0 || (n_req > 0 && (!cu_q || !kv_len || (max_pages > 0 && !block_table))))
         return fail(HKV_EINVAL, "hkv_prefill_plan_create: bad argument");

@@ -2,9 +2,11 @@
 // prefix pages plus the causal part of their own suffix, all read through the block table.
 // (Section 5, "Token usage": a call processes only the tokens that are not already cached.)
 //
-// One workgroup (8 wavefronts, two per SIMD) owns 256 query rows = 256/G consecutive new tokens x
-// the G query heads of one KV head, so every K/V tile staged in LDS is used by all G heads.  Each
-// wavefront owns one 32-row tile and keeps Q^T and the O^T accumulators in registers; K/V stream
+// One workgroup (8 wavefronts, two per SIMD) owns up to 256 query rows = 32 * tbh consecutive new
+// tokens x the G query heads of one KV head (tbh = the largest power of two <= 8 / G), so every K/V
+// tile staged in LDS is used by all G heads; when G is no power of two, 8 / tbh - G wavefronts have
+// no head of their own (they repeat the last one and store nothing).  Each wavefront owns one
+// 32-row tile and keeps Q^T and the O^T accumulators in registers; K/V stream
 // through LDS in 64-token blocks, four stages each, fetched by LDS-direct loads
 // (global_load_lds_dwordx4) two blocks ahead so that the data in flight occupies no registers.
 //
@@ -36,7 +38,6 @@ namespace hkv {
 
 namespace {
 
-constexpr int kRowsPerGroup = 256;
 constexpr int kWaves = 8;                      // one 32-row tile each
 constexpr int kThreads = 64 * kWaves;
 constexpr int KB = 64;                         // tokens per LDS stage (4 pages)
@@ -83,11 +84,12 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillLaunch a) {
     const int n = lane & 31, h = lane >> 5;
     const int Hq = a.num_q_heads, Hkv = a.pool.num_kv_heads;
     const int G = Hq / Hkv;
-    const int tbh = 8 / G;  // 32-token blocks per head inside the workgroup's rows
+    const int tbh = G == 1 ? 8 : G == 2 ? 4 : G <= 4 ? 2 : 1;  // 32-token blocks per head inside the workgroup's rows
     const float c = a.scale * kLog2e;
 
     // the 32-row tile of this wavefront
-    const int head = tl.kv_head * G + wave / tbh;  // query head
+    const bool live = wave / tbh < G;                          // this wavefront has a head of its own
+    const int head = tl.kv_head * G + min(wave / tbh, G - 1);  // query head
     const int tok = 32 * (wave % tbh) + n;         // token index of this lane's row within the tile's new tokens
     bf16x8 qf[8];
     {
@@ -419,7 +421,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillLaunch a) {
 
     // ---- normalise and store; lane (n, h) holds dims 32*dm + 8*(i/4) + 4*h + i%4 of its row
     const float l_tot = l_run + __shfl_xor(l_run, 32);
-    if (tok < tl.n_q) {
+    if (live && tok < tl.n_q) {
         const float inv = 1.0f / l_tot;
         const size_t row = (size_t)(tl.q_row0 + tok) * Hq + head;
         uint16_t *op = static_cast<uint16_t *>(a.out) + row * kHeadDim;
@@ -438,7 +440,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillLaunch a) {
 
 }  // namespace
 
-int prefill_tile_tokens(int group) { return kRowsPerGroup / group; }
+int prefill_tile_tokens(int group) { return 32 * (group == 1 ? 8 : group == 2 ? 4 : group <= 4 ? 2 : 1); }
 
 hipError_t launch_prefill(const PrefillLaunch &a, hipStream_t s) {
     if (a.n_tiles <= 0) return hipSuccess;

@@ -301,6 +301,15 @@ def test_prefill_random_forests(gpu, oracle, seed):
     run_prefill(gpu, oracle, w)
 
 
+@pytest.mark.parametrize("hq,hkv_", [(6, 2), (5, 1), (12, 2), (14, 2), (40, 8)])
+def test_prefill_head_ratios_that_are_no_power_of_two(gpu, oracle, hq, hkv_):
+    """Query/KV head ratios 3, 5, 6, 7 (40 / 8 is the Qwen3-14B shape): some wavefronts of a tile have
+    no head of their own and must neither disturb the others nor store anything."""
+    w = wl.random_forest_workload(70 + hq, mode="prefill", num_q_heads=hq, num_kv_heads=hkv_, depth=2, fanout=2,
+                                  max_node_pages=10, n_roots=2)
+    run_prefill(gpu, oracle, w)
+
+
 def test_prefill_ragged_medium(gpu, oracle):
     """Several query tiles per request, ragged suffix lengths, prefix spanning many 64-token blocks."""
     w = wl.config4(seed=99, n_req=3, prefix_tokens=400 // 16 * 16, lo=70, hi=200)
