@@ -208,6 +208,17 @@ enum { HKV_PLAN_HOST_ONLY = 1 /* build and validate on the host, allocate nothin
 int hkv_decode_plan_create(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes, const int32_t *node_pages,
                            int32_t n_node_pages, const int32_t *req_leaf, int32_t n_req, int32_t num_q_heads,
                            uint32_t flags, hkv_decode_plan **out);
+/* The same for tokens_per_req (1..16) query tokens per request, e.g. the verification of a run of
+ * drafted tokens: the request's T newest tokens (the last T of its path; they must all lie in its
+ * leaf node, whose K/V are already in the pool) are queried together, token t of the T seeing every
+ * key up to and including its own position.  q, out and lse_out of attn_decode_plan_run then hold
+ * n_req * T rows, request-major ([n_req][T][num_q_heads][128]); all counts the introspection calls
+ * return (requests of an item, part_counts) are in query rows, i.e. as for a plan over n_req * T
+ * requests.  A query row that sees no token of some chunk of its leaf gets the empty partial there.
+ * EINVAL if tokens_per_req is out of range or exceeds a request's leaf length. */
+int hkv_decode_plan_create_multi(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes, const int32_t *node_pages,
+                                 int32_t n_node_pages, const int32_t *req_leaf, int32_t n_req, int32_t tokens_per_req,
+                                 int32_t num_q_heads, uint32_t flags, hkv_decode_plan **out);
 int hkv_decode_plan_destroy(hkv_decode_plan *plan);
 /* Bytes of device workspace attn_decode_plan_run needs (partial o and lse), 0 on a null plan. */
 size_t hkv_decode_plan_workspace_bytes(const hkv_decode_plan *plan);

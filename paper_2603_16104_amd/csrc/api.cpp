@@ -75,6 +75,9 @@ struct hkv_decode_plan {
     int32_t *d_pages = nullptr, *d_node_req_idx = nullptr, *d_part_count = nullptr;
     bool profiling = false, profiled_run = false, node_only = false;
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+    // several query tokens per request: n_req above counts query rows (requests x tokens_per_req)
+    int32_t tokens_per_req = 1;
+    int32_t *d_row_leaf = nullptr, *d_row_limit = nullptr;  // one allocation (d_row_leaf), null when tokens_per_req == 1
 };
 
 struct hkv_prefill_plan {
@@ -552,9 +555,57 @@ extern "C" int hkv_decode_plan_create(hkv_pool *pool, const hkv_node *nodes, int
     return HKV_OK;
 }
 
+extern "C" int hkv_decode_plan_create_multi(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes,
+                                            const int32_t *node_pages, int32_t n_node_pages, const int32_t *req_leaf,
+                                            int32_t n_req, int32_t tokens_per_req, int32_t num_q_heads, uint32_t flags,
+                                            hkv_decode_plan **out) {
+    if (!out) return fail(HKV_EINVAL, "hkv_decode_plan_create_multi: null out");
+    *out = nullptr;
+    const int T = tokens_per_req;
+    if (T < 1 || T > 16) return fail(HKV_EINVAL, "hkv_decode_plan_create_multi: %d query tokens per request (1..16)", T);
+    if (n_req < 0 || (n_req > 0 && !req_leaf)) return fail(HKV_EINVAL, "hkv_decode_plan_create_multi: bad request list");
+    if ((int64_t)n_req * T > INT32_MAX / 2) return fail(HKV_EINVAL, "hkv_decode_plan_create_multi: too many query rows");
+    std::vector<int32_t> rows((size_t)n_req * T);
+    for (int r = 0; r < n_req; ++r)
+        for (int t = 0; t < T; ++t) rows[(size_t)r * T + t] = req_leaf[r];
+    hkv_decode_plan *pl = nullptr;
+    if (int rc = hkv_decode_plan_create(pool, nodes, n_nodes, node_pages, n_node_pages, rows.data(), n_req * T,
+                                        num_q_heads, flags, &pl))
+        return rc;
+    pl->tokens_per_req = T;
+    if (T > 1) {
+        std::vector<int32_t> lim((size_t)n_req * T);
+        for (int r = 0; r < n_req; ++r) {
+            const int n_leaf = nodes[req_leaf[r]].n_tokens;  // validated by hkv_decode_plan_create
+            if (n_leaf < T) {
+                hkv_decode_plan_destroy(pl);
+                return fail(HKV_EINVAL, "hkv_decode_plan_create_multi: request %d has %d query tokens but its leaf holds "
+                            "only %d tokens (the newest tokens must lie in the leaf)", r, T, n_leaf);
+            }
+            for (int t = 0; t < T; ++t) lim[(size_t)r * T + t] = n_leaf - (T - 1 - t);
+        }
+        if (pl->dev && n_req > 0) {
+            const size_t bytes = sizeof(int32_t) * rows.size();
+            hipError_t e = hipMalloc((void **)&pl->d_row_leaf, 2 * bytes);
+            if (e == hipSuccess) e = hipMemcpy(pl->d_row_leaf, rows.data(), bytes, hipMemcpyHostToDevice);
+            if (e == hipSuccess) {
+                pl->d_row_limit = pl->d_row_leaf + rows.size();
+                e = hipMemcpy(pl->d_row_limit, lim.data(), bytes, hipMemcpyHostToDevice);
+            }
+            if (e != hipSuccess) {
+                hkv_decode_plan_destroy(pl);
+                return fail_hip(e, "hkv_decode_plan_create_multi");
+            }
+        }
+    }
+    *out = pl;
+    return HKV_OK;
+}
+
 extern "C" int hkv_decode_plan_destroy(hkv_decode_plan *plan) {
     if (!plan) return HKV_OK;
     if (plan->dev) (void)hipFree(plan->dev);  // hipFree waits for work that may still read it
+    if (plan->d_row_leaf) (void)hipFree(plan->d_row_leaf);
     for (hipEvent_t e : plan->ev)
         if (e) (void)hipEventDestroy(e);
     delete plan;
@@ -609,7 +660,8 @@ extern "C" int attn_decode_plan_run(hkv_decode_plan *plan, const void *q, float 
     if (prof) HKV_HIP(hipEventRecord(plan->ev[0], s));
     if (!plan->items.empty()) {
         DecodeLaunch a{view_of(plan->pool), q, plan->d_items, plan->d_pages, plan->d_node_req_idx, o_parts, lse_parts,
-                       (int32_t)plan->items.size(), plan->num_q_heads, plan->max_parts, scale, nullptr};
+                       (int32_t)plan->items.size(), plan->num_q_heads, plan->max_parts, scale, nullptr,
+                       plan->d_row_leaf, plan->d_row_limit};
         HKV_HIP(launch_decode(a, s));
     }
     if (plan->node_only) return HKV_OK;

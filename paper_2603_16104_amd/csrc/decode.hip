@@ -169,6 +169,12 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
         }
     };
     bf16x8 qf[4];
+    // Tokens of this item that this lane's query row may see (all of them unless the row is one of
+    // several query tokens of a request and this is the node that holds the request's newest tokens).
+    int lim = it.n_tokens;
+    auto load_limit = [&](int req) {
+        if (a.row_leaf && a.row_leaf[req] == it.node) lim = a.row_limit[req] - it.tok_begin;
+    };
 
     // Loop-invariant byte offsets of this lane inside a (page, head) block and the page of the step
     // it reads.  bf16: score tile a holds tokens 8*(m/4) + m%4 of the 32-token step, tile b those + 4;
@@ -262,12 +268,19 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
             for (int j = 0; j < NS; ++j)
                 if (j >= first_bad) s[j] = -INFINITY;
         }
+        if (__builtin_amdgcn_ballot_w64(tok0 + NS > lim)) {  // some row of the tile does not see the whole step
+#pragma unroll
+            for (int j = 0; j < NS; ++j)
+                if (tok0 + j >= lim) s[j] = -INFINITY;
+        }
         float mx = s[0];
 #pragma unroll
         for (int j = 1; j < NS; ++j) mx = fmaxf(mx, s[j]);
         mx = rows_max(mx);
         const float m_new = fmaxf(m_run, mx);
-        const float mc = m_new * c;
+        // a row that has seen nothing so far keeps m = -inf; its exponentials use 0 as the reference
+        // (they are all exp2(-inf) = 0), so that no inf - inf arises
+        const float mc = (m_new == -INFINITY) ? 0.f : m_new * c;
         const float alpha = fast_exp2(m_run * c - mc);
         float p[NS];
         float sum = 0.f;
@@ -370,6 +383,7 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
         };
         const int req = load_req();
         load_q(qf, req);
+        load_limit(req);
         issue_stage(0);
         if (n_blk > 1) issue_stage(1);
         HKV_STAMP(1);
@@ -401,12 +415,13 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
         if (active) {
             const float l_row = rows_sum(l_run);
             if (row < rows) {
-                const float inv = 1.0f / l_row;
+                // a row that saw no token of this item delivers the empty partial (o = 0, lse = -inf)
+                const float inv = l_row > 0.f ? 1.0f / l_row : 0.f;
                 const size_t part = (size_t)(req * a.num_q_heads + it.kv_head * G + row % G) * a.max_parts + it.part_slot;
                 float *op = a.o_parts + part * kHeadDim + 4 * g;
 #pragma unroll
                 for (int dt = 0; dt < 8; ++dt) *reinterpret_cast<f32x4 *>(op + 16 * dt) = o[dt] * inv;
-                if (g == 0) a.lse_parts[part] = (m_run * c + fast_log2(l_row)) * kLn2;
+                if (g == 0) a.lse_parts[part] = l_row > 0.f ? (m_run * c + fast_log2(l_row)) * kLn2 : -INFINITY;
             }
         }
         HKV_STAMP(6);
@@ -422,6 +437,7 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
         issue_k(cur);
         issue_v(cur);
         load_q(qf, req);
+        load_limit(req);
         load_step_pages<DT>(nxt, a, it, b + n_ts, last_page);  // clamped: always in bounds
         HKV_STAMP(1);
         bool first = true;
@@ -458,15 +474,20 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
         float M = -INFINITY;
         for (int t = 0; t < n_ts; ++t) M = fmaxf(M, sM[t * n_rt + r_t][r_c]);
         float L = 0.f, acc = 0.f;
-        for (int t = 0; t < n_ts; ++t) {
-            const int w = t * n_rt + r_t;
-            const float wgt = fast_exp2((sM[w][r_c] - M) * c);
-            L += sL[w][r_c] * wgt;
-            acc += sO[w][r_c][d] * wgt;
+        if (M != -INFINITY) {
+            for (int t = 0; t < n_ts; ++t) {
+                const int w = t * n_rt + r_t;
+                const float mw = sM[w][r_c];
+                if (mw == -INFINITY) continue;  // that wavefront's tokens were all invisible to the row
+                const float wgt = fast_exp2((mw - M) * c);
+                L += sL[w][r_c] * wgt;
+                acc += sO[w][r_c][d] * wgt;
+            }
         }
         const size_t part = (size_t)sPart[row];
-        a.o_parts[part * kHeadDim + d] = acc / L;
-        if (d == 0) a.lse_parts[part] = (M * c + fast_log2(L)) * kLn2;
+        // a row that saw no token of this item delivers the empty partial (o = 0, lse = -inf)
+        a.o_parts[part * kHeadDim + d] = L > 0.f ? acc / L : 0.f;
+        if (d == 0) a.lse_parts[part] = L > 0.f ? (M * c + fast_log2(L)) * kLn2 : -INFINITY;
     }
     HKV_STAMP(6);
 #ifdef HKV_TRACE

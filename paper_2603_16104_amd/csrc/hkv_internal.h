@@ -60,6 +60,11 @@ struct DecodeLaunch {
     int32_t max_parts;
     float scale;
     unsigned long long *trace;   // development builds only (HKV_TRACE): 8 timestamps per wavefront, else null
+    // Several query tokens per request (null otherwise): row r of q is query token r % T of request
+    // r / T; inside the node row_leaf[r] it sees only the first row_limit[r] tokens (the causal mask
+    // among the request's newest tokens), every other node of its path it sees whole.
+    const int32_t *row_leaf;     // device [n_req * T]
+    const int32_t *row_limit;    // device [n_req * T]
 };
 
 struct PrefillLaunch {

@@ -427,3 +427,66 @@ def test_workflow_prefix_reuse_equals_naive(gpu, oracle):
             check_close(gpu.bf16_tensor_to_f64(st["out"]), exp_o, f"workflow call {st['call']}")
     finally:
         r.close()
+
+
+# ------------------------------------------------------------------------------ several query tokens per request
+
+def run_decode_multi(gpu, oracle, w, T, seed=5):
+    """Decode of the T newest tokens of every request at once against the oracle's causal suffix
+    attention over the same pool (query token t of a request sits at position kv_len - T + t)."""
+    import torch
+    from paper_2603_16104_amd import binding as hkv
+    f = w.forest
+    hp, dp = both_pools(gpu, oracle, w)
+    q = wl.f32_to_bf16_bits(np.random.default_rng(seed).standard_normal((f.n_req * T, w.num_q_heads, 128)).astype(np.float32))
+    bt, kv_len, *_ = oracle.flatten_workload(w)
+    cu_q = np.arange(f.n_req + 1, dtype=np.int32) * T
+    exp_o, exp_l = oracle.attn_prefill(hp, q, cu_q, bt, kv_len, float(w.scale))
+    plan = hkv.hkv_decode_plan_create_multi(dp.handle, f.nodes, f.node_pages, f.req_leaf, T, w.num_q_heads)
+    ws_bytes = hkv.hkv_decode_plan_workspace_bytes(plan)
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
+    qd = gpu.to_device_bits(q)
+    out = torch.full((f.n_req * T, w.num_q_heads, 128), 0x7FC0, dtype=torch.int16, device="cuda")
+    lse = torch.zeros((f.n_req * T, w.num_q_heads), dtype=torch.float32, device="cuda")
+    for _ in range(2):
+        hkv.attn_decode_plan_run(plan, qd, float(w.scale), out, lse, ws, ws_bytes)
+    torch.cuda.synchronize()
+    got_o, got_l = gpu.bf16_tensor_to_f64(out), lse.cpu().numpy()
+    hkv.hkv_decode_plan_destroy(plan)
+    dp.close()
+    check_close(got_o, exp_o, f"{w.name}_T{T}")
+    check_lse(got_l, exp_l, f"{w.name}_T{T}")
+
+
+def _multi_forest(kv_dtype, hq, hkv_, leaf_tokens, req_leaf, root_tokens=64, seed=31):
+    parent = [-1] + [0] * len(leaf_tokens)
+    ntok = [root_tokens] + list(leaf_tokens)
+    n_used = sum((t + 15) // 16 for t in ntok)
+    f = wl.make_forest(parent, ntok, req_leaf, np.random.default_rng(seed).permutation(n_used + 5).astype(np.int32))
+    return wl.Workload(name="multi", num_q_heads=hq, num_kv_heads=hkv_, kv_dtype=kv_dtype, num_pages=n_used + 5,
+                       seed=seed, forest=f, mode="decode")
+
+
+@pytest.mark.parametrize("kv_dtype", [wl.KV_BF16, wl.KV_FP8_E4M3])
+@pytest.mark.parametrize("T", [1, 3, 4])
+def test_decode_several_query_tokens(gpu, oracle, kv_dtype, T):
+    """Leaves of 48, 21 (ragged) and 100 tokens under a 64-token root, plus a request whose newest tokens
+    are the root's own last ones: in the root's work items that request's rows are masked causally while
+    the other requests' rows see the whole node."""
+    w = _multi_forest(kv_dtype, 8, 2, [48, 21, 100], [1, 2, 3, 0])
+    run_decode_multi(gpu, oracle, w, T)
+
+
+def test_decode_several_query_tokens_chunk_without_visible_token(gpu, oracle, monkeypatch):
+    """16 query tokens over a 40-token leaf cut into chunks of 32 and 8 tokens: the first queries see
+    nothing of the second chunk and must deliver the empty partial there (no NaN)."""
+    monkeypatch.setenv("HKV_DECODE_LEAF_CHUNK", "32")
+    w = _multi_forest(wl.KV_BF16, 4, 4, [40, 16], [1, 2])
+    run_decode_multi(gpu, oracle, w, 16)
+
+
+def test_decode_several_query_tokens_many_rows(gpu, oracle):
+    """40 requests x 2 tokens x 4 heads = 320 rows under the shared root: the LDS-staged path with limits
+    only in the leaves."""
+    w = wl.config2(seed=78, n_req=40, root_tokens=640, private_tokens=100)
+    run_decode_multi(gpu, oracle, w, 2)

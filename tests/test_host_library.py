@@ -334,3 +334,17 @@ def test_merge_argument_validation():
         hkv.lse_merge_dense(0x1004, 0x2000, 0x3000, 4, 4, 8, 0x5000, hkv.BF16, stream=0)
     assert e.value.code == hkv.EINVAL
     assert hkv.attn_prefill_workspace_bytes(1000, 32) == 0
+
+
+def test_decode_several_query_tokens_errors():
+    f = wl.make_forest([-1, 0], [32, 3], [1], np.arange(4, dtype=np.int32))
+    pool = fake_pool(8, 2)
+    with pytest.raises(hkv.HkvError) as e:
+        hkv.hkv_decode_plan_create_multi(pool, f.nodes, f.node_pages, f.req_leaf, 4, 4, hkv.PLAN_HOST_ONLY)   # leaf holds 3 tokens
+    assert e.value.code == hkv.EINVAL
+    with pytest.raises(hkv.HkvError) as e:
+        hkv.hkv_decode_plan_create_multi(pool, f.nodes, f.node_pages, f.req_leaf, 17, 4, hkv.PLAN_HOST_ONLY)
+    assert e.value.code == hkv.EINVAL
+    plan = hkv.hkv_decode_plan_create_multi(pool, f.nodes, f.node_pages, f.req_leaf, 3, 4, hkv.PLAN_HOST_ONLY)
+    assert hkv.hkv_decode_plan_part_counts(plan, 3).tolist() == [2, 2, 2]       # three query rows, root + leaf each
+    hkv.hkv_decode_plan_destroy(plan)
