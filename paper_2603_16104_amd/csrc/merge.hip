@@ -64,15 +64,31 @@ __global__ __launch_bounds__(32 * kDenseRowsPerBlock) void lse_merge_dense_kerne
     const size_t base = (size_t)row * max_parts;
     const float *lp = lse_parts + base;
     const f32x4 *op = reinterpret_cast<const f32x4 *>(o_parts + base * kHeadDim) + l;
+    // With few slots per row all of them are requested before the count is known (slots k < max_parts
+    // exist for every row; what an unused one holds is never looked at), so the count, the lse values
+    // and the partials travel in one round trip instead of two.  With many slots only the used ones
+    // are read.
     float ls[kUnroll];
     f32x4 ov[kUnroll];
+    if (max_parts <= kUnroll) {
 #pragma unroll
-    for (int k = 0; k < kUnroll; ++k) {
-        ls[k] = -INFINITY;
-        ov[k] = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (k < cnt) {
-            ls[k] = lp[k];
-            ov[k] = op[(size_t)k * (kHeadDim / 4)];
+        for (int k = 0; k < kUnroll; ++k) {
+            const int kc = min(k, max_parts - 1);
+            ls[k] = lp[kc];
+            ov[k] = op[(size_t)kc * (kHeadDim / 4)];
+        }
+#pragma unroll
+        for (int k = 0; k < kUnroll; ++k)
+            if (k >= cnt) ls[k] = -INFINITY;
+    } else {
+#pragma unroll
+        for (int k = 0; k < kUnroll; ++k) {
+            ls[k] = -INFINITY;
+            ov[k] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (k < cnt) {
+                ls[k] = lp[k];
+                ov[k] = op[(size_t)k * (kHeadDim / 4)];
+            }
         }
     }
     float M = -INFINITY;
