@@ -125,12 +125,14 @@ int32_t kv_pool_refcount(const hkv_pool *pool, int32_t page_id);
  * prefix KV once and keep it" step seen from the pool.
  *   page_ids: host, ceil((first_slot + n_tokens)/16) entries (at most 65536).
  *   k_src, v_src: device, [n_tokens][num_kv_heads][128] bf16.
- * bf16 pools: plain scatter into the block format.  fp8 pools: first_slot must be 0; every
- * (page, head) block written gets scale = amax/448 over the tokens written into it by this
- * call (1 if amax == 0) and code = round-to-nearest-even(x / scale), saturated to +-448, all in
- * float; a later call that writes the same page recomputes its scale from that call's tokens
- * only, so fp8 pages are written whole (or as the sequence's last, partial page).
- * Slots not written keep their contents.  n_tokens == 0 is a no-op.
+ * bf16 pools: plain scatter into the block format.  fp8 pools: a (page, head) block written from
+ * slot 0 gets scale = amax/448 over the tokens written into it by this call (1 if amax == 0) and
+ * code = round-to-nearest-even(x / scale), saturated to +-448, all in float.  A block that is
+ * continued (the first page of a call with first_slot > 0, e.g. decode appending a token) keeps
+ * a running scale: scale' = max(scale, amax_new/448); if the scale grows, the codes already in
+ * the slots below first_slot are re-encoded as RNE(value(code) * scale / scale') (a second
+ * rounding of those tokens); the scale never shrinks.  Slots [0, first_slot) of such a page must
+ * have been written before.  Slots not written keep their contents.  n_tokens == 0 is a no-op.
  * EINVAL / ERANGE / ESHAPE as above; the ids are checked before anything is queued. */
 int kv_pool_write(hkv_pool *pool, const int32_t *page_ids, int32_t first_slot, int32_t n_tokens,
                   const void *k_src, const void *v_src, void *stream);

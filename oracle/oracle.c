@@ -242,15 +242,17 @@ static float src_as_float(const void *src, int src_dtype, size_t i) {
 /* Store n_tokens consecutive tokens ([n_tokens][Hkv][128], bf16 bits or float) into the pages
  * page_ids[0..], starting at slot first_slot of page_ids[0].  This is the "precompute and keep
  * the KV cache" step of Section 5 seen from the pool.  bf16/fp32 pools: plain copy.  fp8 pools:
- * first_slot must be 0; every touched (page, head) block gets scale = amax/448 over the tokens
- * written into it (1 if amax is 0), computed in float, and code = RNE(x / scale) with the
- * division in float.  Returns 0 or a negative code as in oracle_flatten_tree. */
+ * a (page, head) block written from slot 0 gets scale = amax/448 over the tokens written into it
+ * (1 if amax is 0), computed in float, and code = RNE(x / scale) with the division in float.
+ * A block that is continued (first page of a call with first_slot > 0) keeps a running scale:
+ * scale' = max(scale, amax_new/448); when the scale grows, the codes already in slots below
+ * first_slot are re-encoded as RNE(value(code) * scale / scale'), product and quotient in float;
+ * the scale never shrinks.  Returns 0 or a negative code as in oracle_flatten_tree. */
 int oracle_kv_write(orc_pool *p, void *k_pages, void *v_pages, float *k_scale, float *v_scale,
                     const int32_t *page_ids, int32_t first_slot, int32_t n_tokens, const void *k_src,
                     const void *v_src, int32_t src_dtype) {
     int H = p->num_kv_heads;
     if (n_tokens < 0 || first_slot < 0 || first_slot >= ORC_PAGE) return -1;
-    if (p->dtype == ORC_FP8_E4M3 && first_slot != 0) return -1;
     if (p->dtype == ORC_BF16 && src_dtype != ORC_BF16) return -1;
     int n_pg = (first_slot + n_tokens + ORC_PAGE - 1) / ORC_PAGE;
     for (int i = 0; i < n_pg; ++i)
@@ -269,27 +271,43 @@ int oracle_kv_write(orc_pool *p, void *k_pages, void *v_pages, float *k_scale, f
     }
     for (int i = 0; i < n_pg; ++i) {
         int page = page_ids[i];
-        int t0 = i * ORC_PAGE, t1 = t0 + ORC_PAGE < n_tokens ? t0 + ORC_PAGE : n_tokens;
+        int s_lo = i == 0 ? first_slot : 0;                       /* first slot written in this page */
+        int t0 = i == 0 ? 0 : i * ORC_PAGE - first_slot;           /* token that lands in slot s_lo */
+        int t1 = (i + 1) * ORC_PAGE - first_slot < n_tokens ? (i + 1) * ORC_PAGE - first_slot : n_tokens;
         for (int h = 0; h < H; ++h)
             for (int which = 0; which < 2; ++which) {
                 const void *src = which ? v_src : k_src;
+                uint8_t *codes = (uint8_t *)(which ? v_pages : k_pages);
+                float *scales = which ? v_scale : k_scale;
                 float amax = 0.0f;
                 for (int t = t0; t < t1; ++t)
                     for (int d = 0; d < ORC_D; ++d) {
                         float a = fabsf(src_as_float(src, src_dtype, ((size_t)t * H + h) * ORC_D + d));
                         if (a > amax) amax = a;
                     }
-                float scale = amax > 0.0f ? amax / 448.0f : 1.0f;
-                (which ? v_scale : k_scale)[(size_t)page * H + h] = scale;
+                float scale;
+                if (s_lo == 0) {
+                    scale = amax > 0.0f ? amax / 448.0f : 1.0f;
+                } else {
+                    float old = scales[(size_t)page * H + h];
+                    float cand = amax > 0.0f ? amax / 448.0f : 0.0f;
+                    scale = old >= cand ? old : cand;   /* an unset (NaN) old scale gives cand */
+                    if (!(scale > 0.0f)) scale = 1.0f;
+                    if (scale > old)
+                        for (int sl = 0; sl < s_lo; ++sl)
+                            for (int d = 0; d < ORC_D; ++d) {
+                                size_t off = which ? v_offset(p, page, h, sl, d) : k_offset(p, page, h, sl, d);
+                                float v = (float)orc_e4m3_value(codes[off]) * old;
+                                codes[off] = orc_e4m3_encode(v / scale);
+                            }
+                }
+                scales[(size_t)page * H + h] = scale;
                 for (int t = t0; t < t1; ++t)
                     for (int d = 0; d < ORC_D; ++d) {
                         float x = src_as_float(src, src_dtype, ((size_t)t * H + h) * ORC_D + d);
                         float y = x / scale;
-                        uint8_t c = orc_e4m3_encode(y);
-                        if (which)
-                            ((uint8_t *)v_pages)[v_offset(p, page, h, t - t0, d)] = c;
-                        else
-                            ((uint8_t *)k_pages)[k_offset(p, page, h, t - t0, d)] = c;
+                        size_t off = which ? v_offset(p, page, h, s_lo + (t - t0), d) : k_offset(p, page, h, s_lo + (t - t0), d);
+                        codes[off] = orc_e4m3_encode(y);
                     }
             }
     }

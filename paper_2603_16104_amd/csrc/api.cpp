@@ -233,8 +233,6 @@ extern "C" int kv_pool_write(hkv_pool *pool, const int32_t *page_ids, int32_t fi
     if (!page_ids || !k_src || !v_src) return fail(HKV_EINVAL, "kv_pool_write: null argument");
     if ((reinterpret_cast<uintptr_t>(k_src) | reinterpret_cast<uintptr_t>(v_src)) & 15)
         return fail(HKV_EINVAL, "kv_pool_write: k_src and v_src must be 16-byte aligned");
-    if (pool->d.dtype == HKV_FP8_E4M3 && first_slot != 0)
-        return fail(HKV_EINVAL, "kv_pool_write: fp8 pools are written from slot 0 of a page (first_slot %d)", first_slot);
     int64_t n_pg = ((int64_t)first_slot + n_tokens + HKV_PAGE_SIZE - 1) / HKV_PAGE_SIZE;
     if (n_pg > hkv_pool::kMaxWritePages)
         return fail(HKV_EINVAL, "kv_pool_write: %lld pages in one call (limit %d)", (long long)n_pg,

@@ -1,6 +1,9 @@
 // Scatter of new tokens' K/V into the pool's block format (one workgroup per touched page and KV
 // head).  bf16 pools: plain re-ordering.  fp8 pools: per-block amax, scale = amax/448, codes =
-// round-to-nearest-even(x / scale) saturated to +-448 (OCP e4m3), all in float.
+// round-to-nearest-even(x / scale) saturated to +-448 (OCP e4m3), all in float.  A block that is
+// continued (the call starts at first_slot > 0 of its first page) keeps a running scale:
+// scale' = max(scale, amax_new/448); when the scale grows, the codes already in the slots below
+// first_slot are re-encoded as RNE(value(code) * scale / scale'); the scale never shrinks.
 // (The "compute a prefix's KV once and keep it in GPU memory" step of Section 5, "Proactive Cache
 // Management", seen from the pool.)
 #include "hkv_device.h"
@@ -27,7 +30,7 @@ template <int DT>
 __global__ __launch_bounds__(256) void pool_write_kernel(PoolWriteLaunch a) {
     __shared__ uint16_t sV[kPage][kHeadDim + 8];
     __shared__ float sRed[2][4];
-    __shared__ float sScale[2];
+    __shared__ float sScale[2], sOld[2];
 
     const int pi = blockIdx.x, h = blockIdx.y;
     const int tid = threadIdx.x;
@@ -91,14 +94,37 @@ __global__ __launch_bounds__(256) void pool_write_kernel(PoolWriteLaunch a) {
             sRed[1][tid >> 6] = va;
         }
         __syncthreads();
+        const bool append = s_lo > 0;  // slots below s_lo of this block hold codes of an earlier call
         if (tid < 2) {
             const float am = fmaxf(fmaxf(sRed[tid][0], sRed[tid][1]), fmaxf(sRed[tid][2], sRed[tid][3]));
-            const float sc = am > 0.f ? am / 448.0f : 1.0f;
+            float *scales = tid ? a.v_scale : a.k_scale;
+            float sc, old = 0.f;
+            if (!append) {
+                sc = am > 0.f ? am / 448.0f : 1.0f;
+            } else {
+                old = scales[(size_t)page * a.num_kv_heads + h];
+                const float cand = am > 0.f ? am / 448.0f : 0.f;
+                sc = old >= cand ? old : cand;  // an unset (NaN) old scale gives cand
+                if (!(sc > 0.f)) sc = 1.0f;
+            }
             sScale[tid] = sc;
-            (tid ? a.v_scale : a.k_scale)[(size_t)page * a.num_kv_heads + h] = sc;
+            sOld[tid] = old;
+            scales[(size_t)page * a.num_kv_heads + h] = sc;
         }
         __syncthreads();
         const float ksc = sScale[0], vsc = sScale[1];
+        const bool k_grew = append && ksc > sOld[0], v_grew = append && vsc > sOld[1];
+        auto reencode4 = [](uint32_t w, float old, float sc) {  // four codes: value * old / sc, rounded again
+            const auto lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, false), hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, true);
+            return quant4(lo[0] * old, lo[1] * old, hi[0] * old, hi[1] * old, sc);
+        };
+        if (k_grew && slot < s_lo) {
+            uint8_t *kdst = static_cast<uint8_t *>(a.k_pages) + blk + (d0 >> 6) * (kPage * 64) + slot * 64 + (d0 & 63);
+            u32x2 c = *reinterpret_cast<u32x2 *>(kdst);
+            c[0] = reencode4(c[0], sOld[0], ksc);
+            c[1] = reencode4(c[1], sOld[0], ksc);
+            *reinterpret_cast<u32x2 *>(kdst) = c;
+        }
         if (valid) {
             u32x2 c;
             c[0] = quant4(kf[0], kf[1], kf[2], kf[3], ksc);
@@ -117,9 +143,18 @@ __global__ __launch_bounds__(256) void pool_write_kernel(PoolWriteLaunch a) {
         if (s_lo <= half * 8 && s_hi >= half * 8 + 8) {
             *reinterpret_cast<u32x2 *>(vdst) = c;
         } else {
+            u32x2 r = {0u, 0u};  // the earlier codes of these eight slots, re-encoded if the scale grew
+            if (v_grew && half * 8 < s_lo) {
+                r = *reinterpret_cast<u32x2 *>(vdst);
+                r[0] = reencode4(r[0], sOld[1], vsc);
+                r[1] = reencode4(r[1], sOld[1], vsc);
+            }
             for (int j = 0; j < 8; ++j) {
                 const int sl = half * 8 + j;
-                if (sl >= s_lo && sl < s_hi) vdst[j] = (uint8_t)(c[j >> 2] >> (8 * (j & 3)));
+                if (sl >= s_lo && sl < s_hi)
+                    vdst[j] = (uint8_t)(c[j >> 2] >> (8 * (j & 3)));
+                else if (v_grew && sl < s_lo)
+                    vdst[j] = (uint8_t)(r[j >> 2] >> (8 * (j & 3)));
             }
         }
     }

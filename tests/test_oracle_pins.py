@@ -550,3 +550,61 @@ def test_fp8_pool_write_quantisation(oracle):
         assert np.abs(o[0, h] - bo).max() <= 1e-12 and abs(l[0, h] - bl) <= 1e-12
     # quantisation error of the round trip stays within half an e4m3 step (relative 2^-4) of amax scale
     assert np.abs(deq_k - kf).max() <= np.abs(kf).max() * 2.0 ** -4
+
+
+def test_fp8_append_running_scale(oracle):
+    """Continuing an fp8 page (first_slot > 0).  Pinned by what the rule must reduce to:
+    (a) tokens whose magnitude does not exceed the page's amax leave scale and earlier codes untouched,
+        and the page ends up byte-identical to writing all its tokens in one call (that path is pinned
+        against the library float8 conversion above);
+    (b) a louder token raises the scale to amax_new/448 exactly, maps itself to +-448, and moves every
+        earlier dequantised value by at most half a step of the new grid at that value;
+    (c) the scale never shrinks."""
+    import torch
+    rng = np.random.default_rng(9)
+    H = 2
+    x = rng.standard_normal((16, H, D)).astype(np.float32)
+    x[0, :, 0] = 5.0                                   # the page's amax sits in its first token
+    kb = wl.f32_to_bf16_bits(x)
+    whole = oracle.HostPool(3, H, oracle.FP8_E4M3)
+    whole.write([1], 0, kb, kb)
+    grown = oracle.HostPool(3, H, oracle.FP8_E4M3)
+    for a, b in ((0, 1), (1, 2), (2, 9), (9, 16)):
+        grown.write([1], a, kb[a:b], kb[a:b])
+    assert np.array_equal(grown.k, whole.k) and np.array_equal(grown.v, whole.v)          # (a)
+    assert np.array_equal(grown.k_scale[H:2 * H], whole.k_scale[H:2 * H])
+    assert np.all(grown.k_scale[H:2 * H] == np.float32(5.0) / np.float32(448.0))
+
+    lut = np.array([oracle.e4m3_value(c) for c in range(256)])
+    p = oracle.HostPool(3, H, oracle.FP8_E4M3)
+    quiet = wl.f32_to_bf16_bits((0.1 * rng.standard_normal((5, H, D))).astype(np.float32))
+    p.write([2], 0, quiet, quiet)
+    s_old = p.k_scale[2 * H: 3 * H].copy()
+    blk = lambda pool: pool.k.reshape(3, H, 2, PAGE, 64)[2]           # [head][chunk][slot][64]
+    before = lut[blk(p)[:, :, :5]] * s_old[:, None, None, None].astype(np.float64)
+    loud = np.zeros((1, H, D), dtype=np.float32)
+    loud[0, :, 3] = [-7.0, 3.5]
+    loud_b = wl.f32_to_bf16_bits(loud)
+    p.write([2], 5, loud_b, loud_b)
+    s_new = p.k_scale[2 * H: 3 * H]
+    assert np.array_equal(s_new, (np.float32([7.0, 3.5]) / np.float32(448.0)).astype(np.float32))      # (b)
+    assert blk(p)[0, 0, 5, 3] == 0xFE and blk(p)[1, 0, 5, 3] == 0x7E                  # -448 and +448
+    after = lut[blk(p)[:, :, :5]] * s_new[:, None, None, None].astype(np.float64)
+    # half a step of the e4m3 grid at magnitude m is at most m * 2^-4 (normal range) or 2^-10 (subnormal), times the scale
+    step = np.maximum(np.abs(before) * 2.0 ** -4, 2.0 ** -10 * s_new[:, None, None, None])
+    assert np.all(np.abs(after - before) <= step * (1 + 1e-6))
+    assert np.abs(after - before).max() > 0                                         # it really was re-encoded
+    # reference for the re-encoding itself: the library float8 conversion of value * s_old / s_new
+    for h in range(H):
+        v = (lut[grown_codes := blk(oracle_pool_copy(oracle, quiet, H))[h, :, :5]].astype(np.float32) * s_old[h]) / s_new[h]
+        ref = torch.from_numpy(v.astype(np.float32)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+        assert np.array_equal(blk(p)[h, :, :5], ref)
+    p.write([2], 6, quiet[:3], quiet[:3])
+    assert np.array_equal(p.k_scale[2 * H: 3 * H], s_new)                              # (c)
+
+
+def oracle_pool_copy(oracle, quiet, H):
+    """The page of the test above as it was before the loud token (a fresh pool written the same way)."""
+    q = oracle.HostPool(3, H, oracle.FP8_E4M3)
+    q.write([2], 0, quiet, quiet)
+    return q
