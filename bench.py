@@ -275,7 +275,9 @@ def main() -> int:
             sx, nx, mx, hx, ix = bench_decode(runtime, hkv, wx, max(1, min(args.steps, 20)), 3,
                                               1 if name == "c5" else args.pools, 5)
             print(json.dumps({"workload": wx.name, "ms_per_step": round(sx * 1e3, 5),
-                              "unique_kv_GBps": round(wx.unique_kv_bytes() / sx / 1e9, 2), **ix}), flush=True)
+                              "unique_kv_GBps": round(wx.unique_kv_bytes() / sx / 1e9, 2),
+                              "node_kernel_ms_single_event_pair": round(nx, 5),
+                              "merge_kernel_ms_single_event_pair": round(mx, 5), **ix}), flush=True)
         return 0
 
     w = wl.config2()
