@@ -160,6 +160,7 @@ def bench_workflow(runtime, hkv, wl, shape: str):
     r = runtime.WorkflowRunner(wf)
     capacity = 1 << 16
     n = wf.n_calls
+    longest_pages = max(len(runtime.workflow_prompt_tokens(wf, c)) for c in range(n)) // 16 + 1
     helium = hkv.trt_schedule(r.tree, 1, capacity)[0][0]
     orders = {
         "cache_aware_schedule": (helium, True),
@@ -184,6 +185,10 @@ def bench_workflow(runtime, hkv, wl, shape: str):
             ms.append(ev0.elapsed_time(ev1))
         res["orders"][name] = {"prefill_usage_tokens": int(sum(usage)),
                                "total_token_step_times_M": T, "gpu_ms": round(min(ms), 3)}
+        if cache:   # block-level LRU prefix cache with room for two of the longest prompts (host bookkeeping only)
+            sim = runtime.simulate_prefix_cache(wf, seq, 2 * longest_pages)
+            res["orders"][name]["lru_cache_hit_rate"] = round(sim["hit_rate"], 4)
+            res["orders"][name]["lru_cache_evictions"] = sim["evictions"]
     r.close()
     return res
 

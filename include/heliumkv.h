@@ -301,6 +301,39 @@ int attn_prefill_with_prefix(hkv_pool *pool, const void *q, const int32_t *cu_q,
 size_t attn_prefill_workspace_bytes(int32_t total_q, int32_t num_q_heads);
 
 /* ------------------------------------------------------------------------------------------
+ * Block-level prefix cache over a pool (host bookkeeping only; Section 6, "LLM Engine
+ * Integration": prefixes are kept block by block, precomputed ones are pinned, blocks are evicted
+ * least recently used first and a prefix never before its extensions, an evicted prefix is
+ * recomputed by the next call that needs it).
+ * A block is 16 tokens; its identity is (preceding block, its 16 token ids).  Only full blocks are
+ * shared; a sequence's partial last block is private.  The cache takes its pages from the pool
+ * (kv_pool_alloc: lowest free id first) and holds one pool reference per page it owns.
+ * Evictable = no live sequence uses it, not pinned, no cached block extends it; among those the
+ * oldest last use goes first, ties by lower page id; the clock ticks once per acquire / release. */
+typedef struct hkv_cache hkv_cache;
+int kv_cache_create(hkv_pool *pool, hkv_cache **out);
+int kv_cache_destroy(hkv_cache *cache); /* returns every page it holds to the pool */
+/* Looks up the longest cached prefix of tokens (host, n_tokens ids) in whole blocks, takes a
+ * reference on each hit, and gives every remaining block a page (free list first, then by
+ * eviction); new full blocks enter the cache at once, so the caller must fill them (kv_pool_write
+ * of tokens n_cached_tokens .. n_tokens-1, then attn_prefill_with_prefix) before anyone else hits
+ * them.  page_ids (host, ceil(n_tokens/16) entries) receives the sequence's block table;
+ * n_cached_tokens the number of leading tokens whose KV is already there.  pin != 0 also pins all
+ * full blocks of the sequence.  ENOMEM if no page is free and nothing can be evicted: then the call
+ * gives back what it took and holds nothing. */
+int kv_cache_acquire(hkv_cache *cache, const int32_t *tokens, int32_t n_tokens, int32_t pin, int32_t *page_ids,
+                     int32_t *n_cached_tokens);
+/* Ends a sequence's use of its pages (the list kv_cache_acquire returned): full blocks stay cached
+ * and become evictable once nobody else uses them; the private partial page returns to the pool.
+ * ERANGE if a page is not held by any sequence. */
+int kv_cache_release(hkv_cache *cache, const int32_t *page_ids, int32_t n_pages);
+/* Drops one pin from each listed page that is pinned (others are ignored). */
+int kv_cache_unpin(hkv_cache *cache, const int32_t *page_ids, int32_t n_pages);
+/* Counters since creation (any pointer may be NULL). */
+int kv_cache_stats(const hkv_cache *cache, int64_t *cached_blocks, int64_t *hits, int64_t *misses,
+                   int64_t *evictions);
+
+/* ------------------------------------------------------------------------------------------
  * Scheduling layer (host only, integers only): templated radix tree, token-step cost model and
  * cache-aware scheduling (Section 5: "Modeling Prompt Structure with a Templated Radix Tree",
  * "Scheduling Problem Formulation" with its token-usage and precedence-delay equations, the

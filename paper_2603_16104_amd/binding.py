@@ -32,6 +32,7 @@ EXPORTS = [
     "attn_decode_prefix_tree", "attn_decode_workspace_bytes", "hkv_prefill_plan_create", "hkv_prefill_plan_destroy",
     "hkv_prefill_plan_num_tiles", "hkv_prefill_plan_tiles", "attn_prefill_plan_run", "attn_prefill_with_prefix",
     "attn_prefill_workspace_bytes", "hkv_mfma_probe", "hkv_hbm_read_probe",
+    "kv_cache_create", "kv_cache_destroy", "kv_cache_acquire", "kv_cache_release", "kv_cache_unpin", "kv_cache_stats",
     "trt_build", "trt_destroy", "trt_num_nodes", "trt_num_syms", "trt_num_calls", "trt_nodes", "trt_prefill_usage",
     "trt_evaluate", "trt_schedule",
 ]
@@ -402,3 +403,43 @@ def trt_schedule(tree, n_workers: int, capacity: int):
     _check(lib().trt_schedule(tree, C.c_int32(n_workers), C.c_int64(capacity), _hp(indptr), _hp(flat), _hp(B), _hp(Cc),
                               C.byref(T)))
     return [flat[indptr[i]:indptr[i + 1]].tolist() for i in range(n_workers)], B, Cc, int(T.value)
+
+
+# ---------------------------------------------------------------------------------------------
+# block-level prefix cache (host only)
+
+
+def kv_cache_create(pool) -> C.c_void_p:
+    out = C.c_void_p()
+    _check(lib().kv_cache_create(pool, C.byref(out)))
+    return out
+
+
+def kv_cache_destroy(cache) -> None:
+    _check(lib().kv_cache_destroy(cache))
+
+
+def kv_cache_acquire(cache, tokens, pin: bool = False):
+    """Returns (page ids of the sequence's blocks, number of leading tokens already cached)."""
+    tokens = _host_i32(tokens)
+    pages = np.zeros((len(tokens) + PAGE_SIZE - 1) // PAGE_SIZE, dtype=np.int32)
+    cached = C.c_int32(0)
+    _check(lib().kv_cache_acquire(cache, _hp(tokens), C.c_int32(len(tokens)), C.c_int32(1 if pin else 0), _hp(pages),
+                                  C.byref(cached)))
+    return pages, int(cached.value)
+
+
+def kv_cache_release(cache, pages) -> None:
+    pages = _host_i32(pages)
+    _check(lib().kv_cache_release(cache, _hp(pages), C.c_int32(len(pages))))
+
+
+def kv_cache_unpin(cache, pages) -> None:
+    pages = _host_i32(pages)
+    _check(lib().kv_cache_unpin(cache, _hp(pages), C.c_int32(len(pages))))
+
+
+def kv_cache_stats(cache) -> dict:
+    v = [C.c_int64(0) for _ in range(4)]
+    _check(lib().kv_cache_stats(cache, *[C.byref(x) for x in v]))
+    return dict(zip(("cached_blocks", "hits", "misses", "evictions"), (int(x.value) for x in v)))

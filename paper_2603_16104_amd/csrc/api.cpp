@@ -200,10 +200,13 @@ extern "C" int kv_pool_retain(hkv_pool *pool, int32_t n, const int32_t *ids) {
 
 extern "C" int kv_pool_release(hkv_pool *pool, int32_t n, const int32_t *ids) {
     if (int rc = check_held(pool, n, ids, "kv_pool_release")) return rc;
-    std::vector<int32_t> drop(n ? pool->d.num_pages : 0, 0);
-    for (int i = 0; i < n; ++i)
-        if (++drop[ids[i]] > pool->refcnt[ids[i]])
-            return fail(HKV_EINVAL, "kv_pool_release: page %d released more often than it is held", ids[i]);
+    std::vector<int32_t> sorted(ids, ids + n);  // a page may occur several times: count per page
+    std::sort(sorted.begin(), sorted.end());
+    for (int i = 0, run = 0; i < n; ++i) {
+        run = (i > 0 && sorted[i] == sorted[i - 1]) ? run + 1 : 1;
+        if (run > pool->refcnt[sorted[i]])
+            return fail(HKV_EINVAL, "kv_pool_release: page %d released more often than it is held", sorted[i]);
+    }
     for (int i = 0; i < n; ++i)
         if (--pool->refcnt[ids[i]] == 0) pool->free_list.push_back(ids[i]);
     return HKV_OK;

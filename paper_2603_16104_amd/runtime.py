@@ -221,3 +221,38 @@ class WorkflowRunner:
             hkv.trt_destroy(self.tree)
             self.tree = None
         self.pool.close()
+
+
+def workflow_prompt_tokens(wf: wl.Workflow, call: int) -> list:
+    """The call's full prompt as token ids: static symbols as they are, a placeholder for call x as
+    len_out[x] ids that nothing else uses (what the LLM wrote is not known; only that it is the same
+    text wherever it is quoted)."""
+    out = []
+    for s in wf.templates[call]:
+        if s >= 0:
+            out.append(int(s))
+        else:
+            x = -(s + 1)
+            out.extend(range((1 << 24) + x * 65536, (1 << 24) + x * 65536 + wf.len_out[x]))
+    return out
+
+
+def simulate_prefix_cache(wf: wl.Workflow, sequence, n_pages: int) -> dict:
+    """Host-only: runs the calls of `sequence` one after another through the block-level prefix cache
+    (acquire, then release when the call is done) over a pool of n_pages pages and reports the
+    prefix-cache hit rate = cached prompt tokens / prompt tokens.  No device memory is touched."""
+    pool = hkv.kv_pool_create(n_pages, 1, hkv.BF16, 0x1000, 0x2000)   # addresses are never dereferenced here
+    cache = hkv.kv_cache_create(pool)
+    hit = total = 0
+    try:
+        for c in sequence:
+            toks = workflow_prompt_tokens(wf, c)
+            pages, cached = hkv.kv_cache_acquire(cache, toks)
+            hit += cached
+            total += len(toks)
+            hkv.kv_cache_release(cache, pages)
+        st = hkv.kv_cache_stats(cache)
+    finally:
+        hkv.kv_cache_destroy(cache)
+        hkv.kv_pool_destroy(pool)
+    return {"hit_rate": hit / max(total, 1), "prompt_tokens": total, "evictions": st["evictions"]}

@@ -31,7 +31,7 @@ def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "heliumkv.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b([a-z_0-9]+)\s*\(", header)) - {"defined", "sizeof"}
-    declared = {d for d in declared if d.startswith(("kv_pool", "hkv_", "prefix_tree", "attn_", "lse_merge", "trt_"))}
+    declared = {d for d in declared if d.startswith(("kv_pool", "hkv_", "prefix_tree", "attn_", "lse_merge", "trt_", "kv_cache"))}
     assert len(declared) >= 30
     L = hkv.lib()
     for name in sorted(declared):
