@@ -545,3 +545,45 @@ def test_decode_several_query_tokens_many_rows(gpu, oracle):
     only in the leaves."""
     w = wl.config2(seed=78, n_req=40, root_tokens=640, private_tokens=100)
     run_decode_multi(gpu, oracle, w, 2)
+
+
+def test_decode_and_prefill_runs_are_graph_capturable(gpu, oracle):
+    """attn_decode_plan_run and attn_prefill_plan_run only queue kernels (no allocation, no copies, no
+    memset nodes), so a caller may capture them in a HIP graph: several replays, with eager work and
+    synchronisation in between, must each reproduce the eager result."""
+    import torch
+    w = wl.config2(seed=91, n_req=12, root_tokens=320, private_tokens=70)
+    hp, dp = both_pools(gpu, oracle, w)
+    r = gpu.DecodeRunner(dp, w)
+    pre, _ = wl.config1()
+    dp2 = gpu.DevicePool(pre.num_pages, pre.num_kv_heads, pre.kv_dtype)
+    dp2.fill_from(pre)
+    pr = gpu.PrefillRunner(dp2, pre)
+    r.run()
+    pr.run()
+    torch.cuda.synchronize()
+    ref_d, ref_l, ref_p = r.out.clone(), r.lse.clone(), pr.out.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):          # warm-up on the capture stream
+        r.run()
+        pr.run()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        r.run()
+        pr.run()
+    for rep in range(4):
+        r.out.fill_(7)
+        r.lse.fill_(3.0)
+        pr.out.fill_(9)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(r.out, ref_d) and torch.equal(r.lse, ref_l) and torch.equal(pr.out, ref_p), f"replay {rep}"
+        (r.out.float().sum() + pr.out.float().sum()).item()      # eager work between replays
+    r.close()
+    pr.close()
+    dp.close()
+    dp2.close()
