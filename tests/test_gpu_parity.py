@@ -587,3 +587,39 @@ def test_decode_and_prefill_runs_are_graph_capturable(gpu, oracle):
     pr.close()
     dp.close()
     dp2.close()
+
+
+@pytest.mark.parametrize("late_key", [False, True])
+def test_prefill_prefix_longer_than_the_page_id_window(gpu, oracle, late_key):
+    """A cached prefix of 33 400 tokens (2 088 pages): the kernel keeps 2 048 page ids in LDS at a time and
+    must refill that window on the way; with late_key a dominant key sits behind the refill point, so the
+    running-maximum fallback crosses it as well."""
+    import torch
+    n_prefix, n_new = 33400 // 16 * 16, 70
+    n_pages = (n_prefix + n_new + 15) // 16 + 3
+    f = wl.make_forest([-1, 0], [n_prefix, n_new], [1], np.random.default_rng(6).permutation(n_pages).astype(np.int32))
+    base = wl.Workload(name=f"long_prefix_{late_key}", num_q_heads=4, num_kv_heads=1, kv_dtype=wl.KV_BF16,
+                       num_pages=n_pages, seed=17, forest=f, mode="prefill", q_len=np.array([n_new], dtype=np.int32))
+    w = base
+    if late_key:
+        rng = np.random.default_rng(18)
+        u = rng.standard_normal(128).astype(np.float32)
+        u *= np.sqrt(128.0) / np.linalg.norm(u)
+        kv = {}
+        for node in (0, 1):
+            k, v = base.node_kv(node)
+            kv[node] = (wl.bf16_bits_to_f32(k) * 0.05, wl.bf16_bits_to_f32(v))
+        kv[0][0][33000] = 9.0 * u                     # ~100 nats above everything before it
+        q = np.broadcast_to(u, (n_new, 4, 128)).astype(np.float32) + 0.05 * rng.standard_normal((n_new, 4, 128)).astype(np.float32)
+        w = _FixedWorkload(base, {n: (wl.f32_to_bf16_bits(a), wl.f32_to_bf16_bits(b)) for n, (a, b) in kv.items()},
+                           wl.f32_to_bf16_bits(q))
+    hp, dp = both_pools(gpu, oracle, w)
+    exp_o, exp_l = oracle.run_workload(w, hp)
+    r = gpu.PrefillRunner(dp, w)
+    r.run()
+    torch.cuda.synchronize()
+    got_o, got_l = gpu.bf16_tensor_to_f64(r.out), r.lse.cpu().numpy()
+    r.close()
+    dp.close()
+    check_close(got_o, exp_o, w.name)
+    assert np.abs(got_l - exp_l).max() <= 2e-3 + 1e-6 * np.abs(exp_l).max()
