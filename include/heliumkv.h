@@ -64,6 +64,13 @@ enum {
     HKV_EHIP = -6    /* a HIP runtime call failed (message holds the HIP error string) */
 };
 
+/* Pool element types.  bf16 and fp8 pools are the throughput paths (matrix cores, bf16 q and out).
+ * An fp32 pool selects the full-precision path: k_src / v_src of kv_pool_write, q, and out of the
+ * attention calls are then fp32 as well, all arithmetic is fp32 on the vector ALUs, one wavefront
+ * per (query token, query head) without sharing between requests, no workspace is needed, and
+ * results agree with exact attention to about 1e-6 (the bound asked of fp32 inputs is 1e-4).
+ * fp32 block format: K in 64-byte chunks of 16 floats ((d/16)*256 + slot*16 + d%16), V
+ * dimension-major (d*16 + slot). */
 enum { HKV_BF16 = 0, HKV_FP8_E4M3 = 1, HKV_FP32 = 2 };
 
 typedef struct hkv_pool hkv_pool;

@@ -78,6 +78,10 @@ struct hkv_decode_plan {
     // several query tokens per request: n_req above counts query rows (requests x tokens_per_req)
     int32_t tokens_per_req = 1;
     int32_t *d_row_leaf = nullptr, *d_row_limit = nullptr;  // one allocation (d_row_leaf), null when tokens_per_req == 1
+    // fp32 pools: no work items; every query row walks its own block table (one allocation: d_bt)
+    std::vector<int32_t> row_len;
+    int32_t max_pages = 0;
+    int32_t *d_bt = nullptr, *d_rows_req = nullptr, *d_rows_len = nullptr;
 };
 
 struct hkv_prefill_plan {
@@ -88,6 +92,7 @@ struct hkv_prefill_plan {
     void *dev = nullptr;
     PrefillTile *d_tiles = nullptr;
     int32_t *d_block_table = nullptr;
+    int32_t *d_rows_req = nullptr, *d_rows_len = nullptr;  // fp32 pools: per new token (one allocation: d_rows_req)
 };
 
 struct hkv_pool {
@@ -119,8 +124,8 @@ extern "C" int kv_pool_create(const hkv_pool_desc *desc, hkv_pool **out) {
     if (desc->page_size != HKV_PAGE_SIZE || desc->head_dim != HKV_HEAD_DIM)
         return fail(HKV_ESHAPE, "kv_pool_create: page_size must be 16 and head_dim 128 (got %d, %d)",
                     desc->page_size, desc->head_dim);
-    if (desc->dtype != HKV_BF16 && desc->dtype != HKV_FP8_E4M3)
-        return fail(HKV_ESHAPE, "kv_pool_create: pool dtype %d is not storable (bf16 or fp8 e4m3)", desc->dtype);
+    if (desc->dtype != HKV_BF16 && desc->dtype != HKV_FP8_E4M3 && desc->dtype != HKV_FP32)
+        return fail(HKV_ESHAPE, "kv_pool_create: pool dtype %d (bf16, fp8 e4m3 or fp32)", desc->dtype);
     if (desc->num_pages <= 0 || desc->num_kv_heads <= 0)
         return fail(HKV_EINVAL, "kv_pool_create: num_pages and num_kv_heads must be positive");
     if (!desc->k_pages || !desc->v_pages) return fail(HKV_EINVAL, "kv_pool_create: null page buffer");
@@ -260,7 +265,10 @@ extern "C" int kv_pool_write(hkv_pool *pool, const int32_t *page_ids, int32_t fi
     HKV_HIP(hipMemcpyAsync(d, h, sizeof(int32_t) * (size_t)n_pg, hipMemcpyHostToDevice, s));
     PoolWriteLaunch a{pool->d.k_pages, pool->d.v_pages, pool->d.k_scale, pool->d.v_scale, pool->d.num_kv_heads,
                       pool->d.dtype, d, (int32_t)n_pg, first_slot, n_tokens, k_src, v_src};
-    HKV_HIP(launch_pool_write(a, s));
+    if (pool->d.dtype == HKV_FP32)
+        HKV_HIP(launch_pool_write_fp32(a, s));
+    else
+        HKV_HIP(launch_pool_write(a, s));
     HKV_HIP(hipEventRecord(pool->slot_free[slot], s));
     pool->slot_in_flight[slot] = true;
     return HKV_OK;
@@ -514,6 +522,38 @@ static int upload_decode_plan(hkv_decode_plan &pl) {
     return HKV_OK;
 }
 
+// fp32 pools: per-row block tables (root-to-leaf page lists) and lengths instead of work items
+static int build_fp32_rows(hkv_decode_plan &pl, bool upload) {
+    const int n = pl.n_req;
+    std::vector<std::vector<int32_t>> paths(n);
+    pl.row_len.assign(n, 0);
+    pl.max_pages = 1;
+    for (int r = 0; r < n; ++r) {
+        std::vector<int32_t> chain;
+        for (int v = pl.req_leaf[r]; v >= 0; v = pl.nodes[v].parent) chain.push_back(v);
+        for (auto it = chain.rbegin(); it != chain.rend(); ++it) {
+            const hkv_node &nd = pl.nodes[*it];
+            paths[r].insert(paths[r].end(), pl.node_pages.begin() + nd.page_begin, pl.node_pages.begin() + nd.page_begin + nd.n_pages);
+            pl.row_len[r] += nd.n_tokens;
+        }
+        pl.max_pages = std::max<int32_t>(pl.max_pages, (int32_t)paths[r].size());
+    }
+    if (!upload || n == 0) return HKV_OK;
+    std::vector<int32_t> bt((size_t)n * pl.max_pages, 0), req(n);
+    for (int r = 0; r < n; ++r) {
+        std::copy(paths[r].begin(), paths[r].end(), bt.begin() + (size_t)r * pl.max_pages);
+        req[r] = r;
+    }
+    const size_t b_bt = align_up(sizeof(int32_t) * bt.size(), 256), b_n = align_up(sizeof(int32_t) * n, 256);
+    HKV_HIP(hipMalloc((void **)&pl.d_bt, b_bt + 2 * b_n));
+    pl.d_rows_req = reinterpret_cast<int32_t *>(reinterpret_cast<char *>(pl.d_bt) + b_bt);
+    pl.d_rows_len = reinterpret_cast<int32_t *>(reinterpret_cast<char *>(pl.d_bt) + b_bt + b_n);
+    HKV_HIP(hipMemcpy(pl.d_bt, bt.data(), sizeof(int32_t) * bt.size(), hipMemcpyHostToDevice));
+    HKV_HIP(hipMemcpy(pl.d_rows_req, req.data(), sizeof(int32_t) * n, hipMemcpyHostToDevice));
+    HKV_HIP(hipMemcpy(pl.d_rows_len, pl.row_len.data(), sizeof(int32_t) * n, hipMemcpyHostToDevice));
+    return HKV_OK;
+}
+
 extern "C" int hkv_decode_plan_create(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes,
                                       const int32_t *node_pages, int32_t n_node_pages, const int32_t *req_leaf,
                                       int32_t n_req, int32_t num_q_heads, uint32_t flags, hkv_decode_plan **out) {
@@ -544,6 +584,16 @@ extern "C" int hkv_decode_plan_create(hkv_pool *pool, const hkv_node *nodes, int
     pl->nodes.assign(nodes, nodes + n_nodes);
     pl->node_pages.assign(node_pages, node_pages + n_node_pages);
     pl->req_leaf.assign(req_leaf, req_leaf + n_req);
+    if (pool->d.dtype == HKV_FP32) {  // full-precision path: no work items, no partials
+        if (int rc = build_fp32_rows(*pl, !(flags & HKV_PLAN_HOST_ONLY))) {
+            if (pl->d_bt) (void)hipFree(pl->d_bt);
+            delete pl;
+            return rc;
+        }
+        pl->part_count.assign(n_req, 0);
+        *out = pl;
+        return HKV_OK;
+    }
     plan_items(*pl);
     if (!(flags & HKV_PLAN_HOST_ONLY)) {
         if (int rc = upload_decode_plan(*pl)) {
@@ -585,7 +635,17 @@ extern "C" int hkv_decode_plan_create_multi(hkv_pool *pool, const hkv_node *node
             }
             for (int t = 0; t < T; ++t) lim[(size_t)r * T + t] = n_leaf - (T - 1 - t);
         }
-        if (pl->dev && n_req > 0) {
+        if (pool->d.dtype == HKV_FP32) {  // query token t of a request sees all but the T-1-t newest keys
+            for (int r = 0; r < n_req; ++r)
+                for (int t = 0; t < T; ++t) pl->row_len[(size_t)r * T + t] -= T - 1 - t;
+            if (pl->d_rows_len) {
+                hipError_t e = hipMemcpy(pl->d_rows_len, pl->row_len.data(), sizeof(int32_t) * pl->row_len.size(), hipMemcpyHostToDevice);
+                if (e != hipSuccess) {
+                    hkv_decode_plan_destroy(pl);
+                    return fail_hip(e, "hkv_decode_plan_create_multi");
+                }
+            }
+        } else if (pl->dev && n_req > 0) {
             const size_t bytes = sizeof(int32_t) * rows.size();
             hipError_t e = hipMalloc((void **)&pl->d_row_leaf, 2 * bytes);
             if (e == hipSuccess) e = hipMemcpy(pl->d_row_leaf, rows.data(), bytes, hipMemcpyHostToDevice);
@@ -607,6 +667,7 @@ extern "C" int hkv_decode_plan_destroy(hkv_decode_plan *plan) {
     if (!plan) return HKV_OK;
     if (plan->dev) (void)hipFree(plan->dev);  // hipFree waits for work that may still read it
     if (plan->d_row_leaf) (void)hipFree(plan->d_row_leaf);
+    if (plan->d_bt) (void)hipFree(plan->d_bt);
     for (hipEvent_t e : plan->ev)
         if (e) (void)hipEventDestroy(e);
     delete plan;
@@ -614,7 +675,7 @@ extern "C" int hkv_decode_plan_destroy(hkv_decode_plan *plan) {
 }
 
 extern "C" size_t hkv_decode_plan_workspace_bytes(const hkv_decode_plan *plan) {
-    if (!plan) return 0;
+    if (!plan || plan->pool->d.dtype == HKV_FP32) return 0;
     return align_up((size_t)plan->n_parts * HKV_HEAD_DIM * sizeof(float), 256) +
            align_up((size_t)plan->n_parts * sizeof(float), 256);
 }
@@ -647,6 +708,13 @@ extern "C" int attn_decode_plan_run(hkv_decode_plan *plan, const void *q, float 
     if (!q || !out) return fail(HKV_EINVAL, "attn_decode_plan_run: null q or out");
     if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(out)) & 15)
         return fail(HKV_EINVAL, "attn_decode_plan_run: q and out must be 16-byte aligned");
+    if (plan->pool->d.dtype == HKV_FP32) {
+        if (!plan->d_bt) return fail(HKV_EINVAL, "attn_decode_plan_run: plan was built host-only");
+        RowsLaunch a{view_of(plan->pool), static_cast<const float *>(q), plan->d_bt, plan->d_rows_req, plan->d_rows_len,
+                     static_cast<float *>(out), lse_out, plan->n_req, plan->num_q_heads, plan->max_pages, scale};
+        HKV_HIP(launch_rows_fp32(a, static_cast<hipStream_t>(stream)));
+        return HKV_OK;
+    }
     if (!plan->dev) return fail(HKV_EINVAL, "attn_decode_plan_run: plan was built host-only");
     size_t need = hkv_decode_plan_workspace_bytes(plan);
     if (need && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)))
@@ -761,7 +829,7 @@ extern "C" int hkv_prefill_plan_create(hkv_pool *pool, const int32_t *cu_q, cons
     if (num_q_heads <= 0 || num_q_heads % Hkv) return fail(HKV_ESHAPE, "hkv_prefill_plan_create: %d query heads over %d KV heads", num_q_heads, Hkv);
     const int G = num_q_heads / Hkv;
     if (G > 8) return fail(HKV_ESHAPE, "hkv_prefill_plan_create: query/KV head ratio %d (supported: 1..8)", G);
-    if (pool->d.dtype != HKV_BF16) return fail(HKV_ESHAPE, "hkv_prefill_plan_create: prefill reads bf16 pools only");
+    if (pool->d.dtype == HKV_FP8_E4M3) return fail(HKV_ESHAPE, "hkv_prefill_plan_create: prefill reads bf16 and fp32 pools only");
     if (n_req < 0 || max_pages < 0 || (n_req > 0 && (!cu_q || !kv_len || (max_pages > 0 && !block_table))))
         return fail(HKV_EINVAL, "hkv_prefill_plan_create: bad argument");
     if (n_req > 0 && cu_q[0] != 0) return fail(HKV_EINVAL, "hkv_prefill_plan_create: cu_q[0] must be 0");
@@ -820,8 +888,22 @@ extern "C" int hkv_prefill_plan_create(hkv_pool *pool, const int32_t *cu_q, cons
         if (e == hipSuccess)
             e = hipMemcpy(pl->d_block_table, pl->block_table.data(), sizeof(int32_t) * pl->block_table.size(),
                           hipMemcpyHostToDevice);
+        if (e == hipSuccess && pool->d.dtype == HKV_FP32 && pl->total_q > 0) {
+            std::vector<int32_t> rr(2 * (size_t)pl->total_q);
+            for (int r = 0; r < n_req; ++r)
+                for (int i = cu_q[r]; i < cu_q[r + 1]; ++i) {
+                    rr[i] = r;
+                    rr[(size_t)pl->total_q + i] = kv_len[r] - (cu_q[r + 1] - cu_q[r]) + (i - cu_q[r]) + 1;
+                }
+            e = hipMalloc((void **)&pl->d_rows_req, sizeof(int32_t) * rr.size());
+            if (e == hipSuccess) {
+                pl->d_rows_len = pl->d_rows_req + pl->total_q;
+                e = hipMemcpy(pl->d_rows_req, rr.data(), sizeof(int32_t) * rr.size(), hipMemcpyHostToDevice);
+            }
+        }
         if (e != hipSuccess) {
             if (pl->dev) (void)hipFree(pl->dev);
+            if (pl->d_rows_req) (void)hipFree(pl->d_rows_req);
             delete pl;
             return fail_hip(e, "hkv_prefill_plan_create: device upload");
         }
@@ -833,6 +915,7 @@ extern "C" int hkv_prefill_plan_create(hkv_pool *pool, const int32_t *cu_q, cons
 extern "C" int hkv_prefill_plan_destroy(hkv_prefill_plan *plan) {
     if (!plan) return HKV_OK;
     if (plan->dev) (void)hipFree(plan->dev);
+    if (plan->d_rows_req) (void)hipFree(plan->d_rows_req);
     delete plan;
     return HKV_OK;
 }
@@ -856,6 +939,12 @@ extern "C" int attn_prefill_plan_run(hkv_prefill_plan *plan, const void *q, floa
     if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(out)) & 15)
         return fail(HKV_EINVAL, "attn_prefill_plan_run: q and out must be 16-byte aligned");
     if (!plan->dev) return fail(HKV_EINVAL, "attn_prefill_plan_run: plan was built host-only");
+    if (plan->pool->d.dtype == HKV_FP32) {  // full-precision path: one wavefront per (new token, head)
+        RowsLaunch r{view_of(plan->pool), static_cast<const float *>(q), plan->d_block_table, plan->d_rows_req, plan->d_rows_len,
+                     static_cast<float *>(out), lse_out, plan->total_q, plan->num_q_heads, plan->max_pages, scale};
+        HKV_HIP(launch_rows_fp32(r, static_cast<hipStream_t>(stream)));
+        return HKV_OK;
+    }
     PrefillLaunch a{view_of(plan->pool), q, plan->d_tiles, plan->d_block_table, out, lse_out,
                     (int32_t)plan->tiles.size(), plan->num_q_heads, scale};
     HKV_HIP(launch_prefill(a, static_cast<hipStream_t>(stream)));

@@ -94,6 +94,21 @@ struct PoolWriteLaunch {
     const void *v_src;
 };
 
+// fp32 pools: one wavefront per (query token, query head), no sharing (rows_fp32.hip).
+struct RowsLaunch {
+    PoolView pool;
+    const float *q;              // [n_q_tokens][Hq][128] fp32
+    const int32_t *block_table;  // device [n_rows_of_table][max_pages]
+    const int32_t *row_req;      // device [n_q_tokens]: row of the block table
+    const int32_t *row_len;      // device [n_q_tokens]: keys the token sees
+    float *out;                  // [n_q_tokens][Hq][128] fp32
+    float *lse_out;              // may be null
+    int32_t n_q_tokens;
+    int32_t num_q_heads;
+    int32_t max_pages;
+    float scale;
+};
+
 // Largest token count of a decode item that is shared by more than 16 query rows.
 constexpr int kMaxSharedItemTokens = 2048;
 
@@ -102,6 +117,8 @@ int prefill_tile_tokens(int group);
 
 hipError_t launch_pool_write(const PoolWriteLaunch &a, hipStream_t s);
 hipError_t launch_decode(const DecodeLaunch &a, hipStream_t s);
+hipError_t launch_rows_fp32(const RowsLaunch &a, hipStream_t s);
+hipError_t launch_pool_write_fp32(const PoolWriteLaunch &a, hipStream_t s);
 hipError_t launch_prefill(const PrefillLaunch &a, hipStream_t s);
 hipError_t launch_lse_merge(const float *o_parts, const float *lse_parts, const int32_t *row_indptr,
                             const int32_t *part_idx, int32_t n_rows, void *out, int32_t out_dtype,

@@ -11,7 +11,7 @@ from . import binding as hkv
 from . import workloads as wl
 
 # bf16 bit patterns travel as int16 tensors (full torch support); 0x7FC0 is a bf16 NaN, 0x7F the e4m3 NaN
-_ELEM = {hkv.BF16: (torch.int16, 0x7FC0), hkv.FP8_E4M3: (torch.uint8, 0x7F)}
+_ELEM = {hkv.BF16: (torch.int16, 0x7FC0), hkv.FP8_E4M3: (torch.uint8, 0x7F), hkv.FP32: (torch.float32, float("nan"))}
 
 
 class DevicePool:
@@ -74,7 +74,9 @@ def to_device_bits(a: np.ndarray, device="cuda:0") -> torch.Tensor:
 
 
 def bf16_tensor_to_f64(t: torch.Tensor) -> np.ndarray:
-    """bf16 bit patterns (int16 device tensor) -> float64 numpy."""
+    """bf16 bit patterns (int16 device tensor) -> float64 numpy; fp32 tensors pass through."""
+    if t.dtype == torch.float32:
+        return t.cpu().numpy().astype(np.float64)
     b = t.cpu().numpy().view(np.uint16)
     return wl.bf16_bits_to_f32(b).astype(np.float64)
 
@@ -90,7 +92,8 @@ class DecodeRunner:
         dev = pool.k.device
         self.ws = torch.empty(max(self.ws_bytes, 256), dtype=torch.uint8, device=dev)
         self.q = to_device_bits(workload.q(), dev)
-        self.out = torch.zeros((f.n_req, workload.num_q_heads, hkv.HEAD_DIM), dtype=torch.int16, device=dev)
+        odt = torch.float32 if pool.dtype == hkv.FP32 else torch.int16      # fp32 pools: fp32 q and out
+        self.out = torch.zeros((f.n_req, workload.num_q_heads, hkv.HEAD_DIM), dtype=odt, device=dev)
         self.lse = torch.zeros((f.n_req, workload.num_q_heads), dtype=torch.float32, device=dev)
         self.scale = float(workload.scale)
 
@@ -115,7 +118,8 @@ class PrefillRunner:
         dev = pool.k.device
         tq = workload.total_q()
         self.q = to_device_bits(workload.q(), dev)
-        self.out = torch.zeros((tq, workload.num_q_heads, hkv.HEAD_DIM), dtype=torch.int16, device=dev)
+        odt = torch.float32 if pool.dtype == hkv.FP32 else torch.int16      # fp32 pools: fp32 q and out
+        self.out = torch.zeros((tq, workload.num_q_heads, hkv.HEAD_DIM), dtype=odt, device=dev)
         self.lse = torch.zeros((tq, workload.num_q_heads), dtype=torch.float32, device=dev)
         self.scale = float(workload.scale)
 

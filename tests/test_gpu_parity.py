@@ -623,3 +623,70 @@ def test_prefill_prefix_longer_than_the_page_id_window(gpu, oracle, late_key):
     dp.close()
     check_close(got_o, exp_o, w.name)
     assert np.abs(got_l - exp_l).max() <= 2e-3 + 1e-6 * np.abs(exp_l).max()
+
+
+# ------------------------------------------------------------------------------ fp32 pools (full-precision path)
+
+def check_close_fp32(got, exp, name):
+    """The bound asked of fp32 inputs: 1e-4 on both measures."""
+    err = float(np.abs(got - exp).max())
+    rel = float(np.linalg.norm((got - exp).ravel()) / max(np.linalg.norm(exp.ravel()), 1e-30))
+    assert np.isfinite(got).all(), name
+    assert err <= 1e-4 and rel <= 1e-4, f"{name}: max_abs {err:.3e} rel_l2 {rel:.3e}"
+
+
+@pytest.mark.parametrize("seed", [81, 82, 83])
+def test_fp32_pool_decode_and_pool_bytes(gpu, oracle, seed):
+    import torch
+    hq, hkv_ = [(8, 2), (4, 4), (6, 1)][seed % 3]
+    w = wl.random_forest_workload(seed, kv_dtype=wl.KV_FP32, src_dtype="fp32", num_q_heads=hq, num_kv_heads=hkv_, depth=3,
+                                  fanout=3, max_node_pages=7, n_roots=2)
+    hp, dp = both_pools(gpu, oracle, w)
+    assert np.array_equal(dp.k.cpu().numpy().view(np.uint32), hp.k.view(np.uint32))      # NaN poison included
+    assert np.array_equal(dp.v.cpu().numpy().view(np.uint32), hp.v.view(np.uint32))
+    exp_o, exp_l = oracle.run_workload(w, hp)
+    r = gpu.DecodeRunner(dp, w)
+    assert r.ws_bytes == 0
+    r.run()
+    torch.cuda.synchronize()
+    check_close_fp32(gpu.bf16_tensor_to_f64(r.out), exp_o, w.name)
+    got_l = r.lse.cpu().numpy()
+    fin = np.isfinite(exp_l)
+    assert np.array_equal(np.isfinite(got_l), fin) and np.abs(got_l[fin] - exp_l[fin]).max() <= 1e-4
+    r.close()
+    dp.close()
+
+
+@pytest.mark.parametrize("seed", [85, 86])
+def test_fp32_pool_prefill(gpu, oracle, seed):
+    import torch
+    w = wl.random_forest_workload(seed, mode="prefill", kv_dtype=wl.KV_FP32, src_dtype="fp32", num_q_heads=8, num_kv_heads=2,
+                                  depth=3, fanout=2, max_node_pages=9, n_roots=2)
+    hp, dp = both_pools(gpu, oracle, w)
+    exp_o, exp_l = oracle.run_workload(w, hp)
+    r = gpu.PrefillRunner(dp, w)
+    r.run()
+    torch.cuda.synchronize()
+    check_close_fp32(gpu.bf16_tensor_to_f64(r.out), exp_o, w.name)
+    assert np.abs(r.lse.cpu().numpy() - exp_l).max() <= 1e-4
+    r.close()
+    dp.close()
+
+
+def test_fp32_pool_several_query_tokens(gpu, oracle):
+    import torch
+    from paper_2603_16104_amd import binding as hkv
+    w = _multi_forest(wl.KV_FP32, 8, 2, [48, 21, 100], [1, 2, 3, 0])
+    w.src_dtype = "fp32"
+    f, T = w.forest, 3
+    hp, dp = both_pools(gpu, oracle, w)
+    q = np.random.default_rng(2).standard_normal((f.n_req * T, 8, 128)).astype(np.float32)
+    bt, kv_len, *_ = oracle.flatten_workload(w)
+    exp_o, _ = oracle.attn_prefill(hp, q, np.arange(f.n_req + 1, dtype=np.int32) * T, bt, kv_len, float(w.scale))
+    plan = hkv.hkv_decode_plan_create_multi(dp.handle, f.nodes, f.node_pages, f.req_leaf, T, 8)
+    out = torch.zeros((f.n_req * T, 8, 128), dtype=torch.float32, device="cuda")
+    hkv.attn_decode_plan_run(plan, torch.from_numpy(q).cuda(), float(w.scale), out, None, None, 0)
+    torch.cuda.synchronize()
+    check_close_fp32(out.cpu().numpy().astype(np.float64), exp_o, "fp32_multi")
+    hkv.hkv_decode_plan_destroy(plan)
+    dp.close()

@@ -52,8 +52,9 @@ def test_pool_create_validation():
         hkv.kv_pool_create(8, 2, hkv.FP8_E4M3, FAKE_K, FAKE_V)          # scales missing
     assert e.value.code == hkv.ESHAPE
     with pytest.raises(hkv.HkvError) as e:
-        hkv.kv_pool_create(8, 2, hkv.FP32, FAKE_K, FAKE_V)
+        hkv.kv_pool_create(8, 2, 7, FAKE_K, FAKE_V)                    # unknown dtype
     assert e.value.code == hkv.ESHAPE
+    hkv.kv_pool_destroy(hkv.kv_pool_create(8, 2, hkv.FP32, FAKE_K, FAKE_V))
     with pytest.raises(hkv.HkvError) as e:
         hkv.kv_pool_create(8, 2, hkv.BF16, None, FAKE_V)
     assert e.value.code == hkv.EINVAL
