@@ -201,7 +201,7 @@ def cpu_baseline_decode(w, budget_s: float = 20.0):
     bt, kv_len, *_ = orc.flatten_workload(w)
     q = w.q()
     reps, t_total = 0, 0.0
-    while reps < 1 or (t_total < budget_s / 2 and reps < 20):
+    while reps < 1 or (t_total < budget_s / 2 and reps < 500):      # about 10 s of CPU work
         t0 = time.perf_counter()
         orc.attn_decode(hp, q, bt, kv_len, float(w.scale))
         t_total += time.perf_counter() - t0
