@@ -252,9 +252,9 @@ int hkv_decode_plan_part_counts(const hkv_decode_plan *plan, int32_t *part_count
 int attn_decode_plan_run(hkv_decode_plan *plan, const void *q, float scale, void *out, float *lse_out,
                          void *workspace, size_t workspace_bytes, void *stream);
 
-/* Profiling aid.  mode 0: off.  mode 1: attn_decode_plan_run brackets its two kernels with HIP
- * events on the stream it is given (each event costs a few microseconds of dispatch latency that
- * end up inside the intervals).  mode 2: attn_decode_plan_run launches only the per-node kernel
+/* Profiling aid.  mode 0: off.  mode 1: attn_decode_plan_run attaches a begin and an end HIP event
+ * to each of its two kernel dispatches on the stream it is given, so that an interval is the
+ * kernel's own duration on the device, without the gap to its neighbours in the queue.  mode 2: attn_decode_plan_run launches only the per-node kernel
  * and leaves `out` untouched, so that a caller can time a batch of back-to-back launches of that
  * kernel with two events of its own.
  * hkv_decode_plan_elapsed_ms (mode 1) waits for the most recent profiled run to finish and returns

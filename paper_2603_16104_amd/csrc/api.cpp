@@ -74,7 +74,7 @@ struct hkv_decode_plan {
     DecodeItem *d_items = nullptr;
     int32_t *d_pages = nullptr, *d_node_req_idx = nullptr, *d_part_count = nullptr;
     bool profiling = false, profiled_run = false, node_only = false;
-    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};  // begin/end of the node kernel, begin/end of the merge
     // several query tokens per request: n_req above counts query rows (requests x tokens_per_req)
     int32_t tokens_per_req = 1;
     int32_t *d_row_leaf = nullptr, *d_row_limit = nullptr;  // one allocation (d_row_leaf), null when tokens_per_req == 1
@@ -726,21 +726,17 @@ extern "C" int attn_decode_plan_run(hkv_decode_plan *plan, const void *q, float 
     float *lse_parts = reinterpret_cast<float *>(static_cast<char *>(workspace) +
                                                  align_up((size_t)plan->n_parts * HKV_HEAD_DIM * sizeof(float), 256));
     const bool prof = plan->profiling;
-    if (prof) HKV_HIP(hipEventRecord(plan->ev[0], s));
     if (!plan->items.empty()) {
         DecodeLaunch a{view_of(plan->pool), q, plan->d_items, plan->d_pages, plan->d_node_req_idx, o_parts, lse_parts,
                        (int32_t)plan->items.size(), plan->num_q_heads, plan->max_parts, scale, nullptr,
                        plan->d_row_leaf, plan->d_row_limit};
-        HKV_HIP(launch_decode(a, s));
+        HKV_HIP(launch_decode(a, s, prof ? plan->ev[0] : nullptr, prof ? plan->ev[1] : nullptr));
     }
     if (plan->node_only) return HKV_OK;
-    if (prof) HKV_HIP(hipEventRecord(plan->ev[1], s));
     HKV_HIP(launch_lse_merge_dense(o_parts, lse_parts, plan->d_part_count, plan->num_q_heads, plan->max_parts,
-                                   plan->n_req * plan->num_q_heads, out, HKV_BF16, lse_out, s));
-    if (prof) {
-        HKV_HIP(hipEventRecord(plan->ev[2], s));
-        plan->profiled_run = true;
-    }
+                                   plan->n_req * plan->num_q_heads, out, HKV_BF16, lse_out, s,
+                                   prof ? plan->ev[2] : nullptr, prof ? plan->ev[3] : nullptr));
+    if (prof) plan->profiled_run = !plan->items.empty();
     return HKV_OK;
 }
 
@@ -757,9 +753,9 @@ extern "C" int hkv_decode_plan_set_profiling(hkv_decode_plan *plan, int32_t mode
 extern "C" int hkv_decode_plan_elapsed_ms(hkv_decode_plan *plan, float *node_ms, float *merge_ms) {
     if (!plan || !node_ms || !merge_ms) return fail(HKV_EINVAL, "hkv_decode_plan_elapsed_ms: null argument");
     if (!plan->profiled_run) return fail(HKV_EINVAL, "hkv_decode_plan_elapsed_ms: no profiled run has been queued");
-    HKV_HIP(hipEventSynchronize(plan->ev[2]));
+    HKV_HIP(hipEventSynchronize(plan->ev[3]));
     HKV_HIP(hipEventElapsedTime(node_ms, plan->ev[0], plan->ev[1]));
-    HKV_HIP(hipEventElapsedTime(merge_ms, plan->ev[1], plan->ev[2]));
+    HKV_HIP(hipEventElapsedTime(merge_ms, plan->ev[2], plan->ev[3]));
     return HKV_OK;
 }
 

@@ -20,6 +20,8 @@
 // product has consumed the V registers; nothing in the loop waits for all outstanding loads.
 #include <type_traits>
 
+#include <hip/hip_ext.h>
+
 #include "hkv_device.h"
 
 // Development aid: with -DHKV_TRACE every wavefront records wall-clock stamps at a few points.
@@ -499,12 +501,14 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
 
 }  // namespace
 
-hipError_t launch_decode(const DecodeLaunch &a, hipStream_t s) {
+// With events, they are bound to the dispatch itself (begin and end of the kernel on the device), so
+// their difference is the kernel's duration without the gap to its neighbours in the queue.
+hipError_t launch_decode(const DecodeLaunch &a, hipStream_t s, hipEvent_t ev_begin, hipEvent_t ev_end) {
     if (a.n_items <= 0) return hipSuccess;
     if (a.pool.dtype == 0)
-        hipLaunchKernelGGL(decode_node_kernel<0>, dim3(a.n_items), dim3(kThreads), 0, s, a);
+        hipExtLaunchKernelGGL(decode_node_kernel<0>, dim3(a.n_items), dim3(kThreads), 0, s, ev_begin, ev_end, 0, a);
     else
-        hipLaunchKernelGGL(decode_node_kernel<1>, dim3(a.n_items), dim3(kThreads), 0, s, a);
+        hipExtLaunchKernelGGL(decode_node_kernel<1>, dim3(a.n_items), dim3(kThreads), 0, s, ev_begin, ev_end, 0, a);
     return hipGetLastError();
 }
 

@@ -116,7 +116,7 @@ constexpr int kMaxSharedItemTokens = 2048;
 int prefill_tile_tokens(int group);
 
 hipError_t launch_pool_write(const PoolWriteLaunch &a, hipStream_t s);
-hipError_t launch_decode(const DecodeLaunch &a, hipStream_t s);
+hipError_t launch_decode(const DecodeLaunch &a, hipStream_t s, hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr);
 hipError_t launch_rows_fp32(const RowsLaunch &a, hipStream_t s);
 hipError_t launch_pool_write_fp32(const PoolWriteLaunch &a, hipStream_t s);
 hipError_t launch_prefill(const PrefillLaunch &a, hipStream_t s);
@@ -125,7 +125,8 @@ hipError_t launch_lse_merge(const float *o_parts, const float *lse_parts, const 
                             float *lse_out, hipStream_t s);
 hipError_t launch_lse_merge_dense(const float *o_parts, const float *lse_parts, const int32_t *part_count,
                                   int32_t rows_per_count, int32_t max_parts, int32_t n_rows, void *out,
-                                  int32_t out_dtype, float *lse_out, hipStream_t s);
+                                  int32_t out_dtype, float *lse_out, hipStream_t s, hipEvent_t ev_begin = nullptr,
+                                  hipEvent_t ev_end = nullptr);
 
 hipError_t run_read_probe(const void *const *bufs, int n_buf, size_t bytes, int reps, int n_cu, float *gbps,
                           hipStream_t s);

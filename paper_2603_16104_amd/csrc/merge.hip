@@ -2,6 +2,8 @@
 //   lse = ln sum_n exp(lse_n),  out = sum_n exp(lse_n - lse) * o_n
 // A partial with lse = -inf is skipped without reading its o (which may hold anything); a row
 // without finite partials gives out = 0, lse = -inf.
+#include <hip/hip_ext.h>
+
 #include "hkv_device.h"
 
 namespace hkv {
@@ -130,15 +132,16 @@ __global__ __launch_bounds__(32 * kDenseRowsPerBlock) void lse_merge_dense_kerne
 
 hipError_t launch_lse_merge_dense(const float *o_parts, const float *lse_parts, const int32_t *part_count,
                                   int32_t rows_per_count, int32_t max_parts, int32_t n_rows, void *out,
-                                  int32_t out_dtype, float *lse_out, hipStream_t s) {
+                                  int32_t out_dtype, float *lse_out, hipStream_t s, hipEvent_t ev_begin,
+                                  hipEvent_t ev_end) {
     if (n_rows <= 0) return hipSuccess;
     dim3 grid((n_rows + kDenseRowsPerBlock - 1) / kDenseRowsPerBlock), block(32 * kDenseRowsPerBlock);
     if (out_dtype == 0)
-        hipLaunchKernelGGL(lse_merge_dense_kernel<0>, grid, block, 0, s, o_parts, lse_parts, part_count, rows_per_count,
-                           max_parts, n_rows, out, lse_out);
+        hipExtLaunchKernelGGL(lse_merge_dense_kernel<0>, grid, block, 0, s, ev_begin, ev_end, 0, o_parts, lse_parts,
+                              part_count, rows_per_count, max_parts, n_rows, out, lse_out);
     else
-        hipLaunchKernelGGL(lse_merge_dense_kernel<2>, grid, block, 0, s, o_parts, lse_parts, part_count, rows_per_count,
-                           max_parts, n_rows, out, lse_out);
+        hipExtLaunchKernelGGL(lse_merge_dense_kernel<2>, grid, block, 0, s, ev_begin, ev_end, 0, o_parts, lse_parts,
+                              part_count, rows_per_count, max_parts, n_rows, out, lse_out);
     return hipGetLastError();
 }
 
