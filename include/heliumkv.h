@@ -121,6 +121,18 @@ int kv_pool_retain(hkv_pool *pool, int32_t n, const int32_t *ids /* host */);
  * tail of the free list in the order listed.  Errors as kv_pool_retain. */
 int kv_pool_release(hkv_pool *pool, int32_t n, const int32_t *ids /* host */);
 
+/* Copy-on-write before one holder writes into pages that others may hold too (a sequence forked
+ * from another continues inside the last, partially filled page; sharing itself stays whole
+ * pages, Section 6).  For each listed page: with a single reference it stays as it is; otherwise
+ * the next free page is taken (reference count 1), the whole page (K and V blocks of every head
+ * and, for fp8 pools, its scales) is copied to it on `stream`, one reference of the old page is
+ * dropped and ids[i] is replaced by the new id.  Work queued earlier on `stream` that writes the
+ * old page is seen by the copy; the old page must not be written on other streams meanwhile.
+ *   ids: host, n entries, in/out, no page twice.
+ * ERANGE / EINVAL as kv_pool_retain, EINVAL for a page listed twice, ENOMEM if fewer pages are
+ * free than copies are needed; nothing changes on these errors. */
+int kv_pool_copy_on_write(hkv_pool *pool, int32_t n, int32_t *ids /* host, in/out */, void *stream);
+
 /* Number of free pages, or a negative error code. */
 int32_t kv_pool_num_free(const hkv_pool *pool);
 

@@ -115,6 +115,17 @@ class HostPool:
         if rc:
             raise ValueError(f"oracle_kv_write failed: {rc}")
 
+    def copy_page(self, src: int, dst: int) -> None:
+        """Private copy of a whole page (every head's K and V block and, for fp8, its scales): what a
+        forked sequence needs before it continues inside a partially filled page others still hold."""
+        n = self.num_kv_heads * PAGE * D
+        self.k[dst * n:(dst + 1) * n] = self.k[src * n:(src + 1) * n]
+        self.v[dst * n:(dst + 1) * n] = self.v[src * n:(src + 1) * n]
+        if self.k_scale is not None:
+            h = self.num_kv_heads
+            self.k_scale[dst * h:(dst + 1) * h] = self.k_scale[src * h:(src + 1) * h]
+            self.v_scale[dst * h:(dst + 1) * h] = self.v_scale[src * h:(src + 1) * h]
+
     def fill_from(self, workload) -> None:
         """Write every node's own tokens into the node's pages."""
         f = workload.forest

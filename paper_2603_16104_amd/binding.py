@@ -23,7 +23,7 @@ PLAN_HOST_ONLY = 1
 PAGE_SIZE, HEAD_DIM = 16, 128
 
 EXPORTS = [
-    "hkv_last_error", "kv_pool_create", "kv_pool_destroy", "kv_pool_alloc", "kv_pool_retain", "kv_pool_release",
+    "hkv_last_error", "kv_pool_create", "kv_pool_destroy", "kv_pool_alloc", "kv_pool_retain", "kv_pool_release", "kv_pool_copy_on_write",
     "kv_pool_num_free", "kv_pool_refcount", "kv_pool_write", "prefix_tree_flatten", "prefix_tree_prefill_usage",
     "lse_merge", "hkv_decode_plan_create", "hkv_decode_plan_create_multi", "hkv_decode_plan_destroy", "hkv_decode_plan_workspace_bytes",
     "hkv_decode_plan_num_items", "hkv_decode_plan_num_parts", "hkv_decode_plan_items",
@@ -138,6 +138,13 @@ def kv_pool_retain(pool, ids) -> None:
 def kv_pool_release(pool, ids) -> None:
     ids = _host_i32(ids)
     _check(lib().kv_pool_release(pool, C.c_int32(len(ids)), _hp(ids)))
+
+
+def kv_pool_copy_on_write(pool, ids, stream=None) -> np.ndarray:
+    """Returns the ids to write through: shared pages are replaced by private copies."""
+    ids = _host_i32(ids).copy()
+    _check(lib().kv_pool_copy_on_write(pool, C.c_int32(len(ids)), _hp(ids), _stream(stream)))
+    return ids
 
 
 def kv_pool_num_free(pool) -> int:

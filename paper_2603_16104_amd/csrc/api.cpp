@@ -232,6 +232,42 @@ static PoolView view_of(const hkv_pool *p) {
     return PoolView{p->d.k_pages, p->d.v_pages, p->d.k_scale, p->d.v_scale, p->d.num_kv_heads, p->d.dtype};
 }
 
+extern "C" int kv_pool_copy_on_write(hkv_pool *pool, int32_t n, int32_t *ids, void *stream) {
+    if (int rc = check_held(pool, n, ids, "kv_pool_copy_on_write")) return rc;
+    std::vector<int32_t> sorted(ids, ids + n);
+    std::sort(sorted.begin(), sorted.end());
+    size_t shared = 0;
+    for (int i = 0; i < n; ++i) {
+        if (i > 0 && sorted[i] == sorted[i - 1])
+            return fail(HKV_EINVAL, "kv_pool_copy_on_write: page %d listed twice", sorted[i]);
+        if (pool->refcnt[sorted[i]] <= 0)
+            return fail(HKV_EINVAL, "kv_pool_copy_on_write: page %d is not allocated", sorted[i]);
+        shared += pool->refcnt[sorted[i]] > 1;
+    }
+    if (shared > pool->free_list.size())
+        return fail(HKV_ENOMEM, "kv_pool_copy_on_write: %zu private copies needed, %zu pages free", shared,
+                    pool->free_list.size());
+    PoolCopyLaunch a{};
+    a.pool = view_of(pool);
+    for (int i = 0; i < n; ++i) {
+        const int32_t old = ids[i];
+        if (pool->refcnt[old] == 1) continue;  // sole holder: it may write in place
+        const int32_t fresh = pool->free_list.front();
+        pool->free_list.pop_front();
+        pool->refcnt[fresh] = 1;
+        --pool->refcnt[old];
+        ids[i] = fresh;
+        a.src[a.n] = old;
+        a.dst[a.n] = fresh;
+        if (++a.n == kMaxCopyPairs) {
+            HKV_HIP(launch_pool_copy(a, static_cast<hipStream_t>(stream)));
+            a.n = 0;
+        }
+    }
+    HKV_HIP(launch_pool_copy(a, static_cast<hipStream_t>(stream)));
+    return HKV_OK;
+}
+
 extern "C" int kv_pool_write(hkv_pool *pool, const int32_t *page_ids, int32_t first_slot, int32_t n_tokens,
                              const void *k_src, const void *v_src, void *stream) {
     if (!pool) return fail(HKV_EINVAL, "kv_pool_write: null pool");

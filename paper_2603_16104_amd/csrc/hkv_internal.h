@@ -94,6 +94,15 @@ struct PoolWriteLaunch {
     const void *v_src;
 };
 
+// Whole-page copies inside one pool (copy-on-write of pages that several holders share).
+constexpr int kMaxCopyPairs = 32;
+struct PoolCopyLaunch {
+    PoolView pool;
+    int32_t n;
+    int32_t src[kMaxCopyPairs];
+    int32_t dst[kMaxCopyPairs];
+};
+
 // fp32 pools: one wavefront per (query token, query head), no sharing (rows_fp32.hip).
 struct RowsLaunch {
     PoolView pool;
@@ -116,6 +125,7 @@ constexpr int kMaxSharedItemTokens = 2048;
 int prefill_tile_tokens(int group);
 
 hipError_t launch_pool_write(const PoolWriteLaunch &a, hipStream_t s);
+hipError_t launch_pool_copy(const PoolCopyLaunch &a, hipStream_t s);
 hipError_t launch_decode(const DecodeLaunch &a, hipStream_t s, hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr);
 hipError_t launch_rows_fp32(const RowsLaunch &a, hipStream_t s);
 hipError_t launch_pool_write_fp32(const PoolWriteLaunch &a, hipStream_t s);

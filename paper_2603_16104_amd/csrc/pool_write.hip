@@ -160,7 +160,30 @@ __global__ __launch_bounds__(256) void pool_write_kernel(PoolWriteLaunch a) {
     }
 }
 
+// One workgroup per (pair, K or V): copies the page's blocks of all KV heads, 16 bytes per thread and
+// step, and (fp8 pools) the page's scales.  Source and destination pages are distinct.
+__global__ __launch_bounds__(256) void pool_copy_kernel(PoolCopyLaunch a) {
+    const int pair = blockIdx.x, which = blockIdx.y;
+    const int elem = a.pool.dtype == 0 ? 2 : a.pool.dtype == 1 ? 1 : 4;
+    const size_t page_bytes = (size_t)a.pool.num_kv_heads * kBlockElems * elem;
+    const char *base = static_cast<const char *>(which ? a.pool.v_pages : a.pool.k_pages);
+    const uint4 *src = reinterpret_cast<const uint4 *>(base + (size_t)a.src[pair] * page_bytes);
+    uint4 *dst = reinterpret_cast<uint4 *>(const_cast<char *>(base) + (size_t)a.dst[pair] * page_bytes);
+    for (size_t i = threadIdx.x; i < page_bytes / 16; i += 256) dst[i] = src[i];
+    if (a.pool.dtype == 1) {
+        float *sc = const_cast<float *>(which ? a.pool.v_scale : a.pool.k_scale);
+        for (int h = threadIdx.x; h < a.pool.num_kv_heads; h += 256)
+            sc[(size_t)a.dst[pair] * a.pool.num_kv_heads + h] = sc[(size_t)a.src[pair] * a.pool.num_kv_heads + h];
+    }
+}
+
 }  // namespace
+
+hipError_t launch_pool_copy(const PoolCopyLaunch &a, hipStream_t s) {
+    if (a.n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(pool_copy_kernel, dim3(a.n, 2), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
 
 hipError_t launch_pool_write(const PoolWriteLaunch &a, hipStream_t s) {
     if (a.n_pages <= 0) return hipSuccess;

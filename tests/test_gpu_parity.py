@@ -139,6 +139,57 @@ def test_fp8_append_running_scale_bit_exact(gpu, oracle):
     dp.close()
 
 
+@pytest.mark.parametrize("kv_dtype", [wl.KV_BF16, wl.KV_FP8_E4M3])
+def test_copy_on_write_fork_bit_exact(gpu, oracle, kv_dtype):
+    """A 40-token sequence forked twice inside its partially filled third page: the forks get private copies
+    of that page, the last holder writes in place; pool bytes, scales and page ids equal the oracle's, and
+    decode over the resulting tree (shared full pages, one private leaf per branch) agrees."""
+    import torch
+    from paper_2603_16104_amd import binding as hkv
+    H, n_pages = 2, 12
+    rng = np.random.default_rng(31)
+    mk = lambda n, amp=1.0: wl.f32_to_bf16_bits((amp * rng.standard_normal((n, H, 128))).astype(np.float32))
+    parent = (mk(40), mk(40))
+    cont = {"a": (mk(3), mk(3)), "b": (mk(5, 3.0), mk(5, 1.5)), "c": (mk(12, 0.3), mk(12, 0.3))}   # b raises the fp8 scales
+    hp = oracle.HostPool(n_pages, H, kv_dtype)
+    dp = gpu.DevicePool(n_pages, H, kv_dtype)
+    dev = lambda kv: (gpu.to_device_bits(kv[0]), gpu.to_device_bits(kv[1]))
+    base = hkv.kv_pool_alloc(dp.handle, 3)
+    assert list(base) == [0, 1, 2]
+    hp.write(base, 0, *parent)
+    dp.write(base, 0, *dev(parent))
+    hkv.kv_pool_retain(dp.handle, base)                  # fork b holds the three pages too
+    hkv.kv_pool_retain(dp.handle, base)                  # and fork c
+    pb = hkv.kv_pool_copy_on_write(dp.handle, base[2:])  # b is about to write into page 2
+    pc = hkv.kv_pool_copy_on_write(dp.handle, base[2:])
+    pa = hkv.kv_pool_copy_on_write(dp.handle, base[2:])  # the last holder keeps the page
+    assert (list(pb), list(pc), list(pa)) == ([3], [4], [2])
+    pc = np.concatenate([pc, hkv.kv_pool_alloc(dp.handle, 1)])
+    assert [hkv.kv_pool_refcount(dp.handle, p) for p in range(6)] == [3, 3, 1, 1, 1, 1]
+    hp.copy_page(2, 3)
+    hp.copy_page(2, 4)
+    for ids, name in ((pa, "a"), (pb, "b"), (pc, "c")):
+        hp.write(ids, 8, *cont[name])
+        dp.write(ids, 8, *dev(cont[name]))
+    torch.cuda.synchronize()
+    assert np.array_equal(dp.k.cpu().numpy().view(hp.k.dtype), hp.k) and np.array_equal(dp.v.cpu().numpy().view(hp.v.dtype), hp.v)
+    if kv_dtype == wl.KV_FP8_E4M3:
+        for name in ("k_scale", "v_scale"):
+            g = getattr(dp, name).cpu().numpy().reshape(n_pages, H)[:6]
+            assert np.array_equal(g.view(np.uint32), getattr(hp, name).reshape(n_pages, H)[:6].view(np.uint32)), name
+    f = wl.make_forest([-1, 0, 0, 0], [32, 11, 13, 20], [1, 2, 3], np.array([0, 1, 2, 3, 4, 5], dtype=np.int32))
+    w = wl.Workload(name="forked", num_q_heads=8, num_kv_heads=H, kv_dtype=kv_dtype, num_pages=n_pages, seed=3,
+                    forest=f, mode="decode")
+    exp_o, exp_l = oracle.run_workload(w, hp)
+    r = gpu.DecodeRunner(dp, w)
+    r.run()
+    torch.cuda.synchronize()
+    check_close(gpu.bf16_tensor_to_f64(r.out), exp_o, "forked")
+    check_lse(r.lse.cpu().numpy(), exp_l, "forked")
+    r.close()
+    dp.close()
+
+
 def test_fp8_quantisation_edge_values_bit_exact(gpu, oracle):
     """Ties, subnormal codes, zeros, negative zero and a block whose amax maps exactly to 448."""
     import torch

@@ -116,6 +116,23 @@ def test_pool_alloc_retain_release_matches_model():
     hkv.kv_pool_destroy(pool)
 
 
+def test_pool_copy_on_write_host_side():
+    """Without a device only the cases that queue no copy can run: sole holders keep their pages; every
+    error leaves the pool as it was."""
+    pool = fake_pool(4)
+    a = hkv.kv_pool_alloc(pool, 3)
+    assert list(hkv.kv_pool_copy_on_write(pool, a, stream=0)) == list(a)       # single references: in place
+    assert [hkv.kv_pool_refcount(pool, int(p)) for p in a] == [1, 1, 1] and hkv.kv_pool_num_free(pool) == 1
+    hkv.kv_pool_retain(pool, a[:2])                                           # two shared pages, one free page
+    for ids, code in (([int(a[0]), int(a[0])], hkv.EINVAL), ([3], hkv.EINVAL), ([4], hkv.ERANGE),
+                      ([int(a[0]), int(a[1])], hkv.ENOMEM)):
+        with pytest.raises(hkv.HkvError) as e:
+            hkv.kv_pool_copy_on_write(pool, ids, stream=0)
+        assert e.value.code == code, ids
+        assert [hkv.kv_pool_refcount(pool, p) for p in range(4)] == [2, 2, 1, 0] and hkv.kv_pool_num_free(pool) == 1
+    hkv.kv_pool_destroy(pool)
+
+
 def test_pool_write_validates_before_touching_the_device():
     pool = fake_pool(8)
     for args, code in (((np.array([9], dtype=np.int32), 0, 4), hkv.ERANGE),

@@ -608,3 +608,46 @@ def oracle_pool_copy(oracle, quiet, H):
     q = oracle.HostPool(3, H, oracle.FP8_E4M3)
     q.write([2], 0, quiet, quiet)
     return q
+
+
+def _fork_scenario(seed: int, H: int):
+    """One parent sequence of 40 tokens (its third page holds 8), continued three ways."""
+    rng = np.random.default_rng(seed)
+    mk = lambda n: wl.f32_to_bf16_bits(rng.standard_normal((n, H, D)).astype(np.float32))
+    return {"parent": (mk(40), mk(40)), "a": (mk(3), mk(3)), "b": (mk(5), mk(5)), "c": (mk(12), mk(12))}
+
+
+@pytest.mark.parametrize("dtype_name", ["BF16", "FP8_E4M3"])
+def test_forked_sequences_through_page_copies(oracle, dtype_name):
+    """A sequence forked inside a partially filled page: after a private copy of that page and divergent
+    appends, every branch's pool content and attention equal those of the same branch written alone into
+    pages of its own (same write calls, so fp8 scales take the same history), and the siblings' appends
+    leave one another's pages untouched."""
+    dt = getattr(oracle, dtype_name)
+    H, Hq = 2, 4
+    tok = _fork_scenario(31, H)
+    kp, vp = tok["parent"]
+    shared = oracle.HostPool(12, H, dt)
+    shared.write([0, 1, 2], 0, kp, vp)                 # parent: pages 0, 1 full, page 2 holds 8 tokens
+    shared.copy_page(2, 3)                             # branch b
+    shared.copy_page(2, 4)                             # branch c
+    shared.write([2], 8, *tok["a"])                    # the parent itself goes on in place
+    shared.write([3], 8, *tok["b"])
+    shared.write([4, 5], 8, *tok["c"])                 # runs over into a fresh page
+    tables = {"a": [0, 1, 2], "b": [0, 1, 3], "c": [0, 1, 4, 5]}
+    q = np.random.default_rng(5).standard_normal((1, Hq, D)).astype(np.float32)
+    for name, table in tables.items():
+        own = oracle.HostPool(12, H, dt)
+        kb, vb = tok[name]
+        own_table = [7, 8, 9, 10][:len(table)]
+        own.write(own_table[:3], 0, kp, vp)
+        own.write(own_table[2:], 8, kb, vb)
+        n = 40 + kb.shape[0]
+        nb = H * PAGE * D
+        for ps, po in zip(table, own_table):
+            assert np.array_equal(shared.k[ps * nb:(ps + 1) * nb], own.k[po * nb:(po + 1) * nb]), (name, ps)
+            assert np.array_equal(shared.v[ps * nb:(ps + 1) * nb], own.v[po * nb:(po + 1) * nb]), (name, ps)
+        bt = lambda t: np.asarray([t + [-1] * (4 - len(t))], dtype=np.int32)
+        o1, l1 = oracle.attn_decode(shared, q, bt(table), [n], 0.1)
+        o2, l2 = oracle.attn_decode(own, q, bt(own_table), [n], 0.1)
+        assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
