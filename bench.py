@@ -194,6 +194,60 @@ def bench_workflow(runtime, hkv, wl, shape: str):
     return res
 
 
+def bench_sensitivity(runtime, hkv, wl, model: str, steps: int, warmup: int):
+    """Prefix-sharing sensitivity (the study of Section 7 that varies system / context / question /
+    output lengths over 100 queries): the prefix-tree decode step and the suffix-only prefill against the
+    same requests with nothing shared (private copies of every prompt, whole-prompt prefill), same kernels.
+    Pools are filled with random bf16 values on the device (timing only)."""
+    import torch
+
+    def timed(make_runner, w, n_pools, n_steps, n_warm):
+        pools = []
+        for i in range(n_pools):
+            p = runtime.DevicePool(w.num_pages, w.num_kv_heads, w.kv_dtype, poison=False)
+            p.fill_random(i)
+            pools.append(p)
+        runners = [make_runner(p, w, random_q=True) for p in pools]
+        sec = time_steps(lambda i: runners[i % n_pools].run(), n_steps, n_warm)
+        for r in runners:
+            r.close()
+        for p in pools:
+            p.close()
+        del runners, pools
+        torch.cuda.empty_cache()
+        return sec
+
+    rows = {}
+    for name, (sy, cx, qu, ou) in wl.SENSITIVITY_GRID.items():
+        wd = wl.prefix_sensitivity(sy, cx, qu, ou, model=model, mode="decode")
+        wf = wl.without_sharing(wd)
+        pools_for = lambda w: max(1, min(4, int(600e6 // max(1, w.unique_kv_bytes())) + 1))   # > last-level cache in rotation
+        t_tree = timed(runtime.DecodeRunner, wd, pools_for(wd), steps, warmup)
+        t_flat = timed(runtime.DecodeRunner, wf, pools_for(wf), steps, warmup)
+        wp = wl.prefix_sensitivity(sy, cx, qu, ou, model=model, mode="prefill")
+        wpf = wl.without_sharing(wp)
+        t_pre = timed(runtime.PrefillRunner, wp, 1, 5, 2)
+        t_pre_flat = timed(runtime.PrefillRunner, wpf, 1, 5, 2)
+        rows[name] = {
+            "system_context_question_output": [sy, cx, qu, ou],
+            "decode": {"unique_kv_MB": round(wd.unique_kv_bytes() / 1e6, 1),
+                       "attended_over_unique": round(wf.unique_kv_bytes() / wd.unique_kv_bytes(), 2),
+                       "tree_ms": round(t_tree * 1e3, 4), "unshared_ms": round(t_flat * 1e3, 4),
+                       "tree_unique_GBps": round(wd.unique_kv_bytes() / t_tree / 1e9, 1),
+                       "unshared_GBps": round(wf.unique_kv_bytes() / t_flat / 1e9, 1),
+                       "speedup": round(t_flat / t_tree, 2)},
+            "prefill": {"new_tokens": int(wp.total_q()), "whole_prompt_tokens": int(wpf.total_q()),
+                        "suffix_only_ms": round(t_pre * 1e3, 3), "whole_prompt_ms": round(t_pre_flat * 1e3, 3),
+                        "suffix_only_TFLOPs": round(wp.useful_flop() / t_pre / 1e12, 1),
+                        "whole_prompt_TFLOPs": round(wpf.useful_flop() / t_pre_flat / 1e12, 1),
+                        "speedup": round(t_pre_flat / t_pre, 2)},
+        }
+        log(f"sensitivity {name} done")
+    hq, hk = wl.MODEL_HEADS[model]
+    return {"study": "prefix_sharing_sensitivity", "model_layer": f"{model}: {hq} q / {hk} kv heads, head_dim 128, bf16",
+            "queries": 100, "grid": "own choice (the paper's six settings are only in a figure)", "rows": rows}
+
+
 def cpu_baseline_decode(w, budget_s: float = 20.0):
     """The fp64 oracle as it stands on the host cores: whole workload, repeated within the budget."""
     from oracle import oracle as orc
@@ -230,6 +284,8 @@ def main() -> int:
     ap.add_argument("--no-extras", action="store_true", help="skip the context workloads (c3, c4, pool write)")
     ap.add_argument("--c5", action="store_true", help="also time the fp8 forest (2.4 GB pool, slow to generate)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--sensitivity", choices=["llama3-8b", "qwen3-8b", "qwen3-14b", "qwen3-32b"], default=None,
+                    help="prefix-sharing sensitivity grid for one model's layer shape instead of the headline line")
     ap.add_argument("--profile-workload", choices=["c3", "c4", "c5"], default=None,
                     help="run only this context workload for a few steps and print its figures (for rocprofv3 runs "
                          "of the other kernels; not the headline line)")
@@ -265,6 +321,11 @@ def main() -> int:
 
     if args.workflow:
         print(json.dumps(bench_workflow(runtime, hkv, wl, args.workflow)), flush=True)
+        return 0
+
+    if args.sensitivity:
+        print(json.dumps(bench_sensitivity(runtime, hkv, wl, args.sensitivity, min(args.steps, 100), args.warmup)),
+              flush=True)
         return 0
 
     if args.profile_workload:

@@ -294,8 +294,8 @@ size_t attn_decode_workspace_bytes(hkv_pool *pool, const hkv_node *nodes, int32_
  * all cached prefix tokens plus the causal part of its own suffix, itself included.
  *   cu_q [n_req+1], block_table [n_req][max_pages], kv_len [n_req]: host.  Entries of
  *   block_table beyond ceil(kv_len/16) are ignored.  ERANGE if a used page id is outside the pool.
- * ESHAPE unless num_q_heads is a multiple of num_kv_heads with a ratio of at most 8 (ratios that
- * are no power of two leave part of each workgroup idle: 3 -> 3/4, 5 -> 5/8, 6 -> 6/8, 7 -> 7/8).
+ * ESHAPE unless num_q_heads is a multiple of num_kv_heads with a ratio G of at most 16 (a
+ * workgroup's 256 rows hold floor(256/G) tokens x G heads; at most G - 1 rows stay unused).
  */
 int hkv_prefill_plan_create(hkv_pool *pool, const int32_t *cu_q, const int32_t *block_table, int32_t max_pages,
                             const int32_t *kv_len, int32_t n_req, int32_t num_q_heads, uint32_t flags,

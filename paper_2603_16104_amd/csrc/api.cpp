@@ -495,6 +495,20 @@ static void plan_items(hkv_decode_plan &pl) {
     int leaf_chunk = std::max(256, (mean_leaf / leaf_split + 15) / 16 * 16);
     if (leaf_split == 1) leaf_chunk = 1 << 30;  // whole nodes
     int shared_chunk = std::min(kMaxSharedItemTokens, std::max(512, std::min(mean_leaf, leaf_chunk) / 16 * 16));
+    // Long shared paths: every chunk costs each row below it one partial (written once, read once), so
+    // the chunks grow with the path until a request collects about eight of them from shared nodes.
+    {
+        std::vector<int64_t> shared_above(n_nodes, 0);
+        int64_t longest = 0;
+        for (int v = 0; v < n_nodes; ++v) {
+            const int R = pl.node_req_indptr[v + 1] - pl.node_req_indptr[v];
+            const int64_t up = pl.nodes[v].parent >= 0 ? shared_above[pl.nodes[v].parent] : 0;
+            shared_above[v] = up + (R * G > 16 ? pl.nodes[v].n_tokens : 0);
+            longest = std::max(longest, shared_above[v]);
+        }
+        const int by_path = (int)std::min<int64_t>(kMaxSharedItemTokens, longest / 8 / 256 * 256);
+        shared_chunk = std::max(shared_chunk, by_path);
+    }
     leaf_chunk = env_int("HKV_DECODE_LEAF_CHUNK", leaf_chunk) / 16 * 16;
     shared_chunk = std::min(kMaxSharedItemTokens, env_int("HKV_DECODE_SHARED_CHUNK", shared_chunk)) / 16 * 16;
     struct Proto { DecodeItem it; int64_t cost; };
@@ -860,7 +874,7 @@ extern "C" int hkv_prefill_plan_create(hkv_pool *pool, const int32_t *cu_q, cons
     const int Hkv = pool->d.num_kv_heads;
     if (num_q_heads <= 0 || num_q_heads % Hkv) return fail(HKV_ESHAPE, "hkv_prefill_plan_create: %d query heads over %d KV heads", num_q_heads, Hkv);
     const int G = num_q_heads / Hkv;
-    if (G > 8) return fail(HKV_ESHAPE, "hkv_prefill_plan_create: query/KV head ratio %d (supported: 1..8)", G);
+    if (G > 16) return fail(HKV_ESHAPE, "hkv_prefill_plan_create: query/KV head ratio %d (supported: 1..16)", G);
     if (pool->d.dtype == HKV_FP8_E4M3) return fail(HKV_ESHAPE, "hkv_prefill_plan_create: prefill reads bf16 and fp32 pools only");
     if (n_req < 0 || max_pages < 0 || (n_req > 0 && (!cu_q || !kv_len || (max_pages > 0 && !block_table))))
         return fail(HKV_EINVAL, "hkv_prefill_plan_create: bad argument");

@@ -2,10 +2,10 @@
 // prefix pages plus the causal part of their own suffix, all read through the block table.
 // (Section 5, "Token usage": a call processes only the tokens that are not already cached.)
 //
-// One workgroup (8 wavefronts, two per SIMD) owns up to 256 query rows = 32 * tbh consecutive new
-// tokens x the G query heads of one KV head (tbh = the largest power of two <= 8 / G), so every K/V
-// tile staged in LDS is used by all G heads; when G is no power of two, 8 / tbh - G wavefronts have
-// no head of their own (they repeat the last one and store nothing).  Each wavefront owns one
+// One workgroup (8 wavefronts, two per SIMD) owns up to 256 query rows = floor(256 / G) consecutive
+// new tokens x the G query heads of one KV head, so every K/V tile staged in LDS is used by all G
+// heads.  Rows are numbered token-major (row = token * G + head), so any head ratio fills the
+// eight 32-row tiles except for at most G - 1 rows.  Each wavefront owns one
 // 32-row tile and keeps Q^T and the O^T accumulators in registers; K/V stream
 // through LDS in 64-token blocks, four stages each, fetched by LDS-direct loads
 // (global_load_lds_dwordx4) two blocks ahead so that the data in flight occupies no registers.
@@ -84,13 +84,12 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillLaunch a) {
     const int n = lane & 31, h = lane >> 5;
     const int Hq = a.num_q_heads, Hkv = a.pool.num_kv_heads;
     const int G = Hq / Hkv;
-    const int tbh = G == 1 ? 8 : G == 2 ? 4 : G <= 4 ? 2 : 1;  // 32-token blocks per head inside the workgroup's rows
     const float c = a.scale * kLog2e;
 
     // the 32-row tile of this wavefront
-    const bool live = wave / tbh < G;                          // this wavefront has a head of its own
-    const int head = tl.kv_head * G + min(wave / tbh, G - 1);  // query head
-    const int tok = 32 * (wave % tbh) + n;         // token index of this lane's row within the tile's new tokens
+    const int r_tile = 32 * wave + n;            // this lane's row within the workgroup's rows
+    const int tok = r_tile / G;                  // token index within the tile's new tokens (>= n_q: no such row)
+    const int head = tl.kv_head * G + r_tile % G;  // query head
     bf16x8 qf[8];
     {
         const int qrow = tl.q_row0 + min(tok, tl.n_q - 1);
@@ -99,7 +98,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillLaunch a) {
         for (int kk = 0; kk < 8; ++kk) qf[kk] = as_bf16x8(ld16(qp + (16 * kk + 8 * h) * 2));
     }
     // wavefront-uniform: smallest absolute position among this wavefront's rows
-    const int wave_min_pos = tl.prefix_len + tl.q_begin + 32 * (wave % tbh);
+    const int wave_min_pos = tl.prefix_len + tl.q_begin + min((32 * wave) / G, tl.n_q - 1);
 
     const int kv_end = tl.prefix_len + tl.q_begin + tl.n_q;  // keys any row of the tile can see
     const int n_blk = (kv_end + KB - 1) / KB;
@@ -421,7 +420,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillLaunch a) {
 
     // ---- normalise and store; lane (n, h) holds dims 32*dm + 8*(i/4) + 4*h + i%4 of its row
     const float l_tot = l_run + __shfl_xor(l_run, 32);
-    if (live && tok < tl.n_q) {
+    if (tok < tl.n_q) {
         const float inv = 1.0f / l_tot;
         const size_t row = (size_t)(tl.q_row0 + tok) * Hq + head;
         uint16_t *op = static_cast<uint16_t *>(a.out) + row * kHeadDim;
@@ -440,7 +439,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillLaunch a) {
 
 }  // namespace
 
-int prefill_tile_tokens(int group) { return 32 * (group == 1 ? 8 : group == 2 ? 4 : group <= 4 ? 2 : 1); }
+int prefill_tile_tokens(int group) { return 256 / group; }
 
 hipError_t launch_prefill(const PrefillLaunch &a, hipStream_t s) {
     if (a.n_tiles <= 0) return hipSuccess;

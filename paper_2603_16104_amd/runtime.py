@@ -47,6 +47,20 @@ class DevicePool:
     def write(self, page_ids, first_slot: int, k_src: torch.Tensor, v_src: torch.Tensor, stream=None) -> None:
         hkv.kv_pool_write(self.handle, page_ids, first_slot, int(k_src.shape[0]), k_src, v_src, stream)
 
+    def fill_random(self, seed: int = 0) -> None:
+        """Timing aid for bf16 pools too large to fill through kv_pool_write from host data: every slot
+        of every page gets a standard-normal bf16 value drawn on the device (results are not checked)."""
+        if self.dtype != hkv.BF16:
+            raise ValueError("fill_random: bf16 pools only")
+        g = torch.Generator(device=self.k.device)
+        g.manual_seed(seed)
+        step = 1 << 26
+        for t in (self.k, self.v):
+            for a in range(0, t.numel(), step):
+                b = min(t.numel(), a + step)
+                t[a:b] = torch.randn(b - a, device=t.device, generator=g).to(torch.bfloat16).view(torch.int16)
+        torch.cuda.synchronize()
+
     def fill_from(self, workload: wl.Workload, max_chunk_tokens: int = 1 << 16) -> None:
         """kv_pool_write of every node's own tokens into the node's pages."""
         f = workload.forest
@@ -73,6 +87,11 @@ def to_device_bits(a: np.ndarray, device="cuda:0") -> torch.Tensor:
     return torch.from_numpy(a).to(device)
 
 
+def _device_random_q(n_tokens: int, num_q_heads: int, device) -> torch.Tensor:
+    """Timing aid: standard-normal bf16 queries drawn on the device (bf16 / fp8 pools)."""
+    return torch.randn((n_tokens, num_q_heads, hkv.HEAD_DIM), device=device).to(torch.bfloat16).view(torch.int16)
+
+
 def bf16_tensor_to_f64(t: torch.Tensor) -> np.ndarray:
     """bf16 bit patterns (int16 device tensor) -> float64 numpy; fp32 tensors pass through."""
     if t.dtype == torch.float32:
@@ -84,14 +103,14 @@ def bf16_tensor_to_f64(t: torch.Tensor) -> np.ndarray:
 class DecodeRunner:
     """Plan + buffers for repeated decode steps over one forest."""
 
-    def __init__(self, pool: DevicePool, workload: wl.Workload):
+    def __init__(self, pool: DevicePool, workload: wl.Workload, random_q: bool = False):
         f = workload.forest
         self.pool, self.workload = pool, workload
         self.plan = hkv.hkv_decode_plan_create(pool.handle, f.nodes, f.node_pages, f.req_leaf, workload.num_q_heads)
         self.ws_bytes = hkv.hkv_decode_plan_workspace_bytes(self.plan)
         dev = pool.k.device
         self.ws = torch.empty(max(self.ws_bytes, 256), dtype=torch.uint8, device=dev)
-        self.q = to_device_bits(workload.q(), dev)
+        self.q = _device_random_q(f.n_req, workload.num_q_heads, dev) if random_q else to_device_bits(workload.q(), dev)
         odt = torch.float32 if pool.dtype == hkv.FP32 else torch.int16      # fp32 pools: fp32 q and out
         self.out = torch.zeros((f.n_req, workload.num_q_heads, hkv.HEAD_DIM), dtype=odt, device=dev)
         self.lse = torch.zeros((f.n_req, workload.num_q_heads), dtype=torch.float32, device=dev)
@@ -107,7 +126,7 @@ class DecodeRunner:
 
 
 class PrefillRunner:
-    def __init__(self, pool: DevicePool, workload: wl.Workload):
+    def __init__(self, pool: DevicePool, workload: wl.Workload, random_q: bool = False):
         f = workload.forest
         self.pool, self.workload = pool, workload
         mp = max(1, f.max_pages_per_req())
@@ -117,7 +136,7 @@ class PrefillRunner:
                                                 workload.num_q_heads)
         dev = pool.k.device
         tq = workload.total_q()
-        self.q = to_device_bits(workload.q(), dev)
+        self.q = _device_random_q(tq, workload.num_q_heads, dev) if random_q else to_device_bits(workload.q(), dev)
         odt = torch.float32 if pool.dtype == hkv.FP32 else torch.int16      # fp32 pools: fp32 q and out
         self.out = torch.zeros((tq, workload.num_q_heads, hkv.HEAD_DIM), dtype=odt, device=dev)
         self.lse = torch.zeros((tq, workload.num_q_heads), dtype=torch.float32, device=dev)

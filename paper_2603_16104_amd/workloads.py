@@ -279,6 +279,69 @@ def config5(seed: int = BASE_SEED + 5, n_roots: int = 16, children: int = 32,
                     num_pages=num_pages, seed=seed, forest=f, mode="decode")
 
 
+# (query heads, KV heads) of one layer of the model families the evaluation names (Section 7,
+# "Sensitivity Analysis": Llama-3.1-8B, Qwen3-8B/14B/32B); head_dim is 128 for all of them.
+MODEL_HEADS = {"llama3-8b": (32, 8), "qwen3-8b": (32, 8), "qwen3-14b": (40, 8), "qwen3-32b": (64, 8)}
+
+# (system, context, question, output) token lengths.  The prefix-sharing sensitivity study (Section 7)
+# varies exactly these four; its six settings are only in a figure, so this grid is our own choice:
+# from almost nothing shared to almost everything shared.
+SENSITIVITY_GRID = {
+    "P1": (256, 0, 256, 128),
+    "P2": (2048, 0, 256, 128),
+    "P3": (256, 2048, 128, 128),
+    "P4": (2048, 2048, 128, 128),
+    "P5": (1024, 8192, 64, 256),
+    "P6": (4096, 4096, 512, 512),
+}
+
+
+def prefix_sensitivity(system: int, context: int, question: int, output: int, *, model: str = "qwen3-14b",
+                       n_contexts: int = 10, questions_per_context: int = 10, mode: str = "decode",
+                       kv_dtype: int = KV_BF16, seed: int = BASE_SEED + 6) -> Workload:
+    """Fixed system prompt -> one shared context per group of queries -> one question per query
+    (100 queries by default, as in the study).  Shared segments are rounded up to whole pages.
+    decode: every query has produced half of its `output` tokens; its leaf holds question + those.
+    prefill: the system prompt and the contexts are cached, every query prefills its question."""
+    up = lambda t: (t + PAGE_SIZE - 1) // PAGE_SIZE * PAGE_SIZE
+    hq, hk = MODEL_HEADS[model]
+    leaf_tokens = question + (output // 2 if mode == "decode" else 0)
+    parent, ntok, leaves = [-1], [up(system)], []
+    for _ in range(n_contexts):
+        ctx = 0
+        if context > 0:
+            parent.append(0)
+            ntok.append(up(context))
+            ctx = len(parent) - 1
+        for _ in range(questions_per_context):
+            parent.append(ctx)
+            ntok.append(leaf_tokens)
+            leaves.append(len(parent) - 1)
+    n_used = sum((t + 15) // 16 for t in ntok)
+    num_pages = _pool_pages(n_used)
+    f = make_forest(parent, ntok, leaves, _perm(seed, num_pages))
+    q_len = np.full(len(leaves), question, dtype=np.int32) if mode == "prefill" else None
+    return Workload(name=f"sens_{model}_{system}_{context}_{question}_{output}_{mode}", num_q_heads=hq,
+                    num_kv_heads=hk, kv_dtype=kv_dtype, num_pages=num_pages, seed=seed, forest=f, mode=mode,
+                    q_len=q_len)
+
+
+def without_sharing(w: Workload) -> Workload:
+    """The same requests with nothing shared: every request owns a private copy of its whole path
+    (one root node per request).  decode: each request still has one query token; prefill: each
+    request prefills its whole prompt (no cached prefix).  What a paged engine without prefix reuse
+    would hold and read."""
+    f = w.forest
+    total = [int(sum(f.n_tokens[v] for v in f.path(int(leaf)))) for leaf in f.req_leaf]
+    n_used = sum((t + 15) // 16 for t in total)
+    num_pages = _pool_pages(n_used)
+    flat = make_forest([-1] * len(total), total, list(range(len(total))), _perm(w.seed, num_pages))
+    q_len = np.asarray(total, dtype=np.int32) if w.mode == "prefill" else None
+    return Workload(name=w.name + "_unshared", num_q_heads=w.num_q_heads, num_kv_heads=w.num_kv_heads,
+                    kv_dtype=w.kv_dtype, num_pages=num_pages, seed=w.seed, forest=flat, mode=w.mode, q_len=q_len,
+                    src_dtype=w.src_dtype)
+
+
 def random_forest_workload(seed: int, *, n_roots: int = 2, depth: int = 3, fanout: int = 3,
                            max_node_pages: int = 5, num_q_heads: int = 8, num_kv_heads: int = 2,
                            kv_dtype: int = KV_BF16, mode: str = "decode", ragged: bool = True,

@@ -395,10 +395,11 @@ def test_prefill_random_forests(gpu, oracle, seed):
     run_prefill(gpu, oracle, w)
 
 
-@pytest.mark.parametrize("hq,hkv_", [(6, 2), (5, 1), (12, 2), (14, 2), (40, 8)])
+@pytest.mark.parametrize("hq,hkv_", [(6, 2), (5, 1), (12, 2), (14, 2), (40, 8), (9, 1), (24, 2), (16, 1)])
 def test_prefill_head_ratios_that_are_no_power_of_two(gpu, oracle, hq, hkv_):
-    """Query/KV head ratios 3, 5, 6, 7 (40 / 8 is the Qwen3-14B shape): some wavefronts of a tile have
-    no head of their own and must neither disturb the others nor store anything."""
+    """Query/KV head ratios 3, 5, 6, 7 (40 / 8 is the Qwen3-14B shape), 9, 12 and 16: a tile holds
+    floor(256 / ratio) tokens x ratio heads, a wavefront's 32 rows span several tokens and heads, and the
+    few rows left over must neither disturb the others nor store anything."""
     w = wl.random_forest_workload(70 + hq, mode="prefill", num_q_heads=hq, num_kv_heads=hkv_, depth=2, fanout=2,
                                   max_node_pages=10, n_roots=2)
     run_prefill(gpu, oracle, w)
@@ -741,3 +742,27 @@ def test_fp32_pool_several_query_tokens(gpu, oracle):
     check_close_fp32(out.cpu().numpy().astype(np.float64), exp_o, "fp32_multi")
     hkv.hkv_decode_plan_destroy(plan)
     dp.close()
+
+
+# ------------------------------------------------------------------------------ other model shapes
+
+@pytest.mark.parametrize("model", ["qwen3-14b", "qwen3-32b", "llama3-8b"])
+@pytest.mark.parametrize("mode", ["decode", "prefill"])
+def test_sensitivity_shapes_small(gpu, oracle, model, mode):
+    """System prompt -> shared contexts -> questions, at the layer shapes of the evaluated model families
+    (5, 8 and 4 query heads per KV head), small enough for the oracle; also the same requests unshared."""
+    import torch
+    w = wl.prefix_sensitivity(80, 176, 37, 18, model=model, n_contexts=2, questions_per_context=3, mode=mode, seed=91)
+    for wk in (w, wl.without_sharing(w)):
+        if mode == "decode":
+            run_decode(gpu, oracle, wk)
+        else:
+            hp, dp = both_pools(gpu, oracle, wk)
+            exp_o, exp_l = oracle.run_workload(wk, hp)
+            r = gpu.PrefillRunner(dp, wk)
+            r.run()
+            torch.cuda.synchronize()
+            check_close(gpu.bf16_tensor_to_f64(r.out), exp_o, wk.name)
+            check_lse(r.lse.cpu().numpy(), exp_l, wk.name)
+            r.close()
+            dp.close()

@@ -319,8 +319,9 @@ def test_prefill_plan_error_codes():
              ([1, 8], bt, [40], 4, hkv.EINVAL),             # cu_q must start at 0
              ([0, 8], bt, [80], 4, hkv.ENOMEM),             # needs 5 pages, table has 4
              ([0, 8], bt, [60], 4, hkv.ERANGE),             # reaches the -1 entry
-             ([0, 8], bt, [40], 6, hkv.OK),                 # group of 3 heads: allowed (part of a tile idles)
-             ([0, 8], bt, [40], 18, hkv.ESHAPE),            # group of 9 heads: beyond the 8 of a tile
+             ([0, 8], bt, [40], 6, hkv.OK),                 # group of 3 heads: 85 tokens x 3 heads per tile
+             ([0, 8], bt, [40], 18, hkv.OK),                # group of 9 heads
+             ([0, 8], bt, [40], 34, hkv.ESHAPE),            # group of 17 heads: beyond the supported 16
              ([0, 8], bt, [40], 5, hkv.ESHAPE)]             # 5 query heads over 2 KV heads
     for cu, b, kvl, hq, code in cases:
         if code == hkv.OK:
