@@ -248,6 +248,32 @@ def bench_sensitivity(runtime, hkv, wl, model: str, steps: int, warmup: int):
             "queries": 100, "grid": "own choice (the paper's six settings are only in a figure)", "rows": rows}
 
 
+def bench_mixed(runtime, hkv, wl, steps: int, warmup: int):
+    """A chunked-prefill step (64 decode rows of the c2 shape + 8 prompts prefilling 512 tokens each behind
+    the same shared prefix): everything through one suffix-only prefill launch, against decode rows
+    through the prefix-tree plan + the chunks through prefill.  Four pools in rotation."""
+    import torch
+    w = wl.mixed_step()
+    res = {"workload": w.name, "layer": "32 q / 8 kv heads, head_dim 128, bf16",
+           "unique_kv_MB": round(w.unique_kv_bytes() / 1e6, 1), "new_tokens": int(w.total_q())}
+    for name, make in (("one_prefill_launch", runtime.PrefillRunner), ("tree_decode_plus_prefill", runtime.MixedStepRunner)):
+        pools = []
+        for i in range(4):
+            p = runtime.DevicePool(w.num_pages, w.num_kv_heads, w.kv_dtype, poison=False)
+            p.fill_random(i)
+            pools.append(p)
+        runners = [make(p, w, random_q=True) for p in pools]
+        sec = time_steps(lambda i: runners[i % 4].run(), steps, warmup)
+        res[name + "_ms"] = round(sec * 1e3, 4)
+        for r in runners:
+            r.close()
+        for p in pools:
+            p.close()
+        del runners, pools
+        torch.cuda.empty_cache()
+    return res
+
+
 def cpu_baseline_decode(w, budget_s: float = 20.0):
     """The fp64 oracle as it stands on the host cores: whole workload, repeated within the budget."""
     from oracle import oracle as orc
@@ -284,6 +310,7 @@ def main() -> int:
     ap.add_argument("--no-extras", action="store_true", help="skip the context workloads (c3, c4, pool write)")
     ap.add_argument("--c5", action="store_true", help="also time the fp8 forest (2.4 GB pool, slow to generate)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--mixed", action="store_true", help="a chunked-prefill step: one prefill launch vs tree decode + prefill")
     ap.add_argument("--sensitivity", choices=["llama3-8b", "qwen3-8b", "qwen3-14b", "qwen3-32b"], default=None,
                     help="prefix-sharing sensitivity grid for one model's layer shape instead of the headline line")
     ap.add_argument("--profile-workload", choices=["c3", "c4", "c5"], default=None,
@@ -321,6 +348,10 @@ def main() -> int:
 
     if args.workflow:
         print(json.dumps(bench_workflow(runtime, hkv, wl, args.workflow)), flush=True)
+        return 0
+
+    if args.mixed:
+        print(json.dumps(bench_mixed(runtime, hkv, wl, min(args.steps, 100), args.warmup)), flush=True)
         return 0
 
     if args.sensitivity:

@@ -326,6 +326,22 @@ def prefix_sensitivity(system: int, context: int, question: int, output: int, *,
                     q_len=q_len)
 
 
+def mixed_step(n_decode: int = 64, n_prefill: int = 8, root_tokens: int = 2048, private_tokens: int = 512,
+               chunk_tokens: int = 512, model: str = "llama3-8b", seed: int = BASE_SEED + 7) -> Workload:
+    """One step of an engine with chunked prefill: n_decode requests that bring one new token (context
+    = shared root + private_tokens, the new token is the last of them) next to n_prefill requests that
+    prefill a chunk of chunk_tokens new tokens right behind the shared root."""
+    hq, hk = MODEL_HEADS[model]
+    parent = [-1] + [0] * (n_decode + n_prefill)
+    ntok = [root_tokens] + [private_tokens] * n_decode + [chunk_tokens] * n_prefill
+    q_len = np.asarray([1] * n_decode + [chunk_tokens] * n_prefill, dtype=np.int32)
+    n_used = sum((t + 15) // 16 for t in ntok)
+    num_pages = _pool_pages(n_used)
+    f = make_forest(parent, ntok, list(range(1, n_decode + n_prefill + 1)), _perm(seed, num_pages))
+    return Workload(name=f"mixed_{n_decode}dec_{n_prefill}x{chunk_tokens}pre", num_q_heads=hq, num_kv_heads=hk,
+                    kv_dtype=KV_BF16, num_pages=num_pages, seed=seed, forest=f, mode="prefill", q_len=q_len)
+
+
 def without_sharing(w: Workload) -> Workload:
     """The same requests with nothing shared: every request owns a private copy of its whole path
     (one root node per request).  decode: each request still has one query token; prefill: each
