@@ -51,11 +51,11 @@ __global__ __launch_bounds__(64 * kRowsPerBlock) void lse_merge_kernel(const flo
 
 // Dense variant: row i owns partials i*max_parts + k, k < part_count[i / rows_per_count].  Half a
 // wavefront per row (32 lanes x 4 dims); the first kUnroll partials and their lse values are
-// requested together, so a row costs one memory round trip after its count.
+// requested together, so a row costs one memory round trip after its count (kUnroll is 8, or 16 for
+// forests whose paths collect more than 8 partials).
 constexpr int kDenseRowsPerBlock = 8;
-constexpr int kUnroll = 8;
 
-template <int OUT_DT>
+template <int OUT_DT, int kUnroll>
 __global__ __launch_bounds__(32 * kDenseRowsPerBlock) void lse_merge_dense_kernel(
     const float *__restrict__ o_parts, const float *__restrict__ lse_parts, const int32_t *__restrict__ part_count,
     int32_t rows_per_count, int32_t max_parts, int32_t n_rows, void *__restrict__ out, float *__restrict__ lse_out) {
@@ -136,12 +136,21 @@ hipError_t launch_lse_merge_dense(const float *o_parts, const float *lse_parts, 
                                   hipEvent_t ev_end) {
     if (n_rows <= 0) return hipSuccess;
     dim3 grid((n_rows + kDenseRowsPerBlock - 1) / kDenseRowsPerBlock), block(32 * kDenseRowsPerBlock);
-    if (out_dtype == 0)
-        hipExtLaunchKernelGGL(lse_merge_dense_kernel<0>, grid, block, 0, s, ev_begin, ev_end, 0, o_parts, lse_parts,
-                              part_count, rows_per_count, max_parts, n_rows, out, lse_out);
-    else
-        hipExtLaunchKernelGGL(lse_merge_dense_kernel<2>, grid, block, 0, s, ev_begin, ev_end, 0, o_parts, lse_parts,
-                              part_count, rows_per_count, max_parts, n_rows, out, lse_out);
+    auto go = [&](auto kernel) {
+        hipExtLaunchKernelGGL(kernel, grid, block, 0, s, ev_begin, ev_end, 0, o_parts, lse_parts, part_count,
+                              rows_per_count, max_parts, n_rows, out, lse_out);
+    };
+    if (max_parts <= 8) {
+        if (out_dtype == 0)
+            go(lse_merge_dense_kernel<0, 8>);
+        else
+            go(lse_merge_dense_kernel<2, 8>);
+    } else {
+        if (out_dtype == 0)
+            go(lse_merge_dense_kernel<0, 16>);
+        else
+            go(lse_merge_dense_kernel<2, 16>);
+    }
     return hipGetLastError();
 }
 

@@ -244,11 +244,13 @@ def test_lse_merge_kernel(gpu, oracle):
         assert (got[3] == 0).all() and (got[7] == 0).all()
 
 
-def test_lse_merge_dense_kernel(gpu, oracle):
+@pytest.mark.parametrize("max_parts", [3, 8, 11, 16, 21])
+def test_lse_merge_dense_kernel(gpu, oracle, max_parts):
+    """Slot counts below, at and beyond the two unrolled depths of the kernel (8 and 16)."""
     import torch
     from paper_2603_16104_amd import binding as hkv
     rng = np.random.default_rng(8)
-    rows_per_count, n_groups, max_parts = 4, 37, 11        # more partials than the kernel's unrolled prefix
+    rows_per_count, n_groups = 4, 37
     n_rows = rows_per_count * n_groups - 2                 # last group is ragged
     counts = rng.integers(0, max_parts + 1, size=n_groups).astype(np.int32)
     counts[0], counts[1] = 0, max_parts
