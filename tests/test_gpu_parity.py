@@ -331,6 +331,27 @@ def test_decode_many_requests_per_node(gpu, oracle):
     run_decode(gpu, oracle, w)
 
 
+@pytest.mark.parametrize("kv_dtype", [wl.KV_BF16, wl.KV_FP8_E4M3])
+def test_decode_deep_chain(gpu, oracle, kv_dtype):
+    """A chain of 26 nodes with requests hanging off at several depths: paths collect up to 27 partials
+    (beyond both unrolled depths of the merge), nodes alternate between many and few rows."""
+    rng = np.random.default_rng(17)
+    parent, ntok, leaves = [], [], []
+    for d in range(26):
+        parent.append(d - 1)
+        ntok.append(int(rng.integers(1, 4)) * 16)
+    for d in (0, 3, 3, 9, 15, 15, 15, 25, 25):          # ragged private leaves below chain node d
+        parent.append(d)
+        ntok.append(int(rng.integers(1, 70)))
+        leaves.append(len(parent) - 1)
+    leaves += [25, 12]                                   # and two requests that end on the chain itself
+    n_used = sum((t + 15) // 16 for t in ntok)
+    f = wl.make_forest(parent, ntok, leaves, np.random.default_rng(2).permutation(n_used + 5).astype(np.int32))
+    w = wl.Workload(name="deep_chain", num_q_heads=8, num_kv_heads=2, kv_dtype=kv_dtype, num_pages=n_used + 5, seed=21,
+                    forest=f, mode="decode")
+    run_decode(gpu, oracle, w)
+
+
 def test_decode_config1_one_shot(gpu, oracle):
     _, dec = wl.config1()
     run_decode(gpu, oracle, dec, one_shot=True)
