@@ -224,6 +224,7 @@ def _check_decode_plan(w, oracle):
             a = tok_start[node] + tok_begin
             covered[r][kv_head, a: a + n_tok] += 1
             slots[r][kv_head, slot] += 1
+    assert (items[:, 2] == np.arange(len(items)) % w.num_kv_heads).all(), "item index mod Hkv is the KV head"
     for r in range(f.n_req):
         assert (covered[r] == 1).all(), "every (request, kv head, token) is read by exactly one item"
         assert (slots[r][:, :counts[r]] == 1).all() and (slots[r][:, counts[r]:] == 0).all()
