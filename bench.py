@@ -191,10 +191,21 @@ def bench_workflow(runtime, hkv, wl, shape: str):
             ms.append(ev0.elapsed_time(ev1))
         res["orders"][name] = {"prefill_usage_tokens": int(sum(usage)),
                                "total_token_step_times_M": T, "gpu_ms": round(min(ms), 3)}
-        if cache:   # block-level LRU prefix cache with room for two of the longest prompts (host bookkeeping only)
-            sim = runtime.simulate_prefix_cache(wf, seq, 2 * longest_pages)
+        if cache:   # the same order served through the block-level LRU prefix cache with room for two of the longest prompts
+            pr = runtime.PrefixCacheRunner([runtime.workflow_prompt_tokens(wf, c) for c in seq], 2 * longest_pages, 32, 8,
+                                           random_tensors=True)
+            sim = pr.prepare()
+            pr.run()
+            torch.cuda.synchronize()
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            ev0.record()
+            pr.run()
+            ev1.record()
+            torch.cuda.synchronize()
+            pr.close()
             res["orders"][name]["lru_cache_hit_rate"] = round(sim["hit_rate"], 4)
             res["orders"][name]["lru_cache_evictions"] = sim["evictions"]
+            res["orders"][name]["lru_cache_gpu_ms"] = round(ev0.elapsed_time(ev1), 3)
     r.close()
     return res
 

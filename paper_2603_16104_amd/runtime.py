@@ -329,6 +329,70 @@ class WorkflowRunner:
         self.pool.close()
 
 
+class PrefixCacheRunner:
+    """A sequence of prompts (token ids) served one after another through the block-level prefix
+    cache under a fixed page budget, as an engine with automatic prefix caching does: acquire the
+    prompt's pages (hits come back filled, misses get fresh or evicted pages), write the K/V of the
+    uncached tokens, run suffix-only prefill attention for them, release.  `prepare` plays the
+    whole sequence through the cache on the host (page assignment is deterministic) and builds one
+    plan per prompt; `run` only queues GPU work in the same order, so a page that is evicted and
+    handed to a later prompt is overwritten after its last reader in stream order."""
+
+    def __init__(self, prompts, n_pages: int, num_q_heads: int = 8, num_kv_heads: int = 2, seed: int = wl.BASE_SEED + 11,
+                 device: str = "cuda:0", random_tensors: bool = False):
+        self.prompts, self.Hq, self.Hkv, self.seed, self.device = prompts, num_q_heads, num_kv_heads, seed, device
+        self.random_tensors = random_tensors      # timing only: K/V/q drawn on the device instead of per token
+        self.pool = DevicePool(n_pages, num_kv_heads, hkv.BF16, device)
+        self.cache = hkv.kv_cache_create(self.pool.handle)
+        self.scale = float(1.0 / np.sqrt(np.float32(hkv.HEAD_DIM)))
+        self.steps = []
+
+    def prepare(self) -> dict:
+        hit = total = 0
+        for toks in self.prompts:
+            n = len(toks)
+            pages, cached = hkv.kv_cache_acquire(self.cache, toks)
+            hkv.kv_cache_release(self.cache, pages)      # the call is over before the next one is planned
+            hit += cached
+            total += n
+            step = {"pages": np.asarray(pages, dtype=np.int32), "cached": int(cached), "n": n, "plan": None}
+            new = n - cached
+            if new > 0:
+                if self.random_tensors:
+                    step["k"] = _device_random_q(new, self.Hkv, self.device)
+                    step["v"] = _device_random_q(new, self.Hkv, self.device)
+                    step["q"] = _device_random_q(new, self.Hq, self.device)
+                else:
+                    pos = np.arange(cached, n)
+                    k, v = wl.token_kv(self.seed, toks[cached:], pos, self.Hkv)
+                    step["k"], step["v"] = to_device_bits(k, self.device), to_device_bits(v, self.device)
+                    step["q"] = to_device_bits(wl.token_q(self.seed, toks[cached:], pos, self.Hq), self.device)
+                step["out"] = torch.zeros((new, self.Hq, hkv.HEAD_DIM), dtype=torch.int16, device=self.device)
+                step["lse"] = torch.zeros((new, self.Hq), dtype=torch.float32, device=self.device)
+                step["plan"] = hkv.hkv_prefill_plan_create(self.pool.handle, np.array([0, new], dtype=np.int32),
+                                                           step["pages"][None, :], np.array([n], dtype=np.int32), self.Hq)
+            self.steps.append(step)
+        st = hkv.kv_cache_stats(self.cache)
+        return {"hit_rate": hit / max(total, 1), "prompt_tokens": total, "evictions": st["evictions"]}
+
+    def run(self, stream=None) -> None:
+        for st in self.steps:
+            if st["plan"] is None:
+                continue
+            self.pool.write(st["pages"][st["cached"] // hkv.PAGE_SIZE:], 0, st["k"], st["v"], stream)
+            hkv.attn_prefill_plan_run(st["plan"], st["q"], self.scale, st["out"], st["lse"], stream)
+
+    def close(self) -> None:
+        for st in self.steps:
+            if st["plan"] is not None:
+                hkv.hkv_prefill_plan_destroy(st["plan"])
+        self.steps = []
+        if self.cache is not None:
+            hkv.kv_cache_destroy(self.cache)
+            self.cache = None
+        self.pool.close()
+
+
 def workflow_prompt_tokens(wf: wl.Workflow, call: int) -> list:
     """The call's full prompt as token ids: static symbols as they are, a placeholder for call x as
     len_out[x] ids that nothing else uses (what the LLM wrote is not known; only that it is the same

@@ -537,3 +537,56 @@ def workflow_node_q(seed: int, node: int, n_tokens: int, num_q_heads: int) -> np
     """Query rows (bf16 bits, [n_tokens][Hq][128]) of the tokens of one tree node."""
     x = np.random.default_rng([seed, 23, node]).standard_normal(size=(n_tokens, num_q_heads, HEAD_DIM), dtype=np.float32)
     return f32_to_bf16_bits(x)
+
+
+# ---- token-level synthetic tensors (for engines that cache by token prefix)
+
+def _hash_normal(seed: int, tag: int, token_ids, positions, heads: int) -> np.ndarray:
+    """[n][heads][128] float32, approximately standard normal, a pure function of (seed, tag, token id,
+    position, head, dim): a counter-based generator (64-bit mix of the coordinates, sum of four
+    24-bit uniforms), so that equal (token, position) pairs give equal values in whatever call or
+    order they are asked for."""
+    ids = np.asarray(token_ids, dtype=np.uint64)[:, None, None]
+    pos = np.asarray(positions, dtype=np.uint64)[:, None, None]
+    h = np.arange(heads, dtype=np.uint64)[None, :, None]
+    d = np.arange(HEAD_DIM, dtype=np.uint64)[None, None, :]
+    with np.errstate(over="ignore"):
+        x = (ids * np.uint64(0x9E3779B97F4A7C15) + pos * np.uint64(0xC2B2AE3D27D4EB4F) + h * np.uint64(0x165667B19E3779F9) +
+             d * np.uint64(0xD6E8FEB86659FD93) + np.uint64(seed) * np.uint64(0xA0761D6478BD642F) + np.uint64(tag))
+        acc = np.zeros(x.shape, dtype=np.float64)
+        for r in range(4):
+            x = x + np.uint64(0x9E3779B97F4A7C15)
+            z = x
+            z = (z ^ (z >> np.uint64(30))) * np.uint64(0xBF58476D1CE4E5B9)
+            z = (z ^ (z >> np.uint64(27))) * np.uint64(0x94D049BB133111EB)
+            z = z ^ (z >> np.uint64(31))
+            acc += (z >> np.uint64(40)).astype(np.float64) * (1.0 / (1 << 24))
+    return ((acc - 2.0) * np.sqrt(3.0)).astype(np.float32)
+
+
+def token_kv(seed: int, token_ids, positions, num_kv_heads: int) -> Tuple[np.ndarray, np.ndarray]:
+    """K and V (bf16 bits, [n][Hkv][128]) of tokens given by (id, position in their prompt)."""
+    return (f32_to_bf16_bits(_hash_normal(seed, 1, token_ids, positions, num_kv_heads)),
+            f32_to_bf16_bits(_hash_normal(seed, 2, token_ids, positions, num_kv_heads)))
+
+
+def token_q(seed: int, token_ids, positions, num_q_heads: int) -> np.ndarray:
+    """Query rows (bf16 bits, [n][Hq][128]) of the same tokens."""
+    return f32_to_bf16_bits(_hash_normal(seed, 3, token_ids, positions, num_q_heads))
+
+
+def shared_prefix_prompts(seed: int, n_prompts: int = 12, n_systems: int = 2, n_contexts: int = 3,
+                          system_len: int = 48, context_len: int = 40, question_lo: int = 5,
+                          question_hi: int = 60) -> List[List[int]]:
+    """Token-id prompts with the structure of the evaluated workflows (system prompt, shared context,
+    private question), lengths deliberately not page-aligned, in an order that revisits prefixes."""
+    rng = np.random.default_rng([seed, 31])
+    systems = [list(rng.integers(0, 30000, size=system_len + int(rng.integers(0, 9)))) for _ in range(n_systems)]
+    contexts = [list(rng.integers(0, 30000, size=context_len + int(rng.integers(0, 17)))) for _ in range(n_contexts)]
+    prompts = []
+    for _ in range(n_prompts):
+        sy = systems[int(rng.integers(0, n_systems))]
+        cx = contexts[int(rng.integers(0, n_contexts))]
+        qu = list(rng.integers(0, 30000, size=int(rng.integers(question_lo, question_hi + 1))))
+        prompts.append([int(t) for t in sy + cx + qu])
+    return prompts

@@ -815,3 +815,41 @@ def test_sensitivity_shapes_small(gpu, oracle, model, mode):
             check_lse(r.lse.cpu().numpy(), exp_l, wk.name)
             r.close()
             dp.close()
+
+
+# ------------------------------------------------------------------------------ prefix cache end to end
+
+@pytest.mark.parametrize("seed,n_pages", [(3, 15), (4, 24), (5, 200)])
+def test_prefix_cache_engine_under_page_budget(gpu, oracle, seed, n_pages):
+    """Prompts with shared system prompts and contexts served one after another through kv_cache_* under
+    a page budget (tight: blocks are evicted and their pages reused; ample: everything stays): the pages
+    and hit counts equal the cache oracle's, and every prompt's uncached tokens get the attention output
+    the attention oracle computes from that prompt alone, written into pages of its own."""
+    import torch
+    from oracle import cache as ocache
+    prompts = wl.shared_prefix_prompts(seed)
+    Hq, Hkv = 8, 2
+    r = gpu.PrefixCacheRunner(prompts, n_pages, Hq, Hkv)
+    stats = r.prepare()
+    oc = ocache.PrefixCache(n_pages)
+    for st, toks in zip(r.steps, prompts):
+        pages, cached = oc.acquire(toks)
+        oc.release(pages)
+        assert list(st["pages"]) == pages and st["cached"] == cached
+    assert stats["evictions"] == oc.evictions and 0 < stats["hit_rate"] < 1
+    if n_pages < 30:
+        assert stats["evictions"] > 0
+    r.run()
+    torch.cuda.synchronize()
+    for st, toks in zip(r.steps, prompts):
+        n, cached = st["n"], st["cached"]
+        if n == cached:
+            continue
+        hp = oracle.HostPool((n + 15) // 16, Hkv, oracle.BF16)
+        table = np.arange((n + 15) // 16, dtype=np.int32)
+        hp.write(table, 0, *wl.token_kv(r.seed, toks, np.arange(n), Hkv))
+        q = wl.token_q(r.seed, toks[cached:], np.arange(cached, n), Hq)
+        exp_o, exp_l = oracle.attn_prefill(hp, q, [0, n - cached], table[None, :], [n], r.scale)
+        check_close(gpu.bf16_tensor_to_f64(st["out"]), exp_o, f"prompt of {n} tokens, {cached} cached")
+        check_lse(st["lse"].cpu().numpy(), exp_l, "prefix cache engine")
+    r.close()
