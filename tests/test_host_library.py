@@ -368,3 +368,22 @@ def test_decode_several_query_tokens_errors():
     plan = hkv.hkv_decode_plan_create_multi(pool, f.nodes, f.node_pages, f.req_leaf, 3, 4, hkv.PLAN_HOST_ONLY)
     assert hkv.hkv_decode_plan_part_counts(plan, 3).tolist() == [2, 2, 2]       # three query rows, root + leaf each
     hkv.hkv_decode_plan_destroy(plan)
+
+
+# ------------------------------------------------------------------------------ seeded input generators
+
+def test_token_level_inputs_are_a_function_of_token_and_position():
+    """What a prefix cache relies on: the K/V of a (token id, position) pair do not depend on the call that
+    asks for them; different pairs, heads, tensors and seeds differ; values look standard normal."""
+    ids, pos = np.array([5, 9, 5, 5]), np.array([0, 1, 2, 0])
+    k, v = wl.token_kv(3, ids, pos, 2)
+    assert k.shape == (4, 2, 128) and k.dtype == np.uint16
+    assert np.array_equal(k[0], k[3]) and np.array_equal(v[0], v[3])
+    assert not np.array_equal(k[0], k[2]) and not np.array_equal(k[0], v[0]) and not np.array_equal(k[0, 0], k[0, 1])
+    k2, _ = wl.token_kv(3, ids[1:3], pos[1:3], 2)
+    assert np.array_equal(k2, k[1:3])
+    assert not np.array_equal(wl.token_kv(4, ids, pos, 2)[0], k)
+    x = wl._hash_normal(1, 3, np.arange(500), np.arange(500) % 7, 4)
+    assert abs(float(x.mean())) < 0.01 and abs(float(x.std()) - 1.0) < 0.01 and float(np.abs(x).max()) <= 2 * np.sqrt(3.0)
+    prompts = wl.shared_prefix_prompts(3)
+    assert len({tuple(p[:40]) for p in prompts}) <= 2          # at most two distinct system prompts
