@@ -112,3 +112,61 @@ def test_config5_sampled(gpu, oracle):
     print(f"{w.name}: sampled {len(sample)} requests x {w.num_q_heads} heads: max_abs {res[0]:.3e} rel_l2 {res[1]:.3e}")
     r.close()
     dp.close()
+
+
+@pytest.mark.timeout(600)
+def test_pool_beyond_4_gib_per_buffer(gpu, oracle):
+    """Byte offsets inside the K and V buffers beyond 2^32: a 140 000-page bf16 pool (4.6 GB per buffer)
+    whose forest sits in the highest pages.  Pool writer, copy-on-write copy, both decode paths and
+    prefill are compared with the oracle run on a compact twin (same nodes and seeded K/V, page ids
+    renumbered 0..n-1; the oracle's invariance under page renumbering is pinned on the CPU)."""
+    import torch
+    from paper_2603_16104_amd import binding as hkv
+    num_pages, Hq, Hkv = 140_000, 32, 8
+    rng = np.random.default_rng(77)
+    parent = [-1] + [0] * 22
+    ntok = [256] + [int(t) for t in rng.integers(20, 130, size=22)]
+    n_used = sum((t + 15) // 16 for t in ntok)
+    high = (num_pages - 1 - rng.permutation(4000)[:n_used]).astype(np.int32)      # scattered over the top 4000 pages
+    if num_pages - 1 in high:                                      # the very last page belongs to the root
+        j = int(np.nonzero(high == num_pages - 1)[0][0])
+        high[0], high[j] = high[j], high[0]
+    else:
+        high[0] = num_pages - 1
+    leaves = list(range(1, 23))
+    for mode in ("decode", "prefill"):
+        q_len = np.asarray(ntok[1:], dtype=np.int32) if mode == "prefill" else None
+        big = wl.Workload(name="beyond_4gib_" + mode, num_q_heads=Hq, num_kv_heads=Hkv, kv_dtype=wl.KV_BF16, num_pages=num_pages,
+                          seed=41, forest=wl.make_forest(parent, ntok, leaves, high), mode=mode, q_len=q_len)
+        twin = wl.Workload(name="twin_" + mode, num_q_heads=Hq, num_kv_heads=Hkv, kv_dtype=wl.KV_BF16, num_pages=n_used,
+                           seed=41, forest=wl.make_forest(parent, ntok, leaves, np.arange(n_used, dtype=np.int32)), mode=mode,
+                           q_len=q_len)
+        hp = oracle.HostPool(n_used, Hkv, wl.KV_BF16)
+        hp.fill_from(twin)
+        exp_o, exp_l = oracle.run_workload(twin, hp)
+        dp = gpu.DevicePool(num_pages, Hkv, wl.KV_BF16, poison=False)
+        dp.fill_from(big)
+        # the bytes written to the highest page equal the oracle's for its twin page
+        per_page = Hkv * 16 * 128
+        top = dp.k.view(num_pages, per_page)[num_pages - 1].cpu().numpy().view(np.uint16)
+        assert np.array_equal(top, hp.k.reshape(n_used, per_page)[0])
+        r = (gpu.DecodeRunner if mode == "decode" else gpu.PrefillRunner)(dp, big)
+        r.run()
+        torch.cuda.synchronize()
+        res = check_close(gpu.bf16_tensor_to_f64(r.out), exp_o, big.name)
+        check_lse(r.lse.cpu().numpy(), exp_l, big.name)
+        print(f"{big.name}: max_abs {res[0]:.3e} rel_l2 {res[1]:.3e}")
+        r.close()
+        if mode == "decode":   # copy-on-write of the highest page into a fresh one, bytes compared on the device
+            held = hkv.kv_pool_alloc(dp.handle, num_pages)          # every page: so that page num_pages-1 is allocated
+            hkv.kv_pool_release(dp.handle, held[:10])              # ten free pages at the tail of the free list
+            hkv.kv_pool_retain(dp.handle, [num_pages - 1])
+            new = hkv.kv_pool_copy_on_write(dp.handle, [num_pages - 1])
+            torch.cuda.synchronize()
+            assert int(new[0]) != num_pages - 1
+            for t in (dp.k, dp.v):
+                tv = t.view(num_pages, per_page)
+                assert torch.equal(tv[int(new[0])], tv[num_pages - 1])
+        dp.close()
+        del dp
+        torch.cuda.empty_cache()
