@@ -170,3 +170,35 @@ def test_pool_beyond_4_gib_per_buffer(gpu, oracle):
         dp.close()
         del dp
         torch.cuda.empty_cache()
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("kv_dtype", [wl.KV_BF16, wl.KV_FP8_E4M3])
+def test_pool_write_largest_single_call(gpu, oracle, kv_dtype):
+    """kv_pool_write at its documented limit of 65536 pages (1 048 576 tokens) in one call, ragged at both
+    ends (first_slot 5, last page partly filled): bytes and scales bit-exact."""
+    import torch
+    from paper_2603_16104_amd import binding as hkv
+    n_pages, H, first = 65536, 1, 5
+    n_tok = n_pages * 16 - first - 9
+    rng = np.random.default_rng(23)
+    k = wl.f32_to_bf16_bits(rng.standard_normal((n_tok, H, 128), dtype=np.float32))
+    v = wl.f32_to_bf16_bits(rng.standard_normal((n_tok, H, 128), dtype=np.float32))
+    ids = rng.permutation(n_pages + 7).astype(np.int32)[:n_pages]
+    hp = oracle.HostPool(n_pages + 7, H, kv_dtype)
+    dp = gpu.DevicePool(n_pages + 7, H, kv_dtype)
+    if kv_dtype == wl.KV_FP8_E4M3:      # a continued fp8 page needs its first slots written before
+        head_k = wl.f32_to_bf16_bits(rng.standard_normal((first, H, 128), dtype=np.float32))
+        hp.write(ids[:1], 0, head_k, head_k)
+        dp.write(ids[:1], 0, gpu.to_device_bits(head_k), gpu.to_device_bits(head_k))
+    hp.write(ids, first, k, v)
+    dp.write(ids, first, gpu.to_device_bits(k), gpu.to_device_bits(v))
+    torch.cuda.synchronize()
+    assert np.array_equal(dp.k.cpu().numpy().view(hp.k.dtype), hp.k) and np.array_equal(dp.v.cpu().numpy().view(hp.v.dtype), hp.v)
+    if kv_dtype == wl.KV_FP8_E4M3:
+        used = np.zeros(n_pages + 7, dtype=bool)
+        used[ids] = True
+        for name in ("k_scale", "v_scale"):
+            g, o = getattr(dp, name).cpu().numpy()[used], getattr(hp, name)[used]
+            assert np.array_equal(g.view(np.uint32), o.view(np.uint32)), name
+    dp.close()

@@ -142,6 +142,9 @@ def test_pool_write_validates_before_touching_the_device():
         with pytest.raises(hkv.HkvError) as e:
             hkv.kv_pool_write(pool, args[0], args[1], args[2], 0x50000, 0x60000, stream=0)
         assert e.value.code == code
+    with pytest.raises(hkv.HkvError) as e:                                              # more than 65536 pages in one call
+        hkv.kv_pool_write(pool, np.zeros(65537, dtype=np.int32), 1, 65536 * 16, 0x50000, 0x60000, stream=0)
+    assert e.value.code == hkv.EINVAL and "65537 pages" in str(e.value)
     hkv.kv_pool_write(pool, np.zeros(0, dtype=np.int32), 0, 0, None, None, stream=0)    # empty write is a no-op
     p8 = fake_pool(8, dtype=hkv.FP8_E4M3)          # fp8 pages may be continued at any slot: same checks apply
     with pytest.raises(hkv.HkvError) as e:
