@@ -202,3 +202,52 @@ def test_pool_write_largest_single_call(gpu, oracle, kv_dtype):
             g, o = getattr(dp, name).cpu().numpy()[used], getattr(hp, name)[used]
             assert np.array_equal(g.view(np.uint32), o.view(np.uint32)), name
     dp.close()
+
+
+@pytest.mark.timeout(600)
+def test_very_long_shared_prefix(gpu, oracle):
+    """A 65 536-token prefix shared by 24 requests: decode (the prefix is cut into many LDS-staged chunks and
+    every row collects 30+ partials) element by element, prefill of 150-250 new tokens per request on
+    sampled query tokens (the page-id window of the prefill kernel is refilled hundreds of times)."""
+    import torch
+    rng = np.random.default_rng(5)
+    n_req, Hq, Hkv, root = 24, 4, 1, 65536
+    s = [int(x) for x in rng.integers(150, 251, size=n_req)]
+    parent, ntok = [-1] + [0] * n_req, [root] + s
+    n_used = sum((t + 15) // 16 for t in ntok)
+    pages = rng.permutation(n_used + 11).astype(np.int32)
+    f = wl.make_forest(parent, ntok, list(range(1, n_req + 1)), pages)
+    common = dict(num_q_heads=Hq, num_kv_heads=Hkv, kv_dtype=wl.KV_BF16, num_pages=n_used + 11, seed=61, forest=f)
+    wd = wl.Workload(name="long_prefix_decode", mode="decode", **common)
+    hp, dp = both_pools(gpu, oracle, wd)
+    exp_o, exp_l = oracle.run_workload(wd, hp)
+    r = gpu.DecodeRunner(dp, wd)
+    r.run()
+    torch.cuda.synchronize()
+    res = check_close(gpu.bf16_tensor_to_f64(r.out), exp_o, wd.name)
+    check_lse(r.lse.cpu().numpy(), exp_l, wd.name)
+    from paper_2603_16104_amd import binding as hkv
+    print(f"{wd.name}: max_abs {res[0]:.3e} rel_l2 {res[1]:.3e}, {hkv.hkv_decode_plan_max_parts(r.plan)} partials per row")
+    r.close()
+    wp = wl.Workload(name="long_prefix_prefill", mode="prefill", q_len=np.asarray(s, dtype=np.int32), **common)
+    pr = gpu.PrefillRunner(dp, wp)
+    pr.run()
+    torch.cuda.synchronize()
+    got_o, got_l = gpu.bf16_tensor_to_f64(pr.out), pr.lse.cpu().numpy()
+    assert np.isfinite(got_o).all()
+    obt, okv, *_ = oracle.flatten_workload(wp)
+    cu, q = wp.cu_q(), wp.q()
+    rows, qs, bts, lens = [], [], [], []
+    for _ in range(12):
+        req = int(rng.integers(0, n_req))
+        i = int(rng.choice([0, 1, 63, 64, s[req] - 1, int(rng.integers(0, s[req]))]))
+        rows.append(cu[req] + i)
+        qs.append(q[cu[req] + i])
+        bts.append(obt[req])
+        lens.append(okv[req] - s[req] + i + 1)
+    e_o, e_l = oracle.attn_decode(hp, np.stack(qs), np.stack(bts), np.array(lens, dtype=np.int32), float(wp.scale))
+    res = check_close(got_o[rows], e_o, wp.name)
+    check_lse(got_l[rows], e_l, wp.name)
+    print(f"{wp.name}: sampled {len(rows)} query tokens: max_abs {res[0]:.3e} rel_l2 {res[1]:.3e}")
+    pr.close()
+    dp.close()
