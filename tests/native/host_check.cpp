@@ -1,0 +1,303 @@
+// Exercises the host side of the library (pool bookkeeping, forest indexing, decode / prefill planning,
+// scheduling layer, prefix cache) with seeded random inputs, for a build with AddressSanitizer and
+// UndefinedBehaviorSanitizer.  No kernel is involved: the launchers the host code calls are replaced by
+// the stubs below and every plan is built host-only, so the program runs without a GPU.  Values are
+// checked by the Python tests; here only invariants that are cheap to state are asserted, the point is
+// that the sanitizers see every host code path.  Exit status 0 = clean.
+#include <algorithm>
+#include <cstdint>
+#include <cstdio>
+#include <cstdlib>
+#include <random>
+#include <vector>
+
+#include "../../include/heliumkv.h"
+#include "../../paper_2603_16104_amd/csrc/hkv_internal.h"
+
+namespace hkv {
+hipError_t launch_pool_write(const PoolWriteLaunch &, hipStream_t) { return hipSuccess; }
+hipError_t launch_pool_copy(const PoolCopyLaunch &, hipStream_t) { return hipSuccess; }
+hipError_t launch_decode(const DecodeLaunch &, hipStream_t, hipEvent_t, hipEvent_t) { return hipSuccess; }
+hipError_t launch_rows_fp32(const RowsLaunch &, hipStream_t) { return hipSuccess; }
+hipError_t launch_pool_write_fp32(const PoolWriteLaunch &, hipStream_t) { return hipSuccess; }
+hipError_t launch_prefill(const PrefillLaunch &, hipStream_t) { return hipSuccess; }
+hipError_t launch_lse_merge(const float *, const float *, const int32_t *, const int32_t *, int32_t, void *, int32_t, float *,
+                            hipStream_t) { return hipSuccess; }
+hipError_t launch_lse_merge_dense(const float *, const float *, const int32_t *, int32_t, int32_t, int32_t, void *, int32_t,
+                                  float *, hipStream_t, hipEvent_t, hipEvent_t) { return hipSuccess; }
+hipError_t run_read_probe(const void *const *, int, size_t, int, int, float *, hipStream_t) { return hipSuccess; }
+hipError_t run_mfma_probe(int, int, int, int, float *, float *, hipStream_t) { return hipSuccess; }
+int prefill_tile_tokens(int group) { return 256 / group; }
+}  // namespace hkv
+
+static int failures = 0;
+#define CHECK(cond)                                                        \
+    do {                                                                   \
+        if (!(cond)) {                                                     \
+            std::fprintf(stderr, "%s:%d: %s\n", __FILE__, __LINE__, #cond); \
+            ++failures;                                                    \
+        }                                                                  \
+    } while (0)
+
+static hkv_pool *make_pool(int num_pages, int heads, int dtype, const std::vector<int32_t> *order = nullptr) {
+    hkv_pool_desc d{};
+    d.num_pages = num_pages;
+    d.page_size = 16;
+    d.num_kv_heads = heads;
+    d.head_dim = 128;
+    d.dtype = dtype;
+    d.k_pages = reinterpret_cast<void *>(0x10000);  // never dereferenced on the host
+    d.v_pages = reinterpret_cast<void *>(0x20000);
+    if (dtype == HKV_FP8_E4M3) {
+        d.k_scale = reinterpret_cast<float *>(0x30000);
+        d.v_scale = reinterpret_cast<float *>(0x40000);
+    }
+    d.free_order = order ? order->data() : nullptr;
+    hkv_pool *p = nullptr;
+    CHECK(kv_pool_create(&d, &p) == HKV_OK);
+    return p;
+}
+
+static void pool_traces(std::mt19937 &rng) {
+    for (int trial = 0; trial < 20; ++trial) {
+        const int n = 5 + rng() % 60;
+        std::vector<int32_t> order(n);
+        for (int i = 0; i < n; ++i) order[i] = i;
+        std::shuffle(order.begin(), order.end(), rng);
+        hkv_pool *pool = make_pool(n, 1 + rng() % 4, trial & 1 ? HKV_FP8_E4M3 : HKV_BF16, &order);
+        std::vector<int32_t> held;
+        for (int step = 0; step < 300; ++step) {
+            const int op = rng() % 5;
+            if (op == 0) {
+                std::vector<int32_t> ids(1 + rng() % 6);
+                if (kv_pool_alloc(pool, (int32_t)ids.size(), ids.data()) == HKV_OK) held.insert(held.end(), ids.begin(), ids.end());
+            } else if (op == 1 && !held.empty()) {
+                std::vector<int32_t> ids{held[rng() % held.size()]};
+                CHECK(kv_pool_retain(pool, 1, ids.data()) == HKV_OK);
+                held.push_back(ids[0]);
+            } else if (op == 2 && !held.empty()) {
+                const size_t i = rng() % held.size();
+                CHECK(kv_pool_release(pool, 1, &held[i]) == HKV_OK);
+                held.erase(held.begin() + i);
+            } else if (op == 3 && !held.empty()) {
+                int32_t id = held[rng() % held.size()];
+                const int32_t before = id;
+                const int rc = kv_pool_copy_on_write(pool, 1, &id, nullptr);
+                if (rc == HKV_OK && id != before) *std::find(held.begin(), held.end(), before) = id;
+            } else {
+                int32_t bad[2] = {-1, n + (int32_t)(rng() % 3)};
+                CHECK(kv_pool_retain(pool, 2, bad) == HKV_ERANGE);
+                CHECK(kv_pool_refcount(pool, bad[1]) == HKV_ERANGE);
+            }
+            int64_t refs = 0;
+            for (int p = 0; p < n; ++p) refs += kv_pool_refcount(pool, p);
+            CHECK(refs == (int64_t)held.size());
+        }
+        // validation of kv_pool_write happens before anything touches a device
+        int32_t bad_page = n;
+        CHECK(kv_pool_write(pool, &bad_page, 0, 4, reinterpret_cast<void *>(0x50000), reinterpret_cast<void *>(0x60000), nullptr) ==
+              HKV_ERANGE);
+        CHECK(kv_pool_destroy(pool) == HKV_OK);
+    }
+}
+
+struct Forest {
+    std::vector<hkv_node> nodes;
+    std::vector<int32_t> pages, leaves;
+    int max_pages = 1;
+};
+
+static Forest random_forest(std::mt19937 &rng, int num_pages, bool ragged_internal = false) {
+    Forest f;
+    const int n_nodes = 1 + rng() % 40;
+    std::vector<int> kids(n_nodes, 0), depth_pages(n_nodes, 0);
+    int next_page = 0;
+    for (int v = 0; v < n_nodes; ++v) {
+        const int parent = (v == 0 || rng() % 6 == 0) ? -1 : (int)(rng() % v);
+        if (parent >= 0) ++kids[parent];
+        int tokens = (rng() % 5 == 0) ? 0 : 16 * (1 + rng() % 12);
+        f.nodes.push_back({parent, 0, 0, tokens});
+    }
+    for (int v = 0; v < n_nodes; ++v) {
+        hkv_node &nd = f.nodes[v];
+        if (kids[v] == 0 && nd.n_tokens > 0 && rng() % 2) nd.n_tokens -= rng() % 15;  // ragged leaf
+        if (ragged_internal && kids[v] > 0 && nd.n_tokens > 0) nd.n_tokens -= 3;      // malformed on purpose
+        nd.page_begin = next_page;
+        nd.n_pages = (nd.n_tokens + 15) / 16;
+        next_page += nd.n_pages;
+        depth_pages[v] = nd.n_pages + (nd.parent >= 0 ? depth_pages[nd.parent] : 0);
+        f.max_pages = std::max(f.max_pages, depth_pages[v]);
+    }
+    f.pages.resize(next_page);
+    for (int i = 0; i < next_page; ++i) f.pages[i] = (int32_t)(rng() % num_pages);
+    const int n_req = rng() % 30;
+    for (int r = 0; r < n_req; ++r) f.leaves.push_back((int32_t)(rng() % n_nodes));
+    return f;
+}
+
+static void forests_and_plans(std::mt19937 &rng) {
+    for (int trial = 0; trial < 200; ++trial) {
+        const int num_pages = 600, heads = 1 << (rng() % 4);
+        const int group = 1 + rng() % 16;
+        const int dtype = trial % 5 == 4 ? HKV_FP32 : (trial & 1 ? HKV_FP8_E4M3 : HKV_BF16);
+        hkv_pool *pool = make_pool(num_pages, heads, dtype);
+        Forest f = random_forest(rng, num_pages, trial % 17 == 16);
+        const int n_nodes = (int)f.nodes.size(), n_req = (int)f.leaves.size();
+        std::vector<int32_t> bt((size_t)n_req * f.max_pages), kv_len(n_req), indptr(n_nodes + 1), idx((size_t)n_nodes * std::max(n_req, 1)),
+            tok_start(n_nodes);
+        const int rc = prefix_tree_flatten(f.nodes.data(), n_nodes, f.pages.data(), (int32_t)f.pages.size(), f.leaves.data(), n_req,
+                                           f.max_pages, bt.data(), kv_len.data(), indptr.data(), idx.data(), tok_start.data());
+        if (trial % 17 == 16) {
+            CHECK(rc == HKV_ETREE || rc == HKV_OK);  // OK only if no internal node happened to hold tokens
+        } else {
+            CHECK(rc == HKV_OK);
+        }
+        if (rc == HKV_OK) {
+            // a table one page too short is refused, not overrun
+            if (f.max_pages > 1 && n_req > 0) {
+                int deepest = 0;
+                for (int r = 0; r < n_req; ++r) deepest = std::max(deepest, (kv_len[r] + 15) / 16);
+                if (deepest > 1)
+                    CHECK(prefix_tree_flatten(f.nodes.data(), n_nodes, f.pages.data(), (int32_t)f.pages.size(), f.leaves.data(), n_req,
+                                              deepest - 1, bt.data(), kv_len.data(), nullptr, nullptr, nullptr) == HKV_ENOMEM);
+            }
+            hkv_decode_plan *dp = nullptr;
+            CHECK(hkv_decode_plan_create(pool, f.nodes.data(), n_nodes, f.pages.data(), (int32_t)f.pages.size(), f.leaves.data(), n_req,
+                                         heads * group, HKV_PLAN_HOST_ONLY, &dp) == HKV_OK);
+            if (dp) {
+                std::vector<int32_t> items((size_t)hkv_decode_plan_num_items(dp) * 8 + 8), counts(n_req + 1);
+                CHECK(hkv_decode_plan_items(dp, items.data()) == HKV_OK);
+                CHECK(hkv_decode_plan_part_counts(dp, counts.data()) == HKV_OK);
+                CHECK(hkv_decode_plan_num_parts(dp) == (int64_t)n_req * heads * group * hkv_decode_plan_max_parts(dp) ||
+                      dtype == HKV_FP32);
+                (void)hkv_decode_plan_workspace_bytes(dp);
+                CHECK(attn_decode_plan_run(dp, nullptr, 1.f, nullptr, nullptr, nullptr, 0, nullptr) != HKV_OK || n_req == 0);
+                CHECK(hkv_decode_plan_destroy(dp) == HKV_OK);
+            }
+            // several query tokens per request: needs leaves that hold at least that many tokens
+            hkv_decode_plan *mp = nullptr;
+            const int T = 1 + rng() % 16;
+            const int rcm = hkv_decode_plan_create_multi(pool, f.nodes.data(), n_nodes, f.pages.data(), (int32_t)f.pages.size(),
+                                                         f.leaves.data(), n_req, T, heads * group, HKV_PLAN_HOST_ONLY, &mp);
+            CHECK(rcm == HKV_OK || rcm == HKV_EINVAL);
+            if (mp) CHECK(hkv_decode_plan_destroy(mp) == HKV_OK);
+            // prefill plan over the flattened tables: the last node of every path is new
+            std::vector<int32_t> cu(n_req + 1, 0);
+            for (int r = 0; r < n_req; ++r) cu[r + 1] = cu[r] + std::min<int32_t>(kv_len[r], f.nodes[f.leaves[r]].n_tokens);
+            hkv_prefill_plan *pp = nullptr;
+            const int rcp = hkv_prefill_plan_create(pool, cu.data(), bt.data(), f.max_pages, kv_len.data(), n_req, heads * group,
+                                                    HKV_PLAN_HOST_ONLY, &pp);
+            if (dtype == HKV_FP8_E4M3) {
+                CHECK(rcp == HKV_ESHAPE && pp == nullptr);  // prefill reads bf16 and fp32 pools only
+            } else {
+                if (rcp != HKV_OK) std::fprintf(stderr, "prefill plan: %s\n", hkv_last_error());
+                CHECK(rcp == HKV_OK);
+            }
+            if (pp) {
+                std::vector<int32_t> tiles((size_t)hkv_prefill_plan_num_tiles(pp) * 8 + 8);
+                CHECK(hkv_prefill_plan_tiles(pp, tiles.data()) == HKV_OK);
+                CHECK(hkv_prefill_plan_destroy(pp) == HKV_OK);
+            }
+            std::vector<int64_t> up(n_req + 1);
+            CHECK(prefix_tree_prefill_usage(f.nodes.data(), n_nodes, f.leaves.data(), n_req, up.data()) == HKV_OK);
+        }
+        CHECK(kv_pool_destroy(pool) == HKV_OK);
+    }
+}
+
+static void scheduling_layer(std::mt19937 &rng) {
+    for (int trial = 0; trial < 150; ++trial) {
+        const int n_calls = 1 + rng() % 25, n_workers = 1 + rng() % 3;
+        std::vector<int32_t> indptr{0}, syms, len_out, worker;
+        for (int c = 0; c < n_calls; ++c) {
+            const int n_seg = 1 + rng() % 4;
+            for (int s = 0; s < n_seg; ++s) {
+                if (c > 0 && rng() % 3 == 0) {
+                    syms.push_back(-(int32_t)(rng() % c) - 1);  // quote an earlier call's output
+                } else {
+                    const int base = rng() % 3 * 1000, len = 1 + rng() % 20;
+                    for (int i = 0; i < len; ++i) syms.push_back(base + i);  // long shared runs
+                }
+            }
+            if (trial % 25 == 24 && c == n_calls - 1) syms.push_back(-(int32_t)n_calls - 1);  // names a missing call
+            indptr.push_back((int32_t)syms.size());
+            len_out.push_back((int32_t)(rng() % 40));
+            worker.push_back((int32_t)(rng() % n_workers));
+        }
+        hkv_trt *t = nullptr;
+        const int rc = trt_build(indptr.data(), syms.data(), len_out.data(), worker.data(), n_calls, &t);
+        if (trial % 25 == 24) {
+            CHECK(rc == HKV_ETREE && t == nullptr);
+            continue;
+        }
+        CHECK(rc == HKV_OK);
+        if (!t) continue;
+        const int nn = trt_num_nodes(t), ns = trt_num_syms(t);
+        CHECK(trt_num_calls(t) == n_calls);
+        std::vector<int32_t> parent(nn), call(nn), sb(nn), sl(nn), sy(ns + 1), leaf(n_calls);
+        std::vector<int64_t> w(nn);
+        CHECK(trt_nodes(t, parent.data(), w.data(), call.data(), sb.data(), sl.data(), sy.data(), leaf.data()) == HKV_OK);
+        std::vector<int32_t> sip(n_workers + 1), sig(n_calls);
+        std::vector<int64_t> B(n_calls), C(n_calls);
+        int64_t T = 0, T2 = 0;
+        CHECK(trt_schedule(t, n_workers, 4096, sip.data(), sig.data(), B.data(), C.data(), &T) == HKV_OK);
+        CHECK(trt_evaluate(t, sip.data(), sig.data(), n_workers, 4096, B.data(), C.data(), &T2) == HKV_OK);
+        CHECK(T == T2);
+        std::vector<int64_t> up(n_calls);
+        CHECK(trt_prefill_usage(t, sig.data(), sip[1], up.data()) == HKV_OK);
+        int32_t bad = n_calls;
+        CHECK(trt_prefill_usage(t, &bad, 1, up.data()) == HKV_ERANGE);
+        CHECK(trt_destroy(t) == HKV_OK);
+    }
+}
+
+static void prefix_cache(std::mt19937 &rng) {
+    for (int trial = 0; trial < 30; ++trial) {
+        const int n_pages = 4 + rng() % 40;
+        hkv_pool *pool = make_pool(n_pages, 1, HKV_BF16);
+        hkv_cache *c = nullptr;
+        CHECK(kv_cache_create(pool, &c) == HKV_OK);
+        std::vector<std::vector<int32_t>> live;
+        for (int step = 0; step < 200; ++step) {
+            const int op = rng() % 4;
+            if (op <= 1) {
+                const int n = rng() % 90;
+                std::vector<int32_t> toks(n), pages(n / 16 + 2);
+                const int32_t sys = (int32_t)(rng() % 2);  // one of two 48-token system prompts, then a random tail
+                for (int i = 0; i < n; ++i) toks[i] = i < 48 ? 100 * sys + i : (int32_t)(rng() % 5);
+                int32_t cached = -1;
+                const int rc = kv_cache_acquire(c, toks.data(), n, rng() % 7 == 0, pages.data(), &cached);
+                CHECK(rc == HKV_OK || rc == HKV_ENOMEM);
+                if (rc == HKV_OK) {
+                    CHECK(cached >= 0 && cached <= n && cached % 16 == 0);
+                    pages.resize((n + 15) / 16);
+                    live.push_back(pages);
+                }
+            } else if (op == 2 && !live.empty()) {
+                const size_t i = rng() % live.size();
+                CHECK(kv_cache_release(c, live[i].data(), (int32_t)live[i].size()) == HKV_OK);
+                (void)kv_cache_unpin(c, live[i].data(), (int32_t)live[i].size());
+                live.erase(live.begin() + i);
+            } else {
+                int32_t stray = n_pages + 3;
+                CHECK(kv_cache_release(c, &stray, 1) == HKV_ERANGE);
+            }
+            int64_t blocks, hits, misses, ev;
+            CHECK(kv_cache_stats(c, &blocks, &hits, &misses, &ev) == HKV_OK);
+            CHECK(blocks <= n_pages);
+        }
+        CHECK(kv_cache_destroy(c) == HKV_OK);
+        CHECK(kv_pool_num_free(pool) == n_pages);  // the cache returned everything it held
+        CHECK(kv_pool_destroy(pool) == HKV_OK);
+    }
+}
+
+int main() {
+    std::mt19937 rng(20260316u);
+    pool_traces(rng);
+    forests_and_plans(rng);
+    scheduling_layer(rng);
+    prefix_cache(rng);
+    std::printf("host_check: %d failed checks\n", failures);
+    return failures ? 1 : 0;
+}
