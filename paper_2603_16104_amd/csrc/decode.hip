@@ -222,10 +222,13 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
         for (int dt = 0; dt < 8; ++dt) vf[dt] = ld16(p + dt * ((DT == 0) ? 512 : 256));
     };
 
-    // One step over TB tokens.  MORE: another step follows, so its K and V are requested as soon as
+    // One step over TB tokens.  LAST: the item's last step, the only one that may reach past the item's
+    // end (every other instance carries no end-of-item masking at all).  MORE: another step follows, so its K and V are requested as soon as
     // the registers are free; the last step (and only it) may reach past the item's end.
-    auto step = [&](auto more_tag, int b, const StepPages<DT> &cur, const StepPages<DT> &nxt) {
+    auto step = [&](auto more_tag, auto last_tag, int b, const StepPages<DT> &cur, const StepPages<DT> &nxt) {
         constexpr bool MORE = decltype(more_tag)::value;
+        constexpr bool LAST = decltype(last_tag)::value;
+        static_assert(!(MORE && LAST), "the last step has no successor");
         // ---- S^T = K Q^T
         float s[NS];
         if constexpr (DT == 0) {
@@ -263,7 +266,7 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
 
         // ---- online softmax; lane-local score j belongs to token tok0 + j of the item
         const int tok0 = b * TB + g * NS;
-        const bool tail = !MORE && b * TB + TB > it.n_tokens;  // step reaches past the item's end
+        const bool tail = LAST && b * TB + TB > it.n_tokens;  // step reaches past the item's end
         const int first_bad = it.n_tokens - tok0;               // lane-local index of the first invalid token
         if (tail) {
 #pragma unroll
@@ -389,15 +392,18 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
         issue_stage(0);
         if (n_blk > 1) issue_stage(1);
         HKV_STAMP(1);
-        for (int b = 0; b < n_blk; ++b) {
+        // one step of the item; the last one is peeled off the loop: it alone waits for every load and
+        // carries the end-of-item masking
+        auto staged_step = [&](auto last_tag, int b) {
+            constexpr bool LAST = decltype(last_tag)::value;
             StepPages<DT> cur;
             step_pages(cur, b);  // fp8 scales of this step
             // this wavefront's share of step b has landed once at most the next step's 4 loads are pending
             __builtin_amdgcn_sched_barrier(0);
-            if (b + 1 < n_blk)
-                __builtin_amdgcn_s_waitcnt(vmcnt_imm(4));
-            else
+            if constexpr (LAST)
                 __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+            else
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(4));
             __builtin_amdgcn_s_barrier();  // everyone's share landed; everyone is done with step b-1
             __builtin_amdgcn_sched_barrier(0);
             if (b + 2 < n_blk) issue_stage(b + 2);  // overwrites the stage of step b-1
@@ -409,10 +415,14 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
                     kf[f] = *reinterpret_cast<const u32x4 *>(stage + f * 1024);
                     vf[f] = *reinterpret_cast<const u32x4 *>(stage + (8 + f) * 1024);
                 }
-                step(std::false_type{}, b, cur, cur);
+                step(std::false_type{}, last_tag, b, cur, cur);
             }
+        };
+        for (int b = 0; b + 1 < n_blk; ++b) {
+            staged_step(std::false_type{}, b);
             if (b == 0) HKV_STAMP(2);
         }
+        staged_step(std::true_type{}, n_blk - 1);
         HKV_STAMP(4);
         if (active) {
             const float l_row = rows_sum(l_run);
@@ -444,7 +454,7 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
         HKV_STAMP(1);
         bool first = true;
         while (b + n_ts < n_blk) {
-            step(std::true_type{}, b, cur, nxt);
+            step(std::true_type{}, std::false_type{}, b, cur, nxt);
             if (first) {
                 HKV_STAMP(2);
                 first = false;
@@ -454,7 +464,7 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
             load_step_pages<DT>(nxt, a, it, b + n_ts, last_page);
         }
         HKV_STAMP(3);
-        step(std::false_type{}, b, cur, nxt);
+        step(std::false_type{}, std::true_type{}, b, cur, nxt);
         HKV_STAMP(4);
     }
 
