@@ -250,6 +250,10 @@ size_t hkv_decode_plan_workspace_bytes(const hkv_decode_plan *plan);
  * `node` to n_req requests x (num_q_heads / num_kv_heads) heads of kv_head; row (request r, head
  * h) of the item writes partial (r*num_q_heads + h)*max_parts + part_slot. */
 int32_t hkv_decode_plan_num_items(const hkv_decode_plan *plan);
+/* Workgroups of the per-node kernel: one per item, except that in forests with more items than the
+ * chip holds at once the short items of at most 16 query rows (listed last) share a workgroup four
+ * at a time, one item per wavefront. */
+int32_t hkv_decode_plan_num_workgroups(const hkv_decode_plan *plan);
 int32_t hkv_decode_plan_num_parts(const hkv_decode_plan *plan); /* n_req*num_q_heads*max_parts */
 int hkv_decode_plan_items(const hkv_decode_plan *plan, int32_t *items_out /* [n_items][8] */);
 int32_t hkv_decode_plan_max_parts(const hkv_decode_plan *plan);

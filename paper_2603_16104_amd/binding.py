@@ -26,7 +26,7 @@ EXPORTS = [
     "hkv_last_error", "kv_pool_create", "kv_pool_destroy", "kv_pool_alloc", "kv_pool_retain", "kv_pool_release", "kv_pool_copy_on_write",
     "kv_pool_num_free", "kv_pool_refcount", "kv_pool_write", "prefix_tree_flatten", "prefix_tree_prefill_usage",
     "lse_merge", "hkv_decode_plan_create", "hkv_decode_plan_create_multi", "hkv_decode_plan_destroy", "hkv_decode_plan_workspace_bytes",
-    "hkv_decode_plan_num_items", "hkv_decode_plan_num_parts", "hkv_decode_plan_items",
+    "hkv_decode_plan_num_items", "hkv_decode_plan_num_workgroups", "hkv_decode_plan_num_parts", "hkv_decode_plan_items",
     "hkv_decode_plan_max_parts", "hkv_decode_plan_part_counts", "lse_merge_dense", "attn_decode_plan_run",
     "hkv_decode_plan_set_profiling", "hkv_decode_plan_elapsed_ms",
     "attn_decode_prefix_tree", "attn_decode_workspace_bytes", "hkv_prefill_plan_create", "hkv_prefill_plan_destroy",
@@ -236,6 +236,10 @@ def hkv_decode_plan_items(plan) -> np.ndarray:
     items = np.empty((n, 8), dtype=np.int32)
     _check(lib().hkv_decode_plan_items(plan, _hp(items)))
     return items
+
+
+def hkv_decode_plan_num_workgroups(plan) -> int:
+    return _check(lib().hkv_decode_plan_num_workgroups(plan))
 
 
 def hkv_decode_plan_num_parts(plan) -> int:

@@ -72,6 +72,7 @@ struct hkv_decode_plan {
     // one device allocation holding items | pages | node_req_idx | part_count
     void *dev = nullptr;
     DecodeItem *d_items = nullptr;
+    int32_t n_single = 0;  // items [0, n_single) run one per workgroup, the rest four per workgroup
     int32_t *d_pages = nullptr, *d_node_req_idx = nullptr, *d_part_count = nullptr;
     bool profiling = false, profiled_run = false, node_only = false;
     hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};  // begin/end of the node kernel, begin/end of the merge
@@ -537,9 +538,24 @@ static void plan_items(hkv_decode_plan &pl) {
             }
         }
     }
-    std::stable_sort(protos.begin(), protos.end(), [](const Proto &a, const Proto &b) { return a.cost > b.cost; });
+    // Forests with more items than the chip holds at once: the short items of at most 16 rows are run four
+    // to a workgroup, one per wavefront (a workgroup's start-up then serves four items, and such a
+    // wavefront streams its whole item with one step in flight); they are listed behind the others.
+    const int step_tokens = pl.pool->d.dtype == HKV_FP8_E4M3 ? 64 : 32;
+    const int pack_tokens = env_int("HKV_DECODE_PACK_TOKENS", 12 * step_tokens);
+    const int pack_mode = env_int("HKV_DECODE_PACK", 2);  // 1: never, 2: when the items exceed the resident workgroups, 3: always
+    const bool pack = pack_mode == 3 || (pack_mode == 2 && (int64_t)protos.size() > kResidentGroups);
+    auto packable = [&](const Proto &p) { return pack && p.it.n_req * G <= 16 && p.it.n_tokens <= pack_tokens; };
+    std::stable_sort(protos.begin(), protos.end(), [&](const Proto &a, const Proto &b) {
+        const bool pa = packable(a), pb = packable(b);
+        return pa != pb ? pb : a.cost > b.cost;  // one item per workgroup first, heavy before light in both classes
+    });
     pl.items.clear();
-    for (auto &p : protos) pl.items.push_back(p.it);
+    pl.n_single = 0;
+    for (auto &p : protos) {
+        pl.items.push_back(p.it);
+        pl.n_single += !packable(p);
+    }
     pl.part_count.assign(pl.n_req, 0);
     pl.max_parts = 1;
     for (int r = 0; r < pl.n_req; ++r) {
@@ -742,6 +758,10 @@ extern "C" int hkv_decode_plan_items(const hkv_decode_plan *plan, int32_t *items
     if (!plan->items.empty()) memcpy(items_out, plan->items.data(), sizeof(DecodeItem) * plan->items.size());
     return HKV_OK;
 }
+extern "C" int32_t hkv_decode_plan_num_workgroups(const hkv_decode_plan *plan) {
+    if (!plan) return fail(HKV_EINVAL, "null plan");
+    return plan->n_single + ((int32_t)plan->items.size() - plan->n_single + 3) / 4;
+}
 extern "C" int32_t hkv_decode_plan_max_parts(const hkv_decode_plan *plan) {
     return plan ? plan->max_parts : fail(HKV_EINVAL, "null plan");
 }
@@ -779,7 +799,7 @@ extern "C" int attn_decode_plan_run(hkv_decode_plan *plan, const void *q, float 
     if (!plan->items.empty()) {
         DecodeLaunch a{view_of(plan->pool), q, plan->d_items, plan->d_pages, plan->d_node_req_idx, o_parts, lse_parts,
                        (int32_t)plan->items.size(), plan->num_q_heads, plan->max_parts, scale, nullptr,
-                       plan->d_row_leaf, plan->d_row_limit};
+                       plan->d_row_leaf, plan->d_row_limit, plan->n_single};
         HKV_HIP(launch_decode(a, s, prof ? plan->ev[0] : nullptr, prof ? plan->ev[1] : nullptr));
     }
     if (plan->node_only) return HKV_OK;

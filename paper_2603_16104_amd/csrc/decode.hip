@@ -133,19 +133,25 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
     constexpr int BB = Traits<DT>::kBlockBytes;
 
     HKV_STAMP(0);
-    const DecodeItem it = a.items[blockIdx.x];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // Workgroups [0, n_single) run one item each.  The workgroups behind them run four short items
+    // of at most 16 rows each, one per wavefront (no LDS, no barrier: the wavefronts are independent),
+    // so that a forest of many short nodes does not pay a workgroup's start-up per 64 tokens.
+    const bool packed = (int)blockIdx.x >= a.n_single;
+    const int item_idx = packed ? a.n_single + kWaves * ((int)blockIdx.x - a.n_single) + wave : (int)blockIdx.x;
+    if (packed && item_idx >= a.n_items) return;  // wavefront-uniform
+    const DecodeItem it = a.items[item_idx];
     const int m = lane & 15, g = lane >> 4;
     const int Hkv = a.pool.num_kv_heads;
     const int G = a.num_q_heads / Hkv;
     const int rows = it.n_req * G;
     // Up to 16 rows: the four wavefronts split the tokens and read K/V straight into registers.
     // More rows: each wavefront owns a 16-row tile, all tokens, and K/V are staged once in LDS.
-    const bool shared = rows > 16;
+    const bool shared = !packed && rows > 16;
     const int n_rt = shared ? kWaves : 1;
-    const int n_ts = kWaves / n_rt;
-    const int rt = wave % n_rt, ts = wave / n_rt;
+    const int n_ts = packed ? 1 : kWaves / n_rt;
+    const int rt = packed ? 0 : wave % n_rt, ts = packed ? 0 : wave / n_rt;
     const float c = a.scale * kLog2e;
 
     // Q^T operands of this wavefront's 16 rows; rows past the item's end are zero.  The loads are
@@ -327,6 +333,20 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
         }
     };
 
+    // Partials of a wavefront that has seen all tokens of its rows: normalise and store from registers.
+    auto write_rows = [&](int req) {
+        const float l_row = rows_sum(l_run);
+        if (row < rows) {
+            // a row that saw no token of this item delivers the empty partial (o = 0, lse = -inf)
+            const float inv = l_row > 0.f ? 1.0f / l_row : 0.f;
+            const size_t part = (size_t)(req * a.num_q_heads + it.kv_head * G + row % G) * a.max_parts + it.part_slot;
+            float *op = a.o_parts + part * kHeadDim + 4 * g;
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) *reinterpret_cast<f32x4 *>(op + 16 * dt) = o[dt] * inv;
+            if (g == 0) a.lse_parts[part] = l_row > 0.f ? (m_run * c + fast_log2(l_row)) * kLn2 : -INFINITY;
+        }
+    };
+
     if (shared) {
         // ---- K/V staged in LDS, fetched once for all row tiles of the item (LDS-direct loads: the
         // data in flight occupies no registers, so two further steps are kept in flight).  A stage
@@ -424,18 +444,7 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
         }
         staged_step(std::true_type{}, n_blk - 1);
         HKV_STAMP(4);
-        if (active) {
-            const float l_row = rows_sum(l_run);
-            if (row < rows) {
-                // a row that saw no token of this item delivers the empty partial (o = 0, lse = -inf)
-                const float inv = l_row > 0.f ? 1.0f / l_row : 0.f;
-                const size_t part = (size_t)(req * a.num_q_heads + it.kv_head * G + row % G) * a.max_parts + it.part_slot;
-                float *op = a.o_parts + part * kHeadDim + 4 * g;
-#pragma unroll
-                for (int dt = 0; dt < 8; ++dt) *reinterpret_cast<f32x4 *>(op + 16 * dt) = o[dt] * inv;
-                if (g == 0) a.lse_parts[part] = l_row > 0.f ? (m_run * c + fast_log2(l_row)) * kLn2 : -INFINITY;
-            }
-        }
+        if (active) write_rows(req);
         HKV_STAMP(6);
         return;
     }
@@ -466,6 +475,11 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
         HKV_STAMP(3);
         step(std::false_type{}, std::true_type{}, b, cur, nxt);
         HKV_STAMP(4);
+    }
+    if (packed) {  // this wavefront did the whole item (it holds at least one token, so req is loaded)
+        write_rows(req);
+        HKV_STAMP(6);
+        return;
     }
 
     // combine the wavefronts that split the tokens of a row tile, normalise, write the partials
@@ -515,10 +529,11 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
 // their difference is the kernel's duration without the gap to its neighbours in the queue.
 hipError_t launch_decode(const DecodeLaunch &a, hipStream_t s, hipEvent_t ev_begin, hipEvent_t ev_end) {
     if (a.n_items <= 0) return hipSuccess;
+    const dim3 grid(a.n_single + (a.n_items - a.n_single + kWaves - 1) / kWaves);
     if (a.pool.dtype == 0)
-        hipExtLaunchKernelGGL(decode_node_kernel<0>, dim3(a.n_items), dim3(kThreads), 0, s, ev_begin, ev_end, 0, a);
+        hipExtLaunchKernelGGL(decode_node_kernel<0>, grid, dim3(kThreads), 0, s, ev_begin, ev_end, 0, a);
     else
-        hipExtLaunchKernelGGL(decode_node_kernel<1>, dim3(a.n_items), dim3(kThreads), 0, s, ev_begin, ev_end, 0, a);
+        hipExtLaunchKernelGGL(decode_node_kernel<1>, grid, dim3(kThreads), 0, s, ev_begin, ev_end, 0, a);
     return hipGetLastError();
 }
 

@@ -65,6 +65,9 @@ struct DecodeLaunch {
     // among the request's newest tokens), every other node of its path it sees whole.
     const int32_t *row_leaf;     // device [n_req * T]
     const int32_t *row_limit;    // device [n_req * T]
+    // Items [0, n_single) get a workgroup each; the items behind them (short, at most 16 rows) are run
+    // four to a workgroup, one per wavefront.
+    int32_t n_single;
 };
 
 struct PrefillLaunch {

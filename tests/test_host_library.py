@@ -228,6 +228,13 @@ def _check_decode_plan(w, oracle):
             covered[r][kv_head, a: a + n_tok] += 1
             slots[r][kv_head, slot] += 1
     assert (items[:, 2] == np.arange(len(items)) % w.num_kv_heads).all(), "item index mod Hkv is the KV head"
+    # forests with more items than the 768 resident workgroups: the short items of at most 16 rows come last
+    # and share a workgroup four at a time
+    limit = 768 if w.kv_dtype == wl.KV_FP8_E4M3 else 384
+    short = (items[:, 4] * G <= 16) & (items[:, 1] <= limit) if len(items) > 768 else np.zeros(len(items), dtype=bool)
+    n_single = int((~short).sum())
+    assert not short[:n_single].any() and short[n_single:].all()
+    assert hkv.hkv_decode_plan_num_workgroups(plan) == n_single + (len(items) - n_single + 3) // 4
     for r in range(f.n_req):
         assert (covered[r] == 1).all(), "every (request, kv head, token) is read by exactly one item"
         assert (slots[r][:, :counts[r]] == 1).all() and (slots[r][:, counts[r]:] == 0).all()
