@@ -648,6 +648,31 @@ def test_decode_several_query_tokens_many_rows(gpu, oracle):
     run_decode_multi(gpu, oracle, w, 2)
 
 
+@pytest.mark.parametrize("kv_dtype", [wl.KV_BF16, wl.KV_FP8_E4M3])
+def test_decode_short_items_four_to_a_workgroup(gpu, oracle, kv_dtype, monkeypatch):
+    """The packing of short items (one per wavefront, four per workgroup) forced on for small forests: random
+    forests with ragged and empty nodes and item counts that are no multiple of four, a deep chain, many
+    requests under one node, and several query tokens per request (causal limits inside packed items)."""
+    from paper_2603_16104_amd import binding as hkv
+    monkeypatch.setenv("HKV_DECODE_PACK", "3")
+    for seed in (51, 52, 53, 54):
+        hq, hk = [(8, 2), (8, 1), (4, 4), (16, 1)][seed % 4]
+        w = wl.random_forest_workload(seed, kv_dtype=kv_dtype, num_q_heads=hq, num_kv_heads=hk, depth=4, fanout=3,
+                                      max_node_pages=9, n_roots=2)
+        run_decode(gpu, oracle, w)
+    w = wl.config2(seed=77, n_req=40, root_tokens=1200 // 16 * 16, private_tokens=100)
+    w.kv_dtype = kv_dtype
+    hp, dp = both_pools(gpu, oracle, w)
+    r = gpu.DecodeRunner(dp, w)
+    n_items, n_wg = len(hkv.hkv_decode_plan_items(r.plan)), hkv.hkv_decode_plan_num_workgroups(r.plan)
+    assert n_wg < n_items, "the leaves of this forest are short: they must share workgroups"
+    r.close()
+    dp.close()
+    run_decode(gpu, oracle, w)
+    run_decode_multi(gpu, oracle, _multi_forest(kv_dtype, 8, 2, [48, 21, 100], [1, 2, 3, 0]), 3)
+    run_decode_multi(gpu, oracle, _multi_forest(kv_dtype, 4, 1, [40, 16, 33, 7, 90], [1, 2, 3, 4, 5, 0]), 4)
+
+
 def test_decode_and_prefill_runs_are_graph_capturable(gpu, oracle):
     """attn_decode_plan_run and attn_prefill_plan_run only queue kernels (no allocation, no copies, no
     memset nodes), so a caller may capture them in a HIP graph: several replays, with eager work and
