@@ -24,6 +24,11 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Kernel launches are
  *     asynchronous on it.  All argument validation happens on the host before anything is
  *     queued, so a failing call has no effect on device memory.
+ *   - Threads: objects (pools, plans, caches, trees) carry no locks.  Calls on different objects
+ *     may run on different threads at once; calls on one object, and calls on a plan or cache and
+ *     on the pool it was created over, must be serialised by the caller.  A plan's workspace and
+ *     device index buffers belong to one run at a time: queue runs of one plan on one stream, or
+ *     order them with events.
  *   - Fixed geometry: page size 16 tokens, head dimension 128.  Anything else is HKV_ESHAPE.
  *   - Grouped-query attention: query head h reads KV head h / (num_q_heads / num_kv_heads).
  *
