@@ -389,6 +389,91 @@ int oracle_attn_decode(const orc_pool *p, const void *q, int32_t q_dtype, const 
     return 0;
 }
 
+/* The same attention taken straight from the forest (Section 5, templated radix tree: a call's
+ * prompt is the concatenation of the token segments on the path from the root to its leaf), for
+ * forests whose nodes may end inside a page anywhere: request r's sequence is, node by node from
+ * the root down to req_leaf[r], token t of node v = slot t % 16 of page node_pages[page_begin_v +
+ * t / 16].  nodes: [n_nodes][4] = parent, page_begin, n_pages, n_tokens (parents first).
+ * leaf_visible (optional): of its last node request r sees only the first leaf_visible[r] tokens
+ * (one of several query tokens of a call, which must not see the call's newer tokens).
+ * Plain definition: all scores, their maximum, the exponentials, the weighted sum. */
+int oracle_attn_decode_tree(const orc_pool *p, const void *q, int32_t q_dtype, const int32_t *nodes, int32_t n_nodes,
+                            const int32_t *node_pages, int32_t n_node_pages, const int32_t *req_leaf,
+                            const int32_t *leaf_visible, int32_t n_req, int32_t num_q_heads, float scale, double *out,
+                            double *lse) {
+    if (num_q_heads <= 0 || num_q_heads % p->num_kv_heads) return -3;
+    int G = num_q_heads / p->num_kv_heads;
+    for (int v = 0; v < n_nodes; ++v) {
+        const int32_t *nd = nodes + 4 * (size_t)v;
+        if (nd[0] < -1 || nd[0] >= v || nd[3] < 0 || nd[2] != (nd[3] + ORC_PAGE - 1) / ORC_PAGE) return -4;
+        if (nd[1] < 0 || (int64_t)nd[1] + nd[2] > n_node_pages) return -2;
+        for (int j = 0; j < nd[2]; ++j)
+            if (node_pages[nd[1] + j] < 0 || node_pages[nd[1] + j] >= p->num_pages) return -2;
+    }
+    for (int r = 0; r < n_req; ++r)
+        if (req_leaf[r] < 0 || req_leaf[r] >= n_nodes) return -2;
+#pragma omp parallel for schedule(dynamic)
+    for (int r = 0; r < n_req; ++r) {
+        /* the request's tokens in sequence order as (page, slot) pairs */
+        int depth = 0, total = 0;
+        for (int v = req_leaf[r]; v >= 0; v = nodes[4 * (size_t)v]) ++depth;
+        int *chain = (int *)malloc(sizeof(int) * (size_t)(depth > 0 ? depth : 1));
+        int i = depth;
+        for (int v = req_leaf[r]; v >= 0; v = nodes[4 * (size_t)v]) chain[--i] = v;
+        for (i = 0; i < depth; ++i) {
+            int nt = nodes[4 * (size_t)chain[i] + 3];
+            if (i == depth - 1 && leaf_visible && leaf_visible[r] < nt) nt = leaf_visible[r] < 0 ? 0 : leaf_visible[r];
+            total += nt;
+        }
+        int *pg = (int *)malloc(sizeof(int) * (size_t)(total > 0 ? total : 1));
+        int *sl = (int *)malloc(sizeof(int) * (size_t)(total > 0 ? total : 1));
+        int n = 0;
+        for (i = 0; i < depth; ++i) {
+            const int32_t *nd = nodes + 4 * (size_t)chain[i];
+            int nt = nd[3];
+            if (i == depth - 1 && leaf_visible && leaf_visible[r] < nt) nt = leaf_visible[r] < 0 ? 0 : leaf_visible[r];
+            for (int t = 0; t < nt; ++t) {
+                pg[n] = node_pages[nd[1] + t / ORC_PAGE];
+                sl[n] = t % ORC_PAGE;
+                ++n;
+            }
+        }
+        double *s = (double *)malloc(sizeof(double) * (size_t)(total > 0 ? total : 1));
+        for (int h = 0; h < num_q_heads; ++h) {
+            size_t row = (size_t)r * num_q_heads + h;
+            double *o = out + row * ORC_D;
+            for (int d = 0; d < ORC_D; ++d) o[d] = 0.0;
+            if (total == 0) {
+                lse[row] = -INFINITY;
+                continue;
+            }
+            double qv[ORC_D];
+            for (int d = 0; d < ORC_D; ++d) qv[d] = load_q(q, q_dtype, row * ORC_D + d);
+            double m = -INFINITY;
+            for (int t = 0; t < total; ++t) {
+                double acc = 0.0;
+                for (int d = 0; d < ORC_D; ++d) acc += qv[d] * load_k(p, pg[t], h / G, sl[t], d);
+                s[t] = (double)scale * acc;
+                if (s[t] > m) m = s[t];
+            }
+            double l = 0.0;
+            for (int t = 0; t < total; ++t) {
+                s[t] = exp(s[t] - m);
+                l += s[t];
+            }
+            for (int t = 0; t < total; ++t)
+                for (int d = 0; d < ORC_D; ++d) o[d] += s[t] * load_v(p, pg[t], h / G, sl[t], d);
+            for (int d = 0; d < ORC_D; ++d) o[d] /= l;
+            lse[row] = m + log(l);
+        }
+        free(s);
+        free(sl);
+        free(pg);
+        free(chain);
+    }
+    return 0;
+}
+
 /* Suffix-only prefill (Section 5: a call processes only the tokens that are not already
  * cached).  Request r has s_r = cu_q[r+1] - cu_q[r] new tokens whose K/V are already in the
  * pool at positions prefix_len_r .. kv_len_r - 1, prefix_len_r = kv_len_r - s_r.  New token i

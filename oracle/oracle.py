@@ -181,6 +181,26 @@ def attn_decode(pool: HostPool, q: np.ndarray, block_table, kv_len, scale: float
     return out, lse
 
 
+def attn_decode_tree(pool: HostPool, q: np.ndarray, nodes, node_pages, req_leaf, scale: float, leaf_visible=None):
+    """One query token per request over the token segments on its root-to-leaf path, read straight from
+    the forest (nodes may end inside a page anywhere).  leaf_visible[r]: how many tokens of its last node
+    request r sees (default: all)."""
+    q = np.ascontiguousarray(q)
+    nodes, node_pages, req_leaf = _i32(nodes).reshape(-1, 4), _i32(node_pages), _i32(req_leaf)
+    n_req, Hq = q.shape[0], q.shape[1]
+    assert q.shape[2] == D and len(req_leaf) == n_req
+    out = np.empty((n_req, Hq, D), dtype=np.float64)
+    lse = np.empty((n_req, Hq), dtype=np.float64)
+    lv = None if leaf_visible is None else _i32(leaf_visible)
+    pc = pool._c()
+    rc = lib().oracle_attn_decode_tree(C.byref(pc), _p(q), C.c_int32(_src_dtype(q)), _p(nodes), C.c_int32(nodes.shape[0]),
+                                       _p(node_pages), C.c_int32(len(node_pages)), _p(req_leaf), _p(lv), C.c_int32(n_req),
+                                       C.c_int32(Hq), C.c_float(scale), _p(out), _p(lse))
+    if rc:
+        raise ValueError(f"oracle_attn_decode_tree failed: {rc}")
+    return out, lse
+
+
 def attn_prefill(pool: HostPool, q: np.ndarray, cu_q, block_table, kv_len, scale: float):
     q = np.ascontiguousarray(q)
     cu_q, block_table, kv_len = _i32(cu_q), _i32(block_table), _i32(kv_len)
@@ -242,8 +262,15 @@ def run_workload(workload, pool: Optional[HostPool] = None, req_subset=None):
     if pool is None:
         pool = HostPool(workload.num_pages, workload.num_kv_heads, workload.kv_dtype)
         pool.fill_from(workload)
-    bt, kv_len, _, _, _ = flatten_workload(workload)
+    f = workload.forest
     q = workload.q()
+    has_child = np.zeros(f.n_nodes, dtype=bool)
+    has_child[f.parent[f.parent >= 0]] = True
+    if workload.mode == "decode" and bool(np.any(has_child & (f.n_tokens % PAGE != 0))):
+        # a node with children ends inside a page: no flat block table exists, walk the forest
+        idx = np.arange(f.n_req) if req_subset is None else np.asarray(req_subset)
+        return attn_decode_tree(pool, q[idx], f.nodes, f.node_pages, f.req_leaf[idx], float(workload.scale))
+    bt, kv_len, _, _, _ = flatten_workload(workload)
     if workload.mode == "decode":
         if req_subset is not None:
             idx = np.asarray(req_subset)

@@ -362,9 +362,10 @@ def random_forest_workload(seed: int, *, n_roots: int = 2, depth: int = 3, fanou
                            max_node_pages: int = 5, num_q_heads: int = 8, num_kv_heads: int = 2,
                            kv_dtype: int = KV_BF16, mode: str = "decode", ragged: bool = True,
                            zero_weight_nodes: bool = True, src_dtype: str = "bf16",
-                           extra_pages: int = 7) -> Workload:
-    """Small random forest for tests: internal nodes are page aligned, leaves may be ragged,
-    and (as in the paper's tree, where the root and the leaves carry no tokens) some nodes are empty."""
+                           extra_pages: int = 7, ragged_internal: bool = False) -> Workload:
+    """Small random forest for tests: internal nodes are page aligned (unless ragged_internal: then they
+    may end inside a page, which only the tree decode accepts), leaves may be ragged, and (as in the
+    paper's tree, where the root and the leaves carry no tokens) some nodes are empty."""
     rng = np.random.default_rng([seed, 11])
     parent: List[int] = []
     ntok: List[int] = []
@@ -386,6 +387,8 @@ def random_forest_workload(seed: int, *, n_roots: int = 2, depth: int = 3, fanou
             return
         if zero_weight_nodes and rng.random() < 0.2:
             ntok.append(0)
+        elif ragged_internal:
+            ntok.append(int(rng.integers(1, max_node_pages * PAGE_SIZE + 1)))
         else:
             ntok.append(int(rng.integers(1, max_node_pages + 1)) * PAGE_SIZE)
         for _ in range(int(rng.integers(1, fanout + 1))):

@@ -651,3 +651,53 @@ def test_forked_sequences_through_page_copies(oracle, dtype_name):
         o1, l1 = oracle.attn_decode(shared, q, bt(table), [n], 0.1)
         o2, l2 = oracle.attn_decode(own, q, bt(own_table), [n], 0.1)
         assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
+
+
+# ------------------------------------------------------------------ attention read straight from the forest
+
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_tree_walk_decode_equals_block_table_decode_on_aligned_forests(oracle, seed):
+    """Where a flat block table exists (nodes with children hold whole pages), walking the forest node by
+    node must give the table-based result bit for bit (same token order, same arithmetic)."""
+    w = wl.random_forest_workload(seed, max_node_pages=3, depth=4, fanout=3)
+    pool = oracle_pool(oracle, w)
+    f = w.forest
+    bt, kv_len, *_ = oracle.flatten_workload(w)
+    o1, l1 = oracle.attn_decode(pool, w.q(), bt, kv_len, float(w.scale))
+    o2, l2 = oracle.attn_decode_tree(pool, w.q(), f.nodes, f.node_pages, f.req_leaf, float(w.scale))
+    assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
+
+
+@pytest.mark.parametrize("seed,kv", [(21, "bf16"), (22, "bf16"), (23, "fp32")])
+def test_tree_walk_decode_brute_force_with_ragged_internal_nodes(oracle, seed, kv):
+    """Nodes with children that end inside a page: against dense numpy attention over each request's
+    sequence assembled from the node tensors without any pool."""
+    w = wl.random_forest_workload(seed, max_node_pages=2, depth=4, fanout=2, ragged_internal=True,
+                                  src_dtype="fp32" if kv == "fp32" else "bf16",
+                                  kv_dtype=wl.KV_FP32 if kv == "fp32" else wl.KV_BF16)
+    f = w.forest
+    has_child = np.zeros(f.n_nodes, dtype=bool)
+    has_child[f.parent[f.parent >= 0]] = True
+    assert (has_child & (f.n_tokens % 16 != 0)).any(), "the case must hold a ragged node with children"
+    out, lse = oracle.run_workload(w)
+    bout, blse = brute_workload(w)
+    assert np.abs(out - bout).max() <= 1e-12
+    fin = np.isfinite(blse)
+    assert np.array_equal(np.isfinite(lse), fin) and np.abs(lse[fin] - blse[fin]).max() <= 1e-12
+
+
+def test_tree_walk_decode_leaf_visibility(oracle):
+    """leaf_visible cuts the request's last node: equal to the same forest with that node shortened."""
+    w = wl.random_forest_workload(31, max_node_pages=2, depth=3, fanout=2, ragged_internal=True, zero_weight_nodes=False)
+    f = w.forest
+    pool = oracle_pool(oracle, w)
+    vis = np.maximum(f.n_tokens[f.req_leaf] - 3, 0).astype(np.int32)
+    o1, l1 = oracle.attn_decode_tree(pool, w.q(), f.nodes, f.node_pages, f.req_leaf, float(w.scale), leaf_visible=vis)
+    q = _as_f64(w.q())
+    for r in range(f.n_req):
+        K, V = logical_kv(w, r)
+        T = K.shape[0] - (int(f.n_tokens[f.req_leaf[r]]) - int(vis[r]))
+        for h in range(w.num_q_heads):
+            o, l = brute_attention(q[r, h], K[:T, h // w.group], V[:T, h // w.group], float(w.scale))
+            assert np.abs(o1[r, h] - o).max() <= 1e-12
+            assert (np.isneginf(l) and np.isneginf(l1[r, h])) or abs(l1[r, h] - l) <= 1e-12
