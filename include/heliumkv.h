@@ -63,8 +63,9 @@ enum {
     HKV_EINVAL = -1, /* null pointer, negative size, inconsistent lengths */
     HKV_ERANGE = -2, /* page id, node id or request id outside its range */
     HKV_ESHAPE = -3, /* unsupported geometry or dtype combination */
-    HKV_ETREE = -4,  /* malformed forest: parent after child, page count != ceil(tokens/16),
-                        node with children whose token count is not a multiple of 16 */
+    HKV_ETREE = -4,  /* malformed forest: parent after child, page count != ceil(tokens/16); where a
+                        flat block table is involved also a node with children whose token count
+                        is not a multiple of 16 */
     HKV_ENOMEM = -5, /* pool exhausted, workspace or output table too small */
     HKV_EHIP = -6    /* a HIP runtime call failed (message holds the HIP error string) */
 };
@@ -169,7 +170,9 @@ typedef struct {
     int32_t parent;     /* index of the parent node, -1 for a root; must be < own index */
     int32_t page_begin; /* offset of this node's first page id in node_pages */
     int32_t n_pages;    /* == ceil(n_tokens / 16) */
-    int32_t n_tokens;   /* omega(v) >= 0; must be a multiple of 16 if the node has children */
+    int32_t n_tokens;   /* omega(v) >= 0.  prefix_tree_flatten, prefill and fp32 pools need a multiple
+                           of 16 in every node that has children (positions along a path must map
+                           to pages without gaps); the bf16 / fp8 decode plans do not */
 } hkv_node;
 
 /* Host-only, integer-only.  Expands the forest into what the kernels index with:
@@ -230,7 +233,12 @@ enum { HKV_PLAN_HOST_ONLY = 1 /* build and validate on the host, allocate nothin
 
 /* nodes, node_pages, req_leaf: host.  Validates the forest (ETREE/ERANGE, page ids against the
  * pool), builds the work list and uploads it (blocking).  ESHAPE unless num_q_heads is a
- * multiple of the pool's num_kv_heads with a ratio of at most 16. */
+ * multiple of the pool's num_kv_heads with a ratio of at most 16.
+ * With bf16 and fp8 pools every node is read through its own page list, so any node may end inside
+ * a page (its last page is then partly used and its children start on pages of their own).  That
+ * makes the forest itself the attention mask of a tree of drafted tokens: one node per drafted
+ * token (or run of tokens) under the request's context, one "request" per node to be verified,
+ * and each such row sees the context, its ancestors and itself. */
 int hkv_decode_plan_create(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes, const int32_t *node_pages,
                            int32_t n_node_pages, const int32_t *req_leaf, int32_t n_req, int32_t num_q_heads,
                            uint32_t flags, hkv_decode_plan **out);

@@ -313,8 +313,11 @@ extern "C" int kv_pool_write(hkv_pool *pool, const int32_t *page_ids, int32_t fi
 
 // ---------------------------------------------------------------------------------------------
 // forest
+// whole_page_parents: a node with children must hold a multiple of 16 tokens (what a flat block table
+// needs: positions along a path then map to pages without gaps); false for callers that walk the forest
+// node by node.
 static int validate_forest(const hkv_node *nodes, int32_t n_nodes, const int32_t *node_pages, int32_t n_node_pages,
-                           const char *who) {
+                           const char *who, bool whole_page_parents = true) {
     if (n_nodes < 0 || n_node_pages < 0 || (n_nodes > 0 && !nodes) || (n_node_pages > 0 && !node_pages))
         return fail(HKV_EINVAL, "%s: bad forest arguments", who);
     std::vector<char> has_child(n_nodes, 0);
@@ -329,10 +332,11 @@ static int validate_forest(const hkv_node *nodes, int32_t n_nodes, const int32_t
                         nd.page_begin + nd.n_pages, n_node_pages);
         if (nd.parent >= 0) has_child[nd.parent] = 1;
     }
-    for (int v = 0; v < n_nodes; ++v)
-        if (has_child[v] && nodes[v].n_tokens % HKV_PAGE_SIZE)
-            return fail(HKV_ETREE, "%s: node %d has children but %d tokens (not a multiple of 16)", who, v,
-                        nodes[v].n_tokens);
+    if (whole_page_parents)
+        for (int v = 0; v < n_nodes; ++v)
+            if (has_child[v] && nodes[v].n_tokens % HKV_PAGE_SIZE)
+                return fail(HKV_ETREE, "%s: node %d has children but %d tokens (not a multiple of 16)", who, v,
+                            nodes[v].n_tokens);
     return HKV_OK;
 }
 
@@ -628,7 +632,11 @@ extern "C" int hkv_decode_plan_create(hkv_pool *pool, const hkv_node *nodes, int
     const int Hkv = pool->d.num_kv_heads;
     if (num_q_heads <= 0 || num_q_heads % Hkv || num_q_heads / Hkv > 16)
         return fail(HKV_ESHAPE, "hkv_decode_plan_create: %d query heads over %d KV heads", num_q_heads, Hkv);
-    if (int rc = validate_forest(nodes, n_nodes, node_pages, n_node_pages, "hkv_decode_plan_create")) return rc;
+    // The per-node kernels read every node through its own page list, so nodes may end inside a page
+    // anywhere; the full-precision path walks flat block tables and keeps the whole-page rule.
+    if (int rc = validate_forest(nodes, n_nodes, node_pages, n_node_pages, "hkv_decode_plan_create",
+                                 pool->d.dtype == HKV_FP32))
+        return rc;
     for (int v = 0; v < n_nodes; ++v)
         for (int j = 0; j < nodes[v].n_pages; ++j) {
             int32_t id = node_pages[nodes[v].page_begin + j];

@@ -352,6 +352,66 @@ def test_decode_deep_chain(gpu, oracle, kv_dtype):
     run_decode(gpu, oracle, w)
 
 
+@pytest.mark.parametrize("seed", [61, 62, 63, 64])
+@pytest.mark.parametrize("kv_dtype", [wl.KV_BF16, wl.KV_FP8_E4M3])
+def test_decode_nodes_that_end_inside_a_page(gpu, oracle, seed, kv_dtype):
+    """Forests whose nodes with children hold any token count (their last page is partly used, children
+    start on pages of their own): against the oracle's walk of the forest."""
+    hq, hkv_ = [(8, 2), (8, 1), (4, 4), (16, 1)][seed % 4]
+    w = wl.random_forest_workload(seed, kv_dtype=kv_dtype, num_q_heads=hq, num_kv_heads=hkv_, depth=4, fanout=3,
+                                  max_node_pages=9, n_roots=2, ragged_internal=True)
+    f = w.forest
+    has_child = np.zeros(f.n_nodes, dtype=bool)
+    has_child[f.parent[f.parent >= 0]] = True
+    assert (has_child & (f.n_tokens % 16 != 0)).any()
+    run_decode(gpu, oracle, w)
+
+
+@pytest.mark.parametrize("kv_dtype", [wl.KV_BF16, wl.KV_FP8_E4M3])
+def test_decode_verifies_a_tree_of_drafted_tokens(gpu, oracle, kv_dtype):
+    """Tree-structured verification of drafted tokens expressed as a forest: two calls over a shared system
+    prompt, each with a private context that ends inside a page, and under each context a tree of drafted
+    tokens, one node per token (branching 3, 2, 2: 3 + 6 + 12 nodes); every drafted token is a query row
+    whose "request" ends at its node, so it sees the prompt, its ancestors and itself, and nothing of its
+    siblings.  Checked against the oracle's walk of the forest and, for one row, against dense attention
+    over the tokens of that row's path."""
+    parent, ntok, rows = [-1], [96], []
+    for ctx_tokens in (77, 130):
+        parent.append(0)
+        ntok.append(ctx_tokens)
+        ctx = len(parent) - 1
+        level = [ctx]
+        for width in (3, 2, 2):
+            nxt = []
+            for p in level:
+                for _ in range(width):
+                    parent.append(p)
+                    ntok.append(1)
+                    nxt.append(len(parent) - 1)
+                    rows.append(len(parent) - 1)
+            level = nxt
+    n_used = sum((t + 15) // 16 for t in ntok)
+    f = wl.make_forest(parent, ntok, rows, np.random.default_rng(9).permutation(n_used + 6).astype(np.int32))
+    w = wl.Workload(name="draft_tree", num_q_heads=8, num_kv_heads=2, kv_dtype=kv_dtype, num_pages=n_used + 6, seed=27,
+                    forest=f, mode="decode")
+    assert f.n_req == 42
+    run_decode(gpu, oracle, w)
+    if kv_dtype == wl.KV_BF16:      # the mask really is the ancestor relation: dense attention over the path's tokens
+        hp = oracle.HostPool(w.num_pages, w.num_kv_heads, w.kv_dtype)
+        hp.fill_from(w)
+        exp_o, _ = oracle.run_workload(w, hp)
+        r = 41                                             # a depth-3 token under the second context
+        ks = [wl.bf16_bits_to_f32(w.node_kv(v)[0]).astype(np.float64) for v in f.path(int(f.req_leaf[r]))]
+        vs = [wl.bf16_bits_to_f32(w.node_kv(v)[1]).astype(np.float64) for v in f.path(int(f.req_leaf[r]))]
+        K, V = np.concatenate(ks), np.concatenate(vs)
+        assert K.shape[0] == 96 + 130 + 3
+        q = wl.bf16_bits_to_f32(w.q()[r]).astype(np.float64)
+        for h in range(8):
+            sc = (K[:, h // 4] @ q[h]) * float(w.scale)
+            e = np.exp(sc - sc.max())
+            assert np.abs((e[:, None] * V[:, h // 4]).sum(0) / e.sum() - exp_o[r, h]).max() <= 1e-12
+
+
 def test_decode_config1_one_shot(gpu, oracle):
     _, dec = wl.config1()
     run_decode(gpu, oracle, dec, one_shot=True)

@@ -253,6 +253,46 @@ def test_decode_plan_covers_every_token_once(oracle):
         _check_decode_plan(w, oracle)
 
 
+def test_decode_plan_accepts_nodes_that_end_inside_a_page(oracle):
+    """bf16 / fp8 decode plans read every node through its own pages: parents may hold any token count.
+    Every (request, KV head, token) is still covered exactly once; flat tables, prefill and fp32 pools
+    keep the whole-page rule."""
+    for seed in range(140, 146):
+        w = wl.random_forest_workload(seed, depth=4, fanout=3, n_roots=2, max_node_pages=30, ragged_internal=True,
+                                      kv_dtype=wl.KV_FP8_E4M3 if seed % 2 else wl.KV_BF16)
+        f = w.forest
+        has_child = np.zeros(f.n_nodes, dtype=bool)
+        has_child[f.parent[f.parent >= 0]] = True
+        if not (has_child & (f.n_tokens % 16 != 0)).any():
+            continue
+        pool = fake_pool(w.num_pages, w.num_kv_heads, w.kv_dtype)
+        plan = hkv.hkv_decode_plan_create(pool, f.nodes, f.node_pages, f.req_leaf, w.num_q_heads, hkv.PLAN_HOST_ONLY)
+        items = hkv.hkv_decode_plan_items(plan)
+        tok_start = np.zeros(f.n_nodes, dtype=np.int64)
+        for v in range(f.n_nodes):
+            if f.parent[v] >= 0:
+                tok_start[v] = tok_start[f.parent[v]] + f.n_tokens[f.parent[v]]
+        under = [[r for r in range(f.n_req) if v in f.path(int(f.req_leaf[r]))] for v in range(f.n_nodes)]
+        covered = [np.zeros((w.num_kv_heads, f.kv_len(r)), dtype=np.int32) for r in range(f.n_req)]
+        pos = {v: 0 for v in range(f.n_nodes)}
+        indptr = np.cumsum([0] + [len(u) for u in under])
+        for page_off, n_tok, kv_head, req_off, n_req, slot, tok_begin, node in items:
+            assert page_off == f.page_begin[node] + tok_begin // 16 and tok_begin + n_tok <= f.n_tokens[node]
+            for r in under[node][req_off - indptr[node]: req_off - indptr[node] + n_req]:
+                covered[r][kv_head, tok_start[node] + tok_begin: tok_start[node] + tok_begin + n_tok] += 1
+        assert all((c == 1).all() for c in covered)
+        hkv.hkv_decode_plan_destroy(plan)
+        with pytest.raises(hkv.HkvError) as e:
+            hkv.prefix_tree_flatten(f.nodes, f.node_pages, f.req_leaf, 4096)
+        assert e.value.code == hkv.ETREE
+        p32 = fake_pool(w.num_pages, w.num_kv_heads, hkv.FP32)
+        with pytest.raises(hkv.HkvError) as e:
+            hkv.hkv_decode_plan_create(p32, f.nodes, f.node_pages, f.req_leaf, w.num_q_heads, hkv.PLAN_HOST_ONLY)
+        assert e.value.code == hkv.ETREE
+        hkv.kv_pool_destroy(p32)
+        hkv.kv_pool_destroy(pool)
+
+
 def test_decode_plan_sizes_of_benchmark_configs(oracle):
     items = _check_decode_plan(wl.config2(), oracle)
     assert len(items) == 640            # 64 leaves x 8 heads + 4 chunks x 4 row groups x 8 heads of the root
@@ -268,7 +308,8 @@ def test_decode_plan_error_codes():
     cases = [(nodes, pages, [1], 3, hkv.ESHAPE),                                    # 3 q heads over 2 kv heads
              (nodes, np.array([3, 16], dtype=np.int32), [1], 4, hkv.ERANGE),        # page id outside the pool
              (nodes, pages, [5], 4, hkv.ERANGE),
-             (np.array([[-1, 0, 1, 10], [0, 1, 1, 5]], dtype=np.int32), pages, [1], 4, hkv.ETREE)]
+             (np.array([[-1, 0, 2, 10], [0, 1, 1, 5]], dtype=np.int32), pages, [1], 4, hkv.ETREE),  # 10 tokens are 1 page
+             (np.array([[0, 0, 1, 16], [-1, 1, 1, 5]], dtype=np.int32), pages, [1], 4, hkv.ETREE)]   # parent after child
     for n, p, leaves, hq, code in cases:
         with pytest.raises(hkv.HkvError) as e:
             hkv.hkv_decode_plan_create(pool, n, p, leaves, hq, hkv.PLAN_HOST_ONLY)
