@@ -253,6 +253,16 @@ int hkv_decode_plan_create(hkv_pool *pool, const hkv_node *nodes, int32_t n_node
 int hkv_decode_plan_create_multi(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes, const int32_t *node_pages,
                                  int32_t n_node_pages, const int32_t *req_leaf, int32_t n_req, int32_t tokens_per_req,
                                  int32_t num_q_heads, uint32_t flags, hkv_decode_plan **out);
+/* Verification of a tree of drafted tokens per request (tree-structured speculative decoding): the
+ * request's T = tokens_per_req (1..64) newest tokens, the last T of its leaf node, are drafted
+ * tokens in any order; query row t of the request sees every key before them and drafted token j
+ * iff bit j of visible[r * T + t] is set: its ancestors in the tree of drafts and itself (bit t
+ * must be set, bits >= T must be clear; else EINVAL).  A causal run of T tokens is the mask with
+ * bits 0..t, which is what hkv_decode_plan_create_multi builds.  Row layout and counts as there.
+ * visible: host, [n_req * T].  ESHAPE for fp32 pools (they verify causal runs only). */
+int hkv_decode_plan_create_tree(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes, const int32_t *node_pages,
+                                int32_t n_node_pages, const int32_t *req_leaf, int32_t n_req, int32_t tokens_per_req,
+                                const uint64_t *visible, int32_t num_q_heads, uint32_t flags, hkv_decode_plan **out);
 int hkv_decode_plan_destroy(hkv_decode_plan *plan);
 /* Bytes of device workspace attn_decode_plan_run needs (partial o and lse), 0 on a null plan. */
 size_t hkv_decode_plan_workspace_bytes(const hkv_decode_plan *plan);

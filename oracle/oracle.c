@@ -396,11 +396,15 @@ int oracle_attn_decode(const orc_pool *p, const void *q, int32_t q_dtype, const 
  * t / 16].  nodes: [n_nodes][4] = parent, page_begin, n_pages, n_tokens (parents first).
  * leaf_visible (optional): of its last node request r sees only the first leaf_visible[r] tokens
  * (one of several query tokens of a call, which must not see the call's newer tokens).
+ * tail_len, tail_mask (optional, instead of leaf_visible): the last tail_len tokens of the last node
+ * are drafted tokens of which request r sees number j iff bit j of tail_mask[r] is set (its ancestors
+ * in the tree of drafts and itself); everything before them it sees.
  * Plain definition: all scores, their maximum, the exponentials, the weighted sum. */
 int oracle_attn_decode_tree(const orc_pool *p, const void *q, int32_t q_dtype, const int32_t *nodes, int32_t n_nodes,
                             const int32_t *node_pages, int32_t n_node_pages, const int32_t *req_leaf,
-                            const int32_t *leaf_visible, int32_t n_req, int32_t num_q_heads, float scale, double *out,
-                            double *lse) {
+                            const int32_t *leaf_visible, int32_t tail_len, const uint64_t *tail_mask, int32_t n_req,
+                            int32_t num_q_heads, float scale, double *out, double *lse) {
+    if (tail_mask && (leaf_visible || tail_len < 1 || tail_len > 64)) return -1;
     if (num_q_heads <= 0 || num_q_heads % p->num_kv_heads) return -3;
     int G = num_q_heads / p->num_kv_heads;
     for (int v = 0; v < n_nodes; ++v) {
@@ -433,11 +437,14 @@ int oracle_attn_decode_tree(const orc_pool *p, const void *q, int32_t q_dtype, c
             int nt = nd[3];
             if (i == depth - 1 && leaf_visible && leaf_visible[r] < nt) nt = leaf_visible[r] < 0 ? 0 : leaf_visible[r];
             for (int t = 0; t < nt; ++t) {
+                if (i == depth - 1 && tail_mask && t >= nt - tail_len && !((tail_mask[r] >> (t - (nt - tail_len))) & 1u))
+                    continue; /* a drafted token that is no ancestor of this one */
                 pg[n] = node_pages[nd[1] + t / ORC_PAGE];
                 sl[n] = t % ORC_PAGE;
                 ++n;
             }
         }
+        total = n;
         double *s = (double *)malloc(sizeof(double) * (size_t)(total > 0 ? total : 1));
         for (int h = 0; h < num_q_heads; ++h) {
             size_t row = (size_t)r * num_q_heads + h;

@@ -181,10 +181,12 @@ def attn_decode(pool: HostPool, q: np.ndarray, block_table, kv_len, scale: float
     return out, lse
 
 
-def attn_decode_tree(pool: HostPool, q: np.ndarray, nodes, node_pages, req_leaf, scale: float, leaf_visible=None):
+def attn_decode_tree(pool: HostPool, q: np.ndarray, nodes, node_pages, req_leaf, scale: float, leaf_visible=None,
+                     tail_len: int = 0, tail_mask=None):
     """One query token per request over the token segments on its root-to-leaf path, read straight from
     the forest (nodes may end inside a page anywhere).  leaf_visible[r]: how many tokens of its last node
-    request r sees (default: all)."""
+    request r sees (default: all).  tail_len / tail_mask[r]: the last tail_len tokens of the last node
+    are drafted tokens of which request r sees number j iff bit j of tail_mask[r] is set."""
     q = np.ascontiguousarray(q)
     nodes, node_pages, req_leaf = _i32(nodes).reshape(-1, 4), _i32(node_pages), _i32(req_leaf)
     n_req, Hq = q.shape[0], q.shape[1]
@@ -192,10 +194,13 @@ def attn_decode_tree(pool: HostPool, q: np.ndarray, nodes, node_pages, req_leaf,
     out = np.empty((n_req, Hq, D), dtype=np.float64)
     lse = np.empty((n_req, Hq), dtype=np.float64)
     lv = None if leaf_visible is None else _i32(leaf_visible)
+    tm = None if tail_mask is None else np.ascontiguousarray(tail_mask, dtype=np.uint64)
+    assert tm is None or len(tm) == n_req
     pc = pool._c()
     rc = lib().oracle_attn_decode_tree(C.byref(pc), _p(q), C.c_int32(_src_dtype(q)), _p(nodes), C.c_int32(nodes.shape[0]),
-                                       _p(node_pages), C.c_int32(len(node_pages)), _p(req_leaf), _p(lv), C.c_int32(n_req),
-                                       C.c_int32(Hq), C.c_float(scale), _p(out), _p(lse))
+                                       _p(node_pages), C.c_int32(len(node_pages)), _p(req_leaf), _p(lv),
+                                       C.c_int32(tail_len), _p(tm), C.c_int32(n_req), C.c_int32(Hq), C.c_float(scale),
+                                       _p(out), _p(lse))
     if rc:
         raise ValueError(f"oracle_attn_decode_tree failed: {rc}")
     return out, lse

@@ -25,7 +25,7 @@ PAGE_SIZE, HEAD_DIM = 16, 128
 EXPORTS = [
     "hkv_last_error", "kv_pool_create", "kv_pool_destroy", "kv_pool_alloc", "kv_pool_retain", "kv_pool_release", "kv_pool_copy_on_write",
     "kv_pool_num_free", "kv_pool_refcount", "kv_pool_write", "prefix_tree_flatten", "prefix_tree_prefill_usage",
-    "lse_merge", "hkv_decode_plan_create", "hkv_decode_plan_create_multi", "hkv_decode_plan_destroy", "hkv_decode_plan_workspace_bytes",
+    "lse_merge", "hkv_decode_plan_create", "hkv_decode_plan_create_multi", "hkv_decode_plan_create_tree", "hkv_decode_plan_destroy", "hkv_decode_plan_workspace_bytes",
     "hkv_decode_plan_num_items", "hkv_decode_plan_num_workgroups", "hkv_decode_plan_num_parts", "hkv_decode_plan_items",
     "hkv_decode_plan_max_parts", "hkv_decode_plan_part_counts", "lse_merge_dense", "attn_decode_plan_run",
     "hkv_decode_plan_set_profiling", "hkv_decode_plan_elapsed_ms",
@@ -220,6 +220,21 @@ def hkv_decode_plan_create_multi(pool, nodes, node_pages, req_leaf, tokens_per_r
                                               C.c_int32(len(node_pages)), _hp(req_leaf), C.c_int32(len(req_leaf)),
                                               C.c_int32(tokens_per_req), C.c_int32(num_q_heads), C.c_uint32(flags),
                                               C.byref(out)))
+    return out
+
+
+def hkv_decode_plan_create_tree(pool, nodes, node_pages, req_leaf, tokens_per_req: int, visible, num_q_heads: int,
+                                flags: int = 0) -> C.c_void_p:
+    """visible: [n_req * tokens_per_req] uint64 masks over each request's drafted tokens."""
+    nodes, node_pages, req_leaf = _nodes(nodes), _host_i32(node_pages), _host_i32(req_leaf)
+    visible = np.ascontiguousarray(visible, dtype=np.uint64)
+    if len(visible) != len(req_leaf) * tokens_per_req:
+        raise ValueError("visible must hold one mask per request and drafted token")
+    out = C.c_void_p()
+    _check(lib().hkv_decode_plan_create_tree(pool, _hp(nodes), C.c_int32(nodes.shape[0]), _hp(node_pages),
+                                             C.c_int32(len(node_pages)), _hp(req_leaf), C.c_int32(len(req_leaf)),
+                                             C.c_int32(tokens_per_req), _hp(visible), C.c_int32(num_q_heads),
+                                             C.c_uint32(flags), C.byref(out)))
     return out
 
 

@@ -78,7 +78,9 @@ struct hkv_decode_plan {
     hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};  // begin/end of the node kernel, begin/end of the merge
     // several query tokens per request: n_req above counts query rows (requests x tokens_per_req)
     int32_t tokens_per_req = 1;
-    int32_t *d_row_leaf = nullptr, *d_row_limit = nullptr;  // one allocation (d_row_leaf), null when tokens_per_req == 1
+    // one allocation (d_row_mask), null when tokens_per_req == 1
+    unsigned long long *d_row_mask = nullptr;
+    int32_t *d_row_leaf = nullptr, *d_row_limit = nullptr;
     // fp32 pools: no work items; every query row walks its own block table (one allocation: d_bt)
     std::vector<int32_t> row_len;
     int32_t max_pages = 0;
@@ -680,16 +682,17 @@ extern "C" int hkv_decode_plan_create(hkv_pool *pool, const hkv_node *nodes, int
     return HKV_OK;
 }
 
-extern "C" int hkv_decode_plan_create_multi(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes,
-                                            const int32_t *node_pages, int32_t n_node_pages, const int32_t *req_leaf,
-                                            int32_t n_req, int32_t tokens_per_req, int32_t num_q_heads, uint32_t flags,
-                                            hkv_decode_plan **out) {
-    if (!out) return fail(HKV_EINVAL, "hkv_decode_plan_create_multi: null out");
-    *out = nullptr;
-    const int T = tokens_per_req;
-    if (T < 1 || T > 16) return fail(HKV_EINVAL, "hkv_decode_plan_create_multi: %d query tokens per request (1..16)", T);
-    if (n_req < 0 || (n_req > 0 && !req_leaf)) return fail(HKV_EINVAL, "hkv_decode_plan_create_multi: bad request list");
-    if ((int64_t)n_req * T > INT32_MAX / 2) return fail(HKV_EINVAL, "hkv_decode_plan_create_multi: too many query rows");
+// Plan over n_req * T query rows: the T newest tokens of every request (the last T of its leaf node) are
+// queried together; row t sees everything before them and, of them, token j iff bit j of masks[r * T + t]
+// is set (masks == nullptr: the causal run, bits 0..t).
+static int create_rows_plan(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes, const int32_t *node_pages,
+                            int32_t n_node_pages, const int32_t *req_leaf, int32_t n_req, int32_t T,
+                            const uint64_t *masks, int32_t num_q_heads, uint32_t flags, hkv_decode_plan **out,
+                            const char *who) {
+    if (n_req < 0 || (n_req > 0 && !req_leaf)) return fail(HKV_EINVAL, "%s: bad request list", who);
+    if ((int64_t)n_req * T > INT32_MAX / 2) return fail(HKV_EINVAL, "%s: too many query rows", who);
+    if (masks && pool && pool->d.dtype == HKV_FP32)
+        return fail(HKV_ESHAPE, "%s: the full-precision path verifies causal runs only", who);
     std::vector<int32_t> rows((size_t)n_req * T);
     for (int r = 0; r < n_req; ++r)
         for (int t = 0; t < T; ++t) rows[(size_t)r * T + t] = req_leaf[r];
@@ -698,16 +701,26 @@ extern "C" int hkv_decode_plan_create_multi(hkv_pool *pool, const hkv_node *node
                                         num_q_heads, flags, &pl))
         return rc;
     pl->tokens_per_req = T;
-    if (T > 1) {
+    if (T > 1 || masks) {
         std::vector<int32_t> lim((size_t)n_req * T);
+        std::vector<unsigned long long> vis((size_t)n_req * T);
         for (int r = 0; r < n_req; ++r) {
             const int n_leaf = nodes[req_leaf[r]].n_tokens;  // validated by hkv_decode_plan_create
             if (n_leaf < T) {
                 hkv_decode_plan_destroy(pl);
-                return fail(HKV_EINVAL, "hkv_decode_plan_create_multi: request %d has %d query tokens but its leaf holds "
-                            "only %d tokens (the newest tokens must lie in the leaf)", r, T, n_leaf);
+                return fail(HKV_EINVAL, "%s: request %d has %d query tokens but its leaf holds only %d tokens (the "
+                            "newest tokens must lie in the leaf)", who, r, T, n_leaf);
             }
-            for (int t = 0; t < T; ++t) lim[(size_t)r * T + t] = n_leaf - (T - 1 - t);
+            for (int t = 0; t < T; ++t) {
+                const size_t i = (size_t)r * T + t;
+                lim[i] = n_leaf - T;
+                vis[i] = masks ? masks[i] : (t == 63 ? ~0ull : (1ull << (t + 1)) - 1);
+                if (!(vis[i] >> t & 1) || (T < 64 && vis[i] >> T)) {
+                    hkv_decode_plan_destroy(pl);
+                    return fail(HKV_EINVAL, "%s: request %d token %d: a token must see itself and nothing beyond the %d "
+                                "newest tokens (mask %llx)", who, r, t, T, vis[i]);
+                }
+            }
         }
         if (pool->d.dtype == HKV_FP32) {  // query token t of a request sees all but the T-1-t newest keys
             for (int r = 0; r < n_req; ++r)
@@ -716,20 +729,22 @@ extern "C" int hkv_decode_plan_create_multi(hkv_pool *pool, const hkv_node *node
                 hipError_t e = hipMemcpy(pl->d_rows_len, pl->row_len.data(), sizeof(int32_t) * pl->row_len.size(), hipMemcpyHostToDevice);
                 if (e != hipSuccess) {
                     hkv_decode_plan_destroy(pl);
-                    return fail_hip(e, "hkv_decode_plan_create_multi");
+                    return fail_hip(e, who);
                 }
             }
         } else if (pl->dev && n_req > 0) {
-            const size_t bytes = sizeof(int32_t) * rows.size();
-            hipError_t e = hipMalloc((void **)&pl->d_row_leaf, 2 * bytes);
-            if (e == hipSuccess) e = hipMemcpy(pl->d_row_leaf, rows.data(), bytes, hipMemcpyHostToDevice);
+            const size_t n = rows.size();
+            hipError_t e = hipMalloc((void **)&pl->d_row_mask, n * (sizeof(unsigned long long) + 2 * sizeof(int32_t)));
             if (e == hipSuccess) {
-                pl->d_row_limit = pl->d_row_leaf + rows.size();
-                e = hipMemcpy(pl->d_row_limit, lim.data(), bytes, hipMemcpyHostToDevice);
+                pl->d_row_leaf = reinterpret_cast<int32_t *>(pl->d_row_mask + n);
+                pl->d_row_limit = pl->d_row_leaf + n;
+                e = hipMemcpy(pl->d_row_mask, vis.data(), n * sizeof(unsigned long long), hipMemcpyHostToDevice);
             }
+            if (e == hipSuccess) e = hipMemcpy(pl->d_row_leaf, rows.data(), n * sizeof(int32_t), hipMemcpyHostToDevice);
+            if (e == hipSuccess) e = hipMemcpy(pl->d_row_limit, lim.data(), n * sizeof(int32_t), hipMemcpyHostToDevice);
             if (e != hipSuccess) {
                 hkv_decode_plan_destroy(pl);
-                return fail_hip(e, "hkv_decode_plan_create_multi");
+                return fail_hip(e, who);
             }
         }
     }
@@ -737,10 +752,35 @@ extern "C" int hkv_decode_plan_create_multi(hkv_pool *pool, const hkv_node *node
     return HKV_OK;
 }
 
+extern "C" int hkv_decode_plan_create_multi(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes,
+                                            const int32_t *node_pages, int32_t n_node_pages, const int32_t *req_leaf,
+                                            int32_t n_req, int32_t tokens_per_req, int32_t num_q_heads, uint32_t flags,
+                                            hkv_decode_plan **out) {
+    if (!out) return fail(HKV_EINVAL, "hkv_decode_plan_create_multi: null out");
+    *out = nullptr;
+    if (tokens_per_req < 1 || tokens_per_req > 16)
+        return fail(HKV_EINVAL, "hkv_decode_plan_create_multi: %d query tokens per request (1..16)", tokens_per_req);
+    return create_rows_plan(pool, nodes, n_nodes, node_pages, n_node_pages, req_leaf, n_req, tokens_per_req, nullptr,
+                            num_q_heads, flags, out, "hkv_decode_plan_create_multi");
+}
+
+extern "C" int hkv_decode_plan_create_tree(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes,
+                                           const int32_t *node_pages, int32_t n_node_pages, const int32_t *req_leaf,
+                                           int32_t n_req, int32_t tokens_per_req, const uint64_t *visible,
+                                           int32_t num_q_heads, uint32_t flags, hkv_decode_plan **out) {
+    if (!out) return fail(HKV_EINVAL, "hkv_decode_plan_create_tree: null out");
+    *out = nullptr;
+    if (tokens_per_req < 1 || tokens_per_req > 64)
+        return fail(HKV_EINVAL, "hkv_decode_plan_create_tree: %d drafted tokens per request (1..64)", tokens_per_req);
+    if (n_req > 0 && !visible) return fail(HKV_EINVAL, "hkv_decode_plan_create_tree: null visibility masks");
+    return create_rows_plan(pool, nodes, n_nodes, node_pages, n_node_pages, req_leaf, n_req, tokens_per_req, visible,
+                            num_q_heads, flags, out, "hkv_decode_plan_create_tree");
+}
+
 extern "C" int hkv_decode_plan_destroy(hkv_decode_plan *plan) {
     if (!plan) return HKV_OK;
     if (plan->dev) (void)hipFree(plan->dev);  // hipFree waits for work that may still read it
-    if (plan->d_row_leaf) (void)hipFree(plan->d_row_leaf);
+    if (plan->d_row_mask) (void)hipFree(plan->d_row_mask);
     if (plan->d_bt) (void)hipFree(plan->d_bt);
     for (hipEvent_t e : plan->ev)
         if (e) (void)hipEventDestroy(e);
@@ -807,7 +847,7 @@ extern "C" int attn_decode_plan_run(hkv_decode_plan *plan, const void *q, float 
     if (!plan->items.empty()) {
         DecodeLaunch a{view_of(plan->pool), q, plan->d_items, plan->d_pages, plan->d_node_req_idx, o_parts, lse_parts,
                        (int32_t)plan->items.size(), plan->num_q_heads, plan->max_parts, scale, nullptr,
-                       plan->d_row_leaf, plan->d_row_limit, plan->n_single};
+                       plan->d_row_leaf, plan->d_row_limit, plan->d_row_mask, plan->n_single};
         HKV_HIP(launch_decode(a, s, prof ? plan->ev[0] : nullptr, prof ? plan->ev[1] : nullptr));
     }
     if (plan->node_only) return HKV_OK;

@@ -180,8 +180,12 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
     // Tokens of this item that this lane's query row may see (all of them unless the row is one of
     // several query tokens of a request and this is the node that holds the request's newest tokens).
     int lim = it.n_tokens;
+    unsigned long long vis = 0;  // visibility of the tokens from lim on, one bit each
     auto load_limit = [&](int req) {
-        if (a.row_leaf && a.row_leaf[req] == it.node) lim = a.row_limit[req] - it.tok_begin;
+        if (a.row_leaf && a.row_leaf[req] == it.node) {
+            lim = a.row_limit[req] - it.tok_begin;
+            vis = a.row_mask[req];
+        }
     };
 
     // Loop-invariant byte offsets of this lane inside a (page, head) block and the page of the step
@@ -282,7 +286,10 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
         if (__builtin_amdgcn_ballot_w64(tok0 + NS > lim)) {  // some row of the tile does not see the whole step
 #pragma unroll
             for (int j = 0; j < NS; ++j)
-                if (tok0 + j >= lim) s[j] = -INFINITY;
+            {
+                const int d = tok0 + j - lim;  // index among the request's newest tokens
+                if (d >= 0 && !(d < 64 && ((vis >> d) & 1ull))) s[j] = -INFINITY;
+            }
         }
         float mx = s[0];
 #pragma unroll

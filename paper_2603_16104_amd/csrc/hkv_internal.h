@@ -61,10 +61,13 @@ struct DecodeLaunch {
     float scale;
     unsigned long long *trace;   // development builds only (HKV_TRACE): 8 timestamps per wavefront, else null
     // Several query tokens per request (null otherwise): row r of q is query token r % T of request
-    // r / T; inside the node row_leaf[r] it sees only the first row_limit[r] tokens (the causal mask
-    // among the request's newest tokens), every other node of its path it sees whole.
+    // r / T; inside the node row_leaf[r] it sees the first row_limit[r] tokens (everything before the
+    // request's T newest tokens) and, of the tokens behind them, number j iff bit j of row_mask[r] is
+    // set (a causal run, or the ancestors in a tree of drafted tokens); every other node of its path
+    // it sees whole.
     const int32_t *row_leaf;     // device [n_req * T]
     const int32_t *row_limit;    // device [n_req * T]
+    const unsigned long long *row_mask;  // device [n_req * T]
     // Items [0, n_single) get a workgroup each; the items behind them (short, at most 16 rows) are run
     // four to a workgroup, one per wavefront.
     int32_t n_single;

@@ -674,6 +674,66 @@ def run_decode_multi(gpu, oracle, w, T, seed=5):
     check_lse(got_l, exp_l, f"{w.name}_T{T}")
 
 
+def _draft_parents(widths):
+    parents, level = [], [-1]
+    for wd in widths:
+        nxt = []
+        for p in level:
+            for _ in range(wd):
+                parents.append(p)
+                nxt.append(len(parents) - 1)
+        level = nxt
+    return parents
+
+
+def _ancestor_masks(parents):
+    masks = []
+    for t in range(len(parents)):
+        m, v = 0, t
+        while v >= 0:
+            m |= 1 << v
+            v = parents[v]
+        masks.append(m)
+    return masks
+
+
+@pytest.mark.parametrize("kv_dtype", [wl.KV_BF16, wl.KV_FP8_E4M3])
+@pytest.mark.parametrize("widths", [(3, 2, 2), (2, 2, 1), (1, 1, 1, 1, 1), (4, 4, 3)])
+def test_decode_tree_of_drafted_tokens_by_masks(gpu, oracle, kv_dtype, widths):
+    """hkv_decode_plan_create_tree: every request's leaf ends with a tree of drafted tokens (21, 10, 5 and
+    the first 64 of a 4-4-3 tree), each query row sees the context, its ancestors and itself.  Leaves of 100, 77
+    (ragged), exactly T and T + 1 tokens, and a request whose drafted tokens are the root's own last ones;
+    the drafted block may straddle pages and chunks.  Against the oracle's walk of the forest with the
+    same masks (pinned on the CPU against one forest node per drafted token)."""
+    import torch
+    from paper_2603_16104_amd import binding as hkv
+    parents = _draft_parents(widths)
+    T = len(parents)
+    if T > 64:
+        parents = parents[:64]
+        T = 64
+    masks = _ancestor_masks(parents)
+    w = _multi_forest(kv_dtype, 8, 2, [100, 77, T, T + 1], [1, 2, 3, 4, 0], root_tokens=128)
+    f = w.forest
+    hp, dp = both_pools(gpu, oracle, w)
+    q = wl.f32_to_bf16_bits(np.random.default_rng(6).standard_normal((f.n_req * T, w.num_q_heads, 128)).astype(np.float32))
+    rows_leaf = np.repeat(f.req_leaf, T)
+    exp_o, exp_l = oracle.attn_decode_tree(hp, q, f.nodes, f.node_pages, rows_leaf, float(w.scale), tail_len=T,
+                                           tail_mask=masks * f.n_req)
+    plan = hkv.hkv_decode_plan_create_tree(dp.handle, f.nodes, f.node_pages, f.req_leaf, T, masks * f.n_req, w.num_q_heads)
+    ws_bytes = hkv.hkv_decode_plan_workspace_bytes(plan)
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
+    out = torch.full((f.n_req * T, w.num_q_heads, 128), 0x7FC0, dtype=torch.int16, device="cuda")
+    lse = torch.zeros((f.n_req * T, w.num_q_heads), dtype=torch.float32, device="cuda")
+    for _ in range(2):
+        hkv.attn_decode_plan_run(plan, gpu.to_device_bits(q), float(w.scale), out, lse, ws, ws_bytes)
+    torch.cuda.synchronize()
+    hkv.hkv_decode_plan_destroy(plan)
+    dp.close()
+    check_close(gpu.bf16_tensor_to_f64(out), exp_o, f"draft_tree_{T}")
+    check_lse(lse.cpu().numpy(), exp_l, f"draft_tree_{T}")
+
+
 def _multi_forest(kv_dtype, hq, hkv_, leaf_tokens, req_leaf, root_tokens=64, seed=31):
     parent = [-1] + [0] * len(leaf_tokens)
     ntok = [root_tokens] + list(leaf_tokens)

@@ -293,6 +293,27 @@ def test_decode_plan_accepts_nodes_that_end_inside_a_page(oracle):
         hkv.kv_pool_destroy(pool)
 
 
+def test_tree_verification_plan_error_codes():
+    pool = fake_pool(16, 2)
+    nodes = np.array([[-1, 0, 1, 16], [0, 1, 2, 20]], dtype=np.int32)
+    pages = np.array([3, 4, 5], dtype=np.int32)
+    ok = [0b001, 0b011, 0b101]
+    hkv.hkv_decode_plan_destroy(hkv.hkv_decode_plan_create_tree(pool, nodes, pages, [1], 3, ok, 4, hkv.PLAN_HOST_ONLY))
+    for T, masks, code in ((3, [0b001, 0b001, 0b101], hkv.EINVAL),       # token 1 does not see itself
+                           (3, [0b001, 0b011, 0b1101], hkv.EINVAL),      # a bit beyond the drafted tokens
+                           (65, [1] * 65, hkv.EINVAL),                   # more than 64 drafted tokens
+                           (21, [(1 << (t + 1)) - 1 for t in range(21)], hkv.EINVAL)):   # the leaf holds only 20 tokens
+        with pytest.raises(hkv.HkvError) as e:
+            hkv.hkv_decode_plan_create_tree(pool, nodes, pages, [1], T, masks, 4, hkv.PLAN_HOST_ONLY)
+        assert e.value.code == code, (T, masks)
+    p32 = fake_pool(16, 2, dtype=hkv.FP32)
+    with pytest.raises(hkv.HkvError) as e:
+        hkv.hkv_decode_plan_create_tree(p32, nodes, pages, [1], 3, ok, 4, hkv.PLAN_HOST_ONLY)
+    assert e.value.code == hkv.ESHAPE
+    hkv.kv_pool_destroy(p32)
+    hkv.kv_pool_destroy(pool)
+
+
 def test_decode_plan_sizes_of_benchmark_configs(oracle):
     items = _check_decode_plan(wl.config2(), oracle)
     assert len(items) == 640            # 64 leaves x 8 heads + 4 chunks x 4 row groups x 8 heads of the root

@@ -701,3 +701,68 @@ def test_tree_walk_decode_leaf_visibility(oracle):
             o, l = brute_attention(q[r, h], K[:T, h // w.group], V[:T, h // w.group], float(w.scale))
             assert np.abs(o1[r, h] - o).max() <= 1e-12
             assert (np.isneginf(l) and np.isneginf(l1[r, h])) or abs(l1[r, h] - l) <= 1e-12
+
+
+def _draft_tree(widths):
+    """Parents of the drafted tokens of one tree in topological order (-1: child of the context)."""
+    parents, level = [], [-1]
+    for wd in widths:
+        nxt = []
+        for p in level:
+            for _ in range(wd):
+                parents.append(p)
+                nxt.append(len(parents) - 1)
+        level = nxt
+    return parents
+
+
+def _ancestor_masks(parents):
+    masks = []
+    for t in range(len(parents)):
+        m, v = 0, t
+        while v >= 0:
+            m |= 1 << v
+            v = parents[v]
+        masks.append(m)
+    return masks
+
+
+def test_drafted_token_masks_equal_one_node_per_drafted_token(oracle):
+    """Two formulations of the verification of a tree of drafted tokens must agree bit for bit in the oracle:
+    (A) the drafted tokens are the last T tokens of the request's leaf node and every query row carries a
+    bit mask of the drafted tokens it sees (its ancestors and itself); (B) every drafted token is a forest
+    node of its own under the context, the forest being the mask (pinned above against dense attention)."""
+    H, Hq, ctx_len = 2, 4, 37
+    parents = _draft_tree((2, 2, 1))                 # 2 + 4 + 4 = 10 drafted tokens
+    T = len(parents)
+    rng = np.random.default_rng(19)
+    mk = lambda n: wl.f32_to_bf16_bits(rng.standard_normal((n, H, D)).astype(np.float32))
+    root_kv, ctx_kv, draft_kv = (mk(32), mk(32)), (mk(ctx_len), mk(ctx_len)), (mk(T), mk(T))
+    q = wl.f32_to_bf16_bits(rng.standard_normal((T, Hq, D)).astype(np.float32))
+    # (A) root -> one leaf holding context + drafted tokens
+    n_leaf = ctx_len + T
+    pa = oracle.HostPool(2 + (n_leaf + 15) // 16, H, oracle.BF16)
+    pa.write([0, 1], 0, *root_kv)
+    leaf_pages = list(range(2, 2 + (n_leaf + 15) // 16))
+    pa.write(leaf_pages, 0, np.concatenate([ctx_kv[0], draft_kv[0]]), np.concatenate([ctx_kv[1], draft_kv[1]]))
+    nodes_a = np.array([[-1, 0, 2, 32], [0, 2, len(leaf_pages), n_leaf]], dtype=np.int32)
+    oa, la = oracle.attn_decode_tree(pa, q, nodes_a, np.array([0, 1] + leaf_pages, dtype=np.int32), [1] * T, 0.1,
+                                     tail_len=T, tail_mask=_ancestor_masks(parents))
+    # (B) root -> context -> one node per drafted token
+    n_ctx_pages = (ctx_len + 15) // 16
+    pb = oracle.HostPool(2 + n_ctx_pages + T, H, oracle.BF16)
+    pb.write([0, 1], 0, *root_kv)
+    pb.write(list(range(2, 2 + n_ctx_pages)), 0, *ctx_kv)
+    rows_b = [[-1, 0, 2, 32], [0, 2, n_ctx_pages, ctx_len]]
+    for t in range(T):
+        pb.write([2 + n_ctx_pages + t], 0, draft_kv[0][t:t + 1], draft_kv[1][t:t + 1])
+        rows_b.append([1 if parents[t] < 0 else 2 + parents[t], 2 + n_ctx_pages + t, 1, 1])
+    ob, lb = oracle.attn_decode_tree(pb, q, np.array(rows_b, dtype=np.int32), np.arange(2 + n_ctx_pages + T, dtype=np.int32),
+                                     [2 + t for t in range(T)], 0.1)
+    assert np.array_equal(oa, ob) and np.array_equal(la, lb)
+    # and a causal run is the mask with bits 0..t: equal to leaf_visible
+    oc, lc = oracle.attn_decode_tree(pa, q, nodes_a, np.array([0, 1] + leaf_pages, dtype=np.int32), [1] * T, 0.1,
+                                     tail_len=T, tail_mask=[(1 << (t + 1)) - 1 for t in range(T)])
+    od, ld = oracle.attn_decode_tree(pa, q, nodes_a, np.array([0, 1] + leaf_pages, dtype=np.int32), [1] * T, 0.1,
+                                     leaf_visible=[ctx_len + t + 1 for t in range(T)])
+    assert np.array_equal(oc, od) and np.array_equal(lc, ld)
