@@ -181,6 +181,19 @@ static void forests_and_plans(std::mt19937 &rng) {
                                                          f.leaves.data(), n_req, T, heads * group, HKV_PLAN_HOST_ONLY, &mp);
             CHECK(rcm == HKV_OK || rcm == HKV_EINVAL);
             if (mp) CHECK(hkv_decode_plan_destroy(mp) == HKV_OK);
+            // a tree of drafted tokens per request: random ancestor masks (token t sees itself and earlier ones)
+            const int Td = 1 + rng() % 64;
+            std::vector<uint64_t> vis((size_t)n_req * Td);
+            for (size_t i = 0; i < vis.size(); ++i) {
+                const int t = (int)(i % Td);
+                const uint64_t below = t ? (((uint64_t)rng() << 32 | rng()) & ((1ull << t) - 1)) : 0;
+                vis[i] = below | 1ull << t;
+            }
+            hkv_decode_plan *tp = nullptr;
+            const int rct = hkv_decode_plan_create_tree(pool, f.nodes.data(), n_nodes, f.pages.data(), (int32_t)f.pages.size(),
+                                                        f.leaves.data(), n_req, Td, vis.data(), heads * group, HKV_PLAN_HOST_ONLY, &tp);
+            CHECK(rct == HKV_OK || rct == HKV_EINVAL || (dtype == HKV_FP32 && rct == HKV_ESHAPE));
+            if (tp) CHECK(hkv_decode_plan_destroy(tp) == HKV_OK);
             // prefill plan over the flattened tables: the last node of every path is new
             std::vector<int32_t> cu(n_req + 1, 0);
             for (int r = 0; r < n_req; ++r) cu[r + 1] = cu[r] + std::min<int32_t>(kv_len[r], f.nodes[f.leaves[r]].n_tokens);
