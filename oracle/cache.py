@@ -8,7 +8,7 @@ pinned; under memory pressure unpinned blocks are evicted at block level, least 
 and never a prefix before its extensions (the longest match goes first); an evicted prefix is simply
 recomputed by the next call that needs it.
 
-Readings where the paper is silent (the library takes the same ones; listed in the design doc)
+Readings where the paper is silent (the library takes the same ones)
   C1  A block is 16 consecutive tokens; its identity is (identity of the preceding block, its 16
       token ids): two sequences share a block exactly when they agree on everything up to its end.
       Only full blocks are shared; a sequence's last, partial block is private to it.

@@ -15,7 +15,7 @@ What follows the paper
   * Section 5, "Token usage" / "Precedence delay" / problem formulation: u_p, u_d, u, d, b, c, T.
   * Section 5, the scheduling algorithm (Schedule / Recurse) and the paragraph below it.
 
-Readings taken where the paper is silent (the same ones the library takes; listed in the design doc)
+Readings taken where the paper is silent (the same ones the library takes)
   R1  A template is a list of integer symbols: s >= 0 is a static token id, s < 0 is a placeholder
       for the output of call -(s + 1).  omega(v) = number of static tokens of v's segment plus, for
       every placeholder, the estimated output length len_out of the call it stands for.
