@@ -207,6 +207,30 @@ def bench_workflow(runtime, hkv, wl, shape: str):
             res["orders"][name]["lru_cache_evictions"] = sim["evictions"]
             res["orders"][name]["lru_cache_gpu_ms"] = round(ev0.elapsed_time(ev1), 3)
     r.close()
+    # decode side: the calls of one dependency level generate side by side; the workflow's templated radix
+    # tree is the prefix forest of that step (each call has produced half of its output)
+    res["decode_levels"] = []
+    for k, calls in enumerate(runtime.workflow_levels(wf)):
+        wd = runtime.workflow_decode_workload(wf, calls, [max(1, wf.len_out[c] // 2) for c in calls])
+        wu = wl.without_sharing(wd)
+        row = {"level": k, "calls": len(calls), "unique_kv_MB": round(wd.unique_kv_bytes() / 1e6, 1),
+               "attended_over_unique": round(wu.unique_kv_bytes() / max(1, wd.unique_kv_bytes()), 2)}
+        for name, w in (("tree_decode_us", wd), ("unshared_decode_us", wu)):
+            n_pools = max(1, min(4, int(600e6 // max(1, w.unique_kv_bytes())) + 1))
+            pools = []
+            for i in range(n_pools):
+                p = runtime.DevicePool(w.num_pages, w.num_kv_heads, w.kv_dtype, poison=False)
+                p.fill_random(i)
+                pools.append(p)
+            runners = [runtime.DecodeRunner(p, w, random_q=True) for p in pools]
+            row[name] = round(time_steps(lambda i: runners[i % n_pools].run(), 100, 10) * 1e6, 1)
+            for rr in runners:
+                rr.close()
+            for p in pools:
+                p.close()
+            del runners, pools
+            torch.cuda.empty_cache()
+        res["decode_levels"].append(row)
     return res
 
 

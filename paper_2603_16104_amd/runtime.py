@@ -393,6 +393,47 @@ class PrefixCacheRunner:
         self.pool.close()
 
 
+def workflow_levels(wf: wl.Workflow) -> list:
+    """Calls grouped by dependency depth: level 0 quotes no other call's output, level k + 1 quotes
+    outputs of level <= k.  The calls of one level can decode side by side."""
+    depth = []
+    for tmpl in wf.templates:
+        deps = [-(s + 1) for s in tmpl if s < 0]
+        depth.append(1 + max((depth[d] for d in deps), default=-1))
+    return [[c for c, d in enumerate(depth) if d == k] for k in range(max(depth, default=-1) + 1)]
+
+
+def workflow_decode_workload(wf: wl.Workflow, calls, generated, num_q_heads: int = 32, num_kv_heads: int = 8,
+                             seed: int = wl.BASE_SEED + 12) -> wl.Workload:
+    """The decode step of a batch of workflow calls running side by side, as a prefix forest: the
+    templated radix tree of the workflow (built by the library) restricted to the paths of `calls`,
+    omega(v) tokens per node, and under each call's prompt a private node with the `generated[i]`
+    tokens it has produced so far (the newest one is the query token's own)."""
+    tree = hkv.trt_build(wf.templates, wf.len_out, wf.worker)
+    try:
+        nd = hkv.trt_nodes(tree)
+    finally:
+        hkv.trt_destroy(tree)
+    keep = set()
+    for c in calls:
+        v = int(nd["leaf_of_call"][c])
+        while v >= 0 and v not in keep:
+            keep.add(v)
+            v = int(nd["parent"][v])
+    order = sorted(keep)                       # preorder numbering: parents stay first
+    new_id = {v: i for i, v in enumerate(order)}
+    gen = {int(nd["leaf_of_call"][c]): int(g) for c, g in zip(calls, generated)}
+    parent = [new_id[int(nd["parent"][v])] if nd["parent"][v] >= 0 else -1 for v in order]
+    ntok = [gen.get(v, int(nd["weight"][v])) for v in order]
+    leaves = [new_id[int(nd["leaf_of_call"][c])] for c in calls]
+    n_used = sum((t + 15) // 16 for t in ntok)
+    num_pages = n_used + n_used // 4 + 1
+    pages = np.random.default_rng([seed, 0]).permutation(num_pages).astype(np.int32)
+    f = wl.make_forest(parent, ntok, leaves, pages)
+    return wl.Workload(name=f"{wf.name}_decode_{len(calls)}calls", num_q_heads=num_q_heads, num_kv_heads=num_kv_heads,
+                       kv_dtype=wl.KV_BF16, num_pages=num_pages, seed=seed, forest=f, mode="decode")
+
+
 def workflow_prompt_tokens(wf: wl.Workflow, call: int) -> list:
     """The call's full prompt as token ids: static symbols as they are, a placeholder for call x as
     len_out[x] ids that nothing else uses (what the LLM wrote is not known; only that it is the same

@@ -998,3 +998,18 @@ def test_prefix_cache_engine_under_page_budget(gpu, oracle, seed, n_pages):
         check_close(gpu.bf16_tensor_to_f64(st["out"]), exp_o, f"prompt of {n} tokens, {cached} cached")
         check_lse(st["lse"].cpu().numpy(), exp_l, "prefix cache engine")
     r.close()
+
+
+@pytest.mark.parametrize("shape", ["map_reduce", "debate"])
+def test_workflow_decode_levels(gpu, oracle, shape):
+    """The decode step of every dependency level of a small workflow: the workflow's templated radix tree
+    (built by the library), restricted to the level's calls, is the prefix forest; each call has generated a
+    different number of tokens.  Against the oracle over the same forest."""
+    wf = (wl.workflow_map_reduce(n_queries=3, n_mappers=3, sys_len=48, ctx_len=80, len_out=32) if shape == "map_reduce"
+          else wl.workflow_debate(n_queries=2, n_agents=3, rounds=3, sys_len=64, q_len=48, len_out=16))
+    levels = gpu.workflow_levels(wf)
+    assert len(levels) == (2 if shape == "map_reduce" else 3)
+    for calls in levels:
+        w = gpu.workflow_decode_workload(wf, calls, [1 + (7 * i) % 23 for i in range(len(calls))], 8, 2)
+        assert w.forest.attended_tokens() > w.forest.unique_tokens()      # something is shared
+        run_decode(gpu, oracle, w)
