@@ -337,9 +337,21 @@ int hkv_prefill_plan_tiles(const hkv_prefill_plan *plan, int32_t *tiles_out);
  * [cu_q[n_req]][num_q_heads] float or NULL. */
 int attn_prefill_plan_run(hkv_prefill_plan *plan, const void *q, float scale, void *out, float *lse_out,
                           void *stream);
+/* fp8 pools: the matrix-core kernel reads bf16, so the pages the batch reads (each once, however
+ * many requests share it) are first dequantised (code * scale, rounded to bf16) into a scratch pool
+ * in the caller's workspace: hkv_prefill_plan_workspace_bytes(plan) bytes (8 KiB per distinct page
+ * and KV head; 0 for bf16 and fp32 pools), device memory, 256-byte aligned, scratch.  The pre-pass
+ * moves 3 bytes per cached element against 512 flop per (query, key) pair: well below 1 % of the
+ * kernel at the sizes prefill runs at.  attn_prefill_plan_run is the same call without a workspace.
+ * EINVAL (fp8 pool and no / unaligned workspace), ENOMEM (too small). */
+size_t hkv_prefill_plan_workspace_bytes(const hkv_prefill_plan *plan);
+int attn_prefill_plan_run_ws(hkv_prefill_plan *plan, const void *q, float scale, void *out, float *lse_out,
+                             void *workspace, size_t workspace_bytes, void *stream);
 
-/* One-shot form; workspace may be NULL (attn_prefill_workspace_bytes is 0 in this version: a
- * query tile reads its whole key range itself). */
+/* One-shot form; workspace may be NULL for bf16 and fp32 pools (a query tile reads its whole key
+ * range itself; attn_prefill_workspace_bytes is 0); an fp8 pool needs what
+ * hkv_prefill_plan_workspace_bytes reports for the same batch (the error text of a too small
+ * workspace names the size). */
 int attn_prefill_with_prefix(hkv_pool *pool, const void *q, const int32_t *cu_q, const int32_t *block_table,
                              int32_t max_pages, const int32_t *kv_len, int32_t n_req, int32_t num_q_heads,
                              float scale, void *out, float *lse_out, void *workspace, size_t workspace_bytes,

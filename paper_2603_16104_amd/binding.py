@@ -30,7 +30,7 @@ EXPORTS = [
     "hkv_decode_plan_max_parts", "hkv_decode_plan_part_counts", "lse_merge_dense", "attn_decode_plan_run",
     "hkv_decode_plan_set_profiling", "hkv_decode_plan_elapsed_ms",
     "attn_decode_prefix_tree", "attn_decode_workspace_bytes", "hkv_prefill_plan_create", "hkv_prefill_plan_destroy",
-    "hkv_prefill_plan_num_tiles", "hkv_prefill_plan_tiles", "attn_prefill_plan_run", "attn_prefill_with_prefix",
+    "hkv_prefill_plan_num_tiles", "hkv_prefill_plan_tiles", "attn_prefill_plan_run", "attn_prefill_plan_run_ws", "hkv_prefill_plan_workspace_bytes", "attn_prefill_with_prefix",
     "attn_prefill_workspace_bytes", "hkv_mfma_probe", "hkv_hbm_read_probe",
     "kv_cache_create", "kv_cache_destroy", "kv_cache_acquire", "kv_cache_release", "kv_cache_unpin", "kv_cache_stats",
     "trt_build", "trt_destroy", "trt_num_nodes", "trt_num_syms", "trt_num_calls", "trt_nodes", "trt_prefill_usage",
@@ -62,7 +62,8 @@ def lib():
                                "(python -c 'import __graft_entry__ as g; g.build()'); there is no fallback path")
         L = C.CDLL(LIB_PATH)
         L.hkv_last_error.restype = C.c_char_p
-        for name in ("hkv_decode_plan_workspace_bytes", "attn_decode_workspace_bytes", "attn_prefill_workspace_bytes"):
+        for name in ("hkv_decode_plan_workspace_bytes", "attn_decode_workspace_bytes", "attn_prefill_workspace_bytes",
+                     "hkv_prefill_plan_workspace_bytes"):
             getattr(L, name).restype = C.c_size_t
         _lib = L
     return _lib
@@ -326,8 +327,15 @@ def hkv_prefill_plan_tiles(plan) -> np.ndarray:
     return tiles
 
 
-def attn_prefill_plan_run(plan, q, scale: float, out, lse_out=None, stream=None) -> None:
-    _check(lib().attn_prefill_plan_run(plan, _dev(q), C.c_float(scale), _dev(out), _dev(lse_out), _stream(stream)))
+def attn_prefill_plan_run(plan, q, scale: float, out, lse_out=None, stream=None, workspace=None,
+                          workspace_bytes: int = 0) -> None:
+    """workspace: device scratch of hkv_prefill_plan_workspace_bytes(plan) bytes (fp8 pools only)."""
+    _check(lib().attn_prefill_plan_run_ws(plan, _dev(q), C.c_float(scale), _dev(out), _dev(lse_out), _dev(workspace),
+                                          C.c_size_t(workspace_bytes), _stream(stream)))
+
+
+def hkv_prefill_plan_workspace_bytes(plan) -> int:
+    return int(lib().hkv_prefill_plan_workspace_bytes(plan))
 
 
 def attn_prefill_with_prefix(pool, q, cu_q, block_table, kv_len, num_q_heads: int, scale: float, out, lse_out=None,

@@ -12,6 +12,7 @@
 #include <new>
 #include <numeric>
 #include <string>
+#include <unordered_map>
 #include <vector>
 
 using namespace hkv;
@@ -96,6 +97,10 @@ struct hkv_prefill_plan {
     PrefillTile *d_tiles = nullptr;
     int32_t *d_block_table = nullptr;
     int32_t *d_rows_req = nullptr, *d_rows_len = nullptr;  // fp32 pools: per new token (one allocation: d_rows_req)
+    // fp8 pools: the pages the batch reads are first dequantised into a bf16 scratch pool in the caller's
+    // workspace (page i of the scratch = src_pages[i]); the device block table then holds scratch indices.
+    std::vector<int32_t> src_pages;
+    int32_t *d_src_pages = nullptr;
 };
 
 struct hkv_pool {
@@ -943,7 +948,6 @@ extern "C" int hkv_prefill_plan_create(hkv_pool *pool, const int32_t *cu_q, cons
     if (num_q_heads <= 0 || num_q_heads % Hkv) return fail(HKV_ESHAPE, "hkv_prefill_plan_create: %d query heads over %d KV heads", num_q_heads, Hkv);
     const int G = num_q_heads / Hkv;
     if (G > 16) return fail(HKV_ESHAPE, "hkv_prefill_plan_create: query/KV head ratio %d (supported: 1..16)", G);
-    if (pool->d.dtype == HKV_FP8_E4M3) return fail(HKV_ESHAPE, "hkv_prefill_plan_create: prefill reads bf16 and fp32 pools only");
     if (n_req < 0 || max_pages < 0 || (n_req > 0 && (!cu_q || !kv_len || (max_pages > 0 && !block_table))))
         return fail(HKV_EINVAL, "hkv_prefill_plan_create: bad argument");
     if (n_req > 0 && cu_q[0] != 0) return fail(HKV_EINVAL, "hkv_prefill_plan_create: cu_q[0] must be 0");
@@ -990,18 +994,41 @@ extern "C" int hkv_prefill_plan_create(hkv_pool *pool, const int32_t *cu_q, cons
             pl->tiles.push_back(PrefillTile{p.req, p.q_begin, p.n_q, h, cu_q[p.req] + p.q_begin, kv_len[p.req] - s,
                                             kv_len[p.req], p.req * max_pages});
         }
+    // fp8 pools: number the pages this batch reads (first use first) and point the device table at them
+    std::vector<int32_t> remapped;
+    if (pool->d.dtype == HKV_FP8_E4M3) {
+        std::unordered_map<int32_t, int32_t> index;
+        remapped.assign(pl->block_table.size(), 0);
+        for (int r = 0; r < n_req; ++r) {
+            if (cu_q[r + 1] == cu_q[r]) continue;
+            const int64_t need = ((int64_t)kv_len[r] + HKV_PAGE_SIZE - 1) / HKV_PAGE_SIZE;
+            for (int64_t i = 0; i < need; ++i) {
+                const int32_t id = block_table[(size_t)r * max_pages + i];
+                auto it = index.find(id);
+                if (it == index.end()) {
+                    it = index.emplace(id, (int32_t)pl->src_pages.size()).first;
+                    pl->src_pages.push_back(id);
+                }
+                remapped[(size_t)r * max_pages + i] = it->second;
+            }
+        }
+    }
+    const std::vector<int32_t> &dev_table = pool->d.dtype == HKV_FP8_E4M3 ? remapped : pl->block_table;
     if (!(flags & HKV_PLAN_HOST_ONLY) && !pl->tiles.empty()) {
         size_t off_bt = align_up(sizeof(PrefillTile) * pl->tiles.size(), 256);
-        size_t total = off_bt + align_up(sizeof(int32_t) * pl->block_table.size(), 256) + 256;
+        size_t off_src = off_bt + align_up(sizeof(int32_t) * dev_table.size(), 256);
+        size_t total = off_src + align_up(sizeof(int32_t) * pl->src_pages.size(), 256) + 256;
         hipError_t e = hipMalloc(&pl->dev, total);
         if (e == hipSuccess) {
             pl->d_tiles = static_cast<PrefillTile *>(pl->dev);
             pl->d_block_table = reinterpret_cast<int32_t *>(static_cast<char *>(pl->dev) + off_bt);
+            pl->d_src_pages = reinterpret_cast<int32_t *>(static_cast<char *>(pl->dev) + off_src);
             e = hipMemcpy(pl->d_tiles, pl->tiles.data(), sizeof(PrefillTile) * pl->tiles.size(), hipMemcpyHostToDevice);
         }
         if (e == hipSuccess)
-            e = hipMemcpy(pl->d_block_table, pl->block_table.data(), sizeof(int32_t) * pl->block_table.size(),
-                          hipMemcpyHostToDevice);
+            e = hipMemcpy(pl->d_block_table, dev_table.data(), sizeof(int32_t) * dev_table.size(), hipMemcpyHostToDevice);
+        if (e == hipSuccess && !pl->src_pages.empty())
+            e = hipMemcpy(pl->d_src_pages, pl->src_pages.data(), sizeof(int32_t) * pl->src_pages.size(), hipMemcpyHostToDevice);
         if (e == hipSuccess && pool->d.dtype == HKV_FP32 && pl->total_q > 0) {
             std::vector<int32_t> rr(2 * (size_t)pl->total_q);
             for (int r = 0; r < n_req; ++r)
@@ -1045,8 +1072,18 @@ extern "C" int hkv_prefill_plan_tiles(const hkv_prefill_plan *plan, int32_t *til
     return HKV_OK;
 }
 
+extern "C" size_t hkv_prefill_plan_workspace_bytes(const hkv_prefill_plan *plan) {
+    if (!plan) return 0;
+    return 2 * plan->src_pages.size() * (size_t)plan->pool->d.num_kv_heads * HKV_PAGE_SIZE * HKV_HEAD_DIM * sizeof(uint16_t);
+}
+
 extern "C" int attn_prefill_plan_run(hkv_prefill_plan *plan, const void *q, float scale, void *out, float *lse_out,
                                      void *stream) {
+    return attn_prefill_plan_run_ws(plan, q, scale, out, lse_out, nullptr, 0, stream);
+}
+
+extern "C" int attn_prefill_plan_run_ws(hkv_prefill_plan *plan, const void *q, float scale, void *out, float *lse_out,
+                                        void *workspace, size_t workspace_bytes, void *stream) {
     if (!plan) return fail(HKV_EINVAL, "attn_prefill_plan_run: null plan");
     if (plan->tiles.empty()) return HKV_OK;
     if (!q || !out) return fail(HKV_EINVAL, "attn_prefill_plan_run: null q or out");
@@ -1059,7 +1096,19 @@ extern "C" int attn_prefill_plan_run(hkv_prefill_plan *plan, const void *q, floa
         HKV_HIP(launch_rows_fp32(r, static_cast<hipStream_t>(stream)));
         return HKV_OK;
     }
-    PrefillLaunch a{view_of(plan->pool), q, plan->d_tiles, plan->d_block_table, out, lse_out,
+    PoolView view = view_of(plan->pool);
+    if (plan->pool->d.dtype == HKV_FP8_E4M3) {  // dequantise the pages of this batch, then read the scratch pool
+        const size_t need = hkv_prefill_plan_workspace_bytes(plan);
+        if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255))
+            return fail(HKV_EINVAL, "attn_prefill_plan_run: an fp8 pool needs a 256-byte aligned workspace of %zu bytes", need);
+        if (workspace_bytes < need)
+            return fail(HKV_ENOMEM, "attn_prefill_plan_run: workspace has %zu bytes, %zu needed", workspace_bytes, need);
+        void *k_dst = workspace, *v_dst = static_cast<char *>(workspace) + need / 2;
+        PoolDequantLaunch d{view, plan->d_src_pages, (int32_t)plan->src_pages.size(), k_dst, v_dst};
+        HKV_HIP(launch_pool_dequant(d, static_cast<hipStream_t>(stream)));
+        view = PoolView{k_dst, v_dst, nullptr, nullptr, view.num_kv_heads, HKV_BF16};
+    }
+    PrefillLaunch a{view, q, plan->d_tiles, plan->d_block_table, out, lse_out,
                     (int32_t)plan->tiles.size(), plan->num_q_heads, scale};
     HKV_HIP(launch_prefill(a, static_cast<hipStream_t>(stream)));
     return HKV_OK;
@@ -1069,8 +1118,6 @@ extern "C" int attn_prefill_with_prefix(hkv_pool *pool, const void *q, const int
                                         int32_t max_pages, const int32_t *kv_len, int32_t n_req, int32_t num_q_heads,
                                         float scale, void *out, float *lse_out, void *workspace, size_t workspace_bytes,
                                         void *stream) {
-    (void)workspace;
-    (void)workspace_bytes;
     if (!pool) return fail(HKV_EINVAL, "attn_prefill_with_prefix: null pool");
     hkv_prefill_plan *c = pool->cached_prefill;
     bool same = c && c->dev && c->n_req == n_req && c->num_q_heads == num_q_heads && c->max_pages == max_pages &&
@@ -1085,7 +1132,7 @@ extern "C" int attn_prefill_with_prefix(hkv_pool *pool, const void *q, const int
         if (c) hkv_prefill_plan_destroy(c);
         pool->cached_prefill = c = fresh;
     }
-    return attn_prefill_plan_run(c, q, scale, out, lse_out, stream);
+    return attn_prefill_plan_run_ws(c, q, scale, out, lse_out, workspace, workspace_bytes, stream);
 }
 
 extern "C" size_t attn_prefill_workspace_bytes(int32_t total_q, int32_t num_q_heads) {

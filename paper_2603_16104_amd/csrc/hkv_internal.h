@@ -109,6 +109,16 @@ struct PoolCopyLaunch {
     int32_t dst[kMaxCopyPairs];
 };
 
+// fp8 pages -> bf16 pages of a scratch pool (page i of the scratch = src_pages[i] of the pool), so that
+// the matrix-core prefill kernel can read an fp8 pool.
+struct PoolDequantLaunch {
+    PoolView pool;               // the fp8 pool
+    const int32_t *src_pages;    // device [n_pages]
+    int32_t n_pages;
+    void *k_dst;                 // device, n_pages * num_kv_heads * 2048 bf16, bf16 block format
+    void *v_dst;
+};
+
 // fp32 pools: one wavefront per (query token, query head), no sharing (rows_fp32.hip).
 struct RowsLaunch {
     PoolView pool;
@@ -132,6 +142,7 @@ int prefill_tile_tokens(int group);
 
 hipError_t launch_pool_write(const PoolWriteLaunch &a, hipStream_t s);
 hipError_t launch_pool_copy(const PoolCopyLaunch &a, hipStream_t s);
+hipError_t launch_pool_dequant(const PoolDequantLaunch &a, hipStream_t s);
 hipError_t launch_decode(const DecodeLaunch &a, hipStream_t s, hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr);
 hipError_t launch_rows_fp32(const RowsLaunch &a, hipStream_t s);
 hipError_t launch_pool_write_fp32(const PoolWriteLaunch &a, hipStream_t s);

@@ -177,7 +177,46 @@ __global__ __launch_bounds__(256) void pool_copy_kernel(PoolCopyLaunch a) {
     }
 }
 
+// One workgroup per (scratch page, KV head): value = code * scale, rounded to bf16 (RNE), written in the
+// bf16 block format.  A thread converts 8 consecutive codes of K and of V: in both formats they are 8
+// consecutive elements (K: 8 dimensions of one slot inside a 64-byte chunk; V: 8 slots of one dimension).
+__global__ __launch_bounds__(256) void pool_dequant_kernel(PoolDequantLaunch a) {
+    const int i = blockIdx.x, h = blockIdx.y, tid = threadIdx.x;
+    const int page = a.src_pages[i];
+    const size_t src_blk = ((size_t)page * a.pool.num_kv_heads + h) * kBlockElems;
+    const size_t dst_blk = ((size_t)i * a.pool.num_kv_heads + h) * kBlockElems;
+    const float ks = a.pool.k_scale[(size_t)page * a.pool.num_kv_heads + h];
+    const float vs = a.pool.v_scale[(size_t)page * a.pool.num_kv_heads + h];
+    typedef __attribute__((ext_vector_type(2))) float f32x2;
+    auto convert = [](u32x2 w, float sc) {
+        u32x4 o;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[j], false), hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[j], true);
+            o[2 * j] = pack_bf16(lo[0] * sc, lo[1] * sc);
+            o[2 * j + 1] = pack_bf16(hi[0] * sc, hi[1] * sc);
+        }
+        return o;
+    };
+    {   // K: fp8 element (slot t, dim d) at (d / 64) * 1024 + t * 64 + d % 64, bf16 at (d / 32) * 512 + t * 32 + d % 32
+        const int e = 8 * tid, c = e >> 10, t = (e >> 6) & 15, d = 64 * c + (e & 63);
+        const u32x2 w = *reinterpret_cast<const u32x2 *>(static_cast<const uint8_t *>(a.pool.k_pages) + src_blk + e);
+        *reinterpret_cast<u32x4 *>(static_cast<uint16_t *>(a.k_dst) + dst_blk + (d >> 5) * 512 + t * 32 + (d & 31)) = convert(w, ks);
+    }
+    {   // V: element (slot t, dim d) at d * 16 + t in both formats
+        const int e = 8 * tid;
+        const u32x2 w = *reinterpret_cast<const u32x2 *>(static_cast<const uint8_t *>(a.pool.v_pages) + src_blk + e);
+        *reinterpret_cast<u32x4 *>(static_cast<uint16_t *>(a.v_dst) + dst_blk + e) = convert(w, vs);
+    }
+}
+
 }  // namespace
+
+hipError_t launch_pool_dequant(const PoolDequantLaunch &a, hipStream_t s) {
+    if (a.n_pages <= 0) return hipSuccess;
+    hipLaunchKernelGGL(pool_dequant_kernel, dim3(a.n_pages, a.pool.num_kv_heads), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
 
 hipError_t launch_pool_copy(const PoolCopyLaunch &a, hipStream_t s) {
     if (a.n <= 0) return hipSuccess;

@@ -141,9 +141,11 @@ class PrefillRunner:
         self.out = torch.zeros((tq, workload.num_q_heads, hkv.HEAD_DIM), dtype=odt, device=dev)
         self.lse = torch.zeros((tq, workload.num_q_heads), dtype=torch.float32, device=dev)
         self.scale = float(workload.scale)
+        self.ws_bytes = hkv.hkv_prefill_plan_workspace_bytes(self.plan)      # fp8 pools: scratch for dequantised pages
+        self.ws = torch.empty(max(self.ws_bytes, 256), dtype=torch.uint8, device=dev) if self.ws_bytes else None
 
     def run(self, stream=None) -> None:
-        hkv.attn_prefill_plan_run(self.plan, self.q, self.scale, self.out, self.lse, stream)
+        hkv.attn_prefill_plan_run(self.plan, self.q, self.scale, self.out, self.lse, stream, self.ws, self.ws_bytes)
 
     def close(self) -> None:
         if self.plan is not None:

@@ -17,6 +17,7 @@
 namespace hkv {
 hipError_t launch_pool_write(const PoolWriteLaunch &, hipStream_t) { return hipSuccess; }
 hipError_t launch_pool_copy(const PoolCopyLaunch &, hipStream_t) { return hipSuccess; }
+hipError_t launch_pool_dequant(const PoolDequantLaunch &, hipStream_t) { return hipSuccess; }
 hipError_t launch_decode(const DecodeLaunch &, hipStream_t, hipEvent_t, hipEvent_t) { return hipSuccess; }
 hipError_t launch_rows_fp32(const RowsLaunch &, hipStream_t) { return hipSuccess; }
 hipError_t launch_pool_write_fp32(const PoolWriteLaunch &, hipStream_t) { return hipSuccess; }
@@ -200,12 +201,9 @@ static void forests_and_plans(std::mt19937 &rng) {
             hkv_prefill_plan *pp = nullptr;
             const int rcp = hkv_prefill_plan_create(pool, cu.data(), bt.data(), f.max_pages, kv_len.data(), n_req, heads * group,
                                                     HKV_PLAN_HOST_ONLY, &pp);
-            if (dtype == HKV_FP8_E4M3) {
-                CHECK(rcp == HKV_ESHAPE && pp == nullptr);  // prefill reads bf16 and fp32 pools only
-            } else {
-                if (rcp != HKV_OK) std::fprintf(stderr, "prefill plan: %s\n", hkv_last_error());
-                CHECK(rcp == HKV_OK);
-            }
+            if (rcp != HKV_OK) std::fprintf(stderr, "prefill plan: %s\n", hkv_last_error());
+            CHECK(rcp == HKV_OK);
+            if (pp) CHECK((hkv_prefill_plan_workspace_bytes(pp) > 0) == (dtype == HKV_FP8_E4M3 && hkv_prefill_plan_num_tiles(pp) > 0));
             if (pp) {
                 std::vector<int32_t> tiles((size_t)hkv_prefill_plan_num_tiles(pp) * 8 + 8);
                 CHECK(hkv_prefill_plan_tiles(pp, tiles.data()) == HKV_OK);

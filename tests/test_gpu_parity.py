@@ -33,12 +33,18 @@ def check_close(got, exp, what=""):
     return max_abs, rel
 
 
-def check_lse(got, exp, what=""):
+# Prefill over an fp8 pool reads K rounded once more (code * scale to bf16, relative error <= 2^-9 per element):
+# a score then moves by about 2^-9 / sqrt(3) * |s-scale terms| ~ 1.1e-3 (one sigma, unit-variance q and k), and lse,
+# a weighted mean of scores, by the same; 5e-3 is 4.5 sigma.
+LSE_ABS_FP8_PREFILL = 5e-3
+
+
+def check_lse(got, exp, what="", tol=LSE_ABS):
     got, exp = np.asarray(got, dtype=np.float64), np.asarray(exp, dtype=np.float64)
     fin = np.isfinite(exp)
     assert np.array_equal(np.isneginf(got), np.isneginf(exp)), f"{what}: -inf pattern"
     if fin.any():
-        assert np.abs(got[fin] - exp[fin]).max() <= LSE_ABS, f"{what}: lse {np.abs(got[fin] - exp[fin]).max():.3e}"
+        assert np.abs(got[fin] - exp[fin]).max() <= tol, f"{what}: lse {np.abs(got[fin] - exp[fin]).max():.3e}"
 
 
 def both_pools(gpu, oracle, w):
@@ -453,7 +459,7 @@ def run_prefill(gpu, oracle, w, one_shot=False):
     if one_shot:
         for _ in range(2):
             hkv.attn_prefill_with_prefix(dp.handle, r.q, r.cu_q, r.block_table, r.kv_len, w.num_q_heads, r.scale,
-                                         r.out, r.lse)
+                                         r.out, r.lse, r.ws, r.ws_bytes)
     else:
         r.run()
     torch.cuda.synchronize()
@@ -461,8 +467,49 @@ def run_prefill(gpu, oracle, w, one_shot=False):
     r.close()
     dp.close()
     res = check_close(got_o, exp_o, w.name)
-    check_lse(got_l, exp_l, w.name)
+    check_lse(got_l, exp_l, w.name, LSE_ABS_FP8_PREFILL if w.kv_dtype == wl.KV_FP8_E4M3 else LSE_ABS)
     return res
+
+
+@pytest.mark.parametrize("seed", [61, 62, 63, 64])
+def test_prefill_fp8_pool(gpu, oracle, seed):
+    """Suffix-only prefill over an fp8 pool: the pages the batch reads are dequantised into the caller's
+    workspace (code * scale rounded to bf16: one more rounding of K and V than the oracle, which reads the
+    exact dequantised values; the tolerances are the same) and the matrix-core kernel reads those."""
+    import torch
+    from paper_2603_16104_amd import binding as hkv
+    hq, hkv_ = [(8, 2), (8, 1), (4, 4), (4, 2)][seed % 4]
+    w = wl.random_forest_workload(seed, mode="prefill", num_q_heads=hq, num_kv_heads=hkv_, depth=3, fanout=3,
+                                  max_node_pages=12, n_roots=2, kv_dtype=wl.KV_FP8_E4M3)
+    res = run_prefill(gpu, oracle, w, one_shot=(seed % 2 == 0))
+    print(f"fp8 prefill seed {seed}: max_abs {res[0]:.3e} rel_l2 {res[1]:.3e}")
+    if seed == 61:      # a missing or short workspace is refused before anything is queued
+        hp, dp = both_pools(gpu, oracle, w)
+        r = gpu.PrefillRunner(dp, w)
+        assert r.ws_bytes > 0
+        for ws, nbytes, code in ((None, 0, hkv.EINVAL), (r.ws, r.ws_bytes - 1, hkv.ENOMEM)):
+            with pytest.raises(hkv.HkvError) as e:
+                hkv.attn_prefill_plan_run(r.plan, r.q, r.scale, r.out, r.lse, None, ws, nbytes)
+            assert e.value.code == code
+        r.close()
+        dp.close()
+
+
+def test_prefill_fp8_pool_mixed_batch(gpu, oracle):
+    """Requests that prefill 150, 64 and 17 new tokens next to single-token requests over one shared cached
+    prefix, fp8 pool: the shared prefix pages are dequantised once for the whole batch."""
+    s = [150, 1, 64, 1, 1, 17]
+    parent, ntok = [-1] + [0] * len(s), [208] + s
+    n_used = sum((t + 15) // 16 for t in ntok)
+    f = wl.make_forest(parent, ntok, list(range(1, len(s) + 1)), np.random.default_rng(4).permutation(n_used + 3).astype(np.int32))
+    w = wl.Workload(name="mixed_fp8", num_q_heads=8, num_kv_heads=2, kv_dtype=wl.KV_FP8_E4M3, num_pages=n_used + 3, seed=12,
+                    forest=f, mode="prefill", q_len=np.array(s, dtype=np.int32))
+    hp, dp = both_pools(gpu, oracle, w)
+    r = gpu.PrefillRunner(dp, w)
+    assert r.ws_bytes == n_used * 2 * 8192           # every distinct page once
+    r.close()
+    dp.close()
+    run_prefill(gpu, oracle, w)
 
 
 def test_prefill_config1(gpu, oracle):

@@ -403,10 +403,15 @@ def test_prefill_plan_error_codes():
         with pytest.raises(hkv.HkvError) as e:
             hkv.hkv_prefill_plan_create(pool, cu, b, kvl, hq, hkv.PLAN_HOST_ONLY)
         assert e.value.code == code, str(e.value)
+    # fp8 pools: the batch's distinct pages are dequantised into a workspace of 8 KiB per page and KV head
     p8 = fake_pool(16, 2, dtype=hkv.FP8_E4M3)
-    with pytest.raises(hkv.HkvError) as e:
-        hkv.hkv_prefill_plan_create(p8, [0, 8], bt, [40], 4, hkv.PLAN_HOST_ONLY)
-    assert e.value.code == hkv.ESHAPE
+    bt2 = np.array([[1, 2, 3, -1], [1, 2, 7, 9]], dtype=np.int32)          # pages 1 and 2 are shared
+    plan = hkv.hkv_prefill_plan_create(p8, [0, 8, 8 + 20], bt2, [40, 60], 4, hkv.PLAN_HOST_ONLY)
+    assert hkv.hkv_prefill_plan_workspace_bytes(plan) == 5 * 2 * 8192
+    hkv.hkv_prefill_plan_destroy(plan)
+    plan = hkv.hkv_prefill_plan_create(pool, [0, 8], bt, [40], 4, hkv.PLAN_HOST_ONLY)
+    assert hkv.hkv_prefill_plan_workspace_bytes(plan) == 0
+    hkv.hkv_prefill_plan_destroy(plan)
     hkv.kv_pool_destroy(pool)
     hkv.kv_pool_destroy(p8)
 
