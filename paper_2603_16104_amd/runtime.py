@@ -201,6 +201,8 @@ class MixedStepRunner:
             pcu = np.zeros(len(self.pre_req) + 1, dtype=np.int32)
             pcu[1:] = np.cumsum(ql[self.pre_req])
             self.pre_plan = hkv.hkv_prefill_plan_create(pool.handle, pcu, bt, kv_len, Hq)
+            self.pws_bytes = hkv.hkv_prefill_plan_workspace_bytes(self.pre_plan)     # fp8 pools only
+            self.pws = torch.empty(max(self.pws_bytes, 256), dtype=torch.uint8, device=dev) if self.pws_bytes else None
             if not self._pre_contig:
                 self.pq = torch.empty((len(pre_rows), Hq, hkv.HEAD_DIM), dtype=torch.int16, device=dev)
                 self.pout = torch.empty_like(self.pq)
@@ -220,10 +222,12 @@ class MixedStepRunner:
         if self.pre_plan is not None:
             if self._pre_contig:
                 a, b = self._pre_a, self._pre_a + len(self.pre_rows)
-                hkv.attn_prefill_plan_run(self.pre_plan, self.q[a:b], self.scale, self.out[a:b], self.lse[a:b], stream)
+                hkv.attn_prefill_plan_run(self.pre_plan, self.q[a:b], self.scale, self.out[a:b], self.lse[a:b], stream,
+                                          self.pws, self.pws_bytes)
             else:
                 torch.index_select(self.q, 0, self.pre_rows, out=self.pq)
-                hkv.attn_prefill_plan_run(self.pre_plan, self.pq, self.scale, self.pout, self.plse, stream)
+                hkv.attn_prefill_plan_run(self.pre_plan, self.pq, self.scale, self.pout, self.plse, stream, self.pws,
+                                          self.pws_bytes)
                 self.out.index_copy_(0, self.pre_rows, self.pout)
                 self.lse.index_copy_(0, self.pre_rows, self.plse)
 

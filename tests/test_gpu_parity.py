@@ -547,8 +547,9 @@ def test_prefill_mixed_with_single_token_requests(gpu, oracle):
     run_prefill(gpu, oracle, w)
 
 
+@pytest.mark.parametrize("kv_dtype", [wl.KV_BF16, wl.KV_FP8_E4M3])
 @pytest.mark.parametrize("order", ["interleaved", "decode_first"])
-def test_mixed_step_tree_decode_plus_prefill(gpu, oracle, order):
+def test_mixed_step_tree_decode_plus_prefill(gpu, oracle, order, kv_dtype):
     """The same kind of batch split by the runner: single-token requests through the prefix-tree decode
     plan (shared nodes read once), the others through suffix-only prefill, one output; against the
     oracle, with the two groups interleaved (gather / scatter of rows) and contiguous."""
@@ -557,7 +558,7 @@ def test_mixed_step_tree_decode_plus_prefill(gpu, oracle, order):
     parent, ntok = [-1, 0, 0] + [1, 1, 2, 1, 2, 2, 1][:len(s)], [208, 48, 80] + s
     n_used = sum((t + 15) // 16 for t in ntok)
     f = wl.make_forest(parent, ntok, list(range(3, 3 + len(s))), np.random.default_rng(6).permutation(n_used + 3).astype(np.int32))
-    w = wl.Workload(name="mixed_step_" + order, num_q_heads=8, num_kv_heads=2, kv_dtype=wl.KV_BF16, num_pages=n_used + 3, seed=13,
+    w = wl.Workload(name="mixed_step_" + order, num_q_heads=8, num_kv_heads=2, kv_dtype=kv_dtype, num_pages=n_used + 3, seed=13,
                     forest=f, mode="prefill", q_len=np.array(s, dtype=np.int32))
     hp, dp = both_pools(gpu, oracle, w)
     exp_o, exp_l = oracle.run_workload(w, hp)
@@ -568,7 +569,7 @@ def test_mixed_step_tree_decode_plus_prefill(gpu, oracle, order):
         r.run()
     torch.cuda.synchronize()
     check_close(gpu.bf16_tensor_to_f64(r.out), exp_o, w.name)
-    check_lse(r.lse.cpu().numpy(), exp_l, w.name)
+    check_lse(r.lse.cpu().numpy(), exp_l, w.name, LSE_ABS_FP8_PREFILL if kv_dtype == wl.KV_FP8_E4M3 else LSE_ABS)
     r.close()
     dp.close()
 
