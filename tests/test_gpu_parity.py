@@ -636,6 +636,57 @@ def test_prefill_late_dominant_key(gpu, oracle, beta):
     assert np.abs(got_o[hot:, 0] - vb[hot, 0]).max() <= 2e-2
 
 
+@pytest.mark.parametrize("kv_dtype", [wl.KV_BF16, wl.KV_FP8_E4M3])
+@pytest.mark.parametrize("case", ["zero_query", "huge_scores", "early_dominant_key"])
+def test_decode_closed_forms_on_the_gpu(gpu, oracle, kv_dtype, case):
+    """Degenerate inputs with known answers, through the tree decode (a 96-token shared root and three
+    ragged leaves): a zero query gives the plain mean of the visible V rows and lse = ln(kv_len); queries
+    scaled until the scores reach a few hundred give (almost) one-hot attention without overflow; a
+    dominant key in the root must keep dominating through the merge with the leaves' partials."""
+    rng = np.random.default_rng(33)
+    leaves = [40, 7, 130]
+    f = wl.make_forest([-1, 0, 0, 0], [96] + leaves, [1, 2, 3, 0], np.random.default_rng(3).permutation(30).astype(np.int32))
+    base = wl.Workload(name=f"closed_{case}", num_q_heads=8, num_kv_heads=2, kv_dtype=kv_dtype, num_pages=30, seed=2,
+                       forest=f, mode="decode")
+    kv = {}
+    for node, n in enumerate([96] + leaves):
+        k = rng.standard_normal((n, 2, 128)).astype(np.float32)
+        v = rng.standard_normal((n, 2, 128)).astype(np.float32)
+        kv[node] = [k, v]
+    q = rng.standard_normal((4, 8, 128)).astype(np.float32)
+    if case == "zero_query":
+        q[:] = 0.0
+    elif case == "huge_scores":
+        q *= 30.0                                           # scores of +-300 and more
+    else:
+        u = rng.standard_normal(128).astype(np.float32)
+        u *= np.sqrt(128.0) / np.linalg.norm(u)
+        kv[0][0] *= 0.05
+        for node in (1, 2, 3):
+            kv[node][0] *= 0.05
+        kv[0][0][17] = 6.0 * u                              # 68 nats above everything else
+        q = np.broadcast_to(u, (4, 8, 128)).astype(np.float32) + 0.05 * q
+    w = _FixedWorkload(base, {n: (wl.f32_to_bf16_bits(k), wl.f32_to_bf16_bits(v)) for n, (k, v) in kv.items()},
+                       wl.f32_to_bf16_bits(q))
+    hp, dp = both_pools(gpu, oracle, w)
+    exp_o, exp_l = oracle.run_workload(w, hp)
+    import torch
+    r = gpu.DecodeRunner(dp, w)
+    r.run()
+    torch.cuda.synchronize()
+    got_o, got_l = gpu.bf16_tensor_to_f64(r.out), r.lse.cpu().numpy()
+    r.close()
+    dp.close()
+    check_close(got_o, exp_o, w.name)
+    assert np.abs(got_l - exp_l).max() <= 2e-3 + 1e-6 * np.abs(exp_l).max()
+    if case == "zero_query":
+        lens = np.array([96 + 40, 96 + 7, 96 + 130, 96], dtype=np.float64)
+        assert np.abs(got_l - np.log(lens)[:, None]).max() <= 1e-4
+    if case == "early_dominant_key" and kv_dtype == wl.KV_BF16:
+        vb = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(kv[0][1]))
+        assert np.abs(got_o[:, 0] - vb[17, 0]).max() <= 2e-2
+
+
 @pytest.mark.gpu
 def test_diagnostic_probes(gpu):
     """The ceiling probes run and report figures of the right order (no attention result involved)."""
