@@ -64,7 +64,23 @@ def bench_decode(runtime, hkv, w, steps: int, warmup: int, n_pools: int, profile
     import torch
     pools = make_pools(runtime, w, n_pools)
     runners = [runtime.DecodeRunner(p, w) for p in pools]
+    f = w.forest
+    t0 = time.perf_counter()                                    # tree walk, work list, upload: once per topology
+    for _ in range(5):
+        hkv.hkv_decode_plan_destroy(hkv.hkv_decode_plan_create(pools[0].handle, f.nodes, f.node_pages, f.req_leaf, w.num_q_heads))
+    plan_ms = (time.perf_counter() - t0) / 5 * 1e3
     sec = time_steps(lambda i: runners[i % n_pools].run(), steps, warmup)
+    # spread of the step time: batches of 8 steps between two events each (an event per step would add its own cost)
+    batch_ms = []
+    for bidx in range(25):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(8):
+            runners[(bidx * 8 + i) % n_pools].run()
+        e1.record()
+        e1.synchronize()
+        batch_ms.append(e0.elapsed_time(e1) / 8)
+    batch_ms.sort()
     # same steps again with a begin and an end HIP event attached to each kernel dispatch (on the launch
     # stream): the kernels' own durations, as a kernel trace reports them
     node_ms = merge_ms = 0.0
@@ -109,6 +125,8 @@ def bench_decode(runtime, hkv, w, steps: int, warmup: int, n_pools: int, profile
     del runners, pools
     torch.cuda.empty_cache()
     info["node_kernel_batch_ms"] = round(node_batch_ms, 5)
+    info["ms_per_step_p10_p50_p90"] = [round(batch_ms[int(q * (len(batch_ms) - 1))], 5) for q in (0.1, 0.5, 0.9)]
+    info["host_planning_ms_once_per_topology"] = round(plan_ms, 3)
     if node_each:
         srt = sorted(node_each)
         info["node_kernel_ms_p10_p50_p90"] = [round(srt[int(q * (len(srt) - 1))], 5) for q in (0.1, 0.5, 0.9)]
