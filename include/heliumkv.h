@@ -29,12 +29,18 @@
  *     on the pool it was created over, must be serialised by the caller.  A plan's workspace and
  *     device index buffers belong to one run at a time: queue runs of one plan on one stream, or
  *     order them with events.
- *   - Fixed geometry: page size 16 tokens, head dimension 128.  Anything else is HKV_ESHAPE.
+ *   - Geometry: head dimension 128; page size 16 tokens, or 32, 64 or 128 (a page of 16*S tokens
+ *     is S consecutive 16-token blocks, see below).  Anything else is HKV_ESHAPE.  Where the text
+ *     below says "16" about pages of a forest, a block table or a write, read the pool's page
+ *     size; the storage format and the fp8 scales are always per 16-token block.
  *   - Grouped-query attention: query head h reads KV head h / (num_q_heads / num_kv_heads).
  *
  * Pool storage format (device memory owned by the caller, layout fixed by this library).
- *   For page p and KV head h, the K block and the V block each hold 16*128 elements and start
- *   at element (p*num_kv_heads + h)*2048 of k_pages / v_pages.
+ *   Storage is an array of 16-token blocks.  With page size 16 block b is page b; with page size
+ *   16*S page p is the blocks p*S .. p*S + S - 1, block p*S + j holding slots 16j .. 16j + 15 of
+ *   the page (so a page is one contiguous range of the buffers, S times the 16-token size).
+ *   For block b and KV head h, the K block and the V block each hold 16*128 elements and start
+ *   at element (b*num_kv_heads + h)*2048 of k_pages / v_pages.
  *     K block: the 128 dimensions are cut into chunks of 64 bytes (C = 64/sizeof(element)
  *              dimensions: 32 for bf16, 64 for fp8, 16 for fp32); element (slot t, dim d) is at
  *              (d / C)*16*C + t*C + d % C.
@@ -42,7 +48,8 @@
  *   Both orders hand a 64-lane wavefront its matrix-core operands as 16-byte contiguous loads
  *   and make every (page, head) block one contiguous 4 KiB (bf16) / 2 KiB (fp8) burst.
  *   fp8 pools (OCP e4m3, no infinities, max 448) carry k_scale and v_scale, float
- *   [num_pages][num_kv_heads]; the stored value is code * scale.
+ *   [num_pages * S][num_kv_heads] (one scale per 16-token block and head); the stored value is
+ *   code * scale.
  *   Slots past the end of a sequence and unreferenced pages may hold anything, NaN included.
  */
 #ifndef HELIUMKV_H
@@ -93,13 +100,13 @@ const char *hkv_last_error(void);
  */
 typedef struct {
     int32_t num_pages;
-    int32_t page_size;    /* must be 16 */
+    int32_t page_size;    /* 16, 32, 64 or 128 tokens */
     int32_t num_kv_heads;
     int32_t head_dim;     /* must be 128 */
     int32_t dtype;        /* HKV_BF16 or HKV_FP8_E4M3 */
-    void *k_pages;        /* device, num_pages*num_kv_heads*2048 elements, format above */
+    void *k_pages;        /* device, num_pages*(page_size/16)*num_kv_heads*2048 elements, format above */
     void *v_pages;        /* device, same size */
-    float *k_scale;       /* device, [num_pages][num_kv_heads]; fp8 pools only, else NULL */
+    float *k_scale;       /* device, [num_pages*(page_size/16)][num_kv_heads]; fp8 pools only, else NULL */
     float *v_scale;       /* device, same */
     const int32_t *free_order; /* host, optional permutation of 0..num_pages-1: the order in
                                   which kv_pool_alloc hands pages out; NULL = ascending */
@@ -107,7 +114,7 @@ typedef struct {
 
 /* Creates the host-side pool object.  Borrows the device pointers; copies free_order.
  * EINVAL: null desc/out or buffers, num_pages <= 0, free_order not a permutation.
- * ESHAPE: page_size != 16, head_dim != 128, dtype not storable, scales missing for fp8. */
+ * ESHAPE: page_size not 16/32/64/128, head_dim != 128, dtype not storable, scales missing for fp8. */
 int kv_pool_create(const hkv_pool_desc *desc, hkv_pool **out);
 
 /* Frees host metadata and any cached plan.  Waits for the device to be idle first if a cached
@@ -142,22 +149,27 @@ int kv_pool_copy_on_write(hkv_pool *pool, int32_t n, int32_t *ids /* host, in/ou
 /* Number of free pages, or a negative error code. */
 int32_t kv_pool_num_free(const hkv_pool *pool);
 
+/* Tokens per page of the pool (16, 32, 64 or 128), or a negative error code. */
+int32_t kv_pool_page_size(const hkv_pool *pool);
+
 /* Reference count of one page (0 = free), or a negative error code. */
 int32_t kv_pool_refcount(const hkv_pool *pool, int32_t page_id);
 
 /* Stores the K/V of n_tokens consecutive tokens of one sequence into the pool: token i goes to
- * page page_ids[(first_slot + i) / 16], slot (first_slot + i) % 16.  This is the "compute the
- * prefix KV once and keep it" step seen from the pool.
- *   page_ids: host, ceil((first_slot + n_tokens)/16) entries (at most 65536).
+ * page page_ids[(first_slot + i) / P], slot (first_slot + i) % P, P the pool's page size
+ * (first_slot < P).  This is the "compute the prefix KV once and keep it" step seen from the pool.
+ *   page_ids: host, ceil((first_slot + n_tokens)/P) entries; one call touches at most 65536
+ *   16-token blocks.
  *   k_src, v_src: device, [n_tokens][num_kv_heads][128] bf16.
- * bf16 pools: plain scatter into the block format.  fp8 pools: a (page, head) block written from
- * slot 0 gets scale = amax/448 over the tokens written into it by this call (1 if amax == 0) and
- * code = round-to-nearest-even(x / scale), saturated to +-448, all in float.  A block that is
- * continued (the first page of a call with first_slot > 0, e.g. decode appending a token) keeps
- * a running scale: scale' = max(scale, amax_new/448); if the scale grows, the codes already in
- * the slots below first_slot are re-encoded as RNE(value(code) * scale / scale') (a second
- * rounding of those tokens); the scale never shrinks.  Slots [0, first_slot) of such a page must
- * have been written before.  Slots not written keep their contents.  n_tokens == 0 is a no-op.
+ * bf16 pools: plain scatter into the block format.  fp8 pools: a (16-token block, head) block
+ * written from its slot 0 gets scale = amax/448 over the tokens written into it by this call (1
+ * if amax == 0) and code = round-to-nearest-even(x / scale), saturated to +-448, all in float.
+ * A block that is continued (the first block of a call with first_slot % 16 > 0, e.g. decode
+ * appending a token) keeps a running scale: scale' = max(scale, amax_new/448); if the scale
+ * grows, the codes already in the block's slots below first_slot % 16 are re-encoded as
+ * RNE(value(code) * scale / scale') (a second rounding of those tokens); the scale never
+ * shrinks.  Those slots of such a block must have been written before.  Slots not written keep
+ * their contents.  n_tokens == 0 is a no-op.
  * EINVAL / ERANGE / ESHAPE as above; the ids are checked before anything is queued. */
 int kv_pool_write(hkv_pool *pool, const int32_t *page_ids, int32_t first_slot, int32_t n_tokens,
                   const void *k_src, const void *v_src, void *stream);
@@ -183,11 +195,17 @@ typedef struct {
  *                                       ascending request index
  *   node_tok_start  [n_nodes]           token offset of the node's segment within such a path
  * Any output pointer may be NULL to skip it.  All pointers are host memory.
- * ETREE / ERANGE as documented on the codes; ENOMEM if a path needs more than max_pages. */
+ * ETREE / ERANGE as documented on the codes; ENOMEM if a path needs more than max_pages.
+ * prefix_tree_flatten is the 16-token-page case of prefix_tree_flatten_paged, which takes the page
+ * size of the forest (16, 32, 64 or 128; else ESHAPE). */
 int prefix_tree_flatten(const hkv_node *nodes, int32_t n_nodes, const int32_t *node_pages,
                         int32_t n_node_pages, const int32_t *req_leaf, int32_t n_req, int32_t max_pages,
                         int32_t *block_table, int32_t *kv_len, int32_t *node_req_indptr,
                         int32_t *node_req_idx, int32_t *node_tok_start);
+int prefix_tree_flatten_paged(const hkv_node *nodes, int32_t n_nodes, const int32_t *node_pages,
+                              int32_t n_node_pages, const int32_t *req_leaf, int32_t n_req, int32_t page_size,
+                              int32_t max_pages, int32_t *block_table, int32_t *kv_len, int32_t *node_req_indptr,
+                              int32_t *node_req_idx, int32_t *node_tok_start);
 
 /* Prefill token usage u_p of Section 5 for a sequence of calls on one worker: calls[0]
  * processes every token on path(root, calls[0]); calls[j] only the tokens on the path from the
@@ -268,7 +286,8 @@ int hkv_decode_plan_destroy(hkv_decode_plan *plan);
 size_t hkv_decode_plan_workspace_bytes(const hkv_decode_plan *plan);
 /* Introspection for tests and tools (host copies).  Work item layout, 8 int32 each:
  * (page_off, n_tokens, kv_head, req_off, n_req, part_slot, tok_begin, node).  page_off indexes
- * the plan's page list (= node_pages), req_off the node->request CSR values that
+ * the plan's list of 16-token blocks (= node_pages when the page size is 16; else every page p
+ * of a node expanded to the blocks p*S + j it uses), req_off the node->request CSR values that
  * prefix_tree_flatten returns.  An item applies the tokens [tok_begin, tok_begin + n_tokens) of
  * `node` to n_req requests x (num_q_heads / num_kv_heads) heads of kv_head; row (request r, head
  * h) of the item writes partial (r*num_q_heads + h)*max_parts + part_slot. */

@@ -9,8 +9,8 @@ and never a prefix before its extensions (the longest match goes first); an evic
 recomputed by the next call that needs it.
 
 Readings where the paper is silent (the library takes the same ones)
-  C1  A block is 16 consecutive tokens; its identity is (identity of the preceding block, its 16
-      token ids): two sequences share a block exactly when they agree on everything up to its end.
+  C1  A block is one page of consecutive tokens (16, or the pool's page size); its identity is
+      (identity of the preceding block, its token ids): two sequences share a block exactly when they agree on everything up to its end.
       Only full blocks are shared; a sequence's last, partial block is private to it.
   C2  acquire(tokens): walk the full blocks from the front while they are cached (hits), then give
       every remaining block a page: from the pool's free list (lowest id first, as kv_pool_alloc
@@ -39,7 +39,8 @@ class _Block:
 
 
 class PrefixCache:
-    def __init__(self, num_pages: int, free_order: Optional[Sequence[int]] = None):
+    def __init__(self, num_pages: int, free_order: Optional[Sequence[int]] = None, block: int = BLOCK):
+        self.block = block                       # tokens per cached block = the pool's page size
         self.free: List[int] = list(free_order) if free_order is not None else list(range(num_pages))
         self.root = _Block(None, (), -1)
         self.by_page: Dict[int, _Block] = {}     # cached full blocks
@@ -70,15 +71,15 @@ class PrefixCache:
 
     # ---- interface
     def acquire(self, tokens: Sequence[int], pin: bool = False) -> Tuple[List[int], int]:
-        """Returns (page ids of all ceil(n/16) blocks, number of cached tokens at the front)."""
+        """Returns (page ids of all ceil(n/block) blocks, number of cached tokens at the front)."""
         self.clock += 1
         n = len(tokens)
-        n_full = n // BLOCK
+        n_full = n // self.block
         pages: List[int] = []
         node, j = self.root, 0
         taken: List[_Block] = []
         while j < n_full:                                   # hits
-            key = tuple(int(t) for t in tokens[j * BLOCK:(j + 1) * BLOCK])
+            key = tuple(int(t) for t in tokens[j * self.block:(j + 1) * self.block])
             nxt = node.children.get(key)
             if nxt is None:
                 break
@@ -88,10 +89,10 @@ class PrefixCache:
             pages.append(nxt.page)
             node, j = nxt, j + 1
             self.hits += 1
-        cached = j * BLOCK
+        cached = j * self.block
         try:
             while j < n_full:                               # misses: new full blocks
-                key = tuple(int(t) for t in tokens[j * BLOCK:(j + 1) * BLOCK])
+                key = tuple(int(t) for t in tokens[j * self.block:(j + 1) * self.block])
                 b = _Block(node, key, self._page())
                 b.ref, b.last_use = 1, self.clock
                 node.children[key] = b
@@ -100,7 +101,7 @@ class PrefixCache:
                 pages.append(b.page)
                 node, j = b, j + 1
                 self.misses += 1
-            if n % BLOCK:                                   # private partial block
+            if n % self.block:                                   # private partial block
                 p = self._page()
                 self.private[p] = 1
                 pages.append(p)

@@ -23,13 +23,15 @@
  * operation itself, kept separate).
  *
  * Pool layout (the documented storage format of the library, indexed here by
- * this file's own code).  A page holds 16 token slots.  For page p and KV
- * head h, the K block and the V block each hold 16*128 elements and start at
- * element (p*Hkv + h)*2048.  Inside a K block the 128 dimensions are cut into
+ * this file's own code).  Storage is an array of blocks of 16 token slots; a
+ * page of P = 16*S tokens (S = 1, 2, 4, 8) is the blocks p*S .. p*S + S - 1,
+ * slot s of the page being slot s % 16 of block b = p*S + s / 16.  For block b
+ * and KV head h, the K block and the V block each hold 16*128 elements and
+ * start at element (b*Hkv + h)*2048.  Inside a K block the 128 dimensions are cut into
  * chunks of 64 bytes (C = 64/sizeof(element) dimensions); element (slot t,
  * dim d) sits at (d / C)*16*C + t*C + d % C.  Inside a V block the layout is
  * dimension-major: element (t, d) sits at d*16 + t.  fp8 pools carry two
- * float arrays k_scale[p*Hkv + h], v_scale[p*Hkv + h]; the stored value is
+ * float arrays k_scale[b*Hkv + h], v_scale[b*Hkv + h]; the stored value is
  * code * scale.
  *
  * Every function is pinned by tests/test_oracle_*.py against brute force,
@@ -44,7 +46,7 @@
 #include <omp.h>
 #endif
 
-#define ORC_PAGE 16
+#define ORC_BLOCK 16 /* token slots per storage block */
 #define ORC_D 128
 
 enum { ORC_BF16 = 0, ORC_FP8_E4M3 = 1, ORC_FP32 = 2 };
@@ -53,6 +55,7 @@ typedef struct {
     int32_t num_pages;
     int32_t num_kv_heads;
     int32_t dtype;
+    int32_t page_size; /* tokens per page: 16, 32, 64 or 128 */
     const void *k_pages;
     const void *v_pages;
     const float *k_scale; /* fp8 only */
@@ -110,31 +113,38 @@ uint8_t orc_e4m3_encode(float y) {
 
 static size_t elem_size(int dtype) { return dtype == ORC_BF16 ? 2 : dtype == ORC_FP8_E4M3 ? 1 : 4; }
 
+/* storage block that holds slot `slot` (0 .. page_size - 1) of page `page` */
+static size_t block_of(const orc_pool *p, int page, int slot) {
+    return (size_t)page * (size_t)(p->page_size / ORC_BLOCK) + (size_t)(slot / ORC_BLOCK);
+}
+
 static size_t k_offset(const orc_pool *p, int page, int head, int slot, int d) {
     size_t C = 64 / elem_size(p->dtype);
-    size_t block = ((size_t)page * p->num_kv_heads + head) * (ORC_PAGE * ORC_D);
-    return block + (size_t)(d / C) * ORC_PAGE * C + (size_t)slot * C + (size_t)(d % C);
+    size_t block = (block_of(p, page, slot) * p->num_kv_heads + head) * (ORC_BLOCK * ORC_D);
+    return block + (size_t)(d / C) * ORC_BLOCK * C + (size_t)(slot % ORC_BLOCK) * C + (size_t)(d % C);
 }
 
 static size_t v_offset(const orc_pool *p, int page, int head, int slot, int d) {
-    size_t block = ((size_t)page * p->num_kv_heads + head) * (ORC_PAGE * ORC_D);
-    return block + (size_t)d * ORC_PAGE + (size_t)slot;
+    size_t block = (block_of(p, page, slot) * p->num_kv_heads + head) * (ORC_BLOCK * ORC_D);
+    return block + (size_t)d * ORC_BLOCK + (size_t)(slot % ORC_BLOCK);
 }
 
-static double load_elem(const orc_pool *p, const void *base, const float *scale, size_t off, int page, int head) {
+static double load_elem(const orc_pool *p, const void *base, const float *scale, size_t off, int page, int slot,
+                        int head) {
     switch (p->dtype) {
     case ORC_BF16: return bf16_to_double(((const uint16_t *)base)[off]);
     case ORC_FP8_E4M3:
-        return orc_e4m3_value(((const uint8_t *)base)[off]) * (double)scale[(size_t)page * p->num_kv_heads + head];
+        return orc_e4m3_value(((const uint8_t *)base)[off]) *
+               (double)scale[block_of(p, page, slot) * p->num_kv_heads + head];
     default: return (double)((const float *)base)[off];
     }
 }
 
 static double load_k(const orc_pool *p, int page, int head, int slot, int d) {
-    return load_elem(p, p->k_pages, p->k_scale, k_offset(p, page, head, slot, d), page, head);
+    return load_elem(p, p->k_pages, p->k_scale, k_offset(p, page, head, slot, d), page, slot, head);
 }
 static double load_v(const orc_pool *p, int page, int head, int slot, int d) {
-    return load_elem(p, p->v_pages, p->v_scale, v_offset(p, page, head, slot, d), page, head);
+    return load_elem(p, p->v_pages, p->v_scale, v_offset(p, page, head, slot, d), page, slot, head);
 }
 
 static double load_q(const void *q, int q_dtype, size_t idx) {
@@ -146,22 +156,23 @@ static double load_q(const void *q, int q_dtype, size_t idx) {
 /* nodes: [n_nodes][4] = (parent, page_begin, n_pages, n_tokens), parents before children.
  * Section 5 defines path(r, l) as the nodes from the root down to the leaf; a call's
  * prompt is the concatenation of their token segments.  Returns 0, or a negative code:
- * -1 bad argument, -2 index out of range, -4 malformed tree, -5 max_pages too small. */
+ * -1 bad argument, -2 index out of range, -4 malformed tree, -5 max_pages too small.
+ * page_size: tokens per page of the forest (a node of n tokens holds ceil(n / page_size) pages). */
 int oracle_flatten_tree(const int32_t *nodes, int32_t n_nodes, const int32_t *node_pages, int32_t n_node_pages,
-                        const int32_t *req_leaf, int32_t n_req, int32_t max_pages, int32_t *block_table,
-                        int32_t *kv_len, int32_t *node_req_indptr, int32_t *node_req_idx,
+                        const int32_t *req_leaf, int32_t n_req, int32_t page_size, int32_t max_pages,
+                        int32_t *block_table, int32_t *kv_len, int32_t *node_req_indptr, int32_t *node_req_idx,
                         int32_t *node_tok_start) {
-    if (n_nodes < 0 || n_req < 0 || max_pages < 0) return -1;
+    if (n_nodes < 0 || n_req < 0 || max_pages < 0 || page_size <= 0) return -1;
     int *has_child = (int *)calloc((size_t)n_nodes + 1, sizeof(int));
     for (int v = 0; v < n_nodes; ++v) {
         int par = nodes[4 * v], pb = nodes[4 * v + 1], np = nodes[4 * v + 2], nt = nodes[4 * v + 3];
         if (par < -1 || par >= v) { free(has_child); return -4; }
-        if (nt < 0 || np != (nt + ORC_PAGE - 1) / ORC_PAGE) { free(has_child); return -4; }
+        if (nt < 0 || np != (nt + page_size - 1) / page_size) { free(has_child); return -4; }
         if (pb < 0 || pb + np > n_node_pages) { free(has_child); return -2; }
         if (par >= 0) has_child[par] = 1;
     }
     for (int v = 0; v < n_nodes; ++v)
-        if (has_child[v] && nodes[4 * v + 3] % ORC_PAGE != 0) { free(has_child); return -4; }
+        if (has_child[v] && nodes[4 * v + 3] % page_size != 0) { free(has_child); return -4; }
     free(has_child);
 
     /* token offset at which each node's segment starts along its root path */
@@ -240,26 +251,26 @@ static float src_as_float(const void *src, int src_dtype, size_t i) {
 }
 
 /* Store n_tokens consecutive tokens ([n_tokens][Hkv][128], bf16 bits or float) into the pages
- * page_ids[0..], starting at slot first_slot of page_ids[0].  This is the "precompute and keep
+ * page_ids[0..], starting at slot first_slot (< page size) of page_ids[0].  This is the "precompute and keep
  * the KV cache" step of Section 5 seen from the pool.  bf16/fp32 pools: plain copy.  fp8 pools:
- * a (page, head) block written from slot 0 gets scale = amax/448 over the tokens written into it
+ * a (16-slot block, head) block written from its slot 0 gets scale = amax/448 over the tokens written into it
  * (1 if amax is 0), computed in float, and code = RNE(x / scale) with the division in float.
- * A block that is continued (first page of a call with first_slot > 0) keeps a running scale:
+ * A block that is continued (first block of a call, first_slot % 16 > 0) keeps a running scale:
  * scale' = max(scale, amax_new/448); when the scale grows, the codes already in slots below
- * first_slot are re-encoded as RNE(value(code) * scale / scale'), product and quotient in float;
+ * first_slot % 16 are re-encoded as RNE(value(code) * scale / scale'), product and quotient in float;
  * the scale never shrinks.  Returns 0 or a negative code as in oracle_flatten_tree. */
 int oracle_kv_write(orc_pool *p, void *k_pages, void *v_pages, float *k_scale, float *v_scale,
                     const int32_t *page_ids, int32_t first_slot, int32_t n_tokens, const void *k_src,
                     const void *v_src, int32_t src_dtype) {
-    int H = p->num_kv_heads;
-    if (n_tokens < 0 || first_slot < 0 || first_slot >= ORC_PAGE) return -1;
+    int H = p->num_kv_heads, P = p->page_size;
+    if (n_tokens < 0 || first_slot < 0 || first_slot >= P) return -1;
     if (p->dtype == ORC_BF16 && src_dtype != ORC_BF16) return -1;
-    int n_pg = (first_slot + n_tokens + ORC_PAGE - 1) / ORC_PAGE;
+    int n_pg = (first_slot + n_tokens + P - 1) / P;
     for (int i = 0; i < n_pg; ++i)
         if (page_ids[i] < 0 || page_ids[i] >= p->num_pages) return -2;
     if (p->dtype != ORC_FP8_E4M3) {
         for (int t = 0; t < n_tokens; ++t) {
-            int page = page_ids[(first_slot + t) / ORC_PAGE], slot = (first_slot + t) % ORC_PAGE;
+            int page = page_ids[(first_slot + t) / P], slot = (first_slot + t) % P;
             for (int h = 0; h < H; ++h)
                 for (int d = 0; d < ORC_D; ++d) {
                     size_t s = ((size_t)t * H + h) * ORC_D + d;
@@ -269,11 +280,17 @@ int oracle_kv_write(orc_pool *p, void *k_pages, void *v_pages, float *k_scale, f
         }
         return 0;
     }
-    for (int i = 0; i < n_pg; ++i) {
-        int page = page_ids[i];
-        int s_lo = i == 0 ? first_slot : 0;                       /* first slot written in this page */
-        int t0 = i == 0 ? 0 : i * ORC_PAGE - first_slot;           /* token that lands in slot s_lo */
-        int t1 = (i + 1) * ORC_PAGE - first_slot < n_tokens ? (i + 1) * ORC_PAGE - first_slot : n_tokens;
+    /* fp8: one scale per storage block of 16 slots; walk the blocks the tokens land in */
+    int g0 = first_slot / ORC_BLOCK;      /* first block touched, counted along the listed pages */
+    int fs = first_slot % ORC_BLOCK;      /* first slot written in it */
+    int n_blk = (fs + n_tokens + ORC_BLOCK - 1) / ORC_BLOCK;
+    for (int i = 0; i < n_blk; ++i) {
+        int at = (g0 + i) * ORC_BLOCK;                              /* slot along the listed pages */
+        int page = page_ids[at / P], base = at % P;                 /* the block's first slot in its page */
+        size_t blk = block_of(p, page, base);
+        int s_lo = i == 0 ? fs : 0;                                /* first slot written in this block */
+        int t0 = i == 0 ? 0 : i * ORC_BLOCK - fs;                  /* token that lands in slot s_lo */
+        int t1 = (i + 1) * ORC_BLOCK - fs < n_tokens ? (i + 1) * ORC_BLOCK - fs : n_tokens;
         for (int h = 0; h < H; ++h)
             for (int which = 0; which < 2; ++which) {
                 const void *src = which ? v_src : k_src;
@@ -289,24 +306,25 @@ int oracle_kv_write(orc_pool *p, void *k_pages, void *v_pages, float *k_scale, f
                 if (s_lo == 0) {
                     scale = amax > 0.0f ? amax / 448.0f : 1.0f;
                 } else {
-                    float old = scales[(size_t)page * H + h];
+                    float old = scales[blk * H + h];
                     float cand = amax > 0.0f ? amax / 448.0f : 0.0f;
                     scale = old >= cand ? old : cand;   /* an unset (NaN) old scale gives cand */
                     if (!(scale > 0.0f)) scale = 1.0f;
                     if (scale > old)
                         for (int sl = 0; sl < s_lo; ++sl)
                             for (int d = 0; d < ORC_D; ++d) {
-                                size_t off = which ? v_offset(p, page, h, sl, d) : k_offset(p, page, h, sl, d);
+                                size_t off = which ? v_offset(p, page, h, base + sl, d) : k_offset(p, page, h, base + sl, d);
                                 float v = (float)orc_e4m3_value(codes[off]) * old;
                                 codes[off] = orc_e4m3_encode(v / scale);
                             }
                 }
-                scales[(size_t)page * H + h] = scale;
+                scales[blk * H + h] = scale;
                 for (int t = t0; t < t1; ++t)
                     for (int d = 0; d < ORC_D; ++d) {
                         float x = src_as_float(src, src_dtype, ((size_t)t * H + h) * ORC_D + d);
                         float y = x / scale;
-                        size_t off = which ? v_offset(p, page, h, s_lo + (t - t0), d) : k_offset(p, page, h, s_lo + (t - t0), d);
+                        int sl = base + s_lo + (t - t0);
+                        size_t off = which ? v_offset(p, page, h, sl, d) : k_offset(p, page, h, sl, d);
                         codes[off] = orc_e4m3_encode(y);
                     }
             }
@@ -331,7 +349,7 @@ static void attend_range(const orc_pool *p, const int32_t *pages, int kv_head, c
     double *s = (double *)malloc(sizeof(double) * (size_t)n);
     double m = -INFINITY;
     for (int t = t0; t < t1; ++t) {
-        int page = pages[t / ORC_PAGE], slot = t % ORC_PAGE;
+        int page = pages[t / p->page_size], slot = t % p->page_size;
         double acc = 0.0;
         for (int d = 0; d < ORC_D; ++d) acc += qv[d] * load_k(p, page, kv_head, slot, d);
         s[t - t0] = scale * acc;
@@ -343,7 +361,7 @@ static void attend_range(const orc_pool *p, const int32_t *pages, int kv_head, c
         l += s[i];
     }
     for (int t = t0; t < t1; ++t) {
-        int page = pages[t / ORC_PAGE], slot = t % ORC_PAGE;
+        int page = pages[t / p->page_size], slot = t % p->page_size;
         double w = s[t - t0];
         for (int d = 0; d < ORC_D; ++d) o[d] += w * load_v(p, page, kv_head, slot, d);
     }
@@ -355,7 +373,7 @@ static void attend_range(const orc_pool *p, const int32_t *pages, int kv_head, c
 }
 
 static int check_pages(const orc_pool *p, const int32_t *pages, int kv_len) {
-    int n = (kv_len + ORC_PAGE - 1) / ORC_PAGE;
+    int n = (kv_len + p->page_size - 1) / p->page_size;
     for (int i = 0; i < n; ++i)
         if (pages[i] < 0 || pages[i] >= p->num_pages) return -2;
     return 0;
@@ -372,7 +390,7 @@ int oracle_attn_decode(const orc_pool *p, const void *q, int32_t q_dtype, const 
     if (num_q_heads <= 0 || num_q_heads % p->num_kv_heads) return -3;
     int G = num_q_heads / p->num_kv_heads;
     for (int r = 0; r < n_req; ++r) {
-        if (kv_len[r] < 0 || kv_len[r] > max_pages * ORC_PAGE) return -1;
+        if (kv_len[r] < 0 || kv_len[r] > max_pages * p->page_size) return -1;
         int rc = check_pages(p, block_table + (size_t)r * max_pages, kv_len[r]);
         if (rc) return rc;
     }
@@ -392,8 +410,8 @@ int oracle_attn_decode(const orc_pool *p, const void *q, int32_t q_dtype, const 
 /* The same attention taken straight from the forest (Section 5, templated radix tree: a call's
  * prompt is the concatenation of the token segments on the path from the root to its leaf), for
  * forests whose nodes may end inside a page anywhere: request r's sequence is, node by node from
- * the root down to req_leaf[r], token t of node v = slot t % 16 of page node_pages[page_begin_v +
- * t / 16].  nodes: [n_nodes][4] = parent, page_begin, n_pages, n_tokens (parents first).
+ * the root down to req_leaf[r], token t of node v = slot t % P of page node_pages[page_begin_v +
+ * t / P] (P the pool's page size).  nodes: [n_nodes][4] = parent, page_begin, n_pages, n_tokens (parents first).
  * leaf_visible (optional): of its last node request r sees only the first leaf_visible[r] tokens
  * (one of several query tokens of a call, which must not see the call's newer tokens).
  * tail_len, tail_mask (optional, instead of leaf_visible): the last tail_len tokens of the last node
@@ -409,7 +427,7 @@ int oracle_attn_decode_tree(const orc_pool *p, const void *q, int32_t q_dtype, c
     int G = num_q_heads / p->num_kv_heads;
     for (int v = 0; v < n_nodes; ++v) {
         const int32_t *nd = nodes + 4 * (size_t)v;
-        if (nd[0] < -1 || nd[0] >= v || nd[3] < 0 || nd[2] != (nd[3] + ORC_PAGE - 1) / ORC_PAGE) return -4;
+        if (nd[0] < -1 || nd[0] >= v || nd[3] < 0 || nd[2] != (nd[3] + p->page_size - 1) / p->page_size) return -4;
         if (nd[1] < 0 || (int64_t)nd[1] + nd[2] > n_node_pages) return -2;
         for (int j = 0; j < nd[2]; ++j)
             if (node_pages[nd[1] + j] < 0 || node_pages[nd[1] + j] >= p->num_pages) return -2;
@@ -439,8 +457,8 @@ int oracle_attn_decode_tree(const orc_pool *p, const void *q, int32_t q_dtype, c
             for (int t = 0; t < nt; ++t) {
                 if (i == depth - 1 && tail_mask && t >= nt - tail_len && !((tail_mask[r] >> (t - (nt - tail_len))) & 1u))
                     continue; /* a drafted token that is no ancestor of this one */
-                pg[n] = node_pages[nd[1] + t / ORC_PAGE];
-                sl[n] = t % ORC_PAGE;
+                pg[n] = node_pages[nd[1] + t / p->page_size];
+                sl[n] = t % p->page_size;
                 ++n;
             }
         }
@@ -494,7 +512,7 @@ int oracle_attn_prefill(const orc_pool *p, const void *q, int32_t q_dtype, const
     if (n_req > 0 && cu_q[0] != 0) return -1;
     for (int r = 0; r < n_req; ++r) {
         int s = cu_q[r + 1] - cu_q[r];
-        if (s < 0 || kv_len[r] < s || kv_len[r] > max_pages * ORC_PAGE) return -1;
+        if (s < 0 || kv_len[r] < s || kv_len[r] > max_pages * p->page_size) return -1;
         int rc = check_pages(p, block_table + (size_t)r * max_pages, kv_len[r]);
         if (rc) return rc;
     }

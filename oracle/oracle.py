@@ -32,7 +32,7 @@ def build(force: bool = False) -> str:
 
 class _Pool(C.Structure):
     _fields_ = [("num_pages", C.c_int32), ("num_kv_heads", C.c_int32), ("dtype", C.c_int32),
-                ("k_pages", C.c_void_p), ("v_pages", C.c_void_p),
+                ("page_size", C.c_int32), ("k_pages", C.c_void_p), ("v_pages", C.c_void_p),
                 ("k_scale", C.c_void_p), ("v_scale", C.c_void_p)]
 
 
@@ -81,9 +81,10 @@ class HostPool:
 
     Unused pages and slots are filled with NaN so that anything read by mistake shows."""
 
-    def __init__(self, num_pages: int, num_kv_heads: int, dtype: int, poison: bool = True):
-        self.num_pages, self.num_kv_heads, self.dtype = num_pages, num_kv_heads, dtype
-        n = num_pages * num_kv_heads * PAGE * D
+    def __init__(self, num_pages: int, num_kv_heads: int, dtype: int, poison: bool = True, page_size: int = PAGE):
+        assert page_size in (16, 32, 64, 128)
+        self.num_pages, self.num_kv_heads, self.dtype, self.page_size = num_pages, num_kv_heads, dtype, page_size
+        n = num_pages * num_kv_heads * page_size * D
         et = _elem_np(dtype)
         if dtype == BF16:
             fill = 0x7FC0 if poison else 0
@@ -95,11 +96,12 @@ class HostPool:
         self.v = np.full(n, fill, dtype=et)
         self.k_scale = self.v_scale = None
         if dtype == FP8_E4M3:
-            self.k_scale = np.full(num_pages * num_kv_heads, np.nan if poison else 1.0, dtype=np.float32)
-            self.v_scale = np.full(num_pages * num_kv_heads, np.nan if poison else 1.0, dtype=np.float32)
+            n_sc = num_pages * (page_size // PAGE) * num_kv_heads      # one scale per 16-slot block and head
+            self.k_scale = np.full(n_sc, np.nan if poison else 1.0, dtype=np.float32)
+            self.v_scale = np.full(n_sc, np.nan if poison else 1.0, dtype=np.float32)
 
     def _c(self) -> _Pool:
-        return _Pool(self.num_pages, self.num_kv_heads, self.dtype, _p(self.k), _p(self.v),
+        return _Pool(self.num_pages, self.num_kv_heads, self.dtype, self.page_size, _p(self.k), _p(self.v),
                      _p(self.k_scale), _p(self.v_scale))
 
     def write(self, page_ids, first_slot: int, k_src: np.ndarray, v_src: np.ndarray) -> None:
@@ -107,7 +109,7 @@ class HostPool:
         k_src, v_src = np.ascontiguousarray(k_src), np.ascontiguousarray(v_src)
         n_tokens = k_src.shape[0]
         assert k_src.shape == v_src.shape == (n_tokens, self.num_kv_heads, D)
-        assert len(page_ids) >= (first_slot + n_tokens + PAGE - 1) // PAGE
+        assert len(page_ids) >= (first_slot + n_tokens + self.page_size - 1) // self.page_size
         pc = self._c()
         rc = lib().oracle_kv_write(C.byref(pc), _p(self.k), _p(self.v), _p(self.k_scale), _p(self.v_scale),
                                    _p(page_ids), C.c_int32(first_slot), C.c_int32(n_tokens), _p(k_src),
@@ -118,11 +120,11 @@ class HostPool:
     def copy_page(self, src: int, dst: int) -> None:
         """Private copy of a whole page (every head's K and V block and, for fp8, its scales): what a
         forked sequence needs before it continues inside a partially filled page others still hold."""
-        n = self.num_kv_heads * PAGE * D
+        n = self.num_kv_heads * self.page_size * D
         self.k[dst * n:(dst + 1) * n] = self.k[src * n:(src + 1) * n]
         self.v[dst * n:(dst + 1) * n] = self.v[src * n:(src + 1) * n]
         if self.k_scale is not None:
-            h = self.num_kv_heads
+            h = self.num_kv_heads * (self.page_size // PAGE)
             self.k_scale[dst * h:(dst + 1) * h] = self.k_scale[src * h:(src + 1) * h]
             self.v_scale[dst * h:(dst + 1) * h] = self.v_scale[src * h:(src + 1) * h]
 
@@ -136,7 +138,7 @@ class HostPool:
             self.write(f.node_pages[f.page_begin[v]: f.page_begin[v] + f.n_pages[v]], 0, k, vv)
 
 
-def flatten_tree(nodes, node_pages, req_leaf, max_pages: int):
+def flatten_tree(nodes, node_pages, req_leaf, max_pages: int, page_size: int = PAGE):
     nodes, node_pages, req_leaf = _i32(nodes).reshape(-1, 4), _i32(node_pages), _i32(req_leaf)
     n_nodes, n_req = nodes.shape[0], req_leaf.shape[0]
     bt = np.empty((n_req, max_pages), dtype=np.int32)
@@ -145,7 +147,8 @@ def flatten_tree(nodes, node_pages, req_leaf, max_pages: int):
     idx = np.empty(max(1, n_nodes * max(1, n_req)), dtype=np.int32)
     tok_start = np.empty(n_nodes, dtype=np.int32)
     rc = lib().oracle_flatten_tree(_p(nodes), C.c_int32(n_nodes), _p(node_pages), C.c_int32(len(node_pages)),
-                                   _p(req_leaf), C.c_int32(n_req), C.c_int32(max_pages), _p(bt), _p(kv_len),
+                                   _p(req_leaf), C.c_int32(n_req), C.c_int32(page_size), C.c_int32(max_pages),
+                                   _p(bt), _p(kv_len),
                                    _p(indptr), _p(idx), _p(tok_start))
     if rc:
         raise ValueError(f"oracle_flatten_tree failed: {rc}")
@@ -259,19 +262,19 @@ def num_threads() -> int:
 def flatten_workload(workload):
     f = workload.forest
     mp = max(1, f.max_pages_per_req())
-    return flatten_tree(f.nodes, f.node_pages, f.req_leaf, mp)
+    return flatten_tree(f.nodes, f.node_pages, f.req_leaf, mp, f.page_size)
 
 
 def run_workload(workload, pool: Optional[HostPool] = None, req_subset=None):
     """Whole-workload oracle result (out, lse).  req_subset (decode only) restricts to some requests."""
     if pool is None:
-        pool = HostPool(workload.num_pages, workload.num_kv_heads, workload.kv_dtype)
+        pool = HostPool(workload.num_pages, workload.num_kv_heads, workload.kv_dtype, page_size=workload.page_size)
         pool.fill_from(workload)
     f = workload.forest
     q = workload.q()
     has_child = np.zeros(f.n_nodes, dtype=bool)
     has_child[f.parent[f.parent >= 0]] = True
-    if workload.mode == "decode" and bool(np.any(has_child & (f.n_tokens % PAGE != 0))):
+    if workload.mode == "decode" and bool(np.any(has_child & (f.n_tokens % f.page_size != 0))):
         # a node with children ends inside a page: no flat block table exists, walk the forest
         idx = np.arange(f.n_req) if req_subset is None else np.asarray(req_subset)
         return attn_decode_tree(pool, q[idx], f.nodes, f.node_pages, f.req_leaf[idx], float(workload.scale))

@@ -24,7 +24,8 @@ PAGE_SIZE, HEAD_DIM = 16, 128
 
 EXPORTS = [
     "hkv_last_error", "kv_pool_create", "kv_pool_destroy", "kv_pool_alloc", "kv_pool_retain", "kv_pool_release", "kv_pool_copy_on_write",
-    "kv_pool_num_free", "kv_pool_refcount", "kv_pool_write", "prefix_tree_flatten", "prefix_tree_prefill_usage",
+    "kv_pool_num_free", "kv_pool_page_size", "kv_pool_refcount", "kv_pool_write", "prefix_tree_flatten",
+    "prefix_tree_flatten_paged", "prefix_tree_prefill_usage",
     "lse_merge", "hkv_decode_plan_create", "hkv_decode_plan_create_multi", "hkv_decode_plan_create_tree", "hkv_decode_plan_destroy", "hkv_decode_plan_workspace_bytes",
     "hkv_decode_plan_num_items", "hkv_decode_plan_num_workgroups", "hkv_decode_plan_num_parts", "hkv_decode_plan_items",
     "hkv_decode_plan_max_parts", "hkv_decode_plan_part_counts", "lse_merge_dense", "attn_decode_plan_run",
@@ -152,13 +153,18 @@ def kv_pool_num_free(pool) -> int:
     return _check(lib().kv_pool_num_free(pool))
 
 
+def kv_pool_page_size(pool) -> int:
+    return _check(lib().kv_pool_page_size(pool))
+
+
 def kv_pool_refcount(pool, page_id: int) -> int:
     return _check(lib().kv_pool_refcount(pool, C.c_int32(page_id)))
 
 
 def kv_pool_write(pool, page_ids, first_slot: int, n_tokens: int, k_src, v_src, stream=None) -> None:
     ids = _host_i32(page_ids)
-    need = (first_slot + n_tokens + PAGE_SIZE - 1) // PAGE_SIZE if n_tokens > 0 else 0
+    page = kv_pool_page_size(pool)
+    need = (first_slot + n_tokens + page - 1) // page if n_tokens > 0 else 0
     if len(ids) < need:
         raise HkvError(EINVAL, f"kv_pool_write: {need} page ids needed, {len(ids)} given")
     _check(lib().kv_pool_write(pool, _hp(ids), C.c_int32(first_slot), C.c_int32(n_tokens), _dev(k_src), _dev(v_src),
@@ -166,7 +172,7 @@ def kv_pool_write(pool, page_ids, first_slot: int, n_tokens: int, k_src, v_src, 
 
 
 # ----------------------------------------------------------------------------------------- forest
-def prefix_tree_flatten(nodes, node_pages, req_leaf, max_pages: int):
+def prefix_tree_flatten(nodes, node_pages, req_leaf, max_pages: int, page_size: int = PAGE_SIZE):
     nodes, node_pages, req_leaf = _nodes(nodes), _host_i32(node_pages), _host_i32(req_leaf)
     n_nodes, n_req = nodes.shape[0], req_leaf.shape[0]
     bt = np.empty((n_req, max_pages), dtype=np.int32)
@@ -174,9 +180,15 @@ def prefix_tree_flatten(nodes, node_pages, req_leaf, max_pages: int):
     indptr = np.empty(n_nodes + 1, dtype=np.int32)
     idx = np.empty(max(1, n_nodes * max(1, n_req)), dtype=np.int32)
     tok_start = np.empty(n_nodes, dtype=np.int32)
-    _check(lib().prefix_tree_flatten(_hp(nodes), C.c_int32(n_nodes), _hp(node_pages), C.c_int32(len(node_pages)),
-                                     _hp(req_leaf), C.c_int32(n_req), C.c_int32(max_pages), _hp(bt), _hp(kv_len),
-                                     _hp(indptr), _hp(idx), _hp(tok_start)))
+    if page_size == PAGE_SIZE:
+        _check(lib().prefix_tree_flatten(_hp(nodes), C.c_int32(n_nodes), _hp(node_pages), C.c_int32(len(node_pages)),
+                                         _hp(req_leaf), C.c_int32(n_req), C.c_int32(max_pages), _hp(bt), _hp(kv_len),
+                                         _hp(indptr), _hp(idx), _hp(tok_start)))
+    else:
+        _check(lib().prefix_tree_flatten_paged(_hp(nodes), C.c_int32(n_nodes), _hp(node_pages),
+                                               C.c_int32(len(node_pages)), _hp(req_leaf), C.c_int32(n_req),
+                                               C.c_int32(page_size), C.c_int32(max_pages), _hp(bt), _hp(kv_len),
+                                               _hp(indptr), _hp(idx), _hp(tok_start)))
     return bt, kv_len, indptr, idx[: indptr[-1]].copy(), tok_start
 
 
@@ -453,10 +465,11 @@ def kv_cache_destroy(cache) -> None:
     _check(lib().kv_cache_destroy(cache))
 
 
-def kv_cache_acquire(cache, tokens, pin: bool = False):
-    """Returns (page ids of the sequence's blocks, number of leading tokens already cached)."""
+def kv_cache_acquire(cache, tokens, pin: bool = False, page_size: int = PAGE_SIZE):
+    """Returns (page ids of the sequence's blocks, number of leading tokens already cached);
+    page_size is the page size of the pool the cache was created over."""
     tokens = _host_i32(tokens)
-    pages = np.zeros((len(tokens) + PAGE_SIZE - 1) // PAGE_SIZE, dtype=np.int32)
+    pages = np.zeros((len(tokens) + page_size - 1) // page_size, dtype=np.int32)
     cached = C.c_int32(0)
     _check(lib().kv_cache_acquire(cache, _hp(tokens), C.c_int32(len(tokens)), C.c_int32(1 if pin else 0), _hp(pages),
                                   C.byref(cached)))

@@ -66,8 +66,10 @@ int env_int(const char *name, int dflt) {
 struct hkv_decode_plan {
     hkv_pool *pool = nullptr;
     int32_t n_req = 0, num_q_heads = 0, group = 0, n_parts = 0, max_parts = 1;
-    std::vector<hkv_node> nodes;            // key of the one-shot cache
-    std::vector<int32_t> node_pages, req_leaf;
+    std::vector<hkv_node> key_nodes;        // the caller's forest: key of the one-shot cache
+    std::vector<int32_t> key_pages, req_leaf;
+    std::vector<hkv_node> nodes;            // the same forest in 16-token blocks (page_begin, n_pages into node_pages)
+    std::vector<int32_t> node_pages;
     std::vector<DecodeItem> items;
     std::vector<int32_t> node_req_indptr, node_req_idx, part_count;
     // one device allocation holding items | pages | node_req_idx | part_count
@@ -90,7 +92,9 @@ struct hkv_decode_plan {
 
 struct hkv_prefill_plan {
     hkv_pool *pool = nullptr;
-    int32_t n_req = 0, num_q_heads = 0, max_pages = 0, total_q = 0;
+    int32_t n_req = 0, num_q_heads = 0, total_q = 0;
+    int32_t key_max_pages = 0;   // row length of the caller's block table (pages)
+    int32_t max_pages = 0;       // row length of the device table (16-token blocks)
     std::vector<int32_t> cu_q, block_table, kv_len;   // key of the one-shot cache
     std::vector<PrefillTile> tiles;
     void *dev = nullptr;
@@ -105,6 +109,10 @@ struct hkv_prefill_plan {
 
 struct hkv_pool {
     hkv_pool_desc d{};
+    // A page of page_size = 16 * S tokens is S consecutive 16-token blocks of the buffers: block
+    // page * S + j holds tokens 16 j .. 16 j + 15 of the page.  Everything behind the entry points
+    // (work lists, kernels) deals in 16-token blocks; page ids are translated where they come in.
+    int32_t blocks_per_page = 1;
     std::vector<int32_t> refcnt;
     std::deque<int32_t> free_list;
     // Staging of page ids for kv_pool_write: a ring of slots (pinned host + device, one allocation
@@ -129,9 +137,12 @@ extern "C" const char *hkv_last_error(void) { return g_err.c_str(); }
 extern "C" int kv_pool_create(const hkv_pool_desc *desc, hkv_pool **out) {
     if (!desc || !out) return fail(HKV_EINVAL, "kv_pool_create: null argument");
     *out = nullptr;
-    if (desc->page_size != HKV_PAGE_SIZE || desc->head_dim != HKV_HEAD_DIM)
-        return fail(HKV_ESHAPE, "kv_pool_create: page_size must be 16 and head_dim 128 (got %d, %d)",
+    if ((desc->page_size != 16 && desc->page_size != 32 && desc->page_size != 64 && desc->page_size != 128) ||
+        desc->head_dim != HKV_HEAD_DIM)
+        return fail(HKV_ESHAPE, "kv_pool_create: page_size must be 16, 32, 64 or 128 and head_dim 128 (got %d, %d)",
                     desc->page_size, desc->head_dim);
+    if ((int64_t)desc->num_pages * (desc->page_size / HKV_PAGE_SIZE) > INT32_MAX)
+        return fail(HKV_EINVAL, "kv_pool_create: too many 16-token blocks");
     if (desc->dtype != HKV_BF16 && desc->dtype != HKV_FP8_E4M3 && desc->dtype != HKV_FP32)
         return fail(HKV_ESHAPE, "kv_pool_create: pool dtype %d (bf16, fp8 e4m3 or fp32)", desc->dtype);
     if (desc->num_pages <= 0 || desc->num_kv_heads <= 0)
@@ -145,6 +156,7 @@ extern "C" int kv_pool_create(const hkv_pool_desc *desc, hkv_pool **out) {
     if (!p) return fail(HKV_ENOMEM, "kv_pool_create: out of host memory");
     p->d = *desc;
     p->d.free_order = nullptr;
+    p->blocks_per_page = desc->page_size / HKV_PAGE_SIZE;
     p->refcnt.assign(desc->num_pages, 0);
     if (desc->free_order) {
         std::vector<char> seen(desc->num_pages, 0);
@@ -230,6 +242,11 @@ extern "C" int32_t kv_pool_num_free(const hkv_pool *pool) {
     return (int32_t)pool->free_list.size();
 }
 
+extern "C" int32_t kv_pool_page_size(const hkv_pool *pool) {
+    if (!pool) return fail(HKV_EINVAL, "kv_pool_page_size: null pool");
+    return pool->d.page_size;
+}
+
 extern "C" int32_t kv_pool_refcount(const hkv_pool *pool, int32_t page_id) {
     if (!pool) return fail(HKV_EINVAL, "kv_pool_refcount: null pool");
     if (page_id < 0 || page_id >= pool->d.num_pages) return fail(HKV_ERANGE, "kv_pool_refcount: page id %d", page_id);
@@ -257,6 +274,7 @@ extern "C" int kv_pool_copy_on_write(hkv_pool *pool, int32_t n, int32_t *ids, vo
                     pool->free_list.size());
     PoolCopyLaunch a{};
     a.pool = view_of(pool);
+    a.blocks_per_page = pool->blocks_per_page;
     for (int i = 0; i < n; ++i) {
         const int32_t old = ids[i];
         if (pool->refcnt[old] == 1) continue;  // sole holder: it may write in place
@@ -279,17 +297,20 @@ extern "C" int kv_pool_copy_on_write(hkv_pool *pool, int32_t n, int32_t *ids, vo
 extern "C" int kv_pool_write(hkv_pool *pool, const int32_t *page_ids, int32_t first_slot, int32_t n_tokens,
                              const void *k_src, const void *v_src, void *stream) {
     if (!pool) return fail(HKV_EINVAL, "kv_pool_write: null pool");
-    if (n_tokens < 0 || first_slot < 0 || first_slot >= HKV_PAGE_SIZE)
+    const int P = pool->d.page_size, S = pool->blocks_per_page;
+    if (n_tokens < 0 || first_slot < 0 || first_slot >= P)
         return fail(HKV_EINVAL, "kv_pool_write: n_tokens %d, first_slot %d", n_tokens, first_slot);
     if (n_tokens == 0) return HKV_OK;
     if (!page_ids || !k_src || !v_src) return fail(HKV_EINVAL, "kv_pool_write: null argument");
     if ((reinterpret_cast<uintptr_t>(k_src) | reinterpret_cast<uintptr_t>(v_src)) & 15)
         return fail(HKV_EINVAL, "kv_pool_write: k_src and v_src must be 16-byte aligned");
-    int64_t n_pg = ((int64_t)first_slot + n_tokens + HKV_PAGE_SIZE - 1) / HKV_PAGE_SIZE;
+    // 16-token blocks touched: b0 .. b1 of the listed pages' concatenated blocks
+    const int64_t b0 = first_slot / HKV_PAGE_SIZE, b1 = ((int64_t)first_slot + n_tokens - 1) / HKV_PAGE_SIZE;
+    const int64_t n_pg = b1 - b0 + 1;
     if (n_pg > hkv_pool::kMaxWritePages)
         return fail(HKV_EINVAL, "kv_pool_write: %lld pages in one call (limit %d)", (long long)n_pg,
                     hkv_pool::kMaxWritePages);
-    for (int64_t i = 0; i < n_pg; ++i)
+    for (int64_t i = 0; i <= b1 / S; ++i)
         if (page_ids[i] < 0 || page_ids[i] >= pool->d.num_pages)
             return fail(HKV_ERANGE, "kv_pool_write: page id %d (entry %lld) outside pool of %d pages", page_ids[i],
                         (long long)i, pool->d.num_pages);
@@ -305,10 +326,10 @@ extern "C" int kv_pool_write(hkv_pool *pool, const int32_t *page_ids, int32_t fi
     if (pool->slot_in_flight[slot]) HKV_HIP(hipEventSynchronize(pool->slot_free[slot]));  // its last write is done
     int32_t *h = pool->h_ids + (size_t)slot * hkv_pool::kMaxWritePages;
     int32_t *d = pool->d_ids + (size_t)slot * hkv_pool::kMaxWritePages;
-    memcpy(h, page_ids, sizeof(int32_t) * (size_t)n_pg);
+    for (int64_t b = b0; b <= b1; ++b) h[b - b0] = page_ids[b / S] * S + (int32_t)(b % S);
     HKV_HIP(hipMemcpyAsync(d, h, sizeof(int32_t) * (size_t)n_pg, hipMemcpyHostToDevice, s));
     PoolWriteLaunch a{pool->d.k_pages, pool->d.v_pages, pool->d.k_scale, pool->d.v_scale, pool->d.num_kv_heads,
-                      pool->d.dtype, d, (int32_t)n_pg, first_slot, n_tokens, k_src, v_src};
+                      pool->d.dtype, d, (int32_t)n_pg, first_slot % HKV_PAGE_SIZE, n_tokens, k_src, v_src};
     if (pool->d.dtype == HKV_FP32)
         HKV_HIP(launch_pool_write_fp32(a, s));
     else
@@ -324,7 +345,7 @@ extern "C" int kv_pool_write(hkv_pool *pool, const int32_t *page_ids, int32_t fi
 // needs: positions along a path then map to pages without gaps); false for callers that walk the forest
 // node by node.
 static int validate_forest(const hkv_node *nodes, int32_t n_nodes, const int32_t *node_pages, int32_t n_node_pages,
-                           const char *who, bool whole_page_parents = true) {
+                           const char *who, bool whole_page_parents = true, int page_size = HKV_PAGE_SIZE) {
     if (n_nodes < 0 || n_node_pages < 0 || (n_nodes > 0 && !nodes) || (n_node_pages > 0 && !node_pages))
         return fail(HKV_EINVAL, "%s: bad forest arguments", who);
     std::vector<char> has_child(n_nodes, 0);
@@ -332,7 +353,7 @@ static int validate_forest(const hkv_node *nodes, int32_t n_nodes, const int32_t
         const hkv_node &nd = nodes[v];
         if (nd.parent < -1 || nd.parent >= v)
             return fail(HKV_ETREE, "%s: node %d has parent %d (parents must come first)", who, v, nd.parent);
-        if (nd.n_tokens < 0 || nd.n_pages != (nd.n_tokens + HKV_PAGE_SIZE - 1) / HKV_PAGE_SIZE)
+        if (nd.n_tokens < 0 || nd.n_pages != (nd.n_tokens + page_size - 1) / page_size)
             return fail(HKV_ETREE, "%s: node %d has %d tokens but %d pages", who, v, nd.n_tokens, nd.n_pages);
         if (nd.page_begin < 0 || (int64_t)nd.page_begin + nd.n_pages > n_node_pages)
             return fail(HKV_ERANGE, "%s: node %d pages [%d, %d) outside node_pages of %d", who, v, nd.page_begin,
@@ -341,9 +362,9 @@ static int validate_forest(const hkv_node *nodes, int32_t n_nodes, const int32_t
     }
     if (whole_page_parents)
         for (int v = 0; v < n_nodes; ++v)
-            if (has_child[v] && nodes[v].n_tokens % HKV_PAGE_SIZE)
-                return fail(HKV_ETREE, "%s: node %d has children but %d tokens (not a multiple of 16)", who, v,
-                            nodes[v].n_tokens);
+            if (has_child[v] && nodes[v].n_tokens % page_size)
+                return fail(HKV_ETREE, "%s: node %d has children but %d tokens (not a multiple of %d)", who, v,
+                            nodes[v].n_tokens, page_size);
     return HKV_OK;
 }
 
@@ -368,8 +389,18 @@ extern "C" int prefix_tree_flatten(const hkv_node *nodes, int32_t n_nodes, const
                                    int32_t n_node_pages, const int32_t *req_leaf, int32_t n_req, int32_t max_pages,
                                    int32_t *block_table, int32_t *kv_len, int32_t *node_req_indptr,
                                    int32_t *node_req_idx, int32_t *node_tok_start) {
+    return prefix_tree_flatten_paged(nodes, n_nodes, node_pages, n_node_pages, req_leaf, n_req, HKV_PAGE_SIZE, max_pages,
+                                     block_table, kv_len, node_req_indptr, node_req_idx, node_tok_start);
+}
+
+extern "C" int prefix_tree_flatten_paged(const hkv_node *nodes, int32_t n_nodes, const int32_t *node_pages,
+                                         int32_t n_node_pages, const int32_t *req_leaf, int32_t n_req,
+                                         int32_t page_size, int32_t max_pages, int32_t *block_table, int32_t *kv_len,
+                                         int32_t *node_req_indptr, int32_t *node_req_idx, int32_t *node_tok_start) {
     if (max_pages < 0) return fail(HKV_EINVAL, "prefix_tree_flatten: max_pages %d", max_pages);
-    if (int rc = validate_forest(nodes, n_nodes, node_pages, n_node_pages, "prefix_tree_flatten")) return rc;
+    if (page_size != 16 && page_size != 32 && page_size != 64 && page_size != 128)
+        return fail(HKV_ESHAPE, "prefix_tree_flatten: page_size %d (16, 32, 64 or 128)", page_size);
+    if (int rc = validate_forest(nodes, n_nodes, node_pages, n_node_pages, "prefix_tree_flatten", true, page_size)) return rc;
     std::vector<int32_t> indptr, idx;
     if (int rc = build_node_req_csr(nodes, n_nodes, req_leaf, n_req, indptr, idx, "prefix_tree_flatten")) return rc;
     std::vector<int32_t> tok_start(n_nodes, 0), pages_before(n_nodes, 0);
@@ -642,7 +673,7 @@ extern "C" int hkv_decode_plan_create(hkv_pool *pool, const hkv_node *nodes, int
     // The per-node kernels read every node through its own page list, so nodes may end inside a page
     // anywhere; the full-precision path walks flat block tables and keeps the whole-page rule.
     if (int rc = validate_forest(nodes, n_nodes, node_pages, n_node_pages, "hkv_decode_plan_create",
-                                 pool->d.dtype == HKV_FP32))
+                                 pool->d.dtype == HKV_FP32, pool->d.page_size))
         return rc;
     for (int v = 0; v < n_nodes; ++v)
         for (int j = 0; j < nodes[v].n_pages; ++j) {
@@ -662,9 +693,21 @@ extern "C" int hkv_decode_plan_create(hkv_pool *pool, const hkv_node *nodes, int
         delete pl;
         return rc;
     }
-    pl->nodes.assign(nodes, nodes + n_nodes);
-    pl->node_pages.assign(node_pages, node_pages + n_node_pages);
+    pl->key_nodes.assign(nodes, nodes + n_nodes);
+    pl->key_pages.assign(node_pages, node_pages + n_node_pages);
     pl->req_leaf.assign(req_leaf, req_leaf + n_req);
+    // the plan itself works on 16-token blocks: block j of page p is block p * S + j of the buffers
+    pl->nodes.assign(nodes, nodes + n_nodes);
+    pl->node_pages.clear();
+    const int S = pool->blocks_per_page;
+    for (int v = 0; v < n_nodes; ++v) {
+        hkv_node &nd = pl->nodes[v];
+        const int n_blocks = (nd.n_tokens + HKV_PAGE_SIZE - 1) / HKV_PAGE_SIZE;
+        const int first = (int)pl->node_pages.size();
+        for (int b = 0; b < n_blocks; ++b) pl->node_pages.push_back(node_pages[nodes[v].page_begin + b / S] * S + b % S);
+        nd.page_begin = first;
+        nd.n_pages = n_blocks;
+    }
     if (pool->d.dtype == HKV_FP32) {  // full-precision path: no work items, no partials
         if (int rc = build_fp32_rows(*pl, !(flags & HKV_PLAN_HOST_ONLY))) {
             if (pl->d_bt) (void)hipFree(pl->d_bt);
@@ -884,10 +927,10 @@ extern "C" int hkv_decode_plan_elapsed_ms(hkv_decode_plan *plan, float *node_ms,
 
 static bool same_forest(const hkv_decode_plan *pl, const hkv_node *nodes, int32_t n_nodes, const int32_t *node_pages,
                         int32_t n_node_pages, const int32_t *req_leaf, int32_t n_req, int32_t num_q_heads) {
-    return pl && pl->num_q_heads == num_q_heads && (int32_t)pl->nodes.size() == n_nodes &&
-           (int32_t)pl->node_pages.size() == n_node_pages && (int32_t)pl->req_leaf.size() == n_req &&
-           (n_nodes == 0 || !memcmp(pl->nodes.data(), nodes, sizeof(hkv_node) * n_nodes)) &&
-           (n_node_pages == 0 || !memcmp(pl->node_pages.data(), node_pages, sizeof(int32_t) * n_node_pages)) &&
+    return pl && pl->num_q_heads == num_q_heads && (int32_t)pl->key_nodes.size() == n_nodes &&
+           (int32_t)pl->key_pages.size() == n_node_pages && (int32_t)pl->req_leaf.size() == n_req &&
+           (n_nodes == 0 || !memcmp(pl->key_nodes.data(), nodes, sizeof(hkv_node) * n_nodes)) &&
+           (n_node_pages == 0 || !memcmp(pl->key_pages.data(), node_pages, sizeof(int32_t) * n_node_pages)) &&
            (n_req == 0 || !memcmp(pl->req_leaf.data(), req_leaf, sizeof(int32_t) * n_req));
 }
 
@@ -955,7 +998,7 @@ extern "C" int hkv_prefill_plan_create(hkv_pool *pool, const int32_t *cu_q, cons
         int64_t s = (int64_t)cu_q[r + 1] - cu_q[r];
         if (s < 0) return fail(HKV_EINVAL, "hkv_prefill_plan_create: cu_q decreases at request %d", r);
         if (kv_len[r] < s) return fail(HKV_EINVAL, "hkv_prefill_plan_create: request %d has kv_len %d < %lld new tokens", r, kv_len[r], (long long)s);
-        int64_t need = ((int64_t)kv_len[r] + HKV_PAGE_SIZE - 1) / HKV_PAGE_SIZE;
+        int64_t need = ((int64_t)kv_len[r] + pool->d.page_size - 1) / pool->d.page_size;
         if (need > max_pages) return fail(HKV_ENOMEM, "hkv_prefill_plan_create: request %d needs %lld pages, max_pages is %d", r, (long long)need, max_pages);
         if (s == 0) continue;  // nothing of this request is read
         for (int64_t i = 0; i < need; ++i) {
@@ -969,11 +1012,22 @@ extern "C" int hkv_prefill_plan_create(hkv_pool *pool, const int32_t *cu_q, cons
     pl->pool = pool;
     pl->n_req = n_req;
     pl->num_q_heads = num_q_heads;
-    pl->max_pages = max_pages;
+    pl->key_max_pages = max_pages;
     pl->total_q = n_req ? cu_q[n_req] : 0;
     pl->cu_q.assign(cu_q, cu_q + (n_req ? n_req + 1 : 0));
     pl->kv_len.assign(kv_len, kv_len + n_req);
     if (n_req && max_pages) pl->block_table.assign(block_table, block_table + (size_t)n_req * max_pages);
+    // the kernels index 16-token blocks: block j of page p is block p * S + j of the buffers
+    const int S = pool->blocks_per_page;
+    const int max_blocks = max_pages * S;
+    pl->max_pages = max_blocks;
+    std::vector<int32_t> blocks((size_t)n_req * max_blocks, 0);
+    for (int r = 0; r < n_req; ++r) {
+        if (cu_q[r + 1] == cu_q[r]) continue;
+        const int64_t nb = ((int64_t)kv_len[r] + HKV_PAGE_SIZE - 1) / HKV_PAGE_SIZE;
+        for (int64_t b = 0; b < nb; ++b)
+            blocks[(size_t)r * max_blocks + b] = block_table[(size_t)r * max_pages + b / S] * S + (int32_t)(b % S);
+    }
     const int TQ = prefill_tile_tokens(G);
     struct Proto { int32_t req, q_begin, n_q; int64_t extent; };
     std::vector<Proto> protos;
@@ -992,28 +1046,28 @@ extern "C" int hkv_prefill_plan_create(hkv_pool *pool, const int32_t *cu_q, cons
         for (int h = 0; h < Hkv; ++h) {
             int s = cu_q[p.req + 1] - cu_q[p.req];
             pl->tiles.push_back(PrefillTile{p.req, p.q_begin, p.n_q, h, cu_q[p.req] + p.q_begin, kv_len[p.req] - s,
-                                            kv_len[p.req], p.req * max_pages});
+                                            kv_len[p.req], p.req * max_blocks});
         }
     // fp8 pools: number the pages this batch reads (first use first) and point the device table at them
     std::vector<int32_t> remapped;
     if (pool->d.dtype == HKV_FP8_E4M3) {
         std::unordered_map<int32_t, int32_t> index;
-        remapped.assign(pl->block_table.size(), 0);
+        remapped.assign(blocks.size(), 0);
         for (int r = 0; r < n_req; ++r) {
             if (cu_q[r + 1] == cu_q[r]) continue;
             const int64_t need = ((int64_t)kv_len[r] + HKV_PAGE_SIZE - 1) / HKV_PAGE_SIZE;
             for (int64_t i = 0; i < need; ++i) {
-                const int32_t id = block_table[(size_t)r * max_pages + i];
+                const int32_t id = blocks[(size_t)r * max_blocks + i];
                 auto it = index.find(id);
                 if (it == index.end()) {
                     it = index.emplace(id, (int32_t)pl->src_pages.size()).first;
                     pl->src_pages.push_back(id);
                 }
-                remapped[(size_t)r * max_pages + i] = it->second;
+                remapped[(size_t)r * max_blocks + i] = it->second;
             }
         }
     }
-    const std::vector<int32_t> &dev_table = pool->d.dtype == HKV_FP8_E4M3 ? remapped : pl->block_table;
+    const std::vector<int32_t> &dev_table = pool->d.dtype == HKV_FP8_E4M3 ? remapped : blocks;
     if (!(flags & HKV_PLAN_HOST_ONLY) && !pl->tiles.empty()) {
         size_t off_bt = align_up(sizeof(PrefillTile) * pl->tiles.size(), 256);
         size_t off_src = off_bt + align_up(sizeof(int32_t) * dev_table.size(), 256);
@@ -1120,7 +1174,7 @@ extern "C" int attn_prefill_with_prefix(hkv_pool *pool, const void *q, const int
                                         void *stream) {
     if (!pool) return fail(HKV_EINVAL, "attn_prefill_with_prefix: null pool");
     hkv_prefill_plan *c = pool->cached_prefill;
-    bool same = c && c->dev && c->n_req == n_req && c->num_q_heads == num_q_heads && c->max_pages == max_pages &&
+    bool same = c && c->dev && c->n_req == n_req && c->num_q_heads == num_q_heads && c->key_max_pages == max_pages &&
                 n_req > 0 && cu_q && kv_len && block_table &&
                 !memcmp(c->cu_q.data(), cu_q, sizeof(int32_t) * (n_req + 1)) &&
                 !memcmp(c->kv_len.data(), kv_len, sizeof(int32_t) * n_req) &&

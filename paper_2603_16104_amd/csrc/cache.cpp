@@ -3,7 +3,8 @@
 // Integration": precomputed prefixes are pinned; under memory pressure blocks are evicted least
 // recently used first and a prefix never before its extensions; an evicted prefix is recomputed.)
 //
-// A block is 16 tokens; its identity is (preceding block, its 16 token ids), so two sequences share
+// A block is one page of tokens (16 unless the pool says otherwise); its identity is (preceding block,
+// its token ids), so two sequences share
 // a block exactly when they agree on everything up to its end.  Only full blocks are shared; a
 // sequence's partial last block is private.  Evictable = no live user, not pinned, nothing cached
 // extends it; among those the oldest last use goes first, ties by lower page id; the clock ticks
@@ -38,6 +39,7 @@ struct Block {
 
 struct hkv_cache {
     hkv_pool *pool = nullptr;
+    int32_t block = HKV_PAGE_SIZE;  // tokens per cached block = the pool's page size
     Block root;
     std::unordered_map<int32_t, Block *> by_page;      // cached full blocks
     std::unordered_map<int32_t, int> private_pages;    // partial last blocks in use
@@ -106,6 +108,7 @@ extern "C" int kv_cache_create(hkv_pool *pool, hkv_cache **out) {
     hkv_cache *c = new (std::nothrow) hkv_cache;
     if (!c) return fail(HKV_ENOMEM, "kv_cache_create: out of host memory");
     c->pool = pool;
+    c->block = kv_pool_page_size(pool);
     *out = c;
     return HKV_OK;
 }
@@ -124,12 +127,13 @@ extern "C" int kv_cache_acquire(hkv_cache *c, const int32_t *tokens, int32_t n_t
     if (!c || n_tokens < 0 || (n_tokens > 0 && (!tokens || !page_ids)) || !n_cached_tokens)
         return fail(HKV_EINVAL, "kv_cache_acquire: bad argument");
     ++c->clock;
-    const int n_full = n_tokens / HKV_PAGE_SIZE;
+    const int P = c->block;
+    const int n_full = n_tokens / P;
     Block *node = &c->root;
     std::vector<Block *> taken;
     int j = 0, n_pages = 0;
     for (; j < n_full; ++j) {  // hits
-        std::vector<int32_t> key(tokens + j * HKV_PAGE_SIZE, tokens + (j + 1) * HKV_PAGE_SIZE);
+        std::vector<int32_t> key(tokens + j * P, tokens + (j + 1) * P);
         auto it = node->children.find(key);
         if (it == node->children.end()) break;
         Block *b = it->second;
@@ -142,7 +146,7 @@ extern "C" int kv_cache_acquire(hkv_cache *c, const int32_t *tokens, int32_t n_t
         node = b;
         ++c->hits;
     }
-    *n_cached_tokens = j * HKV_PAGE_SIZE;
+    *n_cached_tokens = j * P;
     bool ok = true;
     for (; j < n_full && ok; ++j) {  // misses: new full blocks enter the cache at once
         const int32_t page = c->take_page();
@@ -157,7 +161,7 @@ extern "C" int kv_cache_acquire(hkv_cache *c, const int32_t *tokens, int32_t n_t
             break;
         }
         b->parent = node;
-        b->key.assign(tokens + j * HKV_PAGE_SIZE, tokens + (j + 1) * HKV_PAGE_SIZE);
+        b->key.assign(tokens + j * P, tokens + (j + 1) * P);
         b->page = page;
         b->ref = 1;
         b->last_use = c->clock;
@@ -169,7 +173,7 @@ extern "C" int kv_cache_acquire(hkv_cache *c, const int32_t *tokens, int32_t n_t
         node = b;
         ++c->misses;
     }
-    if (ok && n_tokens % HKV_PAGE_SIZE) {  // private partial block
+    if (ok && n_tokens % P) {  // private partial block
         const int32_t page = c->take_page();
         if (page < 0) {
             ok = false;

@@ -104,6 +104,7 @@ struct PoolWriteLaunch {
 constexpr int kMaxCopyPairs = 32;
 struct PoolCopyLaunch {
     PoolView pool;
+    int32_t blocks_per_page;     // a page is this many consecutive 16-token blocks
     int32_t n;
     int32_t src[kMaxCopyPairs];
     int32_t dst[kMaxCopyPairs];

@@ -165,15 +165,16 @@ __global__ __launch_bounds__(256) void pool_write_kernel(PoolWriteLaunch a) {
 __global__ __launch_bounds__(256) void pool_copy_kernel(PoolCopyLaunch a) {
     const int pair = blockIdx.x, which = blockIdx.y;
     const int elem = a.pool.dtype == 0 ? 2 : a.pool.dtype == 1 ? 1 : 4;
-    const size_t page_bytes = (size_t)a.pool.num_kv_heads * kBlockElems * elem;
+    const size_t page_bytes = (size_t)a.blocks_per_page * a.pool.num_kv_heads * kBlockElems * elem;
     const char *base = static_cast<const char *>(which ? a.pool.v_pages : a.pool.k_pages);
     const uint4 *src = reinterpret_cast<const uint4 *>(base + (size_t)a.src[pair] * page_bytes);
     uint4 *dst = reinterpret_cast<uint4 *>(const_cast<char *>(base) + (size_t)a.dst[pair] * page_bytes);
     for (size_t i = threadIdx.x; i < page_bytes / 16; i += 256) dst[i] = src[i];
     if (a.pool.dtype == 1) {
         float *sc = const_cast<float *>(which ? a.pool.v_scale : a.pool.k_scale);
-        for (int h = threadIdx.x; h < a.pool.num_kv_heads; h += 256)
-            sc[(size_t)a.dst[pair] * a.pool.num_kv_heads + h] = sc[(size_t)a.src[pair] * a.pool.num_kv_heads + h];
+        const int per_page = a.blocks_per_page * a.pool.num_kv_heads;  // one scale per 16-token block and head
+        for (int h = threadIdx.x; h < per_page; h += 256)
+            sc[(size_t)a.dst[pair] * per_page + h] = sc[(size_t)a.src[pair] * per_page + h];
     }
 }
 

@@ -18,20 +18,21 @@ class DevicePool:
     """A KV page pool in HBM (library storage format), NaN-poisoned until written."""
 
     def __init__(self, num_pages: int, num_kv_heads: int, dtype: int, device: str = "cuda:0",
-                 free_order: Optional[np.ndarray] = None, poison: bool = True):
-        self.num_pages, self.num_kv_heads, self.dtype = num_pages, num_kv_heads, dtype
+                 free_order: Optional[np.ndarray] = None, poison: bool = True, page_size: int = hkv.PAGE_SIZE):
+        self.num_pages, self.num_kv_heads, self.dtype, self.page_size = num_pages, num_kv_heads, dtype, page_size
         tdt, nan_bits = _ELEM[dtype]
-        n = num_pages * num_kv_heads * hkv.PAGE_SIZE * hkv.HEAD_DIM
+        n = num_pages * num_kv_heads * page_size * hkv.HEAD_DIM
         fill = nan_bits if poison else 0
         self.k = torch.full((n,), fill, dtype=tdt, device=device)
         self.v = torch.full((n,), fill, dtype=tdt, device=device)
         self.k_scale = self.v_scale = None
         if dtype == hkv.FP8_E4M3:
             sv = float("nan") if poison else 1.0
-            self.k_scale = torch.full((num_pages * num_kv_heads,), sv, dtype=torch.float32, device=device)
-            self.v_scale = torch.full((num_pages * num_kv_heads,), sv, dtype=torch.float32, device=device)
+            n_sc = num_pages * (page_size // hkv.PAGE_SIZE) * num_kv_heads   # one scale per 16-token block and head
+            self.k_scale = torch.full((n_sc,), sv, dtype=torch.float32, device=device)
+            self.v_scale = torch.full((n_sc,), sv, dtype=torch.float32, device=device)
         self.handle = hkv.kv_pool_create(num_pages, num_kv_heads, dtype, self.k, self.v, self.k_scale, self.v_scale,
-                                         free_order)
+                                         free_order, page_size=page_size)
 
     def close(self) -> None:
         if self.handle is not None:
@@ -65,6 +66,7 @@ class DevicePool:
         """kv_pool_write of every node's own tokens into the node's pages."""
         f = workload.forest
         dev = self.k.device
+        assert f.page_size == self.page_size and max_chunk_tokens % self.page_size == 0
         for node in range(f.n_nodes):
             nt = int(f.n_tokens[node])
             if nt == 0:
@@ -75,7 +77,7 @@ class DevicePool:
                 t1 = min(nt, t0 + max_chunk_tokens)
                 kd = to_device_bits(k[t0:t1], dev)
                 vd = to_device_bits(v[t0:t1], dev)
-                self.write(pages[t0 // 16:], 0, kd, vd)
+                self.write(pages[t0 // self.page_size:], 0, kd, vd)
         torch.cuda.synchronize()
 
 
@@ -130,7 +132,8 @@ class PrefillRunner:
         f = workload.forest
         self.pool, self.workload = pool, workload
         mp = max(1, f.max_pages_per_req())
-        self.block_table, self.kv_len, *_ = hkv.prefix_tree_flatten(f.nodes, f.node_pages, f.req_leaf, mp)
+        self.block_table, self.kv_len, *_ = hkv.prefix_tree_flatten(f.nodes, f.node_pages, f.req_leaf, mp,
+                                                                    f.page_size)
         self.cu_q = workload.cu_q()
         self.plan = hkv.hkv_prefill_plan_create(pool.handle, self.cu_q, self.block_table, self.kv_len,
                                                 workload.num_q_heads)
@@ -197,7 +200,8 @@ class MixedStepRunner:
                 self.dlse = torch.empty((len(self.dec_req), Hq), dtype=torch.float32, device=dev)
         if len(self.pre_req):
             mp = max(1, f.max_pages_per_req())
-            bt, kv_len, *_ = hkv.prefix_tree_flatten(f.nodes, f.node_pages, f.req_leaf[self.pre_req], mp)
+            bt, kv_len, *_ = hkv.prefix_tree_flatten(f.nodes, f.node_pages, f.req_leaf[self.pre_req], mp,
+                                                     f.page_size)
             pcu = np.zeros(len(self.pre_req) + 1, dtype=np.int32)
             pcu[1:] = np.cumsum(ql[self.pre_req])
             self.pre_plan = hkv.hkv_prefill_plan_create(pool.handle, pcu, bt, kv_len, Hq)

@@ -52,9 +52,10 @@ class PrefixForest:
     parent: np.ndarray       # int32 [n_nodes], -1 for a root; parents precede children
     n_tokens: np.ndarray     # int32 [n_nodes]
     page_begin: np.ndarray   # int32 [n_nodes], offset of the node's first page in node_pages
-    n_pages: np.ndarray      # int32 [n_nodes] = ceil(n_tokens / 16)
+    n_pages: np.ndarray      # int32 [n_nodes] = ceil(n_tokens / page_size)
     node_pages: np.ndarray   # int32 [sum n_pages], pool page ids
     req_leaf: np.ndarray     # int32 [n_req]
+    page_size: int = PAGE_SIZE   # tokens per page (16, 32, 64 or 128)
 
     @property
     def n_nodes(self) -> int:
@@ -101,11 +102,11 @@ class PrefixForest:
 
 
 def make_forest(parent: Sequence[int], n_tokens: Sequence[int], req_leaf: Sequence[int],
-                page_ids: np.ndarray) -> PrefixForest:
+                page_ids: np.ndarray, page_size: int = PAGE_SIZE) -> PrefixForest:
     """Lay the nodes' pages out consecutively over the given (already permuted) pool page ids."""
     parent = np.asarray(parent, dtype=np.int32)
     n_tokens = np.asarray(n_tokens, dtype=np.int32)
-    n_pages = ((n_tokens + (PAGE_SIZE - 1)) // PAGE_SIZE).astype(np.int32)
+    n_pages = ((n_tokens + (page_size - 1)) // page_size).astype(np.int32)
     page_begin = np.zeros_like(n_pages)
     if len(n_pages):
         page_begin[1:] = np.cumsum(n_pages)[:-1]
@@ -114,7 +115,7 @@ def make_forest(parent: Sequence[int], n_tokens: Sequence[int], req_leaf: Sequen
         raise ValueError(f"forest needs {total} pages, only {len(page_ids)} given")
     return PrefixForest(parent, n_tokens, page_begin.astype(np.int32), n_pages,
                         np.ascontiguousarray(page_ids[:total], dtype=np.int32),
-                        np.asarray(req_leaf, dtype=np.int32))
+                        np.asarray(req_leaf, dtype=np.int32), page_size)
 
 
 @dataclass
@@ -134,6 +135,10 @@ class Workload:
     @property
     def group(self) -> int:
         return self.num_q_heads // self.num_kv_heads
+
+    @property
+    def page_size(self) -> int:
+        return self.forest.page_size
 
     @property
     def scale(self) -> np.float32:
@@ -362,7 +367,8 @@ def random_forest_workload(seed: int, *, n_roots: int = 2, depth: int = 3, fanou
                            max_node_pages: int = 5, num_q_heads: int = 8, num_kv_heads: int = 2,
                            kv_dtype: int = KV_BF16, mode: str = "decode", ragged: bool = True,
                            zero_weight_nodes: bool = True, src_dtype: str = "bf16",
-                           extra_pages: int = 7, ragged_internal: bool = False) -> Workload:
+                           extra_pages: int = 7, ragged_internal: bool = False,
+                           page_size: int = PAGE_SIZE) -> Workload:
     """Small random forest for tests: internal nodes are page aligned (unless ragged_internal: then they
     may end inside a page, which only the tree decode accepts), leaves may be ragged, and (as in the
     paper's tree, where the root and the leaves carry no tokens) some nodes are empty."""
@@ -379,18 +385,18 @@ def random_forest_workload(seed: int, *, n_roots: int = 2, depth: int = 3, fanou
             if zero_weight_nodes and rng.random() < 0.15:
                 t = 0
             elif ragged:
-                t = int(rng.integers(1, max_node_pages * PAGE_SIZE + 1))
+                t = int(rng.integers(1, max_node_pages * page_size + 1))
             else:
-                t = int(rng.integers(1, max_node_pages + 1)) * PAGE_SIZE
+                t = int(rng.integers(1, max_node_pages + 1)) * page_size
             ntok.append(t)
             leaves.append(idx)
             return
         if zero_weight_nodes and rng.random() < 0.2:
             ntok.append(0)
         elif ragged_internal:
-            ntok.append(int(rng.integers(1, max_node_pages * PAGE_SIZE + 1)))
+            ntok.append(int(rng.integers(1, max_node_pages * page_size + 1)))
         else:
-            ntok.append(int(rng.integers(1, max_node_pages + 1)) * PAGE_SIZE)
+            ntok.append(int(rng.integers(1, max_node_pages + 1)) * page_size)
         for _ in range(int(rng.integers(1, fanout + 1))):
             grow(idx, level + 1)
 
@@ -405,9 +411,9 @@ def random_forest_workload(seed: int, *, n_roots: int = 2, depth: int = 3, fanou
             req_leaf.append(v)
     order = rng.permutation(len(req_leaf))
     req_leaf = [req_leaf[i] for i in order]
-    n_used = sum((t + 15) // 16 for t in ntok)
+    n_used = sum((t + page_size - 1) // page_size for t in ntok)
     num_pages = n_used + extra_pages
-    f = make_forest(parent, ntok, req_leaf, _perm(seed, num_pages))
+    f = make_forest(parent, ntok, req_leaf, _perm(seed, num_pages), page_size)
     q_len = None
     if mode == "prefill":
         # new tokens = the request's last node; everything above it is the cached prefix

@@ -160,17 +160,17 @@ def test_oracle_cache_invariants_on_random_traces(seed):
 
 # ------------------------------------------------------------------ library against the oracle
 
-@pytest.mark.parametrize("seed", range(10))
-def test_library_cache_matches_oracle(seed):
+@pytest.mark.parametrize("seed,page", [(s, 16) for s in range(10)] + [(10, 32), (11, 32), (12, 64)])
+def test_library_cache_matches_oracle(seed, page):
     prompts, ops = random_trace(100 + seed, n_ops=400)
     n_pages = [16, 24, 40][seed % 3]
     order = np.random.default_rng(seed).permutation(n_pages).astype(np.int32) if seed % 2 else None
-    oc = OC.PrefixCache(n_pages, None if order is None else order.tolist())
+    oc = OC.PrefixCache(n_pages, None if order is None else order.tolist(), block=page)
     exp = replay(oc.acquire, oc.release, oc.unpin, prompts, ops)
-    pool = fake_pool(n_pages, 2, free_order=order)
+    pool = fake_pool(n_pages, 2, free_order=order, page_size=page)
     cache = hkv.kv_cache_create(pool)
     try:
-        got = replay(lambda t, p: hkv.kv_cache_acquire(cache, t, p), lambda p: hkv.kv_cache_release(cache, p),
+        got = replay(lambda t, p: hkv.kv_cache_acquire(cache, t, p, page), lambda p: hkv.kv_cache_release(cache, p),
                      lambda p: hkv.kv_cache_unpin(cache, p), prompts, ops)
         assert got == exp
         st = hkv.kv_cache_stats(cache)

@@ -48,9 +48,9 @@ def check_lse(got, exp, what="", tol=LSE_ABS):
 
 
 def both_pools(gpu, oracle, w):
-    hp = oracle.HostPool(w.num_pages, w.num_kv_heads, w.kv_dtype)
+    hp = oracle.HostPool(w.num_pages, w.num_kv_heads, w.kv_dtype, page_size=w.page_size)
     hp.fill_from(w)
-    dp = gpu.DevicePool(w.num_pages, w.num_kv_heads, w.kv_dtype)
+    dp = gpu.DevicePool(w.num_pages, w.num_kv_heads, w.kv_dtype, page_size=w.page_size)
     dp.fill_from(w)
     return hp, dp
 
@@ -60,10 +60,10 @@ def assert_pool_bytes_equal(hp, dp, w):
     used = np.zeros(w.num_pages, dtype=bool)
     for v in range(f.n_nodes):
         used[f.node_pages[f.page_begin[v]: f.page_begin[v] + f.n_pages[v]]] = True
-    H = w.num_kv_heads
+    H = w.num_kv_heads * (w.page_size // 16)          # scales per page: one per 16-token block and head
     for name in ("k", "v"):
-        g = getattr(dp, name).cpu().numpy().view(getattr(hp, name).dtype).reshape(w.num_pages, -1)
-        o = getattr(hp, name).reshape(w.num_pages, -1)
+        g = getattr(dp, name).cpu().numpy().view(np.uint8).reshape(w.num_pages, -1)      # bytes: NaN poison compares too
+        o = getattr(hp, name).view(np.uint8).reshape(w.num_pages, -1)
         assert np.array_equal(g, o), f"pool {name} bytes differ"     # poison included: untouched slots stay untouched
     if w.kv_dtype == wl.KV_FP8_E4M3:
         for name in ("k_scale", "v_scale"):
@@ -1112,3 +1112,135 @@ def test_workflow_decode_levels(gpu, oracle, shape):
         w = gpu.workflow_decode_workload(wf, calls, [1 + (7 * i) % 23 for i in range(len(calls))], 8, 2)
         assert w.forest.attended_tokens() > w.forest.unique_tokens()      # something is shared
         run_decode(gpu, oracle, w)
+
+
+# ------------------------------------------------------------------------------ pages of 32, 64, 128 tokens
+
+@pytest.mark.parametrize("kv_dtype", [wl.KV_BF16, wl.KV_FP8_E4M3, wl.KV_FP32])
+@pytest.mark.parametrize("P", [32, 64, 128])
+def test_larger_pages_pool_bytes_and_decode(gpu, oracle, P, kv_dtype):
+    """Pools whose pages hold 32, 64 or 128 tokens: what kv_pool_write leaves equals the oracle's pool bit
+    for bit (poison of untouched slots included), and tree decode over it meets the bound of its dtype."""
+    import torch
+    w = wl.random_forest_workload(300 + P, kv_dtype=kv_dtype, src_dtype="fp32" if kv_dtype == wl.KV_FP32 else "bf16",
+                                  num_q_heads=8, num_kv_heads=2, depth=3, fanout=3, max_node_pages=3, n_roots=2,
+                                  page_size=P)
+    hp, dp = both_pools(gpu, oracle, w)
+    assert_pool_bytes_equal(hp, dp, w)
+    exp_o, exp_l = oracle.run_workload(w, hp)
+    r = gpu.DecodeRunner(dp, w)
+    r.run()
+    torch.cuda.synchronize()
+    got_o, got_l = gpu.bf16_tensor_to_f64(r.out), r.lse.cpu().numpy()
+    if kv_dtype == wl.KV_FP32:
+        check_close_fp32(got_o, exp_o, w.name)
+        check_lse(got_l, exp_l, w.name, 1e-4)
+    else:
+        check_close(got_o, exp_o, w.name)
+        check_lse(got_l, exp_l, w.name)
+    r.close()
+    dp.close()
+
+
+@pytest.mark.parametrize("P", [32, 128])
+def test_larger_pages_appends_bit_exact(gpu, oracle, P):
+    """fp8 pool with P-token pages continued in ragged pieces that start inside pages and inside 16-token
+    blocks, with magnitudes that grow: codes and the per-block scales equal the oracle's."""
+    import torch
+    rng = np.random.default_rng(P)
+    H, T = 2, 2 * P + 21
+    amp = np.linspace(0.2, 5.0, T)[:, None, None]
+    k = wl.f32_to_bf16_bits((amp * rng.standard_normal((T, H, 128))).astype(np.float32))
+    v = wl.f32_to_bf16_bits((amp[::-1] * rng.standard_normal((T, H, 128))).astype(np.float32))
+    pages = np.array([3, 0, 4], dtype=np.int32)
+    hp = oracle.HostPool(5, H, oracle.FP8_E4M3, page_size=P)
+    dp = gpu.DevicePool(5, H, oracle.FP8_E4M3, page_size=P)
+    cuts = [0, 5, 16, 21, P + 3, P + 4, 2 * P - 1, T]
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        hp.write(pages[a // P:], a % P, k[a:b], v[a:b])
+        dp.write(pages[a // P:], a % P, gpu.to_device_bits(k[a:b]), gpu.to_device_bits(v[a:b]))
+    torch.cuda.synchronize()
+    assert np.array_equal(dp.k.cpu().numpy(), hp.k) and np.array_equal(dp.v.cpu().numpy(), hp.v)   # poison included
+    n_blk = (T + 15) // 16
+    blocks = np.array([pages[b * 16 // P] * (P // 16) + (b * 16 % P) // 16 for b in range(n_blk)])
+    for name in ("k_scale", "v_scale"):
+        g = getattr(dp, name).cpu().numpy().reshape(-1, H)[blocks]
+        o = getattr(hp, name).reshape(-1, H)[blocks]
+        assert np.array_equal(g.view(np.uint32), o.view(np.uint32)), name
+    dp.close()
+
+
+@pytest.mark.parametrize("kv_dtype", [wl.KV_BF16, wl.KV_FP8_E4M3])
+@pytest.mark.parametrize("P", [32, 64])
+def test_larger_pages_decode_nodes_that_end_inside_a_page(gpu, oracle, P, kv_dtype):
+    w = wl.random_forest_workload(310 + P, kv_dtype=kv_dtype, num_q_heads=8, num_kv_heads=2, depth=4, fanout=3,
+                                  max_node_pages=3, n_roots=2, page_size=P, ragged_internal=True)
+    run_decode(gpu, oracle, w)
+    run_decode(gpu, oracle, w, one_shot=True)
+
+
+@pytest.mark.parametrize("kv_dtype", [wl.KV_BF16, wl.KV_FP8_E4M3, wl.KV_FP32])
+@pytest.mark.parametrize("P", [32, 128])
+def test_larger_pages_prefill(gpu, oracle, P, kv_dtype):
+    import torch
+    w = wl.random_forest_workload(320 + P, mode="prefill", kv_dtype=kv_dtype,
+                                  src_dtype="fp32" if kv_dtype == wl.KV_FP32 else "bf16", num_q_heads=8, num_kv_heads=2,
+                                  depth=3, fanout=2, max_node_pages=3, n_roots=2, page_size=P)
+    if kv_dtype != wl.KV_FP32:
+        run_prefill(gpu, oracle, w)
+        run_prefill(gpu, oracle, w, one_shot=True)
+        return
+    hp, dp = both_pools(gpu, oracle, w)
+    exp_o, exp_l = oracle.run_workload(w, hp)
+    r = gpu.PrefillRunner(dp, w)
+    r.run()
+    torch.cuda.synchronize()
+    check_close_fp32(gpu.bf16_tensor_to_f64(r.out), exp_o, w.name)
+    check_lse(r.lse.cpu().numpy(), exp_l, w.name, 1e-4)
+    r.close()
+    dp.close()
+
+
+@pytest.mark.parametrize("kv_dtype", [wl.KV_BF16, wl.KV_FP8_E4M3])
+def test_larger_pages_copy_on_write(gpu, oracle, kv_dtype):
+    """Fork inside a partially filled 64-token page: the private copy carries all four 16-token blocks of
+    the page and, for fp8, their four scales per head."""
+    import torch
+    from paper_2603_16104_amd import binding as hkv
+    P, H, n_pages = 64, 2, 6
+    rng = np.random.default_rng(33)
+    mk = lambda n, amp=1.0: wl.f32_to_bf16_bits((amp * rng.standard_normal((n, H, 128))).astype(np.float32))
+    parent, cont_a, cont_b = (mk(100), mk(100)), (mk(9), mk(9)), (mk(20, 3.0), mk(20, 1.5))
+    hp = oracle.HostPool(n_pages, H, kv_dtype, page_size=P)
+    dp = gpu.DevicePool(n_pages, H, kv_dtype, page_size=P)
+    dev = lambda kv: (gpu.to_device_bits(kv[0]), gpu.to_device_bits(kv[1]))
+    base = hkv.kv_pool_alloc(dp.handle, 2)
+    hp.write(base, 0, *parent)
+    dp.write(base, 0, *dev(parent))
+    hkv.kv_pool_retain(dp.handle, base)
+    pb = hkv.kv_pool_copy_on_write(dp.handle, base[1:])
+    pa = hkv.kv_pool_copy_on_write(dp.handle, base[1:])
+    assert (list(pb), list(pa)) == ([2], [1])
+    hp.copy_page(1, 2)
+    for ids, c in ((pa, cont_a), (pb, cont_b)):
+        hp.write(ids, 100 - P, *c)
+        dp.write(ids, 100 - P, *dev(c))
+    torch.cuda.synchronize()
+    assert np.array_equal(dp.k.cpu().numpy().view(hp.k.dtype), hp.k) and np.array_equal(dp.v.cpu().numpy().view(hp.v.dtype), hp.v)
+    if kv_dtype == wl.KV_FP8_E4M3:
+        for name in ("k_scale", "v_scale"):
+            g = getattr(dp, name).cpu().numpy().reshape(n_pages, -1)[:3]
+            o = getattr(hp, name).reshape(n_pages, -1)[:3]
+            written = np.isfinite(o)                                   # blocks no token reached keep their poison
+            assert np.array_equal(np.isfinite(g), written) and np.array_equal(g[written].view(np.uint32), o[written].view(np.uint32)), name
+    f = wl.make_forest([-1, 0, 0], [64, 45, 56], [1, 2], np.array([0, 1, 2], dtype=np.int32), P)
+    w = wl.Workload(name="forked64", num_q_heads=8, num_kv_heads=H, kv_dtype=kv_dtype, num_pages=n_pages, seed=3,
+                    forest=f, mode="decode")
+    exp_o, exp_l = oracle.run_workload(w, hp)
+    r = gpu.DecodeRunner(dp, w)
+    r.run()
+    torch.cuda.synchronize()
+    check_close(gpu.bf16_tensor_to_f64(r.out), exp_o, "forked64")
+    check_lse(r.lse.cpu().numpy(), exp_l, "forked64")
+    r.close()
+    dp.close()

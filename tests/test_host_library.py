@@ -43,8 +43,12 @@ def test_library_exports_every_declared_symbol():
 
 def test_pool_create_validation():
     with pytest.raises(hkv.HkvError) as e:
-        hkv.kv_pool_create(8, 2, hkv.BF16, FAKE_K, FAKE_V, page_size=32)
+        hkv.kv_pool_create(8, 2, hkv.BF16, FAKE_K, FAKE_V, page_size=48)
     assert e.value.code == hkv.ESHAPE
+    for ps in (16, 32, 64, 128):
+        pool = hkv.kv_pool_create(8, 2, hkv.BF16, FAKE_K, FAKE_V, page_size=ps)
+        assert hkv.kv_pool_page_size(pool) == ps
+        hkv.kv_pool_destroy(pool)
     with pytest.raises(hkv.HkvError) as e:
         hkv.kv_pool_create(8, 2, hkv.BF16, FAKE_K, FAKE_V, head_dim=64)
     assert e.value.code == hkv.ESHAPE
@@ -464,3 +468,101 @@ def test_token_level_inputs_are_a_function_of_token_and_position():
     assert abs(float(x.mean())) < 0.01 and abs(float(x.std()) - 1.0) < 0.01 and float(np.abs(x).max()) <= 2 * np.sqrt(3.0)
     prompts = wl.shared_prefix_prompts(3)
     assert len({tuple(p[:40]) for p in prompts}) <= 2          # at most two distinct system prompts
+
+
+# ------------------------------------------------------------------------------ pages of 32, 64, 128 tokens
+
+def _as_16_token_forest(f, P):
+    """The same forest over 16-token pages: page p of P = 16 S tokens is the blocks p S .. p S + S - 1."""
+    S = P // 16
+    pages, begin, count = [], [], []
+    for v in range(f.n_nodes):
+        nb = (int(f.n_tokens[v]) + 15) // 16
+        begin.append(len(pages))
+        count.append(nb)
+        pages += [int(f.node_pages[f.page_begin[v] + b // S]) * S + b % S for b in range(nb)]
+    return wl.PrefixForest(f.parent, f.n_tokens, np.asarray(begin, dtype=np.int32), np.asarray(count, dtype=np.int32),
+                           np.asarray(pages, dtype=np.int32), f.req_leaf)
+
+
+@pytest.mark.parametrize("P", [32, 64, 128])
+def test_flatten_with_larger_pages_bit_exact_against_oracle(oracle, P):
+    for seed in range(130, 134):
+        f = wl.random_forest_workload(seed, depth=4, fanout=3, n_roots=2, page_size=P).forest
+        mp = max(1, f.max_pages_per_req()) + 1
+        got = hkv.prefix_tree_flatten(f.nodes, f.node_pages, f.req_leaf, mp, P)
+        exp = oracle.flatten_tree(f.nodes, f.node_pages, f.req_leaf, mp, P)
+        for g, e in zip(got, exp):
+            assert np.array_equal(g, e)
+        with pytest.raises(hkv.HkvError) as e:          # page counts fit only the page size they were made for
+            hkv.prefix_tree_flatten(f.nodes, f.node_pages, f.req_leaf, mp, 16)
+        assert e.value.code == hkv.ETREE
+    with pytest.raises(hkv.HkvError) as e:
+        hkv.prefix_tree_flatten(f.nodes, f.node_pages, f.req_leaf, mp, 48)
+    assert e.value.code == hkv.ESHAPE
+
+
+@pytest.mark.parametrize("kv_dtype", [wl.KV_BF16, wl.KV_FP8_E4M3])
+@pytest.mark.parametrize("P", [32, 64, 128])
+def test_plans_over_larger_pages_equal_plans_over_their_16_token_blocks(oracle, P, kv_dtype):
+    """The planners work on 16-token blocks: a forest over P-token pages gives the work items and tiles
+    of the same forest written over the blocks those pages consist of."""
+    S = P // 16
+    for seed, ragged_internal in ((140, False), (141, False), (142, True)):
+        w = wl.random_forest_workload(seed, depth=4, fanout=3, n_roots=2, max_node_pages=6, page_size=P,
+                                      kv_dtype=kv_dtype, ragged_internal=ragged_internal)
+        f, f16 = w.forest, _as_16_token_forest(w.forest, P)
+        big, small = fake_pool(w.num_pages, w.num_kv_heads, kv_dtype, page_size=P), fake_pool(w.num_pages * S, w.num_kv_heads, kv_dtype)
+        a = hkv.hkv_decode_plan_create(big, f.nodes, f.node_pages, f.req_leaf, w.num_q_heads, hkv.PLAN_HOST_ONLY)
+        b = hkv.hkv_decode_plan_create(small, f16.nodes, f16.node_pages, f16.req_leaf, w.num_q_heads, hkv.PLAN_HOST_ONLY)
+        assert np.array_equal(hkv.hkv_decode_plan_items(a), hkv.hkv_decode_plan_items(b))
+        assert np.array_equal(hkv.hkv_decode_plan_part_counts(a, f.n_req), hkv.hkv_decode_plan_part_counts(b, f.n_req))
+        assert hkv.hkv_decode_plan_workspace_bytes(a) == hkv.hkv_decode_plan_workspace_bytes(b)
+        hkv.hkv_decode_plan_destroy(a)
+        hkv.hkv_decode_plan_destroy(b)
+        if not ragged_internal:
+            wp = wl.random_forest_workload(seed, depth=4, fanout=3, n_roots=2, max_node_pages=6, page_size=P,
+                                           kv_dtype=kv_dtype, mode="prefill")
+            fp = wp.forest
+            mp = max(1, fp.max_pages_per_req())
+            bt, kv_len, *_ = oracle.flatten_tree(fp.nodes, fp.node_pages, fp.req_leaf, mp, P)
+            bt16 = np.where(bt[:, :, None] >= 0, bt[:, :, None] * S + np.arange(S)[None, None, :], 0).reshape(fp.n_req, mp * S)
+            a = hkv.hkv_prefill_plan_create(big, wp.cu_q(), np.maximum(bt, 0), kv_len, wp.num_q_heads, hkv.PLAN_HOST_ONLY)
+            b = hkv.hkv_prefill_plan_create(small, wp.cu_q(), bt16.astype(np.int32), kv_len, wp.num_q_heads, hkv.PLAN_HOST_ONLY)
+            assert np.array_equal(hkv.hkv_prefill_plan_tiles(a), hkv.hkv_prefill_plan_tiles(b))
+            assert hkv.hkv_prefill_plan_workspace_bytes(a) == hkv.hkv_prefill_plan_workspace_bytes(b)
+            hkv.hkv_prefill_plan_destroy(a)
+            hkv.hkv_prefill_plan_destroy(b)
+        hkv.kv_pool_destroy(big)
+        hkv.kv_pool_destroy(small)
+
+
+def test_larger_pages_argument_checks():
+    pool = fake_pool(8, page_size=64)
+    # a parent of 32 tokens ends inside a 64-token page: fine for the bf16 decode plan, ETREE for flat tables
+    nodes = np.array([[-1, 0, 1, 32], [0, 1, 1, 70]], dtype=np.int32)
+    with pytest.raises(hkv.HkvError) as e:              # 70 tokens need two 64-token pages
+        hkv.hkv_decode_plan_create(pool, nodes, [0, 1], [1], 8, hkv.PLAN_HOST_ONLY)
+    assert e.value.code == hkv.ETREE
+    nodes[1, 2] = 2
+    plan = hkv.hkv_decode_plan_create(pool, nodes, [0, 1, 2], [1], 8, hkv.PLAN_HOST_ONLY)
+    hkv.hkv_decode_plan_destroy(plan)
+    with pytest.raises(hkv.HkvError) as e:
+        hkv.prefix_tree_flatten(nodes, [0, 1, 2], [1], 4, 64)
+    assert e.value.code == hkv.ETREE
+    with pytest.raises(hkv.HkvError) as e:              # page id beyond the pool's 8 pages
+        hkv.hkv_decode_plan_create(pool, nodes, [0, 1, 8], [1], 8, hkv.PLAN_HOST_ONLY)
+    assert e.value.code == hkv.ERANGE
+    with pytest.raises(hkv.HkvError) as e:              # first_slot must lie inside the first page
+        hkv.kv_pool_write(pool, [0, 1], 64, 4, 0x50000, 0x60000, stream=0)
+    assert e.value.code == hkv.EINVAL
+    with pytest.raises(hkv.HkvError) as e:              # slot 60 + 10 tokens reach into a second page: its id is checked
+        hkv.kv_pool_write(pool, [0, 9], 60, 10, 0x50000, 0x60000, stream=0)
+    assert e.value.code == hkv.ERANGE
+    # prefill: a request of 130 tokens needs three 64-token pages
+    with pytest.raises(hkv.HkvError) as e:
+        hkv.hkv_prefill_plan_create(pool, [0, 10], np.zeros((1, 2), dtype=np.int32), [130], 8, hkv.PLAN_HOST_ONLY)
+    assert e.value.code == hkv.ENOMEM
+    plan = hkv.hkv_prefill_plan_create(pool, [0, 10], np.array([[0, 1, 2]], dtype=np.int32), [130], 8, hkv.PLAN_HOST_ONLY)
+    hkv.hkv_prefill_plan_destroy(plan)
+    hkv.kv_pool_destroy(pool)

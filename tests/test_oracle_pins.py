@@ -766,3 +766,79 @@ def test_drafted_token_masks_equal_one_node_per_drafted_token(oracle):
     od, ld = oracle.attn_decode_tree(pa, q, nodes_a, np.array([0, 1] + leaf_pages, dtype=np.int32), [1] * T, 0.1,
                                      leaf_visible=[ctx_len + t + 1 for t in range(T)])
     assert np.array_equal(oc, od) and np.array_equal(lc, ld)
+
+
+# ------------------------------------------------------------------ pages of 32, 64 and 128 tokens
+
+@pytest.mark.parametrize("dtype_name", ["BF16", "FP8_E4M3", "FP32"])
+@pytest.mark.parametrize("P", [32, 64, 128])
+def test_larger_pages_are_runs_of_16_token_blocks(oracle, dtype_name, P):
+    """A page of P = 16 S tokens is the S consecutive 16-token blocks p S .. p S + S - 1 of the same
+    buffers: writing a sequence through P-token pages [p0, p1, ..] leaves, bit for bit, what writing it
+    through the 16-token pages [p0 S, p0 S + 1, .., p1 S, ..] leaves (the 16-token format is pinned above),
+    in one piece and in appended pieces that start inside a page and inside a block."""
+    dtype = getattr(oracle, dtype_name)
+    rng = np.random.default_rng(P)
+    S, H, n_big = P // 16, 2, 5
+    T = 2 * P + 21
+    amp = np.linspace(0.2, 5.0, T)[:, None, None]             # growing magnitudes: fp8 scales rise on appends
+    kf = (amp * rng.standard_normal((T, H, D))).astype(np.float32)
+    vf = (amp[::-1] * rng.standard_normal((T, H, D))).astype(np.float32)
+    k, v = (kf, vf) if dtype == oracle.FP32 else (wl.f32_to_bf16_bits(kf), wl.f32_to_bf16_bits(vf))
+    big = np.array([3, 0, 4], dtype=np.int32)
+    small = (big[:, None] * S + np.arange(S)[None, :]).reshape(-1).astype(np.int32)
+    for cuts in ([0, T], [0, 5, 16, 21, P + 3, P + 4, 2 * P - 1, T]):
+        a_pool = oracle.HostPool(n_big, H, dtype, page_size=P)
+        b_pool = oracle.HostPool(n_big * S, H, dtype)
+        for a, b in zip(cuts[:-1], cuts[1:]):
+            a_pool.write(big[a // P:], a % P, k[a:b], v[a:b])
+            b_pool.write(small[a // 16:], a % 16, k[a:b], v[a:b])
+        for name in ("k", "v") + (("k_scale", "v_scale") if dtype == oracle.FP8_E4M3 else ()):
+            x, y = getattr(a_pool, name), getattr(b_pool, name)
+            assert x.shape == y.shape and np.array_equal(x.view(np.uint8), y.view(np.uint8)), (name, cuts)
+    # and attention reads them back the same way: a P-page table against the equivalent 16-token table
+    q = rng.standard_normal((1, 4, D)).astype(np.float32)
+    q = q if dtype == oracle.FP32 else wl.f32_to_bf16_bits(q)
+    o1, l1 = oracle.attn_decode(a_pool, q, big[None, :], np.array([T], dtype=np.int32), 0.09)
+    o2, l2 = oracle.attn_decode(b_pool, q, small[None, :], np.array([T], dtype=np.int32), 0.09)
+    assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
+    a_pool.copy_page(3, 1)
+    big2 = np.array([1, 0, 4], dtype=np.int32)
+    o3, l3 = oracle.attn_decode(a_pool, q, big2[None, :], np.array([T], dtype=np.int32), 0.09)
+    assert np.array_equal(o1, o3) and np.array_equal(l1, l3)
+
+
+@pytest.mark.parametrize("P", [32, 64])
+@pytest.mark.parametrize("seed,mode", [(5, "decode"), (6, "prefill")])
+def test_brute_force_small_forests_with_larger_pages(oracle, P, seed, mode):
+    w = wl.random_forest_workload(seed, mode=mode, page_size=P, max_node_pages=2, depth=3, fanout=2)
+    assert w.page_size == P and (w.forest.n_pages == (w.forest.n_tokens + P - 1) // P).all()
+    got_o, got_l = oracle.run_workload(w)
+    exp_o, exp_l = brute_workload(w)
+    assert np.abs(got_o - exp_o).max() <= 1e-12
+    fin = np.isfinite(exp_l)
+    assert np.array_equal(np.isneginf(got_l), np.isneginf(exp_l)) and np.abs(got_l[fin] - exp_l[fin]).max() <= 1e-12
+
+
+@pytest.mark.parametrize("P", [32, 128])
+def test_tree_walk_with_larger_pages_and_ragged_internal_nodes(oracle, P):
+    w = wl.random_forest_workload(77, page_size=P, max_node_pages=2, depth=3, fanout=2, ragged_internal=True)
+    f = w.forest
+    has_child = np.zeros(f.n_nodes, dtype=bool)
+    has_child[f.parent[f.parent >= 0]] = True
+    assert (has_child & (f.n_tokens % P != 0)).any()
+    got_o, got_l = oracle.run_workload(w)
+    exp_o, exp_l = brute_workload(w)
+    assert np.abs(got_o - exp_o).max() <= 1e-12
+
+
+@pytest.mark.parametrize("P", [32, 64])
+def test_flatten_tree_with_larger_pages_against_python_walk(oracle, P):
+    w = wl.random_forest_workload(27, depth=4, fanout=3, n_roots=3, page_size=P)
+    f = w.forest
+    mp = max(1, f.max_pages_per_req()) + 2
+    got = oracle.flatten_tree(f.nodes, f.node_pages, f.req_leaf, mp, P)
+    for g, e in zip(got, py_flatten(f, mp)):
+        assert np.array_equal(g, e)
+    with pytest.raises(ValueError):                # the same forest is malformed for another page size
+        oracle.flatten_tree(f.nodes, f.node_pages, f.req_leaf, mp, 16)
