@@ -247,7 +247,20 @@ int lse_merge_dense(const float *o_parts, const float *lse_parts, const int32_t 
  * A plan holds the flattened topology (work list, page ids, merge CSR) on host and device so
  * that a serving loop pays for the tree walk once per topology, not once per step.
  */
-enum { HKV_PLAN_HOST_ONLY = 1 /* build and validate on the host, allocate nothing on the device */ };
+enum {
+    HKV_PLAN_HOST_ONLY = 1, /* build and validate on the host, allocate nothing on the device */
+    /* Decode plans over fp8 pools only (ESHAPE otherwise): both products run on the fp8 matrix
+     * instruction.  K and V codes enter as they are; a query row is split into two e4m3 terms
+     * (after a power-of-two scaling of the row; exact for every element down to 2^-10 of the
+     * row's largest), a probability, scaled by its block's V scale relative to the largest V scale
+     * of the 64-token step it belongs to, into two e4m3 terms that carry 8 significant bits, as the
+     * bf16 value of the default path does.  Same speed and the same error bounds as the default
+     * path, with one condition the default path does not have: a weight below about 2^-14 of the
+     * step's largest weight-times-scale loses relative precision (e4m3 has no more range), which
+     * shows only if the V scales of the four 16-token blocks of one step differ by more than about
+     * 2^7 while the attention weight sits on the blocks with the small scales. */
+    HKV_PLAN_FP8_MATRIX = 2
+};
 
 /* nodes, node_pages, req_leaf: host.  Validates the forest (ETREE/ERANGE, page ids against the
  * pool), builds the work list and uploads it (blocking).  ESHAPE unless num_q_heads is a

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libheliumkv.so")
 
 OK, EINVAL, ERANGE, ESHAPE, ETREE, ENOMEM, EHIP = 0, -1, -2, -3, -4, -5, -6
 BF16, FP8_E4M3, FP32 = 0, 1, 2
-PLAN_HOST_ONLY = 1
+PLAN_HOST_ONLY, PLAN_FP8_MATRIX = 1, 2
 PAGE_SIZE, HEAD_DIM = 16, 128
 
 EXPORTS = [

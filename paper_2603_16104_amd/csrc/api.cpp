@@ -76,6 +76,8 @@ struct hkv_decode_plan {
     void *dev = nullptr;
     DecodeItem *d_items = nullptr;
     int32_t n_single = 0;  // items [0, n_single) run one per workgroup, the rest four per workgroup
+    int32_t n_stages = 3;  // LDS stages of 16 KiB per workgroup of the per-node kernel
+    bool fp8_matrix = false;  // fp8 pools: both products on the fp8 matrix instruction (HKV_PLAN_FP8_MATRIX)
     int32_t *d_pages = nullptr, *d_node_req_idx = nullptr, *d_part_count = nullptr;
     bool profiling = false, profiled_run = false, node_only = false;
     hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};  // begin/end of the node kernel, begin/end of the merge
@@ -598,6 +600,9 @@ static void plan_items(hkv_decode_plan &pl) {
         pl.items.push_back(p.it);
         pl.n_single += !packable(p);
     }
+    // LDS stages per workgroup.  The fp8 kernel runs two workgroups per CU (registers), so each may own
+    // half of the CU's 160 KiB: five stages, four steps of a shared item in flight instead of two.
+    pl.n_stages = std::min(5, std::max(3, env_int("HKV_DECODE_STAGES", pl.pool->d.dtype == HKV_FP8_E4M3 ? 5 : 3)));
     pl.part_count.assign(pl.n_req, 0);
     pl.max_parts = 1;
     for (int r = 0; r < pl.n_req; ++r) {
@@ -627,6 +632,8 @@ static int upload_decode_plan(hkv_decode_plan &pl) {
     HKV_HIP(up(pl.d_pages, pl.node_pages.data(), sizeof(int32_t) * pl.node_pages.size()));
     HKV_HIP(up(pl.d_node_req_idx, pl.node_req_idx.data(), sizeof(int32_t) * pl.node_req_idx.size()));
     HKV_HIP(up(pl.d_part_count, pl.part_count.data(), sizeof(int32_t) * pl.part_count.size()));
+    // here, so that the first run may already be under graph capture
+    HKV_HIP(prepare_decode_launch(pl.pool->d.dtype == HKV_BF16 ? 0 : pl.fp8_matrix ? 2 : 1));
     return HKV_OK;
 }
 
@@ -670,6 +677,8 @@ extern "C" int hkv_decode_plan_create(hkv_pool *pool, const hkv_node *nodes, int
     const int Hkv = pool->d.num_kv_heads;
     if (num_q_heads <= 0 || num_q_heads % Hkv || num_q_heads / Hkv > 16)
         return fail(HKV_ESHAPE, "hkv_decode_plan_create: %d query heads over %d KV heads", num_q_heads, Hkv);
+    if ((flags & HKV_PLAN_FP8_MATRIX) && pool->d.dtype != HKV_FP8_E4M3)
+        return fail(HKV_ESHAPE, "hkv_decode_plan_create: HKV_PLAN_FP8_MATRIX needs an fp8 pool");
     // The per-node kernels read every node through its own page list, so nodes may end inside a page
     // anywhere; the full-precision path walks flat block tables and keeps the whole-page rule.
     if (int rc = validate_forest(nodes, n_nodes, node_pages, n_node_pages, "hkv_decode_plan_create",
@@ -688,6 +697,7 @@ extern "C" int hkv_decode_plan_create(hkv_pool *pool, const hkv_node *nodes, int
     pl->n_req = n_req;
     pl->num_q_heads = num_q_heads;
     pl->group = num_q_heads / Hkv;
+    pl->fp8_matrix = pool->d.dtype == HKV_FP8_E4M3 && ((flags & HKV_PLAN_FP8_MATRIX) || env_int("HKV_FP8_MATRIX", 0) == 1);
     if (int rc = build_node_req_csr(nodes, n_nodes, req_leaf, n_req, pl->node_req_indptr, pl->node_req_idx,
                                     "hkv_decode_plan_create")) {
         delete pl;
@@ -895,7 +905,8 @@ extern "C" int attn_decode_plan_run(hkv_decode_plan *plan, const void *q, float 
     if (!plan->items.empty()) {
         DecodeLaunch a{view_of(plan->pool), q, plan->d_items, plan->d_pages, plan->d_node_req_idx, o_parts, lse_parts,
                        (int32_t)plan->items.size(), plan->num_q_heads, plan->max_parts, scale, nullptr,
-                       plan->d_row_leaf, plan->d_row_limit, plan->d_row_mask, plan->n_single};
+                       plan->d_row_leaf, plan->d_row_limit, plan->d_row_mask, plan->n_single, plan->n_stages,
+                       plan->fp8_matrix ? 1 : 0};
         HKV_HIP(launch_decode(a, s, prof ? plan->ev[0] : nullptr, prof ? plan->ev[1] : nullptr));
     }
     if (plan->node_only) return HKV_OK;

@@ -45,7 +45,7 @@ constexpr int kWaves = 4;
 constexpr int kThreads = kWaves * 64;
 constexpr int kORow = kHeadDim + 4;  // padded LDS row: 16 rows x 132 floats do not collide in banks
 constexpr int kStageBytes = 16 * 1024;  // one step's 16 operand fragments x 64 lanes x 16 bytes
-constexpr int kStages = 3;
+constexpr int kMinStages = 3, kMaxStages = 5;  // the launch picks how many stages a workgroup owns
 constexpr int kIdRegs = 2;  // LDS-staged items hold their page ids in registers: at most 64*kIdRegs pages
 static_assert(kMaxSharedItemTokens <= 64 * kIdRegs * kPage, "planner limit exceeds what the kernel can index");
 
@@ -64,13 +64,46 @@ struct Traits<0> {  // bf16 pool
     static constexpr int kBlockBytes = kBlockElems * 2;
 };
 template <>
-struct Traits<1> {  // fp8 e4m3 pool
+struct Traits<1> {  // fp8 e4m3 pool, codes widened to bf16 in registers (exact)
     static constexpr int kTokBlock = 64;
     static constexpr int kBlockBytes = kBlockElems;
 };
+template <>
+struct Traits<2> : Traits<1> {};  // fp8 e4m3 pool, codes fed to the fp8 matrix instruction as they are
 
 __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+// fp8 matrix instruction: A and B hold 8 e4m3 codes each (k = 8 * (lane / 16) + byte), the lane
+// layout of the operands and of the result is that of the bf16 instruction above.
+__device__ __forceinline__ f32x4 mfma16_fp8(uint32_t a_lo, uint32_t a_hi, long b, f32x4 c) {
+    const long a = (long)(((unsigned long)a_hi << 32) | a_lo);
+    return __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a, b, c, 0, 0, 0);
+}
+
+// Two-term e4m3 representation of eight floats x[0..7] (|x| <= 448): hi = fp8(x), lo = fp8(x - hi).
+// With 4 significant bits per term the pair carries 8, as many as a bf16 value.
+__device__ __forceinline__ void split_fp8x8(const float (&x)[8], long &hi, long &lo) {
+    typedef __attribute__((ext_vector_type(2))) float f32x2;
+    uint32_t h[2] = {0u, 0u}, l[2] = {0u, 0u};
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {  // dword j holds elements 4j .. 4j+3: two in the lower half, two in the upper
+        h[j] = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(x[4 * j], x[4 * j + 1], (int)h[j], false);
+        h[j] = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(x[4 * j + 2], x[4 * j + 3], (int)h[j], true);
+        const f32x2 b0 = __builtin_amdgcn_cvt_pk_f32_fp8((int)h[j], false), b1 = __builtin_amdgcn_cvt_pk_f32_fp8((int)h[j], true);
+        l[j] = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(x[4 * j] - b0[0], x[4 * j + 1] - b0[1], (int)l[j], false);
+        l[j] = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(x[4 * j + 2] - b1[0], x[4 * j + 3] - b1[1], (int)l[j], true);
+    }
+    hi = (long)(((unsigned long)h[1] << 32) | h[0]);
+    lo = (long)(((unsigned long)l[1] << 32) | l[0]);
+}
+
+// Keeps the first n (of 8) codes of an operand, zeroes the rest (garbage slots may hold NaN codes).
+__device__ __forceinline__ void zero_fp8_from(uint32_t &w0, uint32_t &w1, int n) {
+    const unsigned long keep = n >= 8 ? ~0ul : n <= 0 ? 0ul : ((1ul << (8 * n)) - 1ul);
+    w0 &= (uint32_t)keep;
+    w1 &= (uint32_t)(keep >> 32);
 }
 
 __device__ __forceinline__ bf16x8 zero_bf16_from(bf16x8 v, int first_bad) {
@@ -97,7 +130,7 @@ __device__ __forceinline__ void load_step_pages(StepPages<DT> &sp, const DecodeL
 #pragma unroll
     for (int i = 0; i < StepPages<DT>::N; ++i) {
         sp.id[i] = a.pages[it.page_off + min(blk * StepPages<DT>::N + i, last_page)];
-        if constexpr (DT == 1) {
+        if constexpr (DT != 0) {
             sp.ksc[i] = a.pool.k_scale[(size_t)sp.id[i] * a.pool.num_kv_heads + it.kv_head];
             sp.vsc[i] = a.pool.v_scale[(size_t)sp.id[i] * a.pool.num_kv_heads + it.kv_head];
         }
@@ -119,14 +152,14 @@ __device__ __forceinline__ T pick(const T (&v)[4], int sel) {
 
 template <int DT>
 __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(DecodeLaunch a) {
-    // LDS: a ring of kStages K/V stages for items shared by many query rows; items with at most 16
+    // LDS: a ring of a.n_stages K/V stages for items shared by many query rows; items with at most 16
     // rows use the same bytes for the cross-wavefront combine instead.
-    __shared__ __attribute__((aligned(16))) char smem[kStages * kStageBytes];
+    extern __shared__ __attribute__((aligned(16))) char smem[];  // a.n_stages * kStageBytes
     float(*sO)[16][kORow] = reinterpret_cast<float(*)[16][kORow]>(smem);
     float(*sM)[16] = reinterpret_cast<float(*)[16]>(smem + sizeof(float) * kWaves * 16 * kORow);
     float(*sL)[16] = sM + kWaves;
     int *sPart = reinterpret_cast<int *>(sL + kWaves);  // partial index of each of the 16 rows
-    static_assert(sizeof(float) * (kWaves * 16 * kORow + 2 * kWaves * 16 + 16) <= kStages * kStageBytes, "LDS overlay");
+    static_assert(sizeof(float) * (kWaves * 16 * kORow + 2 * kWaves * 16 + 16) <= kMinStages * kStageBytes, "LDS overlay");
 
     constexpr int TB = Traits<DT>::kTokBlock;
     constexpr int NS = TB / 4;  // scores per lane (16 query rows x TB tokens over 64 lanes)
@@ -177,6 +210,35 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
         }
     };
     bf16x8 qf[4];
+    // DT == 2: the query row as two e4m3 terms per element, q * 2^e = hi + lo with the row's largest
+    // magnitude brought into [128, 256) by the power of two 2^e (exact for every element down to 2^-10
+    // of the largest; below that the second term is rounded to a multiple of 2^-9); q_unscale = 2^-e.
+    long qh[4], ql[4];
+    float q_unscale = 1.0f;
+    auto split_q = [&]() {
+        if constexpr (DT == 2) {
+            float qx[4][8];
+            float amax = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    qx[i][j] = (float)qf[i][j];
+                    amax = fmaxf(amax, fabsf(qx[i][j]));
+                }
+            amax = rows_max(amax);
+            // exponent field of the largest magnitude, kept where both 2^e and 2^-e are normal floats
+            const int ex = min(max((int)(__float_as_uint(amax) >> 23), 8), 254);
+            const float up = __uint_as_float((uint32_t)(261 - ex) << 23);  // 2^(7 - (ex - 127))
+            q_unscale = __uint_as_float((uint32_t)(ex - 7) << 23);        // its reciprocal
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) qx[i][j] *= up;
+                split_fp8x8(qx[i], qh[i], ql[i]);
+            }
+        }
+    };
     // Tokens of this item that this lane's query row may see (all of them unless the row is one of
     // several query tokens of a request and this is the node that holds the request's newest tokens).
     int lim = it.n_tokens;
@@ -206,6 +268,7 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
     for (int dt = 0; dt < 8; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     float m_run = -INFINITY;  // running maximum of the raw scores of this lane's row
     float l_run = 0.f;        // this lane's share of the row sum
+    uint32_t v_ref_bits = 0;  // DT == 2: bit pattern of the last step's v_ref (wavefront-uniform), 0 before the first
 
     const int n_blk = (it.n_tokens + TB - 1) / TB;
     const int last_page = (it.n_tokens - 1) >> 4;
@@ -253,7 +316,7 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
                 s[i] = sa[i];
                 s[4 + i] = sb[i];
             }
-        } else {
+        } else if constexpr (DT == 1) {
             const float ksc = pick(cur.ksc, g);
 #pragma unroll
             for (int t4 = 0; t4 < 4; ++t4) {
@@ -266,6 +329,23 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
                 }
 #pragma unroll
                 for (int i = 0; i < 4; ++i) s[t4 * 4 + i] = acc[i] * ksc;
+            }
+        } else {
+            // codes of K against the two terms of Q; the block scale and the row's 2^-e come afterwards
+            const float kq = pick(cur.ksc, g) * q_unscale;
+#pragma unroll
+            for (int t4 = 0; t4 < 4; ++t4) {
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks2 = 0; ks2 < 2; ++ks2) {
+                    const u32x4 w = kf[t4 * 2 + ks2];
+                    acc = mfma16_fp8(w[0], w[1], qh[ks2 * 2], acc);
+                    acc = mfma16_fp8(w[0], w[1], ql[ks2 * 2], acc);
+                    acc = mfma16_fp8(w[2], w[3], qh[ks2 * 2 + 1], acc);
+                    acc = mfma16_fp8(w[2], w[3], ql[ks2 * 2 + 1], acc);
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) s[t4 * 4 + i] = acc[i] * kq;
             }
         }
         if constexpr (MORE) {  // the K registers are free again; keep the request exactly here
@@ -302,35 +382,79 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
         const float alpha = fast_exp2(m_run * c - mc);
         float p[NS];
         float sum = 0.f;
+        if constexpr (DT != 2) {
 #pragma unroll
-        for (int j = 0; j < NS; ++j) {
-            p[j] = fast_exp2(__builtin_fmaf(s[j], c, -mc));
-            sum += p[j];
-        }
-        l_run = l_run * alpha + sum;
-        m_run = m_new;
-        if (__builtin_amdgcn_ballot_w64(alpha != 1.0f)) {
+            for (int j = 0; j < NS; ++j) {
+                p[j] = fast_exp2(__builtin_fmaf(s[j], c, -mc));
+                sum += p[j];
+            }
+            l_run = l_run * alpha + sum;
+            m_run = m_new;
+            if (__builtin_amdgcn_ballot_w64(alpha != 1.0f)) {
 #pragma unroll
-            for (int dt = 0; dt < 8; ++dt) o[dt] *= alpha;
+                for (int dt = 0; dt < 8; ++dt) o[dt] *= alpha;
+            }
+        } else {
+            // The second product runs on codes of V, so a token's weight carries its block's V scale:
+            // x = p * vs / v_ref * 2^8 <= 256, with v_ref the largest V scale of this step's four blocks
+            // rounded up to a power of two (o is kept in units of v_ref * 2^-8 and is rescaled whenever
+            // v_ref changes from one step to the next, in either direction).
+            uint32_t top = 0;  // largest V scale of the step; positive floats order like their bit patterns
+#pragma unroll
+            for (int i = 0; i < StepPages<DT>::N; ++i) top = max(top, __float_as_uint(cur.vsc[i]));
+            const uint32_t ref_new = max((top + 0x007FFFFFu) & 0x7F800000u, 0x00800000u);  // power of two, normal
+            const float grow = __uint_as_float(v_ref_bits) * __uint_as_float(0x7F000000u - ref_new);  // v_ref_old / v_ref_new
+            v_ref_bits = ref_new;
+            const float lv = fast_log2(pick(cur.vsc, g) * __uint_as_float(0x7F000000u - ref_new)) + 8.0f;
+#pragma unroll
+            for (int j = 0; j < NS; ++j) {
+                p[j] = fast_exp2(__builtin_fmaf(s[j], c, lv - mc));
+                sum += p[j];
+            }
+            l_run = l_run * alpha + sum * fast_exp2(-lv);
+            m_run = m_new;
+            const float alpha_o = alpha * grow;
+            if (__builtin_amdgcn_ballot_w64(alpha_o != 1.0f)) {
+#pragma unroll
+                for (int dt = 0; dt < 8; ++dt) o[dt] *= alpha_o;
+            }
         }
 
         // ---- O^T += V^T P^T
-        const float vs = (DT == 0) ? 1.0f : pick(cur.vsc, g);
+        if constexpr (DT != 2) {
+            const float vs = (DT == 0) ? 1.0f : pick(cur.vsc, g);
 #pragma unroll
-        for (int ks = 0; ks < NS / 8; ++ks) {
-            u32x4 pw;
+            for (int ks = 0; ks < NS / 8; ++ks) {
+                u32x4 pw;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) pw[j] = pack_bf16(p[ks * 8 + 2 * j] * vs, p[ks * 8 + 2 * j + 1] * vs);
-            const bf16x8 pb = as_bf16x8(pw);
+                for (int j = 0; j < 4; ++j) pw[j] = pack_bf16(p[ks * 8 + 2 * j] * vs, p[ks * 8 + 2 * j + 1] * vs);
+                const bf16x8 pb = as_bf16x8(pw);
 #pragma unroll
-            for (int dt = 0; dt < 8; ++dt) {
-                bf16x8 va;
-                if constexpr (DT == 0)
-                    va = as_bf16x8(vf[dt]);
-                else
-                    va = fp8x8_to_bf16x8(vf[dt][2 * ks], vf[dt][2 * ks + 1]);
-                if (tail) va = zero_bf16_from(va, first_bad - 8 * ks);  // garbage slots may hold NaN
-                o[dt] = mfma16(va, pb, o[dt]);
+                for (int dt = 0; dt < 8; ++dt) {
+                    bf16x8 va;
+                    if constexpr (DT == 0)
+                        va = as_bf16x8(vf[dt]);
+                    else
+                        va = fp8x8_to_bf16x8(vf[dt][2 * ks], vf[dt][2 * ks + 1]);
+                    if (tail) va = zero_bf16_from(va, first_bad - 8 * ks);  // garbage slots may hold NaN
+                    o[dt] = mfma16(va, pb, o[dt]);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int ks = 0; ks < NS / 8; ++ks) {
+                float x[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) x[j] = p[ks * 8 + j];
+                long ph, pl;
+                split_fp8x8(x, ph, pl);
+#pragma unroll
+                for (int dt = 0; dt < 8; ++dt) {
+                    uint32_t v0 = vf[dt][2 * ks], v1 = vf[dt][2 * ks + 1];
+                    if (tail) zero_fp8_from(v0, v1, first_bad - 8 * ks);  // garbage slots may hold NaN codes
+                    o[dt] = mfma16_fp8(v0, v1, ph, o[dt]);
+                    o[dt] = mfma16_fp8(v0, v1, pl, o[dt]);
+                }
             }
         }
         if constexpr (MORE) {  // the V registers are free again
@@ -345,7 +469,8 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
         const float l_row = rows_sum(l_run);
         if (row < rows) {
             // a row that saw no token of this item delivers the empty partial (o = 0, lse = -inf)
-            const float inv = l_row > 0.f ? 1.0f / l_row : 0.f;
+            float inv = l_row > 0.f ? 1.0f / l_row : 0.f;
+            if constexpr (DT == 2) inv *= __uint_as_float(v_ref_bits) * 0.00390625f;  // o is in units of v_ref * 2^-8
             const size_t part = (size_t)(req * a.num_q_heads + it.kv_head * G + row % G) * a.max_parts + it.part_slot;
             float *op = a.o_parts + part * kHeadDim + 4 * g;
 #pragma unroll
@@ -356,7 +481,8 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
 
     if (shared) {
         // ---- K/V staged in LDS, fetched once for all row tiles of the item (LDS-direct loads: the
-        // data in flight occupies no registers, so two further steps are kept in flight).  A stage
+        // data in flight occupies no registers, so n_stages - 1 steps are kept in flight: a step of
+        // such an item takes about a memory round trip divided by that number).  A stage
         // holds the 16 operand fragments of a step in lane order; wavefront w fetches fragments
         // w, 4+w (K) and 8+w, 12+w (V) with exactly the addresses the register path uses.
         const bool active = rt * 16 < rows;
@@ -368,7 +494,7 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
 #pragma unroll
         for (int r = 0; r < kIdRegs; ++r) {
             id_lane[r] = a.pages[it.page_off + min(lane + 64 * r, last_page)];
-            if constexpr (DT == 1) {
+            if constexpr (DT != 0) {
                 ksc_lane[r] = a.pool.k_scale[(size_t)id_lane[r] * Hkv + it.kv_head];
                 vsc_lane[r] = a.pool.v_scale[(size_t)id_lane[r] * Hkv + it.kv_head];
             }
@@ -388,16 +514,19 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
                         vv = vsc_lane[r];
                     }
                 sp.id[i] = __builtin_amdgcn_readlane(idv, lo);
-                if constexpr (DT == 1) {
+                if constexpr (DT != 0) {
                     sp.ksc[i] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, kv), lo));
                     sp.vsc[i] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, vv), lo));
                 }
             }
         };
+        const int n_stages = a.n_stages, n_ahead = n_stages - 1;
+        int issue_slot = 0, read_slot = 0;  // stage of the next step to request / to consume (step % n_stages)
         auto issue_stage = [&](int blk) {
             StepPages<DT> sp;
             step_pages(sp, blk);
-            char *stage = smem + (blk % kStages) * kStageBytes;
+            char *stage = smem + issue_slot * kStageBytes;
+            issue_slot = issue_slot + 1 == n_stages ? 0 : issue_slot + 1;
             const char *pk = kb + (size_t)pick(sp.id, k_sel) * page_stride;
             const char *pv = vb + (size_t)pick(sp.id, v_sel) * page_stride;
 #pragma unroll
@@ -416,8 +545,8 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
         const int req = load_req();
         load_q(qf, req);
         load_limit(req);
-        issue_stage(0);
-        if (n_blk > 1) issue_stage(1);
+        for (int i = 0; i < n_ahead && i < n_blk; ++i) issue_stage(i);
+        split_q();
         HKV_STAMP(1);
         // one step of the item; the last one is peeled off the loop: it alone waits for every load and
         // carries the end-of-item masking
@@ -425,18 +554,27 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
             constexpr bool LAST = decltype(last_tag)::value;
             StepPages<DT> cur;
             step_pages(cur, b);  // fp8 scales of this step
-            // this wavefront's share of step b has landed once at most the next step's 4 loads are pending
+            // this wavefront's share of step b has landed once at most the 4 loads of each later step
+            // requested so far are pending (loads complete in order)
             __builtin_amdgcn_sched_barrier(0);
-            if constexpr (LAST)
+            if constexpr (LAST) {
                 __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-            else
-                __builtin_amdgcn_s_waitcnt(vmcnt_imm(4));
+            } else {
+                const int later = min(n_ahead - 1, n_blk - 1 - b);  // >= 1 here; wavefront-uniform
+                if (later >= 3)
+                    __builtin_amdgcn_s_waitcnt(vmcnt_imm(12));
+                else if (later == 2)
+                    __builtin_amdgcn_s_waitcnt(vmcnt_imm(8));
+                else
+                    __builtin_amdgcn_s_waitcnt(vmcnt_imm(4));
+            }
             __builtin_amdgcn_s_barrier();  // everyone's share landed; everyone is done with step b-1
             __builtin_amdgcn_sched_barrier(0);
-            if (b + 2 < n_blk) issue_stage(b + 2);  // overwrites the stage of step b-1
+            if (b + n_ahead < n_blk) issue_stage(b + n_ahead);  // overwrites the stage of step b-1
             __builtin_amdgcn_sched_barrier(0);
+            const char *stage = smem + read_slot * kStageBytes + lane * 16;
+            read_slot = read_slot + 1 == n_stages ? 0 : read_slot + 1;
             if (active) {
-                const char *stage = smem + (b % kStages) * kStageBytes + lane * 16;
 #pragma unroll
                 for (int f = 0; f < 8; ++f) {
                     kf[f] = *reinterpret_cast<const u32x4 *>(stage + f * 1024);
@@ -467,6 +605,7 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
         load_q(qf, req);
         load_limit(req);
         load_step_pages<DT>(nxt, a, it, b + n_ts, last_page);  // clamped: always in bounds
+        split_q();
         HKV_STAMP(1);
         bool first = true;
         while (b + n_ts < n_blk) {
@@ -491,6 +630,11 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
 
     // combine the wavefronts that split the tokens of a row tile, normalise, write the partials
     const float l_row = rows_sum(l_run);
+    if constexpr (DT == 2) {  // o leaves the units of this wavefront's v_ref * 2^-8
+        const float unit = __uint_as_float(v_ref_bits) * 0.00390625f;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) o[dt] *= unit;
+    }
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt) *reinterpret_cast<f32x4 *>(&sO[wave][m][16 * dt + 4 * g]) = o[dt];
     if (g == 0) {
@@ -534,13 +678,37 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
 
 // With events, they are bound to the dispatch itself (begin and end of the kernel on the device), so
 // their difference is the kernel's duration without the gap to its neighbours in the queue.
+// More than 64 KiB of LDS per workgroup has to be allowed once per kernel and device.
+// variant: 0 bf16 pool, 1 fp8 pool (codes widened to bf16), 2 fp8 pool on the fp8 matrix instruction.
+hipError_t prepare_decode_launch(int32_t variant) {
+    static bool allowed[3][64] = {};
+    int dev = 0;
+    if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
+    if (variant < 0 || variant > 2) return hipErrorInvalidValue;
+    if (dev < 0 || dev >= 64 || allowed[variant][dev]) return hipSuccess;
+    const void *fn = variant == 0   ? reinterpret_cast<const void *>(decode_node_kernel<0>)
+                     : variant == 1 ? reinterpret_cast<const void *>(decode_node_kernel<1>)
+                                    : reinterpret_cast<const void *>(decode_node_kernel<2>);
+    if (hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxStages * kStageBytes);
+        e != hipSuccess)
+        return e;
+    allowed[variant][dev] = true;
+    return hipSuccess;
+}
+
 hipError_t launch_decode(const DecodeLaunch &a, hipStream_t s, hipEvent_t ev_begin, hipEvent_t ev_end) {
     if (a.n_items <= 0) return hipSuccess;
+    if (a.n_stages < kMinStages || a.n_stages > kMaxStages) return hipErrorInvalidValue;
+    const int variant = a.pool.dtype == 0 ? 0 : a.fp8_matrix ? 2 : 1;
+    if (hipError_t e = prepare_decode_launch(variant); e != hipSuccess) return e;
     const dim3 grid(a.n_single + (a.n_items - a.n_single + kWaves - 1) / kWaves);
-    if (a.pool.dtype == 0)
-        hipExtLaunchKernelGGL(decode_node_kernel<0>, grid, dim3(kThreads), 0, s, ev_begin, ev_end, 0, a);
+    const unsigned lds = (unsigned)a.n_stages * kStageBytes;
+    if (variant == 0)
+        hipExtLaunchKernelGGL(decode_node_kernel<0>, grid, dim3(kThreads), lds, s, ev_begin, ev_end, 0, a);
+    else if (variant == 1)
+        hipExtLaunchKernelGGL(decode_node_kernel<1>, grid, dim3(kThreads), lds, s, ev_begin, ev_end, 0, a);
     else
-        hipExtLaunchKernelGGL(decode_node_kernel<1>, grid, dim3(kThreads), 0, s, ev_begin, ev_end, 0, a);
+        hipExtLaunchKernelGGL(decode_node_kernel<2>, grid, dim3(kThreads), lds, s, ev_begin, ev_end, 0, a);
     return hipGetLastError();
 }
 

@@ -71,6 +71,12 @@ struct DecodeLaunch {
     // Items [0, n_single) get a workgroup each; the items behind them (short, at most 16 rows) are run
     // four to a workgroup, one per wavefront.
     int32_t n_single;
+    // LDS stages of 16 KiB a workgroup owns (3..5): items shared by more than 16 query rows keep
+    // n_stages - 1 steps in flight.  The launch reserves n_stages * 16 KiB of LDS per workgroup.
+    int32_t n_stages;
+    // fp8 pools: run both products on the fp8 matrix instruction (codes of K and V as they are, query
+    // and probabilities as two e4m3 terms each) instead of widening the codes to bf16.
+    int32_t fp8_matrix;
 };
 
 struct PrefillLaunch {
@@ -144,6 +150,7 @@ int prefill_tile_tokens(int group);
 hipError_t launch_pool_write(const PoolWriteLaunch &a, hipStream_t s);
 hipError_t launch_pool_copy(const PoolCopyLaunch &a, hipStream_t s);
 hipError_t launch_pool_dequant(const PoolDequantLaunch &a, hipStream_t s);
+hipError_t prepare_decode_launch(int32_t variant);  // 0 bf16, 1 fp8, 2 fp8 on the fp8 matrix instruction; once per device, outside graph capture
 hipError_t launch_decode(const DecodeLaunch &a, hipStream_t s, hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr);
 hipError_t launch_rows_fp32(const RowsLaunch &a, hipStream_t s);
 hipError_t launch_pool_write_fp32(const PoolWriteLaunch &a, hipStream_t s);

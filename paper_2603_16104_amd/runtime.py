@@ -105,10 +105,11 @@ def bf16_tensor_to_f64(t: torch.Tensor) -> np.ndarray:
 class DecodeRunner:
     """Plan + buffers for repeated decode steps over one forest."""
 
-    def __init__(self, pool: DevicePool, workload: wl.Workload, random_q: bool = False):
+    def __init__(self, pool: DevicePool, workload: wl.Workload, random_q: bool = False, flags: int = 0):
         f = workload.forest
         self.pool, self.workload = pool, workload
-        self.plan = hkv.hkv_decode_plan_create(pool.handle, f.nodes, f.node_pages, f.req_leaf, workload.num_q_heads)
+        self.plan = hkv.hkv_decode_plan_create(pool.handle, f.nodes, f.node_pages, f.req_leaf, workload.num_q_heads,
+                                               flags)
         self.ws_bytes = hkv.hkv_decode_plan_workspace_bytes(self.plan)
         dev = pool.k.device
         self.ws = torch.empty(max(self.ws_bytes, 256), dtype=torch.uint8, device=dev)

@@ -1244,3 +1244,96 @@ def test_larger_pages_copy_on_write(gpu, oracle, kv_dtype):
     check_lse(r.lse.cpu().numpy(), exp_l, "forked64")
     r.close()
     dp.close()
+
+
+# ------------------------------------------------------------------------------ fp8 pools on the fp8 matrix instruction
+
+@pytest.fixture
+def fp8_matrix(monkeypatch):
+    """Every decode plan over an fp8 pool built while this is active takes the HKV_PLAN_FP8_MATRIX path."""
+    monkeypatch.setenv("HKV_FP8_MATRIX", "1")
+
+
+@pytest.mark.parametrize("seed", [51, 52, 53, 54])
+def test_fp8_matrix_variant_random_forests(gpu, oracle, seed, fp8_matrix):
+    hq, hkv_ = [(8, 2), (8, 1), (4, 4), (16, 1)][seed % 4]
+    w = wl.random_forest_workload(seed, kv_dtype=wl.KV_FP8_E4M3, num_q_heads=hq, num_kv_heads=hkv_, depth=4, fanout=3,
+                                  max_node_pages=9, n_roots=2)
+    run_decode(gpu, oracle, w)
+    run_decode(gpu, oracle, w, one_shot=True)
+
+
+def test_fp8_matrix_variant_by_plan_flag(gpu, oracle):
+    """The flag of hkv_decode_plan_create selects the path (no environment involved); c2-like shape with
+    LDS-staged shared items, register items and a ragged tail, both paths inside the bounds."""
+    import torch
+    from paper_2603_16104_amd import binding as hkv
+    w = wl.random_forest_workload(57, kv_dtype=wl.KV_FP8_E4M3, num_q_heads=16, num_kv_heads=2, depth=3, fanout=4,
+                                  max_node_pages=20, n_roots=1, zero_weight_nodes=False)
+    hp, dp = both_pools(gpu, oracle, w)
+    exp_o, exp_l = oracle.run_workload(w, hp)
+    got = {}
+    for flags in (0, hkv.PLAN_FP8_MATRIX):
+        r = gpu.DecodeRunner(dp, w, flags=flags)
+        r.run()
+        torch.cuda.synchronize()
+        got[flags] = gpu.bf16_tensor_to_f64(r.out)
+        check_close(got[flags], exp_o, f"flags {flags}")
+        check_lse(r.lse.cpu().numpy(), exp_l, f"flags {flags}")
+        r.close()
+    assert not np.array_equal(got[0], got[hkv.PLAN_FP8_MATRIX]), "the flag did not change the arithmetic"
+    dp.close()
+
+
+def test_fp8_matrix_variant_on_the_other_decode_paths(gpu, oracle, fp8_matrix, monkeypatch):
+    """Deep chains, nodes that end inside a page, several query tokens and trees of drafted tokens, short
+    items four to a workgroup, the closed forms, the mixed step and 64-token pages, all on the variant."""
+    f8 = wl.KV_FP8_E4M3
+    test_decode_deep_chain(gpu, oracle, f8)
+    test_decode_nodes_that_end_inside_a_page(gpu, oracle, 61, f8)
+    test_decode_several_query_tokens(gpu, oracle, f8, 3)
+    test_decode_tree_of_drafted_tokens_by_masks(gpu, oracle, f8, (3, 2, 2))
+    test_decode_verifies_a_tree_of_drafted_tokens(gpu, oracle, f8)
+    test_decode_short_items_four_to_a_workgroup(gpu, oracle, f8, monkeypatch)
+    for case in ("zero_query", "huge_scores", "early_dominant_key"):
+        test_decode_closed_forms_on_the_gpu(gpu, oracle, f8, case)
+    test_mixed_step_tree_decode_plus_prefill(gpu, oracle, "interleaved", f8)
+    test_larger_pages_pool_bytes_and_decode(gpu, oracle, 64, f8)
+
+
+@pytest.mark.parametrize("n_large,log2_ratio", [(64, 14), (16, 6)])
+def test_fp8_matrix_variant_block_scales_far_apart(gpu, oracle, n_large, log2_ratio, fp8_matrix, monkeypatch):
+    """V scales that differ by 2^14 between 64-token steps (the reference scale of the probabilities follows
+    from step to step), and by 2^6 inside one step, with all attention weight on the small-scale blocks; one
+    wavefront walks the whole item, so the reference has to move down within it."""
+    import torch
+    from paper_2603_16104_amd import binding as hkv
+    monkeypatch.setenv("HKV_DECODE_PACK", "3")
+    H, Hq, T = 2, 8, 640
+    rng = np.random.default_rng(7)
+    q = rng.standard_normal((1, Hq, 128)).astype(np.float32)
+    K = rng.standard_normal((T, H, 128)).astype(np.float32)
+    V = rng.standard_normal((T, H, 128)).astype(np.float32)
+    V[:n_large] *= 2.0 ** log2_ratio
+    K[:n_large] = -16.0 * q[0].reshape(H, Hq // H, 128).mean(1)[None] + 0.1 * K[:n_large]     # scores near -45: weight ~ 0
+    kb, vb, qb = wl.f32_to_bf16_bits(K), wl.f32_to_bf16_bits(V), wl.f32_to_bf16_bits(q)
+    pages = np.arange(T // 16, dtype=np.int32)
+    hp = oracle.HostPool(T // 16, H, oracle.FP8_E4M3)
+    hp.write(pages, 0, kb, vb)
+    dp = gpu.DevicePool(T // 16, H, oracle.FP8_E4M3)
+    dp.write(pages, 0, gpu.to_device_bits(kb), gpu.to_device_bits(vb))
+    scale = float(1 / np.sqrt(128))
+    exp_o, exp_l = oracle.attn_decode(hp, qb, pages[None, :], np.array([T], dtype=np.int32), scale)
+    f = wl.make_forest([-1], [T], [0], pages)
+    plan = hkv.hkv_decode_plan_create(dp.handle, f.nodes, f.node_pages, f.req_leaf, Hq)
+    assert hkv.hkv_decode_plan_num_workgroups(plan) < len(hkv.hkv_decode_plan_items(plan))    # one wavefront per item
+    nb = hkv.hkv_decode_plan_workspace_bytes(plan)
+    ws = torch.empty(max(nb, 256), dtype=torch.uint8, device="cuda")
+    out = torch.zeros((1, Hq, 128), dtype=torch.int16, device="cuda")
+    lse = torch.zeros((1, Hq), dtype=torch.float32, device="cuda")
+    hkv.attn_decode_plan_run(plan, gpu.to_device_bits(qb), scale, out, lse, ws, nb)
+    torch.cuda.synchronize()
+    check_close(gpu.bf16_tensor_to_f64(out), exp_o, "scales far apart")
+    check_lse(lse.cpu().numpy(), exp_l, "scales far apart")
+    hkv.hkv_decode_plan_destroy(plan)
+    dp.close()

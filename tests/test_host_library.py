@@ -566,3 +566,19 @@ def test_larger_pages_argument_checks():
     plan = hkv.hkv_prefill_plan_create(pool, [0, 10], np.array([[0, 1, 2]], dtype=np.int32), [130], 8, hkv.PLAN_HOST_ONLY)
     hkv.hkv_prefill_plan_destroy(plan)
     hkv.kv_pool_destroy(pool)
+
+
+def test_fp8_matrix_flag_is_for_fp8_pools():
+    nodes, pages = np.array([[-1, 0, 2, 32]], dtype=np.int32), [0, 1]
+    pool = fake_pool(4)
+    with pytest.raises(hkv.HkvError) as e:
+        hkv.hkv_decode_plan_create(pool, nodes, pages, [0], 8, hkv.PLAN_HOST_ONLY | hkv.PLAN_FP8_MATRIX)
+    assert e.value.code == hkv.ESHAPE
+    hkv.kv_pool_destroy(pool)
+    p8 = fake_pool(4, dtype=hkv.FP8_E4M3)
+    a = hkv.hkv_decode_plan_create(p8, nodes, pages, [0], 8, hkv.PLAN_HOST_ONLY | hkv.PLAN_FP8_MATRIX)
+    b = hkv.hkv_decode_plan_create(p8, nodes, pages, [0], 8, hkv.PLAN_HOST_ONLY)
+    assert np.array_equal(hkv.hkv_decode_plan_items(a), hkv.hkv_decode_plan_items(b))      # same work list, other arithmetic
+    hkv.hkv_decode_plan_destroy(a)
+    hkv.hkv_decode_plan_destroy(b)
+    hkv.kv_pool_destroy(p8)
