@@ -60,10 +60,10 @@ def make_pools(runtime, w, n_pools: int):
     return pools
 
 
-def bench_decode(runtime, hkv, w, steps: int, warmup: int, n_pools: int, profile_steps: int):
+def bench_decode(runtime, hkv, w, steps: int, warmup: int, n_pools: int, profile_steps: int, flags: int = 0):
     import torch
     pools = make_pools(runtime, w, n_pools)
-    runners = [runtime.DecodeRunner(p, w) for p in pools]
+    runners = [runtime.DecodeRunner(p, w, flags=flags) for p in pools]
     f = w.forest
     t0 = time.perf_counter()                                    # tree walk, work list, upload: once per topology
     for _ in range(5):
@@ -367,11 +367,13 @@ def main() -> int:
     ap.add_argument("--pools", type=int, default=4, help="identical pools to rotate over (cache defeat)")
     ap.add_argument("--no-extras", action="store_true", help="skip the context workloads (c3, c4, pool write)")
     ap.add_argument("--c5", action="store_true", help="also time the fp8 forest (2.4 GB pool, slow to generate)")
+    ap.add_argument("--fp8-matrix", action="store_true",
+                    help="run the fp8 forest on the fp8 matrix instruction (HKV_PLAN_FP8_MATRIX) instead of the default path")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--mixed", action="store_true", help="a chunked-prefill step: one prefill launch vs tree decode + prefill")
     ap.add_argument("--sensitivity", choices=["llama3-8b", "qwen3-8b", "qwen3-14b", "qwen3-32b"], default=None,
                     help="prefix-sharing sensitivity grid for one model's layer shape instead of the headline line")
-    ap.add_argument("--profile-workload", choices=["c3", "c4", "c5"], default=None,
+    ap.add_argument("--profile-workload", choices=["c3", "c4", "c5", "c5_leaves", "c5_roots"], default=None,
                     help="run only this context workload for a few steps and print its figures (for rocprofv3 runs "
                          "of the other kernels; not the headline line)")
     ap.add_argument("--workflow", choices=["map_reduce", "debate", "reflect"], default=None,
@@ -427,9 +429,13 @@ def main() -> int:
                               "mfma_bf16_frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
                               "new_tokens_per_s": round(w4.total_q() / s4, 1), "tiles": t4}), flush=True)
         else:
-            wx = wl.config3() if name == "c3" else wl.config5()
+            # c5_leaves / c5_roots: the fp8 forest with its roots, resp. its leaves, cut down to one block, to
+            # time the few-row items (private leaves) and the many-row items (shared roots) apart
+            wx = {"c3": wl.config3, "c5": wl.config5, "c5_leaves": lambda: wl.config5(root_tokens=16),
+                  "c5_roots": lambda: wl.config5(child_tokens=16)}[name]()
             sx, nx, mx, hx, ix = bench_decode(runtime, hkv, wx, max(1, min(args.steps, 20)), 3,
-                                              1 if name == "c5" else args.pools, 5)
+                                              args.pools if name == "c3" else 1, 5,
+                                              hkv.PLAN_FP8_MATRIX if name != "c3" and args.fp8_matrix else 0)
             print(json.dumps({"workload": wx.name, "ms_per_step": round(sx * 1e3, 5),
                               "unique_kv_GBps": round(wx.unique_kv_bytes() / sx / 1e9, 2),
                               "node_kernel_ms": round(nx, 5),
@@ -532,8 +538,9 @@ def main() -> int:
         result["extra"]["kv_pool_write_src_GBps"] = round(bench_pool_write(runtime, w, 20), 1)
     if args.c5:
         w5 = wl.config5()
-        s5, n5, m5, h5, i5 = bench_decode(runtime, hkv, w5, 20, 3, 1, 10)
+        s5, n5, m5, h5, i5 = bench_decode(runtime, hkv, w5, 20, 3, 1, 10, hkv.PLAN_FP8_MATRIX if args.fp8_matrix else 0)
         result["extra"]["c5_forest_fp8_decode"] = {
+            "path": "fp8 matrix instruction" if args.fp8_matrix else "codes widened to bf16",
             "unique_kv_GBps": round(w5.unique_kv_bytes() / s5 / 1e9, 2),
             "attended_tokens_per_s": round(w5.forest.attended_tokens() / s5, 1),
             "ms_per_step": round(s5 * 1e3, 5), "node_kernel_ms": round(n5, 5), "merge_kernel_ms": round(m5, 5),
