@@ -48,16 +48,24 @@ __device__ __forceinline__ bf16x8 fp8x8_to_bf16x8(uint32_t w0, uint32_t w1) {
 }
 
 // Reductions across the four 16-lane rows of a wavefront (lanes l, l^16, l^32, l^48 hold the
-// same matrix column): after the call every lane holds the result.
+// same matrix column): after the call every lane holds the result.  v_permlane16_swap exchanges the
+// odd rows of its first operand with the even rows of its second, v_permlane32_swap the upper half of
+// the first with the lower half of the second; fed the same value twice they return (even rows twice,
+// odd rows twice) resp. (lower half twice, upper half twice), all in the vector ALU, where a shuffle
+// through ds_bpermute would be an LDS round trip in the middle of every softmax step.
 __device__ __forceinline__ float rows_max(float v) {
-    v = fmaxf(v, __shfl_xor(v, 16));
-    v = fmaxf(v, __shfl_xor(v, 32));
-    return v;
+    uint32_t x = __float_as_uint(v);
+    const auto a = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+    x = __float_as_uint(fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1])));
+    const auto b = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
 }
 __device__ __forceinline__ float rows_sum(float v) {
-    v += __shfl_xor(v, 16);
-    v += __shfl_xor(v, 32);
-    return v;
+    uint32_t x = __float_as_uint(v);
+    const auto a = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+    x = __float_as_uint(__uint_as_float(a[0]) + __uint_as_float(a[1]));
+    const auto b = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
