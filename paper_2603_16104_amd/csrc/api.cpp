@@ -559,6 +559,29 @@ static void plan_items(hkv_decode_plan &pl) {
     }
     leaf_chunk = env_int("HKV_DECODE_LEAF_CHUNK", leaf_chunk) / 16 * 16;
     shared_chunk = std::min(kMaxSharedItemTokens, env_int("HKV_DECODE_SHARED_CHUNK", shared_chunk)) / 16 * 16;
+    // Few-row nodes a little longer than what one wavefront takes alone (pack_tokens): run whole, their
+    // four wavefronts get only a few steps each and pay a start-up and a combine through LDS for them.
+    // When cutting them into pieces of at most pack_tokens makes the forest large enough for the
+    // four-items-per-workgroup mode, each wavefront streams a piece of 8 to 12 steps on its own instead
+    // (c2: 512-token leaves as 2 x 256, per-node kernel 31.7 -> 30.0 us).  Nodes of 8 / 3 pack_tokens and
+    // more keep their four wavefronts: those already get that many steps each.
+    const int step_tokens = pl.pool->d.dtype == HKV_FP8_E4M3 ? 64 : 32;
+    const int pack_tokens = env_int("HKV_DECODE_PACK_TOKENS", 12 * step_tokens);
+    const int pack_mode = env_int("HKV_DECODE_PACK", 2);  // 1: never, 2: when the items exceed the resident workgroups, 3: always
+    auto cut_for_packing = [&](int n_tokens) { return n_tokens > pack_tokens && 3 * n_tokens < 8 * pack_tokens; };
+    bool cut_leaves = false;
+    if (leaf_split == 1 && pack_mode != 1 && !getenv("HKV_DECODE_LEAF_CHUNK")) {
+        int64_t units = shared_units;
+        bool any = false;
+        for (int v = 0; v < n_nodes; ++v) {
+            const int R = pl.node_req_indptr[v + 1] - pl.node_req_indptr[v];
+            const int T = pl.nodes[v].n_tokens;
+            if (T == 0 || R == 0 || R * G > 16) continue;
+            any |= cut_for_packing(T);
+            units += (int64_t)Hkv * (cut_for_packing(T) ? (T + pack_tokens - 1) / pack_tokens : 1);
+        }
+        cut_leaves = any && (pack_mode == 3 || units > kResidentGroups);
+    }
     struct Proto { DecodeItem it; int64_t cost; };
     std::vector<Proto> protos;
     std::vector<int32_t> node_chunks(n_nodes, 0), slot_base(n_nodes, 0);
@@ -568,6 +591,7 @@ static void plan_items(hkv_decode_plan &pl) {
         int R = pl.node_req_indptr[v + 1] - pl.node_req_indptr[v];
         if (nd.n_tokens == 0 || R == 0) continue;
         int chunk = std::max(16, R * G > 16 ? shared_chunk : leaf_chunk);
+        if (R * G <= 16 && cut_leaves && cut_for_packing(nd.n_tokens)) chunk = pack_tokens;  // equal pieces below
         // equal chunks of whole pages
         int n_chunks = (nd.n_tokens + chunk - 1) / chunk;
         int pages_per_chunk = (nd.n_pages + n_chunks - 1) / n_chunks;
@@ -588,9 +612,6 @@ static void plan_items(hkv_decode_plan &pl) {
     // Forests with more items than the chip holds at once: the short items of at most 16 rows are run four
     // to a workgroup, one per wavefront (a workgroup's start-up then serves four items, and such a
     // wavefront streams its whole item with one step in flight); they are listed behind the others.
-    const int step_tokens = pl.pool->d.dtype == HKV_FP8_E4M3 ? 64 : 32;
-    const int pack_tokens = env_int("HKV_DECODE_PACK_TOKENS", 12 * step_tokens);
-    const int pack_mode = env_int("HKV_DECODE_PACK", 2);  // 1: never, 2: when the items exceed the resident workgroups, 3: always
     const bool pack = pack_mode == 3 || (pack_mode == 2 && (int64_t)protos.size() > kResidentGroups);
     auto packable = [&](const Proto &p) { return pack && p.it.n_req * G <= 16 && p.it.n_tokens <= pack_tokens; };
     std::stable_sort(protos.begin(), protos.end(), [&](const Proto &a, const Proto &b) {

@@ -320,10 +320,20 @@ def test_tree_verification_plan_error_codes():
 
 def test_decode_plan_sizes_of_benchmark_configs(oracle):
     items = _check_decode_plan(wl.config2(), oracle)
-    assert len(items) == 640            # 64 leaves x 8 heads + 4 chunks x 4 row groups x 8 heads of the root
-    # heavy items first
-    cost = items[:, 1] * np.maximum(16, items[:, 4] * 4)
-    assert (np.diff(cost) <= 0).all()
+    # 4 chunks x 4 row groups x 8 heads of the root, one item per workgroup, heavy first; then the 64 leaves of
+    # 512 tokens x 8 heads as two pieces of 256 each, four to a workgroup (one wavefront streams a piece)
+    assert len(items) == 128 + 1024
+    assert (items[:128, 4] == 16).all() and (items[:128, 1] == 512).all()
+    assert (items[128:, 4] == 1).all() and (items[128:, 1] == 256).all()
+    pool = fake_pool(wl.config2().num_pages, 8)
+    f = wl.config2().forest
+    plan = hkv.hkv_decode_plan_create(pool, f.nodes, f.node_pages, f.req_leaf, 32, hkv.PLAN_HOST_ONLY)
+    assert hkv.hkv_decode_plan_num_workgroups(plan) == 128 + 256 and hkv.hkv_decode_plan_max_parts(plan) == 6
+    hkv.hkv_decode_plan_destroy(plan)
+    hkv.kv_pool_destroy(pool)
+    # a forest too small to fill the chip in that mode keeps its leaves whole (8 requests: 16 root + 64 leaf items)
+    small = _check_decode_plan(wl.config2(n_req=8), oracle)
+    assert (small[small[:, 4] == 1][:, 1] >= 256).all() and len(small) < 768
 
 
 def test_decode_plan_error_codes():
