@@ -332,6 +332,74 @@ def bench_mixed(runtime, hkv, wl, steps: int, warmup: int):
     return res
 
 
+def bench_decode_loop(runtime, hkv, wl, steps: int, warmup: int):
+    """Generation loop on the c2 shape: every step stores one new token per request (kv_pool_append, one
+    launch), updates the plan and runs the prefix-tree decode.  With a growing plan the update is
+    hkv_decode_plan_append; without, a new plan per step.  Four independent loops (pool + plan each) take
+    turns so that the 256 MB last-level cache cannot hold the KV bytes.  Wall clock, host work included."""
+    import numpy as np
+    import torch
+    w = wl.config2()
+    f = w.forest
+    n_loops, res = 4, {"workload": w.name + " + one generated token per request and step", "loops_rotated": 4}
+    k_new = _rand_bits(torch, (f.n_req, w.num_kv_heads, 128))
+    v_new = _rand_bits(torch, (f.n_req, w.num_kv_heads, 128))
+    for mode in ("growing_plan", "new_plan_every_step"):
+        loops = []
+        for i in range(n_loops):
+            p = runtime.DevicePool(w.num_pages + f.n_req * ((steps + warmup) // 16 + 2), w.num_kv_heads, w.kv_dtype, poison=False)
+            p.fill_random(i)
+            hkv.kv_pool_alloc(p.handle, w.num_pages)                      # the forest's pages are in use
+            r = runtime.DecodeRunner(p, w, random_q=True, reserve_tokens=steps + warmup if mode == "growing_plan" else 0)
+            loops.append({"pool": p, "runner": r, "n_tokens": f.n_tokens.copy(),
+                          "last_page": np.array([f.node_pages[f.page_begin[v] + f.n_pages[v] - 1] for v in f.req_leaf]),
+                          "nodes": f.nodes.copy(), "node_pages": [list(f.node_pages[f.page_begin[v]: f.page_begin[v] + f.n_pages[v]])
+                                                                  for v in range(f.n_nodes)]})
+        host_us = []
+
+        def step(i):
+            lp = loops[i % n_loops]
+            t0 = time.perf_counter()
+            leaves = f.req_leaf
+            slots = lp["n_tokens"][leaves] % 16
+            new = np.full(f.n_req, -1, dtype=np.int32)
+            need = np.nonzero(slots == 0)[0]
+            if len(need):
+                new[need] = hkv.kv_pool_alloc(lp["pool"].handle, len(need))
+                lp["last_page"][need] = new[need]
+                for r_ in need:
+                    lp["node_pages"][leaves[r_]].append(int(new[r_]))
+            hkv.kv_pool_append(lp["pool"].handle, lp["last_page"], slots, k_new, v_new)
+            lp["n_tokens"][leaves] += 1
+            if mode == "growing_plan":
+                lp["runner"].append(new)
+            else:                                                              # what a caller without it has to do
+                nodes = lp["nodes"]
+                nodes[:, 3] = lp["n_tokens"]
+                nodes[:, 2] = (lp["n_tokens"] + 15) // 16
+                nodes[1:, 1] = np.cumsum(nodes[:-1, 2])
+                pages = np.fromiter((p_ for l in lp["node_pages"] for p_ in l), dtype=np.int32)
+                old = lp["runner"].plan
+                lp["runner"].plan = hkv.hkv_decode_plan_create(lp["pool"].handle, nodes, pages, f.req_leaf, w.num_q_heads)
+                hkv.hkv_decode_plan_destroy(old)
+            host_us.append((time.perf_counter() - t0) * 1e6)
+            lp["runner"].run()
+
+        sec = time_steps(step, steps, warmup)
+        res[mode + "_us_per_step"] = round(sec * 1e6, 2)
+        res[mode + "_host_us_before_the_run_call"] = round(float(np.median(host_us[warmup:])), 2)
+        for lp in loops:
+            lp["runner"].close()
+            lp["pool"].close()
+        del loops
+        torch.cuda.empty_cache()
+    return res
+
+
+def _rand_bits(torch, shape):
+    return torch.randn(shape, device="cuda").to(torch.bfloat16).view(torch.int16)
+
+
 def cpu_baseline_decode(w, budget_s: float = 20.0):
     """The fp64 oracle as it stands on the host cores: whole workload, repeated within the budget."""
     from oracle import oracle as orc
@@ -370,6 +438,9 @@ def main() -> int:
     ap.add_argument("--fp8-matrix", action="store_true",
                     help="run the fp8 forest on the fp8 matrix instruction (HKV_PLAN_FP8_MATRIX) instead of the default path")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--decode-loop", action="store_true",
+                    help="generation loop on the c2 shape: token append + plan update + decode per step, with a growing "
+                         "plan and with a new plan per step (not the headline line)")
     ap.add_argument("--mixed", action="store_true", help="a chunked-prefill step: one prefill launch vs tree decode + prefill")
     ap.add_argument("--sensitivity", choices=["llama3-8b", "qwen3-8b", "qwen3-14b", "qwen3-32b"], default=None,
                     help="prefix-sharing sensitivity grid for one model's layer shape instead of the headline line")
@@ -412,6 +483,10 @@ def main() -> int:
 
     if args.mixed:
         print(json.dumps(bench_mixed(runtime, hkv, wl, min(args.steps, 100), args.warmup)), flush=True)
+        return 0
+
+    if args.decode_loop:
+        print(json.dumps(bench_decode_loop(runtime, hkv, wl, min(args.steps, 160), args.warmup)), flush=True)
         return 0
 
     if args.sensitivity:

@@ -174,6 +174,15 @@ int32_t kv_pool_refcount(const hkv_pool *pool, int32_t page_id);
 int kv_pool_write(hkv_pool *pool, const int32_t *page_ids, int32_t first_slot, int32_t n_tokens,
                   const void *k_src, const void *v_src, void *stream);
 
+/* The decode step's write: one new token for each of n sequences in one launch.  Token i (row i
+ * of k_src / v_src, device, [n][num_kv_heads][128] bf16) goes to slot slots[i] (0 .. page size - 1)
+ * of page page_ids[i]; page_ids and slots are host arrays of n entries (n <= 32768).  Same
+ * arithmetic as kv_pool_write with n_tokens = 1 (fp8: the block's running scale, re-encoding of
+ * its earlier codes if the scale grows).  No two tokens of one call may go to the same 16-token
+ * block.  bf16 and fp8 pools (ESHAPE for fp32 pools: use kv_pool_write). */
+int kv_pool_append(hkv_pool *pool, const int32_t *page_ids, const int32_t *slots, int32_t n,
+                   const void *k_src, const void *v_src, void *stream);
+
 /* ------------------------------------------------------------------------------------------
  * Prefix forest (the call-level templated radix tree of Section 5: every leaf is one LLM
  * call, a call's prompt is the concatenation of the token segments on path(root, leaf)).
@@ -294,6 +303,25 @@ int hkv_decode_plan_create_multi(hkv_pool *pool, const hkv_node *nodes, int32_t 
 int hkv_decode_plan_create_tree(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes, const int32_t *node_pages,
                                 int32_t n_node_pages, const int32_t *req_leaf, int32_t n_req, int32_t tokens_per_req,
                                 const uint64_t *visible, int32_t num_q_heads, uint32_t flags, hkv_decode_plan **out);
+/* A plan for a decode loop: as hkv_decode_plan_create, with room for every request's leaf to grow by
+ * up to reserve_tokens tokens, so that generating a token does not cost a new plan (a tree walk, a
+ * device allocation and a blocking upload) but one call of hkv_decode_plan_append.  Every request
+ * needs a leaf of its own for that: a node without children, named by no other request, holding at
+ * least one token (ETREE otherwise).  bf16 and fp8 pools (ESHAPE for fp32 pools).
+ *
+ * hkv_decode_plan_append: every request's leaf has grown by one token, whose K/V the caller stores
+ * (kv_pool_append) before the next run.  new_page_ids: host, [n_req]; entry r is read only if the
+ * token opens a new page (the leaf held a multiple of the page size), and is then the id of that
+ * page; may be NULL if no request needs one.  Host work is a few microseconds; the updated work
+ * list travels by an asynchronous copy on `stream`, which must be the stream of the runs before
+ * and after it (the copy is ordered between them).  ENOMEM once reserve_tokens appends are used up
+ * (build a new plan then), EINVAL on a plan that was not created growing, ERANGE for a page id
+ * outside the pool; nothing changes on error.  The chunking of the forest stays as planned at
+ * creation: a leaf's last chunk simply gets longer. */
+int hkv_decode_plan_create_growing(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes, const int32_t *node_pages,
+                                   int32_t n_node_pages, const int32_t *req_leaf, int32_t n_req, int32_t num_q_heads,
+                                   int32_t reserve_tokens, uint32_t flags, hkv_decode_plan **out);
+int hkv_decode_plan_append(hkv_decode_plan *plan, const int32_t *new_page_ids, void *stream);
 int hkv_decode_plan_destroy(hkv_decode_plan *plan);
 /* Bytes of device workspace attn_decode_plan_run needs (partial o and lse), 0 on a null plan. */
 size_t hkv_decode_plan_workspace_bytes(const hkv_decode_plan *plan);

@@ -24,7 +24,8 @@ PAGE_SIZE, HEAD_DIM = 16, 128
 
 EXPORTS = [
     "hkv_last_error", "kv_pool_create", "kv_pool_destroy", "kv_pool_alloc", "kv_pool_retain", "kv_pool_release", "kv_pool_copy_on_write",
-    "kv_pool_num_free", "kv_pool_page_size", "kv_pool_refcount", "kv_pool_write", "prefix_tree_flatten",
+    "kv_pool_num_free", "kv_pool_page_size", "kv_pool_refcount", "kv_pool_write", "kv_pool_append", "prefix_tree_flatten",
+    "hkv_decode_plan_create_growing", "hkv_decode_plan_append",
     "prefix_tree_flatten_paged", "prefix_tree_prefill_usage",
     "lse_merge", "hkv_decode_plan_create", "hkv_decode_plan_create_multi", "hkv_decode_plan_create_tree", "hkv_decode_plan_destroy", "hkv_decode_plan_workspace_bytes",
     "hkv_decode_plan_num_items", "hkv_decode_plan_num_workgroups", "hkv_decode_plan_num_parts", "hkv_decode_plan_items",
@@ -171,6 +172,15 @@ def kv_pool_write(pool, page_ids, first_slot: int, n_tokens: int, k_src, v_src, 
                                _stream(stream) if n_tokens > 0 else C.c_void_p(None)))
 
 
+def kv_pool_append(pool, page_ids, slots, k_src, v_src, stream=None) -> None:
+    """One new token for each of len(page_ids) sequences: row i goes to slot slots[i] of page page_ids[i]."""
+    ids, sl = _host_i32(page_ids), _host_i32(slots)
+    if len(ids) != len(sl):
+        raise HkvError(EINVAL, "kv_pool_append: page_ids and slots differ in length")
+    _check(lib().kv_pool_append(pool, _hp(ids), _hp(sl), C.c_int32(len(ids)), _dev(k_src), _dev(v_src),
+                                _stream(stream) if len(ids) > 0 else C.c_void_p(None)))
+
+
 # ----------------------------------------------------------------------------------------- forest
 def prefix_tree_flatten(nodes, node_pages, req_leaf, max_pages: int, page_size: int = PAGE_SIZE):
     nodes, node_pages, req_leaf = _nodes(nodes), _host_i32(node_pages), _host_i32(req_leaf)
@@ -216,6 +226,22 @@ def lse_merge_dense(o_parts, lse_parts, part_count, rows_per_count: int, max_par
 
 
 # ----------------------------------------------------------------------------------------- decode
+def hkv_decode_plan_create_growing(pool, nodes, node_pages, req_leaf, num_q_heads: int, reserve_tokens: int,
+                                   flags: int = 0) -> C.c_void_p:
+    nodes, node_pages, req_leaf = _nodes(nodes), _host_i32(node_pages), _host_i32(req_leaf)
+    out = C.c_void_p()
+    _check(lib().hkv_decode_plan_create_growing(pool, _hp(nodes), C.c_int32(nodes.shape[0]), _hp(node_pages),
+                                                C.c_int32(len(node_pages)), _hp(req_leaf), C.c_int32(len(req_leaf)),
+                                                C.c_int32(num_q_heads), C.c_int32(reserve_tokens), C.c_uint32(flags),
+                                                C.byref(out)))
+    return out
+
+
+def hkv_decode_plan_append(plan, new_page_ids=None, stream=None) -> None:
+    ids = None if new_page_ids is None else _host_i32(new_page_ids)
+    _check(lib().hkv_decode_plan_append(plan, _hp(ids), _stream(stream)))
+
+
 def hkv_decode_plan_create(pool, nodes, node_pages, req_leaf, num_q_heads: int, flags: int = 0) -> C.c_void_p:
     nodes, node_pages, req_leaf = _nodes(nodes), _host_i32(node_pages), _host_i32(req_leaf)
     out = C.c_void_p()

@@ -90,6 +90,18 @@ struct hkv_decode_plan {
     std::vector<int32_t> row_len;
     int32_t max_pages = 0;
     int32_t *d_bt = nullptr, *d_rows_req = nullptr, *d_rows_len = nullptr;
+    // growing plans (hkv_decode_plan_create_growing): every request's leaf has block slots in node_pages
+    // for reserve_tokens more tokens; grow_items holds, per request, the num_kv_heads items of the leaf's
+    // last chunk.  Items and block list are re-sent after every append through a ring of pinned buffers.
+    int32_t reserve_tokens = 0, appended = 0;
+    std::vector<int32_t> grow_items;
+    static constexpr int kGrowSlots = 4;
+    char *h_grow = nullptr;  // pinned, kGrowSlots x grow_bytes
+    char *d_grow = nullptr;  // the same memory as the device addresses it
+    size_t grow_bytes = 0;   // items + block list as laid out on the device, a multiple of 16
+    hipEvent_t grow_free[kGrowSlots] = {};
+    bool grow_in_flight[kGrowSlots] = {};
+    int grow_next = 0;
 };
 
 struct hkv_prefill_plan {
@@ -123,6 +135,7 @@ struct hkv_pool {
     static constexpr int kMaxWritePages = 65536;
     static constexpr int kWriteSlots = 8;
     int32_t *h_ids = nullptr;  // pinned host, kWriteSlots x kMaxWritePages
+    int32_t *hd_ids = nullptr; // the same memory as the device addresses it (source of the copy kernel)
     int32_t *d_ids = nullptr;  // device, same shape
     hipEvent_t slot_free[kWriteSlots] = {};
     bool slot_in_flight[kWriteSlots] = {};
@@ -296,6 +309,16 @@ extern "C" int kv_pool_copy_on_write(hkv_pool *pool, int32_t n, int32_t *ids, vo
     return HKV_OK;
 }
 
+static int ensure_write_staging(hkv_pool *pool) {
+    if (pool->h_ids) return HKV_OK;
+    const size_t bytes = sizeof(int32_t) * hkv_pool::kMaxWritePages * hkv_pool::kWriteSlots;
+    HKV_HIP(hipHostMalloc((void **)&pool->h_ids, bytes, hipHostMallocDefault));
+    HKV_HIP(hipHostGetDevicePointer((void **)&pool->hd_ids, pool->h_ids, 0));
+    HKV_HIP(hipMalloc((void **)&pool->d_ids, bytes));
+    for (hipEvent_t &e : pool->slot_free) HKV_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    return HKV_OK;
+}
+
 extern "C" int kv_pool_write(hkv_pool *pool, const int32_t *page_ids, int32_t first_slot, int32_t n_tokens,
                              const void *k_src, const void *v_src, void *stream) {
     if (!pool) return fail(HKV_EINVAL, "kv_pool_write: null pool");
@@ -317,25 +340,68 @@ extern "C" int kv_pool_write(hkv_pool *pool, const int32_t *page_ids, int32_t fi
             return fail(HKV_ERANGE, "kv_pool_write: page id %d (entry %lld) outside pool of %d pages", page_ids[i],
                         (long long)i, pool->d.num_pages);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (!pool->h_ids) {
-        const size_t bytes = sizeof(int32_t) * hkv_pool::kMaxWritePages * hkv_pool::kWriteSlots;
-        HKV_HIP(hipHostMalloc((void **)&pool->h_ids, bytes, hipHostMallocDefault));
-        HKV_HIP(hipMalloc((void **)&pool->d_ids, bytes));
-        for (hipEvent_t &e : pool->slot_free) HKV_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
-    }
+    if (int rc = ensure_write_staging(pool)) return rc;
     const int slot = pool->next_slot;
     pool->next_slot = (slot + 1) % hkv_pool::kWriteSlots;
     if (pool->slot_in_flight[slot]) HKV_HIP(hipEventSynchronize(pool->slot_free[slot]));  // its last write is done
     int32_t *h = pool->h_ids + (size_t)slot * hkv_pool::kMaxWritePages;
     int32_t *d = pool->d_ids + (size_t)slot * hkv_pool::kMaxWritePages;
     for (int64_t b = b0; b <= b1; ++b) h[b - b0] = page_ids[b / S] * S + (int32_t)(b % S);
-    HKV_HIP(hipMemcpyAsync(d, h, sizeof(int32_t) * (size_t)n_pg, hipMemcpyHostToDevice, s));
+    // a copy kernel on the stream reads the pinned slot (a DMA copy between kernels of one stream costs more)
+    HKV_HIP(launch_upload(pool->hd_ids + (size_t)slot * hkv_pool::kMaxWritePages, d, align_up(sizeof(int32_t) * (size_t)n_pg, 16), s));
     PoolWriteLaunch a{pool->d.k_pages, pool->d.v_pages, pool->d.k_scale, pool->d.v_scale, pool->d.num_kv_heads,
-                      pool->d.dtype, d, (int32_t)n_pg, first_slot % HKV_PAGE_SIZE, n_tokens, k_src, v_src};
+                      pool->d.dtype, d, (int32_t)n_pg, first_slot % HKV_PAGE_SIZE, n_tokens, k_src, v_src, nullptr};
     if (pool->d.dtype == HKV_FP32)
         HKV_HIP(launch_pool_write_fp32(a, s));
     else
         HKV_HIP(launch_pool_write(a, s));
+    HKV_HIP(hipEventRecord(pool->slot_free[slot], s));
+    pool->slot_in_flight[slot] = true;
+    return HKV_OK;
+}
+
+extern "C" int kv_pool_append(hkv_pool *pool, const int32_t *page_ids, const int32_t *slots, int32_t n,
+                              const void *k_src, const void *v_src, void *stream) {
+    if (!pool) return fail(HKV_EINVAL, "kv_pool_append: null pool");
+    if (n < 0) return fail(HKV_EINVAL, "kv_pool_append: n %d", n);
+    if (n == 0) return HKV_OK;
+    if (!page_ids || !slots || !k_src || !v_src) return fail(HKV_EINVAL, "kv_pool_append: null argument");
+    if (pool->d.dtype == HKV_FP32) return fail(HKV_ESHAPE, "kv_pool_append: bf16 and fp8 pools only");
+    if ((reinterpret_cast<uintptr_t>(k_src) | reinterpret_cast<uintptr_t>(v_src)) & 15)
+        return fail(HKV_EINVAL, "kv_pool_append: k_src and v_src must be 16-byte aligned");
+    if (n > hkv_pool::kMaxWritePages / 2) return fail(HKV_EINVAL, "kv_pool_append: %d tokens in one call (limit %d)", n, hkv_pool::kMaxWritePages / 2);
+    const int P = pool->d.page_size, S = pool->blocks_per_page;
+    for (int i = 0; i < n; ++i) {
+        if (page_ids[i] < 0 || page_ids[i] >= pool->d.num_pages)
+            return fail(HKV_ERANGE, "kv_pool_append: page id %d (entry %d) outside pool of %d pages", page_ids[i], i, pool->d.num_pages);
+        if (slots[i] < 0 || slots[i] >= P) return fail(HKV_EINVAL, "kv_pool_append: slot %d (entry %d)", slots[i], i);
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (n <= kMaxInlineAppend) {  // the usual decode batch: everything travels in the kernel arguments
+        PoolAppendInline a{};
+        a.base = PoolWriteLaunch{pool->d.k_pages, pool->d.v_pages, pool->d.k_scale, pool->d.v_scale, pool->d.num_kv_heads,
+                                 pool->d.dtype, nullptr, n, 0, n, k_src, v_src, nullptr};
+        for (int i = 0; i < n; ++i) {
+            a.block[i] = page_ids[i] * S + slots[i] / HKV_PAGE_SIZE;
+            a.slot[i] = (uint8_t)(slots[i] % HKV_PAGE_SIZE);
+        }
+        HKV_HIP(launch_pool_append_inline(a, s));
+        return HKV_OK;
+    }
+    if (int rc = ensure_write_staging(pool)) return rc;
+    const int slot = pool->next_slot;
+    pool->next_slot = (slot + 1) % hkv_pool::kWriteSlots;
+    if (pool->slot_in_flight[slot]) HKV_HIP(hipEventSynchronize(pool->slot_free[slot]));
+    int32_t *h = pool->h_ids + (size_t)slot * hkv_pool::kMaxWritePages;
+    int32_t *d = pool->d_ids + (size_t)slot * hkv_pool::kMaxWritePages;
+    for (int i = 0; i < n; ++i) {  // block ids, then the slots inside them
+        h[i] = page_ids[i] * S + slots[i] / HKV_PAGE_SIZE;
+        h[n + i] = slots[i] % HKV_PAGE_SIZE;
+    }
+    HKV_HIP(launch_upload(pool->hd_ids + (size_t)slot * hkv_pool::kMaxWritePages, d, align_up(sizeof(int32_t) * 2 * (size_t)n, 16), s));
+    PoolWriteLaunch a{pool->d.k_pages, pool->d.v_pages, pool->d.k_scale, pool->d.v_scale, pool->d.num_kv_heads,
+                      pool->d.dtype, d, n, 0, n, k_src, v_src, d + n};
+    HKV_HIP(launch_pool_write(a, s));
     HKV_HIP(hipEventRecord(pool->slot_free[slot], s));
     pool->slot_in_flight[slot] = true;
     return HKV_OK;
@@ -656,6 +722,13 @@ static int upload_decode_plan(hkv_decode_plan &pl) {
     HKV_HIP(up(pl.d_pages, pl.node_pages.data(), sizeof(int32_t) * pl.node_pages.size()));
     HKV_HIP(up(pl.d_node_req_idx, pl.node_req_idx.data(), sizeof(int32_t) * pl.node_req_idx.size()));
     HKV_HIP(up(pl.d_part_count, pl.part_count.data(), sizeof(int32_t) * pl.part_count.size()));
+    if (pl.reserve_tokens > 0) {
+        pl.grow_bytes = align_up(off_pages + sizeof(int32_t) * pl.node_pages.size(), 16);  // inside the allocation: off_nri is 256-aligned
+        HKV_HIP(hipHostMalloc((void **)&pl.h_grow, pl.grow_bytes * hkv_decode_plan::kGrowSlots, hipHostMallocDefault));
+        HKV_HIP(hipHostGetDevicePointer((void **)&pl.d_grow, pl.h_grow, 0));
+        memset(pl.h_grow, 0, pl.grow_bytes * hkv_decode_plan::kGrowSlots);
+        for (hipEvent_t &e : pl.grow_free) HKV_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    }
     // here, so that the first run may already be under graph capture
     HKV_HIP(prepare_decode_launch(pl.pool->d.dtype == HKV_BF16 ? 0 : pl.fp8_matrix ? 2 : 1));
     return HKV_OK;
@@ -693,9 +766,9 @@ static int build_fp32_rows(hkv_decode_plan &pl, bool upload) {
     return HKV_OK;
 }
 
-extern "C" int hkv_decode_plan_create(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes,
-                                      const int32_t *node_pages, int32_t n_node_pages, const int32_t *req_leaf,
-                                      int32_t n_req, int32_t num_q_heads, uint32_t flags, hkv_decode_plan **out) {
+static int create_decode_plan(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes, const int32_t *node_pages,
+                              int32_t n_node_pages, const int32_t *req_leaf, int32_t n_req, int32_t num_q_heads,
+                              uint32_t flags, int32_t reserve_tokens, hkv_decode_plan **out) {
     if (!pool || !out) return fail(HKV_EINVAL, "hkv_decode_plan_create: null argument");
     *out = nullptr;
     const int Hkv = pool->d.num_kv_heads;
@@ -734,11 +807,19 @@ extern "C" int hkv_decode_plan_create(hkv_pool *pool, const hkv_node *nodes, int
     pl->nodes.assign(nodes, nodes + n_nodes);
     pl->node_pages.clear();
     const int S = pool->blocks_per_page;
+    std::vector<char> grows(n_nodes, 0);
+    if (reserve_tokens > 0)
+        for (int r = 0; r < n_req; ++r) grows[req_leaf[r]] = 1;
+    pl->reserve_tokens = reserve_tokens;
     for (int v = 0; v < n_nodes; ++v) {
         hkv_node &nd = pl->nodes[v];
         const int n_blocks = (nd.n_tokens + HKV_PAGE_SIZE - 1) / HKV_PAGE_SIZE;
         const int first = (int)pl->node_pages.size();
         for (int b = 0; b < n_blocks; ++b) pl->node_pages.push_back(node_pages[nodes[v].page_begin + b / S] * S + b % S);
+        if (grows[v]) {  // slots for the blocks the leaf may grow into; until then they repeat its last block (in bounds)
+            const int cap = (nd.n_tokens + reserve_tokens + HKV_PAGE_SIZE - 1) / HKV_PAGE_SIZE;
+            for (int b = n_blocks; b < cap; ++b) pl->node_pages.push_back(pl->node_pages.back());
+        }
         nd.page_begin = first;
         nd.n_pages = n_blocks;
     }
@@ -753,14 +834,109 @@ extern "C" int hkv_decode_plan_create(hkv_pool *pool, const hkv_node *nodes, int
         return HKV_OK;
     }
     plan_items(*pl);
+    if (reserve_tokens > 0) {  // the items that grow with each request: the leaf's last chunk, one per KV head
+        pl->grow_items.assign((size_t)n_req * Hkv, -1);
+        for (int r = 0; r < n_req; ++r) {
+            const int v = req_leaf[r];
+            int last_begin = -1;
+            for (const DecodeItem &it : pl->items)
+                if (it.node == v) last_begin = std::max(last_begin, it.tok_begin);
+            for (size_t i = 0; i < pl->items.size(); ++i)
+                if (pl->items[i].node == v && pl->items[i].tok_begin == last_begin)
+                    pl->grow_items[(size_t)r * Hkv + pl->items[i].kv_head] = (int32_t)i;
+        }
+        pl->key_nodes.clear();  // never the pool's cached one-shot plan
+        pl->key_pages.clear();
+    }
     if (!(flags & HKV_PLAN_HOST_ONLY)) {
         if (int rc = upload_decode_plan(*pl)) {
-            if (pl->dev) (void)hipFree(pl->dev);
-            delete pl;
+            hkv_decode_plan_destroy(pl);
             return rc;
         }
     }
     *out = pl;
+    return HKV_OK;
+}
+
+extern "C" int hkv_decode_plan_create(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes,
+                                      const int32_t *node_pages, int32_t n_node_pages, const int32_t *req_leaf,
+                                      int32_t n_req, int32_t num_q_heads, uint32_t flags, hkv_decode_plan **out) {
+    return create_decode_plan(pool, nodes, n_nodes, node_pages, n_node_pages, req_leaf, n_req, num_q_heads, flags, 0, out);
+}
+
+extern "C" int hkv_decode_plan_create_growing(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes,
+                                              const int32_t *node_pages, int32_t n_node_pages,
+                                              const int32_t *req_leaf, int32_t n_req, int32_t num_q_heads,
+                                              int32_t reserve_tokens, uint32_t flags, hkv_decode_plan **out) {
+    if (!pool || !out) return fail(HKV_EINVAL, "hkv_decode_plan_create_growing: null argument");
+    *out = nullptr;
+    if (pool->d.dtype == HKV_FP32) return fail(HKV_ESHAPE, "hkv_decode_plan_create_growing: bf16 and fp8 pools only");
+    if (reserve_tokens < 1 || reserve_tokens > (1 << 20))
+        return fail(HKV_EINVAL, "hkv_decode_plan_create_growing: reserve_tokens %d", reserve_tokens);
+    if (n_nodes < 0 || n_req < 0 || (n_nodes > 0 && !nodes) || (n_req > 0 && !req_leaf))
+        return fail(HKV_EINVAL, "hkv_decode_plan_create_growing: bad forest arguments");
+    // every request needs a leaf of its own to grow: no other request on it, no children, at least one token
+    std::vector<int32_t> users(n_nodes, 0);
+    for (int r = 0; r < n_req; ++r) {
+        if (req_leaf[r] < 0 || req_leaf[r] >= n_nodes)
+            return fail(HKV_ERANGE, "hkv_decode_plan_create_growing: request %d names node %d of %d", r, req_leaf[r], n_nodes);
+        ++users[req_leaf[r]];
+    }
+    for (int v = 0; v < n_nodes; ++v)
+        if (nodes[v].parent >= 0 && nodes[v].parent < n_nodes && users[nodes[v].parent])
+            return fail(HKV_ETREE, "hkv_decode_plan_create_growing: node %d, the leaf of a request, has children", nodes[v].parent);
+    for (int r = 0; r < n_req; ++r) {
+        if (users[req_leaf[r]] != 1)
+            return fail(HKV_ETREE, "hkv_decode_plan_create_growing: node %d is the leaf of %d requests", req_leaf[r], users[req_leaf[r]]);
+        if (nodes[req_leaf[r]].n_tokens < 1)
+            return fail(HKV_ETREE, "hkv_decode_plan_create_growing: the leaf of request %d holds no token", r);
+    }
+    return create_decode_plan(pool, nodes, n_nodes, node_pages, n_node_pages, req_leaf, n_req, num_q_heads, flags,
+                              reserve_tokens, out);
+}
+
+extern "C" int hkv_decode_plan_append(hkv_decode_plan *plan, const int32_t *new_page_ids, void *stream) {
+    if (!plan) return fail(HKV_EINVAL, "hkv_decode_plan_append: null plan");
+    if (plan->reserve_tokens <= 0) return fail(HKV_EINVAL, "hkv_decode_plan_append: not a growing plan");
+    if (plan->appended >= plan->reserve_tokens)
+        return fail(HKV_ENOMEM, "hkv_decode_plan_append: the %d reserved tokens are used up", plan->reserve_tokens);
+    hkv_pool *pool = plan->pool;
+    const int P = pool->d.page_size, S = pool->blocks_per_page, Hkv = pool->d.num_kv_heads;
+    // check everything before anything changes
+    for (int r = 0; r < plan->n_req; ++r) {
+        const hkv_node &nd = plan->nodes[plan->req_leaf[r]];
+        if (nd.n_tokens % P) continue;  // the new token goes into the leaf's last page
+        if (!new_page_ids) return fail(HKV_EINVAL, "hkv_decode_plan_append: request %d needs a new page, none given", r);
+        if (new_page_ids[r] < 0 || new_page_ids[r] >= pool->d.num_pages)
+            return fail(HKV_ERANGE, "hkv_decode_plan_append: page id %d for request %d outside pool of %d pages",
+                        new_page_ids[r], r, pool->d.num_pages);
+    }
+    for (int r = 0; r < plan->n_req; ++r) {
+        hkv_node &nd = plan->nodes[plan->req_leaf[r]];
+        if (nd.n_tokens % HKV_PAGE_SIZE == 0) {  // a new 16-token block: of a new page, or the next one of the last page
+            const int32_t block = nd.n_tokens % P == 0 ? new_page_ids[r] * S
+                                                      : plan->node_pages[nd.page_begin + nd.n_pages - 1] + 1;
+            plan->node_pages[nd.page_begin + nd.n_pages] = block;
+            ++nd.n_pages;
+        }
+        ++nd.n_tokens;
+        for (int h = 0; h < Hkv; ++h) ++plan->items[plan->grow_items[(size_t)r * Hkv + h]].n_tokens;
+    }
+    ++plan->appended;
+    if (!plan->dev) return HKV_OK;  // host-only plan
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int slot = plan->grow_next;
+    plan->grow_next = (slot + 1) % hkv_decode_plan::kGrowSlots;
+    if (plan->grow_in_flight[slot]) HKV_HIP(hipEventSynchronize(plan->grow_free[slot]));  // its last copy is done
+    char *h = plan->h_grow + (size_t)slot * plan->grow_bytes;
+    const size_t off_pages = reinterpret_cast<char *>(plan->d_pages) - static_cast<char *>(plan->dev);
+    memcpy(h, plan->items.data(), sizeof(DecodeItem) * plan->items.size());
+    memcpy(h + off_pages, plan->node_pages.data(), sizeof(int32_t) * plan->node_pages.size());
+    // a copy kernel on the stream reads the pinned buffer (a DMA copy between two kernels of one stream
+    // costs far more than it moves here)
+    HKV_HIP(launch_upload(plan->d_grow + (size_t)slot * plan->grow_bytes, plan->dev, plan->grow_bytes, s));
+    HKV_HIP(hipEventRecord(plan->grow_free[slot], s));
+    plan->grow_in_flight[slot] = true;
     return HKV_OK;
 }
 
@@ -865,6 +1041,9 @@ extern "C" int hkv_decode_plan_destroy(hkv_decode_plan *plan) {
     if (plan->d_row_mask) (void)hipFree(plan->d_row_mask);
     if (plan->d_bt) (void)hipFree(plan->d_bt);
     for (hipEvent_t e : plan->ev)
+        if (e) (void)hipEventDestroy(e);
+    if (plan->h_grow) (void)hipHostFree(plan->h_grow);
+    for (hipEvent_t e : plan->grow_free)
         if (e) (void)hipEventDestroy(e);
     delete plan;
     return HKV_OK;

@@ -104,6 +104,18 @@ struct PoolWriteLaunch {
     int32_t n_tokens;
     const void *k_src;
     const void *v_src;
+    // One token for each of n_pages sequences instead of one run of tokens (null otherwise): workgroup
+    // (i, head) stores source row i at slot slots[i] (0..15) of block page_ids[i]; first_slot and
+    // n_tokens are not used.
+    const int32_t *slots;        // device
+};
+
+// One token for each of up to kMaxInlineAppend sequences, ids and slots by value.
+constexpr int kMaxInlineAppend = 256;
+struct PoolAppendInline {
+    PoolWriteLaunch base;        // page_ids / slots / first_slot / n_tokens unused; n_pages = number of tokens
+    int32_t block[kMaxInlineAppend];
+    uint8_t slot[kMaxInlineAppend];
 };
 
 // Whole-page copies inside one pool (copy-on-write of pages that several holders share).
@@ -148,6 +160,9 @@ constexpr int kMaxSharedItemTokens = 2048;
 int prefill_tile_tokens(int group);
 
 hipError_t launch_pool_write(const PoolWriteLaunch &a, hipStream_t s);
+// src may be pinned host memory (its device-side address); bytes is rounded down to a multiple of 16
+hipError_t launch_upload(const void *src, void *dst, size_t bytes, hipStream_t s);
+hipError_t launch_pool_append_inline(const PoolAppendInline &a, hipStream_t s);
 hipError_t launch_pool_copy(const PoolCopyLaunch &a, hipStream_t s);
 hipError_t launch_pool_dequant(const PoolDequantLaunch &a, hipStream_t s);
 hipError_t prepare_decode_launch(int32_t variant);  // 0 bf16, 1 fp8, 2 fp8 on the fp8 matrix instruction; once per device, outside graph capture

@@ -6,6 +6,8 @@
 // first_slot are re-encoded as RNE(value(code) * scale / scale'); the scale never shrinks.
 // (The "compute a prefix's KV once and keep it in GPU memory" step of Section 5, "Proactive Cache
 // Management", seen from the pool.)
+#include <algorithm>
+
 #include "hkv_device.h"
 
 namespace hkv {
@@ -26,8 +28,11 @@ __device__ __forceinline__ uint32_t quant4(float a, float b, float c, float d, f
     return (uint32_t)p;
 }
 
+// One workgroup's work.  single: one token per block (source row pi goes to slot one_slot of block
+// `page`) instead of a run of tokens over consecutive blocks.
 template <int DT>
-__global__ __launch_bounds__(256) void pool_write_kernel(PoolWriteLaunch a) {
+__device__ __forceinline__ void pool_write_block(const PoolWriteLaunch &a, const int page, const bool single,
+                                                 const int one_slot) {
     __shared__ uint16_t sV[kPage][kHeadDim + 8];
     __shared__ float sRed[2][4];
     __shared__ float sScale[2], sOld[2];
@@ -35,9 +40,8 @@ __global__ __launch_bounds__(256) void pool_write_kernel(PoolWriteLaunch a) {
     const int pi = blockIdx.x, h = blockIdx.y;
     const int tid = threadIdx.x;
     const int slot = tid >> 4, d0 = (tid & 15) * 8;
-    const int tok = pi * kPage + slot - a.first_slot;
-    const bool valid = tok >= 0 && tok < a.n_tokens;
-    const int page = a.page_ids[pi];
+    const int tok = single ? pi : pi * kPage + slot - a.first_slot;  // source row of this thread's slot
+    const bool valid = single ? slot == one_slot : (tok >= 0 && tok < a.n_tokens);
     const size_t blk = ((size_t)page * a.num_kv_heads + h) * kBlockElems;
 
     u32x4 kw = {0u, 0u, 0u, 0u}, vw = {0u, 0u, 0u, 0u};
@@ -49,8 +53,8 @@ __global__ __launch_bounds__(256) void pool_write_kernel(PoolWriteLaunch a) {
     *reinterpret_cast<u32x4 *>(&sV[slot][d0]) = vw;
 
     // which slots of this page does the call write?  (contiguous range)
-    const int s_lo = max(0, a.first_slot - pi * kPage);
-    const int s_hi = min(kPage, a.first_slot + a.n_tokens - pi * kPage);  // exclusive
+    const int s_lo = single ? one_slot : max(0, a.first_slot - pi * kPage);
+    const int s_hi = single ? one_slot + 1 : min(kPage, a.first_slot + a.n_tokens - pi * kPage);  // exclusive
 
     if (DT == 0) {
         if (valid) {
@@ -160,6 +164,20 @@ __global__ __launch_bounds__(256) void pool_write_kernel(PoolWriteLaunch a) {
     }
 }
 
+template <int DT>
+__global__ __launch_bounds__(256) void pool_write_kernel(PoolWriteLaunch a) {
+    const int pi = blockIdx.x;
+    pool_write_block<DT>(a, a.page_ids[pi], a.slots != nullptr, a.slots ? a.slots[pi] : 0);
+}
+
+// The decode step's append for up to kMaxInlineAppend sequences: block ids and slots travel in the kernel
+// arguments, so the call needs no staging buffer, no copy and no event.
+template <int DT>
+__global__ __launch_bounds__(256) void pool_append_inline_kernel(PoolAppendInline a) {
+    const int pi = blockIdx.x;
+    pool_write_block<DT>(a.base, a.block[pi], true, a.slot[pi]);
+}
+
 // One workgroup per (pair, K or V): copies the page's blocks of all KV heads, 16 bytes per thread and
 // step, and (fp8 pools) the page's scales.  Source and destination pages are distinct.
 __global__ __launch_bounds__(256) void pool_copy_kernel(PoolCopyLaunch a) {
@@ -211,6 +229,11 @@ __global__ __launch_bounds__(256) void pool_dequant_kernel(PoolDequantLaunch a) 
     }
 }
 
+// Plain copy of n16 16-byte pieces; the source may be pinned host memory (read over the host link).
+__global__ __launch_bounds__(256) void upload_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n16) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
 }  // namespace
 
 hipError_t launch_pool_dequant(const PoolDequantLaunch &a, hipStream_t s) {
@@ -219,9 +242,28 @@ hipError_t launch_pool_dequant(const PoolDequantLaunch &a, hipStream_t s) {
     return hipGetLastError();
 }
 
+hipError_t launch_upload(const void *src, void *dst, size_t bytes, hipStream_t s) {
+    const size_t n16 = bytes / 16;
+    if (n16 == 0) return hipSuccess;
+    const unsigned blocks = (unsigned)std::min<size_t>((n16 + 255) / 256, 256);
+    hipLaunchKernelGGL(upload_kernel, dim3(blocks), dim3(256), 0, s, static_cast<const uint4 *>(src),
+                       static_cast<uint4 *>(dst), n16);
+    return hipGetLastError();
+}
+
 hipError_t launch_pool_copy(const PoolCopyLaunch &a, hipStream_t s) {
     if (a.n <= 0) return hipSuccess;
     hipLaunchKernelGGL(pool_copy_kernel, dim3(a.n, 2), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_pool_append_inline(const PoolAppendInline &a, hipStream_t s) {
+    if (a.base.n_pages <= 0) return hipSuccess;
+    dim3 grid(a.base.n_pages, a.base.num_kv_heads), block(256);
+    if (a.base.dtype == 0)
+        hipLaunchKernelGGL(pool_append_inline_kernel<0>, grid, block, 0, s, a);
+    else
+        hipLaunchKernelGGL(pool_append_inline_kernel<1>, grid, block, 0, s, a);
     return hipGetLastError();
 }
 

@@ -105,11 +105,16 @@ def bf16_tensor_to_f64(t: torch.Tensor) -> np.ndarray:
 class DecodeRunner:
     """Plan + buffers for repeated decode steps over one forest."""
 
-    def __init__(self, pool: DevicePool, workload: wl.Workload, random_q: bool = False, flags: int = 0):
+    def __init__(self, pool: DevicePool, workload: wl.Workload, random_q: bool = False, flags: int = 0,
+                 reserve_tokens: int = 0):
         f = workload.forest
         self.pool, self.workload = pool, workload
-        self.plan = hkv.hkv_decode_plan_create(pool.handle, f.nodes, f.node_pages, f.req_leaf, workload.num_q_heads,
-                                               flags)
+        if reserve_tokens > 0:      # a decode loop: every request's leaf may grow (append) without a new plan
+            self.plan = hkv.hkv_decode_plan_create_growing(pool.handle, f.nodes, f.node_pages, f.req_leaf,
+                                                           workload.num_q_heads, reserve_tokens, flags)
+        else:
+            self.plan = hkv.hkv_decode_plan_create(pool.handle, f.nodes, f.node_pages, f.req_leaf,
+                                                   workload.num_q_heads, flags)
         self.ws_bytes = hkv.hkv_decode_plan_workspace_bytes(self.plan)
         dev = pool.k.device
         self.ws = torch.empty(max(self.ws_bytes, 256), dtype=torch.uint8, device=dev)
@@ -121,6 +126,10 @@ class DecodeRunner:
 
     def run(self, stream=None) -> None:
         hkv.attn_decode_plan_run(self.plan, self.q, self.scale, self.out, self.lse, self.ws, self.ws_bytes, stream)
+
+    def append(self, new_page_ids=None, stream=None) -> None:
+        """Every request's leaf has grown by one token (plans created with reserve_tokens only)."""
+        hkv.hkv_decode_plan_append(self.plan, new_page_ids, stream)
 
     def close(self) -> None:
         if self.plan is not None:

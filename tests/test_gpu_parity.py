@@ -1337,3 +1337,73 @@ def test_fp8_matrix_variant_block_scales_far_apart(gpu, oracle, n_large, log2_ra
     check_lse(lse.cpu().numpy(), exp_l, "scales far apart")
     hkv.hkv_decode_plan_destroy(plan)
     dp.close()
+
+
+# ------------------------------------------------------------------------------ decode loop: append, grow, run
+
+@pytest.mark.parametrize("page_size", [16, 64])
+@pytest.mark.parametrize("kv_dtype", [wl.KV_BF16, wl.KV_FP8_E4M3])
+def test_decode_loop_with_a_growing_plan(gpu, oracle, kv_dtype, page_size):
+    """Generation steps without new plans: every step stores one new token per request (kv_pool_append, one
+    launch), tells the plan (hkv_decode_plan_append) and runs it.  Pool bytes equal the oracle's pool after
+    every step; the outputs are checked against the oracle over the grown forest.  Leaves start inside a
+    block, at a block boundary and at a page boundary, and cross several of each."""
+    import torch
+    from paper_2603_16104_amd import binding as hkv
+    H, Hq, P = 2, 8, page_size
+    parent = [-1, 0, 0, 1, 1, 2]
+    ntok = [3 * P, 2 * P, P, 5, P - 1, 2 * P]                     # leaves 3, 4, 5 of requests 0, 1, 2
+    n_pages = 64
+    perm = np.random.default_rng(11).permutation(n_pages).astype(np.int32)
+    f = wl.make_forest(parent, ntok, [3, 4, 5], perm, P)
+    w = wl.Workload(name="loop", num_q_heads=Hq, num_kv_heads=H, kv_dtype=kv_dtype, num_pages=n_pages, seed=17, forest=f,
+                    mode="decode")
+    hp, dp = both_pools(gpu, oracle, w)
+    free = list(perm[int(f.n_pages.sum()):])
+    steps = P + 19
+    r = gpu.DecodeRunner(dp, w, reserve_tokens=steps)
+    n_tokens, pages_of = f.n_tokens.copy(), {v: list(f.node_pages[f.page_begin[v]: f.page_begin[v] + f.n_pages[v]]) for v in (3, 4, 5)}
+    rng = np.random.default_rng(5)
+    # magnitudes that grow (K) and shrink (V): fp8 scales rise now and then; V stays near unit scale, the
+    # absolute error bound is meant for such data
+    k_amp, v_amp = np.linspace(0.5, 3.0, steps), np.linspace(1.5, 0.4, steps)
+    for step in range(steps):
+        k = wl.f32_to_bf16_bits((k_amp[step] * rng.standard_normal((3, H, 128))).astype(np.float32))
+        v = wl.f32_to_bf16_bits((v_amp[step] * rng.standard_normal((3, H, 128))).astype(np.float32))
+        new = np.full(3, -1, dtype=np.int32)
+        ids, slots = [], []
+        for i, leaf in enumerate((3, 4, 5)):
+            if n_tokens[leaf] % P == 0:
+                new[i] = free.pop(0)
+                pages_of[leaf].append(int(new[i]))
+            ids.append(pages_of[leaf][-1])
+            slots.append(int(n_tokens[leaf] % P))
+            hp.write([ids[-1]], slots[-1], k[i:i + 1], v[i:i + 1])
+            n_tokens[leaf] += 1
+        hkv.kv_pool_append(dp.handle, ids, slots, gpu.to_device_bits(k), gpu.to_device_bits(v))
+        r.append(new)
+        r.run()
+        if step % 7 == 0 or step >= steps - 3:
+            torch.cuda.synchronize()
+            assert np.array_equal(dp.k.cpu().numpy().view(np.uint8), hp.k.view(np.uint8)), f"K bytes, step {step}"
+            assert np.array_equal(dp.v.cpu().numpy().view(np.uint8), hp.v.view(np.uint8)), f"V bytes, step {step}"
+            n_pg = f.n_pages.copy()
+            for leaf in (3, 4, 5):
+                n_pg[leaf] = len(pages_of[leaf])
+            lists = [list(f.node_pages[f.page_begin[u]: f.page_begin[u] + f.n_pages[u]]) if u < 3 else pages_of[u] for u in range(6)]
+            g = wl.PrefixForest(f.parent, n_tokens.copy(), np.concatenate([[0], np.cumsum(n_pg)[:-1]]).astype(np.int32), n_pg,
+                                np.asarray([p for l in lists for p in l], dtype=np.int32), f.req_leaf, P)
+            wg = wl.Workload(name="loop", num_q_heads=Hq, num_kv_heads=H, kv_dtype=kv_dtype, num_pages=n_pages, seed=17,
+                             forest=g, mode="decode")
+            exp_o, exp_l = oracle.run_workload(wg, hp)
+            check_close(gpu.bf16_tensor_to_f64(r.out), exp_o, f"step {step}")
+            check_lse(r.lse.cpu().numpy(), exp_l, f"step {step}")
+    if kv_dtype == wl.KV_FP8_E4M3:
+        torch.cuda.synchronize()
+        touched = sorted({p * (P // 16) + b for leaf in (3, 4, 5) for j, p in enumerate(pages_of[leaf])
+                          for b in range(P // 16) if j * P + b * 16 < n_tokens[leaf]})
+        for name in ("k_scale", "v_scale"):
+            g_, o_ = getattr(dp, name).cpu().numpy().reshape(-1, H)[touched], getattr(hp, name).reshape(-1, H)[touched]
+            assert np.array_equal(g_.view(np.uint32), o_.view(np.uint32)), name
+    r.close()
+    dp.close()

@@ -592,3 +592,116 @@ def test_fp8_matrix_flag_is_for_fp8_pools():
     hkv.hkv_decode_plan_destroy(a)
     hkv.hkv_decode_plan_destroy(b)
     hkv.kv_pool_destroy(p8)
+
+
+# ------------------------------------------------------------------------------ plans that grow with the decode loop
+
+def _grown(f, page_size, steps, next_page):
+    """The forest after `steps` appends to every request's leaf; new pages are taken from next_page()."""
+    n_tokens, n_pages = f.n_tokens.copy(), f.n_pages.copy()
+    lists = [list(f.node_pages[f.page_begin[v]: f.page_begin[v] + f.n_pages[v]]) for v in range(f.n_nodes)]
+    log = []
+    for _ in range(steps):
+        new = np.full(f.n_req, -1, dtype=np.int32)
+        for r, v in enumerate(f.req_leaf):
+            if n_tokens[v] % page_size == 0:
+                new[r] = next_page()
+                lists[v].append(int(new[r]))
+                n_pages[v] += 1
+            n_tokens[v] += 1
+        log.append(new)
+    begin = np.concatenate([[0], np.cumsum(n_pages)[:-1]]).astype(np.int32)
+    g = wl.PrefixForest(f.parent, n_tokens, begin, n_pages, np.asarray([p for l in lists for p in l], dtype=np.int32),
+                        f.req_leaf, page_size)
+    return g, log
+
+
+@pytest.mark.parametrize("page_size", [16, 64])
+@pytest.mark.parametrize("kv_dtype", [wl.KV_BF16, wl.KV_FP8_E4M3])
+def test_growing_plan_covers_the_grown_forest(oracle, page_size, kv_dtype):
+    """After k appends the work list covers every (request, KV head, token) of the grown forest exactly once and has
+    kept its chunking: only the leaves' last chunks got longer (which blocks they read is checked on the GPU)."""
+    H, Hq, S = 2, 8, page_size // 16
+    parent = [-1, 0, 0, 1, 1, 2]
+    ntok = [4 * page_size, 2 * page_size, page_size, 5, page_size - 1, 3 * page_size]     # leaves 3, 4, 5 of requests 0, 1, 2
+    pages = np.random.default_rng(3).permutation(200).astype(np.int32)
+    f = wl.make_forest(parent, ntok, [3, 4, 5], pages, page_size)
+    used = int(f.n_pages.sum())
+    pool = fake_pool(200, H, kv_dtype, page_size=page_size)
+    steps = 2 * page_size + 3
+    plan = hkv.hkv_decode_plan_create_growing(pool, f.nodes, f.node_pages, f.req_leaf, Hq, steps, hkv.PLAN_HOST_ONLY)
+    before = hkv.hkv_decode_plan_items(plan)
+    fresh = iter(pages[used:].tolist())
+    g, log = _grown(f, page_size, steps, lambda: next(fresh))
+    for new in log:
+        hkv.hkv_decode_plan_append(plan, new, stream=0)
+    with pytest.raises(hkv.HkvError) as e:                     # the reserve is used up
+        hkv.hkv_decode_plan_append(plan, np.zeros(3, dtype=np.int32), stream=0)
+    assert e.value.code == hkv.ENOMEM
+    items = hkv.hkv_decode_plan_items(plan)
+    assert len(items) == len(before) and np.array_equal(items[:, [0, 2, 3, 4, 5, 6, 7]], before[:, [0, 2, 3, 4, 5, 6, 7]])
+    assert ((items[:, 1] - before[:, 1]) == np.where(np.isin(items[:, 7], [3, 4, 5]) & (items[:, 1] != before[:, 1]), steps, 0)).all()
+    covered = {r: np.zeros((H, int(g.kv_len(r))), dtype=np.int32) for r in range(3)}
+    starts = {v: sum(int(g.n_tokens[u]) for u in g.path(v)[:-1]) for v in range(g.n_nodes)}
+    members = {v: [r for r in range(3) if v in g.path(int(g.req_leaf[r]))] for v in range(g.n_nodes)}
+    for page_off, n_tok, kv_head, req_off, n_req, slot, tok_begin, node in items:
+        for r in members[node]:
+            a = starts[node] + tok_begin
+            covered[r][kv_head, a: a + n_tok] += 1
+    for r in range(3):
+        assert (covered[r] == 1).all()
+    hkv.hkv_decode_plan_destroy(plan)
+    hkv.kv_pool_destroy(pool)
+
+
+def test_growing_plan_argument_checks():
+    pool = fake_pool(16, 2)
+    nodes = np.array([[-1, 0, 1, 16], [0, 1, 1, 5], [0, 2, 1, 16]], dtype=np.int32)
+    pages = np.array([3, 4, 5], dtype=np.int32)
+    mk = lambda n, leaves, reserve=8, p=pool: hkv.hkv_decode_plan_create_growing(p, n, pages, leaves, 4, reserve, hkv.PLAN_HOST_ONLY)
+    for leaves, code in (([0], hkv.ETREE),            # the leaf has children
+                         ([1, 1], hkv.ETREE),         # two requests on one leaf
+                         ([3], hkv.ERANGE)):
+        with pytest.raises(hkv.HkvError) as e:
+            mk(nodes, leaves)
+        assert e.value.code == code, str(e.value)
+    empty = nodes.copy()
+    empty[1] = [0, 1, 0, 0]
+    with pytest.raises(hkv.HkvError) as e:                # a leaf without a token
+        mk(empty, [1])
+    assert e.value.code == hkv.ETREE
+    with pytest.raises(hkv.HkvError) as e:
+        mk(nodes, [1], reserve=0)
+    assert e.value.code == hkv.EINVAL
+    p32 = fake_pool(16, 2, hkv.FP32)
+    with pytest.raises(hkv.HkvError) as e:
+        mk(nodes, [1], p=p32)
+    assert e.value.code == hkv.ESHAPE
+    plan = mk(nodes, [1, 2])
+    with pytest.raises(hkv.HkvError) as e:                # request 1 (16 tokens in its leaf) opens a page: none given
+        hkv.hkv_decode_plan_append(plan, None, stream=0)
+    assert e.value.code == hkv.EINVAL
+    with pytest.raises(hkv.HkvError) as e:
+        hkv.hkv_decode_plan_append(plan, [0, 16], stream=0)
+    assert e.value.code == hkv.ERANGE
+    before = hkv.hkv_decode_plan_items(plan)
+    assert np.array_equal(before, hkv.hkv_decode_plan_items(plan))      # the failed calls changed nothing
+    hkv.hkv_decode_plan_append(plan, [-1, 7], stream=0)                  # request 0 still has room in its page
+    plain = hkv.hkv_decode_plan_create(pool, nodes, pages, [1], 4, hkv.PLAN_HOST_ONLY)
+    with pytest.raises(hkv.HkvError) as e:
+        hkv.hkv_decode_plan_append(plain, None, stream=0)
+    assert e.value.code == hkv.EINVAL
+    for p in (plan, plain):
+        hkv.hkv_decode_plan_destroy(p)
+    with pytest.raises(hkv.HkvError) as e:                # append writes: checked before anything is queued
+        hkv.kv_pool_append(pool, [1, 16], [0, 3], 0x50000, 0x60000, stream=0)
+    assert e.value.code == hkv.ERANGE
+    with pytest.raises(hkv.HkvError) as e:
+        hkv.kv_pool_append(pool, [1, 2], [0, 16], 0x50000, 0x60000, stream=0)
+    assert e.value.code == hkv.EINVAL
+    with pytest.raises(hkv.HkvError) as e:
+        hkv.kv_pool_append(p32, [1], [0], 0x50000, 0x60000, stream=0)
+    assert e.value.code == hkv.ESHAPE
+    hkv.kv_pool_append(pool, [], [], None, None, stream=0)
+    hkv.kv_pool_destroy(pool)
+    hkv.kv_pool_destroy(p32)
