@@ -306,12 +306,101 @@ static void prefix_cache(std::mt19937 &rng) {
     }
 }
 
+// Plans that grow with a decode loop, on pools with pages of 16 to 128 tokens: random chains of shared nodes
+// with one private leaf per request, appended to until the reserve is used up; the work list has to cover
+// every token of every request exactly once after each append.
+static void growing_plans(std::mt19937 &rng) {
+    for (int trial = 0; trial < 60; ++trial) {
+        const int P = 16 << (trial % 4), heads = 1 << (rng() % 3), group = 1 + rng() % 8;
+        const int dtype = trial & 1 ? HKV_FP8_E4M3 : HKV_BF16;
+        hkv_pool_desc d{};
+        d.num_pages = 400;
+        d.page_size = P;
+        d.num_kv_heads = heads;
+        d.head_dim = 128;
+        d.dtype = dtype;
+        d.k_pages = reinterpret_cast<void *>(0x10000);
+        d.v_pages = reinterpret_cast<void *>(0x20000);
+        d.k_scale = reinterpret_cast<float *>(0x30000);
+        d.v_scale = reinterpret_cast<float *>(0x40000);
+        hkv_pool *pool = nullptr;
+        CHECK(kv_pool_create(&d, &pool) == HKV_OK);
+        if (!pool) continue;
+        CHECK(kv_pool_page_size(pool) == P);
+        const int n_req = 1 + rng() % 5, n_shared = 1 + rng() % 3;
+        std::vector<hkv_node> nodes;
+        std::vector<int32_t> pages, leaves;
+        int next_page = 0;
+        auto add = [&](int parent, int tokens) {
+            const int n_pages = (tokens + P - 1) / P;
+            nodes.push_back(hkv_node{parent, (int32_t)pages.size(), n_pages, tokens});
+            for (int j = 0; j < n_pages; ++j) pages.push_back(next_page++);
+            return (int)nodes.size() - 1;
+        };
+        int tip = -1;
+        for (int k = 0; k < n_shared; ++k) tip = add(tip, P * (int)(1 + rng() % 3));
+        for (int r = 0; r < n_req; ++r) leaves.push_back(add(tip, 1 + (int)(rng() % (3 * P))));
+        const int reserve = 1 + (int)(rng() % (2 * P + 5));
+        hkv_decode_plan *plan = nullptr;
+        CHECK(hkv_decode_plan_create_growing(pool, nodes.data(), (int32_t)nodes.size(), pages.data(), (int32_t)pages.size(), leaves.data(),
+                                             n_req, heads * group, reserve, HKV_PLAN_HOST_ONLY, &plan) == HKV_OK);
+        if (!plan) {
+            kv_pool_destroy(pool);
+            continue;
+        }
+        std::vector<int32_t> len(n_req);
+        int shared_tokens = 0;
+        for (int v = 0; v <= tip; ++v) shared_tokens += nodes[v].n_tokens;
+        for (int r = 0; r < n_req; ++r) len[r] = nodes[leaves[r]].n_tokens;
+        for (int step = 0; step <= reserve; ++step) {
+            std::vector<int32_t> fresh(n_req, -1);
+            for (int r = 0; r < n_req; ++r)
+                if (len[r] % P == 0) fresh[r] = next_page++;
+            const int rc = hkv_decode_plan_append(plan, fresh.data(), nullptr);
+            if (step == reserve) {
+                CHECK(rc == HKV_ENOMEM);
+                break;
+            }
+            CHECK(rc == HKV_OK);
+            for (int r = 0; r < n_req; ++r) ++len[r];
+            const int n_items = hkv_decode_plan_num_items(plan);
+            std::vector<int32_t> items((size_t)n_items * 8 + 8);
+            CHECK(hkv_decode_plan_items(plan, items.data()) == HKV_OK);
+            std::vector<int64_t> leaf_tokens(n_req, 0);
+            int64_t shared_seen = 0;
+            for (int i = 0; i < n_items; ++i) {
+                const int32_t *it = &items[(size_t)i * 8];  // page_off, n_tokens, kv_head, req_off, n_req, slot, tok_begin, node
+                if (it[7] <= tip)
+                    shared_seen += (int64_t)it[1] * it[4];
+                else
+                    leaf_tokens[it[7] - tip - 1] += it[1];
+            }
+            CHECK(shared_seen == (int64_t)shared_tokens * n_req * heads);
+            for (int r = 0; r < n_req; ++r) CHECK(leaf_tokens[r] == (int64_t)len[r] * heads);
+        }
+        // batched append writes: argument checks only (the launchers are stubs here)
+        std::vector<int32_t> ids(n_req), slots(n_req);
+        for (int r = 0; r < n_req; ++r) {
+            ids[r] = (int32_t)(rng() % 400);
+            slots[r] = (int32_t)(rng() % P);
+        }
+        CHECK(kv_pool_append(pool, ids.data(), slots.data(), n_req, reinterpret_cast<void *>(0x50000), reinterpret_cast<void *>(0x60000),
+                             nullptr) == HKV_OK);
+        slots[0] = P;
+        CHECK(kv_pool_append(pool, ids.data(), slots.data(), n_req, reinterpret_cast<void *>(0x50000), reinterpret_cast<void *>(0x60000),
+                             nullptr) == HKV_EINVAL);
+        CHECK(hkv_decode_plan_destroy(plan) == HKV_OK);
+        CHECK(kv_pool_destroy(pool) == HKV_OK);
+    }
+}
+
 int main() {
     std::mt19937 rng(20260316u);
     pool_traces(rng);
     forests_and_plans(rng);
     scheduling_layer(rng);
     prefix_cache(rng);
+    growing_plans(rng);
     std::printf("host_check: %d failed checks\n", failures);
     return failures ? 1 : 0;
 }
