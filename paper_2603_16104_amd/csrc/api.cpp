@@ -98,6 +98,7 @@ struct hkv_decode_plan {
     static constexpr int kGrowSlots = 4;
     char *h_grow = nullptr;  // pinned, kGrowSlots x grow_bytes
     char *d_grow = nullptr;  // the same memory as the device addresses it
+    int32_t *d_grow_items = nullptr;  // device copy of grow_items (up to 256 requests: updates by a small kernel)
     size_t grow_bytes = 0;   // items + block list as laid out on the device, a multiple of 16
     hipEvent_t grow_free[kGrowSlots] = {};
     bool grow_in_flight[kGrowSlots] = {};
@@ -377,7 +378,8 @@ extern "C" int kv_pool_append(hkv_pool *pool, const int32_t *page_ids, const int
         if (slots[i] < 0 || slots[i] >= P) return fail(HKV_EINVAL, "kv_pool_append: slot %d (entry %d)", slots[i], i);
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (n <= kMaxInlineAppend) {  // the usual decode batch: everything travels in the kernel arguments
+    // HKV_APPEND_INLINE=0 (tests): take the path of larger batches
+    if (n <= kMaxInlineAppend && env_int("HKV_APPEND_INLINE", 1) == 1) {  // the usual decode batch: everything travels in the kernel arguments
         PoolAppendInline a{};
         a.base = PoolWriteLaunch{pool->d.k_pages, pool->d.v_pages, pool->d.k_scale, pool->d.v_scale, pool->d.num_kv_heads,
                                  pool->d.dtype, nullptr, n, 0, n, k_src, v_src, nullptr};
@@ -722,7 +724,11 @@ static int upload_decode_plan(hkv_decode_plan &pl) {
     HKV_HIP(up(pl.d_pages, pl.node_pages.data(), sizeof(int32_t) * pl.node_pages.size()));
     HKV_HIP(up(pl.d_node_req_idx, pl.node_req_idx.data(), sizeof(int32_t) * pl.node_req_idx.size()));
     HKV_HIP(up(pl.d_part_count, pl.part_count.data(), sizeof(int32_t) * pl.part_count.size()));
-    if (pl.reserve_tokens > 0) {
+    // HKV_GROW_INLINE=0 (tests): take the path of larger batches, the work list re-sent from pinned memory
+    if (pl.reserve_tokens > 0 && pl.n_req <= kMaxInlineAppend && !pl.grow_items.empty() && env_int("HKV_GROW_INLINE", 1) == 1) {
+        HKV_HIP(hipMalloc((void **)&pl.d_grow_items, sizeof(int32_t) * pl.grow_items.size()));
+        HKV_HIP(hipMemcpy(pl.d_grow_items, pl.grow_items.data(), sizeof(int32_t) * pl.grow_items.size(), hipMemcpyHostToDevice));
+    } else if (pl.reserve_tokens > 0) {
         pl.grow_bytes = align_up(off_pages + sizeof(int32_t) * pl.node_pages.size(), 16);  // inside the allocation: off_nri is 256-aligned
         HKV_HIP(hipHostMalloc((void **)&pl.h_grow, pl.grow_bytes * hkv_decode_plan::kGrowSlots, hipHostMallocDefault));
         HKV_HIP(hipHostGetDevicePointer((void **)&pl.d_grow, pl.h_grow, 0));
@@ -845,6 +851,11 @@ static int create_decode_plan(hkv_pool *pool, const hkv_node *nodes, int32_t n_n
                 if (pl->items[i].node == v && pl->items[i].tok_begin == last_begin)
                     pl->grow_items[(size_t)r * Hkv + pl->items[i].kv_head] = (int32_t)i;
         }
+        for (int32_t gi : pl->grow_items)
+            if (gi < 0) {
+                delete pl;
+                return fail(HKV_EINVAL, "hkv_decode_plan_create_growing: a leaf without work items");
+            }
         pl->key_nodes.clear();  // never the pool's cached one-shot plan
         pl->key_pages.clear();
     }
@@ -911,12 +922,19 @@ extern "C" int hkv_decode_plan_append(hkv_decode_plan *plan, const int32_t *new_
             return fail(HKV_ERANGE, "hkv_decode_plan_append: page id %d for request %d outside pool of %d pages",
                         new_page_ids[r], r, pool->d.num_pages);
     }
+    const bool inline_update = plan->dev && plan->d_grow_items;
+    PlanGrowInline g{};
     for (int r = 0; r < plan->n_req; ++r) {
         hkv_node &nd = plan->nodes[plan->req_leaf[r]];
+        if (inline_update) g.new_block[r] = -1;
         if (nd.n_tokens % HKV_PAGE_SIZE == 0) {  // a new 16-token block: of a new page, or the next one of the last page
             const int32_t block = nd.n_tokens % P == 0 ? new_page_ids[r] * S
                                                       : plan->node_pages[nd.page_begin + nd.n_pages - 1] + 1;
             plan->node_pages[nd.page_begin + nd.n_pages] = block;
+            if (inline_update) {
+                g.new_block[r] = block;
+                g.block_pos[r] = nd.page_begin + nd.n_pages;
+            }
             ++nd.n_pages;
         }
         ++nd.n_tokens;
@@ -925,6 +943,15 @@ extern "C" int hkv_decode_plan_append(hkv_decode_plan *plan, const int32_t *new_
     ++plan->appended;
     if (!plan->dev) return HKV_OK;  // host-only plan
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (inline_update) {  // the usual batch: the change travels in the arguments of a small kernel
+        g.items = plan->d_items;
+        g.pages = plan->d_pages;
+        g.grow_items = plan->d_grow_items;
+        g.n_grow = (int32_t)plan->grow_items.size();
+        g.n_req = plan->n_req;
+        HKV_HIP(launch_plan_grow_inline(g, s));
+        return HKV_OK;
+    }
     const int slot = plan->grow_next;
     plan->grow_next = (slot + 1) % hkv_decode_plan::kGrowSlots;
     if (plan->grow_in_flight[slot]) HKV_HIP(hipEventSynchronize(plan->grow_free[slot]));  // its last copy is done
@@ -1043,6 +1070,7 @@ extern "C" int hkv_decode_plan_destroy(hkv_decode_plan *plan) {
     for (hipEvent_t e : plan->ev)
         if (e) (void)hipEventDestroy(e);
     if (plan->h_grow) (void)hipHostFree(plan->h_grow);
+    if (plan->d_grow_items) (void)hipFree(plan->d_grow_items);
     for (hipEvent_t e : plan->grow_free)
         if (e) (void)hipEventDestroy(e);
     delete plan;

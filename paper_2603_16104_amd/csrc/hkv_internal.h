@@ -118,6 +118,19 @@ struct PoolAppendInline {
     uint8_t slot[kMaxInlineAppend];
 };
 
+// One decode step's change to an uploaded growing plan, for up to kMaxInlineAppend requests: the items
+// listed in grow_items get one token more, and request r's new 16-token block (if it opens one) is
+// entered at position block_pos[r] of the plan's block list.
+struct PlanGrowInline {
+    DecodeItem *items;           // device
+    int32_t *pages;              // device
+    const int32_t *grow_items;   // device, n_grow entries
+    int32_t n_grow;
+    int32_t n_req;
+    int32_t new_block[kMaxInlineAppend];  // -1: none
+    int32_t block_pos[kMaxInlineAppend];
+};
+
 // Whole-page copies inside one pool (copy-on-write of pages that several holders share).
 constexpr int kMaxCopyPairs = 32;
 struct PoolCopyLaunch {
@@ -163,6 +176,7 @@ hipError_t launch_pool_write(const PoolWriteLaunch &a, hipStream_t s);
 // src may be pinned host memory (its device-side address); bytes is rounded down to a multiple of 16
 hipError_t launch_upload(const void *src, void *dst, size_t bytes, hipStream_t s);
 hipError_t launch_pool_append_inline(const PoolAppendInline &a, hipStream_t s);
+hipError_t launch_plan_grow_inline(const PlanGrowInline &a, hipStream_t s);
 hipError_t launch_pool_copy(const PoolCopyLaunch &a, hipStream_t s);
 hipError_t launch_pool_dequant(const PoolDequantLaunch &a, hipStream_t s);
 hipError_t prepare_decode_launch(int32_t variant);  // 0 bf16, 1 fp8, 2 fp8 on the fp8 matrix instruction; once per device, outside graph capture

@@ -234,7 +234,20 @@ __global__ __launch_bounds__(256) void upload_kernel(const uint4 *__restrict__ s
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
 }
 
+__global__ __launch_bounds__(256) void plan_grow_inline_kernel(PlanGrowInline a) {
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    if (t < a.n_grow) a.items[a.grow_items[t]].n_tokens += 1;
+    if (t < a.n_req && a.new_block[t] >= 0) a.pages[a.block_pos[t]] = a.new_block[t];
+}
+
 }  // namespace
+
+hipError_t launch_plan_grow_inline(const PlanGrowInline &a, hipStream_t s) {
+    const int n = a.n_grow > a.n_req ? a.n_grow : a.n_req;
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(plan_grow_inline_kernel, dim3((n + 255) / 256), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
 
 hipError_t launch_pool_dequant(const PoolDequantLaunch &a, hipStream_t s) {
     if (a.n_pages <= 0) return hipSuccess;

@@ -1341,15 +1341,18 @@ def test_fp8_matrix_variant_block_scales_far_apart(gpu, oracle, n_large, log2_ra
 
 # ------------------------------------------------------------------------------ decode loop: append, grow, run
 
-@pytest.mark.parametrize("page_size", [16, 64])
+@pytest.mark.parametrize("page_size,inline", [(16, True), (64, True), (16, False), (32, False)])
 @pytest.mark.parametrize("kv_dtype", [wl.KV_BF16, wl.KV_FP8_E4M3])
-def test_decode_loop_with_a_growing_plan(gpu, oracle, kv_dtype, page_size):
+def test_decode_loop_with_a_growing_plan(gpu, oracle, kv_dtype, page_size, inline, monkeypatch):
     """Generation steps without new plans: every step stores one new token per request (kv_pool_append, one
     launch), tells the plan (hkv_decode_plan_append) and runs it.  Pool bytes equal the oracle's pool after
     every step; the outputs are checked against the oracle over the grown forest.  Leaves start inside a
     block, at a block boundary and at a page boundary, and cross several of each."""
     import torch
     from paper_2603_16104_amd import binding as hkv
+    if not inline:      # the paths of batches beyond 256 requests: ids and work list through pinned staging buffers
+        monkeypatch.setenv("HKV_GROW_INLINE", "0")
+        monkeypatch.setenv("HKV_APPEND_INLINE", "0")
     H, Hq, P = 2, 8, page_size
     parent = [-1, 0, 0, 1, 1, 2]
     ntok = [3 * P, 2 * P, P, 5, P - 1, 2 * P]                     # leaves 3, 4, 5 of requests 0, 1, 2
