@@ -6,6 +6,9 @@
 // first_slot are re-encoded as RNE(value(code) * scale / scale'); the scale never shrinks.
 // (The "compute a prefix's KV once and keep it in GPU memory" step of Section 5, "Proactive Cache
 // Management", seen from the pool.)
+// Also here, all small: the one-token-per-sequence form of the writer for decode steps, whole-page
+// copies (copy-on-write), the fp8 -> bf16 pre-pass of prefill over fp8 pools, the copy kernel that
+// replaces small host-to-device DMA copies, and the in-place update of a growing decode plan.
 #include <algorithm>
 
 #include "hkv_device.h"
