@@ -259,7 +259,7 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
     const uint32_t k_off = (uint32_t)it.kv_head * BB +
                            ((DT == 0) ? (((m >> 2) & 1) * 8 + (m & 3)) * 64 + g * 16 : (m & 3) * 64 + g * 16);
     const uint32_t v_off = (uint32_t)it.kv_head * BB + ((DT == 0) ? m * 32 + (g & 1) * 16 : m * 16);
-    const size_t page_stride = (size_t)Hkv * BB;
+    const uint32_t page_stride = (uint32_t)Hkv * BB;  // 32-bit factors: id * stride is one 32 x 32 -> 64 bit multiply-add
     const char *kb = static_cast<const char *>(a.pool.k_pages) + k_off;
     const char *vb = static_cast<const char *>(a.pool.v_pages) + v_off;
 
@@ -275,7 +275,7 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
 
     u32x4 kf[8], vf[8];
     auto issue_k = [&](const StepPages<DT> &sp) {
-        const char *p = kb + (size_t)pick(sp.id, k_sel) * page_stride;
+        const char *p = kb + (uint64_t)(uint32_t)pick(sp.id, k_sel) * page_stride;
         if constexpr (DT == 0) {
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
@@ -290,7 +290,7 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
         }
     };
     auto issue_v = [&](const StepPages<DT> &sp) {
-        const char *p = vb + (size_t)pick(sp.id, v_sel) * page_stride;
+        const char *p = vb + (uint64_t)(uint32_t)pick(sp.id, v_sel) * page_stride;
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) vf[dt] = ld16(p + dt * ((DT == 0) ? 512 : 256));
     };
@@ -527,8 +527,8 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
             step_pages(sp, blk);
             char *stage = smem + issue_slot * kStageBytes;
             issue_slot = issue_slot + 1 == n_stages ? 0 : issue_slot + 1;
-            const char *pk = kb + (size_t)pick(sp.id, k_sel) * page_stride;
-            const char *pv = vb + (size_t)pick(sp.id, v_sel) * page_stride;
+            const char *pk = kb + (uint64_t)(uint32_t)pick(sp.id, k_sel) * page_stride;
+            const char *pv = vb + (uint64_t)(uint32_t)pick(sp.id, v_sel) * page_stride;
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 const int f = 4 * j + wave;
