@@ -105,7 +105,7 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillLaunch a) {
     const int last_page = (tl.kv_len - 1) >> 4;
     const char *kbase = static_cast<const char *>(a.pool.k_pages) + (size_t)tl.kv_head * (kBlockElems * 2);
     const char *vbase = static_cast<const char *>(a.pool.v_pages) + (size_t)tl.kv_head * (kBlockElems * 2);
-    const size_t page_stride = (size_t)Hkv * (kBlockElems * 2);
+    const uint32_t page_stride = (uint32_t)Hkv * (kBlockElems * 2);  // 32-bit factors: one multiply-add per address
     const int32_t *bt = a.block_table + tl.bt_off;
 
     // LDS-direct loads: a wavefront-level load writes 1 KiB, lane l at byte 16*l.  The LDS image of a
@@ -122,10 +122,10 @@ __global__ __launch_bounds__(kThreads, 2) void prefill_kernel(PrefillLaunch a) {
     auto fill_ids = [&](int first_page) {  // all threads; the caller separates it from readers by barriers
         for (int i = tid; i < kIdSlots; i += kThreads) sIds[i] = bt[min(first_page + i, last_page)];
     };
-    auto k_source = [&](int id, int cq) { return kbase + (size_t)id * page_stride + cq * 1024 + k_in_quarter; };
+    auto k_source = [&](int id, int cq) { return kbase + ((uint64_t)(uint32_t)id * page_stride + (uint32_t)(cq * 1024 + k_in_quarter)); };
     auto v_source = [&](int id, int cq) {
         const int v_d = cq * 32 + (lane >> 1);
-        return vbase + (size_t)id * page_stride + v_d * 32 + ((v_unit ^ ((v_d >> 3) & 1)) << 4);
+        return vbase + ((uint64_t)(uint32_t)id * page_stride + (uint32_t)(v_d * 32 + ((v_unit ^ ((v_d >> 3) & 1)) << 4)));
     };
     // Main path: lane l of a window register holds the id of page 64 * (blk / 16) + l (pages past the
     // sequence are clamped: in bounds), so a request costs a lane read instead of a memory access.
