@@ -682,10 +682,9 @@ static void plan_items(hkv_decode_plan &pl) {
     // wavefront streams its whole item with one step in flight); they are listed behind the others.
     const bool pack = pack_mode == 3 || (pack_mode == 2 && (int64_t)protos.size() > kResidentGroups);
     auto packable = [&](const Proto &p) { return pack && p.it.n_req * G <= 16 && p.it.n_tokens <= pack_tokens; };
-    std::stable_sort(protos.begin(), protos.end(), [&](const Proto &a, const Proto &b) {
-        const bool pa = packable(a), pb = packable(b);
-        return pa != pb ? pb : a.cost > b.cost;  // one item per workgroup first, heavy before light in both classes
-    });
+    // one item per workgroup first, heavy before light in both classes: a single integer key per item
+    for (Proto &p : protos) p.cost = (packable(p) ? 0 : (int64_t)1 << 56) + p.cost;
+    std::stable_sort(protos.begin(), protos.end(), [](const Proto &a, const Proto &b) { return a.cost > b.cost; });
     pl.items.clear();
     pl.n_single = 0;
     for (auto &p : protos) {
@@ -813,6 +812,7 @@ static int create_decode_plan(hkv_pool *pool, const hkv_node *nodes, int32_t n_n
     pl->nodes.assign(nodes, nodes + n_nodes);
     pl->node_pages.clear();
     const int S = pool->blocks_per_page;
+    pl->node_pages.reserve((size_t)n_node_pages * S + (reserve_tokens > 0 ? (size_t)n_req * (reserve_tokens / HKV_PAGE_SIZE + 2) : 0));
     std::vector<char> grows(n_nodes, 0);
     if (reserve_tokens > 0)
         for (int r = 0; r < n_req; ++r) grows[req_leaf[r]] = 1;
