@@ -716,13 +716,16 @@ static int upload_decode_plan(hkv_decode_plan &pl) {
     pl.d_pages = reinterpret_cast<int32_t *>(base + off_pages);
     pl.d_node_req_idx = reinterpret_cast<int32_t *>(base + off_nri);
     pl.d_part_count = reinterpret_cast<int32_t *>(base + off_cnt);
-    auto up = [&](void *dst, const void *src, size_t n) -> hipError_t {
-        return n ? hipMemcpy(dst, src, n, hipMemcpyHostToDevice) : hipSuccess;
+    // one host image, one copy
+    std::vector<char> image(total, 0);
+    auto put = [&](size_t off, const void *src, size_t n) {
+        if (n) memcpy(image.data() + off, src, n);
     };
-    HKV_HIP(up(pl.d_items, pl.items.data(), sizeof(DecodeItem) * pl.items.size()));
-    HKV_HIP(up(pl.d_pages, pl.node_pages.data(), sizeof(int32_t) * pl.node_pages.size()));
-    HKV_HIP(up(pl.d_node_req_idx, pl.node_req_idx.data(), sizeof(int32_t) * pl.node_req_idx.size()));
-    HKV_HIP(up(pl.d_part_count, pl.part_count.data(), sizeof(int32_t) * pl.part_count.size()));
+    put(off_items, pl.items.data(), sizeof(DecodeItem) * pl.items.size());
+    put(off_pages, pl.node_pages.data(), sizeof(int32_t) * pl.node_pages.size());
+    put(off_nri, pl.node_req_idx.data(), sizeof(int32_t) * pl.node_req_idx.size());
+    put(off_cnt, pl.part_count.data(), sizeof(int32_t) * pl.part_count.size());
+    HKV_HIP(hipMemcpy(pl.dev, image.data(), total, hipMemcpyHostToDevice));
     // HKV_GROW_INLINE=0 (tests): take the path of larger batches, the work list re-sent from pinned memory
     if (pl.reserve_tokens > 0 && pl.n_req <= kMaxInlineAppend && !pl.grow_items.empty() && env_int("HKV_GROW_INLINE", 1) == 1) {
         HKV_HIP(hipMalloc((void **)&pl.d_grow_items, sizeof(int32_t) * pl.grow_items.size()));
