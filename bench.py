@@ -333,9 +333,9 @@ def bench_mixed(runtime, hkv, wl, steps: int, warmup: int):
 
 
 def bench_decode_loop(runtime, hkv, wl, steps: int, warmup: int):
-    """Generation loop on the c2 shape: every step stores one new token per request (kv_pool_append, one
-    launch), updates the plan and runs the prefix-tree decode.  With a growing plan the update is
-    hkv_decode_plan_append; without, a new plan per step.  Four independent loops (pool + plan each) take
+    """Generation loop on the c2 shape: every step stores one new token per request, updates the plan and
+    runs the prefix-tree decode.  With a growing plan, store and update are one call
+    (hkv_decode_plan_append_tokens); without, kv_pool_append and a new plan per step.  Four independent loops (pool + plan each) take
     turns so that the 256 MB last-level cache cannot hold the KV bytes.  Wall clock, host work included."""
     import numpy as np
     import torch
@@ -369,11 +369,11 @@ def bench_decode_loop(runtime, hkv, wl, steps: int, warmup: int):
                 lp["last_page"][need] = new[need]
                 for r_ in need:
                     lp["node_pages"][leaves[r_]].append(int(new[r_]))
-            hkv.kv_pool_append(lp["pool"].handle, lp["last_page"], slots, k_new, v_new)
             lp["n_tokens"][leaves] += 1
-            if mode == "growing_plan":
-                lp["runner"].append(new)
+            if mode == "growing_plan":                                         # tokens and plan update in one launch
+                lp["runner"].append_tokens(new, k_new, v_new)
             else:                                                              # what a caller without it has to do
+                hkv.kv_pool_append(lp["pool"].handle, lp["last_page"], slots, k_new, v_new)
                 nodes = lp["nodes"]
                 nodes[:, 3] = lp["n_tokens"]
                 nodes[:, 2] = (lp["n_tokens"] + 15) // 16

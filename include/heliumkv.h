@@ -322,6 +322,12 @@ int hkv_decode_plan_create_growing(hkv_pool *pool, const hkv_node *nodes, int32_
                                    int32_t n_node_pages, const int32_t *req_leaf, int32_t n_req, int32_t num_q_heads,
                                    int32_t reserve_tokens, uint32_t flags, hkv_decode_plan **out);
 int hkv_decode_plan_append(hkv_decode_plan *plan, const int32_t *new_page_ids, void *stream);
+/* The same together with the write: row r of k_src / v_src (device, [n_req][num_kv_heads][128] bf16)
+ * is the new token of request r and is stored at the end of its leaf, as kv_pool_append would store
+ * it (the plan knows the page and the slot).  For up to 256 requests the write and the plan's update
+ * are one kernel launch.  Errors as hkv_decode_plan_append; EINVAL for null or unaligned k_src / v_src. */
+int hkv_decode_plan_append_tokens(hkv_decode_plan *plan, const int32_t *new_page_ids, const void *k_src,
+                                  const void *v_src, void *stream);
 int hkv_decode_plan_destroy(hkv_decode_plan *plan);
 /* Bytes of device workspace attn_decode_plan_run needs (partial o and lse), 0 on a null plan. */
 size_t hkv_decode_plan_workspace_bytes(const hkv_decode_plan *plan);

@@ -25,7 +25,7 @@ PAGE_SIZE, HEAD_DIM = 16, 128
 EXPORTS = [
     "hkv_last_error", "kv_pool_create", "kv_pool_destroy", "kv_pool_alloc", "kv_pool_retain", "kv_pool_release", "kv_pool_copy_on_write",
     "kv_pool_num_free", "kv_pool_page_size", "kv_pool_refcount", "kv_pool_write", "kv_pool_append", "prefix_tree_flatten",
-    "hkv_decode_plan_create_growing", "hkv_decode_plan_append",
+    "hkv_decode_plan_create_growing", "hkv_decode_plan_append", "hkv_decode_plan_append_tokens",
     "prefix_tree_flatten_paged", "prefix_tree_prefill_usage",
     "lse_merge", "hkv_decode_plan_create", "hkv_decode_plan_create_multi", "hkv_decode_plan_create_tree", "hkv_decode_plan_destroy", "hkv_decode_plan_workspace_bytes",
     "hkv_decode_plan_num_items", "hkv_decode_plan_num_workgroups", "hkv_decode_plan_num_parts", "hkv_decode_plan_items",
@@ -240,6 +240,11 @@ def hkv_decode_plan_create_growing(pool, nodes, node_pages, req_leaf, num_q_head
 def hkv_decode_plan_append(plan, new_page_ids=None, stream=None) -> None:
     ids = None if new_page_ids is None else _host_i32(new_page_ids)
     _check(lib().hkv_decode_plan_append(plan, _hp(ids), _stream(stream)))
+
+
+def hkv_decode_plan_append_tokens(plan, new_page_ids, k_src, v_src, stream=None) -> None:
+    ids = None if new_page_ids is None else _host_i32(new_page_ids)
+    _check(lib().hkv_decode_plan_append_tokens(plan, _hp(ids), _dev(k_src), _dev(v_src), _stream(stream)))
 
 
 def hkv_decode_plan_create(pool, nodes, node_pages, req_leaf, num_q_heads: int, flags: int = 0) -> C.c_void_p:

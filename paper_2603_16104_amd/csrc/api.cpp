@@ -909,7 +909,10 @@ extern "C" int hkv_decode_plan_create_growing(hkv_pool *pool, const hkv_node *no
                               reserve_tokens, out);
 }
 
-extern "C" int hkv_decode_plan_append(hkv_decode_plan *plan, const int32_t *new_page_ids, void *stream) {
+// k_src / v_src: null (the caller stores the tokens itself), or the new token of every request, stored here
+// at the end of its leaf, in the same launch as the plan's update where that runs as a kernel.
+static int plan_append(hkv_decode_plan *plan, const int32_t *new_page_ids, const void *k_src, const void *v_src,
+                       void *stream) {
     if (!plan) return fail(HKV_EINVAL, "hkv_decode_plan_append: null plan");
     if (plan->reserve_tokens <= 0) return fail(HKV_EINVAL, "hkv_decode_plan_append: not a growing plan");
     if (plan->appended >= plan->reserve_tokens)
@@ -925,11 +928,30 @@ extern "C" int hkv_decode_plan_append(hkv_decode_plan *plan, const int32_t *new_
             return fail(HKV_ERANGE, "hkv_decode_plan_append: page id %d for request %d outside pool of %d pages",
                         new_page_ids[r], r, pool->d.num_pages);
     }
+    const bool with_tokens = k_src != nullptr;
+    if (with_tokens && (!v_src || ((reinterpret_cast<uintptr_t>(k_src) | reinterpret_cast<uintptr_t>(v_src)) & 15)))
+        return fail(HKV_EINVAL, "hkv_decode_plan_append_tokens: k_src and v_src must be non-null and 16-byte aligned");
     const bool inline_update = plan->dev && plan->d_grow_items;
     PlanGrowInline g{};
+    PoolAppendInline w{};
+    std::vector<int32_t> w_page, w_slot;  // the tokens' places, for the path of larger batches
+    if (with_tokens && !inline_update) {
+        w_page.resize(plan->n_req);
+        w_slot.resize(plan->n_req);
+    }
     for (int r = 0; r < plan->n_req; ++r) {
         hkv_node &nd = plan->nodes[plan->req_leaf[r]];
         if (inline_update) g.new_block[r] = -1;
+        if (with_tokens) {  // where the new token goes: slot n_tokens % P of the leaf's last (or new) page
+            const int32_t page = nd.n_tokens % P == 0 ? new_page_ids[r] : plan->node_pages[nd.page_begin + nd.n_pages - 1] / S;
+            if (inline_update) {
+                w.block[r] = page * S + (nd.n_tokens % P) / HKV_PAGE_SIZE;
+                w.slot[r] = (uint8_t)(nd.n_tokens % HKV_PAGE_SIZE);
+            } else {
+                w_page[r] = page;
+                w_slot[r] = nd.n_tokens % P;
+            }
+        }
         if (nd.n_tokens % HKV_PAGE_SIZE == 0) {  // a new 16-token block: of a new page, or the next one of the last page
             const int32_t block = nd.n_tokens % P == 0 ? new_page_ids[r] * S
                                                       : plan->node_pages[nd.page_begin + nd.n_pages - 1] + 1;
@@ -952,9 +974,17 @@ extern "C" int hkv_decode_plan_append(hkv_decode_plan *plan, const int32_t *new_
         g.grow_items = plan->d_grow_items;
         g.n_grow = (int32_t)plan->grow_items.size();
         g.n_req = plan->n_req;
-        HKV_HIP(launch_plan_grow_inline(g, s));
+        if (with_tokens) {  // the same launch stores the tokens
+            w.base = PoolWriteLaunch{pool->d.k_pages, pool->d.v_pages, pool->d.k_scale, pool->d.v_scale, Hkv, pool->d.dtype,
+                                     nullptr, plan->n_req, 0, plan->n_req, k_src, v_src, nullptr};
+            HKV_HIP(launch_decode_step_append(w, g, s));
+        } else {
+            HKV_HIP(launch_plan_grow_inline(g, s));
+        }
         return HKV_OK;
     }
+    if (with_tokens)
+        if (int rc = kv_pool_append(pool, w_page.data(), w_slot.data(), plan->n_req, k_src, v_src, stream)) return rc;
     const int slot = plan->grow_next;
     plan->grow_next = (slot + 1) % hkv_decode_plan::kGrowSlots;
     if (plan->grow_in_flight[slot]) HKV_HIP(hipEventSynchronize(plan->grow_free[slot]));  // its last copy is done
@@ -968,6 +998,16 @@ extern "C" int hkv_decode_plan_append(hkv_decode_plan *plan, const int32_t *new_
     HKV_HIP(hipEventRecord(plan->grow_free[slot], s));
     plan->grow_in_flight[slot] = true;
     return HKV_OK;
+}
+
+extern "C" int hkv_decode_plan_append(hkv_decode_plan *plan, const int32_t *new_page_ids, void *stream) {
+    return plan_append(plan, new_page_ids, nullptr, nullptr, stream);
+}
+
+extern "C" int hkv_decode_plan_append_tokens(hkv_decode_plan *plan, const int32_t *new_page_ids, const void *k_src,
+                                             const void *v_src, void *stream) {
+    if (!k_src || !v_src) return fail(HKV_EINVAL, "hkv_decode_plan_append_tokens: null k_src / v_src");
+    return plan_append(plan, new_page_ids, k_src, v_src, stream);
 }
 
 // Plan over n_req * T query rows: the T newest tokens of every request (the last T of its leaf node) are

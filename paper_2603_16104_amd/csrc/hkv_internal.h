@@ -176,6 +176,8 @@ hipError_t launch_pool_write(const PoolWriteLaunch &a, hipStream_t s);
 // src may be pinned host memory (its device-side address); bytes is rounded down to a multiple of 16
 hipError_t launch_upload(const void *src, void *dst, size_t bytes, hipStream_t s);
 hipError_t launch_pool_append_inline(const PoolAppendInline &a, hipStream_t s);
+// both in one launch: workgroup (r, head) stores request r's token and lengthens the leaf's item of that head
+hipError_t launch_decode_step_append(const PoolAppendInline &w, const PlanGrowInline &g, hipStream_t s);
 hipError_t launch_plan_grow_inline(const PlanGrowInline &a, hipStream_t s);
 hipError_t launch_pool_copy(const PoolCopyLaunch &a, hipStream_t s);
 hipError_t launch_pool_dequant(const PoolDequantLaunch &a, hipStream_t s);

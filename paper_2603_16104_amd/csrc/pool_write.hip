@@ -243,7 +243,27 @@ __global__ __launch_bounds__(256) void plan_grow_inline_kernel(PlanGrowInline a)
     if (t < a.n_req && a.new_block[t] >= 0) a.pages[a.block_pos[t]] = a.new_block[t];
 }
 
+// A decode step's append in one launch: workgroup (r, head) stores request r's new token and lengthens the
+// item of that head in the request's leaf (grow_items is [request][head]); head 0 enters a new block id.
+template <int DT>
+__global__ __launch_bounds__(256) void decode_step_append_kernel(PoolAppendInline w, PlanGrowInline g) {
+    const int r = blockIdx.x, h = blockIdx.y;
+    pool_write_block<DT>(w.base, w.block[r], true, w.slot[r]);
+    if (threadIdx.x == 0) g.items[g.grow_items[r * w.base.num_kv_heads + h]].n_tokens += 1;
+    if (threadIdx.x == 1 && h == 0 && g.new_block[r] >= 0) g.pages[g.block_pos[r]] = g.new_block[r];
+}
+
 }  // namespace
+
+hipError_t launch_decode_step_append(const PoolAppendInline &w, const PlanGrowInline &g, hipStream_t s) {
+    if (w.base.n_pages <= 0) return hipSuccess;
+    dim3 grid(w.base.n_pages, w.base.num_kv_heads), block(256);
+    if (w.base.dtype == 0)
+        hipLaunchKernelGGL(decode_step_append_kernel<0>, grid, block, 0, s, w, g);
+    else
+        hipLaunchKernelGGL(decode_step_append_kernel<1>, grid, block, 0, s, w, g);
+    return hipGetLastError();
+}
 
 hipError_t launch_plan_grow_inline(const PlanGrowInline &a, hipStream_t s) {
     const int n = a.n_grow > a.n_req ? a.n_grow : a.n_req;

@@ -131,6 +131,10 @@ class DecodeRunner:
         """Every request's leaf has grown by one token (plans created with reserve_tokens only)."""
         hkv.hkv_decode_plan_append(self.plan, new_page_ids, stream)
 
+    def append_tokens(self, new_page_ids, k_new: torch.Tensor, v_new: torch.Tensor, stream=None) -> None:
+        """The same, and the new tokens' K/V ([n_req][Hkv][128]) are stored at the end of the leaves."""
+        hkv.hkv_decode_plan_append_tokens(self.plan, new_page_ids, k_new, v_new, stream)
+
     def close(self) -> None:
         if self.plan is not None:
             hkv.hkv_decode_plan_destroy(self.plan)

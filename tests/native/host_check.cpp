@@ -20,6 +20,7 @@ hipError_t launch_pool_copy(const PoolCopyLaunch &, hipStream_t) { return hipSuc
 hipError_t launch_upload(const void *, void *, size_t, hipStream_t) { return hipSuccess; }
 hipError_t launch_pool_append_inline(const PoolAppendInline &, hipStream_t) { return hipSuccess; }
 hipError_t launch_plan_grow_inline(const PlanGrowInline &, hipStream_t) { return hipSuccess; }
+hipError_t launch_decode_step_append(const PoolAppendInline &, const PlanGrowInline &, hipStream_t) { return hipSuccess; }
 hipError_t launch_pool_dequant(const PoolDequantLaunch &, hipStream_t) { return hipSuccess; }
 hipError_t launch_decode(const DecodeLaunch &, hipStream_t, hipEvent_t, hipEvent_t) { return hipSuccess; }
 hipError_t prepare_decode_launch(int32_t) { return hipSuccess; }

@@ -1341,9 +1341,10 @@ def test_fp8_matrix_variant_block_scales_far_apart(gpu, oracle, n_large, log2_ra
 
 # ------------------------------------------------------------------------------ decode loop: append, grow, run
 
-@pytest.mark.parametrize("page_size,inline", [(16, True), (64, True), (16, False), (32, False)])
+@pytest.mark.parametrize("page_size,inline,fused", [(16, True, False), (64, True, False), (16, False, False), (32, False, False),
+                                                    (16, True, True), (64, True, True), (32, False, True)])
 @pytest.mark.parametrize("kv_dtype", [wl.KV_BF16, wl.KV_FP8_E4M3])
-def test_decode_loop_with_a_growing_plan(gpu, oracle, kv_dtype, page_size, inline, monkeypatch):
+def test_decode_loop_with_a_growing_plan(gpu, oracle, kv_dtype, page_size, inline, fused, monkeypatch):
     """Generation steps without new plans: every step stores one new token per request (kv_pool_append, one
     launch), tells the plan (hkv_decode_plan_append) and runs it.  Pool bytes equal the oracle's pool after
     every step; the outputs are checked against the oracle over the grown forest.  Leaves start inside a
@@ -1383,8 +1384,11 @@ def test_decode_loop_with_a_growing_plan(gpu, oracle, kv_dtype, page_size, inlin
             slots.append(int(n_tokens[leaf] % P))
             hp.write([ids[-1]], slots[-1], k[i:i + 1], v[i:i + 1])
             n_tokens[leaf] += 1
-        hkv.kv_pool_append(dp.handle, ids, slots, gpu.to_device_bits(k), gpu.to_device_bits(v))
-        r.append(new)
+        if fused:       # hkv_decode_plan_append_tokens: the plan knows where the tokens go
+            r.append_tokens(new, gpu.to_device_bits(k), gpu.to_device_bits(v))
+        else:
+            hkv.kv_pool_append(dp.handle, ids, slots, gpu.to_device_bits(k), gpu.to_device_bits(v))
+            r.append(new)
         r.run()
         if step % 7 == 0 or step >= steps - 3:
             torch.cuda.synchronize()
