@@ -38,6 +38,52 @@ def test_config2_full(gpu, oracle):
 
 
 @pytest.mark.timeout(300)
+def test_config2_generation_loop(gpu, oracle):
+    """Configuration 2 as a generation loop: 35 steps of one new token per request through the growing plan
+    (store and plan update in one call), the configuration the decode-loop bench times; every request opens a
+    new page twice on the way.  Outputs of the last step against the oracle over the grown forest, pool bytes
+    against the oracle's pool."""
+    import torch
+    w = wl.config2()
+    f = w.forest
+    hp, dp = both_pools(gpu, oracle, w)
+    steps = 35
+    free = [p for p in range(w.num_pages) if p not in set(f.node_pages.tolist())]
+    assert len(free) >= 3 * f.n_req
+    r = gpu.DecodeRunner(dp, w, reserve_tokens=steps)
+    n_tokens = f.n_tokens.copy()
+    pages_of = {int(v): list(f.node_pages[f.page_begin[v]: f.page_begin[v] + f.n_pages[v]]) for v in f.req_leaf}
+    rng = np.random.default_rng(9)
+    for step in range(steps):
+        k = wl.f32_to_bf16_bits(rng.standard_normal((f.n_req, w.num_kv_heads, 128)).astype(np.float32))
+        v = wl.f32_to_bf16_bits(rng.standard_normal((f.n_req, w.num_kv_heads, 128)).astype(np.float32))
+        new = np.full(f.n_req, -1, dtype=np.int32)
+        for i, leaf in enumerate(f.req_leaf):
+            if n_tokens[leaf] % 16 == 0:
+                new[i] = free.pop(0)
+                pages_of[int(leaf)].append(int(new[i]))
+            hp.write([pages_of[int(leaf)][-1]], int(n_tokens[leaf] % 16), k[i:i + 1], v[i:i + 1])
+            n_tokens[leaf] += 1
+        r.append_tokens(new, gpu.to_device_bits(k), gpu.to_device_bits(v))
+        r.run()
+    torch.cuda.synchronize()
+    assert np.array_equal(dp.k.cpu().numpy().view(np.uint16), hp.k) and np.array_equal(dp.v.cpu().numpy().view(np.uint16), hp.v)
+    n_pg = (n_tokens + 15) // 16
+    lists = [pages_of[v] if v in pages_of else list(f.node_pages[f.page_begin[v]: f.page_begin[v] + f.n_pages[v]])
+             for v in range(f.n_nodes)]
+    g = wl.PrefixForest(f.parent, n_tokens, np.concatenate([[0], np.cumsum(n_pg)[:-1]]).astype(np.int32), n_pg.astype(np.int32),
+                        np.asarray([p for l in lists for p in l], dtype=np.int32), f.req_leaf)
+    wg = wl.Workload(name="c2_grown", num_q_heads=w.num_q_heads, num_kv_heads=w.num_kv_heads, kv_dtype=w.kv_dtype,
+                     num_pages=w.num_pages, seed=w.seed, forest=g, mode="decode")
+    exp_o, exp_l = oracle.run_workload(wg, hp)
+    res = check_close(gpu.bf16_tensor_to_f64(r.out), exp_o, "c2 generation loop")
+    check_lse(r.lse.cpu().numpy(), exp_l, "c2 generation loop")
+    print(f"c2 generation loop: max_abs {res[0]:.3e} rel_l2 {res[1]:.3e}")
+    r.close()
+    dp.close()
+
+
+@pytest.mark.timeout(300)
 def test_config3_full(gpu, oracle):
     _decode_full(gpu, oracle, wl.config3())
 
