@@ -430,8 +430,8 @@ def cpu_baseline_decode(w, budget_s: float = 20.0):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--pools", type=int, default=4, help="identical pools to rotate over (cache defeat)")
     ap.add_argument("--no-extras", action="store_true", help="skip the context workloads (c3, c4, pool write)")
     ap.add_argument("--c5", action="store_true", help="also time the fp8 forest (2.4 GB pool, slow to generate)")
