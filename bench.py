@@ -508,7 +508,7 @@ def main() -> int:
             # time the few-row items (private leaves) and the many-row items (shared roots) apart
             wx = {"c3": wl.config3, "c5": wl.config5, "c5_leaves": lambda: wl.config5(root_tokens=16),
                   "c5_roots": lambda: wl.config5(child_tokens=16)}[name]()
-            sx, nx, mx, hx, ix = bench_decode(runtime, hkv, wx, max(1, min(args.steps, 20)), 3,
+            sx, nx, mx, hx, ix = bench_decode(runtime, hkv, wx, max(1, min(args.steps, 40)), 10,
                                               args.pools if name == "c3" else 1, 5,
                                               hkv.PLAN_FP8_MATRIX if name != "c3" and args.fp8_matrix else 0)
             print(json.dumps({"workload": wx.name, "ms_per_step": round(sx * 1e3, 5),
@@ -613,7 +613,7 @@ def main() -> int:
         result["extra"]["kv_pool_write_src_GBps"] = round(bench_pool_write(runtime, w, 20), 1)
     if args.c5:
         w5 = wl.config5()
-        s5, n5, m5, h5, i5 = bench_decode(runtime, hkv, w5, 20, 3, 1, 10, hkv.PLAN_FP8_MATRIX if args.fp8_matrix else 0)
+        s5, n5, m5, h5, i5 = bench_decode(runtime, hkv, w5, 40, 10, 1, 10, hkv.PLAN_FP8_MATRIX if args.fp8_matrix else 0)
         result["extra"]["c5_forest_fp8_decode"] = {
             "path": "fp8 matrix instruction" if args.fp8_matrix else "codes widened to bf16",
             "unique_kv_GBps": round(w5.unique_kv_bytes() / s5 / 1e9, 2),
