@@ -705,3 +705,11 @@ def test_growing_plan_argument_checks():
     hkv.kv_pool_append(pool, [], [], None, None, stream=0)
     hkv.kv_pool_destroy(pool)
     hkv.kv_pool_destroy(p32)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; with --gpus above 1 it says so and exits before touching a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "one GPU" in (r.stdout + r.stderr)
