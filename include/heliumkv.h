@@ -312,9 +312,10 @@ int hkv_decode_plan_create_tree(hkv_pool *pool, const hkv_node *nodes, int32_t n
  * hkv_decode_plan_append: every request's leaf has grown by one token, whose K/V the caller stores
  * (kv_pool_append) before the next run.  new_page_ids: host, [n_req]; entry r is read only if the
  * token opens a new page (the leaf held a multiple of the page size), and is then the id of that
- * page; may be NULL if no request needs one.  Host work is a few microseconds; the updated work
- * list travels by an asynchronous copy on `stream`, which must be the stream of the runs before
- * and after it (the copy is ordered between them).  ENOMEM once reserve_tokens appends are used up
+ * page; may be NULL if no request needs one.  Host work is a few microseconds; the device's copy
+ * of the work list is updated by a small kernel queued on `stream` (beyond 256 requests: re-sent
+ * from pinned memory by a copy kernel), which must be the stream of the runs before and after it
+ * (the update is ordered between them).  ENOMEM once reserve_tokens appends are used up
  * (build a new plan then), EINVAL on a plan that was not created growing, ERANGE for a page id
  * outside the pool; nothing changes on error.  The chunking of the forest stays as planned at
  * creation: a leaf's last chunk simply gets longer. */
