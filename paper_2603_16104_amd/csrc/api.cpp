@@ -685,6 +685,27 @@ static void plan_items(hkv_decode_plan &pl) {
     // one item per workgroup first, heavy before light in both classes: a single integer key per item
     for (Proto &p : protos) p.cost = (packable(p) ? 0 : (int64_t)1 << 56) + p.cost;
     std::stable_sort(protos.begin(), protos.end(), [](const Proto &a, const Proto &b) { return a.cost > b.cost; });
+    // Among the one-item workgroups, items shared by more than 16 query rows are bound by their instruction
+    // stream and items of few rows by memory: the two classes are dispatched side by side, each spread evenly
+    // over the list (groups of 8 = one workgroup per XCD), so that both are resident on every CU throughout
+    // instead of one class after the other.  Within a class the order stays heavy before light.
+    const char *il = getenv("HKV_DECODE_INTERLEAVE");  // development knob: group size, 0 = one class after the other
+    if (const int group = il && *il ? atoi(il) : 8; group > 0) {
+        std::vector<Proto> many, few, rest, merged;
+        for (auto &p : protos) (packable(p) ? rest : p.it.n_req * G > 16 ? many : few).push_back(p);
+        if (!many.empty() && !few.empty()) {
+            merged.reserve(protos.size());
+            size_t a = 0, b = 0;
+            while (a < many.size()) {
+                for (int i = 0; i < group && a < many.size(); ++i) merged.push_back(many[a++]);
+                const size_t target = (size_t)((double)a * few.size() / many.size() + 0.5);
+                while (b < target && b < few.size()) merged.push_back(few[b++]);
+            }
+            while (b < few.size()) merged.push_back(few[b++]);
+            merged.insert(merged.end(), rest.begin(), rest.end());
+            protos.swap(merged);
+        }
+    }
     pl.items.clear();
     pl.n_single = 0;
     for (auto &p : protos) {

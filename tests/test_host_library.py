@@ -336,6 +336,39 @@ def test_decode_plan_sizes_of_benchmark_configs(oracle):
     assert (small[small[:, 4] == 1][:, 1] >= 256).all() and len(small) < 768
 
 
+def test_many_row_and_few_row_items_are_dispatched_side_by_side(monkeypatch):
+    """c5: 2048 items of the shared roots (64 query rows each) and 4096 items of the private leaves (8 rows, too
+    long for the four-to-a-workgroup mode).  Both classes are spread evenly over the work list, heavy before
+    light within a class; the development knob restores one class after the other; the items are the same."""
+    w = wl.config5()
+    f = w.forest
+    pool = fake_pool(w.num_pages, w.num_kv_heads, dtype=hkv.FP8_E4M3)
+
+    def items_of():
+        plan = hkv.hkv_decode_plan_create(pool, f.nodes, f.node_pages, f.req_leaf, w.num_q_heads, hkv.PLAN_HOST_ONLY)
+        it = hkv.hkv_decode_plan_items(plan).copy()
+        assert hkv.hkv_decode_plan_num_workgroups(plan) == len(it)
+        hkv.hkv_decode_plan_destroy(plan)
+        return it
+
+    mixed = items_of()
+    many = mixed[:, 4] * (w.num_q_heads // w.num_kv_heads) > 16
+    assert many.sum() == 2048 and (~many).sum() == 4096
+    # every window of 48 consecutive items holds its share of both classes (8 and 16 per 24)
+    for b in range(0, len(mixed), 48):
+        assert many[b:b + 48].sum() == 16
+    for cls in (many, ~many):
+        cost = mixed[cls, 1].astype(np.int64)
+        assert (np.diff(cost) <= 0).all()
+    monkeypatch.setenv("HKV_DECODE_INTERLEAVE", "0")
+    apart = items_of()
+    many_apart = apart[:, 4] * (w.num_q_heads // w.num_kv_heads) > 16
+    assert many_apart[:2048].all() and not many_apart[2048:].any()
+    assert sorted(map(tuple, mixed.tolist())) == sorted(map(tuple, apart.tolist()))
+    assert (mixed[many] == apart[many_apart]).all() and (mixed[~many] == apart[~many_apart]).all()
+    hkv.kv_pool_destroy(pool)
+
+
 def test_decode_plan_error_codes():
     pool = fake_pool(16, 2)
     nodes = np.array([[-1, 0, 1, 16], [0, 1, 1, 5]], dtype=np.int32)
