@@ -358,6 +358,23 @@ int hkv_decode_plan_part_counts(const hkv_decode_plan *plan, int32_t *part_count
 int attn_decode_plan_run(hkv_decode_plan *plan, const void *q, float scale, void *out, float *lse_out,
                          void *workspace, size_t workspace_bytes, void *stream);
 
+/* attn_decode_plan_run for callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the partial results go to a workspace the
+ * library holds itself, a fixed array of hkv_static_workspace_bytes() = 32 MiB of device memory per
+ * GPU that exists from the time the library is loaded until the process ends, so the call takes
+ * neither a workspace nor allocates anything (no hipMalloc / hipFree, no allocating library routine);
+ * it only queues the same two kernels on `stream`.  q, out, lse_out, scale: as attn_decode_plan_run.
+ * ENOMEM if hkv_decode_plan_workspace_bytes(plan) exceeds the array (e.g. more than 65 000 partials of
+ * 516 bytes: use attn_decode_plan_run with a workspace of the caller's then); nothing is queued on
+ * error.  All calls on one GPU share the one array and it keeps the last call's contents (every slot
+ * that is read is written first by the same call, so nothing has to be cleared): two such calls
+ * that overlap in time on one GPU, on different streams or from different plans, race; queue them
+ * on one stream or order them with events.  The plan must have been created on the GPU that is
+ * current at the call. */
+size_t hkv_static_workspace_bytes(void);
+int attn_decode_plan_run_static(hkv_decode_plan *plan, const void *q, float scale, void *out, float *lse_out,
+                                void *stream);
+
 /* Profiling aid.  mode 0: off.  mode 1: attn_decode_plan_run attaches a begin and an end HIP event
  * to each of its two kernel dispatches on the stream it is given, so that an interval is the
  * kernel's own duration on the device, without the gap to its neighbours in the queue.  mode 2: attn_decode_plan_run launches only the per-node kernel

@@ -30,6 +30,7 @@ EXPORTS = [
     "lse_merge", "hkv_decode_plan_create", "hkv_decode_plan_create_multi", "hkv_decode_plan_create_tree", "hkv_decode_plan_destroy", "hkv_decode_plan_workspace_bytes",
     "hkv_decode_plan_num_items", "hkv_decode_plan_num_workgroups", "hkv_decode_plan_num_parts", "hkv_decode_plan_items",
     "hkv_decode_plan_max_parts", "hkv_decode_plan_part_counts", "lse_merge_dense", "attn_decode_plan_run",
+    "attn_decode_plan_run_static", "hkv_static_workspace_bytes",
     "hkv_decode_plan_set_profiling", "hkv_decode_plan_elapsed_ms",
     "attn_decode_prefix_tree", "attn_decode_workspace_bytes", "hkv_prefill_plan_create", "hkv_prefill_plan_destroy",
     "hkv_prefill_plan_num_tiles", "hkv_prefill_plan_tiles", "attn_prefill_plan_run", "attn_prefill_plan_run_ws", "hkv_prefill_plan_workspace_bytes", "attn_prefill_with_prefix",
@@ -65,7 +66,7 @@ def lib():
         L = C.CDLL(LIB_PATH)
         L.hkv_last_error.restype = C.c_char_p
         for name in ("hkv_decode_plan_workspace_bytes", "attn_decode_workspace_bytes", "attn_prefill_workspace_bytes",
-                     "hkv_prefill_plan_workspace_bytes"):
+                     "hkv_prefill_plan_workspace_bytes", "hkv_static_workspace_bytes"):
             getattr(L, name).restype = C.c_size_t
         _lib = L
     return _lib
@@ -318,6 +319,14 @@ def hkv_decode_plan_part_counts(plan, n_req: int) -> np.ndarray:
 def attn_decode_plan_run(plan, q, scale: float, out, lse_out, workspace, workspace_bytes: int, stream=None) -> None:
     _check(lib().attn_decode_plan_run(plan, _dev(q), C.c_float(scale), _dev(out), _dev(lse_out), _dev(workspace),
                                       C.c_size_t(workspace_bytes), _stream(stream)))
+
+
+def hkv_static_workspace_bytes() -> int:
+    return int(lib().hkv_static_workspace_bytes())
+
+
+def attn_decode_plan_run_static(plan, q, scale: float, out, lse_out, stream=None) -> None:
+    _check(lib().attn_decode_plan_run_static(plan, _dev(q), C.c_float(scale), _dev(out), _dev(lse_out), _stream(stream)))
 
 
 def hkv_decode_plan_set_profiling(plan, mode) -> None:

@@ -759,7 +759,7 @@ static int upload_decode_plan(hkv_decode_plan &pl) {
         for (hipEvent_t &e : pl.grow_free) HKV_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
     }
     // here, so that the first run may already be under graph capture
-    HKV_HIP(prepare_decode_launch(pl.pool->d.dtype == HKV_BF16 ? 0 : pl.fp8_matrix ? 2 : 1));
+    HKV_HIP(prepare_decode_device(nullptr));
     return HKV_OK;
 }
 
@@ -1172,26 +1172,16 @@ extern "C" int hkv_decode_plan_part_counts(const hkv_decode_plan *plan, int32_t 
     return HKV_OK;
 }
 
-extern "C" int attn_decode_plan_run(hkv_decode_plan *plan, const void *q, float scale, void *out, float *lse_out,
-                                    void *workspace, size_t workspace_bytes, void *stream) {
-    if (!plan) return fail(HKV_EINVAL, "attn_decode_plan_run: null plan");
-    if (plan->n_req == 0) return HKV_OK;
-    if (!q || !out) return fail(HKV_EINVAL, "attn_decode_plan_run: null q or out");
-    if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(out)) & 15)
-        return fail(HKV_EINVAL, "attn_decode_plan_run: q and out must be 16-byte aligned");
+// The common part of the two run calls; arguments are checked by the callers.  workspace holds at least
+// hkv_decode_plan_workspace_bytes(plan) bytes (unused for fp32 pools).
+static int run_decode_plan(hkv_decode_plan *plan, const void *q, float scale, void *out, float *lse_out,
+                           void *workspace, void *stream) {
     if (plan->pool->d.dtype == HKV_FP32) {
-        if (!plan->d_bt) return fail(HKV_EINVAL, "attn_decode_plan_run: plan was built host-only");
         RowsLaunch a{view_of(plan->pool), static_cast<const float *>(q), plan->d_bt, plan->d_rows_req, plan->d_rows_len,
                      static_cast<float *>(out), lse_out, plan->n_req, plan->num_q_heads, plan->max_pages, scale};
         HKV_HIP(launch_rows_fp32(a, static_cast<hipStream_t>(stream)));
         return HKV_OK;
     }
-    if (!plan->dev) return fail(HKV_EINVAL, "attn_decode_plan_run: plan was built host-only");
-    size_t need = hkv_decode_plan_workspace_bytes(plan);
-    if (need && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)))
-        return fail(HKV_EINVAL, "attn_decode_plan_run: workspace must be non-null and 256-byte aligned");
-    if (workspace_bytes < need)
-        return fail(HKV_ENOMEM, "attn_decode_plan_run: workspace has %zu bytes, %zu needed", workspace_bytes, need);
     hipStream_t s = static_cast<hipStream_t>(stream);
     float *o_parts = static_cast<float *>(workspace);
     float *lse_parts = reinterpret_cast<float *>(static_cast<char *>(workspace) +
@@ -1210,6 +1200,45 @@ extern "C" int attn_decode_plan_run(hkv_decode_plan *plan, const void *q, float 
                                    prof ? plan->ev[2] : nullptr, prof ? plan->ev[3] : nullptr));
     if (prof) plan->profiled_run = !plan->items.empty();
     return HKV_OK;
+}
+
+static int check_decode_run(const hkv_decode_plan *plan, const void *q, const void *out, const char *who) {
+    if (!q || !out) return fail(HKV_EINVAL, "%s: null q or out", who);
+    if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(out)) & 15)
+        return fail(HKV_EINVAL, "%s: q and out must be 16-byte aligned", who);
+    if (plan->pool->d.dtype == HKV_FP32 ? !plan->d_bt : !plan->dev)
+        return fail(HKV_EINVAL, "%s: plan was built host-only", who);
+    return HKV_OK;
+}
+
+extern "C" int attn_decode_plan_run(hkv_decode_plan *plan, const void *q, float scale, void *out, float *lse_out,
+                                    void *workspace, size_t workspace_bytes, void *stream) {
+    if (!plan) return fail(HKV_EINVAL, "attn_decode_plan_run: null plan");
+    if (plan->n_req == 0) return HKV_OK;
+    if (int rc = check_decode_run(plan, q, out, "attn_decode_plan_run")) return rc;
+    const size_t need = hkv_decode_plan_workspace_bytes(plan);
+    if (need && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)))
+        return fail(HKV_EINVAL, "attn_decode_plan_run: workspace must be non-null and 256-byte aligned");
+    if (workspace_bytes < need)
+        return fail(HKV_ENOMEM, "attn_decode_plan_run: workspace has %zu bytes, %zu needed", workspace_bytes, need);
+    return run_decode_plan(plan, q, scale, out, lse_out, workspace, stream);
+}
+
+extern "C" size_t hkv_static_workspace_bytes(void) { return kStaticWorkspaceBytes; }
+
+extern "C" int attn_decode_plan_run_static(hkv_decode_plan *plan, const void *q, float scale, void *out,
+                                           float *lse_out, void *stream) {
+    if (!plan) return fail(HKV_EINVAL, "attn_decode_plan_run_static: null plan");
+    if (plan->n_req == 0) return HKV_OK;
+    if (int rc = check_decode_run(plan, q, out, "attn_decode_plan_run_static")) return rc;
+    const size_t need = hkv_decode_plan_workspace_bytes(plan);
+    if (need > kStaticWorkspaceBytes)
+        return fail(HKV_ENOMEM, "attn_decode_plan_run_static: the plan needs %zu bytes of workspace, the static "
+                    "workspace holds %zu (use attn_decode_plan_run with a workspace of the caller's)", need,
+                    (size_t)kStaticWorkspaceBytes);
+    void *ws = nullptr;  // this device's copy of the static array (looked up when the plan was created)
+    HKV_HIP(prepare_decode_device(&ws));
+    return run_decode_plan(plan, q, scale, out, lse_out, ws, stream);
 }
 
 extern "C" int hkv_decode_plan_set_profiling(hkv_decode_plan *plan, int32_t mode) {

@@ -18,6 +18,7 @@
 // page ids come through scalar loads one step ahead, K of step b+1 is requested as soon as the
 // first product of step b has consumed the K registers, V of step b+1 as soon as the second
 // product has consumed the V registers; nothing in the loop waits for all outstanding loads.
+#include <mutex>
 #include <type_traits>
 
 #include <hip/hip_ext.h>
@@ -676,31 +677,58 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
 
 }  // namespace
 
-// With events, they are bound to the dispatch itself (begin and end of the kernel on the device), so
-// their difference is the kernel's duration without the gap to its neighbours in the queue.
-// More than 64 KiB of LDS per workgroup has to be allowed once per kernel and device.
-// variant: 0 bf16 pool, 1 fp8 pool (codes widened to bf16), 2 fp8 pool on the fp8 matrix instruction.
-hipError_t prepare_decode_launch(int32_t variant) {
-    static bool allowed[3][64] = {};
+// Per-device set-up of the decode path, done once per device with that device current (at plan creation,
+// i.e. outside any graph capture): more than 64 KiB of LDS per workgroup has to be allowed once per kernel
+// variant (0 bf16 pool, 1 fp8 pool with codes widened to bf16, 2 fp8 pool on the fp8 matrix instruction),
+// and the device's own copy of the static workspace below is looked up.
+namespace {
+constexpr int kMaxDevices = 64;
+struct DeviceSetup {
+    std::once_flag once;
+    hipError_t err = hipSuccess;
+    void *static_ws = nullptr;  // this device's address of `scratch`
+};
+DeviceSetup g_setup[kMaxDevices];
+}  // namespace
+}  // namespace hkv
+
+// Workspace of attn_decode_plan_run_static, for callers that cannot allocate device memory: the partial
+// results (o, lse) of one decode step.  Every GPU the library runs on holds its own copy at its own
+// address until the process ends.  In host code the name below is only a handle for hipGetSymbolAddress:
+// kernels, copies and fills get the looked-up device address, never the name.
+static __device__ __align__(256) unsigned char scratch[hkv::kStaticWorkspaceBytes];
+
+namespace hkv {
+
+static hipError_t setup_device(DeviceSetup &st) {
+    const void *fns[3] = {reinterpret_cast<const void *>(decode_node_kernel<0>),
+                          reinterpret_cast<const void *>(decode_node_kernel<1>),
+                          reinterpret_cast<const void *>(decode_node_kernel<2>)};
+    for (const void *fn : fns)
+        if (hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxStages * kStageBytes);
+            e != hipSuccess)
+            return e;
+    return hipGetSymbolAddress(&st.static_ws, HIP_SYMBOL(scratch));
+}
+
+hipError_t prepare_decode_device(void **static_ws) {
     int dev = 0;
     if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
-    if (variant < 0 || variant > 2) return hipErrorInvalidValue;
-    if (dev < 0 || dev >= 64 || allowed[variant][dev]) return hipSuccess;
-    const void *fn = variant == 0   ? reinterpret_cast<const void *>(decode_node_kernel<0>)
-                     : variant == 1 ? reinterpret_cast<const void *>(decode_node_kernel<1>)
-                                    : reinterpret_cast<const void *>(decode_node_kernel<2>);
-    if (hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxStages * kStageBytes);
-        e != hipSuccess)
-        return e;
-    allowed[variant][dev] = true;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    DeviceSetup &st = g_setup[dev];
+    std::call_once(st.once, [&st] { st.err = setup_device(st); });
+    if (st.err != hipSuccess) return st.err;
+    if (static_ws) *static_ws = st.static_ws;
     return hipSuccess;
 }
 
+// With events, they are bound to the dispatch itself (begin and end of the kernel on the device), so
+// their difference is the kernel's duration without the gap to its neighbours in the queue.
 hipError_t launch_decode(const DecodeLaunch &a, hipStream_t s, hipEvent_t ev_begin, hipEvent_t ev_end) {
     if (a.n_items <= 0) return hipSuccess;
     if (a.n_stages < kMinStages || a.n_stages > kMaxStages) return hipErrorInvalidValue;
     const int variant = a.pool.dtype == 0 ? 0 : a.fp8_matrix ? 2 : 1;
-    if (hipError_t e = prepare_decode_launch(variant); e != hipSuccess) return e;
+    if (hipError_t e = prepare_decode_device(nullptr); e != hipSuccess) return e;
     const dim3 grid(a.n_single + (a.n_items - a.n_single + kWaves - 1) / kWaves);
     const unsigned lds = (unsigned)a.n_stages * kStageBytes;
     if (variant == 0)

@@ -181,7 +181,11 @@ hipError_t launch_decode_step_append(const PoolAppendInline &w, const PlanGrowIn
 hipError_t launch_plan_grow_inline(const PlanGrowInline &a, hipStream_t s);
 hipError_t launch_pool_copy(const PoolCopyLaunch &a, hipStream_t s);
 hipError_t launch_pool_dequant(const PoolDequantLaunch &a, hipStream_t s);
-hipError_t prepare_decode_launch(int32_t variant);  // 0 bf16, 1 fp8, 2 fp8 on the fp8 matrix instruction; once per device, outside graph capture
+// Once per device (later calls only read the result), with that device current and outside graph capture:
+// allows the decode kernels their LDS and looks up the device's static workspace (kStaticWorkspaceBytes
+// bytes, 256-byte aligned), returned through static_ws unless that is null.  Safe from several threads.
+constexpr size_t kStaticWorkspaceBytes = (size_t)32 << 20;
+hipError_t prepare_decode_device(void **static_ws);
 hipError_t launch_decode(const DecodeLaunch &a, hipStream_t s, hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr);
 hipError_t launch_rows_fp32(const RowsLaunch &a, hipStream_t s);
 hipError_t launch_pool_write_fp32(const PoolWriteLaunch &a, hipStream_t s);

@@ -23,7 +23,10 @@ hipError_t launch_plan_grow_inline(const PlanGrowInline &, hipStream_t) { return
 hipError_t launch_decode_step_append(const PoolAppendInline &, const PlanGrowInline &, hipStream_t) { return hipSuccess; }
 hipError_t launch_pool_dequant(const PoolDequantLaunch &, hipStream_t) { return hipSuccess; }
 hipError_t launch_decode(const DecodeLaunch &, hipStream_t, hipEvent_t, hipEvent_t) { return hipSuccess; }
-hipError_t prepare_decode_launch(int32_t) { return hipSuccess; }
+hipError_t prepare_decode_device(void **ws) {
+    if (ws) *ws = nullptr;
+    return hipSuccess;
+}
 hipError_t launch_rows_fp32(const RowsLaunch &, hipStream_t) { return hipSuccess; }
 hipError_t launch_pool_write_fp32(const PoolWriteLaunch &, hipStream_t) { return hipSuccess; }
 hipError_t launch_prefill(const PrefillLaunch &, hipStream_t) { return hipSuccess; }
