@@ -1,16 +1,18 @@
 #!/usr/bin/env python3
 """Benchmark of the prefix-tree paged-attention hot path on one MI355X.
 
-A step is one pass of the hot path over one batch of the headline workload: the Llama-3-8B
-shaped decode (64 requests sharing a 2048-token prefix, 512 private tokens each, one query token
-per request) = per-node decode kernel + log-sum-exp merge kernel behind attn_decode_plan_run.
+A step is one pass of the hot path over one batch of the headline workload, the largest
+single-GPU configuration: the 70B-shaped prefix forest with an fp8 KV pool (16 roots of 8192
+tokens, 32 children of 2048 tokens each, 512 requests, one query token per request)
+= per-node decode kernel + log-sum-exp merge kernel behind attn_decode_plan_run.
 All inputs are resident in HBM before the timed region; the plan (tree walk, work list) is built
-once per topology outside it.  Steps rotate over several identical pools so that the 256 MB
-last-level cache cannot serve the KV bytes.
+once per topology outside it.  The other single-GPU configurations (Llama-3-8B shaped decode,
+speculative fan-out decode, prefix-hit prefill) follow under "extra"; the two small decode
+workloads rotate over several identical pools so that the 256 MB last-level cache cannot serve
+their KV bytes.
 
 Prints one JSON line: the headline metric (unique-KV bytes per second), the roofline of the
-dominant kernel measured with HIP events, the CPU oracle timed on the host cores, and (unless
---no-extras) the other single-GPU workloads as context.
+dominant kernel measured with HIP events, and the CPU oracle timed on the host cores.
 """
 from __future__ import annotations
 
@@ -44,6 +46,32 @@ def time_steps(fn, steps: int, warmup: int):
     return (time.perf_counter() - t0) / steps
 
 
+def time_steps_spread(fn, steps: int, warmup: int, batch: int):
+    """`warmup` untimed steps, then exactly `steps` timed ones between two synchronisations.  Returns the
+    mean by the wall clock and the per-step times of the batches of `batch` steps the same timed steps
+    are cut into (one HIP event between batches), sorted."""
+    import torch
+    for i in range(warmup):
+        fn(i)
+    n_b = (steps + batch - 1) // batch
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(n_b + 1)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    evs[0].record()
+    for i in range(steps):
+        fn(warmup + i)
+        if (i + 1) % batch == 0 or i == steps - 1:
+            evs[(i + batch) // batch].record()
+    torch.cuda.synchronize()
+    mean = (time.perf_counter() - t0) / steps
+    per = sorted(evs[b].elapsed_time(evs[b + 1]) * 1e-3 / (min(steps, (b + 1) * batch) - b * batch) for b in range(n_b))
+    return mean, per
+
+
+def pct(sorted_vals, q: float):
+    return sorted_vals[int(q * (len(sorted_vals) - 1))]
+
+
 def make_pools(runtime, w, n_pools: int):
     """n_pools identical pools (same page ids, distinct HBM), each with its own plan and buffers."""
     first = runtime.DevicePool(w.num_pages, w.num_kv_heads, w.kv_dtype)
@@ -60,31 +88,25 @@ def make_pools(runtime, w, n_pools: int):
     return pools
 
 
-def bench_decode(runtime, hkv, w, steps: int, warmup: int, n_pools: int, profile_steps: int, flags: int = 0):
+def bench_decode(runtime, hkv, w, steps: int, warmup: int, n_pools: int, profile_steps: int, flags: int = 0,
+                 batch: int = 8, graph: bool = False, hot: bool = False):
+    """Times attn_decode_plan_run over `w`, rotating over n_pools identical pools.  Returns a dict:
+    sec (median step, seconds), sec_mean (wall clock over the timed steps), node_ms / merge_ms (each kernel's
+    own duration from begin/end events attached to its dispatches), and what describes the plan."""
     import torch
     pools = make_pools(runtime, w, n_pools)
     runners = [runtime.DecodeRunner(p, w, flags=flags) for p in pools]
     f = w.forest
     t0 = time.perf_counter()                                    # tree walk, work list, upload: once per topology
-    for _ in range(5):
+    for _ in range(3):
         hkv.hkv_decode_plan_destroy(hkv.hkv_decode_plan_create(pools[0].handle, f.nodes, f.node_pages, f.req_leaf, w.num_q_heads))
-    plan_ms = (time.perf_counter() - t0) / 5 * 1e3
-    sec = time_steps(lambda i: runners[i % n_pools].run(), steps, warmup)
-    # spread of the step time: batches of 8 steps between two events each (an event per step would add its own cost)
-    batch_ms = []
-    for bidx in range(25):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for i in range(8):
-            runners[(bidx * 8 + i) % n_pools].run()
-        e1.record()
-        e1.synchronize()
-        batch_ms.append(e0.elapsed_time(e1) / 8)
-    batch_ms.sort()
+    plan_ms = (time.perf_counter() - t0) / 3 * 1e3
+    mean, per = time_steps_spread(lambda i: runners[i % n_pools].run(), steps, warmup, batch)
+    res = {"sec": pct(per, 0.5), "sec_mean": mean,
+           "ms_per_step_p10_p50_p90": [round(pct(per, q) * 1e3, 5) for q in (0.1, 0.5, 0.9)]}
     # same steps again with a begin and an end HIP event attached to each kernel dispatch (on the launch
     # stream): the kernels' own durations, as a kernel trace reports them
-    node_ms = merge_ms = 0.0
-    node_each = []
+    node_each, merge_each = [], []
     for r in runners:
         hkv.hkv_decode_plan_set_profiling(r.plan, True)
     for i in range(profile_steps):
@@ -92,31 +114,48 @@ def bench_decode(runtime, hkv, w, steps: int, warmup: int, n_pools: int, profile
         r.run()
         a, b = hkv.hkv_decode_plan_elapsed_ms(r.plan)
         node_each.append(a)
-        node_ms += a
-        merge_ms += b
-    node_ms /= max(1, profile_steps)
-    merge_ms /= max(1, profile_steps)
-    # the dominant kernel alone: back-to-back launches between two events on the launch stream, so
-    # that no event sits between kernels (per-launch time = kernel + the gap to the next launch)
-    for r in runners:
-        hkv.hkv_decode_plan_set_profiling(r.plan, 2)
-    for i in range(warmup):
-        runners[i % n_pools].run()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    ev0.record()
-    for i in range(steps):
-        runners[(warmup + i) % n_pools].run()
-    ev1.record()
-    torch.cuda.synchronize()
-    node_batch_ms = ev0.elapsed_time(ev1) / steps
+        merge_each.append(b)
     for r in runners:
         hkv.hkv_decode_plan_set_profiling(r.plan, 0)
-    # cache-resident variant for context (always the same pool)
-    sec_hot = time_steps(lambda i: runners[0].run(), steps, warmup)
-    info = {
+    res["node_ms"] = sum(node_each) / max(1, len(node_each))
+    res["merge_ms"] = sum(merge_each) / max(1, len(merge_each))
+    if node_each:
+        srt = sorted(node_each)
+        res["node_kernel_ms_p10_p50_p90"] = [round(pct(srt, q), 5) for q in (0.1, 0.5, 0.9)]
+    if graph:
+        # the same steps as one HIP graph of n_pools steps (one per pool), replayed: no launch call between kernels
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for r in runners:
+                r.run()
+            side.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                for r in runners:
+                    r.run()
+        torch.cuda.synchronize()
+        reps = max(1, steps // n_pools)
+        for _ in range(3):
+            g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        res["graph_replay_ms_per_step"] = round(e0.elapsed_time(e1) / (reps * n_pools), 5)
+        del g
+    if hot:   # cache-resident variant for context (always the same pool; only meaningful below 256 MB)
+        res["cache_resident_ms_per_step"] = round(time_steps(lambda i: runners[0].run(), steps, warmup) * 1e3, 5)
+    res["info"] = {
         "items": int(len(hkv.hkv_decode_plan_items(runners[0].plan))),
+        "workgroups": int(hkv.hkv_decode_plan_num_workgroups(runners[0].plan)),
         "partials": int(hkv.hkv_decode_plan_num_parts(runners[0].plan)),
+        "max_partials_per_row": int(hkv.hkv_decode_plan_max_parts(runners[0].plan)),
         "workspace_bytes": int(runners[0].ws_bytes),
+        "host_planning_ms_once_per_topology": round(plan_ms, 3),
     }
     for r in runners:
         r.close()
@@ -124,13 +163,29 @@ def bench_decode(runtime, hkv, w, steps: int, warmup: int, n_pools: int, profile
         p.close()
     del runners, pools
     torch.cuda.empty_cache()
-    info["node_kernel_batch_ms"] = round(node_batch_ms, 5)
-    info["ms_per_step_p10_p50_p90"] = [round(batch_ms[int(q * (len(batch_ms) - 1))], 5) for q in (0.1, 0.5, 0.9)]
-    info["host_planning_ms_once_per_topology"] = round(plan_ms, 3)
-    if node_each:
-        srt = sorted(node_each)
-        info["node_kernel_ms_p10_p50_p90"] = [round(srt[int(q * (len(srt) - 1))], 5) for q in (0.1, 0.5, 0.9)]
-    return sec, node_ms, merge_ms, sec_hot, info
+    return res
+
+
+def decode_entry(w, res):
+    """One decode workload's figures as they go into the JSON line."""
+    uniq = w.unique_kv_bytes()
+    out = {
+        "unique_kv_bytes": uniq,
+        "unique_kv_GBps": round(uniq / res["sec"] / 1e9, 2),
+        "attended_tokens_per_s": round(w.forest.attended_tokens() / res["sec"], 1),
+        "ms_per_step": round(res["sec"] * 1e3, 5),
+        "ms_per_step_mean_wall": round(res["sec_mean"] * 1e3, 5),
+        "ms_per_step_p10_p50_p90": res["ms_per_step_p10_p50_p90"],
+        "hbm_frac_whole_step": round(uniq / res["sec"] / 1e9 / HBM_PEAK_GBS, 4),
+        "node_kernel_ms": round(res["node_ms"], 5),
+        "node_kernel_hbm_frac": round(uniq / (res["node_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) if res["node_ms"] else None,
+        "merge_kernel_ms": round(res["merge_ms"], 5),
+        **res["info"],
+    }
+    for k in ("node_kernel_ms_p10_p50_p90", "graph_replay_ms_per_step", "cache_resident_ms_per_step"):
+        if k in res:
+            out[k] = res[k]
+    return out
 
 
 def bench_prefill(runtime, hkv, w, steps: int, warmup: int):
@@ -401,42 +456,112 @@ def _rand_bits(torch, shape):
 
 
 def cpu_baseline_decode(w, budget_s: float = 20.0):
-    """The fp64 oracle as it stands on the host cores: whole workload, repeated within the budget."""
+    """The fp64 oracle as it stands on the host cores, on a bounded sample of the workload: the requests
+    below the first root (the whole workload when it has a single root), repeated within the budget."""
+    import numpy as np
     from oracle import oracle as orc
+    f = w.forest
+    first_root = int(f.path(int(f.req_leaf[0]))[0])
+    sample = [r for r in range(f.n_req) if int(f.path(int(f.req_leaf[r]))[0]) == first_root]
+    nodes = sorted({v for r in sample for v in f.path(int(f.req_leaf[r]))})
     hp = orc.HostPool(w.num_pages, w.num_kv_heads, w.kv_dtype)
-    hp.fill_from(w)
+    for v in nodes:                                              # only the nodes the sample reads
+        if f.n_tokens[v]:
+            k, vv = w.node_kv(v)
+            hp.write(f.node_pages[f.page_begin[v]: f.page_begin[v] + f.n_pages[v]], 0, k, vv)
     bt, kv_len, *_ = orc.flatten_workload(w)
     q = w.q()
+    idx = np.asarray(sample)
     reps, t_total = 0, 0.0
     while reps < 1 or (t_total < budget_s / 2 and reps < 500):      # about 10 s of CPU work
         t0 = time.perf_counter()
-        orc.attn_decode(hp, q, bt, kv_len, float(w.scale))
+        orc.attn_decode(hp, q[idx], bt[idx], kv_len[idx], float(w.scale))
         t_total += time.perf_counter() - t0
         reps += 1
     sec = t_total / reps
+    uniq = int(sum(int(f.n_tokens[v]) for v in nodes)) * w.kv_bytes_per_token()
+    attended = int(kv_len[idx].sum())
     return {
-        "value": w.unique_kv_bytes() / sec / 1e9,
+        "value": uniq / sec / 1e9,
         "unit": "GB/s",
         "cores": orc.num_threads(),
         "kind": "oracle",
-        "sample": f"whole workload ({w.forest.n_req} requests, {w.forest.attended_tokens()} attended tokens), "
-                  f"mean of {reps} runs, {sec:.3f} s each; the oracle gathers every request's full sequence, "
-                  "so it reads attended rather than unique bytes",
-        "attended_tokens_per_s": w.forest.attended_tokens() / sec,
-        "seconds_per_step": sec,
+        "sample": f"{len(sample)} of {f.n_req} requests (all requests below the first root: {len(nodes)} nodes, "
+                  f"{uniq} unique KV bytes, {attended} attended tokens), mean of {reps} runs, {sec:.3f} s each; "
+                  "the oracle gathers every request's full sequence, so it reads attended rather than unique bytes",
+        "attended_tokens_per_s": attended / sec,
+        "seconds_per_run": sec,
     }
+
+
+def load_traffic(name: str):
+    """HBM bytes per launch of the dominant kernel from the rocprofv3 counter runs kept under profiles/."""
+    tpath = os.path.join(ROOT, "profiles", name)
+    if os.path.exists(tpath):
+        try:
+            return json.load(open(tpath)).get("hbm_bytes_per_launch")
+        except Exception:
+            return None
+    return None
+
+
+def sweep_read_probe(torch, bp):
+    """Plain streaming reads over launch shapes and sizes: the best rate this machine gives a kernel that only reads."""
+    rows = []
+    sizes = {"142.6 MB (c2)": 142606336, "184.5 MB (c3)": 184549376, "2416 MB (c5)": 2415919104}
+    for label, nbytes in sizes.items():
+        n_buf = 4 if nbytes < (1 << 30) else 1
+        bufs = [torch.zeros(nbytes // 4, dtype=torch.int32, device="cuda") for _ in range(n_buf)]
+        reps = 100 if nbytes < (1 << 30) else 12
+        for wgs in (2, 4, 8, 16):
+            for threads in (256, 512, 1024):
+                if wgs * threads > 2048 * 2:
+                    continue
+                for in_flight in (2, 4, 8, 16):
+                    for contiguous in (False, True):
+                        for nt in (False, True):
+                            g = bp.hbm_read(bufs, nbytes, reps, wgs, threads, in_flight, contiguous, nt)
+                            rows.append({"size": label, "wgs_per_cu": wgs, "threads": threads, "in_flight": in_flight,
+                                         "contiguous": contiguous, "nontemporal": nt, "GBps": round(g, 1)})
+        del bufs
+        torch.cuda.empty_cache()
+        best = max((r for r in rows if r["size"] == label), key=lambda r: r["GBps"])
+        log(f"read probe {label}: best {best}")
+    # the same bytes as randomly placed (page, head) blocks, one block per wavefront at a time: a decode step's pattern
+    for label, nbytes in sizes.items():
+        n_buf = 4 if nbytes < (1 << 30) else 1
+        bufs = [torch.zeros(nbytes // 4, dtype=torch.int32, device="cuda") for _ in range(n_buf)]
+        reps = 100 if nbytes < (1 << 30) else 12
+        for block in (2048, 4096):
+            g = torch.Generator(device="cuda")
+            g.manual_seed(5)
+            for perm in (False, True):
+                n_blocks = nbytes // block
+                order = (torch.randperm(n_blocks, device="cuda", generator=g) if perm
+                         else torch.arange(n_blocks, device="cuda")).to(torch.int32)
+                for wgs in (1, 2, 3, 4, 8):
+                    for depth in (1, 2, 4):
+                        for nt in (False, True):
+                            gb = bp.hbm_paged_read(bufs, order, block, reps, wgs, 256, depth, nt)
+                            rows.append({"size": label, "paged_block_bytes": block, "random_order": perm, "wgs_per_cu": wgs,
+                                         "threads": 256, "blocks_ahead": depth, "nontemporal": nt, "GBps": round(gb, 1)})
+        del bufs
+        torch.cuda.empty_cache()
+        best = max((r for r in rows if r["size"] == label and r.get("random_order")), key=lambda r: r["GBps"])
+        log(f"paged read probe {label}: best random-order {best}")
+    return rows
 
 
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=1000)
-    ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--pools", type=int, default=4, help="identical pools to rotate over (cache defeat)")
-    ap.add_argument("--no-extras", action="store_true", help="skip the context workloads (c3, c4, pool write)")
-    ap.add_argument("--c5", action="store_true", help="also time the fp8 forest (2.4 GB pool, slow to generate)")
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--pools", type=int, default=4, help="identical pools the small decode workloads rotate over (cache defeat)")
+    ap.add_argument("--no-extras", action="store_true", help="skip the other workloads (c2, c3, c4, pool write, probes)")
     ap.add_argument("--fp8-matrix", action="store_true",
                     help="run the fp8 forest on the fp8 matrix instruction (HKV_PLAN_FP8_MATRIX) instead of the default path")
+    ap.add_argument("--hot", action="store_true", help="also time the small decode workloads without pool rotation (cache-resident)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--decode-loop", action="store_true",
                     help="generation loop on the c2 shape: token append + plan update + decode per step, with a growing "
@@ -444,12 +569,14 @@ def main() -> int:
     ap.add_argument("--mixed", action="store_true", help="a chunked-prefill step: one prefill launch vs tree decode + prefill")
     ap.add_argument("--sensitivity", choices=["llama3-8b", "qwen3-8b", "qwen3-14b", "qwen3-32b"], default=None,
                     help="prefix-sharing sensitivity grid for one model's layer shape instead of the headline line")
-    ap.add_argument("--profile-workload", choices=["c3", "c4", "c5", "c5_leaves", "c5_roots"], default=None,
-                    help="run only this context workload for a few steps and print its figures (for rocprofv3 runs "
-                         "of the other kernels; not the headline line)")
+    ap.add_argument("--profile-workload", choices=["c2", "c3", "c4", "c5", "c5_leaves", "c5_roots", "c3_leaves", "c3_shared"],
+                    default=None,
+                    help="run only this workload for a few steps and print its figures (for rocprofv3 runs; not the headline line)")
     ap.add_argument("--workflow", choices=["map_reduce", "debate", "reflect"], default=None,
                     help="scheduling-layer experiment: run the prefill side of a synthetic workflow on one worker "
                          "under several call orders and print token steps beside measured GPU time (not the headline line)")
+    ap.add_argument("--sweep-read-probe", action="store_true",
+                    help="sweep the plain-read probe over launch shapes and sizes and print the table (not the headline line)")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
                     help="also run a plain elementwise copy kernel over this many MiB three times (a known-size "
                          "kernel to calibrate rocprofv3's FETCH_SIZE / WRITE_SIZE counters against)")
@@ -461,6 +588,7 @@ def main() -> int:
 
     import torch
     from paper_2603_16104_amd import binding as hkv, runtime, workloads as wl
+    import bench_probes as bp
     if not torch.cuda.is_available():
         print("bench.py needs an MI355X; no GPU is visible", file=sys.stderr)
         return 2
@@ -476,6 +604,10 @@ def main() -> int:
         log(f"copy probe: 3 x elementwise add over {n * 4} bytes read + {n * 4} bytes written")
         del src, dst
         torch.cuda.empty_cache()
+
+    if args.sweep_read_probe:
+        print(json.dumps(sweep_read_probe(torch, bp)), flush=True)
+        return 0
 
     if args.workflow:
         print(json.dumps(bench_workflow(runtime, hkv, wl, args.workflow)), flush=True)
@@ -494,6 +626,7 @@ def main() -> int:
               flush=True)
         return 0
 
+    fp8_flags = hkv.PLAN_FP8_MATRIX if args.fp8_matrix else 0
     if args.profile_workload:
         name = args.profile_workload
         if name == "c4":
@@ -504,95 +637,98 @@ def main() -> int:
                               "mfma_bf16_frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
                               "new_tokens_per_s": round(w4.total_q() / s4, 1), "tiles": t4}), flush=True)
         else:
-            # c5_leaves / c5_roots: the fp8 forest with its roots, resp. its leaves, cut down to one block, to
-            # time the few-row items (private leaves) and the many-row items (shared roots) apart
-            wx = {"c3": wl.config3, "c5": wl.config5, "c5_leaves": lambda: wl.config5(root_tokens=16),
-                  "c5_roots": lambda: wl.config5(child_tokens=16)}[name]()
-            sx, nx, mx, hx, ix = bench_decode(runtime, hkv, wx, max(1, min(args.steps, 40)), 10,
-                                              args.pools if name == "c3" else 1, 5,
-                                              hkv.PLAN_FP8_MATRIX if name != "c3" and args.fp8_matrix else 0)
-            print(json.dumps({"workload": wx.name, "ms_per_step": round(sx * 1e3, 5),
-                              "unique_kv_GBps": round(wx.unique_kv_bytes() / sx / 1e9, 2),
-                              "node_kernel_ms": round(nx, 5),
-                              "merge_kernel_ms": round(mx, 5), **ix}), flush=True)
+            # *_leaves / c5_roots / c3_shared: the forest with its shared nodes, resp. its leaves, cut down to one
+            # block, to time the few-row items (private leaves) and the many-row items (shared nodes) apart
+            wx = {"c2": wl.config2, "c3": wl.config3, "c5": wl.config5,
+                  "c5_leaves": lambda: wl.config5(root_tokens=16), "c5_roots": lambda: wl.config5(child_tokens=16),
+                  "c3_leaves": lambda: wl.config3(root_tokens=16, child_tokens=16),
+                  "c3_shared": lambda: wl.config3(leaf_tokens=16)}[name]()
+            small = wx.unique_kv_bytes() < (1 << 29)
+            rx = bench_decode(runtime, hkv, wx, max(1, min(args.steps, 100 if small else 40)), 10,
+                              args.pools if small else 1, 10, fp8_flags if wx.kv_dtype == wl.KV_FP8_E4M3 else 0,
+                              batch=8 if small else 1)
+            print(json.dumps({"workload": wx.name, **decode_entry(wx, rx)}), flush=True)
         return 0
 
-    w = wl.config2()
-    log(f"workload {w.name}: {w.forest.n_req} requests, unique KV {w.unique_kv_bytes() / 1e6:.1f} MB")
-    sec, node_ms, merge_ms, sec_hot, info = bench_decode(runtime, hkv, w, args.steps, args.warmup, args.pools,
-                                                        min(args.steps, 100))
-    uniq = w.unique_kv_bytes()
-    value = uniq / sec / 1e9
-    node_batch_ms = info.pop("node_kernel_batch_ms")
-    node_pct = info.pop("node_kernel_ms_p10_p50_p90", None)
-    achieved = uniq / (node_ms * 1e-3) / 1e9
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "decode_c2_traffic.json")
-    if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
-        except Exception:
-            traffic = None
+    # ---- headline: the largest single-GPU configuration (2.4 GB of fp8 KV: far beyond the last-level cache, one pool)
+    w5 = wl.config5()
+    f5 = w5.forest
+    log(f"workload {w5.name}: {f5.n_req} requests, unique KV {w5.unique_kv_bytes() / 1e6:.1f} MB")
+    r5 = bench_decode(runtime, hkv, w5, args.steps, args.warmup, 1, min(max(args.steps, 10), 50), fp8_flags, batch=1)
+    e5 = decode_entry(w5, r5)
+    uniq = w5.unique_kv_bytes()
+    achieved = uniq / (r5["node_ms"] * 1e-3) / 1e9
     result = {
         "metric": "decode_unique_kv_bandwidth",
-        "value": round(value, 2),
+        "value": e5["unique_kv_GBps"],
         "unit": "GB/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": round(sec * 1e3, 5),
+        "ms_per_step": e5["ms_per_step"],
+        "ms_per_step_how": "median over the timed steps (one HIP event after every step); ms_per_step_mean_wall is "
+                           "the wall clock between two synchronisations around the same steps divided by their number",
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16",
+        "dtype": "bf16 matrix arithmetic with fp32 accumulation over fp8 e4m3 KV" if not args.fp8_matrix else
+                 "fp8 e4m3 matrix arithmetic (two-term q and p) with fp32 accumulation over fp8 e4m3 KV",
         "data": "synthetic",
         "config": {
-            "workload": "c2_llama8b_decode: 64 requests, 2048-token shared prefix + 512 private tokens each, "
-                        "32 q / 8 kv heads, head_dim 128, page 16, bf16 KV, 1 query token per request",
-            "unique_kv_bytes": uniq,
-            "attended_tokens": w.forest.attended_tokens(),
-            "attended_tokens_per_s": round(w.forest.attended_tokens() / sec, 1),
-            "pools_rotated": args.pools,
+            "workload": "c5_forest_fp8_decode: 16 roots of 8192 tokens x 32 children of 2048 tokens = 512 requests, "
+                        "64 q / 8 kv heads, head_dim 128, page 16, fp8 e4m3 KV with per-page per-head fp32 scales, "
+                        "bf16 queries, 1 query token per request",
+            "pools_rotated": 1,
             "step": "attn_decode_plan_run = per-node decode kernel + lse merge kernel; plan built once outside",
-            **info,
+            **{k: v for k, v in e5.items() if k not in ("unique_kv_GBps", "ms_per_step")},
         },
         "roofline": {
             "bound": "hbm",
-            "kernel": "decode_node_kernel<bf16>",
+            "kernel": "decode_node_kernel<fp8>" if not args.fp8_matrix else "decode_node_kernel<fp8 matrix>",
             "achieved": round(achieved, 2),
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
-            "traffic": traffic,
-            "kernel_ms": round(node_ms, 5),
+            "traffic": load_traffic("decode_c5_traffic.json"),
+            "traffic_how": "HBM bytes per launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs kept under profiles/ "
+                           "(a stored figure of the same command, not measured in this run)",
+            "algorithmic_bytes_per_launch": uniq,
+            "kernel_ms": round(r5["node_ms"], 5),
             "kernel_ms_how": "begin/end HIP events attached to each dispatch of this kernel on the launch stream, "
-                             "inside whole steps, rotating pools; average over the profiled steps",
-            "kernel_ms_p10_p50_p90": node_pct,
-            "merge_kernel_ms": round(merge_ms, 5),
-            "kernel_ms_back_to_back_incl_launch_gap": round(node_batch_ms, 5),
-            "whole_step_frac": round(value / HBM_PEAK_GBS, 4),
+                             "inside whole steps; average over the profiled steps",
+            "kernel_ms_p10_p50_p90": r5.get("node_kernel_ms_p10_p50_p90"),
+            "merge_kernel_ms": round(r5["merge_ms"], 5),
+            "whole_step_frac": e5["hbm_frac_whole_step"],
         },
         "paper_context": "the paper reports end-to-end speedups only (up to 1.56x over KVFlow on 2x H100 NVL); "
                          "no attention-kernel number exists to compare with",
+        "extra": {},
     }
-    result["extra"] = {"c2_cache_resident_GBps": round(uniq / sec_hot / 1e9, 2)}
-    # what a kernel that only reads the same number of bytes reaches, same rotation, same launch cadence
-    bufs = [torch.zeros(uniq // 4, dtype=torch.int32, device="cuda") for _ in range(args.pools)]
-    read_gbps = hkv.hkv_hbm_read_probe(bufs, uniq, 100)
-    del bufs
+    log("c5 done")
+    # what a kernel that only reads the same number of bytes reaches (best launch shape of the probe sweep)
+    buf = [torch.zeros(uniq // 4, dtype=torch.int32, device="cuda")]
+    read_gbps = max(bp.hbm_read(buf, uniq, 10, wgs, 256, inf) for wgs, inf in ((8, 4), (8, 8), (16, 4)))
+    del buf
     torch.cuda.empty_cache()
     result["roofline"]["plain_read_same_bytes_GBps"] = round(read_gbps, 1)
     result["roofline"]["frac_of_plain_read"] = round(achieved / read_gbps, 4)
 
     if not args.no_extras:
-        w3 = wl.config3()
-        s3, n3, m3, h3, i3 = bench_decode(runtime, hkv, w3, max(20, args.steps // 2), args.warmup, args.pools, 50)
-        result["extra"]["c3_fanout_decode"] = {
-            "unique_kv_GBps": round(w3.unique_kv_bytes() / s3 / 1e9, 2),
-            "attended_tokens_per_s": round(w3.forest.attended_tokens() / s3, 1),
-            "ms_per_step": round(s3 * 1e3, 5), "node_kernel_ms": round(n3, 5), "merge_kernel_ms": round(m3, 5),
-            "hbm_frac_whole_step": round(w3.unique_kv_bytes() / s3 / 1e9 / HBM_PEAK_GBS, 4), "node_kernel_batch_ms": i3.pop("node_kernel_batch_ms"), **i3}
-        log("c3 done")
+        small_steps = max(20, min(5 * args.steps, 1000))
+        for key, make, tfile in (("c2_llama8b_decode", wl.config2, "decode_c2_traffic.json"),
+                                 ("c3_fanout_decode", wl.config3, "decode_c3_traffic.json")):
+            wx = make()
+            rx = bench_decode(runtime, hkv, wx, small_steps, 50, args.pools, 100, batch=8, graph=True, hot=args.hot)
+            result["extra"][key] = {"pools_rotated": args.pools, **decode_entry(wx, rx)}
+            t = load_traffic(tfile)
+            if t is not None:
+                result["extra"][key]["node_kernel_hbm_traffic_bytes"] = t
+            bufs = [torch.zeros(wx.unique_kv_bytes() // 4, dtype=torch.int32, device="cuda") for _ in range(args.pools)]
+            g = max(bp.hbm_read(bufs, wx.unique_kv_bytes(), 100, wgs, 256, inf) for wgs, inf in ((8, 4), (8, 8), (16, 4)))
+            del bufs
+            torch.cuda.empty_cache()
+            result["extra"][key]["plain_read_same_bytes_GBps"] = round(g, 1)
+            log(f"{key} done")
         w4 = wl.config4()
         s4, k4, t4 = bench_prefill(runtime, hkv, w4, 5, 2)
         tflops = w4.useful_flop() / (k4 * 1e-3) / 1e12
@@ -603,26 +739,17 @@ def main() -> int:
             "useful_flop": int(w4.useful_flop()), "tiles": t4}
         # matrix-core ceiling with nothing else running: zero operands (nominal clock) and random ones
         # (the clock settles under the power limit), two wavefronts per SIMD as in the prefill kernel
-        tf0, ghz0 = hkv.hkv_mfma_probe(100000, False, 2)
-        tf1, ghz1 = hkv.hkv_mfma_probe(100000, True, 2)
+        tf0, ghz0 = bp.mfma_bf16(100000, False, 2)
+        tf1, ghz1 = bp.mfma_bf16(100000, True, 2)
         result["extra"]["mfma_probe_bf16"] = {
             "zero_operands_TFLOPs": round(tf0, 1), "zero_operands_clock_GHz": round(ghz0, 3),
             "random_operands_TFLOPs": round(tf1, 1), "random_operands_clock_GHz": round(ghz1, 3)}
         result["extra"]["c4_prefix_hit_prefill"]["frac_of_random_operand_probe"] = round(tflops / tf1, 4)
         log("c4 done")
-        result["extra"]["kv_pool_write_src_GBps"] = round(bench_pool_write(runtime, w, 20), 1)
-    if args.c5:
-        w5 = wl.config5()
-        s5, n5, m5, h5, i5 = bench_decode(runtime, hkv, w5, 40, 10, 1, 10, hkv.PLAN_FP8_MATRIX if args.fp8_matrix else 0)
-        result["extra"]["c5_forest_fp8_decode"] = {
-            "path": "fp8 matrix instruction" if args.fp8_matrix else "codes widened to bf16",
-            "unique_kv_GBps": round(w5.unique_kv_bytes() / s5 / 1e9, 2),
-            "attended_tokens_per_s": round(w5.forest.attended_tokens() / s5, 1),
-            "ms_per_step": round(s5 * 1e3, 5), "node_kernel_ms": round(n5, 5), "merge_kernel_ms": round(m5, 5),
-            "hbm_frac_whole_step": round(w5.unique_kv_bytes() / s5 / 1e9 / HBM_PEAK_GBS, 4), "node_kernel_batch_ms": i5.pop("node_kernel_batch_ms"), **i5}
+        result["extra"]["kv_pool_write_src_GBps"] = round(bench_pool_write(runtime, wl.config2(), 20), 1)
     if not args.no_cpu:
         log("timing the CPU oracle")
-        result["cpu_baseline"] = cpu_baseline_decode(w)
+        result["cpu_baseline"] = cpu_baseline_decode(w5)
     else:
         result["cpu_baseline"] = None
     print(json.dumps(result), flush=True)

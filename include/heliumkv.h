@@ -103,7 +103,7 @@ typedef struct {
     int32_t page_size;    /* 16, 32, 64 or 128 tokens */
     int32_t num_kv_heads;
     int32_t head_dim;     /* must be 128 */
-    int32_t dtype;        /* HKV_BF16 or HKV_FP8_E4M3 */
+    int32_t dtype;        /* HKV_BF16, HKV_FP8_E4M3 or HKV_FP32 */
     void *k_pages;        /* device, num_pages*(page_size/16)*num_kv_heads*2048 elements, format above */
     void *v_pages;        /* device, same size */
     float *k_scale;       /* device, [num_pages*(page_size/16)][num_kv_heads]; fp8 pools only, else NULL */
@@ -375,13 +375,11 @@ size_t hkv_static_workspace_bytes(void);
 int attn_decode_plan_run_static(hkv_decode_plan *plan, const void *q, float scale, void *out, float *lse_out,
                                 void *stream);
 
-/* Profiling aid.  mode 0: off.  mode 1: attn_decode_plan_run attaches a begin and an end HIP event
- * to each of its two kernel dispatches on the stream it is given, so that an interval is the
- * kernel's own duration on the device, without the gap to its neighbours in the queue.  mode 2: attn_decode_plan_run launches only the per-node kernel
- * and leaves `out` untouched, so that a caller can time a batch of back-to-back launches of that
- * kernel with two events of its own.
- * hkv_decode_plan_elapsed_ms (mode 1) waits for the most recent profiled run to finish and returns
- * the GPU time of the per-node kernel and of the merge kernel in milliseconds.
+/* Profiling aid.  mode 0: off.  mode 1: attn_decode_plan_run attaches a begin and an end HIP event to
+ * each of its two kernel dispatches on the stream it is given, so that an interval is the kernel's own
+ * duration on the device, without the gap to its neighbours in the queue.
+ * hkv_decode_plan_elapsed_ms waits for the most recent profiled run to finish and returns the GPU time
+ * of the per-node kernel and of the merge kernel in milliseconds.
  * EINVAL if no profiled run has been queued. */
 int hkv_decode_plan_set_profiling(hkv_decode_plan *plan, int32_t mode);
 int hkv_decode_plan_elapsed_ms(hkv_decode_plan *plan, float *node_ms /* host */, float *merge_ms /* host */);
@@ -529,29 +527,6 @@ int trt_evaluate(const hkv_trt *tree, const int32_t *sigma_indptr, const int32_t
  * NULL), T.  ERANGE if a call's worker is >= n_workers. */
 int trt_schedule(const hkv_trt *tree, int32_t n_workers, int64_t capacity, int32_t *sigma_indptr,
                  int32_t *sigma, int64_t *B, int64_t *C, int64_t *T);
-
-/* ------------------------------------------------------------------------------------------
- * Diagnostics (no part of the attention path; for callers that report a roofline).
- * Runs a register-only stream of bf16 matrix-core instructions (v_mfma_f32_32x32x16_bf16, the
- * one the prefill kernel is built on) on every compute unit of the current device,
- * waves_per_simd in {1, 2} wavefronts per SIMD, iters x 4 instructions per wavefront, with
- * all-zero operands (random_operands = 0) or random ones (1: realistic switching activity, the
- * clock settles under the power limit).  Blocks until done.  tflops (host): dense bf16 TFLOP/s by
- * HIP event time; clock_ghz (host): core clock during the run, from the core-cycle and 100 MHz
- * counters read inside the kernel.  Allocates and frees a few KiB of device memory.
- * EINVAL (null pointers, iters < 1, waves_per_simd not 1 or 2), EHIP. */
-int hkv_mfma_probe(int32_t iters, int32_t random_operands, int32_t waves_per_simd, float *tflops,
-                   float *clock_ghz, void *stream);
-
-/* Plain streaming-read ceiling: a kernel that does nothing but read `bytes` bytes (a multiple of
- * 16; 16-byte loads, four in flight per lane, 8 workgroups of 256 threads per compute unit) is
- * launched `reps` times back to back, launch i over bufs[i % n_buf], so that with buffers larger
- * in sum than the last-level cache every launch reads HBM, exactly as a decode step over rotating
- * pools does.  bufs: host array of n_buf device pointers, 16-byte aligned, owned by the caller.
- * gbps (host): bytes * reps / time between two HIP events around the launches (launch gaps
- * included, as in a real step).  Blocks until done.  EINVAL, EHIP. */
-int hkv_hbm_read_probe(const void *const *bufs, int32_t n_buf, size_t bytes, int32_t reps, float *gbps,
-                       void *stream);
 
 #ifdef __cplusplus
 }

@@ -34,7 +34,7 @@ EXPORTS = [
     "hkv_decode_plan_set_profiling", "hkv_decode_plan_elapsed_ms",
     "attn_decode_prefix_tree", "attn_decode_workspace_bytes", "hkv_prefill_plan_create", "hkv_prefill_plan_destroy",
     "hkv_prefill_plan_num_tiles", "hkv_prefill_plan_tiles", "attn_prefill_plan_run", "attn_prefill_plan_run_ws", "hkv_prefill_plan_workspace_bytes", "attn_prefill_with_prefix",
-    "attn_prefill_workspace_bytes", "hkv_mfma_probe", "hkv_hbm_read_probe",
+    "attn_prefill_workspace_bytes",
     "kv_cache_create", "kv_cache_destroy", "kv_cache_acquire", "kv_cache_release", "kv_cache_unpin", "kv_cache_stats",
     "trt_build", "trt_destroy", "trt_num_nodes", "trt_num_syms", "trt_num_calls", "trt_nodes", "trt_prefill_usage",
     "trt_evaluate", "trt_schedule",
@@ -330,7 +330,7 @@ def attn_decode_plan_run_static(plan, q, scale: float, out, lse_out, stream=None
 
 
 def hkv_decode_plan_set_profiling(plan, mode) -> None:
-    """mode: 0/False off, 1/True events around both kernels, 2 launch the per-node kernel only."""
+    """mode: 0/False off, 1/True begin and end events on both kernel dispatches."""
     _check(lib().hkv_decode_plan_set_profiling(plan, C.c_int32(int(mode))))
 
 
@@ -402,23 +402,6 @@ def attn_prefill_with_prefix(pool, q, cu_q, block_table, kv_len, num_q_heads: in
 
 def attn_prefill_workspace_bytes(total_q: int, num_q_heads: int) -> int:
     return int(lib().attn_prefill_workspace_bytes(C.c_int32(total_q), C.c_int32(num_q_heads)))
-
-
-def hkv_mfma_probe(iters: int, random_operands: bool, waves_per_simd: int = 2, stream=None):
-    """Returns (TFLOP/s, core clock in GHz) of the register-only bf16 matrix-core stream."""
-    tf, ghz = C.c_float(0.0), C.c_float(0.0)
-    _check(lib().hkv_mfma_probe(C.c_int32(iters), C.c_int32(1 if random_operands else 0), C.c_int32(waves_per_simd),
-                                C.byref(tf), C.byref(ghz), _stream(stream)))
-    return float(tf.value), float(ghz.value)
-
-
-def hkv_hbm_read_probe(bufs, nbytes: int, reps: int, stream=None) -> float:
-    """GB/s of a plain read kernel over the device tensors `bufs` (nbytes of each), launch i on bufs[i % len]."""
-    ptrs = (C.c_void_p * len(bufs))(*[b.data_ptr() for b in bufs])
-    gbps = C.c_float(0.0)
-    _check(lib().hkv_hbm_read_probe(ptrs, C.c_int32(len(bufs)), C.c_size_t(nbytes), C.c_int32(reps), C.byref(gbps),
-                                    _stream(stream)))
-    return float(gbps.value)
 
 
 # ---------------------------------------------------------------------------------------------

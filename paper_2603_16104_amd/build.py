@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libheliumkv.so")
-SOURCES = ["api.cpp", "decode.hip", "merge.hip", "pool_write.hip", "prefill.hip", "probe.hip", "rows_fp32.hip", "trt.cpp", "cache.cpp"]
+SOURCES = ["api.cpp", "decode.hip", "merge.hip", "pool_write.hip", "prefill.hip", "rows_fp32.hip", "trt.cpp", "cache.cpp"]
 HEADERS = ["hkv_internal.h", "hkv_device.h", os.path.join("..", "..", "include", "heliumkv.h")]
 
 # Packed-FP32 VALU forms are switched off for every kernel in this library.

@@ -79,7 +79,7 @@ struct hkv_decode_plan {
     int32_t n_stages = 3;  // LDS stages of 16 KiB per workgroup of the per-node kernel
     bool fp8_matrix = false;  // fp8 pools: both products on the fp8 matrix instruction (HKV_PLAN_FP8_MATRIX)
     int32_t *d_pages = nullptr, *d_node_req_idx = nullptr, *d_part_count = nullptr;
-    bool profiling = false, profiled_run = false, node_only = false;
+    bool profiling = false, profiled_run = false;
     hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};  // begin/end of the node kernel, begin/end of the merge
     // several query tokens per request: n_req above counts query rows (requests x tokens_per_req)
     int32_t tokens_per_req = 1;
@@ -1189,12 +1189,11 @@ static int run_decode_plan(hkv_decode_plan *plan, const void *q, float scale, vo
     const bool prof = plan->profiling;
     if (!plan->items.empty()) {
         DecodeLaunch a{view_of(plan->pool), q, plan->d_items, plan->d_pages, plan->d_node_req_idx, o_parts, lse_parts,
-                       (int32_t)plan->items.size(), plan->num_q_heads, plan->max_parts, scale, nullptr,
+                       (int32_t)plan->items.size(), plan->num_q_heads, plan->max_parts, scale,
                        plan->d_row_leaf, plan->d_row_limit, plan->d_row_mask, plan->n_single, plan->n_stages,
                        plan->fp8_matrix ? 1 : 0};
         HKV_HIP(launch_decode(a, s, prof ? plan->ev[0] : nullptr, prof ? plan->ev[1] : nullptr));
     }
-    if (plan->node_only) return HKV_OK;
     HKV_HIP(launch_lse_merge_dense(o_parts, lse_parts, plan->d_part_count, plan->num_q_heads, plan->max_parts,
                                    plan->n_req * plan->num_q_heads, out, HKV_BF16, lse_out, s,
                                    prof ? plan->ev[2] : nullptr, prof ? plan->ev[3] : nullptr));
@@ -1243,11 +1242,10 @@ extern "C" int attn_decode_plan_run_static(hkv_decode_plan *plan, const void *q,
 
 extern "C" int hkv_decode_plan_set_profiling(hkv_decode_plan *plan, int32_t mode) {
     if (!plan) return fail(HKV_EINVAL, "hkv_decode_plan_set_profiling: null plan");
-    if (mode < 0 || mode > 2) return fail(HKV_EINVAL, "hkv_decode_plan_set_profiling: mode %d", mode);
+    if (mode < 0 || mode > 1) return fail(HKV_EINVAL, "hkv_decode_plan_set_profiling: mode %d", mode);
     if (mode == 1 && !plan->ev[0])
         for (hipEvent_t &e : plan->ev) HKV_HIP(hipEventCreate(&e));
     plan->profiling = mode == 1;
-    plan->node_only = mode == 2;
     return HKV_OK;
 }
 
@@ -1528,33 +1526,4 @@ extern "C" size_t attn_prefill_workspace_bytes(int32_t total_q, int32_t num_q_he
     (void)total_q;
     (void)num_q_heads;
     return 0;
-}
-
-// ---------------------------------------------------------------------------------------------
-// diagnostics
-extern "C" int hkv_mfma_probe(int32_t iters, int32_t random_operands, int32_t waves_per_simd, float *tflops,
-                              float *clock_ghz, void *stream) {
-    if (!tflops || !clock_ghz) return fail(HKV_EINVAL, "hkv_mfma_probe: null output pointer");
-    if (iters < 1 || (waves_per_simd != 1 && waves_per_simd != 2))
-        return fail(HKV_EINVAL, "hkv_mfma_probe: iters %d, waves_per_simd %d", iters, waves_per_simd);
-    int dev = 0, n_cu = 0;
-    HKV_HIP(hipGetDevice(&dev));
-    HKV_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
-    HKV_HIP(run_mfma_probe(n_cu, 4 * waves_per_simd, iters, random_operands != 0, tflops, clock_ghz,
-                           static_cast<hipStream_t>(stream)));
-    return HKV_OK;
-}
-
-extern "C" int hkv_hbm_read_probe(const void *const *bufs, int32_t n_buf, size_t bytes, int32_t reps, float *gbps,
-                                  void *stream) {
-    if (!bufs || !gbps || n_buf < 1 || reps < 1 || bytes < 16 || bytes % 16)
-        return fail(HKV_EINVAL, "hkv_hbm_read_probe: bad argument (n_buf %d, reps %d, bytes %zu)", n_buf, reps, bytes);
-    for (int i = 0; i < n_buf; ++i)
-        if (!bufs[i] || (reinterpret_cast<uintptr_t>(bufs[i]) & 15))
-            return fail(HKV_EINVAL, "hkv_hbm_read_probe: buffer %d is null or not 16-byte aligned", i);
-    int dev = 0, n_cu = 0;
-    HKV_HIP(hipGetDevice(&dev));
-    HKV_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
-    HKV_HIP(run_read_probe(bufs, n_buf, bytes, reps, n_cu, gbps, static_cast<hipStream_t>(stream)));
-    return HKV_OK;
 }

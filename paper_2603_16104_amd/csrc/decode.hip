@@ -25,19 +25,6 @@
 
 #include "hkv_device.h"
 
-// Development aid: with -DHKV_TRACE every wavefront records wall-clock stamps at a few points.
-#ifdef HKV_TRACE
-#define HKV_STAMP(slot)                                                                              \
-    do {                                                                                             \
-        if (a.trace && (threadIdx.x & 63) == 0)                                                      \
-            a.trace[((size_t)blockIdx.x * kWaves + (threadIdx.x >> 6)) * 8 + (slot)] = wall_clock64(); \
-    } while (0)
-#else
-#define HKV_STAMP(slot) \
-    do {                \
-    } while (0)
-#endif
-
 namespace hkv {
 
 namespace {
@@ -166,7 +153,6 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
     constexpr int NS = TB / 4;  // scores per lane (16 query rows x TB tokens over 64 lanes)
     constexpr int BB = Traits<DT>::kBlockBytes;
 
-    HKV_STAMP(0);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // Workgroups [0, n_single) run one item each.  The workgroups behind them run four short items
@@ -280,20 +266,20 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
         if constexpr (DT == 0) {
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
-                kf[ks] = ld16(p + ks * 1024);
-                kf[4 + ks] = ld16(p + ks * 1024 + 256);
+                kf[ks] = ld16_stream(p + ks * 1024);
+                kf[4 + ks] = ld16_stream(p + ks * 1024 + 256);
             }
         } else {
 #pragma unroll
             for (int t4 = 0; t4 < 4; ++t4)
 #pragma unroll
-                for (int ks2 = 0; ks2 < 2; ++ks2) kf[t4 * 2 + ks2] = ld16(p + ks2 * 1024 + t4 * 256);
+                for (int ks2 = 0; ks2 < 2; ++ks2) kf[t4 * 2 + ks2] = ld16_stream(p + ks2 * 1024 + t4 * 256);
         }
     };
     auto issue_v = [&](const StepPages<DT> &sp) {
         const char *p = vb + (uint64_t)(uint32_t)pick(sp.id, v_sel) * page_stride;
 #pragma unroll
-        for (int dt = 0; dt < 8; ++dt) vf[dt] = ld16(p + dt * ((DT == 0) ? 512 : 256));
+        for (int dt = 0; dt < 8; ++dt) vf[dt] = ld16_stream(p + dt * ((DT == 0) ? 512 : 256));
     };
 
     // One step over TB tokens.  LAST: the item's last step, the only one that may reach past the item's
@@ -548,7 +534,6 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
         load_limit(req);
         for (int i = 0; i < n_ahead && i < n_blk; ++i) issue_stage(i);
         split_q();
-        HKV_STAMP(1);
         // one step of the item; the last one is peeled off the loop: it alone waits for every load and
         // carries the end-of-item masking
         auto staged_step = [&](auto last_tag, int b) {
@@ -584,14 +569,9 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
                 step(std::false_type{}, last_tag, b, cur, cur);
             }
         };
-        for (int b = 0; b + 1 < n_blk; ++b) {
-            staged_step(std::false_type{}, b);
-            if (b == 0) HKV_STAMP(2);
-        }
+        for (int b = 0; b + 1 < n_blk; ++b) staged_step(std::false_type{}, b);
         staged_step(std::true_type{}, n_blk - 1);
-        HKV_STAMP(4);
         if (active) write_rows(req);
-        HKV_STAMP(6);
         return;
     }
 
@@ -607,25 +587,16 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
         load_limit(req);
         load_step_pages<DT>(nxt, a, it, b + n_ts, last_page);  // clamped: always in bounds
         split_q();
-        HKV_STAMP(1);
-        bool first = true;
         while (b + n_ts < n_blk) {
             step(std::true_type{}, std::false_type{}, b, cur, nxt);
-            if (first) {
-                HKV_STAMP(2);
-                first = false;
-            }
             b += n_ts;
             cur = nxt;
             load_step_pages<DT>(nxt, a, it, b + n_ts, last_page);
         }
-        HKV_STAMP(3);
         step(std::false_type{}, std::true_type{}, b, cur, nxt);
-        HKV_STAMP(4);
     }
     if (packed) {  // this wavefront did the whole item (it holds at least one token, so req is loaded)
         write_rows(req);
-        HKV_STAMP(6);
         return;
     }
 
@@ -645,7 +616,6 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
         if (wave == 0 && row < rows) sPart[m] = (req * a.num_q_heads + it.kv_head * G + row % G) * a.max_parts + it.part_slot;
     }
     __syncthreads();
-    HKV_STAMP(5);
     for (int idx = tid; idx < rows * kHeadDim; idx += kThreads) {
         const int row = idx >> 7, d = idx & 127;
         const int r_t = row >> 4, r_c = row & 15;
@@ -667,12 +637,6 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
         a.o_parts[part * kHeadDim + d] = L > 0.f ? acc / L : 0.f;
         if (d == 0) a.lse_parts[part] = L > 0.f ? (M * c + fast_log2(L)) * kLn2 : -INFINITY;
     }
-    HKV_STAMP(6);
-#ifdef HKV_TRACE
-    if (a.trace && (threadIdx.x & 63) == 0)
-        a.trace[((size_t)blockIdx.x * kWaves + (threadIdx.x >> 6)) * 8 + 7] =
-            ((unsigned long long)__builtin_amdgcn_s_getreg((31 << 11) | 20) << 32) | __builtin_amdgcn_s_getreg((31 << 11) | 4);
-#endif
 }
 
 }  // namespace

@@ -20,6 +20,11 @@ constexpr float kLn2 = 0.6931471805599453f;
 
 // 16-byte global load of matrix-core operand data (8 bf16 or 16 fp8).
 __device__ __forceinline__ u32x4 ld16(const void *p) { return *reinterpret_cast<const u32x4 *>(p); }
+// The same with the streaming hint: for bytes that are read once per launch (K/V of a node that few query
+// rows share), so that they do not displace what other workgroups will read again.
+__device__ __forceinline__ u32x4 ld16_stream(const void *p) {
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+}
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 

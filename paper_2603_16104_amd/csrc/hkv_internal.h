@@ -59,7 +59,6 @@ struct DecodeLaunch {
     int32_t num_q_heads;
     int32_t max_parts;
     float scale;
-    unsigned long long *trace;   // development builds only (HKV_TRACE): 8 timestamps per wavefront, else null
     // Several query tokens per request (null otherwise): row r of q is query token r % T of request
     // r / T; inside the node row_leaf[r] it sees the first row_limit[r] tokens (everything before the
     // request's T newest tokens) and, of the tokens behind them, number j iff bit j of row_mask[r] is
@@ -197,10 +196,5 @@ hipError_t launch_lse_merge_dense(const float *o_parts, const float *lse_parts, 
                                   int32_t rows_per_count, int32_t max_parts, int32_t n_rows, void *out,
                                   int32_t out_dtype, float *lse_out, hipStream_t s, hipEvent_t ev_begin = nullptr,
                                   hipEvent_t ev_end = nullptr);
-
-hipError_t run_read_probe(const void *const *bufs, int n_buf, size_t bytes, int reps, int n_cu, float *gbps,
-                          hipStream_t s);
-hipError_t run_mfma_probe(int n_cu, int waves, int iters, int random_operands, float *tflops, float *clock_ghz,
-                          hipStream_t s);
 
 }  // namespace hkv

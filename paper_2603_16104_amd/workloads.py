@@ -235,15 +235,16 @@ def config2(seed: int = BASE_SEED + 2, n_req: int = 64, root_tokens: int = 2048,
                     num_pages=num_pages, seed=seed, forest=f, mode="decode")
 
 
-def config3(seed: int = BASE_SEED + 3) -> Workload:
+def config3(seed: int = BASE_SEED + 3, root_tokens: int = 4096, child_tokens: int = 1024,
+            leaf_tokens: int = 256) -> Workload:
     """Speculative fan-out tree: 4096 -> 8 x 1024 -> 128 x 256."""
     parent = [-1] + [0] * 8
-    ntok = [4096] + [1024] * 8
+    ntok = [root_tokens] + [child_tokens] * 8
     leaves = []
     for c in range(8):
         for _ in range(16):
             parent.append(1 + c)
-            ntok.append(256)
+            ntok.append(leaf_tokens)
             leaves.append(len(parent) - 1)
     n_used = sum((t + 15) // 16 for t in ntok)
     num_pages = _pool_pages(n_used)

@@ -688,21 +688,23 @@ def test_decode_closed_forms_on_the_gpu(gpu, oracle, kv_dtype, case):
 
 
 @pytest.mark.gpu
-def test_diagnostic_probes(gpu):
-    """The ceiling probes run and report figures of the right order (no attention result involved)."""
+def test_bench_probes(gpu):
+    """The ceiling probes of the bench (bench_probes.hip, no part of the library) run and report figures of
+    the right order; no attention result is involved."""
     import torch
-    from paper_2603_16104_amd import binding as hkv
-    tf0, ghz0 = hkv.hkv_mfma_probe(20000, False, 2)
-    tf1, ghz1 = hkv.hkv_mfma_probe(20000, True, 2)
+    import bench_probes as bp
+    tf0, ghz0 = bp.mfma_bf16(20000, False, 2)
+    tf1, ghz1 = bp.mfma_bf16(20000, True, 2)
     assert 500.0 < tf1 <= tf0 * 1.05 < 2700.0          # never above the 2.5 PFLOP/s data-sheet peak (+ timer slack)
     assert 0.5 < ghz1 <= ghz0 * 1.05 < 2.6
     bufs = [torch.zeros(1 << 24, dtype=torch.int32, device="cuda") for _ in range(4)]   # 4 x 64 MiB
-    gbps = hkv.hkv_hbm_read_probe(bufs, 1 << 26, 40)
-    assert 1000.0 < gbps < 8000.0 * 1.6                # cache hits may lift it above the HBM peak
-    with pytest.raises(hkv.HkvError):
-        hkv.hkv_mfma_probe(0, False, 2)
-    with pytest.raises(hkv.HkvError):
-        hkv.hkv_hbm_read_probe(bufs, 24, 1)
+    for kw in ({}, {"wgs_per_cu": 4, "threads": 512, "in_flight": 8, "contiguous": True, "nontemporal": True}):
+        gbps = bp.hbm_read(bufs, 1 << 26, 40, **kw)
+        assert 1000.0 < gbps < 8000.0 * 1.6            # cache hits may lift it above the HBM peak
+    with pytest.raises(RuntimeError):
+        bp.mfma_bf16(0, False, 2)
+    with pytest.raises(RuntimeError):
+        bp.hbm_read(bufs, 24, 1)
 
 
 @pytest.mark.gpu
