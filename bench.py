@@ -106,7 +106,7 @@ def bench_decode(runtime, hkv, w, steps: int, warmup: int, n_pools: int, profile
            "ms_per_step_p10_p50_p90": [round(pct(per, q) * 1e3, 5) for q in (0.1, 0.5, 0.9)]}
     # same steps again with a begin and an end HIP event attached to each kernel dispatch (on the launch
     # stream): the kernels' own durations, as a kernel trace reports them
-    node_each, merge_each = [], []
+    node_each, merge_each, rows_each, tile_each = [], [], [], []
     for r in runners:
         hkv.hkv_decode_plan_set_profiling(r.plan, True)
     for i in range(profile_steps):
@@ -115,10 +115,15 @@ def bench_decode(runtime, hkv, w, steps: int, warmup: int, n_pools: int, profile
         a, b = hkv.hkv_decode_plan_elapsed_ms(r.plan)
         node_each.append(a)
         merge_each.append(b)
+        a, b = hkv.hkv_decode_plan_elapsed_kernels_ms(r.plan)
+        rows_each.append(a)
+        tile_each.append(b)
     for r in runners:
         hkv.hkv_decode_plan_set_profiling(r.plan, 0)
     res["node_ms"] = sum(node_each) / max(1, len(node_each))
     res["merge_ms"] = sum(merge_each) / max(1, len(merge_each))
+    res["rows_kernel_ms"] = sum(rows_each) / max(1, len(rows_each))
+    res["tile_kernel_ms"] = sum(tile_each) / max(1, len(tile_each))
     if node_each:
         srt = sorted(node_each)
         res["node_kernel_ms_p10_p50_p90"] = [round(pct(srt, q), 5) for q in (0.1, 0.5, 0.9)]
@@ -151,6 +156,8 @@ def bench_decode(runtime, hkv, w, steps: int, warmup: int, n_pools: int, profile
         res["cache_resident_ms_per_step"] = round(time_steps(lambda i: runners[0].run(), steps, warmup) * 1e3, 5)
     res["info"] = {
         "items": int(len(hkv.hkv_decode_plan_items(runners[0].plan))),
+        "tile_items": int(hkv.hkv_decode_plan_num_tile_items(runners[0].plan)),
+        "tile_workgroups": int(hkv.hkv_decode_plan_tile_workgroups(runners[0].plan)),
         "workgroups": int(hkv.hkv_decode_plan_num_workgroups(runners[0].plan)),
         "partials": int(hkv.hkv_decode_plan_num_parts(runners[0].plan)),
         "max_partials_per_row": int(hkv.hkv_decode_plan_max_parts(runners[0].plan)),
@@ -180,6 +187,8 @@ def decode_entry(w, res):
         "node_kernel_ms": round(res["node_ms"], 5),
         "node_kernel_hbm_frac": round(uniq / (res["node_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) if res["node_ms"] else None,
         "merge_kernel_ms": round(res["merge_ms"], 5),
+        "rows_kernel_ms": round(res["rows_kernel_ms"], 5),
+        "tile_kernel_ms": round(res["tile_kernel_ms"], 5),
         **res["info"],
     }
     for k in ("node_kernel_ms_p10_p50_p90", "graph_replay_ms_per_step", "cache_resident_ms_per_step"):
@@ -561,6 +570,8 @@ def main() -> int:
     ap.add_argument("--no-extras", action="store_true", help="skip the other workloads (c2, c3, c4, pool write, probes)")
     ap.add_argument("--fp8-matrix", action="store_true",
                     help="run the fp8 forest on the fp8 matrix instruction (HKV_PLAN_FP8_MATRIX) instead of the default path")
+    ap.add_argument("--one-stream", action="store_true",
+                    help="decode plans queue the tile kernel in front of the other on one stream (HKV_PLAN_ONE_STREAM)")
     ap.add_argument("--hot", action="store_true", help="also time the small decode workloads without pool rotation (cache-resident)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--decode-loop", action="store_true",
@@ -626,7 +637,8 @@ def main() -> int:
               flush=True)
         return 0
 
-    fp8_flags = hkv.PLAN_FP8_MATRIX if args.fp8_matrix else 0
+    one = hkv.PLAN_ONE_STREAM if args.one_stream else 0
+    fp8_flags = (hkv.PLAN_FP8_MATRIX if args.fp8_matrix else 0) | one
     if args.profile_workload:
         name = args.profile_workload
         if name == "c4":
@@ -645,7 +657,7 @@ def main() -> int:
                   "c3_shared": lambda: wl.config3(leaf_tokens=16)}[name]()
             small = wx.unique_kv_bytes() < (1 << 29)
             rx = bench_decode(runtime, hkv, wx, max(1, min(args.steps, 100 if small else 40)), 10,
-                              args.pools if small else 1, 10, fp8_flags if wx.kv_dtype == wl.KV_FP8_E4M3 else 0,
+                              args.pools if small else 1, 10, fp8_flags if wx.kv_dtype == wl.KV_FP8_E4M3 else one,
                               batch=8 if small else 1)
             print(json.dumps({"workload": wx.name, **decode_entry(wx, rx)}), flush=True)
         return 0
@@ -718,7 +730,7 @@ def main() -> int:
         for key, make, tfile in (("c2_llama8b_decode", wl.config2, "decode_c2_traffic.json"),
                                  ("c3_fanout_decode", wl.config3, "decode_c3_traffic.json")):
             wx = make()
-            rx = bench_decode(runtime, hkv, wx, small_steps, 50, args.pools, 100, batch=8, graph=True, hot=args.hot)
+            rx = bench_decode(runtime, hkv, wx, small_steps, 50, args.pools, 100, one, batch=8, graph=True, hot=args.hot)
             result["extra"][key] = {"pools_rotated": args.pools, **decode_entry(wx, rx)}
             t = load_traffic(tfile)
             if t is not None:

@@ -268,7 +268,13 @@ enum {
      * step's largest weight-times-scale loses relative precision (e4m3 has no more range), which
      * shows only if the V scales of the four 16-token blocks of one step differ by more than about
      * 2^7 while the attention weight sits on the blocks with the small scales. */
-    HKV_PLAN_FP8_MATRIX = 2
+    HKV_PLAN_FP8_MATRIX = 2,
+    /* Decode plans: attn_decode_plan_run normally queues the kernel for nodes shared by many query rows on a
+     * stream of the plan's own, beside the kernel that streams the other nodes on the caller's stream (one
+     * event forks to it, one joins it before the merge; both are ordered after everything queued earlier on
+     * the caller's stream, and the call is safe under stream capture).  With this flag everything is queued
+     * on the caller's stream, one kernel after the other. */
+    HKV_PLAN_ONE_STREAM = 4
 };
 
 /* nodes, node_pages, req_leaf: host.  Validates the forest (ETREE/ERANGE, page ids against the
@@ -340,6 +346,11 @@ size_t hkv_decode_plan_workspace_bytes(const hkv_decode_plan *plan);
  * `node` to n_req requests x (num_q_heads / num_kv_heads) heads of kv_head; row (request r, head
  * h) of the item writes partial (r*num_q_heads + h)*max_parts + part_slot. */
 int32_t hkv_decode_plan_num_items(const hkv_decode_plan *plan);
+/* Of these, the last hkv_decode_plan_num_tile_items are items of nodes shared by 128 query rows or more (up
+ * to 256 / G requests each, at most 2048 tokens): they are run by a second kernel, built like the prefill
+ * kernel (256-row tiles), on hkv_decode_plan_tile_workgroups persistent workgroups. */
+int32_t hkv_decode_plan_num_tile_items(const hkv_decode_plan *plan);
+int32_t hkv_decode_plan_tile_workgroups(const hkv_decode_plan *plan);
 /* Workgroups of the per-node kernel: one per item, except that in forests with more items than the
  * chip holds at once the short items of at most 16 query rows (listed last) share a workgroup four
  * at a time, one item per wavefront. */
@@ -383,6 +394,10 @@ int attn_decode_plan_run_static(hkv_decode_plan *plan, const void *q, float scal
  * EINVAL if no profiled run has been queued. */
 int hkv_decode_plan_set_profiling(hkv_decode_plan *plan, int32_t mode);
 int hkv_decode_plan_elapsed_ms(hkv_decode_plan *plan, float *node_ms /* host */, float *merge_ms /* host */);
+/* The same run's per-node phase by kernel: the kernel over the items of few rows and the tile kernel (0 for
+ * one that did not run); node_ms above spans both, from the earlier begin to the later end. */
+int hkv_decode_plan_elapsed_kernels_ms(hkv_decode_plan *plan, float *rows_kernel_ms /* host */,
+                                       float *tile_kernel_ms /* host */);
 
 /* One-shot form: plans (or reuses the plan cached in the pool when the forest is unchanged) and
  * runs.  Same arguments as the two calls above. */

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libheliumkv.so")
 
 OK, EINVAL, ERANGE, ESHAPE, ETREE, ENOMEM, EHIP = 0, -1, -2, -3, -4, -5, -6
 BF16, FP8_E4M3, FP32 = 0, 1, 2
-PLAN_HOST_ONLY, PLAN_FP8_MATRIX = 1, 2
+PLAN_HOST_ONLY, PLAN_FP8_MATRIX, PLAN_ONE_STREAM = 1, 2, 4
 PAGE_SIZE, HEAD_DIM = 16, 128
 
 EXPORTS = [
@@ -31,7 +31,8 @@ EXPORTS = [
     "hkv_decode_plan_num_items", "hkv_decode_plan_num_workgroups", "hkv_decode_plan_num_parts", "hkv_decode_plan_items",
     "hkv_decode_plan_max_parts", "hkv_decode_plan_part_counts", "lse_merge_dense", "attn_decode_plan_run",
     "attn_decode_plan_run_static", "hkv_static_workspace_bytes",
-    "hkv_decode_plan_set_profiling", "hkv_decode_plan_elapsed_ms",
+    "hkv_decode_plan_set_profiling", "hkv_decode_plan_elapsed_ms", "hkv_decode_plan_elapsed_kernels_ms",
+    "hkv_decode_plan_num_tile_items", "hkv_decode_plan_tile_workgroups",
     "attn_decode_prefix_tree", "attn_decode_workspace_bytes", "hkv_prefill_plan_create", "hkv_prefill_plan_destroy",
     "hkv_prefill_plan_num_tiles", "hkv_prefill_plan_tiles", "attn_prefill_plan_run", "attn_prefill_plan_run_ws", "hkv_prefill_plan_workspace_bytes", "attn_prefill_with_prefix",
     "attn_prefill_workspace_bytes",
@@ -338,6 +339,21 @@ def hkv_decode_plan_elapsed_ms(plan):
     a, b = C.c_float(), C.c_float()
     _check(lib().hkv_decode_plan_elapsed_ms(plan, C.byref(a), C.byref(b)))
     return float(a.value), float(b.value)
+
+
+def hkv_decode_plan_elapsed_kernels_ms(plan):
+    """(kernel over the few-row items, tile kernel) of the most recent profiled run, milliseconds."""
+    a, b = C.c_float(), C.c_float()
+    _check(lib().hkv_decode_plan_elapsed_kernels_ms(plan, C.byref(a), C.byref(b)))
+    return float(a.value), float(b.value)
+
+
+def hkv_decode_plan_num_tile_items(plan) -> int:
+    return _check(lib().hkv_decode_plan_num_tile_items(plan))
+
+
+def hkv_decode_plan_tile_workgroups(plan) -> int:
+    return _check(lib().hkv_decode_plan_tile_workgroups(plan))
 
 
 def attn_decode_prefix_tree(pool, q, nodes, node_pages, req_leaf, num_q_heads: int, scale: float, out, lse_out,

@@ -71,10 +71,19 @@ struct hkv_decode_plan {
     std::vector<hkv_node> nodes;            // the same forest in 16-token blocks (page_begin, n_pages into node_pages)
     std::vector<int32_t> node_pages;
     std::vector<DecodeItem> items;
+    // Items shared by kMinTileItemRows query rows or more (up to 256 / G requests each): run by the 256-row
+    // tile kernel on tile_workgroups persistent workgroups, on a stream of the plan's own next to the kernel
+    // that runs `items` (or in front of it on the caller's stream when concurrent is false).
+    std::vector<DecodeItem> tile_items;
+    int32_t tile_workgroups = 0;
+    bool no_tiles = false, concurrent = true;
+    hipStream_t side = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    hipEvent_t ev_tile[2] = {nullptr, nullptr};  // profiling: begin/end of the tile kernel
     std::vector<int32_t> node_req_indptr, node_req_idx, part_count;
-    // one device allocation holding items | pages | node_req_idx | part_count
+    // one device allocation holding items | pages | node_req_idx | part_count | tile_items
     void *dev = nullptr;
-    DecodeItem *d_items = nullptr;
+    DecodeItem *d_items = nullptr, *d_tile_items = nullptr;
     int32_t n_single = 0;  // items [0, n_single) run one per workgroup, the rest four per workgroup
     int32_t n_stages = 3;  // LDS stages of 16 KiB per workgroup of the per-node kernel
     bool fp8_matrix = false;  // fp8 pools: both products on the fp8 matrix instruction (HKV_PLAN_FP8_MATRIX)
@@ -589,10 +598,31 @@ static void plan_items(hkv_decode_plan &pl) {
     // below 256 tokens.  Nodes shared by more rows run one row tile per wavefront over all tokens
     // of the item, so their chunks are kept near the typical leaf-type item to finish together.
     const int kResidentGroups = 768;  // 256 CUs x 3 workgroups
+    // Nodes shared by many rows go to the 256-row tile kernel (not with per-row visibility, which that kernel
+    // does not know, and not when the caller asked for the fp8 matrix instruction).
+    const int tile_min_rows = env_int("HKV_DECODE_TILE_ROWS", 128);
+    // The second kernel, its stream and the two events pay only when that share of the step is large (measured:
+    // c2 and c3, 2 and 9 GFLOP of such work in steps of 30 to 50 us, lose; c5, 137 GFLOP in 0.5 ms, gains 11 %).
+    bool tiles_pay = false;
+    {
+        double flop = 0;
+        for (int v = 0; v < n_nodes; ++v) {
+            const int R = pl.node_req_indptr[v + 1] - pl.node_req_indptr[v];
+            if (R * G >= std::max(tile_min_rows, kMinTileItemRows))
+                flop += 4.0 * HKV_HEAD_DIM * pl.nodes[v].n_tokens * (double)R * pl.num_q_heads;
+        }
+        const char *e = getenv("HKV_DECODE_TILE_GFLOP");  // development knob
+        tiles_pay = flop >= 1e9 * (e && *e ? atof(e) : 40.0);
+    }
+    auto tiled = [&](int v) {
+        const int R = pl.node_req_indptr[v + 1] - pl.node_req_indptr[v];
+        return tiles_pay && !pl.no_tiles && !pl.fp8_matrix && pl.nodes[v].n_tokens > 0 &&
+               R * G >= std::max(tile_min_rows, kMinTileItemRows);
+    };
     int64_t leaf_units = 0, leaf_tokens = 0, shared_units = 0;
     for (int v = 0; v < n_nodes; ++v) {
         int R = pl.node_req_indptr[v + 1] - pl.node_req_indptr[v];
-        if (pl.nodes[v].n_tokens == 0 || R == 0) continue;
+        if (pl.nodes[v].n_tokens == 0 || R == 0 || tiled(v)) continue;
         if (R * G > 16) {  // counted at the smallest chunk length used for such nodes
             shared_units += (int64_t)((R + max_req_per_item - 1) / max_req_per_item) * Hkv *
                             ((pl.nodes[v].n_tokens + 511) / 512);
@@ -618,7 +648,7 @@ static void plan_items(hkv_decode_plan &pl) {
         for (int v = 0; v < n_nodes; ++v) {
             const int R = pl.node_req_indptr[v + 1] - pl.node_req_indptr[v];
             const int64_t up = pl.nodes[v].parent >= 0 ? shared_above[pl.nodes[v].parent] : 0;
-            shared_above[v] = up + (R * G > 16 ? pl.nodes[v].n_tokens : 0);
+            shared_above[v] = up + (R * G > 16 && !tiled(v) ? pl.nodes[v].n_tokens : 0);
             longest = std::max(longest, shared_above[v]);
         }
         int64_t by_path = std::min<int64_t>(1024, (longest / 6 + 128) / 256 * 256);
@@ -650,6 +680,45 @@ static void plan_items(hkv_decode_plan &pl) {
         }
         cut_leaves = any && (pack_mode == 3 || units > kResidentGroups);
     }
+    // The tile kernel's share of the chip: its persistent workgroups hold one compute unit each for as long as
+    // the other kernel streams its bytes, so their number follows from the two amounts of work (matrix
+    // arithmetic at about 3.5 TFLOP/s per compute unit against bytes at about 5.5 TB/s for the chip).
+    const int req_per_tile = std::max(1, 256 / G);
+    pl.tile_items.clear();
+    pl.tile_workgroups = 0;
+    int tile_chunk = kMaxTileItemTokens;
+    {
+        double tile_flop = 0, other_bytes = 0;
+        int64_t tile_units = 0, tile_tokens_max = 0;
+        const double bytes_per_token = 2.0 * HKV_HEAD_DIM * (pl.pool->d.dtype == HKV_FP8_E4M3 ? 1 : 2);
+        for (int v = 0; v < n_nodes; ++v) {
+            const int R = pl.node_req_indptr[v + 1] - pl.node_req_indptr[v];
+            if (pl.nodes[v].n_tokens == 0 || R == 0) continue;
+            if (tiled(v)) {
+                tile_flop += 4.0 * HKV_HEAD_DIM * pl.nodes[v].n_tokens * (double)R * pl.num_q_heads;
+                tile_units += (int64_t)((R + req_per_tile - 1) / req_per_tile) * Hkv;
+                tile_tokens_max = std::max<int64_t>(tile_tokens_max, pl.nodes[v].n_tokens);
+            } else {
+                other_bytes += bytes_per_token * pl.nodes[v].n_tokens * Hkv;
+            }
+        }
+        if (tile_units > 0) {
+            const int n_cu = 256;
+            int wgs = n_cu;
+            if (other_bytes > 0) {
+                const double t_other = other_bytes / 5.5e12;
+                wgs = (int)(tile_flop / (3.5e12 * t_other) + 0.999);
+                wgs = std::min(n_cu - 64, std::max(8, (wgs + 7) / 8 * 8));  // whole groups of 8: one per XCD
+            }
+            wgs = env_int("HKV_DECODE_TILE_WGS", wgs);
+            pl.tile_workgroups = wgs;
+            // chunks: at least two rounds of items per workgroup where the nodes are long enough, few partials otherwise
+            const int64_t per_unit = std::max<int64_t>(1, (2 * (int64_t)wgs + tile_units - 1) / tile_units);
+            int64_t ch = (tile_tokens_max / per_unit + 63) / 64 * 64;
+            tile_chunk = (int)std::min<int64_t>(kMaxTileItemTokens, std::max<int64_t>(256, ch));
+            tile_chunk = std::min(kMaxTileItemTokens, env_int("HKV_DECODE_TILE_CHUNK", tile_chunk)) / 16 * 16;
+        }
+    }
     struct Proto { DecodeItem it; int64_t cost; };
     std::vector<Proto> protos;
     std::vector<int32_t> node_chunks(n_nodes, 0), slot_base(n_nodes, 0);
@@ -658,6 +727,22 @@ static void plan_items(hkv_decode_plan &pl) {
         if (nd.parent >= 0) slot_base[v] = slot_base[nd.parent] + node_chunks[nd.parent];
         int R = pl.node_req_indptr[v + 1] - pl.node_req_indptr[v];
         if (nd.n_tokens == 0 || R == 0) continue;
+        if (tiled(v)) {  // equal chunks of whole pages x equal request groups x KV heads, longest chunks first below
+            const int n_chunks = (nd.n_tokens + tile_chunk - 1) / tile_chunk;
+            const int pages_per_chunk = (nd.n_pages + n_chunks - 1) / n_chunks;
+            node_chunks[v] = (nd.n_pages + pages_per_chunk - 1) / pages_per_chunk;
+            const int n_groups = (R + req_per_tile - 1) / req_per_tile;
+            const int req_per_group = (R + n_groups - 1) / n_groups;
+            for (int pg = 0, ci = 0; pg < nd.n_pages; pg += pages_per_chunk, ++ci) {
+                const int tb = pg * 16;
+                const int nt = std::min(pages_per_chunk * 16, nd.n_tokens - tb);
+                for (int r0 = 0; r0 < R; r0 += req_per_group)
+                    for (int h = 0; h < Hkv; ++h)
+                        pl.tile_items.push_back(DecodeItem{nd.page_begin + pg, nt, h, pl.node_req_indptr[v] + r0,
+                                                           std::min(req_per_group, R - r0), slot_base[v] + ci, tb, v});
+            }
+            continue;
+        }
         int chunk = std::max(16, R * G > 16 ? shared_chunk : leaf_chunk);
         if (R * G <= 16 && cut_leaves && cut_for_packing(nd.n_tokens)) chunk = pack_tokens;  // equal pieces below
         // equal chunks of whole pages
@@ -706,6 +791,9 @@ static void plan_items(hkv_decode_plan &pl) {
             protos.swap(merged);
         }
     }
+    std::stable_sort(pl.tile_items.begin(), pl.tile_items.end(),
+                     [](const DecodeItem &x, const DecodeItem &y) { return x.n_tokens > y.n_tokens; });
+    pl.tile_workgroups = std::min<int32_t>(pl.tile_workgroups, (int32_t)pl.tile_items.size());
     pl.items.clear();
     pl.n_single = 0;
     for (auto &p : protos) {
@@ -730,13 +818,15 @@ static int upload_decode_plan(hkv_decode_plan &pl) {
     size_t off_pages = align_up(off_items + sizeof(DecodeItem) * pl.items.size(), 256);
     size_t off_nri = align_up(off_pages + sizeof(int32_t) * pl.node_pages.size(), 256);
     size_t off_cnt = align_up(off_nri + sizeof(int32_t) * pl.node_req_idx.size(), 256);
-    size_t total = align_up(off_cnt + sizeof(int32_t) * pl.part_count.size(), 256) + 256;
+    size_t off_tiles = align_up(off_cnt + sizeof(int32_t) * pl.part_count.size(), 256);
+    size_t total = align_up(off_tiles + sizeof(DecodeItem) * pl.tile_items.size(), 256) + 256;
     HKV_HIP(hipMalloc(&pl.dev, total));
     char *base = static_cast<char *>(pl.dev);
     pl.d_items = reinterpret_cast<DecodeItem *>(base + off_items);
     pl.d_pages = reinterpret_cast<int32_t *>(base + off_pages);
     pl.d_node_req_idx = reinterpret_cast<int32_t *>(base + off_nri);
     pl.d_part_count = reinterpret_cast<int32_t *>(base + off_cnt);
+    pl.d_tile_items = reinterpret_cast<DecodeItem *>(base + off_tiles);
     // one host image, one copy
     std::vector<char> image(total, 0);
     auto put = [&](size_t off, const void *src, size_t n) {
@@ -746,6 +836,7 @@ static int upload_decode_plan(hkv_decode_plan &pl) {
     put(off_pages, pl.node_pages.data(), sizeof(int32_t) * pl.node_pages.size());
     put(off_nri, pl.node_req_idx.data(), sizeof(int32_t) * pl.node_req_idx.size());
     put(off_cnt, pl.part_count.data(), sizeof(int32_t) * pl.part_count.size());
+    put(off_tiles, pl.tile_items.data(), sizeof(DecodeItem) * pl.tile_items.size());
     HKV_HIP(hipMemcpy(pl.dev, image.data(), total, hipMemcpyHostToDevice));
     // HKV_GROW_INLINE=0 (tests): take the path of larger batches, the work list re-sent from pinned memory
     if (pl.reserve_tokens > 0 && pl.n_req <= kMaxInlineAppend && !pl.grow_items.empty() && env_int("HKV_GROW_INLINE", 1) == 1) {
@@ -757,6 +848,11 @@ static int upload_decode_plan(hkv_decode_plan &pl) {
         HKV_HIP(hipHostGetDevicePointer((void **)&pl.d_grow, pl.h_grow, 0));
         memset(pl.h_grow, 0, pl.grow_bytes * hkv_decode_plan::kGrowSlots);
         for (hipEvent_t &e : pl.grow_free) HKV_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    }
+    if (!pl.tile_items.empty()) {  // the tile kernel's own stream and the two events that fork to it and join it
+        HKV_HIP(hipStreamCreateWithFlags(&pl.side, hipStreamNonBlocking));
+        HKV_HIP(hipEventCreateWithFlags(&pl.ev_fork, hipEventDisableTiming));
+        HKV_HIP(hipEventCreateWithFlags(&pl.ev_join, hipEventDisableTiming));
     }
     // here, so that the first run may already be under graph capture
     HKV_HIP(prepare_decode_device(nullptr));
@@ -795,6 +891,9 @@ static int build_fp32_rows(hkv_decode_plan &pl, bool upload) {
     return HKV_OK;
 }
 
+// internal flag: no item may go to the 256-row tile kernel (plans with per-row visibility)
+constexpr uint32_t kPlanNoTiles = 0x40000000u;
+
 static int create_decode_plan(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes, const int32_t *node_pages,
                               int32_t n_node_pages, const int32_t *req_leaf, int32_t n_req, int32_t num_q_heads,
                               uint32_t flags, int32_t reserve_tokens, hkv_decode_plan **out) {
@@ -824,6 +923,8 @@ static int create_decode_plan(hkv_pool *pool, const hkv_node *nodes, int32_t n_n
     pl->num_q_heads = num_q_heads;
     pl->group = num_q_heads / Hkv;
     pl->fp8_matrix = pool->d.dtype == HKV_FP8_E4M3 && ((flags & HKV_PLAN_FP8_MATRIX) || env_int("HKV_FP8_MATRIX", 0) == 1);
+    pl->no_tiles = (flags & kPlanNoTiles) != 0;
+    pl->concurrent = !(flags & HKV_PLAN_ONE_STREAM);
     if (int rc = build_node_req_csr(nodes, n_nodes, req_leaf, n_req, pl->node_req_indptr, pl->node_req_idx,
                                     "hkv_decode_plan_create")) {
         delete pl;
@@ -896,7 +997,8 @@ static int create_decode_plan(hkv_pool *pool, const hkv_node *nodes, int32_t n_n
 extern "C" int hkv_decode_plan_create(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes,
                                       const int32_t *node_pages, int32_t n_node_pages, const int32_t *req_leaf,
                                       int32_t n_req, int32_t num_q_heads, uint32_t flags, hkv_decode_plan **out) {
-    return create_decode_plan(pool, nodes, n_nodes, node_pages, n_node_pages, req_leaf, n_req, num_q_heads, flags, 0, out);
+    return create_decode_plan(pool, nodes, n_nodes, node_pages, n_node_pages, req_leaf, n_req, num_q_heads,
+                              flags & ~kPlanNoTiles, 0, out);
 }
 
 extern "C" int hkv_decode_plan_create_growing(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes,
@@ -1046,8 +1148,9 @@ static int create_rows_plan(hkv_pool *pool, const hkv_node *nodes, int32_t n_nod
     for (int r = 0; r < n_req; ++r)
         for (int t = 0; t < T; ++t) rows[(size_t)r * T + t] = req_leaf[r];
     hkv_decode_plan *pl = nullptr;
-    if (int rc = hkv_decode_plan_create(pool, nodes, n_nodes, node_pages, n_node_pages, rows.data(), n_req * T,
-                                        num_q_heads, flags, &pl))
+    const uint32_t rows_flags = (flags & ~kPlanNoTiles) | ((T > 1 || masks) ? kPlanNoTiles : 0u);
+    if (int rc = create_decode_plan(pool, nodes, n_nodes, node_pages, n_node_pages, rows.data(), n_req * T, num_q_heads,
+                                    rows_flags, 0, &pl))
         return rc;
     pl->tokens_per_req = T;
     if (T > 1 || masks) {
@@ -1133,6 +1236,9 @@ extern "C" int hkv_decode_plan_destroy(hkv_decode_plan *plan) {
     if (plan->d_bt) (void)hipFree(plan->d_bt);
     for (hipEvent_t e : plan->ev)
         if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : {plan->ev_fork, plan->ev_join, plan->ev_tile[0], plan->ev_tile[1]})
+        if (e) (void)hipEventDestroy(e);
+    if (plan->side) (void)hipStreamDestroy(plan->side);
     if (plan->h_grow) (void)hipHostFree(plan->h_grow);
     if (plan->d_grow_items) (void)hipFree(plan->d_grow_items);
     for (hipEvent_t e : plan->grow_free)
@@ -1148,7 +1254,13 @@ extern "C" size_t hkv_decode_plan_workspace_bytes(const hkv_decode_plan *plan) {
 }
 
 extern "C" int32_t hkv_decode_plan_num_items(const hkv_decode_plan *plan) {
-    return plan ? (int32_t)plan->items.size() : fail(HKV_EINVAL, "null plan");
+    return plan ? (int32_t)(plan->items.size() + plan->tile_items.size()) : fail(HKV_EINVAL, "null plan");
+}
+extern "C" int32_t hkv_decode_plan_num_tile_items(const hkv_decode_plan *plan) {
+    return plan ? (int32_t)plan->tile_items.size() : fail(HKV_EINVAL, "null plan");
+}
+extern "C" int32_t hkv_decode_plan_tile_workgroups(const hkv_decode_plan *plan) {
+    return plan ? plan->tile_workgroups : fail(HKV_EINVAL, "null plan");
 }
 extern "C" int32_t hkv_decode_plan_num_parts(const hkv_decode_plan *plan) {
     return plan ? plan->n_parts : fail(HKV_EINVAL, "null plan");
@@ -1157,11 +1269,13 @@ extern "C" int hkv_decode_plan_items(const hkv_decode_plan *plan, int32_t *items
     if (!plan || !items_out) return fail(HKV_EINVAL, "hkv_decode_plan_items: null argument");
     static_assert(sizeof(DecodeItem) == 32, "item layout is part of the introspection contract");
     if (!plan->items.empty()) memcpy(items_out, plan->items.data(), sizeof(DecodeItem) * plan->items.size());
+    if (!plan->tile_items.empty())
+        memcpy(items_out + 8 * plan->items.size(), plan->tile_items.data(), sizeof(DecodeItem) * plan->tile_items.size());
     return HKV_OK;
 }
 extern "C" int32_t hkv_decode_plan_num_workgroups(const hkv_decode_plan *plan) {
     if (!plan) return fail(HKV_EINVAL, "null plan");
-    return plan->n_single + ((int32_t)plan->items.size() - plan->n_single + 3) / 4;
+    return plan->n_single + ((int32_t)plan->items.size() - plan->n_single + 3) / 4;  // (the tile kernel's are counted apart)
 }
 extern "C" int32_t hkv_decode_plan_max_parts(const hkv_decode_plan *plan) {
     return plan ? plan->max_parts : fail(HKV_EINVAL, "null plan");
@@ -1187,17 +1301,37 @@ static int run_decode_plan(hkv_decode_plan *plan, const void *q, float scale, vo
     float *lse_parts = reinterpret_cast<float *>(static_cast<char *>(workspace) +
                                                  align_up((size_t)plan->n_parts * HKV_HEAD_DIM * sizeof(float), 256));
     const bool prof = plan->profiling;
+    const bool tiles = !plan->tile_items.empty();
+    const bool fork = tiles && plan->concurrent && !plan->items.empty();
+    // The tile kernel goes first and stays on the caller's stream, so that its persistent workgroups, which need
+    // a whole compute unit each, take theirs before the other kernel's many small workgroups fill the chip; that
+    // kernel follows on the plan's own stream (behind an event that marks the same point of the caller's stream)
+    // and is joined again before the merge.
+    if (fork) {
+        HKV_HIP(hipEventRecord(plan->ev_fork, s));
+        HKV_HIP(hipStreamWaitEvent(plan->side, plan->ev_fork, 0));
+    }
+    if (tiles) {
+        DecodeTilesLaunch t{view_of(plan->pool), q, plan->d_tile_items, plan->d_pages, plan->d_node_req_idx, o_parts, lse_parts,
+                            (int32_t)plan->tile_items.size(), plan->num_q_heads, plan->max_parts, scale, plan->tile_workgroups};
+        HKV_HIP(launch_decode_tiles(t, s, prof ? plan->ev_tile[0] : nullptr, prof ? plan->ev_tile[1] : nullptr));
+    }
     if (!plan->items.empty()) {
+        hipStream_t rs = fork ? plan->side : s;
         DecodeLaunch a{view_of(plan->pool), q, plan->d_items, plan->d_pages, plan->d_node_req_idx, o_parts, lse_parts,
                        (int32_t)plan->items.size(), plan->num_q_heads, plan->max_parts, scale,
                        plan->d_row_leaf, plan->d_row_limit, plan->d_row_mask, plan->n_single, plan->n_stages,
                        plan->fp8_matrix ? 1 : 0};
-        HKV_HIP(launch_decode(a, s, prof ? plan->ev[0] : nullptr, prof ? plan->ev[1] : nullptr));
+        HKV_HIP(launch_decode(a, rs, prof ? plan->ev[0] : nullptr, prof ? plan->ev[1] : nullptr));
+        if (fork) {
+            HKV_HIP(hipEventRecord(plan->ev_join, plan->side));
+            HKV_HIP(hipStreamWaitEvent(s, plan->ev_join, 0));
+        }
     }
     HKV_HIP(launch_lse_merge_dense(o_parts, lse_parts, plan->d_part_count, plan->num_q_heads, plan->max_parts,
                                    plan->n_req * plan->num_q_heads, out, HKV_BF16, lse_out, s,
                                    prof ? plan->ev[2] : nullptr, prof ? plan->ev[3] : nullptr));
-    if (prof) plan->profiled_run = !plan->items.empty();
+    if (prof) plan->profiled_run = !plan->items.empty() || tiles;
     return HKV_OK;
 }
 
@@ -1243,9 +1377,29 @@ extern "C" int attn_decode_plan_run_static(hkv_decode_plan *plan, const void *q,
 extern "C" int hkv_decode_plan_set_profiling(hkv_decode_plan *plan, int32_t mode) {
     if (!plan) return fail(HKV_EINVAL, "hkv_decode_plan_set_profiling: null plan");
     if (mode < 0 || mode > 1) return fail(HKV_EINVAL, "hkv_decode_plan_set_profiling: mode %d", mode);
-    if (mode == 1 && !plan->ev[0])
+    if (mode == 1 && !plan->ev[0]) {
         for (hipEvent_t &e : plan->ev) HKV_HIP(hipEventCreate(&e));
+        for (hipEvent_t &e : plan->ev_tile) HKV_HIP(hipEventCreate(&e));
+    }
     plan->profiling = mode == 1;
+    return HKV_OK;
+}
+
+// GPU time of the node phase of the most recent profiled run: from the earlier begin to the later end of the
+// kernel over `items` and the tile kernel (either may be absent), and each of the two on its own.
+static int node_phase_ms(hkv_decode_plan *plan, float *span, float *rows_ms, float *tile_ms) {
+    const bool rows = !plan->items.empty(), tiles = !plan->tile_items.empty();
+    *span = *rows_ms = *tile_ms = 0.f;
+    if (rows) HKV_HIP(hipEventElapsedTime(rows_ms, plan->ev[0], plan->ev[1]));
+    if (tiles) HKV_HIP(hipEventElapsedTime(tile_ms, plan->ev_tile[0], plan->ev_tile[1]));
+    if (rows && tiles) {  // on the time line of the tile kernel's begin
+        float rows_begin = 0.f, rows_end = 0.f;
+        HKV_HIP(hipEventElapsedTime(&rows_begin, plan->ev_tile[0], plan->ev[0]));
+        HKV_HIP(hipEventElapsedTime(&rows_end, plan->ev_tile[0], plan->ev[1]));
+        *span = std::max(*tile_ms, rows_end) - std::min(0.f, rows_begin);
+    } else {
+        *span = rows ? *rows_ms : *tile_ms;
+    }
     return HKV_OK;
 }
 
@@ -1253,9 +1407,18 @@ extern "C" int hkv_decode_plan_elapsed_ms(hkv_decode_plan *plan, float *node_ms,
     if (!plan || !node_ms || !merge_ms) return fail(HKV_EINVAL, "hkv_decode_plan_elapsed_ms: null argument");
     if (!plan->profiled_run) return fail(HKV_EINVAL, "hkv_decode_plan_elapsed_ms: no profiled run has been queued");
     HKV_HIP(hipEventSynchronize(plan->ev[3]));
-    HKV_HIP(hipEventElapsedTime(node_ms, plan->ev[0], plan->ev[1]));
+    float rows_ms = 0.f, tile_ms = 0.f;
+    if (int rc = node_phase_ms(plan, node_ms, &rows_ms, &tile_ms)) return rc;
     HKV_HIP(hipEventElapsedTime(merge_ms, plan->ev[2], plan->ev[3]));
     return HKV_OK;
+}
+
+extern "C" int hkv_decode_plan_elapsed_kernels_ms(hkv_decode_plan *plan, float *rows_kernel_ms, float *tile_kernel_ms) {
+    if (!plan || !rows_kernel_ms || !tile_kernel_ms) return fail(HKV_EINVAL, "hkv_decode_plan_elapsed_kernels_ms: null argument");
+    if (!plan->profiled_run) return fail(HKV_EINVAL, "hkv_decode_plan_elapsed_kernels_ms: no profiled run has been queued");
+    HKV_HIP(hipEventSynchronize(plan->ev[3]));
+    float span = 0.f;
+    return node_phase_ms(plan, &span, rows_kernel_ms, tile_kernel_ms);
 }
 
 static bool same_forest(const hkv_decode_plan *pl, const hkv_node *nodes, int32_t n_nodes, const int32_t *node_pages,

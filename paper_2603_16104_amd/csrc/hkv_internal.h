@@ -168,6 +168,26 @@ struct RowsLaunch {
 // Largest token count of a decode item that is shared by more than 16 query rows.
 constexpr int kMaxSharedItemTokens = 2048;
 
+// Decode items shared by more than kMinTileItemRows query rows are run by the 256-row tile kernel (the
+// prefill kernel in its second role), on a stream of its own next to the kernel that streams the rest.
+constexpr int kMinTileItemRows = 65;
+constexpr int kMaxTileItemTokens = 2048;  // tokens per such item
+constexpr int kScaleSlots = 256;          // pages whose fp8 scales the tile kernel keeps in LDS
+struct DecodeTilesLaunch {
+    PoolView pool;
+    const void *q;               // [n_req][Hq][128] bf16
+    const DecodeItem *items;     // device: the items of this kernel (at most 256 / G requests each)
+    const int32_t *pages;        // device: the plan's block list
+    const int32_t *node_req_idx; // device: node->request CSR values
+    float *o_parts;
+    float *lse_parts;
+    int32_t n_items;
+    int32_t num_q_heads;
+    int32_t max_parts;
+    float scale;
+    int32_t n_workgroups;        // persistent workgroups: workgroup w runs items w, w + n_workgroups, ...
+};
+
 // Query tokens per prefill workgroup for a given group size G (rows per workgroup / G).
 int prefill_tile_tokens(int group);
 
@@ -189,6 +209,7 @@ hipError_t launch_decode(const DecodeLaunch &a, hipStream_t s, hipEvent_t ev_beg
 hipError_t launch_rows_fp32(const RowsLaunch &a, hipStream_t s);
 hipError_t launch_pool_write_fp32(const PoolWriteLaunch &a, hipStream_t s);
 hipError_t launch_prefill(const PrefillLaunch &a, hipStream_t s);
+hipError_t launch_decode_tiles(const DecodeTilesLaunch &a, hipStream_t s, hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr);
 hipError_t launch_lse_merge(const float *o_parts, const float *lse_parts, const int32_t *row_indptr,
                             const int32_t *part_idx, int32_t n_rows, void *out, int32_t out_dtype,
                             float *lse_out, hipStream_t s);

@@ -218,12 +218,17 @@ def _check_decode_plan(w, oracle):
     assert hkv.hkv_decode_plan_workspace_bytes(plan) >= hkv.hkv_decode_plan_num_parts(plan) * 516
     covered = [np.zeros((w.num_kv_heads, int(kv_len[r])), dtype=np.int32) for r in range(f.n_req)]
     slots = [np.zeros((w.num_kv_heads, max_parts), dtype=np.int32) for _ in range(f.n_req)]
-    for page_off, n_tok, kv_head, req_off, n_req, slot, tok_begin, node in items:
+    n_tile = hkv.hkv_decode_plan_num_tile_items(plan)          # the last n_tile items belong to the 256-row tile kernel
+    n_rows_items = len(items) - n_tile
+    for i, (page_off, n_tok, kv_head, req_off, n_req, slot, tok_begin, node) in enumerate(items):
         assert 1 <= n_tok and tok_begin % 16 == 0 and tok_begin + n_tok <= f.n_tokens[node]
         assert page_off == f.page_begin[node] + tok_begin // 16
-        assert 1 <= n_req and n_req * G <= 64
-        if n_req * G > 16:
-            assert n_tok <= 2048                       # what the LDS-staged path can index
+        if i >= n_rows_items:
+            assert 128 <= (indptr[node + 1] - indptr[node]) * G and 1 <= n_req <= max(1, 256 // G) and n_tok <= 2048
+        else:
+            assert 1 <= n_req and n_req * G <= 64
+            if n_req * G > 16:
+                assert n_tok <= 2048                       # what the LDS-staged path can index
         assert indptr[node] <= req_off and req_off + n_req <= indptr[node + 1]
         if tok_begin + n_tok < f.n_tokens[node]:
             assert n_tok % 16 == 0                     # only a node's last chunk may end inside a page
@@ -232,13 +237,17 @@ def _check_decode_plan(w, oracle):
             covered[r][kv_head, a: a + n_tok] += 1
             slots[r][kv_head, slot] += 1
     assert (items[:, 2] == np.arange(len(items)) % w.num_kv_heads).all(), "item index mod Hkv is the KV head"
+    assert (n_tile == 0) == (hkv.hkv_decode_plan_tile_workgroups(plan) == 0)
+    assert hkv.hkv_decode_plan_tile_workgroups(plan) <= min(n_tile, 256)
     # forests with more items than the 768 resident workgroups: the short items of at most 16 rows come last
     # and share a workgroup four at a time
+    rows_items = items[:n_rows_items]
     limit = 768 if w.kv_dtype == wl.KV_FP8_E4M3 else 384
-    short = (items[:, 4] * G <= 16) & (items[:, 1] <= limit) if len(items) > 768 else np.zeros(len(items), dtype=bool)
+    short = ((rows_items[:, 4] * G <= 16) & (rows_items[:, 1] <= limit) if n_rows_items > 768
+             else np.zeros(n_rows_items, dtype=bool))
     n_single = int((~short).sum())
     assert not short[:n_single].any() and short[n_single:].all()
-    assert hkv.hkv_decode_plan_num_workgroups(plan) == n_single + (len(items) - n_single + 3) // 4
+    assert hkv.hkv_decode_plan_num_workgroups(plan) == n_single + (n_rows_items - n_single + 3) // 4
     for r in range(f.n_req):
         assert (covered[r] == 1).all(), "every (request, kv head, token) is read by exactly one item"
         assert (slots[r][:, :counts[r]] == 1).all() and (slots[r][:, counts[r]:] == 0).all()
@@ -343,6 +352,7 @@ def test_many_row_and_few_row_items_are_dispatched_side_by_side(monkeypatch):
     w = wl.config5()
     f = w.forest
     pool = fake_pool(w.num_pages, w.num_kv_heads, dtype=hkv.FP8_E4M3)
+    monkeypatch.setenv("HKV_DECODE_TILE_GFLOP", "1000000")     # keep the roots out of the 256-row tile kernel here
 
     def items_of():
         plan = hkv.hkv_decode_plan_create(pool, f.nodes, f.node_pages, f.req_leaf, w.num_q_heads, hkv.PLAN_HOST_ONLY)
@@ -367,6 +377,37 @@ def test_many_row_and_few_row_items_are_dispatched_side_by_side(monkeypatch):
     assert sorted(map(tuple, mixed.tolist())) == sorted(map(tuple, apart.tolist()))
     assert (mixed[many] == apart[many_apart]).all() and (mixed[~many] == apart[~many_apart]).all()
     hkv.kv_pool_destroy(pool)
+
+
+def test_large_many_row_share_goes_to_the_tile_kernel(oracle):
+    """c5: the 16 roots (256 query rows per KV head, 137 GFLOP) become items of the 256-row tile kernel: one
+    request group of 32 per root and KV head, 4 chunks of 2048 tokens, on a multiple of 8 persistent
+    workgroups; the private leaves stay with the other kernel.  c2 and c3 (2 and 9 GFLOP of such work) and
+    plans with several query tokens per request keep everything in one kernel."""
+    w = wl.config5()
+    f = w.forest
+    items = _check_decode_plan(w, oracle)
+    pool = fake_pool(w.num_pages, w.num_kv_heads, dtype=hkv.FP8_E4M3)
+    plan = hkv.hkv_decode_plan_create(pool, f.nodes, f.node_pages, f.req_leaf, w.num_q_heads, hkv.PLAN_HOST_ONLY)
+    n_tile = hkv.hkv_decode_plan_num_tile_items(plan)
+    assert n_tile == 16 * 8 * 4 and len(items) == n_tile + 4096
+    tiles = items[-n_tile:]
+    assert (tiles[:, 4] == 32).all() and (tiles[:, 1] == 2048).all() and (tiles[:, 7] < 16).all()
+    wgs = hkv.hkv_decode_plan_tile_workgroups(plan)
+    assert 8 <= wgs <= 192 and wgs % 8 == 0
+    assert (items[:-n_tile, 4] == 1).all()
+    hkv.hkv_decode_plan_destroy(plan)
+    multi = hkv.hkv_decode_plan_create_multi(pool, f.nodes, f.node_pages, f.req_leaf, 2, w.num_q_heads, hkv.PLAN_HOST_ONLY)
+    assert hkv.hkv_decode_plan_num_tile_items(multi) == 0
+    hkv.hkv_decode_plan_destroy(multi)
+    hkv.kv_pool_destroy(pool)
+    for small in (wl.config2(), wl.config3()):
+        sp = fake_pool(small.num_pages, small.num_kv_heads)
+        plan = hkv.hkv_decode_plan_create(sp, small.forest.nodes, small.forest.node_pages, small.forest.req_leaf,
+                                          small.num_q_heads, hkv.PLAN_HOST_ONLY)
+        assert hkv.hkv_decode_plan_num_tile_items(plan) == 0 and hkv.hkv_decode_plan_tile_workgroups(plan) == 0
+        hkv.hkv_decode_plan_destroy(plan)
+        hkv.kv_pool_destroy(sp)
 
 
 def test_decode_plan_error_codes():
