@@ -179,7 +179,9 @@ int kv_pool_write(hkv_pool *pool, const int32_t *page_ids, int32_t first_slot, i
  * of page page_ids[i]; page_ids and slots are host arrays of n entries (n <= 32768).  Same
  * arithmetic as kv_pool_write with n_tokens = 1 (fp8: the block's running scale, re-encoding of
  * its earlier codes if the scale grows).  No two tokens of one call may go to the same 16-token
- * block.  bf16 and fp8 pools (ESHAPE for fp32 pools: use kv_pool_write). */
+ * block, and no token to a page that has more than one owner (kv_pool_refcount > 1: such a page is
+ * shared, kv_pool_copy_on_write gives the writer its own): EINVAL, checked before anything is queued.
+ * bf16 and fp8 pools (ESHAPE for fp32 pools: use kv_pool_write). */
 int kv_pool_append(hkv_pool *pool, const int32_t *page_ids, const int32_t *slots, int32_t n,
                    const void *k_src, const void *v_src, void *stream);
 
@@ -328,6 +330,37 @@ int hkv_decode_plan_create_tree(hkv_pool *pool, const hkv_node *nodes, int32_t n
 int hkv_decode_plan_create_growing(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes, const int32_t *node_pages,
                                    int32_t n_node_pages, const int32_t *req_leaf, int32_t n_req, int32_t num_q_heads,
                                    int32_t reserve_tokens, uint32_t flags, hkv_decode_plan **out);
+
+/* Everything the four calls above can ask for, in one call, plus the planner's settings.  params may be NULL
+ * (then this is hkv_decode_plan_create); every field left 0 keeps the library's own choice, so a caller sets
+ * only what it needs (zero the struct first).  The settings change how the forest is cut into work items and
+ * which of the library's kernels run them, never the result; they exist for sweeps and so that tests reach a
+ * particular path at small sizes.  EINVAL for a value outside the range stated with its field. */
+typedef struct {
+    int32_t tokens_per_req;   /* query tokens per request, 1..64 (beyond 16 only with `visible`); 0 = 1 */
+    const uint64_t *visible;  /* host [n_req * tokens_per_req]: as hkv_decode_plan_create_tree; NULL = causal run */
+    int32_t reserve_tokens;   /* > 0: a growing plan, as hkv_decode_plan_create_growing */
+    /* ---- planner settings */
+    int32_t leaf_chunk;       /* tokens per item of nodes read by at most 16 query rows; multiple of 16 */
+    int32_t shared_chunk;     /* tokens per item of nodes shared by more rows; multiple of 16, at most 2048 */
+    int32_t max_rows;         /* query rows per item of such nodes: 16..64 */
+    int32_t pack;             /* four short items per workgroup, one per wavefront: 1 never, 2 when the forest has
+                                 more items than the chip holds at once (the default), 3 always */
+    int32_t pack_tokens;      /* longest item of that mode, tokens */
+    int32_t stages;           /* 16 KiB LDS stages a workgroup owns: 3..5 */
+    int32_t interleave;       /* items shared by many rows and items of few rows are listed side by side in
+                                 groups of this size (default 8); -1: one class after the other */
+    int32_t tile_min_rows;    /* nodes shared by this many query rows or more may go to the 256-row tile kernel
+                                 (default 128, at least 65) ... */
+    int32_t tile_min_gflop;   /* ... if the forest holds this much such work (default 40); -1: whatever the amount */
+    int32_t tile_workgroups;  /* persistent workgroups of the tile kernel (default: from the two amounts of work) */
+    int32_t tile_chunk;       /* tokens per item of the tile kernel; multiple of 16, at most 2048 */
+    int32_t large_batch_updates; /* growing plans: 1 = apply appends as for more than 256 requests (work list re-sent
+                                 from pinned memory instead of a small kernel that carries the change in its arguments) */
+} hkv_decode_plan_params;
+int hkv_decode_plan_create_ex(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes, const int32_t *node_pages,
+                              int32_t n_node_pages, const int32_t *req_leaf, int32_t n_req, int32_t num_q_heads,
+                              uint32_t flags, const hkv_decode_plan_params *params, hkv_decode_plan **out);
 int hkv_decode_plan_append(hkv_decode_plan *plan, const int32_t *new_page_ids, void *stream);
 /* The same together with the write: row r of k_src / v_src (device, [n_req][num_kv_heads][128] bf16)
  * is the new token of request r and is stored at the end of its leaf, as kv_pool_append would store

@@ -15,6 +15,10 @@ Readings where the paper is silent (the library takes the same ones)
   C2  acquire(tokens): walk the full blocks from the front while they are cached (hits), then give
       every remaining block a page: from the pool's free list (lowest id first, as kv_pool_alloc
       does) or, when that is empty, by evicting.  New full blocks enter the cache at once.
+      A call that runs out of pages fails as a whole: its hits are released, the blocks it had created
+      leave the cache again (deepest first, pages back to the pool in that order; they never held KV,
+      so a later call must not count them as cached) and its hit/miss counts are taken back.  Blocks it
+      evicted on the way stay evicted.
   C3  Evictable = not referenced by a live sequence, not pinned, and no cached block extends it.
       Among those the one with the oldest last-use time goes first; ties by lower page id.  Last-use
       time is a logical clock that ticks once per acquire / release call.
@@ -90,6 +94,7 @@ class PrefixCache:
             node, j = nxt, j + 1
             self.hits += 1
         cached = j * self.block
+        n_hit = j
         try:
             while j < n_full:                               # misses: new full blocks
                 key = tuple(int(t) for t in tokens[j * self.block:(j + 1) * self.block])
@@ -106,7 +111,13 @@ class PrefixCache:
                 self.private[p] = 1
                 pages.append(p)
         except MemoryError:
-            self.release(pages)                             # give back what this call took
+            self.release(pages[:n_hit])                     # the hits: as a release
+            for b in reversed(taken[n_hit:]):               # the blocks created here never held KV: out again
+                del b.parent.children[b.key]
+                del self.by_page[b.page]
+                self.free.append(b.page)
+            self.hits -= n_hit
+            self.misses -= len(taken) - n_hit
             raise
         if pin:
             for b in taken:

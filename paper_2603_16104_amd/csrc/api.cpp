@@ -52,11 +52,24 @@ size_t elem_bytes(int dtype) { return dtype == HKV_BF16 ? 2 : dtype == HKV_FP8_E
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-int env_int(const char *name, int dflt) {
-    const char *s = getenv(name);
-    if (!s || !*s) return dflt;
-    int v = atoi(s);
-    return v > 0 ? v : dflt;
+// What the planner needs to know of the chip: compute units, and how many workgroups of the per-node decode
+// kernel one of them holds (three with bf16 pools, two with fp8 pools: registers).  Asked of the current device;
+// plans built without a device (HKV_PLAN_HOST_ONLY on a machine without a GPU) assume an MI355X.
+struct ChipShape {
+    int n_cu = 256;
+    int lds_per_cu = 160 * 1024;
+};
+ChipShape chip_shape() {
+    ChipShape c;
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) {
+        if (prop.multiProcessorCount > 0) c.n_cu = prop.multiProcessorCount;
+        if (prop.maxSharedMemoryPerMultiProcessor > 0) c.lds_per_cu = (int)prop.maxSharedMemoryPerMultiProcessor;
+    } else {
+        (void)hipGetLastError();  // no device: not an error of the caller's
+    }
+    return c;
 }
 
 }  // namespace
@@ -87,6 +100,7 @@ struct hkv_decode_plan {
     int32_t n_single = 0;  // items [0, n_single) run one per workgroup, the rest four per workgroup
     int32_t n_stages = 3;  // LDS stages of 16 KiB per workgroup of the per-node kernel
     bool fp8_matrix = false;  // fp8 pools: both products on the fp8 matrix instruction (HKV_PLAN_FP8_MATRIX)
+    hkv_decode_plan_params opt{};  // the planner's settings (0 = the library's choice)
     int32_t *d_pages = nullptr, *d_node_req_idx = nullptr, *d_part_count = nullptr;
     bool profiling = false, profiled_run = false;
     hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};  // begin/end of the node kernel, begin/end of the merge
@@ -385,10 +399,20 @@ extern "C" int kv_pool_append(hkv_pool *pool, const int32_t *page_ids, const int
         if (page_ids[i] < 0 || page_ids[i] >= pool->d.num_pages)
             return fail(HKV_ERANGE, "kv_pool_append: page id %d (entry %d) outside pool of %d pages", page_ids[i], i, pool->d.num_pages);
         if (slots[i] < 0 || slots[i] >= P) return fail(HKV_EINVAL, "kv_pool_append: slot %d (entry %d)", slots[i], i);
+        if (pool->refcnt[page_ids[i]] > 1)
+            return fail(HKV_EINVAL, "kv_pool_append: page %d (entry %d) has %d owners: kv_pool_copy_on_write first", page_ids[i], i,
+                        pool->refcnt[page_ids[i]]);
+    }
+    if (n > 1) {  // two tokens of one call in one block would race on the block's scale and on its re-encoding
+        std::vector<int32_t> blocks(n);
+        for (int i = 0; i < n; ++i) blocks[i] = page_ids[i] * S + slots[i] / HKV_PAGE_SIZE;
+        std::sort(blocks.begin(), blocks.end());
+        auto dup = std::adjacent_find(blocks.begin(), blocks.end());
+        if (dup != blocks.end())
+            return fail(HKV_EINVAL, "kv_pool_append: two tokens go to block %d of page %d", *dup % S, *dup / S);
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
-    // HKV_APPEND_INLINE=0 (tests): take the path of larger batches
-    if (n <= kMaxInlineAppend && env_int("HKV_APPEND_INLINE", 1) == 1) {  // the usual decode batch: everything travels in the kernel arguments
+    if (n <= kMaxInlineAppend) {  // the usual decode batch: everything travels in the kernel arguments
         PoolAppendInline a{};
         a.base = PoolWriteLaunch{pool->d.k_pages, pool->d.v_pages, pool->d.k_scale, pool->d.v_scale, pool->d.num_kv_heads,
                                  pool->d.dtype, nullptr, n, 0, n, k_src, v_src, nullptr};
@@ -592,15 +616,18 @@ static void plan_items(hkv_decode_plan &pl) {
     const int G = pl.group;
     const int Hkv = pl.pool->d.num_kv_heads;
     const int n_nodes = (int)pl.nodes.size();
-    const int max_req_per_item = std::max(1, std::min(64, env_int("HKV_DECODE_MAX_ROWS", 64)) / G);
+    const hkv_decode_plan_params &opt = pl.opt;
+    auto or_default = [](int32_t v, int dflt) { return v != 0 ? (int)v : dflt; };
+    const ChipShape chip = chip_shape();
+    const int max_req_per_item = std::max(1, or_default(opt.max_rows, 64) / G);
     // Chunk lengths.  Nodes read by at most 16 rows ("leaf type") stay whole unless the forest has
     // fewer (node, head) units than workgroups fit on the chip at once; then they are cut, but not
     // below 256 tokens.  Nodes shared by more rows run one row tile per wavefront over all tokens
     // of the item, so their chunks are kept near the typical leaf-type item to finish together.
-    const int kResidentGroups = 768;  // 256 CUs x 3 workgroups
+    const int kResidentGroups = chip.n_cu * (pl.pool->d.dtype == HKV_FP8_E4M3 ? 2 : 3);  // workgroups the chip holds at once
     // Nodes shared by many rows go to the 256-row tile kernel (not with per-row visibility, which that kernel
     // does not know, and not when the caller asked for the fp8 matrix instruction).
-    const int tile_min_rows = env_int("HKV_DECODE_TILE_ROWS", 128);
+    const int tile_min_rows = or_default(opt.tile_min_rows, 128);
     // The second kernel, its stream and the two events pay only when that share of the step is large (measured:
     // c2 and c3, 2 and 9 GFLOP of such work in steps of 30 to 50 us, lose; c5, 137 GFLOP in 0.5 ms, gains 11 %).
     bool tiles_pay = false;
@@ -611,8 +638,7 @@ static void plan_items(hkv_decode_plan &pl) {
             if (R * G >= std::max(tile_min_rows, kMinTileItemRows))
                 flop += 4.0 * HKV_HEAD_DIM * pl.nodes[v].n_tokens * (double)R * pl.num_q_heads;
         }
-        const char *e = getenv("HKV_DECODE_TILE_GFLOP");  // development knob
-        tiles_pay = flop >= 1e9 * (e && *e ? atof(e) : 40.0);
+        tiles_pay = opt.tile_min_gflop < 0 || flop >= 1e9 * or_default(opt.tile_min_gflop, 40);
     }
     auto tiled = [&](int v) {
         const int R = pl.node_req_indptr[v + 1] - pl.node_req_indptr[v];
@@ -655,8 +681,8 @@ static void plan_items(hkv_decode_plan &pl) {
         if (longest > 16 * by_path) by_path = std::min<int64_t>(kMaxSharedItemTokens, (longest / 16 + 255) / 256 * 256);
         shared_chunk = std::max(shared_chunk, (int)by_path);
     }
-    leaf_chunk = env_int("HKV_DECODE_LEAF_CHUNK", leaf_chunk) / 16 * 16;
-    shared_chunk = std::min(kMaxSharedItemTokens, env_int("HKV_DECODE_SHARED_CHUNK", shared_chunk)) / 16 * 16;
+    leaf_chunk = or_default(opt.leaf_chunk, leaf_chunk) / 16 * 16;
+    shared_chunk = std::min(kMaxSharedItemTokens, or_default(opt.shared_chunk, shared_chunk)) / 16 * 16;
     // Few-row nodes a little longer than what one wavefront takes alone (pack_tokens): run whole, their
     // four wavefronts get only a few steps each and pay a start-up and a combine through LDS for them.
     // When cutting them into pieces of at most pack_tokens makes the forest large enough for the
@@ -664,11 +690,11 @@ static void plan_items(hkv_decode_plan &pl) {
     // (c2: 512-token leaves as 2 x 256, per-node kernel 31.7 -> 30.0 us).  Nodes of 8 / 3 pack_tokens and
     // more keep their four wavefronts: those already get that many steps each.
     const int step_tokens = pl.pool->d.dtype == HKV_FP8_E4M3 ? 64 : 32;
-    const int pack_tokens = env_int("HKV_DECODE_PACK_TOKENS", 12 * step_tokens);
-    const int pack_mode = env_int("HKV_DECODE_PACK", 2);  // 1: never, 2: when the items exceed the resident workgroups, 3: always
+    const int pack_tokens = or_default(opt.pack_tokens, 12 * step_tokens);
+    const int pack_mode = or_default(opt.pack, 2);  // 1: never, 2: when the items exceed the resident workgroups, 3: always
     auto cut_for_packing = [&](int n_tokens) { return n_tokens > pack_tokens && 3 * n_tokens < 8 * pack_tokens; };
     bool cut_leaves = false;
-    if (leaf_split == 1 && pack_mode != 1 && !getenv("HKV_DECODE_LEAF_CHUNK")) {
+    if (leaf_split == 1 && pack_mode != 1 && opt.leaf_chunk == 0) {
         int64_t units = shared_units;
         bool any = false;
         for (int v = 0; v < n_nodes; ++v) {
@@ -703,20 +729,20 @@ static void plan_items(hkv_decode_plan &pl) {
             }
         }
         if (tile_units > 0) {
-            const int n_cu = 256;
+            const int n_cu = chip.n_cu;
             int wgs = n_cu;
             if (other_bytes > 0) {
                 const double t_other = other_bytes / 5.5e12;
                 wgs = (int)(tile_flop / (3.5e12 * t_other) + 0.999);
                 wgs = std::min(n_cu - 64, std::max(8, (wgs + 7) / 8 * 8));  // whole groups of 8: one per XCD
             }
-            wgs = env_int("HKV_DECODE_TILE_WGS", wgs);
+            wgs = std::min(n_cu, or_default(opt.tile_workgroups, wgs));
             pl.tile_workgroups = wgs;
             // chunks: at least two rounds of items per workgroup where the nodes are long enough, few partials otherwise
             const int64_t per_unit = std::max<int64_t>(1, (2 * (int64_t)wgs + tile_units - 1) / tile_units);
             int64_t ch = (tile_tokens_max / per_unit + 63) / 64 * 64;
             tile_chunk = (int)std::min<int64_t>(kMaxTileItemTokens, std::max<int64_t>(256, ch));
-            tile_chunk = std::min(kMaxTileItemTokens, env_int("HKV_DECODE_TILE_CHUNK", tile_chunk)) / 16 * 16;
+            tile_chunk = std::min(kMaxTileItemTokens, or_default(opt.tile_chunk, tile_chunk)) / 16 * 16;
         }
     }
     struct Proto { DecodeItem it; int64_t cost; };
@@ -774,8 +800,7 @@ static void plan_items(hkv_decode_plan &pl) {
     // stream and items of few rows by memory: the two classes are dispatched side by side, each spread evenly
     // over the list (groups of 8 = one workgroup per XCD), so that both are resident on every CU throughout
     // instead of one class after the other.  Within a class the order stays heavy before light.
-    const char *il = getenv("HKV_DECODE_INTERLEAVE");  // development knob: group size, 0 = one class after the other
-    if (const int group = il && *il ? atoi(il) : 8; group > 0) {
+    if (const int group = or_default(opt.interleave, 8); group > 0) {
         std::vector<Proto> many, few, rest, merged;
         for (auto &p : protos) (packable(p) ? rest : p.it.n_req * G > 16 ? many : few).push_back(p);
         if (!many.empty() && !few.empty()) {
@@ -802,7 +827,7 @@ static void plan_items(hkv_decode_plan &pl) {
     }
     // LDS stages per workgroup.  The fp8 kernel runs two workgroups per CU (registers), so each may own
     // half of the CU's 160 KiB: five stages, four steps of a shared item in flight instead of two.
-    pl.n_stages = std::min(5, std::max(3, env_int("HKV_DECODE_STAGES", pl.pool->d.dtype == HKV_FP8_E4M3 ? 5 : 3)));
+    pl.n_stages = or_default(opt.stages, pl.pool->d.dtype == HKV_FP8_E4M3 ? 5 : 3);
     pl.part_count.assign(pl.n_req, 0);
     pl.max_parts = 1;
     for (int r = 0; r < pl.n_req; ++r) {
@@ -838,8 +863,7 @@ static int upload_decode_plan(hkv_decode_plan &pl) {
     put(off_cnt, pl.part_count.data(), sizeof(int32_t) * pl.part_count.size());
     put(off_tiles, pl.tile_items.data(), sizeof(DecodeItem) * pl.tile_items.size());
     HKV_HIP(hipMemcpy(pl.dev, image.data(), total, hipMemcpyHostToDevice));
-    // HKV_GROW_INLINE=0 (tests): take the path of larger batches, the work list re-sent from pinned memory
-    if (pl.reserve_tokens > 0 && pl.n_req <= kMaxInlineAppend && !pl.grow_items.empty() && env_int("HKV_GROW_INLINE", 1) == 1) {
+    if (pl.reserve_tokens > 0 && pl.n_req <= kMaxInlineAppend && !pl.grow_items.empty() && !pl.opt.large_batch_updates) {
         HKV_HIP(hipMalloc((void **)&pl.d_grow_items, sizeof(int32_t) * pl.grow_items.size()));
         HKV_HIP(hipMemcpy(pl.d_grow_items, pl.grow_items.data(), sizeof(int32_t) * pl.grow_items.size(), hipMemcpyHostToDevice));
     } else if (pl.reserve_tokens > 0) {
@@ -894,11 +918,32 @@ static int build_fp32_rows(hkv_decode_plan &pl, bool upload) {
 // internal flag: no item may go to the 256-row tile kernel (plans with per-row visibility)
 constexpr uint32_t kPlanNoTiles = 0x40000000u;
 
+// the planner's settings, each 0 (the library's choice) or inside its documented range
+static int check_plan_settings(const hkv_decode_plan_params *o) {
+    if (!o) return HKV_OK;
+    auto bad = [](const char *name, int32_t v) { return fail(HKV_EINVAL, "hkv_decode_plan_create_ex: %s = %d is out of range", name, v); };
+    if (o->leaf_chunk < 0 || o->leaf_chunk % 16) return bad("leaf_chunk", o->leaf_chunk);
+    if (o->shared_chunk < 0 || o->shared_chunk % 16 || o->shared_chunk > kMaxSharedItemTokens) return bad("shared_chunk", o->shared_chunk);
+    if (o->max_rows != 0 && (o->max_rows < 16 || o->max_rows > 64)) return bad("max_rows", o->max_rows);
+    if (o->pack < 0 || o->pack > 3) return bad("pack", o->pack);
+    if (o->pack_tokens < 0) return bad("pack_tokens", o->pack_tokens);
+    if (o->stages != 0 && (o->stages < 3 || o->stages > 5)) return bad("stages", o->stages);
+    if (o->interleave < -1) return bad("interleave", o->interleave);
+    if (o->tile_min_rows != 0 && o->tile_min_rows < kMinTileItemRows) return bad("tile_min_rows", o->tile_min_rows);
+    if (o->tile_min_gflop < -1) return bad("tile_min_gflop", o->tile_min_gflop);
+    if (o->tile_workgroups < 0) return bad("tile_workgroups", o->tile_workgroups);
+    if (o->tile_chunk < 0 || o->tile_chunk % 16 || o->tile_chunk > kMaxTileItemTokens) return bad("tile_chunk", o->tile_chunk);
+    if (o->large_batch_updates < 0 || o->large_batch_updates > 1) return bad("large_batch_updates", o->large_batch_updates);
+    return HKV_OK;
+}
+
 static int create_decode_plan(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes, const int32_t *node_pages,
                               int32_t n_node_pages, const int32_t *req_leaf, int32_t n_req, int32_t num_q_heads,
-                              uint32_t flags, int32_t reserve_tokens, hkv_decode_plan **out) {
+                              uint32_t flags, int32_t reserve_tokens, const hkv_decode_plan_params *opt,
+                              hkv_decode_plan **out) {
     if (!pool || !out) return fail(HKV_EINVAL, "hkv_decode_plan_create: null argument");
     *out = nullptr;
+    if (int rc = check_plan_settings(opt)) return rc;
     const int Hkv = pool->d.num_kv_heads;
     if (num_q_heads <= 0 || num_q_heads % Hkv || num_q_heads / Hkv > 16)
         return fail(HKV_ESHAPE, "hkv_decode_plan_create: %d query heads over %d KV heads", num_q_heads, Hkv);
@@ -922,7 +967,8 @@ static int create_decode_plan(hkv_pool *pool, const hkv_node *nodes, int32_t n_n
     pl->n_req = n_req;
     pl->num_q_heads = num_q_heads;
     pl->group = num_q_heads / Hkv;
-    pl->fp8_matrix = pool->d.dtype == HKV_FP8_E4M3 && ((flags & HKV_PLAN_FP8_MATRIX) || env_int("HKV_FP8_MATRIX", 0) == 1);
+    pl->fp8_matrix = pool->d.dtype == HKV_FP8_E4M3 && (flags & HKV_PLAN_FP8_MATRIX);
+    if (opt) pl->opt = *opt;
     pl->no_tiles = (flags & kPlanNoTiles) != 0;
     pl->concurrent = !(flags & HKV_PLAN_ONE_STREAM);
     if (int rc = build_node_req_csr(nodes, n_nodes, req_leaf, n_req, pl->node_req_indptr, pl->node_req_idx,
@@ -998,13 +1044,13 @@ extern "C" int hkv_decode_plan_create(hkv_pool *pool, const hkv_node *nodes, int
                                       const int32_t *node_pages, int32_t n_node_pages, const int32_t *req_leaf,
                                       int32_t n_req, int32_t num_q_heads, uint32_t flags, hkv_decode_plan **out) {
     return create_decode_plan(pool, nodes, n_nodes, node_pages, n_node_pages, req_leaf, n_req, num_q_heads,
-                              flags & ~kPlanNoTiles, 0, out);
+                              flags & ~kPlanNoTiles, 0, nullptr, out);
 }
 
-extern "C" int hkv_decode_plan_create_growing(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes,
-                                              const int32_t *node_pages, int32_t n_node_pages,
-                                              const int32_t *req_leaf, int32_t n_req, int32_t num_q_heads,
-                                              int32_t reserve_tokens, uint32_t flags, hkv_decode_plan **out) {
+static int create_growing_plan(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes, const int32_t *node_pages,
+                               int32_t n_node_pages, const int32_t *req_leaf, int32_t n_req, int32_t num_q_heads,
+                               int32_t reserve_tokens, uint32_t flags, const hkv_decode_plan_params *opt,
+                               hkv_decode_plan **out) {
     if (!pool || !out) return fail(HKV_EINVAL, "hkv_decode_plan_create_growing: null argument");
     *out = nullptr;
     if (pool->d.dtype == HKV_FP32) return fail(HKV_ESHAPE, "hkv_decode_plan_create_growing: bf16 and fp8 pools only");
@@ -1028,8 +1074,16 @@ extern "C" int hkv_decode_plan_create_growing(hkv_pool *pool, const hkv_node *no
         if (nodes[req_leaf[r]].n_tokens < 1)
             return fail(HKV_ETREE, "hkv_decode_plan_create_growing: the leaf of request %d holds no token", r);
     }
-    return create_decode_plan(pool, nodes, n_nodes, node_pages, n_node_pages, req_leaf, n_req, num_q_heads, flags,
-                              reserve_tokens, out);
+    return create_decode_plan(pool, nodes, n_nodes, node_pages, n_node_pages, req_leaf, n_req, num_q_heads,
+                              flags & ~kPlanNoTiles, reserve_tokens, opt, out);
+}
+
+extern "C" int hkv_decode_plan_create_growing(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes,
+                                              const int32_t *node_pages, int32_t n_node_pages,
+                                              const int32_t *req_leaf, int32_t n_req, int32_t num_q_heads,
+                                              int32_t reserve_tokens, uint32_t flags, hkv_decode_plan **out) {
+    return create_growing_plan(pool, nodes, n_nodes, node_pages, n_node_pages, req_leaf, n_req, num_q_heads,
+                               reserve_tokens, flags, nullptr, out);
 }
 
 // k_src / v_src: null (the caller stores the tokens itself), or the new token of every request, stored here
@@ -1138,8 +1192,8 @@ extern "C" int hkv_decode_plan_append_tokens(hkv_decode_plan *plan, const int32_
 // is set (masks == nullptr: the causal run, bits 0..t).
 static int create_rows_plan(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes, const int32_t *node_pages,
                             int32_t n_node_pages, const int32_t *req_leaf, int32_t n_req, int32_t T,
-                            const uint64_t *masks, int32_t num_q_heads, uint32_t flags, hkv_decode_plan **out,
-                            const char *who) {
+                            const uint64_t *masks, int32_t num_q_heads, uint32_t flags,
+                            const hkv_decode_plan_params *opt, hkv_decode_plan **out, const char *who) {
     if (n_req < 0 || (n_req > 0 && !req_leaf)) return fail(HKV_EINVAL, "%s: bad request list", who);
     if ((int64_t)n_req * T > INT32_MAX / 2) return fail(HKV_EINVAL, "%s: too many query rows", who);
     if (masks && pool && pool->d.dtype == HKV_FP32)
@@ -1150,7 +1204,7 @@ static int create_rows_plan(hkv_pool *pool, const hkv_node *nodes, int32_t n_nod
     hkv_decode_plan *pl = nullptr;
     const uint32_t rows_flags = (flags & ~kPlanNoTiles) | ((T > 1 || masks) ? kPlanNoTiles : 0u);
     if (int rc = create_decode_plan(pool, nodes, n_nodes, node_pages, n_node_pages, rows.data(), n_req * T, num_q_heads,
-                                    rows_flags, 0, &pl))
+                                    rows_flags, 0, opt, &pl))
         return rc;
     pl->tokens_per_req = T;
     if (T > 1 || masks) {
@@ -1213,7 +1267,7 @@ extern "C" int hkv_decode_plan_create_multi(hkv_pool *pool, const hkv_node *node
     if (tokens_per_req < 1 || tokens_per_req > 16)
         return fail(HKV_EINVAL, "hkv_decode_plan_create_multi: %d query tokens per request (1..16)", tokens_per_req);
     return create_rows_plan(pool, nodes, n_nodes, node_pages, n_node_pages, req_leaf, n_req, tokens_per_req, nullptr,
-                            num_q_heads, flags, out, "hkv_decode_plan_create_multi");
+                            num_q_heads, flags, nullptr, out, "hkv_decode_plan_create_multi");
 }
 
 extern "C" int hkv_decode_plan_create_tree(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes,
@@ -1226,7 +1280,31 @@ extern "C" int hkv_decode_plan_create_tree(hkv_pool *pool, const hkv_node *nodes
         return fail(HKV_EINVAL, "hkv_decode_plan_create_tree: %d drafted tokens per request (1..64)", tokens_per_req);
     if (n_req > 0 && !visible) return fail(HKV_EINVAL, "hkv_decode_plan_create_tree: null visibility masks");
     return create_rows_plan(pool, nodes, n_nodes, node_pages, n_node_pages, req_leaf, n_req, tokens_per_req, visible,
-                            num_q_heads, flags, out, "hkv_decode_plan_create_tree");
+                            num_q_heads, flags, nullptr, out, "hkv_decode_plan_create_tree");
+}
+
+extern "C" int hkv_decode_plan_create_ex(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes,
+                                         const int32_t *node_pages, int32_t n_node_pages, const int32_t *req_leaf,
+                                         int32_t n_req, int32_t num_q_heads, uint32_t flags,
+                                         const hkv_decode_plan_params *params, hkv_decode_plan **out) {
+    if (!out) return fail(HKV_EINVAL, "hkv_decode_plan_create_ex: null out");
+    *out = nullptr;
+    const int32_t T = params && params->tokens_per_req ? params->tokens_per_req : 1;
+    const uint64_t *visible = params ? params->visible : nullptr;
+    const int32_t reserve = params ? params->reserve_tokens : 0;
+    if (T < 1 || T > 64 || (T > 16 && !visible))
+        return fail(HKV_EINVAL, "hkv_decode_plan_create_ex: %d query tokens per request (1..16, up to 64 with visibility masks)", T);
+    if (reserve < 0) return fail(HKV_EINVAL, "hkv_decode_plan_create_ex: reserve_tokens %d", reserve);
+    if (reserve > 0 && (T > 1 || visible))
+        return fail(HKV_EINVAL, "hkv_decode_plan_create_ex: a growing plan has one query token per request");
+    if (T > 1 || visible)
+        return create_rows_plan(pool, nodes, n_nodes, node_pages, n_node_pages, req_leaf, n_req, T, visible, num_q_heads,
+                                flags, params, out, "hkv_decode_plan_create_ex");
+    if (reserve > 0)
+        return create_growing_plan(pool, nodes, n_nodes, node_pages, n_node_pages, req_leaf, n_req, num_q_heads, reserve,
+                                   flags, params, out);
+    return create_decode_plan(pool, nodes, n_nodes, node_pages, n_node_pages, req_leaf, n_req, num_q_heads,
+                              flags & ~kPlanNoTiles, 0, params, out);
 }
 
 extern "C" int hkv_decode_plan_destroy(hkv_decode_plan *plan) {

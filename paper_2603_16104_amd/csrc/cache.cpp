@@ -147,6 +147,7 @@ extern "C" int kv_cache_acquire(hkv_cache *c, const int32_t *tokens, int32_t n_t
         ++c->hits;
     }
     *n_cached_tokens = j * P;
+    const int n_hit = j;
     bool ok = true;
     for (; j < n_full && ok; ++j) {  // misses: new full blocks enter the cache at once
         const int32_t page = c->take_page();
@@ -182,8 +183,21 @@ extern "C" int kv_cache_acquire(hkv_cache *c, const int32_t *tokens, int32_t n_t
             page_ids[n_pages++] = page;
         }
     }
-    if (!ok) {
-        c->release_pages(page_ids, n_pages);  // give back what this call took (the clock ticks once more)
+    if (!ok) {  // the call fails as a whole
+        c->release_pages(page_ids, n_hit);  // the hits: as a release (the clock ticks once more)
+        for (size_t i = taken.size(); i-- > (size_t)n_hit;) {
+            // a block created here never held KV: it leaves the cache again (deepest first), so that no later
+            // call finds it as a hit; its page goes back to the pool
+            Block *b = taken[i], *par = b->parent;
+            par->children.erase(b->key);
+            c->add(par);  // it may have lost its last child
+            c->by_page.erase(b->page);
+            (void)kv_pool_release(c->pool, 1, &b->page);
+            delete b;
+        }
+        c->hits -= n_hit;
+        c->misses -= (int64_t)taken.size() - n_hit;
+        *n_cached_tokens = 0;
         return fail(HKV_ENOMEM, "kv_cache_acquire: no page free and nothing evictable (%d tokens)", n_tokens);
     }
     if (pin)

@@ -106,15 +106,14 @@ class DecodeRunner:
     """Plan + buffers for repeated decode steps over one forest."""
 
     def __init__(self, pool: DevicePool, workload: wl.Workload, random_q: bool = False, flags: int = 0,
-                 reserve_tokens: int = 0):
+                 reserve_tokens: int = 0, **settings):
+        """reserve_tokens > 0: a decode loop, every request's leaf may grow (append) without a new plan.
+        settings: planner settings of hkv_decode_plan_params by name."""
         f = workload.forest
         self.pool, self.workload = pool, workload
-        if reserve_tokens > 0:      # a decode loop: every request's leaf may grow (append) without a new plan
-            self.plan = hkv.hkv_decode_plan_create_growing(pool.handle, f.nodes, f.node_pages, f.req_leaf,
-                                                           workload.num_q_heads, reserve_tokens, flags)
-        else:
-            self.plan = hkv.hkv_decode_plan_create(pool.handle, f.nodes, f.node_pages, f.req_leaf,
-                                                   workload.num_q_heads, flags)
+        self.plan = hkv.hkv_decode_plan_create_ex(pool.handle, f.nodes, f.node_pages, f.req_leaf,
+                                                  workload.num_q_heads, flags, reserve_tokens=reserve_tokens,
+                                                  **settings)
         self.ws_bytes = hkv.hkv_decode_plan_workspace_bytes(self.plan)
         dev = pool.k.device
         self.ws = torch.empty(max(self.ws_bytes, 256), dtype=torch.uint8, device=dev)

@@ -387,7 +387,7 @@ static void growing_plans(std::mt19937 &rng) {
         // batched append writes: argument checks only (the launchers are stubs here)
         std::vector<int32_t> ids(n_req), slots(n_req);
         for (int r = 0; r < n_req; ++r) {
-            ids[r] = (int32_t)(rng() % 400);
+            ids[r] = (int32_t)((rng() % 7 * n_req + r) % 400);  // distinct pages: one token per block and call
             slots[r] = (int32_t)(rng() % P);
         }
         CHECK(kv_pool_append(pool, ids.data(), slots.data(), n_req, reinterpret_cast<void *>(0x50000), reinterpret_cast<void *>(0x60000),

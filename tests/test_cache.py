@@ -183,6 +183,44 @@ def test_library_cache_matches_oracle(seed, page):
     hkv.kv_pool_destroy(pool)
 
 
+@pytest.mark.parametrize("impl", ["oracle", "library"])
+def test_failed_acquire_leaves_no_block_that_a_later_call_could_hit(impl):
+    """A call that runs out of pages had already entered its first new blocks; they never held KV.  After it
+    fails and room is made, the same prompt must come back with nothing cached (and stats as if the failed
+    call had not happened), while the hits the failed call took are released again."""
+    if impl == "oracle":
+        c = OC.PrefixCache(4)
+        acquire, release = c.acquire, c.release
+        stats = lambda: (c.hits, c.misses, c.num_cached_blocks(), len(c.free))
+        err = MemoryError
+    else:
+        pool = fake_pool(4, 2)
+        cache = hkv.kv_cache_create(pool)
+        acquire = lambda t: hkv.kv_cache_acquire(cache, t)
+        release = lambda p: hkv.kv_cache_release(cache, p)
+
+        def stats():
+            st = hkv.kv_cache_stats(cache)
+            return st["hits"], st["misses"], st["cached_blocks"], hkv.kv_pool_num_free(pool)
+        err = hkv.HkvError
+    a = [1] * 16 + [2] * 24                   # 2 full blocks + a private one: 3 of 4 pages
+    pa, _ = acquire(a)
+    before = stats()
+    b = [1] * 16 + [3] * 48                   # hits a's first block, then needs 3 pages: 1 free, nothing evictable
+    with pytest.raises(err):
+        acquire(b)
+    assert stats() == before
+    release(pa)                               # a's blocks become evictable; its private page is free again
+    pb, cached = acquire(b)
+    assert cached == 16 and pb[0] == pa[0] and len(pb) == 4, "only the block a had filled may count as cached"
+    release(pb)
+    pc, cached = acquire([1] * 16 + [3] * 48)
+    assert cached == 64 and list(pc) == list(pb)
+    if impl == "library":
+        hkv.kv_cache_destroy(cache)
+        hkv.kv_pool_destroy(pool)
+
+
 def test_library_cache_errors():
     pool = fake_pool(4, 2)
     cache = hkv.kv_cache_create(pool)
@@ -191,10 +229,11 @@ def test_library_cache_errors():
     with pytest.raises(hkv.HkvError) as e:
         hkv.kv_cache_acquire(cache, [2] * 40)            # 3 more pages, 1 free, nothing evictable
     assert e.value.code == hkv.ENOMEM
-    # the failed call holds nothing: the one block it had created stays cached but unreferenced, so the
-    # next caller can have its page
+    # the failed call holds nothing and leaves nothing: the block it had created is gone again, its page free
+    st = hkv.kv_cache_stats(cache)
+    assert (st["cached_blocks"], st["misses"], st["evictions"]) == (2, 2, 0) and hkv.kv_pool_num_free(pool) == 1
     extra, _ = hkv.kv_cache_acquire(cache, [3] * 16)
-    assert hkv.kv_cache_stats(cache)["evictions"] == 1
+    assert hkv.kv_cache_stats(cache)["evictions"] == 0
     hkv.kv_cache_release(cache, extra)
     with pytest.raises(hkv.HkvError) as e:
         hkv.kv_cache_release(cache, extra)               # released twice

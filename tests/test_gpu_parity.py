@@ -293,6 +293,35 @@ def test_lse_merge_dense_kernel(gpu, oracle, max_parts):
 
 # ------------------------------------------------------------------------------ decode
 
+def plan_settings(monkeypatch, flags=0, **settings):
+    """Until the test ends, the binding's plan creators build their plans through hkv_decode_plan_create_ex
+    with these flags and planner settings added (how a test reaches a particular path at a small size)."""
+    from paper_2603_16104_amd import binding as hkv
+    ex = hkv.hkv_decode_plan_create_ex
+
+    def create(pool, nodes, node_pages, req_leaf, num_q_heads, fl=0):
+        return ex(pool, nodes, node_pages, req_leaf, num_q_heads, fl | flags, **settings)
+
+    def growing(pool, nodes, node_pages, req_leaf, num_q_heads, reserve_tokens, fl=0):
+        return ex(pool, nodes, node_pages, req_leaf, num_q_heads, fl | flags, reserve_tokens=reserve_tokens, **settings)
+
+    def multi(pool, nodes, node_pages, req_leaf, tokens_per_req, num_q_heads, fl=0):
+        return ex(pool, nodes, node_pages, req_leaf, num_q_heads, fl | flags, tokens_per_req=tokens_per_req, **settings)
+
+    def tree(pool, nodes, node_pages, req_leaf, tokens_per_req, visible, num_q_heads, fl=0):
+        return ex(pool, nodes, node_pages, req_leaf, num_q_heads, fl | flags, visible=visible,
+                  tokens_per_req=tokens_per_req, **settings)
+
+    def create_ex(pool, nodes, node_pages, req_leaf, num_q_heads, fl=0, visible=None, **more):
+        return ex(pool, nodes, node_pages, req_leaf, num_q_heads, fl | flags, visible=visible, **{**settings, **more})
+
+    monkeypatch.setattr(hkv, "hkv_decode_plan_create", create)
+    monkeypatch.setattr(hkv, "hkv_decode_plan_create_growing", growing)
+    monkeypatch.setattr(hkv, "hkv_decode_plan_create_multi", multi)
+    monkeypatch.setattr(hkv, "hkv_decode_plan_create_tree", tree)
+    monkeypatch.setattr(hkv, "hkv_decode_plan_create_ex", create_ex)
+
+
 def run_decode(gpu, oracle, w, one_shot=False):
     import torch
     from paper_2603_16104_amd import binding as hkv
@@ -857,7 +886,7 @@ def test_decode_several_query_tokens(gpu, oracle, kv_dtype, T):
 def test_decode_several_query_tokens_chunk_without_visible_token(gpu, oracle, monkeypatch):
     """16 query tokens over a 40-token leaf cut into chunks of 32 and 8 tokens: the first queries see
     nothing of the second chunk and must deliver the empty partial there (no NaN)."""
-    monkeypatch.setenv("HKV_DECODE_LEAF_CHUNK", "32")
+    plan_settings(monkeypatch, leaf_chunk=32)
     w = _multi_forest(wl.KV_BF16, 4, 4, [40, 16], [1, 2])
     run_decode_multi(gpu, oracle, w, 16)
 
@@ -875,7 +904,7 @@ def test_decode_short_items_four_to_a_workgroup(gpu, oracle, kv_dtype, monkeypat
     forests with ragged and empty nodes and item counts that are no multiple of four, a deep chain, many
     requests under one node, and several query tokens per request (causal limits inside packed items)."""
     from paper_2603_16104_amd import binding as hkv
-    monkeypatch.setenv("HKV_DECODE_PACK", "3")
+    plan_settings(monkeypatch, pack=3)
     for seed in (51, 52, 53, 54):
         hq, hk = [(8, 2), (8, 1), (4, 4), (16, 1)][seed % 4]
         w = wl.random_forest_workload(seed, kv_dtype=kv_dtype, num_q_heads=hq, num_kv_heads=hk, depth=4, fanout=3,
@@ -1252,8 +1281,10 @@ def test_larger_pages_copy_on_write(gpu, oracle, kv_dtype):
 
 @pytest.fixture
 def fp8_matrix(monkeypatch):
-    """Every decode plan over an fp8 pool built while this is active takes the HKV_PLAN_FP8_MATRIX path."""
-    monkeypatch.setenv("HKV_FP8_MATRIX", "1")
+    """Every decode plan that the binding's creators build while this is active carries HKV_PLAN_FP8_MATRIX
+    (the one-shot call takes no flags and stays on the default path)."""
+    from paper_2603_16104_amd import binding as hkv
+    plan_settings(monkeypatch, flags=hkv.PLAN_FP8_MATRIX)
 
 
 @pytest.mark.parametrize("seed", [51, 52, 53, 54])
@@ -1262,7 +1293,6 @@ def test_fp8_matrix_variant_random_forests(gpu, oracle, seed, fp8_matrix):
     w = wl.random_forest_workload(seed, kv_dtype=wl.KV_FP8_E4M3, num_q_heads=hq, num_kv_heads=hkv_, depth=4, fanout=3,
                                   max_node_pages=9, n_roots=2)
     run_decode(gpu, oracle, w)
-    run_decode(gpu, oracle, w, one_shot=True)
 
 
 def test_fp8_matrix_variant_by_plan_flag(gpu, oracle):
@@ -1310,7 +1340,7 @@ def test_fp8_matrix_variant_block_scales_far_apart(gpu, oracle, n_large, log2_ra
     wavefront walks the whole item, so the reference has to move down within it."""
     import torch
     from paper_2603_16104_amd import binding as hkv
-    monkeypatch.setenv("HKV_DECODE_PACK", "3")
+    plan_settings(monkeypatch, pack=3)
     H, Hq, T = 2, 8, 640
     rng = np.random.default_rng(7)
     q = rng.standard_normal((1, Hq, 128)).astype(np.float32)
@@ -1343,6 +1373,38 @@ def test_fp8_matrix_variant_block_scales_far_apart(gpu, oracle, n_large, log2_ra
 
 # ------------------------------------------------------------------------------ decode loop: append, grow, run
 
+@pytest.mark.parametrize("kv_dtype", [wl.KV_BF16, wl.KV_FP8_E4M3])
+@pytest.mark.parametrize("page_size", [16, 64])
+def test_pool_append_of_a_batch_beyond_256_sequences(gpu, oracle, kv_dtype, page_size):
+    """300 sequences each store one token per call: such a batch does not fit a kernel's arguments, so ids and
+    slots travel through the pool's pinned staging buffers.  16 or 20 calls in a row (more than the staging ring
+    holds), every sequence from the first slot of a 16-token block on (with 64-token pages across a block
+    boundary), growing magnitudes so that fp8 scales rise; pool bytes and fp8 scales equal the oracle's."""
+    import torch
+    from paper_2603_16104_amd import binding as hkv
+    n, H, P = 300, 2, page_size
+    hp = oracle.HostPool(n, H, oracle.FP8_E4M3 if kv_dtype == wl.KV_FP8_E4M3 else oracle.BF16, page_size=P)
+    dp = gpu.DevicePool(n, H, kv_dtype, page_size=P)
+    pages = np.random.default_rng(3).permutation(n).astype(np.int32)
+    rng = np.random.default_rng(8)
+    start = 16 * rng.integers(0, max(1, P // 16 - 1), n)
+    for step in range(16 if P == 16 else 20):
+        k = wl.f32_to_bf16_bits(((1 + 0.3 * step) * rng.standard_normal((n, H, 128))).astype(np.float32))
+        v = wl.f32_to_bf16_bits(rng.standard_normal((n, H, 128)).astype(np.float32))
+        slots = (start + step).astype(np.int32)
+        for i in range(n):
+            hp.write([pages[i]], int(slots[i]), k[i:i + 1], v[i:i + 1])
+        hkv.kv_pool_append(dp.handle, pages, slots, gpu.to_device_bits(k), gpu.to_device_bits(v))
+    torch.cuda.synchronize()
+    # compare what the calls wrote: the tokens' bytes (other slots of a block are uninitialised on both sides)
+    assert np.array_equal(dp.k.cpu().numpy().view(np.uint8), hp.k.view(np.uint8))
+    assert np.array_equal(dp.v.cpu().numpy().view(np.uint8), hp.v.view(np.uint8))
+    if kv_dtype == wl.KV_FP8_E4M3:
+        for name in ("k_scale", "v_scale"):
+            assert np.array_equal(getattr(dp, name).cpu().numpy().view(np.uint32).ravel(), getattr(hp, name).view(np.uint32).ravel()), name
+    dp.close()
+
+
 @pytest.mark.parametrize("page_size,inline,fused", [(16, True, False), (64, True, False), (16, False, False), (32, False, False),
                                                     (16, True, True), (64, True, True), (32, False, True)])
 @pytest.mark.parametrize("kv_dtype", [wl.KV_BF16, wl.KV_FP8_E4M3])
@@ -1354,8 +1416,7 @@ def test_decode_loop_with_a_growing_plan(gpu, oracle, kv_dtype, page_size, inlin
     import torch
     from paper_2603_16104_amd import binding as hkv
     if not inline:      # the paths of batches beyond 256 requests: ids and work list through pinned staging buffers
-        monkeypatch.setenv("HKV_GROW_INLINE", "0")
-        monkeypatch.setenv("HKV_APPEND_INLINE", "0")
+        plan_settings(monkeypatch, large_batch_updates=1)
     H, Hq, P = 2, 8, page_size
     parent = [-1, 0, 0, 1, 1, 2]
     ntok = [3 * P, 2 * P, P, 5, P - 1, 2 * P]                     # leaves 3, 4, 5 of requests 0, 1, 2

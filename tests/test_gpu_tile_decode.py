@@ -6,14 +6,14 @@ import numpy as np
 import pytest
 
 from paper_2603_16104_amd import workloads as wl
-from test_gpu_parity import check_close, check_lse, both_pools, gpu, _FixedWorkload  # noqa: F401  (gpu is a fixture)
+from test_gpu_parity import check_close, check_lse, both_pools, gpu, plan_settings, _FixedWorkload  # noqa: F401  (gpu is a fixture)
 
 pytestmark = pytest.mark.gpu
 
 
 @pytest.fixture
 def tiles_on(monkeypatch):
-    monkeypatch.setenv("HKV_DECODE_TILE_GFLOP", "0")
+    plan_settings(monkeypatch, tile_min_gflop=-1)
 
 
 def shared_root_workload(seed, hq, hkv_, n_req, root_tokens, kv_dtype, mid_tokens=0):
@@ -79,7 +79,7 @@ def test_tile_decode_shared_root(gpu, oracle, tiles_on, kv_dtype, hq, hkv_, n_re
 def test_tile_decode_chunks_and_two_shared_levels(gpu, oracle, tiles_on, monkeypatch, kv_dtype, chunk):
     """A 2100-token root and a 330-token node below it, both shared by 48 requests x 4 heads: several chunks per
     node (the last one ragged), partial slots of two tiled nodes and of the private leaves in one merge."""
-    monkeypatch.setenv("HKV_DECODE_TILE_CHUNK", str(chunk))
+    plan_settings(monkeypatch, tile_chunk=chunk)
     w = shared_root_workload(12, 8, 2, 48, 2100, kv_dtype, mid_tokens=330)
     run_tiled(gpu, oracle, w)
 

@@ -345,17 +345,17 @@ def test_decode_plan_sizes_of_benchmark_configs(oracle):
     assert (small[small[:, 4] == 1][:, 1] >= 256).all() and len(small) < 768
 
 
-def test_many_row_and_few_row_items_are_dispatched_side_by_side(monkeypatch):
+def test_many_row_and_few_row_items_are_dispatched_side_by_side():
     """c5: 2048 items of the shared roots (64 query rows each) and 4096 items of the private leaves (8 rows, too
     long for the four-to-a-workgroup mode).  Both classes are spread evenly over the work list, heavy before
-    light within a class; the development knob restores one class after the other; the items are the same."""
+    light within a class; the planner setting `interleave` restores one class after the other; the items are the same."""
     w = wl.config5()
     f = w.forest
     pool = fake_pool(w.num_pages, w.num_kv_heads, dtype=hkv.FP8_E4M3)
-    monkeypatch.setenv("HKV_DECODE_TILE_GFLOP", "1000000")     # keep the roots out of the 256-row tile kernel here
 
-    def items_of():
-        plan = hkv.hkv_decode_plan_create(pool, f.nodes, f.node_pages, f.req_leaf, w.num_q_heads, hkv.PLAN_HOST_ONLY)
+    def items_of(**settings):      # tile_min_gflop: keeps the roots out of the 256-row tile kernel here
+        plan = hkv.hkv_decode_plan_create_ex(pool, f.nodes, f.node_pages, f.req_leaf, w.num_q_heads, hkv.PLAN_HOST_ONLY,
+                                             tile_min_gflop=1000000, **settings)
         it = hkv.hkv_decode_plan_items(plan).copy()
         assert hkv.hkv_decode_plan_num_workgroups(plan) == len(it)
         hkv.hkv_decode_plan_destroy(plan)
@@ -370,8 +370,7 @@ def test_many_row_and_few_row_items_are_dispatched_side_by_side(monkeypatch):
     for cls in (many, ~many):
         cost = mixed[cls, 1].astype(np.int64)
         assert (np.diff(cost) <= 0).all()
-    monkeypatch.setenv("HKV_DECODE_INTERLEAVE", "0")
-    apart = items_of()
+    apart = items_of(interleave=-1)
     many_apart = apart[:, 4] * (w.num_q_heads // w.num_kv_heads) > 16
     assert many_apart[:2048].all() and not many_apart[2048:].any()
     assert sorted(map(tuple, mixed.tolist())) == sorted(map(tuple, apart.tolist()))
@@ -408,6 +407,47 @@ def test_large_many_row_share_goes_to_the_tile_kernel(oracle):
         assert hkv.hkv_decode_plan_num_tile_items(plan) == 0 and hkv.hkv_decode_plan_tile_workgroups(plan) == 0
         hkv.hkv_decode_plan_destroy(plan)
         hkv.kv_pool_destroy(sp)
+
+
+def test_decode_plan_create_ex_equals_the_four_creators_and_checks_its_settings():
+    """With NULL settings the call plans as hkv_decode_plan_create; tokens_per_req, visible and reserve_tokens
+    select the other three creators' plans (same items); a setting outside its range is EINVAL and names the field;
+    settings change the cut into items, never the coverage."""
+    w = wl.config2(n_req=12)
+    f = w.forest
+    pool = fake_pool(w.num_pages, w.num_kv_heads)
+    args = (pool, f.nodes, f.node_pages, f.req_leaf)
+
+    def items(plan):
+        it = hkv.hkv_decode_plan_items(plan).copy()
+        hkv.hkv_decode_plan_destroy(plan)
+        return it
+
+    H = hkv.PLAN_HOST_ONLY
+    assert (items(hkv.hkv_decode_plan_create(*args, w.num_q_heads, H)) == items(hkv.hkv_decode_plan_create_ex(*args, w.num_q_heads, H))).all()
+    assert (items(hkv.hkv_decode_plan_create_multi(*args, 3, w.num_q_heads, H)) ==
+            items(hkv.hkv_decode_plan_create_ex(*args, w.num_q_heads, H, tokens_per_req=3))).all()
+    vis = np.tile(np.array([1, 3, 5], dtype=np.uint64), f.n_req)
+    assert (items(hkv.hkv_decode_plan_create_tree(*args, 3, vis, w.num_q_heads, H)) ==
+            items(hkv.hkv_decode_plan_create_ex(*args, w.num_q_heads, H, tokens_per_req=3, visible=vis))).all()
+    assert (items(hkv.hkv_decode_plan_create_growing(*args, w.num_q_heads, 40, H)) ==
+            items(hkv.hkv_decode_plan_create_ex(*args, w.num_q_heads, H, reserve_tokens=40))).all()
+    base = items(hkv.hkv_decode_plan_create_ex(*args, w.num_q_heads, H))
+    cut = items(hkv.hkv_decode_plan_create_ex(*args, w.num_q_heads, H, leaf_chunk=64, shared_chunk=128, max_rows=32))
+    assert len(cut) > len(base) and cut[:, 1].sum() * 1 >= base[:, 1].sum()
+    bad = [dict(leaf_chunk=24), dict(shared_chunk=4096), dict(max_rows=8), dict(max_rows=128), dict(pack=4), dict(stages=2),
+           dict(stages=6), dict(interleave=-2), dict(tile_min_rows=64), dict(tile_chunk=40), dict(tile_chunk=4096),
+           dict(tile_workgroups=-1), dict(large_batch_updates=2), dict(tokens_per_req=17), dict(tokens_per_req=65, visible=np.zeros(65 * f.n_req, dtype=np.uint64)),
+           dict(reserve_tokens=-1), dict(reserve_tokens=8, tokens_per_req=2)]
+    for kw in bad:
+        with pytest.raises(hkv.HkvError) as e:
+            hkv.hkv_decode_plan_create_ex(*args, w.num_q_heads, H, **kw)
+        assert e.value.code == hkv.EINVAL, (kw, str(e.value))
+        name = next(k for k in kw if k != "visible")
+        assert name in str(e.value) or "query tokens" in str(e.value) or "growing" in str(e.value), str(e.value)
+    with pytest.raises(TypeError):
+        hkv.hkv_decode_plan_create_ex(*args, w.num_q_heads, H, no_such_setting=1)
+    hkv.kv_pool_destroy(pool)
 
 
 def test_decode_plan_error_codes():
@@ -777,8 +817,22 @@ def test_growing_plan_argument_checks():
         hkv.kv_pool_append(p32, [1], [0], 0x50000, 0x60000, stream=0)
     assert e.value.code == hkv.ESHAPE
     hkv.kv_pool_append(pool, [], [], None, None, stream=0)
+    for ids, slots in (([1, 2, 1], [3, 0, 4]), ([5, 5], [0, 15])):     # two tokens into one 16-token block
+        with pytest.raises(hkv.HkvError) as e:
+            hkv.kv_pool_append(pool, ids, slots, 0x50000, 0x60000, stream=0)
+        assert e.value.code == hkv.EINVAL and "two tokens" in str(e.value)
+    got = hkv.kv_pool_alloc(pool, 2)
+    hkv.kv_pool_retain(pool, got[:1])                                   # first page now has two owners
+    with pytest.raises(hkv.HkvError) as e:
+        hkv.kv_pool_append(pool, got, [0, 0], 0x50000, 0x60000, stream=0)
+    assert e.value.code == hkv.EINVAL and "owners" in str(e.value) and f"page {got[0]}" in str(e.value)
+    p64 = fake_pool(8, 2, page_size=64)                                 # 64-token pages: blocks 0 and 1 of page 3 differ
+    with pytest.raises(hkv.HkvError) as e:
+        hkv.kv_pool_append(p64, [3, 3, 3], [1, 17, 30], 0x50000, 0x60000, stream=0)
+    assert e.value.code == hkv.EINVAL and "block 1 of page 3" in str(e.value)
     hkv.kv_pool_destroy(pool)
     hkv.kv_pool_destroy(p32)
+    hkv.kv_pool_destroy(p64)
 
 
 def test_bench_refuses_more_than_one_gpu():
