@@ -532,6 +532,26 @@ int oracle_attn_prefill(const orc_pool *p, const void *q, int32_t q_dtype, const
     return 0;
 }
 
+/* The keys and values of one sequence, read through its page list and widened to double (fp8: code value
+ * times the block's scale): k_out, v_out [kv_len][Hkv][128].  For the matrix form of the attention in
+ * oracle.py, which needs the operands as arrays. */
+int oracle_gather_kv(const orc_pool *p, const int32_t *pages, int32_t kv_len, double *k_out, double *v_out) {
+    if (kv_len < 0) return -1;
+    int rc = check_pages(p, pages, kv_len);
+    if (rc) return rc;
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < kv_len; ++t) {
+        int page = pages[t / p->page_size], slot = t % p->page_size;
+        for (int h = 0; h < p->num_kv_heads; ++h)
+            for (int d = 0; d < ORC_D; ++d) {
+                size_t o = ((size_t)t * p->num_kv_heads + h) * ORC_D + d;
+                k_out[o] = load_k(p, page, h, slot, d);
+                v_out[o] = load_v(p, page, h, slot, d);
+            }
+    }
+    return 0;
+}
+
 /* Normalised attention weights p_t / l of one (request, q-head) over its whole sequence;
  * exposed so that tests can check the softmax itself. */
 int oracle_attn_probs(const orc_pool *p, const void *q, int32_t q_dtype, const int32_t *pages, int32_t kv_len,

@@ -226,6 +226,71 @@ def attn_prefill(pool: HostPool, q: np.ndarray, cu_q, block_table, kv_len, scale
     return out, lse
 
 
+def gather_kv(pool: HostPool, pages, kv_len: int):
+    """K and V of one sequence as double arrays [kv_len][Hkv][128] (read through the page list)."""
+    pages = _i32(pages)
+    k = np.empty((kv_len, pool.num_kv_heads, D), dtype=np.float64)
+    v = np.empty_like(k)
+    pc = pool._c()
+    rc = lib().oracle_gather_kv(C.byref(pc), _p(pages), C.c_int32(kv_len), _p(k), _p(v))
+    if rc:
+        raise ValueError(f"oracle_gather_kv failed: {rc}")
+    return k, v
+
+
+def _q_as_double(q: np.ndarray) -> np.ndarray:
+    if q.dtype == np.uint16:       # bf16 bit patterns
+        return (q.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    return q.astype(np.float64)
+
+
+def attn_matrix_form(pool: HostPool, q: np.ndarray, cu_q, block_table, kv_len, scale: float, requests=None,
+                     tokens=None):
+    """Suffix attention of whole requests with matrix products as steps (Section 5: a call computes its
+    uncached suffix against the whole prompt): request r brings s_r = cu_q[r+1] - cu_q[r] query tokens at
+    positions kv_len_r - s_r ..; token i of them sees keys 0 .. kv_len_r - s_r + i.  Per request and KV head
+    S = scale * Q K^T, masked, m = row max, P = exp(S - m), l = row sum, O = P V / l, lse = m + ln l:
+    the same definition as oracle_attn_prefill / oracle_attn_decode (s_r = 1), evaluated for all rows of a
+    request at once, so that complete requests of the large configurations finish in seconds.
+    requests: which requests to compute (default all); tokens: {request: indices of its new tokens to compute}
+    for requests of which only some rows are wanted (default: all of a request's tokens).
+    Returns (out [rows][Hq][128], lse [rows][Hq], rows) with rows = the global q row of every computed row,
+    in order."""
+    cu_q, block_table, kv_len = _i32(cu_q), _i32(block_table), _i32(kv_len)
+    Hq, Hk = q.shape[1], pool.num_kv_heads
+    G = Hq // Hk
+    requests = range(len(kv_len)) if requests is None else requests
+    outs, lses, rows = [], [], []
+    sc = float(np.float32(scale))
+    for r in requests:
+        a, b = int(cu_q[r]), int(cu_q[r + 1])
+        s, T = b - a, int(kv_len[r])
+        which = np.arange(s) if tokens is None or r not in tokens else np.asarray(tokens[r], dtype=np.int64)
+        assert ((which >= 0) & (which < s)).all()
+        k, v = gather_kv(pool, block_table[r], T)
+        qd = _q_as_double(q[a + which])                             # [n][Hq][128]
+        o = np.zeros((len(which), Hq, D))
+        l_ = np.full((len(which), Hq), -np.inf)
+        if T > 0 and len(which):
+            visible = np.arange(T)[None, :] <= (T - s + which)[:, None]             # [n][T]
+            for j in range(Hk):                                     # KV head j serves q heads j*G .. j*G + G - 1
+                kh, vh = np.ascontiguousarray(k[:, j, :]), np.ascontiguousarray(v[:, j, :])     # [T][128]
+                for h in range(j * G, (j + 1) * G):
+                    S = sc * (np.ascontiguousarray(qd[:, h, :]) @ kh.T)     # [n][T]
+                    S[~visible] = -np.inf
+                    m = S.max(axis=1, keepdims=True)
+                    P = np.exp(S - m)
+                    l = P.sum(axis=1, keepdims=True)
+                    o[:, h, :] = (P @ vh) / l
+                    l_[:, h] = (m + np.log(l))[:, 0]
+        outs.append(o)
+        lses.append(l_)
+        rows.append(a + which)
+    if not outs:
+        return np.zeros((0, Hq, D)), np.zeros((0, Hq)), np.zeros(0, dtype=np.int64)
+    return np.concatenate(outs), np.concatenate(lses), np.concatenate(rows)
+
+
 def attn_probs(pool: HostPool, q_row: np.ndarray, pages, kv_len: int, q_head: int, num_q_heads: int, scale: float):
     """q_row: [Hq][128] of one token; returns the softmax weights over the kv_len tokens."""
     q_row, pages = np.ascontiguousarray(q_row), _i32(pages)
@@ -259,9 +324,19 @@ def num_threads() -> int:
     return int(lib().oracle_num_threads())
 
 
+def max_pages_per_request(nodes, req_leaf) -> int:
+    """Pages on the longest root-to-leaf path among the requests (parents come before children)."""
+    nodes, req_leaf = _i32(nodes).reshape(-1, 4), _i32(req_leaf)
+    along = np.zeros(nodes.shape[0], dtype=np.int64)
+    for v in range(nodes.shape[0]):
+        par = int(nodes[v, 0])
+        along[v] = int(nodes[v, 2]) + (along[par] if par >= 0 else 0)
+    return int(along[req_leaf].max()) if len(req_leaf) else 0
+
+
 def flatten_workload(workload):
     f = workload.forest
-    mp = max(1, f.max_pages_per_req())
+    mp = max(1, max_pages_per_request(f.nodes, f.req_leaf))
     return flatten_tree(f.nodes, f.node_pages, f.req_leaf, mp, f.page_size)
 
 

@@ -1,8 +1,8 @@
 """GPU parity at the full sizes of the benchmark configurations, in the launch configuration the
 bench times (plan objects, default work splitting).  Configurations 2 and 3 are compared with the
-oracle element by element; 4 and 5 on sampled outputs the oracle computes one by one (the oracle's
-prefill of a token equals its decode of that token over the keys it may see, which
-tests/test_oracle_pins.py pins)."""
+oracle element by element, and so is every request of configurations 4 and 5 through the oracle's matrix
+form of the definition (which tests/test_oracle_pins.py pins to the row-by-row routine and to brute force;
+some rows go through the row-by-row routine too)."""
 import numpy as np
 import pytest
 
@@ -88,76 +88,127 @@ def test_config3_full(gpu, oracle):
     _decode_full(gpu, oracle, wl.config3())
 
 
-@pytest.mark.timeout(300)
-def test_config4_sampled(gpu, oracle):
+# ---- configurations 4 and 5 at full size: the GPU runs once per module, the oracle checks it in slices (each a
+# test of its own, so that none runs for minutes without a sign of life)
+
+@pytest.fixture(scope="module")
+def c4_run(gpu, oracle):
     import torch
-    from paper_2603_16104_amd import binding as hkv
     w = wl.config4()
     hp, dp = both_pools(gpu, oracle, w)
     r = gpu.PrefillRunner(dp, w)
     r.run()
     torch.cuda.synchronize()
     got_o, got_l = gpu.bf16_tensor_to_f64(r.out), r.lse.cpu().numpy()
-    assert np.isfinite(got_o).all()
-    # indexing outputs bit-exact against the oracle's own tree walk
     obt, okv, *_ = oracle.flatten_workload(w)
+    # indexing outputs bit-exact against the oracle's own tree walk
     assert np.array_equal(r.block_table, obt) and np.array_equal(r.kv_len, okv)
-    rng = np.random.default_rng(4)
-    cu = w.cu_q()
-    q = w.q()
-    rows, qs, bts, lens = [], [], [], []
-    for _ in range(40):
-        req = int(rng.integers(0, w.forest.n_req))
-        s = int(cu[req + 1] - cu[req])
-        i = int(rng.choice([0, 1, 15, 16, 63, 64, s - 1, int(rng.integers(0, s))]))
-        rows.append(cu[req] + i)
-        qs.append(q[cu[req] + i])
-        bts.append(obt[req])
-        lens.append(okv[req] - s + i + 1)
-    exp_o, exp_l = oracle.attn_decode(hp, np.stack(qs), np.stack(bts), np.array(lens, dtype=np.int32), float(w.scale))
-    res = check_close(got_o[rows], exp_o, w.name)
-    check_lse(got_l[rows], exp_l, w.name)
-    print(f"{w.name}: sampled {len(rows)} query tokens x {w.num_q_heads} heads: max_abs {res[0]:.3e} rel_l2 {res[1]:.3e}")
     r.close()
     dp.close()
+    return w, hp, w.q(), obt, okv, got_o, got_l
 
 
-@pytest.mark.timeout(900)
-def test_config5_sampled(gpu, oracle):
-    """fp8 forest: the GPU pool is written by kv_pool_write from the full seeded data; the oracle's pool
-    holds (bit-exactly compared) only the nodes that the sampled requests read."""
+@pytest.mark.timeout(300)
+@pytest.mark.parametrize("part", [0, 1, 2, 3])
+def test_config4_every_request(gpu, oracle, c4_run, part):
+    """Every new token of all 32 requests (eight per test) against the oracle's matrix form of the same
+    definition (pinned to the row-by-row routine and to brute force in tests/test_oracle_pins.py)."""
+    w, hp, q, obt, okv, got_o, got_l = c4_run
+    assert np.isfinite(got_o).all() and np.isfinite(got_l).all()
+    reqs = list(range(part, w.forest.n_req, 4))
+    exp_o, exp_l, rows = oracle.attn_matrix_form(hp, q, w.cu_q(), obt, okv, float(w.scale), requests=reqs)
+    res = check_close(got_o[rows], exp_o, w.name)
+    check_lse(got_l[rows], exp_l, w.name)
+    print(f"{w.name}: requests {reqs}, {len(rows)} query tokens x {w.num_q_heads} heads: max_abs {res[0]:.3e} rel_l2 {res[1]:.3e}")
+
+
+@pytest.mark.timeout(300)
+def test_config4_tile_boundaries_of_every_request(gpu, oracle, c4_run):
+    """The kernel works on tiles of 256 query rows of one KV head = 256 / G consecutive new tokens of a request.
+    First and last token of every such tile of every request (the last tile is ragged), plus tokens drawn at
+    random: a quick check that names the tile when one is dropped, doubled or given the wrong causal limit;
+    a handful of tokens go through the row-by-row C routine as well."""
+    w, hp, q, obt, okv, got_o, got_l = c4_run
+    cu = w.cu_q()
+    tile = 256 // (w.num_q_heads // w.num_kv_heads)
+    rng = np.random.default_rng(4)
+    tokens = {}
+    for r in range(w.forest.n_req):
+        s = int(cu[r + 1] - cu[r])
+        edge = {t for b in range(0, s, tile) for t in (b, min(s, b + tile) - 1)}
+        tokens[r] = sorted(edge | {int(x) for x in rng.integers(0, s, 6)})
+    exp_o, exp_l, rows = oracle.attn_matrix_form(hp, q, cu, obt, okv, float(w.scale), tokens=tokens)
+    res = check_close(got_o[rows], exp_o, w.name)
+    check_lse(got_l[rows], exp_l, w.name)
+    print(f"{w.name}: {len(rows)} tile-boundary and random query tokens of all {w.forest.n_req} requests: max_abs {res[0]:.3e} rel_l2 {res[1]:.3e}")
+    some = rows[rng.integers(0, len(rows), 12)]
+    req = np.searchsorted(cu, some, side="right") - 1
+    lens = okv[req] - (cu[req + 1] - cu[req]) + (some - cu[req]) + 1
+    row_o, row_l = oracle.attn_decode(hp, q[some], obt[req], lens.astype(np.int32), float(w.scale))
+    check_close(got_o[some], row_o, w.name + " (row by row)")
+    check_lse(got_l[some], row_l, w.name + " (row by row)")
+
+
+@pytest.fixture(scope="module")
+def c5_run(gpu, oracle):
+    """The fp8 forest in both pools: every node's seeded K/V is drawn once, quantised by the oracle into its pool
+    and by kv_pool_write into the device pool; bytes and scales of both pools are compared as a whole."""
     import torch
+    from concurrent.futures import ThreadPoolExecutor
     w = wl.config5()
     f = w.forest
+    hp = oracle.HostPool(w.num_pages, w.num_kv_heads, w.kv_dtype)
     dp = gpu.DevicePool(w.num_pages, w.num_kv_heads, w.kv_dtype)
-    dp.fill_from(w)
-    print("c5: device pool filled", flush=True)
+
+    def host_side(v):       # nodes own disjoint pages: their writes into the oracle's pool do not meet
+        k, vv = w.node_kv(v)
+        hp.write(f.node_pages[f.page_begin[v]: f.page_begin[v] + f.n_pages[v]], 0, k, vv)
+        return v, k, vv
+
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        for v, k, vv in ex.map(host_side, [v for v in range(f.n_nodes) if f.n_tokens[v] > 0]):
+            dp.write(f.node_pages[f.page_begin[v]: f.page_begin[v] + f.n_pages[v]], 0, gpu.to_device_bits(k), gpu.to_device_bits(vv))
+    torch.cuda.synchronize()
+    print("c5: both pools filled", flush=True)
+    used = np.sort(f.node_pages)
+    for name, per_page in (("k", 16 * 128 * w.num_kv_heads), ("v", 16 * 128 * w.num_kv_heads),
+                           ("k_scale", w.num_kv_heads), ("v_scale", w.num_kv_heads)):
+        g = getattr(dp, name).cpu().numpy().reshape(w.num_pages, per_page)[used]
+        o = getattr(hp, name).reshape(w.num_pages, per_page)[used]
+        assert np.array_equal(g.view(np.uint8), o.view(np.uint8)), f"{name}: the pools differ"
     r = gpu.DecodeRunner(dp, w)
     r.run()
     torch.cuda.synchronize()
     got_o, got_l = gpu.bf16_tensor_to_f64(r.out), r.lse.cpu().numpy()
-    assert np.isfinite(got_o).all() and np.isfinite(got_l).all()
-    sample = [0, 1, 31, 32, 200, 511]
-    hp = oracle.HostPool(w.num_pages, w.num_kv_heads, w.kv_dtype)
-    nodes = sorted({v for req in sample for v in f.path(int(f.req_leaf[req]))})
-    for v in nodes:
-        k, vv = w.node_kv(v)
-        pages = f.node_pages[f.page_begin[v]: f.page_begin[v] + f.n_pages[v]]
-        hp.write(pages, 0, k, vv)
-        # the bytes the GPU quantised for these pages equal the oracle's
-        idx = torch.from_numpy(pages.astype(np.int64)).cuda()
-        for name, per_page in (("k", 16 * 128 * w.num_kv_heads), ("v", 16 * 128 * w.num_kv_heads),
-                               ("k_scale", w.num_kv_heads), ("v_scale", w.num_kv_heads)):
-            g = getattr(dp, name).view(w.num_pages, per_page)[idx].cpu().numpy()
-            o = getattr(hp, name).reshape(w.num_pages, per_page)[pages]
-            assert np.array_equal(g.view(np.uint8), o.view(np.uint8)), f"{name} of node {v}"
-    print("c5: oracle pool filled for the sample", flush=True)
-    exp_o, exp_l = oracle.run_workload(w, hp, req_subset=sample)
-    res = check_close(got_o[sample], exp_o, w.name)
-    check_lse(got_l[sample], exp_l, w.name)
-    print(f"{w.name}: sampled {len(sample)} requests x {w.num_q_heads} heads: max_abs {res[0]:.3e} rel_l2 {res[1]:.3e}")
+    first = r.out.clone()
+    r.run()
+    torch.cuda.synchronize()
+    assert torch.equal(first, r.out)
     r.close()
     dp.close()
+    bt, kv_len, *_ = oracle.flatten_workload(w)
+    return w, hp, w.q(), bt, kv_len, got_o, got_l
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("part", [0, 1, 2, 3])
+def test_config5_every_request(gpu, oracle, c5_run, part):
+    """All 512 requests of the fp8 forest (every root, every row of every 256-row tile of the shared nodes, every
+    private leaf), 128 per test, element by element against the oracle's matrix form over the oracle's own pool;
+    eight of them through the row-by-row C routine as well."""
+    w, hp, q, bt, kv_len, got_o, got_l = c5_run
+    assert np.isfinite(got_o).all() and np.isfinite(got_l).all()
+    reqs = list(range(part, w.forest.n_req, 4))        # every root has requests in every part
+    cu = np.arange(w.forest.n_req + 1, dtype=np.int32)
+    exp_o, exp_l, rows = oracle.attn_matrix_form(hp, q, cu, bt, kv_len, float(w.scale), requests=reqs)
+    assert np.array_equal(rows, reqs)
+    res = check_close(got_o[rows], exp_o, w.name)
+    check_lse(got_l[rows], exp_l, w.name)
+    print(f"{w.name}: {len(reqs)} requests x {w.num_q_heads} heads: max_abs {res[0]:.3e} rel_l2 {res[1]:.3e}")
+    some = reqs[::16]
+    row_o, row_l = oracle.run_workload(w, hp, req_subset=some)
+    check_close(got_o[some], row_o, w.name + " (row by row)")
+    check_lse(got_l[some], row_l, w.name + " (row by row)")
 
 
 @pytest.mark.timeout(600)

@@ -129,6 +129,63 @@ def test_library_sdpa_float64(oracle):
         assert np.abs(ref.permute(1, 0, 2).numpy() - out[cu[r]:cu[r + 1]]).max() <= 1e-12
 
 
+@pytest.mark.parametrize("seed,mode,kv", [(1, "decode", "bf16"), (3, "prefill", "bf16"), (4, "prefill", "fp8"),
+                                          (2, "decode", "fp8"), (7, "prefill", "fp32")])
+def test_matrix_form_against_brute_force_and_row_form(oracle, seed, mode, kv):
+    """attn_matrix_form (whole requests through matrix products) against the brute force on K/V built from the
+    node tensors, never touching a pool (bf16 / fp32 pools store them exactly), and against the row-by-row C
+    routine over the same pool (all pool types): ragged forests, empty nodes, requests with 0, 1 and several
+    new tokens.  A transposed operand, a mask shifted by one or a wrong head group fails either."""
+    kv_dtype = {"bf16": wl.KV_BF16, "fp8": wl.KV_FP8_E4M3, "fp32": wl.KV_FP32}[kv]
+    w = wl.random_forest_workload(seed, mode=mode, max_node_pages=3, depth=3, fanout=2, kv_dtype=kv_dtype,
+                                  src_dtype="fp32" if kv == "fp32" else "bf16")
+    pool = oracle_pool(oracle, w)
+    bt, kv_len, *_ = oracle.flatten_workload(w)
+    out, lse, rows = oracle.attn_matrix_form(pool, w.q(), w.cu_q(), bt, kv_len, float(w.scale))
+    assert np.array_equal(rows, np.arange(w.total_q()))
+    rout, rlse = oracle.run_workload(w, pool)
+    fin = np.isfinite(rlse)
+    assert np.array_equal(np.isfinite(lse), fin)
+    assert np.abs(out - rout).max() <= 1e-12 and np.abs(lse[fin] - rlse[fin]).max() <= 1e-12
+    if kv != "fp8":
+        bout, blse = brute_workload(w)
+        assert np.abs(out - bout).max() <= 1e-12 and np.abs(lse[fin] - blse[fin]).max() <= 1e-12
+    # a subset of requests: the same rows, in the order asked for
+    if w.forest.n_req >= 2:
+        sub = [w.forest.n_req - 1, 0]
+        so, sl, srows = oracle.attn_matrix_form(pool, w.q(), w.cu_q(), bt, kv_len, float(w.scale), requests=sub)
+        assert np.abs(so - out[srows]).max() <= 1e-12 and np.array_equal(np.isfinite(sl), np.isfinite(lse[srows]))
+        cu = w.cu_q()
+        assert np.array_equal(srows, np.concatenate([np.arange(cu[r], cu[r + 1]) for r in sub]))
+    # some tokens of a request only
+    cu = w.cu_q()
+    big = int(np.argmax(np.diff(cu)))
+    n_new = int(cu[big + 1] - cu[big])
+    pick = sorted({0, n_new - 1, n_new // 2})
+    to, tl, trows = oracle.attn_matrix_form(pool, w.q(), w.cu_q(), bt, kv_len, float(w.scale), requests=[big],
+                                            tokens={big: pick})
+    assert np.array_equal(trows, cu[big] + np.array(pick))
+    assert np.abs(to - out[trows]).max() <= 1e-12 and np.abs(tl - lse[trows]).max() <= 1e-12
+
+
+def test_matrix_form_closed_form_running_mean(oracle):
+    """Equal keys give equal scores, so new token i returns the mean of the values it may see: with
+    V_t = t in every dimension and a prefix of p tokens, out_i = (p + i) / 2 and lse_i = s0 + ln(p + i + 1)."""
+    T, s, H = 45, 7, 2
+    K = np.ones((T, H, D), dtype=np.float32)
+    V = np.broadcast_to(np.arange(T, dtype=np.float32)[:, None, None], (T, H, D)).copy()
+    pool = oracle.HostPool(3, H, oracle.FP32)
+    pages = np.array([2, 0, 1], dtype=np.int32)
+    pool.write(pages, 0, K, V)
+    q = np.full((s, 4, D), 0.25, dtype=np.float32)
+    scale = 0.5
+    out, lse, _ = oracle.attn_matrix_form(pool, q, [0, s], pages[None, :], [T], scale)
+    p = T - s
+    for i in range(s):
+        assert np.abs(out[i] - (p + i) / 2).max() <= 1e-12
+        assert np.abs(lse[i] - (scale * 0.25 * D + math.log(p + i + 1))).max() <= 1e-12
+
+
 # ------------------------------------------------------------------ invariants
 
 def test_page_permutation_invariance(oracle):
