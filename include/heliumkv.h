@@ -340,6 +340,11 @@ typedef struct {
     int32_t tokens_per_req;   /* query tokens per request, 1..64 (beyond 16 only with `visible`); 0 = 1 */
     const uint64_t *visible;  /* host [n_req * tokens_per_req]: as hkv_decode_plan_create_tree; NULL = causal run */
     int32_t reserve_tokens;   /* > 0: a growing plan, as hkv_decode_plan_create_growing */
+    const int32_t *q_rows;    /* host [n_req * tokens_per_req] or NULL: row i of the plan (request i / T, token i % T)
+                                 reads row q_rows[i] of q and writes row q_rows[i] of out and lse_out, so that a
+                                 step's decode rows may lie anywhere among the rows of other work (a mixed
+                                 step).  Entries >= 0 and all different (EINVAL); bf16 and fp8 pools (ESHAPE
+                                 for fp32 pools).  NULL: row i */
     /* ---- planner settings */
     int32_t leaf_chunk;       /* tokens per item of nodes read by at most 16 query rows; multiple of 16 */
     int32_t shared_chunk;     /* tokens per item of nodes shared by more rows; multiple of 16, at most 2048 */
@@ -457,6 +462,14 @@ size_t attn_decode_workspace_bytes(hkv_pool *pool, const hkv_node *nodes, int32_
 int hkv_prefill_plan_create(hkv_pool *pool, const int32_t *cu_q, const int32_t *block_table, int32_t max_pages,
                             const int32_t *kv_len, int32_t n_req, int32_t num_q_heads, uint32_t flags,
                             hkv_prefill_plan **out);
+/* The same for a step that mixes prefill with other work in one q / out / lse (Section 6, engine integration:
+ * chunks of prompts run next to decode steps): request r's q_len[r] new tokens are rows q_row_begin[r] ..
+ * q_row_begin[r] + q_len[r] - 1 of q, out and lse_out; rows no request names are neither read nor written.
+ * q_row_begin, q_len: host [n_req], >= 0; EINVAL if two requests share a row.  bf16 and fp8 pools
+ * (ESHAPE for fp32 pools).  Everything else as hkv_prefill_plan_create. */
+int hkv_prefill_plan_create_rows(hkv_pool *pool, const int32_t *q_row_begin, const int32_t *q_len,
+                                 const int32_t *block_table, int32_t max_pages, const int32_t *kv_len, int32_t n_req,
+                                 int32_t num_q_heads, uint32_t flags, hkv_prefill_plan **out);
 int hkv_prefill_plan_destroy(hkv_prefill_plan *plan);
 /* Number of (request, query tile, kv head) workgroups the plan launches. */
 int32_t hkv_prefill_plan_num_tiles(const hkv_prefill_plan *plan);

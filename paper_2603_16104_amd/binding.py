@@ -27,7 +27,7 @@ EXPORTS = [
     "kv_pool_num_free", "kv_pool_page_size", "kv_pool_refcount", "kv_pool_write", "kv_pool_append", "prefix_tree_flatten",
     "hkv_decode_plan_create_growing", "hkv_decode_plan_append", "hkv_decode_plan_append_tokens",
     "prefix_tree_flatten_paged", "prefix_tree_prefill_usage",
-    "lse_merge", "hkv_decode_plan_create", "hkv_decode_plan_create_multi", "hkv_decode_plan_create_tree", "hkv_decode_plan_create_ex", "hkv_decode_plan_destroy", "hkv_decode_plan_workspace_bytes",
+    "lse_merge", "hkv_decode_plan_create", "hkv_decode_plan_create_multi", "hkv_decode_plan_create_tree", "hkv_decode_plan_create_ex", "hkv_prefill_plan_create_rows", "hkv_decode_plan_destroy", "hkv_decode_plan_workspace_bytes",
     "hkv_decode_plan_num_items", "hkv_decode_plan_num_workgroups", "hkv_decode_plan_num_parts", "hkv_decode_plan_items",
     "hkv_decode_plan_max_parts", "hkv_decode_plan_part_counts", "lse_merge_dense", "attn_decode_plan_run",
     "attn_decode_plan_run_static", "hkv_static_workspace_bytes",
@@ -287,18 +287,20 @@ def hkv_decode_plan_create_tree(pool, nodes, node_pages, req_leaf, tokens_per_re
 class DecodePlanParams(C.Structure):
     """hkv_decode_plan_params: what to plan (query tokens per request, visibility masks, room to grow) and the
     planner's settings; every field left 0 keeps the library's choice."""
-    _fields_ = [("tokens_per_req", C.c_int32), ("visible", C.c_void_p), ("reserve_tokens", C.c_int32)] + [
+    _fields_ = [("tokens_per_req", C.c_int32), ("visible", C.c_void_p), ("reserve_tokens", C.c_int32),
+                ("q_rows", C.c_void_p)] + [
         (name, C.c_int32) for name in ("leaf_chunk", "shared_chunk", "max_rows", "pack", "pack_tokens", "stages",
                                        "interleave", "tile_min_rows", "tile_min_gflop", "tile_workgroups",
                                        "tile_chunk", "large_batch_updates")]
 
 
 def hkv_decode_plan_create_ex(pool, nodes, node_pages, req_leaf, num_q_heads: int, flags: int = 0, visible=None,
-                              **params) -> C.c_void_p:
-    """params: fields of hkv_decode_plan_params by name (tokens_per_req, reserve_tokens, leaf_chunk, pack, ...)."""
+                              q_rows=None, **params) -> C.c_void_p:
+    """params: fields of hkv_decode_plan_params by name (tokens_per_req, reserve_tokens, leaf_chunk, pack, ...);
+    q_rows: the row of q / out / lse of every row of the plan."""
     nodes, node_pages, req_leaf = _nodes(nodes), _host_i32(node_pages), _host_i32(req_leaf)
     st = DecodePlanParams()
-    known = {name for name, _ in DecodePlanParams._fields_} - {"visible"}
+    known = {name for name, _ in DecodePlanParams._fields_} - {"visible", "q_rows"}
     for name, value in params.items():
         if name not in known:
             raise TypeError(f"hkv_decode_plan_create_ex: no setting named {name!r}")
@@ -308,6 +310,11 @@ def hkv_decode_plan_create_ex(pool, nodes, node_pages, req_leaf, num_q_heads: in
         if len(visible) != len(req_leaf) * max(1, st.tokens_per_req):
             raise ValueError("visible must hold one mask per request and drafted token")
         st.visible = visible.ctypes.data
+    if q_rows is not None:
+        q_rows = _host_i32(q_rows)
+        if len(q_rows) != len(req_leaf) * max(1, st.tokens_per_req):
+            raise ValueError("q_rows must hold one row per request and query token")
+        st.q_rows = q_rows.ctypes.data
     out = C.c_void_p()
     _check(lib().hkv_decode_plan_create_ex(pool, _hp(nodes), C.c_int32(nodes.shape[0]), _hp(node_pages),
                                            C.c_int32(len(node_pages)), _hp(req_leaf), C.c_int32(len(req_leaf)),
@@ -412,6 +419,20 @@ def hkv_prefill_plan_create(pool, cu_q, block_table, kv_len, num_q_heads: int, f
     _check(lib().hkv_prefill_plan_create(pool, _hp(cu_q), _hp(bt), C.c_int32(bt.shape[1] if bt.ndim == 2 else 0),
                                          _hp(kv_len), C.c_int32(len(kv_len)), C.c_int32(num_q_heads),
                                          C.c_uint32(flags), C.byref(out)))
+    return out
+
+
+def hkv_prefill_plan_create_rows(pool, q_row_begin, q_len, block_table, kv_len, num_q_heads: int,
+                                 flags: int = 0) -> C.c_void_p:
+    q_row_begin, q_len, kv_len = _host_i32(q_row_begin), _host_i32(q_len), _host_i32(kv_len)
+    if not len(q_row_begin) == len(q_len) == len(kv_len):
+        raise ValueError("q_row_begin, q_len and kv_len hold one entry per request")
+    bt = _host_i32(block_table).reshape(len(kv_len), -1) if len(kv_len) else _host_i32(block_table).reshape(0, 0)
+    out = C.c_void_p()
+    _check(lib().hkv_prefill_plan_create_rows(pool, _hp(q_row_begin), _hp(q_len), _hp(bt),
+                                              C.c_int32(bt.shape[1] if bt.ndim == 2 else 0), _hp(kv_len),
+                                              C.c_int32(len(kv_len)), C.c_int32(num_q_heads), C.c_uint32(flags),
+                                              C.byref(out)))
     return out
 
 

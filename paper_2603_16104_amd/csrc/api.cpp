@@ -102,6 +102,8 @@ struct hkv_decode_plan {
     bool fp8_matrix = false;  // fp8 pools: both products on the fp8 matrix instruction (HKV_PLAN_FP8_MATRIX)
     hkv_decode_plan_params opt{};  // the planner's settings (0 = the library's choice)
     int32_t *d_pages = nullptr, *d_node_req_idx = nullptr, *d_part_count = nullptr;
+    std::vector<int32_t> q_rows;  // row of q / out / lse of every row of the plan (empty: row r is row r)
+    int32_t *d_q_rows = nullptr;
     bool profiling = false, profiled_run = false;
     hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};  // begin/end of the node kernel, begin/end of the merge
     // several query tokens per request: n_req above counts query rows (requests x tokens_per_req)
@@ -844,7 +846,8 @@ static int upload_decode_plan(hkv_decode_plan &pl) {
     size_t off_nri = align_up(off_pages + sizeof(int32_t) * pl.node_pages.size(), 256);
     size_t off_cnt = align_up(off_nri + sizeof(int32_t) * pl.node_req_idx.size(), 256);
     size_t off_tiles = align_up(off_cnt + sizeof(int32_t) * pl.part_count.size(), 256);
-    size_t total = align_up(off_tiles + sizeof(DecodeItem) * pl.tile_items.size(), 256) + 256;
+    size_t off_qrows = align_up(off_tiles + sizeof(DecodeItem) * pl.tile_items.size(), 256);
+    size_t total = align_up(off_qrows + sizeof(int32_t) * pl.q_rows.size(), 256) + 256;
     HKV_HIP(hipMalloc(&pl.dev, total));
     char *base = static_cast<char *>(pl.dev);
     pl.d_items = reinterpret_cast<DecodeItem *>(base + off_items);
@@ -852,6 +855,7 @@ static int upload_decode_plan(hkv_decode_plan &pl) {
     pl.d_node_req_idx = reinterpret_cast<int32_t *>(base + off_nri);
     pl.d_part_count = reinterpret_cast<int32_t *>(base + off_cnt);
     pl.d_tile_items = reinterpret_cast<DecodeItem *>(base + off_tiles);
+    pl.d_q_rows = pl.q_rows.empty() ? nullptr : reinterpret_cast<int32_t *>(base + off_qrows);
     // one host image, one copy
     std::vector<char> image(total, 0);
     auto put = [&](size_t off, const void *src, size_t n) {
@@ -862,6 +866,7 @@ static int upload_decode_plan(hkv_decode_plan &pl) {
     put(off_nri, pl.node_req_idx.data(), sizeof(int32_t) * pl.node_req_idx.size());
     put(off_cnt, pl.part_count.data(), sizeof(int32_t) * pl.part_count.size());
     put(off_tiles, pl.tile_items.data(), sizeof(DecodeItem) * pl.tile_items.size());
+    put(off_qrows, pl.q_rows.data(), sizeof(int32_t) * pl.q_rows.size());
     HKV_HIP(hipMemcpy(pl.dev, image.data(), total, hipMemcpyHostToDevice));
     if (pl.reserve_tokens > 0 && pl.n_req <= kMaxInlineAppend && !pl.grow_items.empty() && !pl.opt.large_batch_updates) {
         HKV_HIP(hipMalloc((void **)&pl.d_grow_items, sizeof(int32_t) * pl.grow_items.size()));
@@ -969,6 +974,21 @@ static int create_decode_plan(hkv_pool *pool, const hkv_node *nodes, int32_t n_n
     pl->group = num_q_heads / Hkv;
     pl->fp8_matrix = pool->d.dtype == HKV_FP8_E4M3 && (flags & HKV_PLAN_FP8_MATRIX);
     if (opt) pl->opt = *opt;
+    if (opt && opt->q_rows) {
+        if (pool->d.dtype == HKV_FP32) {
+            delete pl;
+            return fail(HKV_ESHAPE, "hkv_decode_plan_create_ex: q_rows with an fp32 pool");
+        }
+        pl->q_rows.assign(opt->q_rows, opt->q_rows + n_req);
+        std::vector<int32_t> sorted(pl->q_rows);
+        std::sort(sorted.begin(), sorted.end());
+        if (!sorted.empty() && (sorted.front() < 0 || std::adjacent_find(sorted.begin(), sorted.end()) != sorted.end())) {
+            delete pl;
+            return fail(HKV_EINVAL, "hkv_decode_plan_create_ex: q_rows must be non-negative and all different");
+        }
+        pl->opt.q_rows = nullptr;  // the caller's array is not kept
+    }
+    pl->opt.visible = nullptr;
     pl->no_tiles = (flags & kPlanNoTiles) != 0;
     pl->concurrent = !(flags & HKV_PLAN_ONE_STREAM);
     if (int rc = build_node_req_csr(nodes, n_nodes, req_leaf, n_req, pl->node_req_indptr, pl->node_req_idx,
@@ -1391,7 +1411,8 @@ static int run_decode_plan(hkv_decode_plan *plan, const void *q, float scale, vo
     }
     if (tiles) {
         DecodeTilesLaunch t{view_of(plan->pool), q, plan->d_tile_items, plan->d_pages, plan->d_node_req_idx, o_parts, lse_parts,
-                            (int32_t)plan->tile_items.size(), plan->num_q_heads, plan->max_parts, scale, plan->tile_workgroups};
+                            (int32_t)plan->tile_items.size(), plan->num_q_heads, plan->max_parts, scale, plan->tile_workgroups,
+                            plan->d_q_rows};
         HKV_HIP(launch_decode_tiles(t, s, prof ? plan->ev_tile[0] : nullptr, prof ? plan->ev_tile[1] : nullptr));
     }
     if (!plan->items.empty()) {
@@ -1399,7 +1420,7 @@ static int run_decode_plan(hkv_decode_plan *plan, const void *q, float scale, vo
         DecodeLaunch a{view_of(plan->pool), q, plan->d_items, plan->d_pages, plan->d_node_req_idx, o_parts, lse_parts,
                        (int32_t)plan->items.size(), plan->num_q_heads, plan->max_parts, scale,
                        plan->d_row_leaf, plan->d_row_limit, plan->d_row_mask, plan->n_single, plan->n_stages,
-                       plan->fp8_matrix ? 1 : 0};
+                       plan->fp8_matrix ? 1 : 0, plan->d_q_rows};
         HKV_HIP(launch_decode(a, rs, prof ? plan->ev[0] : nullptr, prof ? plan->ev[1] : nullptr));
         if (fork) {
             HKV_HIP(hipEventRecord(plan->ev_join, plan->side));
@@ -1408,7 +1429,7 @@ static int run_decode_plan(hkv_decode_plan *plan, const void *q, float scale, vo
     }
     HKV_HIP(launch_lse_merge_dense(o_parts, lse_parts, plan->d_part_count, plan->num_q_heads, plan->max_parts,
                                    plan->n_req * plan->num_q_heads, out, HKV_BF16, lse_out, s,
-                                   prof ? plan->ev[2] : nullptr, prof ? plan->ev[3] : nullptr));
+                                   prof ? plan->ev[2] : nullptr, prof ? plan->ev[3] : nullptr, plan->d_q_rows));
     if (prof) plan->profiled_run = !plan->items.empty() || tiles;
     return HKV_OK;
 }
@@ -1556,9 +1577,11 @@ extern "C" size_t attn_decode_workspace_bytes(hkv_pool *pool, const hkv_node *no
 
 // ---------------------------------------------------------------------------------------------
 // prefill planning
-extern "C" int hkv_prefill_plan_create(hkv_pool *pool, const int32_t *cu_q, const int32_t *block_table,
-                                       int32_t max_pages, const int32_t *kv_len, int32_t n_req, int32_t num_q_heads,
-                                       uint32_t flags, hkv_prefill_plan **out) {
+// cu_q: request r's new tokens are rows cu_q[r] .. cu_q[r + 1] - 1 of q / out / lse.  q_row_begin (may be null):
+// they are rows q_row_begin[r] .. q_row_begin[r] + (cu_q[r + 1] - cu_q[r]) - 1 instead.
+static int create_prefill_plan(hkv_pool *pool, const int32_t *cu_q, const int32_t *q_row_begin, const int32_t *block_table,
+                               int32_t max_pages, const int32_t *kv_len, int32_t n_req, int32_t num_q_heads,
+                               uint32_t flags, hkv_prefill_plan **out) {
     if (!pool || !out) return fail(HKV_EINVAL, "hkv_prefill_plan_create: null argument");
     *out = nullptr;
     const int Hkv = pool->d.num_kv_heads;
@@ -1619,7 +1642,7 @@ extern "C" int hkv_prefill_plan_create(hkv_pool *pool, const int32_t *cu_q, cons
     for (const Proto &p : protos)
         for (int h = 0; h < Hkv; ++h) {
             int s = cu_q[p.req + 1] - cu_q[p.req];
-            pl->tiles.push_back(PrefillTile{p.req, p.q_begin, p.n_q, h, cu_q[p.req] + p.q_begin, kv_len[p.req] - s,
+            pl->tiles.push_back(PrefillTile{p.req, p.q_begin, p.n_q, h, (q_row_begin ? q_row_begin[p.req] : cu_q[p.req]) + p.q_begin, kv_len[p.req] - s,
                                             kv_len[p.req], p.req * max_blocks});
         }
     // fp8 pools: number the pages this batch reads (first use first) and point the device table at them
@@ -1679,6 +1702,34 @@ extern "C" int hkv_prefill_plan_create(hkv_pool *pool, const int32_t *cu_q, cons
     }
     *out = pl;
     return HKV_OK;
+}
+
+extern "C" int hkv_prefill_plan_create(hkv_pool *pool, const int32_t *cu_q, const int32_t *block_table,
+                                       int32_t max_pages, const int32_t *kv_len, int32_t n_req, int32_t num_q_heads,
+                                       uint32_t flags, hkv_prefill_plan **out) {
+    return create_prefill_plan(pool, cu_q, nullptr, block_table, max_pages, kv_len, n_req, num_q_heads, flags, out);
+}
+
+extern "C" int hkv_prefill_plan_create_rows(hkv_pool *pool, const int32_t *q_row_begin, const int32_t *q_len,
+                                            const int32_t *block_table, int32_t max_pages, const int32_t *kv_len,
+                                            int32_t n_req, int32_t num_q_heads, uint32_t flags, hkv_prefill_plan **out) {
+    if (!pool || !out) return fail(HKV_EINVAL, "hkv_prefill_plan_create_rows: null argument");
+    *out = nullptr;
+    if (pool->d.dtype == HKV_FP32) return fail(HKV_ESHAPE, "hkv_prefill_plan_create_rows: bf16 and fp8 pools only");
+    if (n_req < 0 || (n_req > 0 && (!q_row_begin || !q_len))) return fail(HKV_EINVAL, "hkv_prefill_plan_create_rows: bad argument");
+    std::vector<int32_t> cu((size_t)n_req + 1, 0);
+    std::vector<std::pair<int64_t, int64_t>> spans;
+    for (int r = 0; r < n_req; ++r) {
+        if (q_len[r] < 0 || q_row_begin[r] < 0 || (int64_t)q_row_begin[r] + q_len[r] > INT32_MAX || (int64_t)cu[r] + q_len[r] > INT32_MAX)
+            return fail(HKV_EINVAL, "hkv_prefill_plan_create_rows: request %d: rows %d .. + %d", r, q_row_begin[r], q_len[r]);
+        cu[r + 1] = cu[r] + q_len[r];
+        if (q_len[r] > 0) spans.push_back({q_row_begin[r], (int64_t)q_row_begin[r] + q_len[r]});
+    }
+    std::sort(spans.begin(), spans.end());
+    for (size_t i = 1; i < spans.size(); ++i)
+        if (spans[i].first < spans[i - 1].second)
+            return fail(HKV_EINVAL, "hkv_prefill_plan_create_rows: two requests share row %lld", (long long)spans[i].first);
+    return create_prefill_plan(pool, cu.data(), q_row_begin, block_table, max_pages, kv_len, n_req, num_q_heads, flags, out);
 }
 
 extern "C" int hkv_prefill_plan_destroy(hkv_prefill_plan *plan) {

@@ -185,7 +185,8 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
     };
     auto load_q = [&](bf16x8 (&qf)[4], int req) {
         const int head = it.kv_head * G + rowc % G;
-        const char *qp = static_cast<const char *>(a.q) + ((size_t)req * a.num_q_heads + head) * (kHeadDim * 2);
+        const int q_row = a.q_rows ? a.q_rows[req] : req;
+        const char *qp = static_cast<const char *>(a.q) + ((size_t)q_row * a.num_q_heads + head) * (kHeadDim * 2);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             // bf16 pool: k-step i covers dims 32*i + 8*g ..; fp8 pool: k-step (i/2, i%2) covers

@@ -76,6 +76,8 @@ struct DecodeLaunch {
     // fp8 pools: run both products on the fp8 matrix instruction (codes of K and V as they are, query
     // and probabilities as two e4m3 terms each) instead of widening the codes to bf16.
     int32_t fp8_matrix;
+    // Row r of the plan reads row q_rows[r] of q (device; null: row r).  Partials stay indexed by r.
+    const int32_t *q_rows;
 };
 
 struct PrefillLaunch {
@@ -186,6 +188,7 @@ struct DecodeTilesLaunch {
     int32_t max_parts;
     float scale;
     int32_t n_workgroups;        // persistent workgroups: workgroup w runs items w, w + n_workgroups, ...
+    const int32_t *q_rows;       // device, may be null: as DecodeLaunch::q_rows
 };
 
 // Query tokens per prefill workgroup for a given group size G (rows per workgroup / G).
@@ -213,9 +216,11 @@ hipError_t launch_decode_tiles(const DecodeTilesLaunch &a, hipStream_t s, hipEve
 hipError_t launch_lse_merge(const float *o_parts, const float *lse_parts, const int32_t *row_indptr,
                             const int32_t *part_idx, int32_t n_rows, void *out, int32_t out_dtype,
                             float *lse_out, hipStream_t s);
+// out_rows (device, may be null): the rows of group g = row / rows_per_count are written to group out_rows[g]
+// of out / lse_out instead of group g.
 hipError_t launch_lse_merge_dense(const float *o_parts, const float *lse_parts, const int32_t *part_count,
                                   int32_t rows_per_count, int32_t max_parts, int32_t n_rows, void *out,
                                   int32_t out_dtype, float *lse_out, hipStream_t s, hipEvent_t ev_begin = nullptr,
-                                  hipEvent_t ev_end = nullptr);
+                                  hipEvent_t ev_end = nullptr, const int32_t *out_rows = nullptr);
 
 }  // namespace hkv

@@ -58,7 +58,8 @@ constexpr int kDenseRowsPerBlock = 8;
 template <int OUT_DT, int kUnroll>
 __global__ __launch_bounds__(32 * kDenseRowsPerBlock) void lse_merge_dense_kernel(
     const float *__restrict__ o_parts, const float *__restrict__ lse_parts, const int32_t *__restrict__ part_count,
-    int32_t rows_per_count, int32_t max_parts, int32_t n_rows, void *__restrict__ out, float *__restrict__ lse_out) {
+    int32_t rows_per_count, int32_t max_parts, int32_t n_rows, void *__restrict__ out, float *__restrict__ lse_out,
+    const int32_t *__restrict__ out_rows) {
     const int row = blockIdx.x * kDenseRowsPerBlock + (threadIdx.x >> 5);
     const int l = threadIdx.x & 31;
     if (row >= n_rows) return;
@@ -117,15 +118,16 @@ __global__ __launch_bounds__(32 * kDenseRowsPerBlock) void lse_merge_dense_kerne
         }
         acc *= 1.0f / z;
     }
+    const size_t dst = out_rows ? (size_t)out_rows[row / rows_per_count] * rows_per_count + row % rows_per_count : (size_t)row;
     if (OUT_DT == 0) {
         u32x2 w;
         w[0] = pack_bf16(acc[0], acc[1]);
         w[1] = pack_bf16(acc[2], acc[3]);
-        reinterpret_cast<u32x2 *>(out)[(size_t)row * (kHeadDim / 4) + l] = w;
+        reinterpret_cast<u32x2 *>(out)[dst * (kHeadDim / 4) + l] = w;
     } else {
-        reinterpret_cast<f32x4 *>(out)[(size_t)row * (kHeadDim / 4) + l] = acc;
+        reinterpret_cast<f32x4 *>(out)[dst * (kHeadDim / 4) + l] = acc;
     }
-    if (lse_out && l == 0) lse_out[row] = (M == -INFINITY) ? -INFINITY : M + fast_log2(z) * kLn2;
+    if (lse_out && l == 0) lse_out[dst] = (M == -INFINITY) ? -INFINITY : M + fast_log2(z) * kLn2;
 }
 
 }  // namespace
@@ -133,12 +135,12 @@ __global__ __launch_bounds__(32 * kDenseRowsPerBlock) void lse_merge_dense_kerne
 hipError_t launch_lse_merge_dense(const float *o_parts, const float *lse_parts, const int32_t *part_count,
                                   int32_t rows_per_count, int32_t max_parts, int32_t n_rows, void *out,
                                   int32_t out_dtype, float *lse_out, hipStream_t s, hipEvent_t ev_begin,
-                                  hipEvent_t ev_end) {
+                                  hipEvent_t ev_end, const int32_t *out_rows) {
     if (n_rows <= 0) return hipSuccess;
     dim3 grid((n_rows + kDenseRowsPerBlock - 1) / kDenseRowsPerBlock), block(32 * kDenseRowsPerBlock);
     auto go = [&](auto kernel) {
         hipExtLaunchKernelGGL(kernel, grid, block, 0, s, ev_begin, ev_end, 0, o_parts, lse_parts, part_count,
-                              rows_per_count, max_parts, n_rows, out, lse_out);
+                              rows_per_count, max_parts, n_rows, out, lse_out, out_rows);
     };
     if (max_parts <= 8) {
         if (out_dtype == 0)

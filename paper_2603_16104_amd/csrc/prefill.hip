@@ -104,6 +104,7 @@ struct TileArgs {
     float *o_parts;              // decode items: partial results
     float *lse_parts;
     int32_t max_parts;
+    const int32_t *q_rows;       // decode items, may be null: row r of the plan reads row q_rows[r] of q
 };
 
 // DECODE: decode work items (persistent workgroups, partial results) instead of prefill tiles.
@@ -190,14 +191,18 @@ __global__ __launch_bounds__(kThreads, 2) void attn_tile_kernel(TileArgs a) {
     const int tok = r_tile / G;                  // token (request) index within the tile (>= n_slots: no such row)
     const int head = kv_head * G + r_tile % G;   // query head
     const int slot_c = min(tok, n_slots - 1);
-    uint32_t io_row;                             // row of q (and of out / of the partials' owner)
-    if constexpr (DECODE)
-        io_row = (uint32_t)a.node_req_idx[it.req_off + slot_c] * Hq + head;
-    else
-        io_row = (uint32_t)(tl.q_row0 + slot_c) * Hq + head;
+    uint32_t io_row;                             // row of out (prefill) / of the partials' owner (decode items)
+    uint32_t q_row;                              // row of q
+    if constexpr (DECODE) {
+        const uint32_t r = (uint32_t)a.node_req_idx[it.req_off + slot_c];
+        io_row = r * Hq + head;
+        q_row = (a.q_rows ? (uint32_t)a.q_rows[r] : r) * Hq + head;
+    } else {
+        q_row = io_row = (uint32_t)(tl.q_row0 + slot_c) * Hq + head;
+    }
     bf16x8 qf[8];
     {
-        const char *qp = static_cast<const char *>(a.q) + (size_t)io_row * (kHeadDim * 2);
+        const char *qp = static_cast<const char *>(a.q) + (size_t)q_row * (kHeadDim * 2);
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) qf[kk] = as_bf16x8(ld16(qp + (16 * kk + 8 * h) * 2));
     }
@@ -682,6 +687,7 @@ hipError_t launch_decode_tiles(const DecodeTilesLaunch &d, hipStream_t s, hipEve
     a.o_parts = d.o_parts;
     a.lse_parts = d.lse_parts;
     a.max_parts = d.max_parts;
+    a.q_rows = d.q_rows;
     const dim3 grid(d.n_workgroups < d.n_items ? d.n_workgroups : d.n_items);
     if (d.pool.dtype == 0)
         hipExtLaunchKernelGGL((attn_tile_kernel<true, false>), grid, dim3(kThreads), 0, s, ev_begin, ev_end, 0, a);

@@ -173,12 +173,9 @@ class MixedStepRunner:
     """One engine step that mixes decode rows with chunks of prompts being prefilled (chunked
     prefill): requests bringing one new token go through the prefix-tree decode plan, so the
     shared part of their paths is read once for all of them; requests bringing several go
-    through suffix-only prefill.  Both plans are queued back to back on one stream and write
-    disjoint rows of one output.  Row order of q / out / lse: the workload's own (request by
-    request); the two groups need not be contiguous, each kernel addresses its rows through a
-    compact copy of q and a scatter of its output done by index tensors prepared once (those
-    copies run on torch's current stream, so pass no other stream unless both groups are
-    contiguous runs of rows)."""
+    through suffix-only prefill.  Both plans are queued back to back on one stream and address
+    disjoint rows of one q / out / lse, in the workload's own row order (request by request):
+    each plan is told which rows are its own, so the two groups need not be contiguous."""
 
     def __init__(self, pool: DevicePool, workload: wl.Workload, random_q: bool = False):
         assert workload.mode == "prefill"
@@ -195,58 +192,25 @@ class MixedStepRunner:
         self.lse = torch.zeros((tq, Hq), dtype=torch.float32, device=dev)
         self.scale = float(workload.scale)
         self.dec_plan = self.pre_plan = None
-        # rows are gathered / scattered only when a group is not one contiguous run of rows
-        self.dec_rows = torch.from_numpy(cu[self.dec_req].astype(np.int64)).to(dev)
-        pre_rows = np.concatenate([np.arange(cu[r], cu[r + 1]) for r in self.pre_req]) if len(self.pre_req) else np.zeros(0, np.int64)
-        self.pre_rows = torch.from_numpy(pre_rows.astype(np.int64)).to(dev)
-        self._dec_contig = len(self.dec_req) > 0 and bool(np.all(np.diff(cu[self.dec_req]) == 1))
-        self._pre_contig = len(pre_rows) > 0 and bool(np.all(np.diff(pre_rows) == 1))
-        self._dec_a = int(cu[self.dec_req[0]]) if len(self.dec_req) else 0
-        self._pre_a = int(pre_rows[0]) if len(pre_rows) else 0
         if len(self.dec_req):
-            self.dec_plan = hkv.hkv_decode_plan_create(pool.handle, f.nodes, f.node_pages, f.req_leaf[self.dec_req], Hq)
+            self.dec_plan = hkv.hkv_decode_plan_create_ex(pool.handle, f.nodes, f.node_pages, f.req_leaf[self.dec_req], Hq,
+                                                          q_rows=cu[self.dec_req])
             self.ws_bytes = hkv.hkv_decode_plan_workspace_bytes(self.dec_plan)
             self.ws = torch.empty(max(self.ws_bytes, 256), dtype=torch.uint8, device=dev)
-            if not self._dec_contig:
-                self.dq = torch.empty((len(self.dec_req), Hq, hkv.HEAD_DIM), dtype=torch.int16, device=dev)
-                self.dout = torch.empty_like(self.dq)
-                self.dlse = torch.empty((len(self.dec_req), Hq), dtype=torch.float32, device=dev)
         if len(self.pre_req):
             mp = max(1, f.max_pages_per_req())
             bt, kv_len, *_ = hkv.prefix_tree_flatten(f.nodes, f.node_pages, f.req_leaf[self.pre_req], mp,
                                                      f.page_size)
-            pcu = np.zeros(len(self.pre_req) + 1, dtype=np.int32)
-            pcu[1:] = np.cumsum(ql[self.pre_req])
-            self.pre_plan = hkv.hkv_prefill_plan_create(pool.handle, pcu, bt, kv_len, Hq)
+            self.pre_plan = hkv.hkv_prefill_plan_create_rows(pool.handle, cu[self.pre_req], ql[self.pre_req], bt, kv_len, Hq)
             self.pws_bytes = hkv.hkv_prefill_plan_workspace_bytes(self.pre_plan)     # fp8 pools only
             self.pws = torch.empty(max(self.pws_bytes, 256), dtype=torch.uint8, device=dev) if self.pws_bytes else None
-            if not self._pre_contig:
-                self.pq = torch.empty((len(pre_rows), Hq, hkv.HEAD_DIM), dtype=torch.int16, device=dev)
-                self.pout = torch.empty_like(self.pq)
-                self.plse = torch.empty((len(pre_rows), Hq), dtype=torch.float32, device=dev)
 
     def run(self, stream=None) -> None:
         if self.dec_plan is not None:
-            if self._dec_contig:
-                a, b = self._dec_a, self._dec_a + len(self.dec_req)
-                hkv.attn_decode_plan_run(self.dec_plan, self.q[a:b], self.scale, self.out[a:b], self.lse[a:b], self.ws,
-                                         self.ws_bytes, stream)
-            else:
-                torch.index_select(self.q, 0, self.dec_rows, out=self.dq)
-                hkv.attn_decode_plan_run(self.dec_plan, self.dq, self.scale, self.dout, self.dlse, self.ws, self.ws_bytes, stream)
-                self.out.index_copy_(0, self.dec_rows, self.dout)
-                self.lse.index_copy_(0, self.dec_rows, self.dlse)
+            hkv.attn_decode_plan_run(self.dec_plan, self.q, self.scale, self.out, self.lse, self.ws, self.ws_bytes, stream)
         if self.pre_plan is not None:
-            if self._pre_contig:
-                a, b = self._pre_a, self._pre_a + len(self.pre_rows)
-                hkv.attn_prefill_plan_run(self.pre_plan, self.q[a:b], self.scale, self.out[a:b], self.lse[a:b], stream,
-                                          self.pws, self.pws_bytes)
-            else:
-                torch.index_select(self.q, 0, self.pre_rows, out=self.pq)
-                hkv.attn_prefill_plan_run(self.pre_plan, self.pq, self.scale, self.pout, self.plse, stream, self.pws,
-                                          self.pws_bytes)
-                self.out.index_copy_(0, self.pre_rows, self.pout)
-                self.lse.index_copy_(0, self.pre_rows, self.plse)
+            hkv.attn_prefill_plan_run(self.pre_plan, self.q, self.scale, self.out, self.lse, stream, self.pws,
+                                      self.pws_bytes)
 
     def close(self) -> None:
         if self.dec_plan is not None:

@@ -161,3 +161,42 @@ def test_tile_decode_is_graph_capturable(gpu, oracle, tiles_on):
     del g
     r.close()
     dp.close()
+
+
+@pytest.mark.parametrize("kv_dtype", [wl.KV_BF16, wl.KV_FP8_E4M3])
+@pytest.mark.parametrize("T", [1, 2])
+def test_decode_rows_anywhere_in_q_and_out(gpu, oracle, tiles_on, kv_dtype, T):
+    """hkv_decode_plan_params.q_rows: the plan's rows are scattered over a q / out / lse three times as long
+    (every third row, in a shuffled order); both kernels read their query rows from there, the merge writes
+    there, the rows in between keep what they held.  70 requests x 4 heads under one root (tile kernel) with
+    ragged leaves (the other kernel); with two query tokens per request as well."""
+    import torch
+    from paper_2603_16104_amd import binding as hkv
+    w = shared_root_workload(21, 8, 2, 70, 1104, kv_dtype)      # whole pages: the oracle walks a flat block table
+    f = w.forest
+    hp, dp = both_pools(gpu, oracle, w)
+    n_rows = f.n_req * T
+    q = wl.f32_to_bf16_bits(np.random.default_rng(3).standard_normal((n_rows, w.num_q_heads, 128)).astype(np.float32))
+    bt, kv_len, *_ = oracle.flatten_workload(w)
+    exp_o, exp_l = oracle.attn_prefill(hp, q, np.arange(f.n_req + 1, dtype=np.int32) * T, bt, kv_len, float(w.scale))
+    rows = (3 * np.random.default_rng(4).permutation(n_rows) + 1).astype(np.int32)
+    q_big = np.zeros((3 * n_rows, w.num_q_heads, 128), dtype=np.uint16)
+    q_big[:] = 0x7FC0                                   # a row read by mistake poisons its output
+    q_big[rows] = q
+    plan = hkv.hkv_decode_plan_create_ex(dp.handle, f.nodes, f.node_pages, f.req_leaf, w.num_q_heads, tokens_per_req=T,
+                                         q_rows=rows)
+    assert (hkv.hkv_decode_plan_num_tile_items(plan) > 0) == (T == 1)      # plans of several query tokens keep to one kernel
+    nb = hkv.hkv_decode_plan_workspace_bytes(plan)
+    ws = torch.empty(max(nb, 256), dtype=torch.uint8, device="cuda")
+    out = torch.full((3 * n_rows, w.num_q_heads, 128), 0x1234, dtype=torch.int16, device="cuda")
+    lse = torch.full((3 * n_rows, w.num_q_heads), 7.5, dtype=torch.float32, device="cuda")
+    hkv.attn_decode_plan_run(plan, gpu.to_device_bits(q_big), float(w.scale), out, lse, ws, nb)
+    torch.cuda.synchronize()
+    idx = torch.from_numpy(rows.astype(np.int64)).cuda()
+    check_close(gpu.bf16_tensor_to_f64(out[idx]), exp_o, w.name)
+    check_lse(lse[idx].cpu().numpy(), exp_l, w.name)
+    other = np.setdiff1d(np.arange(3 * n_rows), rows)
+    oi = torch.from_numpy(other).cuda()
+    assert bool((out[oi] == 0x1234).all()) and bool((lse[oi] == 7.5).all()), "rows of other work were written"
+    hkv.hkv_decode_plan_destroy(plan)
+    dp.close()

@@ -450,6 +450,47 @@ def test_decode_plan_create_ex_equals_the_four_creators_and_checks_its_settings(
     hkv.kv_pool_destroy(pool)
 
 
+def test_row_lists_of_a_mixed_step():
+    """q_rows of a decode plan and q_row_begin / q_len of a prefill plan: what is accepted, and that the
+    prefill tiles address the rows asked for."""
+    w = wl.config2(n_req=6)
+    f = w.forest
+    pool = fake_pool(w.num_pages, w.num_kv_heads)
+    args = (pool, f.nodes, f.node_pages, f.req_leaf, w.num_q_heads, hkv.PLAN_HOST_ONLY)
+    hkv.hkv_decode_plan_destroy(hkv.hkv_decode_plan_create_ex(*args, q_rows=[9, 0, 4, 2, 30, 7]))
+    for rows in ([9, 0, 4, 2, 30, 9], [0, 1, 2, 3, 4, -1]):
+        with pytest.raises(hkv.HkvError) as e:
+            hkv.hkv_decode_plan_create_ex(*args, q_rows=rows)
+        assert e.value.code == hkv.EINVAL and "q_rows" in str(e.value)
+    with pytest.raises(ValueError):
+        hkv.hkv_decode_plan_create_ex(*args, q_rows=[0, 1, 2])
+    hkv.hkv_decode_plan_destroy(hkv.hkv_decode_plan_create_ex(*args, tokens_per_req=2, q_rows=np.arange(12)[::-1]))
+    p32 = fake_pool(w.num_pages, w.num_kv_heads, dtype=hkv.FP32)
+    with pytest.raises(hkv.HkvError) as e:
+        hkv.hkv_decode_plan_create_ex(p32, *args[1:], q_rows=[0, 1, 2, 3, 4, 5])
+    assert e.value.code == hkv.ESHAPE
+    # prefill: three requests of 70, 0 and 5 new tokens at rows 100.., (none), 3..
+    bt = np.tile(np.arange(8, dtype=np.int32), (3, 1))
+    kv_len, q_len, begin = [100, 40, 128], [70, 0, 5], [100, 0, 3]
+    plan = hkv.hkv_prefill_plan_create_rows(pool, begin, q_len, bt, kv_len, w.num_q_heads, hkv.PLAN_HOST_ONLY)
+    tiles = hkv.hkv_prefill_plan_tiles(plan)            # (req, q_begin, n_q, kv_head, q_row0, prefix_len, kv_len, bt_off)
+    same = hkv.hkv_prefill_plan_create(pool, [0, 70, 70, 75], bt, kv_len, w.num_q_heads, hkv.PLAN_HOST_ONLY)
+    ref = hkv.hkv_prefill_plan_tiles(same)
+    assert np.array_equal(np.delete(tiles, 4, axis=1), np.delete(ref, 4, axis=1))
+    assert np.array_equal(tiles[:, 4], np.asarray(begin)[tiles[:, 0]] + tiles[:, 1])
+    for pl in (plan, same):
+        hkv.hkv_prefill_plan_destroy(pl)
+    for b, n in (([0, 50, 69], [70, 0, 5]), ([0, 0, -1], [70, 0, 5]), ([0, 0, 80], [70, -1, 5])):
+        with pytest.raises(hkv.HkvError) as e:
+            hkv.hkv_prefill_plan_create_rows(pool, b, n, bt, kv_len, w.num_q_heads, hkv.PLAN_HOST_ONLY)
+        assert e.value.code == hkv.EINVAL, str(e.value)
+    with pytest.raises(hkv.HkvError) as e:
+        hkv.hkv_prefill_plan_create_rows(p32, begin, q_len, bt, kv_len, w.num_q_heads, hkv.PLAN_HOST_ONLY)
+    assert e.value.code == hkv.ESHAPE
+    hkv.kv_pool_destroy(pool)
+    hkv.kv_pool_destroy(p32)
+
+
 def test_decode_plan_error_codes():
     pool = fake_pool(16, 2)
     nodes = np.array([[-1, 0, 1, 16], [0, 1, 1, 5]], dtype=np.int32)
