@@ -88,6 +88,9 @@ def make_pools(runtime, w, n_pools: int):
     return pools
 
 
+PLAN_SETTINGS = {}      # --plan name=value ...: planner settings of hkv_decode_plan_params for every decode plan timed here
+
+
 def bench_decode(runtime, hkv, w, steps: int, warmup: int, n_pools: int, profile_steps: int, flags: int = 0,
                  batch: int = 8, graph: bool = False, hot: bool = False):
     """Times attn_decode_plan_run over `w`, rotating over n_pools identical pools.  Returns a dict:
@@ -95,7 +98,7 @@ def bench_decode(runtime, hkv, w, steps: int, warmup: int, n_pools: int, profile
     own duration from begin/end events attached to its dispatches), and what describes the plan."""
     import torch
     pools = make_pools(runtime, w, n_pools)
-    runners = [runtime.DecodeRunner(p, w, flags=flags) for p in pools]
+    runners = [runtime.DecodeRunner(p, w, flags=flags, **PLAN_SETTINGS) for p in pools]
     f = w.forest
     t0 = time.perf_counter()                                    # tree walk, work list, upload: once per topology
     for _ in range(3):
@@ -572,6 +575,9 @@ def main() -> int:
                     help="run the fp8 forest on the fp8 matrix instruction (HKV_PLAN_FP8_MATRIX) instead of the default path")
     ap.add_argument("--one-stream", action="store_true",
                     help="decode plans queue the tile kernel in front of the other on one stream (HKV_PLAN_ONE_STREAM)")
+    ap.add_argument("--plan", nargs="*", default=[], metavar="NAME=VALUE",
+                    help="planner settings (fields of hkv_decode_plan_params) for the decode plans, e.g. leaf_chunk=1024")
+    ap.add_argument("--graph", action="store_true", help="with --profile-workload: also time the step as a replayed HIP graph")
     ap.add_argument("--hot", action="store_true", help="also time the small decode workloads without pool rotation (cache-resident)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--decode-loop", action="store_true",
@@ -597,6 +603,9 @@ def main() -> int:
               "run with --gpus 1", file=sys.stderr)
         return 2
 
+    for kv in args.plan:
+        name, _, value = kv.partition("=")
+        PLAN_SETTINGS[name] = int(value)
     import torch
     from paper_2603_16104_amd import binding as hkv, runtime, workloads as wl
     import bench_probes as bp
@@ -658,7 +667,7 @@ def main() -> int:
             small = wx.unique_kv_bytes() < (1 << 29)
             rx = bench_decode(runtime, hkv, wx, max(1, min(args.steps, 100 if small else 40)), 10,
                               args.pools if small else 1, 10, fp8_flags if wx.kv_dtype == wl.KV_FP8_E4M3 else one,
-                              batch=8 if small else 1)
+                              batch=8 if small else 1, graph=args.graph)
             print(json.dumps({"workload": wx.name, **decode_entry(wx, rx)}), flush=True)
         return 0
 

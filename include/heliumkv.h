@@ -374,7 +374,9 @@ int hkv_decode_plan_append(hkv_decode_plan *plan, const int32_t *new_page_ids, v
 int hkv_decode_plan_append_tokens(hkv_decode_plan *plan, const int32_t *new_page_ids, const void *k_src,
                                   const void *v_src, void *stream);
 int hkv_decode_plan_destroy(hkv_decode_plan *plan);
-/* Bytes of device workspace attn_decode_plan_run needs (partial o and lse), 0 on a null plan. */
+/* Bytes of device workspace attn_decode_plan_run needs (per partial: o as 128 fp16 values times a power of two,
+ * that power's reciprocal and lse as floats),
+ * 0 on a null plan. */
 size_t hkv_decode_plan_workspace_bytes(const hkv_decode_plan *plan);
 /* Introspection for tests and tools (host copies).  Work item layout, 8 int32 each:
  * (page_off, n_tokens, kv_head, req_off, n_req, part_slot, tok_begin, node).  page_off indexes
@@ -413,8 +415,8 @@ int attn_decode_plan_run(hkv_decode_plan *plan, const void *q, float scale, void
  * GPU that exists from the time the library is loaded until the process ends, so the call takes
  * neither a workspace nor allocates anything (no hipMalloc / hipFree, no allocating library routine);
  * it only queues the same two kernels on `stream`.  q, out, lse_out, scale: as attn_decode_plan_run.
- * ENOMEM if hkv_decode_plan_workspace_bytes(plan) exceeds the array (e.g. more than 65 000 partials of
- * 516 bytes: use attn_decode_plan_run with a workspace of the caller's then); nothing is queued on
+ * ENOMEM if hkv_decode_plan_workspace_bytes(plan) exceeds the array (e.g. more than 127 000 partials of
+ * 264 bytes: use attn_decode_plan_run with a workspace of the caller's then); nothing is queued on
  * error.  All calls on one GPU share the one array and it keeps the last call's contents (every slot
  * that is read is written first by the same call, so nothing has to be cleared): two such calls
  * that overlap in time on one GPU, on different streams or from different plans, race; queue them

@@ -1347,8 +1347,8 @@ extern "C" int hkv_decode_plan_destroy(hkv_decode_plan *plan) {
 
 extern "C" size_t hkv_decode_plan_workspace_bytes(const hkv_decode_plan *plan) {
     if (!plan || plan->pool->d.dtype == HKV_FP32) return 0;
-    return align_up((size_t)plan->n_parts * HKV_HEAD_DIM * sizeof(float), 256) +
-           align_up((size_t)plan->n_parts * sizeof(float), 256);
+    return align_up((size_t)plan->n_parts * HKV_HEAD_DIM * sizeof(uint16_t), 256) +
+           2 * align_up((size_t)plan->n_parts * sizeof(float), 256);
 }
 
 extern "C" int32_t hkv_decode_plan_num_items(const hkv_decode_plan *plan) {
@@ -1395,9 +1395,11 @@ static int run_decode_plan(hkv_decode_plan *plan, const void *q, float scale, vo
         return HKV_OK;
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
-    float *o_parts = static_cast<float *>(workspace);
+    // per partial: o as fp16 times a power of two, lse, and the reciprocal of that power
+    uint16_t *o_parts = static_cast<uint16_t *>(workspace);
     float *lse_parts = reinterpret_cast<float *>(static_cast<char *>(workspace) +
-                                                 align_up((size_t)plan->n_parts * HKV_HEAD_DIM * sizeof(float), 256));
+                                                 align_up((size_t)plan->n_parts * HKV_HEAD_DIM * sizeof(uint16_t), 256));
+    float *down_parts = lse_parts + align_up((size_t)plan->n_parts * sizeof(float), 256) / sizeof(float);
     const bool prof = plan->profiling;
     const bool tiles = !plan->tile_items.empty();
     const bool fork = tiles && plan->concurrent && !plan->items.empty();
@@ -1411,14 +1413,14 @@ static int run_decode_plan(hkv_decode_plan *plan, const void *q, float scale, vo
     }
     if (tiles) {
         DecodeTilesLaunch t{view_of(plan->pool), q, plan->d_tile_items, plan->d_pages, plan->d_node_req_idx, o_parts, lse_parts,
-                            (int32_t)plan->tile_items.size(), plan->num_q_heads, plan->max_parts, scale, plan->tile_workgroups,
+                            down_parts, (int32_t)plan->tile_items.size(), plan->num_q_heads, plan->max_parts, scale, plan->tile_workgroups,
                             plan->d_q_rows};
         HKV_HIP(launch_decode_tiles(t, s, prof ? plan->ev_tile[0] : nullptr, prof ? plan->ev_tile[1] : nullptr));
     }
     if (!plan->items.empty()) {
         hipStream_t rs = fork ? plan->side : s;
         DecodeLaunch a{view_of(plan->pool), q, plan->d_items, plan->d_pages, plan->d_node_req_idx, o_parts, lse_parts,
-                       (int32_t)plan->items.size(), plan->num_q_heads, plan->max_parts, scale,
+                       down_parts, (int32_t)plan->items.size(), plan->num_q_heads, plan->max_parts, scale,
                        plan->d_row_leaf, plan->d_row_limit, plan->d_row_mask, plan->n_single, plan->n_stages,
                        plan->fp8_matrix ? 1 : 0, plan->d_q_rows};
         HKV_HIP(launch_decode(a, rs, prof ? plan->ev[0] : nullptr, prof ? plan->ev[1] : nullptr));
@@ -1429,7 +1431,7 @@ static int run_decode_plan(hkv_decode_plan *plan, const void *q, float scale, vo
     }
     HKV_HIP(launch_lse_merge_dense(o_parts, lse_parts, plan->d_part_count, plan->num_q_heads, plan->max_parts,
                                    plan->n_req * plan->num_q_heads, out, HKV_BF16, lse_out, s,
-                                   prof ? plan->ev[2] : nullptr, prof ? plan->ev[3] : nullptr, plan->d_q_rows));
+                                   prof ? plan->ev[2] : nullptr, prof ? plan->ev[3] : nullptr, plan->d_q_rows, down_parts));
     if (prof) plan->profiled_run = !plan->items.empty() || tiles;
     return HKV_OK;
 }

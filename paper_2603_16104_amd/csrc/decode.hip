@@ -455,14 +455,30 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
     // Partials of a wavefront that has seen all tokens of its rows: normalise and store from registers.
     auto write_rows = [&](int req) {
         const float l_row = rows_sum(l_run);
-        if (row < rows) {
-            // a row that saw no token of this item delivers the empty partial (o = 0, lse = -inf)
-            float inv = l_row > 0.f ? 1.0f / l_row : 0.f;
-            if constexpr (DT == 2) inv *= __uint_as_float(v_ref_bits) * 0.00390625f;  // o is in units of v_ref * 2^-8
-            const size_t part = (size_t)(req * a.num_q_heads + it.kv_head * G + row % G) * a.max_parts + it.part_slot;
-            float *op = a.o_parts + part * kHeadDim + 4 * g;
+        // a row that saw no token of this item delivers the empty partial (o = 0, lse = -inf)
+        float inv = l_row > 0.f ? 1.0f / l_row : 0.f;
+        if constexpr (DT == 2) inv *= __uint_as_float(v_ref_bits) * 0.00390625f;  // o is in units of v_ref * 2^-8
+        float amax = 0.f;
 #pragma unroll
-            for (int dt = 0; dt < 8; ++dt) *reinterpret_cast<f32x4 *>(op + 16 * dt) = o[dt] * inv;
+        for (int dt = 0; dt < 8; ++dt) {
+            o[dt] *= inv;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) amax = fmaxf(amax, fabsf(o[dt][i]));
+        }
+        amax = rows_max(amax);  // the row's 128 values sit in the four lanes m, m + 16, m + 32, m + 48 (all lanes take part)
+        float up, down;
+        part_factors(amax, up, down);
+        if (row < rows) {
+            const size_t part = (size_t)(req * a.num_q_heads + it.kv_head * G + row % G) * a.max_parts + it.part_slot;
+            uint16_t *op = a.o_parts + part * kHeadDim + 4 * g;
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) {
+                u32x2 w;
+                w[0] = pack_f16(o[dt][0] * up, o[dt][1] * up);
+                w[1] = pack_f16(o[dt][2] * up, o[dt][3] * up);
+                *reinterpret_cast<u32x2 *>(op + 16 * dt) = w;
+            }
+            if (g == 0) a.down_parts[part] = down;
             if (g == 0) a.lse_parts[part] = l_row > 0.f ? (m_run * c + fast_log2(l_row)) * kLn2 : -INFINITY;
         }
     };
@@ -617,12 +633,13 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
         if (wave == 0 && row < rows) sPart[m] = (req * a.num_q_heads + it.kv_head * G + row % G) * a.max_parts + it.part_slot;
     }
     __syncthreads();
-    for (int idx = tid; idx < rows * kHeadDim; idx += kThreads) {
-        const int row = idx >> 7, d = idx & 127;
+    // a row's 64 pairs of neighbouring dims are one wavefront's 64 lanes: wavefront w takes rows w, w + 4, ...
+    for (int row = wave; row < rows; row += kWaves) {
+        const int d = lane * 2;
         const int r_t = row >> 4, r_c = row & 15;
         float M = -INFINITY;
         for (int t = 0; t < n_ts; ++t) M = fmaxf(M, sM[t * n_rt + r_t][r_c]);
-        float L = 0.f, acc = 0.f;
+        float L = 0.f, acc0 = 0.f, acc1 = 0.f;
         if (M != -INFINITY) {
             for (int t = 0; t < n_ts; ++t) {
                 const int w = t * n_rt + r_t;
@@ -630,13 +647,25 @@ __global__ __launch_bounds__(kThreads, DT == 0 ? 3 : 2) void decode_node_kernel(
                 if (mw == -INFINITY) continue;  // that wavefront's tokens were all invisible to the row
                 const float wgt = fast_exp2((mw - M) * c);
                 L += sL[w][r_c] * wgt;
-                acc += sO[w][r_c][d] * wgt;
+                acc0 += sO[w][r_c][d] * wgt;
+                acc1 += sO[w][r_c][d + 1] * wgt;
             }
         }
         const size_t part = (size_t)sPart[row];
         // a row that saw no token of this item delivers the empty partial (o = 0, lse = -inf)
-        a.o_parts[part * kHeadDim + d] = L > 0.f ? acc / L : 0.f;
-        if (d == 0) a.lse_parts[part] = L > 0.f ? (M * c + fast_log2(L)) * kLn2 : -INFINITY;
+        const float inv = L > 0.f ? 1.0f / L : 0.f;
+        acc0 *= inv;
+        acc1 *= inv;
+        float amax = fmaxf(fabsf(acc0), fabsf(acc1));
+#pragma unroll
+        for (int sh = 1; sh < 64; sh <<= 1) amax = fmaxf(amax, __shfl_xor(amax, sh));
+        float up, down;
+        part_factors(amax, up, down);
+        *reinterpret_cast<uint32_t *>(a.o_parts + part * kHeadDim + d) = pack_f16(acc0 * up, acc1 * up);
+        if (lane == 0) {
+            a.down_parts[part] = down;
+            a.lse_parts[part] = L > 0.f ? (M * c + fast_log2(L)) * kLn2 : -INFINITY;
+        }
     }
 }
 

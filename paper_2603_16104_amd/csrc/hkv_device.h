@@ -38,6 +38,24 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, v);
 }
 
+// Partial results of the decode plans travel as fp16 with one power-of-two factor per partial (a row of 128
+// values): 11 significant bits relative to the row's largest magnitude, so that what the merge reads carries
+// more precision than the bf16 output it produces, at half the bytes of fp32.
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+__device__ __forceinline__ uint32_t pack_f16(float lo, float hi) {
+    f16x2 v;
+    v[0] = (_Float16)lo;
+    v[1] = (_Float16)hi;
+    return __builtin_bit_cast(uint32_t, v);
+}
+// For a row whose largest magnitude is amax: `up` = power of two with amax * up in [2^14, 2^15) (fp16 holds
+// up to 65504), `down` = 1 / up.  amax = 0 or tiny: up = 2^114; inf / NaN rows stay inf / NaN.
+__device__ __forceinline__ void part_factors(float amax, float &up, float &down) {
+    const uint32_t e = max((__float_as_uint(amax) >> 23) & 0xFFu, 27u);
+    up = __uint_as_float((268u - e) << 23);
+    down = __uint_as_float((e - 14u) << 23);
+}
+
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
 // Eight e4m3 codes (two dwords) -> eight bf16 (exact: every e4m3 value is a bf16 value), one

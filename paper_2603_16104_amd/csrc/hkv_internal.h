@@ -53,8 +53,9 @@ struct DecodeLaunch {
     const DecodeItem *items;     // device
     const int32_t *pages;        // device: the plan's page list
     const int32_t *node_req_idx; // device: node->request CSR values
-    float *o_parts;              // [n_req*Hq*max_parts][128]
+    uint16_t *o_parts;           // [n_req*Hq*max_parts][128] fp16, each partial times a power of two of its own ...
     float *lse_parts;            // [n_req*Hq*max_parts]
+    float *down_parts;           // [n_req*Hq*max_parts]: ... whose reciprocal is kept here
     int32_t n_items;
     int32_t num_q_heads;
     int32_t max_parts;
@@ -181,8 +182,9 @@ struct DecodeTilesLaunch {
     const DecodeItem *items;     // device: the items of this kernel (at most 256 / G requests each)
     const int32_t *pages;        // device: the plan's block list
     const int32_t *node_req_idx; // device: node->request CSR values
-    float *o_parts;
+    uint16_t *o_parts;           // as DecodeLaunch::o_parts
     float *lse_parts;
+    float *down_parts;
     int32_t n_items;
     int32_t num_q_heads;
     int32_t max_parts;
@@ -218,9 +220,12 @@ hipError_t launch_lse_merge(const float *o_parts, const float *lse_parts, const 
                             float *lse_out, hipStream_t s);
 // out_rows (device, may be null): the rows of group g = row / rows_per_count are written to group out_rows[g]
 // of out / lse_out instead of group g.
-hipError_t launch_lse_merge_dense(const float *o_parts, const float *lse_parts, const int32_t *part_count,
+// down_parts (device, may be null): o_parts holds fp16 values, partial n to be multiplied by down_parts[n] (the
+// decode plans' own partials), instead of floats.
+hipError_t launch_lse_merge_dense(const void *o_parts, const float *lse_parts, const int32_t *part_count,
                                   int32_t rows_per_count, int32_t max_parts, int32_t n_rows, void *out,
                                   int32_t out_dtype, float *lse_out, hipStream_t s, hipEvent_t ev_begin = nullptr,
-                                  hipEvent_t ev_end = nullptr, const int32_t *out_rows = nullptr);
+                                  hipEvent_t ev_end = nullptr, const int32_t *out_rows = nullptr,
+                                  const float *down_parts = nullptr);
 
 }  // namespace hkv

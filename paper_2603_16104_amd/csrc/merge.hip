@@ -4,6 +4,8 @@
 // without finite partials gives out = 0, lse = -inf.
 #include <hip/hip_ext.h>
 
+#include <type_traits>
+
 #include "hkv_device.h"
 
 namespace hkv {
@@ -55,30 +57,45 @@ __global__ __launch_bounds__(64 * kRowsPerBlock) void lse_merge_kernel(const flo
 // forests whose paths collect more than 8 partials).
 constexpr int kDenseRowsPerBlock = 8;
 
-template <int OUT_DT, int kUnroll>
+// four consecutive values of a partial, as floats
+template <bool PB16>
+__device__ __forceinline__ f32x4 load_part4(const void *o_parts, size_t elem) {
+    if constexpr (PB16) {  // fp16; the caller applies the partial's factor
+        const u32x2 w = *reinterpret_cast<const u32x2 *>(static_cast<const uint16_t *>(o_parts) + elem);
+        const uint32_t w0 = w[0], w1 = w[1];  // (a bit cast straight from a vector element reads element 0 for both)
+        const f16x2 a = __builtin_bit_cast(f16x2, w0), b = __builtin_bit_cast(f16x2, w1);
+        return f32x4{(float)a[0], (float)a[1], (float)b[0], (float)b[1]};
+    } else {
+        return *reinterpret_cast<const f32x4 *>(static_cast<const float *>(o_parts) + elem);
+    }
+}
+
+template <int OUT_DT, int kUnroll, bool PB16>
 __global__ __launch_bounds__(32 * kDenseRowsPerBlock) void lse_merge_dense_kernel(
-    const float *__restrict__ o_parts, const float *__restrict__ lse_parts, const int32_t *__restrict__ part_count,
+    const void *__restrict__ o_parts, const float *__restrict__ lse_parts, const int32_t *__restrict__ part_count,
     int32_t rows_per_count, int32_t max_parts, int32_t n_rows, void *__restrict__ out, float *__restrict__ lse_out,
-    const int32_t *__restrict__ out_rows) {
+    const int32_t *__restrict__ out_rows, const float *__restrict__ down_parts) {
     const int row = blockIdx.x * kDenseRowsPerBlock + (threadIdx.x >> 5);
     const int l = threadIdx.x & 31;
     if (row >= n_rows) return;
     const int cnt = min(part_count[row / rows_per_count], max_parts);
     const size_t base = (size_t)row * max_parts;
     const float *lp = lse_parts + base;
-    const f32x4 *op = reinterpret_cast<const f32x4 *>(o_parts + base * kHeadDim) + l;
+    const float *dp = PB16 ? down_parts + base : nullptr;  // fp16 partials: the factor each one is to be multiplied by
+    const size_t o0 = base * kHeadDim + 4 * l;  // element index of this lane's four dims in slot 0
     // With few slots per row all of them are requested before the count is known (slots k < max_parts
     // exist for every row; what an unused one holds is never looked at), so the count, the lse values
     // and the partials travel in one round trip instead of two.  With many slots only the used ones
     // are read.
-    float ls[kUnroll];
+    float ls[kUnroll], ds[kUnroll];
     f32x4 ov[kUnroll];
     if (max_parts <= kUnroll) {
 #pragma unroll
         for (int k = 0; k < kUnroll; ++k) {
             const int kc = min(k, max_parts - 1);
             ls[k] = lp[kc];
-            ov[k] = op[(size_t)kc * (kHeadDim / 4)];
+            ds[k] = PB16 ? dp[kc] : 1.0f;
+            ov[k] = load_part4<PB16>(o_parts, o0 + (size_t)kc * kHeadDim);
         }
 #pragma unroll
         for (int k = 0; k < kUnroll; ++k)
@@ -87,10 +104,12 @@ __global__ __launch_bounds__(32 * kDenseRowsPerBlock) void lse_merge_dense_kerne
 #pragma unroll
         for (int k = 0; k < kUnroll; ++k) {
             ls[k] = -INFINITY;
+            ds[k] = 1.0f;
             ov[k] = f32x4{0.f, 0.f, 0.f, 0.f};
             if (k < cnt) {
                 ls[k] = lp[k];
-                ov[k] = op[(size_t)k * (kHeadDim / 4)];
+                if (PB16) ds[k] = dp[k];
+                ov[k] = load_part4<PB16>(o_parts, o0 + (size_t)k * kHeadDim);
             }
         }
     }
@@ -106,7 +125,7 @@ __global__ __launch_bounds__(32 * kDenseRowsPerBlock) void lse_merge_dense_kerne
             if (ls[k] != -INFINITY) {  // an empty partial may hold anything in o
                 const float w = fast_exp2((ls[k] - M) * kLog2e);
                 z += w;
-                acc += ov[k] * w;
+                acc += ov[k] * (w * ds[k]);
             }
         }
         for (int k = kUnroll; k < cnt; ++k) {
@@ -114,7 +133,7 @@ __global__ __launch_bounds__(32 * kDenseRowsPerBlock) void lse_merge_dense_kerne
             if (lk == -INFINITY) continue;
             const float w = fast_exp2((lk - M) * kLog2e);
             z += w;
-            acc += op[(size_t)k * (kHeadDim / 4)] * w;
+            acc += load_part4<PB16>(o_parts, o0 + (size_t)k * kHeadDim) * (PB16 ? w * dp[k] : w);
         }
         acc *= 1.0f / z;
     }
@@ -132,27 +151,34 @@ __global__ __launch_bounds__(32 * kDenseRowsPerBlock) void lse_merge_dense_kerne
 
 }  // namespace
 
-hipError_t launch_lse_merge_dense(const float *o_parts, const float *lse_parts, const int32_t *part_count,
+hipError_t launch_lse_merge_dense(const void *o_parts, const float *lse_parts, const int32_t *part_count,
                                   int32_t rows_per_count, int32_t max_parts, int32_t n_rows, void *out,
                                   int32_t out_dtype, float *lse_out, hipStream_t s, hipEvent_t ev_begin,
-                                  hipEvent_t ev_end, const int32_t *out_rows) {
+                                  hipEvent_t ev_end, const int32_t *out_rows, const float *down_parts) {
     if (n_rows <= 0) return hipSuccess;
     dim3 grid((n_rows + kDenseRowsPerBlock - 1) / kDenseRowsPerBlock), block(32 * kDenseRowsPerBlock);
     auto go = [&](auto kernel) {
         hipExtLaunchKernelGGL(kernel, grid, block, 0, s, ev_begin, ev_end, 0, o_parts, lse_parts, part_count,
-                              rows_per_count, max_parts, n_rows, out, lse_out, out_rows);
+                              rows_per_count, max_parts, n_rows, out, lse_out, out_rows, down_parts);
     };
-    if (max_parts <= 8) {
-        if (out_dtype == 0)
-            go(lse_merge_dense_kernel<0, 8>);
-        else
-            go(lse_merge_dense_kernel<2, 8>);
-    } else {
-        if (out_dtype == 0)
-            go(lse_merge_dense_kernel<0, 16>);
-        else
-            go(lse_merge_dense_kernel<2, 16>);
-    }
+    auto pick = [&](auto pb16) {
+        constexpr bool PB = decltype(pb16)::value;
+        if (max_parts <= 8) {
+            if (out_dtype == 0)
+                go(lse_merge_dense_kernel<0, 8, PB>);
+            else
+                go(lse_merge_dense_kernel<2, 8, PB>);
+        } else {
+            if (out_dtype == 0)
+                go(lse_merge_dense_kernel<0, 16, PB>);
+            else
+                go(lse_merge_dense_kernel<2, 16, PB>);
+        }
+    };
+    if (down_parts)
+        pick(std::true_type{});
+    else
+        pick(std::false_type{});
     return hipGetLastError();
 }
 

@@ -101,8 +101,9 @@ struct TileArgs {
     void *out;                   // prefill: [tokens][Hq][128] bf16
     float *lse_out;              // prefill: may be null
     const int32_t *node_req_idx; // decode items: node->request CSR values
-    float *o_parts;              // decode items: partial results
-    float *lse_parts;
+    uint16_t *o_parts;           // decode items: partial results (o in fp16 times a power of two per partial,
+    float *lse_parts;            // lse and the reciprocal of that power in fp32)
+    float *down_parts;
     int32_t max_parts;
     const int32_t *q_rows;       // decode items, may be null: row r of the plan reads row q_rows[r] of q
 };
@@ -619,20 +620,32 @@ __global__ __launch_bounds__(kThreads, 2) void attn_tile_kernel(TileArgs a) {
 
     // ---- normalise and store; lane (n, h) holds dims 32*dm + 8*(i/4) + 4*h + i%4 of its row
     const float l_tot = l_run + __shfl_xor(l_run, 32);
+    float up = 1.f, down = 1.f;
+    if constexpr (DECODE) {  // the partial goes out as fp16 times a power of two that puts the row's largest value near 2^14
+        float amax = 0.f;
+#pragma unroll
+        for (int dm = 0; dm < 4; ++dm)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) amax = fmaxf(amax, fabsf(o[dm][i]));
+        amax = fmaxf(amax, __shfl_xor(amax, 32)) * (1.0f / l_tot);
+        part_factors(amax, up, down);
+        up *= 1.0f / l_tot;
+    }
     if (tok < n_slots) {
         const float inv = 1.0f / l_tot;
-        if constexpr (DECODE) {  // the row's partial for this chunk of the node: o in fp32, lse
+        if constexpr (DECODE) {  // the row's partial for this chunk of the node
             const size_t part = (size_t)io_row * a.max_parts + it.part_slot;
-            float *op = a.o_parts + part * kHeadDim + 4 * h;
+            uint16_t *op = a.o_parts + part * kHeadDim + 4 * h;
 #pragma unroll
             for (int dm = 0; dm < 4; ++dm)
 #pragma unroll
                 for (int q4 = 0; q4 < 4; ++q4) {
-                    f32x4 w;
-#pragma unroll
-                    for (int jj = 0; jj < 4; ++jj) w[jj] = o[dm][4 * q4 + jj] * inv;
-                    *reinterpret_cast<f32x4 *>(op + 32 * dm + 8 * q4) = w;
+                    u32x2 w;
+                    w[0] = pack_f16(o[dm][4 * q4] * up, o[dm][4 * q4 + 1] * up);
+                    w[1] = pack_f16(o[dm][4 * q4 + 2] * up, o[dm][4 * q4 + 3] * up);
+                    *reinterpret_cast<u32x2 *>(op + 32 * dm + 8 * q4) = w;
                 }
+            if (h == 0) a.down_parts[part] = down;
             if (h == 0) a.lse_parts[part] = (m_fin + fast_log2(l_tot)) * kLn2;
         } else {
             uint16_t *op = static_cast<uint16_t *>(a.out) + (size_t)io_row * kHeadDim;
@@ -687,6 +700,7 @@ hipError_t launch_decode_tiles(const DecodeTilesLaunch &d, hipStream_t s, hipEve
     a.o_parts = d.o_parts;
     a.lse_parts = d.lse_parts;
     a.max_parts = d.max_parts;
+    a.down_parts = d.down_parts;
     a.q_rows = d.q_rows;
     const dim3 grid(d.n_workgroups < d.n_items ? d.n_workgroups : d.n_items);
     if (d.pool.dtype == 0)

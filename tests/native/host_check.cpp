@@ -33,8 +33,8 @@ hipError_t launch_prefill(const PrefillLaunch &, hipStream_t) { return hipSucces
 hipError_t launch_decode_tiles(const DecodeTilesLaunch &, hipStream_t, hipEvent_t, hipEvent_t) { return hipSuccess; }
 hipError_t launch_lse_merge(const float *, const float *, const int32_t *, const int32_t *, int32_t, void *, int32_t, float *,
                             hipStream_t) { return hipSuccess; }
-hipError_t launch_lse_merge_dense(const float *, const float *, const int32_t *, int32_t, int32_t, int32_t, void *, int32_t,
-                                  float *, hipStream_t, hipEvent_t, hipEvent_t, const int32_t *) { return hipSuccess; }
+hipError_t launch_lse_merge_dense(const void *, const float *, const int32_t *, int32_t, int32_t, int32_t, void *, int32_t,
+                                  float *, hipStream_t, hipEvent_t, hipEvent_t, const int32_t *, const float *) { return hipSuccess; }
 hipError_t run_read_probe(const void *const *, int, size_t, int, int, float *, hipStream_t) { return hipSuccess; }
 hipError_t run_mfma_probe(int, int, int, int, float *, float *, hipStream_t) { return hipSuccess; }
 int prefill_tile_tokens(int group) { return 256 / group; }

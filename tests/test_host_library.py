@@ -215,7 +215,7 @@ def _check_decode_plan(w, oracle):
     max_parts = hkv.hkv_decode_plan_max_parts(plan)
     counts = hkv.hkv_decode_plan_part_counts(plan, f.n_req)
     assert hkv.hkv_decode_plan_num_parts(plan) == f.n_req * w.num_q_heads * max_parts
-    assert hkv.hkv_decode_plan_workspace_bytes(plan) >= hkv.hkv_decode_plan_num_parts(plan) * 516
+    assert hkv.hkv_decode_plan_workspace_bytes(plan) >= hkv.hkv_decode_plan_num_parts(plan) * 264
     covered = [np.zeros((w.num_kv_heads, int(kv_len[r])), dtype=np.int32) for r in range(f.n_req)]
     slots = [np.zeros((w.num_kv_heads, max_parts), dtype=np.int32) for _ in range(f.n_req)]
     n_tile = hkv.hkv_decode_plan_num_tile_items(plan)          # the last n_tile items belong to the 256-row tile kernel

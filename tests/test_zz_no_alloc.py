@@ -65,7 +65,7 @@ def test_static_workspace_limit_is_an_error(gpu):
     """A plan whose partials exceed the static array is refused with ENOMEM before anything is queued."""
     import torch
     from paper_2603_16104_amd import binding as hkv
-    n_req, Hq = 2048, 64                                   # 2048 * 64 partials of 516 B = 67.6 MB > 32 MiB
+    n_req, Hq = 2048, 64                                   # 2048 * 64 rows x 2 partials of 264 B = 69 MB > 32 MiB
     parent = [-1] + [0] * n_req
     w_tokens = [16] * (n_req + 1)
     pages = np.arange(n_req + 1, dtype=np.int32)
