@@ -359,9 +359,12 @@ typedef struct {
                                  (default 128, at least 65) ... */
     int32_t tile_min_gflop;   /* ... if the forest holds this much such work (default 40); -1: whatever the amount */
     int32_t tile_workgroups;  /* persistent workgroups of the tile kernel (default: from the two amounts of work) */
-    int32_t tile_chunk;       /* tokens per item of the tile kernel; multiple of 16, at most 2048 */
+    int32_t tile_chunk;       /* tokens per item of the tile kernel; multiple of 16, at most 8192 */
     int32_t large_batch_updates; /* growing plans: 1 = apply appends as for more than 256 requests (work list re-sent
                                  from pinned memory instead of a small kernel that carries the change in its arguments) */
+    int32_t fused;            /* -1: never run the two kinds of items as one launch (then the tile kernel runs beside the
+                                 other on a second stream, or in front of it with HKV_PLAN_ONE_STREAM); 0: one
+                                 launch whenever no other item is shared by more than 16 query rows */
 } hkv_decode_plan_params;
 int hkv_decode_plan_create_ex(hkv_pool *pool, const hkv_node *nodes, int32_t n_nodes, const int32_t *node_pages,
                               int32_t n_node_pages, const int32_t *req_leaf, int32_t n_req, int32_t num_q_heads,
@@ -387,10 +390,13 @@ size_t hkv_decode_plan_workspace_bytes(const hkv_decode_plan *plan);
  * h) of the item writes partial (r*num_q_heads + h)*max_parts + part_slot. */
 int32_t hkv_decode_plan_num_items(const hkv_decode_plan *plan);
 /* Of these, the last hkv_decode_plan_num_tile_items are items of nodes shared by 128 query rows or more (up
- * to 256 / G requests each, at most 2048 tokens): they are run by a second kernel, built like the prefill
- * kernel (256-row tiles), on hkv_decode_plan_tile_workgroups persistent workgroups. */
+ * to 256 / G requests each, at most 8192 tokens): they are run by code built like the prefill kernel (256-row
+ * tiles) on hkv_decode_plan_tile_workgroups persistent workgroups.  hkv_decode_plan_is_fused: 1 if those
+ * workgroups and the workgroups of the other items go out as one launch (possible when none of the other
+ * items is shared by more than 16 query rows), 0 if they are two kernels on two streams. */
 int32_t hkv_decode_plan_num_tile_items(const hkv_decode_plan *plan);
 int32_t hkv_decode_plan_tile_workgroups(const hkv_decode_plan *plan);
+int32_t hkv_decode_plan_is_fused(const hkv_decode_plan *plan);
 /* Workgroups of the per-node kernel: one per item, except that in forests with more items than the
  * chip holds at once the short items of at most 16 query rows (listed last) share a workgroup four
  * at a time, one item per wavefront. */

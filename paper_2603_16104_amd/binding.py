@@ -32,7 +32,7 @@ EXPORTS = [
     "hkv_decode_plan_max_parts", "hkv_decode_plan_part_counts", "lse_merge_dense", "attn_decode_plan_run",
     "attn_decode_plan_run_static", "hkv_static_workspace_bytes",
     "hkv_decode_plan_set_profiling", "hkv_decode_plan_elapsed_ms", "hkv_decode_plan_elapsed_kernels_ms",
-    "hkv_decode_plan_num_tile_items", "hkv_decode_plan_tile_workgroups",
+    "hkv_decode_plan_num_tile_items", "hkv_decode_plan_tile_workgroups", "hkv_decode_plan_is_fused",
     "attn_decode_prefix_tree", "attn_decode_workspace_bytes", "hkv_prefill_plan_create", "hkv_prefill_plan_destroy",
     "hkv_prefill_plan_num_tiles", "hkv_prefill_plan_tiles", "attn_prefill_plan_run", "attn_prefill_plan_run_ws", "hkv_prefill_plan_workspace_bytes", "attn_prefill_with_prefix",
     "attn_prefill_workspace_bytes",
@@ -291,7 +291,7 @@ class DecodePlanParams(C.Structure):
                 ("q_rows", C.c_void_p)] + [
         (name, C.c_int32) for name in ("leaf_chunk", "shared_chunk", "max_rows", "pack", "pack_tokens", "stages",
                                        "interleave", "tile_min_rows", "tile_min_gflop", "tile_workgroups",
-                                       "tile_chunk", "large_batch_updates")]
+                                       "tile_chunk", "large_batch_updates", "fused")]
 
 
 def hkv_decode_plan_create_ex(pool, nodes, node_pages, req_leaf, num_q_heads: int, flags: int = 0, visible=None,
@@ -388,6 +388,10 @@ def hkv_decode_plan_elapsed_kernels_ms(plan):
 
 def hkv_decode_plan_num_tile_items(plan) -> int:
     return _check(lib().hkv_decode_plan_num_tile_items(plan))
+
+
+def hkv_decode_plan_is_fused(plan) -> bool:
+    return bool(lib().hkv_decode_plan_is_fused(plan))
 
 
 def hkv_decode_plan_tile_workgroups(plan) -> int:

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libheliumkv.so")
 SOURCES = ["api.cpp", "decode.hip", "merge.hip", "pool_write.hip", "prefill.hip", "rows_fp32.hip", "trt.cpp", "cache.cpp"]
-HEADERS = ["hkv_internal.h", "hkv_device.h", os.path.join("..", "..", "include", "heliumkv.h")]
+HEADERS = ["hkv_internal.h", "hkv_device.h", "rows_body.h", "tile_body.h", os.path.join("..", "..", "include", "heliumkv.h")]
 
 # Packed-FP32 VALU forms are switched off for every kernel in this library.
 HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",

@@ -90,6 +90,7 @@ struct hkv_decode_plan {
     std::vector<DecodeItem> tile_items;
     int32_t tile_workgroups = 0;
     bool no_tiles = false, concurrent = true;
+    bool fused = false;  // both kinds of items go out as one launch (no item of `items` has more than 16 rows)
     hipStream_t side = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     hipEvent_t ev_tile[2] = {nullptr, nullptr};  // profiling: begin/end of the tile kernel
@@ -740,9 +741,10 @@ static void plan_items(hkv_decode_plan &pl) {
             }
             wgs = std::min(n_cu, or_default(opt.tile_workgroups, wgs));
             pl.tile_workgroups = wgs;
-            // chunks: at least two rounds of items per workgroup where the nodes are long enough, few partials otherwise
-            const int64_t per_unit = std::max<int64_t>(1, (2 * (int64_t)wgs + tile_units - 1) / tile_units);
-            int64_t ch = (tile_tokens_max / per_unit + 63) / 64 * 64;
+            // chunks: about one item per workgroup (a workgroup that is done gives its compute unit to the other
+            // items, and every chunk costs every row below the node a partial), more where the nodes are few
+            const int64_t n_chunks = std::max<int64_t>(1, std::min<int64_t>((wgs + tile_units / 2) / tile_units, tile_tokens_max / 256));
+            int64_t ch = ((tile_tokens_max + n_chunks - 1) / n_chunks + 63) / 64 * 64;
             tile_chunk = (int)std::min<int64_t>(kMaxTileItemTokens, std::max<int64_t>(256, ch));
             tile_chunk = std::min(kMaxTileItemTokens, or_default(opt.tile_chunk, tile_chunk)) / 16 * 16;
         }
@@ -820,6 +822,9 @@ static void plan_items(hkv_decode_plan &pl) {
     }
     std::stable_sort(pl.tile_items.begin(), pl.tile_items.end(),
                      [](const DecodeItem &x, const DecodeItem &y) { return x.n_tokens > y.n_tokens; });
+    // a workgroup per item while that leaves a quarter of the chip to the other kernel's first workgroups
+    if (opt.tile_workgroups == 0 && (int)pl.tile_items.size() <= chip.n_cu - 64)
+        pl.tile_workgroups = (int32_t)pl.tile_items.size();
     pl.tile_workgroups = std::min<int32_t>(pl.tile_workgroups, (int32_t)pl.tile_items.size());
     pl.items.clear();
     pl.n_single = 0;
@@ -838,6 +843,10 @@ static void plan_items(hkv_decode_plan &pl) {
         pl.max_parts = std::max(pl.max_parts, pl.part_count[r]);
     }
     pl.n_parts = pl.n_req * pl.num_q_heads * pl.max_parts;
+    // One launch for both kinds of items where the kernel allows it: its workgroups of the other items run two
+    // blocks side by side, which works as long as no item synchronises per step (more than 16 query rows).
+    pl.fused = !pl.tile_items.empty() && !pl.items.empty() && opt.fused >= 0 && !pl.fp8_matrix;
+    for (const DecodeItem &it : pl.items) pl.fused = pl.fused && it.n_req * G <= 16;
 }
 
 static int upload_decode_plan(hkv_decode_plan &pl) {
@@ -878,7 +887,7 @@ static int upload_decode_plan(hkv_decode_plan &pl) {
         memset(pl.h_grow, 0, pl.grow_bytes * hkv_decode_plan::kGrowSlots);
         for (hipEvent_t &e : pl.grow_free) HKV_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
     }
-    if (!pl.tile_items.empty()) {  // the tile kernel's own stream and the two events that fork to it and join it
+    if (!pl.tile_items.empty() && !pl.fused) {  // the tile kernel's own stream and the two events that fork to it and join it
         HKV_HIP(hipStreamCreateWithFlags(&pl.side, hipStreamNonBlocking));
         HKV_HIP(hipEventCreateWithFlags(&pl.ev_fork, hipEventDisableTiming));
         HKV_HIP(hipEventCreateWithFlags(&pl.ev_join, hipEventDisableTiming));
@@ -939,6 +948,7 @@ static int check_plan_settings(const hkv_decode_plan_params *o) {
     if (o->tile_workgroups < 0) return bad("tile_workgroups", o->tile_workgroups);
     if (o->tile_chunk < 0 || o->tile_chunk % 16 || o->tile_chunk > kMaxTileItemTokens) return bad("tile_chunk", o->tile_chunk);
     if (o->large_batch_updates < 0 || o->large_batch_updates > 1) return bad("large_batch_updates", o->large_batch_updates);
+    if (o->fused < -1 || o->fused > 0) return bad("fused", o->fused);
     return HKV_OK;
 }
 
@@ -1357,6 +1367,9 @@ extern "C" int32_t hkv_decode_plan_num_items(const hkv_decode_plan *plan) {
 extern "C" int32_t hkv_decode_plan_num_tile_items(const hkv_decode_plan *plan) {
     return plan ? (int32_t)plan->tile_items.size() : fail(HKV_EINVAL, "null plan");
 }
+extern "C" int32_t hkv_decode_plan_is_fused(const hkv_decode_plan *plan) {
+    return plan ? (plan->fused ? 1 : 0) : fail(HKV_EINVAL, "null plan");
+}
 extern "C" int32_t hkv_decode_plan_tile_workgroups(const hkv_decode_plan *plan) {
     return plan ? plan->tile_workgroups : fail(HKV_EINVAL, "null plan");
 }
@@ -1402,7 +1415,7 @@ static int run_decode_plan(hkv_decode_plan *plan, const void *q, float scale, vo
     float *down_parts = lse_parts + align_up((size_t)plan->n_parts * sizeof(float), 256) / sizeof(float);
     const bool prof = plan->profiling;
     const bool tiles = !plan->tile_items.empty();
-    const bool fork = tiles && plan->concurrent && !plan->items.empty();
+    const bool fork = tiles && plan->concurrent && !plan->items.empty() && !plan->fused;
     // The tile kernel goes first and stays on the caller's stream, so that its persistent workgroups, which need
     // a whole compute unit each, take theirs before the other kernel's many small workgroups fill the chip; that
     // kernel follows on the plan's own stream (behind an event that marks the same point of the caller's stream)
@@ -1411,18 +1424,20 @@ static int run_decode_plan(hkv_decode_plan *plan, const void *q, float scale, vo
         HKV_HIP(hipEventRecord(plan->ev_fork, s));
         HKV_HIP(hipStreamWaitEvent(plan->side, plan->ev_fork, 0));
     }
-    if (tiles) {
-        DecodeTilesLaunch t{view_of(plan->pool), q, plan->d_tile_items, plan->d_pages, plan->d_node_req_idx, o_parts, lse_parts,
-                            down_parts, (int32_t)plan->tile_items.size(), plan->num_q_heads, plan->max_parts, scale, plan->tile_workgroups,
-                            plan->d_q_rows};
+    const DecodeTilesLaunch t{view_of(plan->pool), q, plan->d_tile_items, plan->d_pages, plan->d_node_req_idx, o_parts, lse_parts,
+                              down_parts, (int32_t)plan->tile_items.size(), plan->num_q_heads, plan->max_parts, scale,
+                              plan->tile_workgroups, plan->d_q_rows};
+    const DecodeLaunch a{view_of(plan->pool), q, plan->d_items, plan->d_pages, plan->d_node_req_idx, o_parts, lse_parts,
+                         down_parts, (int32_t)plan->items.size(), plan->num_q_heads, plan->max_parts, scale,
+                         plan->d_row_leaf, plan->d_row_limit, plan->d_row_mask, plan->n_single, plan->n_stages,
+                         plan->fp8_matrix ? 1 : 0, plan->d_q_rows};
+    if (plan->fused) {
+        HKV_HIP(launch_decode_fused(a, t, s, prof ? plan->ev[0] : nullptr, prof ? plan->ev[1] : nullptr));
+    } else if (tiles) {
         HKV_HIP(launch_decode_tiles(t, s, prof ? plan->ev_tile[0] : nullptr, prof ? plan->ev_tile[1] : nullptr));
     }
-    if (!plan->items.empty()) {
+    if (!plan->items.empty() && !plan->fused) {
         hipStream_t rs = fork ? plan->side : s;
-        DecodeLaunch a{view_of(plan->pool), q, plan->d_items, plan->d_pages, plan->d_node_req_idx, o_parts, lse_parts,
-                       down_parts, (int32_t)plan->items.size(), plan->num_q_heads, plan->max_parts, scale,
-                       plan->d_row_leaf, plan->d_row_limit, plan->d_row_mask, plan->n_single, plan->n_stages,
-                       plan->fp8_matrix ? 1 : 0, plan->d_q_rows};
         HKV_HIP(launch_decode(a, rs, prof ? plan->ev[0] : nullptr, prof ? plan->ev[1] : nullptr));
         if (fork) {
             HKV_HIP(hipEventRecord(plan->ev_join, plan->side));
@@ -1489,7 +1504,7 @@ extern "C" int hkv_decode_plan_set_profiling(hkv_decode_plan *plan, int32_t mode
 // GPU time of the node phase of the most recent profiled run: from the earlier begin to the later end of the
 // kernel over `items` and the tile kernel (either may be absent), and each of the two on its own.
 static int node_phase_ms(hkv_decode_plan *plan, float *span, float *rows_ms, float *tile_ms) {
-    const bool rows = !plan->items.empty(), tiles = !plan->tile_items.empty();
+    const bool rows = !plan->items.empty(), tiles = !plan->tile_items.empty() && !plan->fused;  // (one launch: its events are ev[0..1])
     *span = *rows_ms = *tile_ms = 0.f;
     if (rows) HKV_HIP(hipEventElapsedTime(rows_ms, plan->ev[0], plan->ev[1]));
     if (tiles) HKV_HIP(hipEventElapsedTime(tile_ms, plan->ev_tile[0], plan->ev_tile[1]));

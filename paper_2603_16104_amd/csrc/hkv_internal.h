@@ -174,8 +174,8 @@ constexpr int kMaxSharedItemTokens = 2048;
 // Decode items shared by more than kMinTileItemRows query rows are run by the 256-row tile kernel (the
 // prefill kernel in its second role), on a stream of its own next to the kernel that streams the rest.
 constexpr int kMinTileItemRows = 65;
-constexpr int kMaxTileItemTokens = 2048;  // tokens per such item
-constexpr int kScaleSlots = 256;          // pages whose fp8 scales the tile kernel keeps in LDS
+constexpr int kMaxTileItemTokens = 8192;  // tokens per such item
+constexpr int kScaleSlots = 512;          // pages whose fp8 scales the tile kernel keeps in LDS
 struct DecodeTilesLaunch {
     PoolView pool;
     const void *q;               // [n_req][Hq][128] bf16
@@ -195,6 +195,9 @@ struct DecodeTilesLaunch {
 
 // Query tokens per prefill workgroup for a given group size G (rows per workgroup / G).
 int prefill_tile_tokens(int group);
+// Both kinds of decode items in one launch (no item of `a` may be shared by more than 16 query rows).
+hipError_t launch_decode_fused(const DecodeLaunch &a, const DecodeTilesLaunch &d, hipStream_t s,
+                               hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr);
 
 hipError_t launch_pool_write(const PoolWriteLaunch &a, hipStream_t s);
 // src may be pinned host memory (its device-side address); bytes is rounded down to a multiple of 16

@@ -31,6 +31,7 @@ hipError_t launch_rows_fp32(const RowsLaunch &, hipStream_t) { return hipSuccess
 hipError_t launch_pool_write_fp32(const PoolWriteLaunch &, hipStream_t) { return hipSuccess; }
 hipError_t launch_prefill(const PrefillLaunch &, hipStream_t) { return hipSuccess; }
 hipError_t launch_decode_tiles(const DecodeTilesLaunch &, hipStream_t, hipEvent_t, hipEvent_t) { return hipSuccess; }
+hipError_t launch_decode_fused(const DecodeLaunch &, const DecodeTilesLaunch &, hipStream_t, hipEvent_t, hipEvent_t) { return hipSuccess; }
 hipError_t launch_lse_merge(const float *, const float *, const int32_t *, const int32_t *, int32_t, void *, int32_t, float *,
                             hipStream_t) { return hipSuccess; }
 hipError_t launch_lse_merge_dense(const void *, const float *, const int32_t *, int32_t, int32_t, int32_t, void *, int32_t,

@@ -224,7 +224,7 @@ def _check_decode_plan(w, oracle):
         assert 1 <= n_tok and tok_begin % 16 == 0 and tok_begin + n_tok <= f.n_tokens[node]
         assert page_off == f.page_begin[node] + tok_begin // 16
         if i >= n_rows_items:
-            assert 128 <= (indptr[node + 1] - indptr[node]) * G and 1 <= n_req <= max(1, 256 // G) and n_tok <= 2048
+            assert 128 <= (indptr[node + 1] - indptr[node]) * G and 1 <= n_req <= max(1, 256 // G) and n_tok <= 8192
         else:
             assert 1 <= n_req and n_req * G <= 64
             if n_req * G > 16:
@@ -379,23 +379,35 @@ def test_many_row_and_few_row_items_are_dispatched_side_by_side():
 
 
 def test_large_many_row_share_goes_to_the_tile_kernel(oracle):
-    """c5: the 16 roots (256 query rows per KV head, 137 GFLOP) become items of the 256-row tile kernel: one
-    request group of 32 per root and KV head, 4 chunks of 2048 tokens, on a multiple of 8 persistent
-    workgroups; the private leaves stay with the other kernel.  c2 and c3 (2 and 9 GFLOP of such work) and
-    plans with several query tokens per request keep everything in one kernel."""
+    """c5: the 16 roots (256 query rows per KV head, 137 GFLOP) become items of the 256-row tile: one request
+    group of 32 per root and KV head, the root's 8192 tokens in one item, a workgroup per item; the private
+    leaves (8 rows each) are the other items, so both kinds go out as one launch unless the caller says
+    otherwise.  c2 and c3 (2 and 9 GFLOP of such work) and plans with several query tokens per request have
+    no tile items."""
     w = wl.config5()
     f = w.forest
     items = _check_decode_plan(w, oracle)
     pool = fake_pool(w.num_pages, w.num_kv_heads, dtype=hkv.FP8_E4M3)
     plan = hkv.hkv_decode_plan_create(pool, f.nodes, f.node_pages, f.req_leaf, w.num_q_heads, hkv.PLAN_HOST_ONLY)
     n_tile = hkv.hkv_decode_plan_num_tile_items(plan)
-    assert n_tile == 16 * 8 * 4 and len(items) == n_tile + 4096
+    assert n_tile == 16 * 8 and len(items) == n_tile + 4096
     tiles = items[-n_tile:]
-    assert (tiles[:, 4] == 32).all() and (tiles[:, 1] == 2048).all() and (tiles[:, 7] < 16).all()
-    wgs = hkv.hkv_decode_plan_tile_workgroups(plan)
-    assert 8 <= wgs <= 192 and wgs % 8 == 0
+    assert (tiles[:, 4] == 32).all() and (tiles[:, 1] == 8192).all() and (tiles[:, 7] < 16).all()
+    assert hkv.hkv_decode_plan_tile_workgroups(plan) == 128 and hkv.hkv_decode_plan_is_fused(plan)
     assert (items[:-n_tile, 4] == 1).all()
     hkv.hkv_decode_plan_destroy(plan)
+    two = hkv.hkv_decode_plan_create_ex(pool, f.nodes, f.node_pages, f.req_leaf, w.num_q_heads, hkv.PLAN_HOST_ONLY, fused=-1,
+                                        tile_chunk=2048, tile_workgroups=96)
+    assert not hkv.hkv_decode_plan_is_fused(two) and hkv.hkv_decode_plan_num_tile_items(two) == 16 * 8 * 4
+    assert hkv.hkv_decode_plan_tile_workgroups(two) == 96
+    hkv.hkv_decode_plan_destroy(two)
+    # a forest with a node shared by 64 rows besides the big one keeps two kernels: such items synchronise per step
+    mixed = wl.make_forest([-1, 0] + [1] * 8 + [0] * 56, [4096, 512] + [64] * 64, list(range(2, 66)), np.arange(4096 // 16 + 512 // 16 + 64 * 4, dtype=np.int32))
+    mp = fake_pool(len(mixed.node_pages), 8)
+    plan = hkv.hkv_decode_plan_create_ex(mp, mixed.nodes, mixed.node_pages, mixed.req_leaf, 64, hkv.PLAN_HOST_ONLY, tile_min_gflop=-1)
+    assert hkv.hkv_decode_plan_num_tile_items(plan) > 0 and not hkv.hkv_decode_plan_is_fused(plan)
+    hkv.hkv_decode_plan_destroy(plan)
+    hkv.kv_pool_destroy(mp)
     multi = hkv.hkv_decode_plan_create_multi(pool, f.nodes, f.node_pages, f.req_leaf, 2, w.num_q_heads, hkv.PLAN_HOST_ONLY)
     assert hkv.hkv_decode_plan_num_tile_items(multi) == 0
     hkv.hkv_decode_plan_destroy(multi)
@@ -436,7 +448,7 @@ def test_decode_plan_create_ex_equals_the_four_creators_and_checks_its_settings(
     cut = items(hkv.hkv_decode_plan_create_ex(*args, w.num_q_heads, H, leaf_chunk=64, shared_chunk=128, max_rows=32))
     assert len(cut) > len(base) and cut[:, 1].sum() * 1 >= base[:, 1].sum()
     bad = [dict(leaf_chunk=24), dict(shared_chunk=4096), dict(max_rows=8), dict(max_rows=128), dict(pack=4), dict(stages=2),
-           dict(stages=6), dict(interleave=-2), dict(tile_min_rows=64), dict(tile_chunk=40), dict(tile_chunk=4096),
+           dict(stages=6), dict(interleave=-2), dict(tile_min_rows=64), dict(tile_chunk=40), dict(tile_chunk=16384), dict(fused=1), dict(fused=-2),
            dict(tile_workgroups=-1), dict(large_batch_updates=2), dict(tokens_per_req=17), dict(tokens_per_req=65, visible=np.zeros(65 * f.n_req, dtype=np.uint64)),
            dict(reserve_tokens=-1), dict(reserve_tokens=8, tokens_per_req=2)]
     for kw in bad:
