@@ -161,6 +161,7 @@ def bench_decode(runtime, hkv, w, steps: int, warmup: int, n_pools: int, profile
         "items": int(len(hkv.hkv_decode_plan_items(runners[0].plan))),
         "tile_items": int(hkv.hkv_decode_plan_num_tile_items(runners[0].plan)),
         "tile_workgroups": int(hkv.hkv_decode_plan_tile_workgroups(runners[0].plan)),
+        "one_launch": bool(hkv.hkv_decode_plan_is_fused(runners[0].plan)),
         "workgroups": int(hkv.hkv_decode_plan_num_workgroups(runners[0].plan)),
         "partials": int(hkv.hkv_decode_plan_num_parts(runners[0].plan)),
         "max_partials_per_row": int(hkv.hkv_decode_plan_max_parts(runners[0].plan)),
@@ -214,10 +215,12 @@ def bench_prefill(runtime, hkv, w, steps: int, warmup: int):
     torch.cuda.synchronize()
     kern_ms = ev0.elapsed_time(ev1) / steps
     tiles = int(len(hkv.hkv_prefill_plan_tiles(r.plan)))
+    # tiles that took the running-maximum fallback, per launch (the plan counts them over all its runs)
+    fallback = hkv.hkv_prefill_plan_fallback_tiles(r.plan) / (2 * steps + warmup)
     r.close()
     pool.close()
     torch.cuda.empty_cache()
-    return sec, kern_ms, tiles
+    return sec, kern_ms, tiles, fallback
 
 
 def bench_pool_write(runtime, w, steps: int):
@@ -652,11 +655,12 @@ def main() -> int:
         name = args.profile_workload
         if name == "c4":
             w4 = wl.config4()
-            s4, k4, t4 = bench_prefill(runtime, hkv, w4, max(1, min(args.steps, 10)), 2)
+            s4, k4, t4, fb4 = bench_prefill(runtime, hkv, w4, max(1, min(args.steps, 10)), 2)
             tf = w4.useful_flop() / (k4 * 1e-3) / 1e12
             print(json.dumps({"workload": w4.name, "kernel_ms": round(k4, 4), "useful_TFLOPs": round(tf, 2),
                               "mfma_bf16_frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
-                              "new_tokens_per_s": round(w4.total_q() / s4, 1), "tiles": t4}), flush=True)
+                              "new_tokens_per_s": round(w4.total_q() / s4, 1), "tiles": t4,
+                              "fallback_tiles_per_launch": fb4}), flush=True)
         else:
             # *_leaves / c5_roots / c3_shared: the forest with its shared nodes, resp. its leaves, cut down to one
             # block, to time the few-row items (private leaves) and the many-row items (shared nodes) apart
@@ -705,7 +709,9 @@ def main() -> int:
         },
         "roofline": {
             "bound": "hbm",
-            "kernel": "decode_node_kernel<fp8>" if not args.fp8_matrix else "decode_node_kernel<fp8 matrix>",
+            "kernel": ("decode_fused_kernel<fp8> (tile items and the other items in one launch)" if e5.get("one_launch") else
+                       "decode_node_kernel<fp8> + attn_tile_kernel<decode, fp8> side by side (span from the earlier begin "
+                       "to the later end)") if not args.fp8_matrix else "decode_node_kernel<fp8 matrix>",
             "achieved": round(achieved, 2),
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
@@ -751,13 +757,14 @@ def main() -> int:
             result["extra"][key]["plain_read_same_bytes_GBps"] = round(g, 1)
             log(f"{key} done")
         w4 = wl.config4()
-        s4, k4, t4 = bench_prefill(runtime, hkv, w4, 5, 2)
+        s4, k4, t4, fb4 = bench_prefill(runtime, hkv, w4, 5, 2)
         tflops = w4.useful_flop() / (k4 * 1e-3) / 1e12
         result["extra"]["c4_prefix_hit_prefill"] = {
             "new_tokens_per_s": round(w4.total_q() / s4, 1), "ms_per_step": round(s4 * 1e3, 4),
             "kernel_ms": round(k4, 4), "useful_TFLOPs": round(tflops, 2),
             "mfma_bf16_frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4), "new_tokens": int(w4.total_q()),
-            "useful_flop": int(w4.useful_flop()), "tiles": t4}
+            "useful_flop": int(w4.useful_flop()), "tiles": t4,
+            "fallback_tiles_per_launch": fb4}     # tiles that repeated with a running softmax maximum (about twice the cost each)
         # matrix-core ceiling with nothing else running: zero operands (nominal clock) and random ones
         # (the clock settles under the power limit), two wavefronts per SIMD as in the prefill kernel
         tf0, ghz0 = bp.mfma_bf16(100000, False, 2)

@@ -481,6 +481,11 @@ int hkv_prefill_plan_create_rows(hkv_pool *pool, const int32_t *q_row_begin, con
 int hkv_prefill_plan_destroy(hkv_prefill_plan *plan);
 /* Number of (request, query tile, kv head) workgroups the plan launches. */
 int32_t hkv_prefill_plan_num_tiles(const hkv_prefill_plan *plan);
+/* The prefill kernel keeps one softmax reference per row (the maximum of its first 32 scores); a tile in which a
+ * later score exceeds it by more than the exponent range allows repeats with a running maximum, at about
+ * twice the cost.  count (host): how many tiles did so over all runs of this plan so far (the call waits for
+ * the device).  bf16 and fp8 pools; always 0 for fp32 pools. */
+int hkv_prefill_plan_fallback_tiles(hkv_prefill_plan *plan, int64_t *count);
 /* Tile layout for tests, 8 int32 each: (req, q_begin, n_q, kv_head, q_row0, prefix_len, kv_len, bt_off). */
 int hkv_prefill_plan_tiles(const hkv_prefill_plan *plan, int32_t *tiles_out);
 

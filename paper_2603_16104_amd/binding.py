@@ -27,7 +27,7 @@ EXPORTS = [
     "kv_pool_num_free", "kv_pool_page_size", "kv_pool_refcount", "kv_pool_write", "kv_pool_append", "prefix_tree_flatten",
     "hkv_decode_plan_create_growing", "hkv_decode_plan_append", "hkv_decode_plan_append_tokens",
     "prefix_tree_flatten_paged", "prefix_tree_prefill_usage",
-    "lse_merge", "hkv_decode_plan_create", "hkv_decode_plan_create_multi", "hkv_decode_plan_create_tree", "hkv_decode_plan_create_ex", "hkv_prefill_plan_create_rows", "hkv_decode_plan_destroy", "hkv_decode_plan_workspace_bytes",
+    "lse_merge", "hkv_decode_plan_create", "hkv_decode_plan_create_multi", "hkv_decode_plan_create_tree", "hkv_decode_plan_create_ex", "hkv_prefill_plan_create_rows", "hkv_prefill_plan_fallback_tiles", "hkv_decode_plan_destroy", "hkv_decode_plan_workspace_bytes",
     "hkv_decode_plan_num_items", "hkv_decode_plan_num_workgroups", "hkv_decode_plan_num_parts", "hkv_decode_plan_items",
     "hkv_decode_plan_max_parts", "hkv_decode_plan_part_counts", "lse_merge_dense", "attn_decode_plan_run",
     "attn_decode_plan_run_static", "hkv_static_workspace_bytes",
@@ -438,6 +438,12 @@ def hkv_prefill_plan_create_rows(pool, q_row_begin, q_len, block_table, kv_len, 
                                               C.c_int32(len(kv_len)), C.c_int32(num_q_heads), C.c_uint32(flags),
                                               C.byref(out)))
     return out
+
+
+def hkv_prefill_plan_fallback_tiles(plan) -> int:
+    n = C.c_int64()
+    _check(lib().hkv_prefill_plan_fallback_tiles(plan, C.byref(n)))
+    return int(n.value)
 
 
 def hkv_prefill_plan_destroy(plan) -> None:

@@ -146,6 +146,7 @@ struct hkv_prefill_plan {
     // workspace (page i of the scratch = src_pages[i]); the device block table then holds scratch indices.
     std::vector<int32_t> src_pages;
     int32_t *d_src_pages = nullptr;
+    unsigned int *d_fallback = nullptr;  // tiles that repeated with a running maximum, over all runs of the plan
 };
 
 struct hkv_pool {
@@ -1685,8 +1686,13 @@ static int create_prefill_plan(hkv_pool *pool, const int32_t *cu_q, const int32_
     if (!(flags & HKV_PLAN_HOST_ONLY) && !pl->tiles.empty()) {
         size_t off_bt = align_up(sizeof(PrefillTile) * pl->tiles.size(), 256);
         size_t off_src = off_bt + align_up(sizeof(int32_t) * dev_table.size(), 256);
-        size_t total = off_src + align_up(sizeof(int32_t) * pl->src_pages.size(), 256) + 256;
+        size_t off_fb = off_src + align_up(sizeof(int32_t) * pl->src_pages.size(), 256);
+        size_t total = off_fb + 256;
         hipError_t e = hipMalloc(&pl->dev, total);
+        if (e == hipSuccess) {
+            pl->d_fallback = reinterpret_cast<unsigned int *>(static_cast<char *>(pl->dev) + off_fb);
+            e = hipMemset(pl->d_fallback, 0, 256);
+        }
         if (e == hipSuccess) {
             pl->d_tiles = static_cast<PrefillTile *>(pl->dev);
             pl->d_block_table = reinterpret_cast<int32_t *>(static_cast<char *>(pl->dev) + off_bt);
@@ -1768,6 +1774,16 @@ extern "C" int hkv_prefill_plan_tiles(const hkv_prefill_plan *plan, int32_t *til
     return HKV_OK;
 }
 
+extern "C" int hkv_prefill_plan_fallback_tiles(hkv_prefill_plan *plan, int64_t *count) {
+    if (!plan || !count) return fail(HKV_EINVAL, "hkv_prefill_plan_fallback_tiles: null argument");
+    *count = 0;
+    if (!plan->d_fallback) return HKV_OK;  // host-only plan, or a plan without tiles
+    unsigned int n = 0;
+    HKV_HIP(hipMemcpy(&n, plan->d_fallback, sizeof(n), hipMemcpyDeviceToHost));
+    *count = n;
+    return HKV_OK;
+}
+
 extern "C" size_t hkv_prefill_plan_workspace_bytes(const hkv_prefill_plan *plan) {
     if (!plan) return 0;
     return 2 * plan->src_pages.size() * (size_t)plan->pool->d.num_kv_heads * HKV_PAGE_SIZE * HKV_HEAD_DIM * sizeof(uint16_t);
@@ -1805,7 +1821,7 @@ extern "C" int attn_prefill_plan_run_ws(hkv_prefill_plan *plan, const void *q, f
         view = PoolView{k_dst, v_dst, nullptr, nullptr, view.num_kv_heads, HKV_BF16};
     }
     PrefillLaunch a{view, q, plan->d_tiles, plan->d_block_table, out, lse_out,
-                    (int32_t)plan->tiles.size(), plan->num_q_heads, scale};
+                    (int32_t)plan->tiles.size(), plan->num_q_heads, scale, plan->d_fallback};
     HKV_HIP(launch_prefill(a, static_cast<hipStream_t>(stream)));
     return HKV_OK;
 }

@@ -91,6 +91,7 @@ struct PrefillLaunch {
     int32_t n_tiles;
     int32_t num_q_heads;
     float scale;
+    unsigned int *fallback_tiles;  // device, may be null: counts the tiles that had to repeat with a running maximum
 };
 
 struct PoolWriteLaunch {

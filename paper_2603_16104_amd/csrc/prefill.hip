@@ -33,6 +33,7 @@ hipError_t launch_prefill(const PrefillLaunch &p, hipStream_t s) {
     a.scale = p.scale;
     a.out = p.out;
     a.lse_out = p.lse_out;
+    a.fallback_tiles = p.fallback_tiles;
     hipLaunchKernelGGL((attn_tile_kernel<false, false>), dim3(p.n_tiles), dim3(kThreads), 0, s, a);
     return hipGetLastError();
 }

@@ -109,6 +109,7 @@ struct TileArgs {
     float *down_parts;
     int32_t max_parts;
     const int32_t *q_rows;       // decode items, may be null: row r of the plan reads row q_rows[r] of q
+    unsigned int *fallback_tiles;  // may be null: incremented once per tile that takes the running-maximum path
 };
 
 // DECODE: decode work items (persistent workgroups, partial results) instead of prefill tiles.
@@ -552,6 +553,7 @@ __device__ __forceinline__ void body(const TileArgs &a, char *lds, int first, in
     if (__builtin_amdgcn_ballot_w64(!(l_run < kSumLimit))) sBail = 1;
     __syncthreads();
     const bool bail = sBail != 0;
+    if (bail && tid == 0 && a.fallback_tiles) atomicAdd(a.fallback_tiles, 1u);
     float m_fin = mc;
 
     // =========================================================================================

@@ -656,6 +656,13 @@ def test_prefill_late_dominant_key(gpu, oracle, beta):
     import torch
     torch.cuda.synchronize()
     got_o, got_l = gpu.bf16_tensor_to_f64(r.out), r.lse.cpu().numpy()
+    from paper_2603_16104_amd import binding as hkv
+    n_fallback, n_tiles = hkv.hkv_prefill_plan_fallback_tiles(r.plan), len(hkv.hkv_prefill_plan_tiles(r.plan))
+    # the plan counts the tiles that repeated with a running maximum: none in the first case, the ones behind the key else
+    assert n_fallback == 0 if beta < 5 else 0 < n_fallback <= n_tiles, (beta, n_fallback, n_tiles)
+    r.run()
+    torch.cuda.synchronize()
+    assert hkv.hkv_prefill_plan_fallback_tiles(r.plan) == 2 * n_fallback      # cumulative over the plan's runs
     r.close()
     dp.close()
     check_close(got_o, exp_o, w.name)
