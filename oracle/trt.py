@@ -28,6 +28,26 @@ Readings taken where the paper is silent (the same ones the library takes)
       are only described in prose; the reading is written out at `cache_aware_schedule`.
       PARITY UNPINNED for those choices: the tests pin validity, determinism, agreement of the
       reported times with the evaluator, and the paper's three-call example, not optimality.
+  R6  PartitionWorkflow (named in the algorithm, described in one sentence: operators are partitioned
+      across the workers and replicated per assignment to balance load).  Reading: the calls of a batch
+      fall into groups that share data (connected through dependencies: one group per input query of
+      the batch); a group goes to one worker as a whole, so an operator is replicated on every worker
+      that received one of its queries; groups are placed largest estimated token usage first, each on
+      the worker with the least usage so far (ties: lower number).  Estimated usage of a call =
+      len_out * omega(its whole prompt) + u_d (no sharing assumed).  Written out at `partition_workflow`.
+      PARITY UNPINNED for the placement rule; the tests pin what any reading must satisfy (a partition,
+      no dependency across workers, the greedy bound on the imbalance, closed forms).
+  R7  Nested sequences (the paragraph below the algorithm): a worker's final schedule is a sequence of
+      inner sequences; an inner sequence holds the calls of that worker that share their static prompt
+      (the first node below the root on their path: the system prompt of an operator family), in the
+      order in which the recursion emitted them (query by query, as the depth-first walk leaves them).
+      The intermediate buffer collects emitted calls per static prompt and releases a family as one
+      inner sequence when its last call on that worker has been emitted.  Written out at `nested_sequences`.
+  R8  Soft schedule, best-effort execution: a worker that falls free issues the first call of its
+      nested order whose inputs have all been issued (it may wait for them to arrive, but does not
+      overtake within what can run), so an order that the dependencies contradict is repaired at run time
+      instead of being rejected.  Written out at `run_soft_schedule`; on orders the dependencies allow
+      it equals `evaluate_schedule`.
 """
 from __future__ import annotations
 
@@ -335,3 +355,113 @@ def topological_order_of_deps(deps: Sequence[Sequence[int]]) -> List[int]:
         else:
             raise ValueError("dependency cycle")
     return order
+
+
+# ---------------------------------------------------------------------------------------------
+# PartitionWorkflow (R6), nested sequences (R7), best-effort execution of a soft schedule (R8)
+
+
+def partition_workflow(calls: Sequence[Call], n_workers: int) -> List[int]:
+    """Worker of every call.  Groups = connected components of the dependency graph; cost of a group =
+    sum over its calls of len_out * omega(prompt) + u_d with omega as in R1; groups in order of
+    decreasing cost (ties: smaller first call) each go to the worker with the least cost so far
+    (ties: lower number)."""
+    n = len(calls)
+    if n_workers < 1:
+        raise ValueError("n_workers")
+    comp = list(range(n))
+
+    def find(x):
+        while comp[x] != x:
+            x = comp[x]
+        return x
+
+    for c in range(n):
+        for x in calls[c].deps():
+            if not 0 <= x < n:
+                raise ValueError("dependency outside the batch")
+            a, b = find(c), find(x)
+            if a != b:
+                comp[max(a, b)] = min(a, b)
+    cost = [0] * n
+    for c in range(n):
+        omega = sum(1 if sym >= 0 else calls[-(sym + 1)].len_out for sym in calls[c].template)
+        cost[c] = calls[c].len_out * omega + decode_usage(calls[c].len_out)
+    groups: Dict[int, List[int]] = {}
+    for c in range(n):
+        groups.setdefault(find(c), []).append(c)
+    order = sorted(groups, key=lambda g: (-sum(cost[c] for c in groups[g]), g))
+    load = [0] * n_workers
+    worker = [0] * n
+    for g in order:
+        w = min(range(n_workers), key=lambda i: (load[i], i))
+        for c in groups[g]:
+            worker[c] = w
+        load[w] += sum(cost[c] for c in groups[g])
+    return worker
+
+
+def static_prompt_node(t: TRT, call: int) -> int:
+    """The first node below the root on the call's path (its leaf itself for an empty prompt)."""
+    v = t.leaf_of_call[call]
+    while t.parent[v] > 0:
+        v = t.parent[v]
+    return v
+
+
+def nested_sequences(t: TRT, sigma: Sequence[Sequence[int]]) -> List[List[List[int]]]:
+    """Per worker the inner sequences in the order in which the buffer releases them (R7)."""
+    out: List[List[List[int]]] = []
+    for seq in sigma:
+        total: Dict[int, int] = {}
+        for c in seq:
+            g = static_prompt_node(t, c)
+            total[g] = total.get(g, 0) + 1
+        buffer: Dict[int, List[int]] = {}
+        released: List[List[int]] = []
+        for c in seq:
+            g = static_prompt_node(t, c)
+            buffer.setdefault(g, []).append(c)
+            if len(buffer[g]) == total[g]:
+                released.append(buffer.pop(g))
+        out.append(released)
+    return out
+
+
+def run_soft_schedule(t: TRT, order: Sequence[Sequence[int]], capacity: int):
+    """Best-effort execution of per-worker priority orders (the flattened nested sequences) under the cost
+    model (R8).  Repeatedly: every worker with calls left names the first call of its order whose
+    dependencies have all been issued; its start would be the larger of the worker's free step and, over the
+    dependencies, completion + precedence delay; the worker whose candidate starts earliest (ties: lower
+    number) issues it.  Returns (sigma, B, C, T): the order in which each worker ran its calls, start and
+    completion per call, total token step (scaled by M as in evaluate_schedule)."""
+    n = t.n_calls
+    if sorted(c for seq in order for c in seq) != list(range(n)):
+        raise ValueError("the orders are no partition of the calls")
+    issued = [False] * n
+    B, Cc = [0] * n, [0] * n
+    left = [list(seq) for seq in order]
+    sigma: List[List[int]] = [[] for _ in order]
+    free = [0] * len(order)
+    for _ in range(n):
+        best = None
+        for w, seq in enumerate(left):
+            cand = next((c for c in seq if all(issued[x] for x in t.deps[c])), None)
+            if cand is None:
+                continue
+            b = free[w]
+            for x in t.deps[cand]:
+                b = max(b, Cc[x] + capacity * t.len_out[x])
+            if best is None or b < best[0]:
+                best = (b, w, cand)
+        if best is None:
+            raise ValueError("dependency cycle")
+        b, w, c = best
+        prev = sigma[w][-1] if sigma[w] else -1
+        B[c] = b
+        Cc[c] = b + t.len_out[c] * prefill_usage(t, prev, c) + decode_usage(t.len_out[c])
+        free[w] = Cc[c]
+        issued[c] = True
+        sigma[w].append(c)
+        left[w].remove(c)
+    return sigma, B, Cc, (max(Cc) if n else 0)

@@ -434,7 +434,7 @@ def all_configs():
 # Workflow shapes for the scheduling layer: lists of LLM calls with prefix templates.
 # A template is a list of int symbols: s >= 0 static token id, s < 0 the output of call -(s+1).
 # Only the structure of the paper's primitive workflows is used (Section 7, "Workloads": map-reduce,
-# multi-agent debate, reflection); token ids and lengths are synthetic.
+# multi-agent debate, reflection, iterative refinement, parallel chains); token ids and lengths are synthetic.
 
 
 class Workflow:
@@ -510,6 +510,36 @@ def workflow_reflect(n_queries: int = 4, sys_len: int = 64, q_len: int = 48, len
         a = w.add(s_ans + question, len_out, wk)
         c = w.add(s_crit + question + [Workflow.out(a)], len_out, wk)
         w.add(s_rev + question + [Workflow.out(a), Workflow.out(c)], len_out, wk)
+    return w
+
+
+def workflow_iterative(n_queries: int = 4, n_chunks: int = 6, sys_len: int = 64, chunk_len: int = 96, len_out: int = 32,
+                       n_workers: int = 1) -> Workflow:
+    """Iterative refinement: per input item its chunks are summarised one after the other by one summariser,
+    [system prompt | chunk j | summary so far] (the first call has no summary yet)."""
+    w = Workflow("iterative")
+    sys_first, sys_refine = w.fresh_tokens(sys_len), w.fresh_tokens(sys_len)
+    for q in range(n_queries):
+        wk = q % n_workers
+        prev = -1
+        for j in range(n_chunks):
+            chunk = w.fresh_tokens(chunk_len)
+            prev = w.add((sys_first if j == 0 else sys_refine) + chunk + ([Workflow.out(prev)] if j else []), len_out, wk)
+    return w
+
+
+def workflow_parallel(n_queries: int = 3, n_experts: int = 7, n_chunks: int = 6, sys_len: int = 64, chunk_len: int = 96,
+                      len_out: int = 32, n_workers: int = 1) -> Workflow:
+    """Parallel chains: per input item every expert reads every chunk, [expert system prompt | chunk]; a
+    writer aggregates all insights, [writer system prompt | all expert outputs]."""
+    w = Workflow("parallel")
+    exp_sys = [w.fresh_tokens(sys_len) for _ in range(n_experts)]
+    writer_sys = w.fresh_tokens(sys_len)
+    for q in range(n_queries):
+        wk = q % n_workers
+        chunks = [w.fresh_tokens(chunk_len) for _ in range(n_chunks)]
+        insights = [w.add(exp_sys[e] + chunks[k], len_out, wk) for e in range(n_experts) for k in range(n_chunks)]
+        w.add(writer_sys + [Workflow.out(c) for c in insights], len_out, wk)
     return w
 
 

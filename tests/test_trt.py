@@ -213,6 +213,186 @@ def test_oracle_schedule_groups_shared_prefixes():
     assert T <= O.evaluate_schedule(t, [opwise], 8192)[2]
 
 
+# ------------------------------------------------------------------ oracle pins: partition, nested sequences, soft execution
+
+def two_operator_example(n_queries=3, sys_len=32, q_len=16, len_out=8):
+    """The paper's tree figure: operators 2 and 3 start with the same static system prompt, followed by a
+    question prompt that is unique to each query of the batch; operator 3 also reads the output of operator 1,
+    which has a system prompt of its own."""
+    w = wl.Workflow("two_operators")
+    sys_a, sys_b = w.fresh_tokens(sys_len), w.fresh_tokens(sys_len)
+    ids = []
+    for q in range(n_queries):
+        question = w.fresh_tokens(q_len)
+        o1 = w.add(sys_a + question, len_out)
+        o2 = w.add(sys_b + question, len_out)
+        o3 = w.add(sys_b + question + [wl.Workflow.out(o1)], len_out)
+        ids.append((o1, o2, o3))
+    return w, ids
+
+
+@pytest.mark.parametrize("make", [lambda: wl.workflow_map_reduce(6, 3), lambda: wl.workflow_debate(5, 3, 2), lambda: wl.workflow_reflect(7),
+                                  lambda: wl.workflow_iterative(5, 4), lambda: wl.workflow_parallel(4, 3, 2),
+                                  lambda: wl.random_workflow(3, n_calls=30), lambda: wl.random_workflow(8, n_calls=30, p_placeholder=0.05)])
+@pytest.mark.parametrize("n_workers", [1, 2, 3])
+def test_oracle_partition_invariants(make, n_workers):
+    """What any reading of PartitionWorkflow must give: every call on exactly one worker, no dependency between
+    workers (a query's calls stay together, so its prefixes are cached where they are used), and the greedy
+    guarantee: no worker carries more than the mean load plus one group."""
+    w = make()
+    calls = calls_of(w)
+    worker = O.partition_workflow(calls, n_workers)
+    assert len(worker) == len(calls) and all(0 <= x < n_workers for x in worker)
+    for c, call in enumerate(calls):
+        assert all(worker[x] == worker[c] for x in call.deps())
+    lo = [c.len_out for c in calls]
+    cost = [c.len_out * sym_weight(c.template, lo) + c.len_out * (c.len_out + 1) // 2 for c in calls]
+    # groups by brute force: flood fill over the undirected dependency graph
+    adj = {c: set() for c in range(len(calls))}
+    for c, call in enumerate(calls):
+        for x in call.deps():
+            adj[c].add(x)
+            adj[x].add(c)
+    seen, groups = set(), []
+    for c in range(len(calls)):
+        if c in seen:
+            continue
+        todo, g = [c], []
+        while todo:
+            v = todo.pop()
+            if v in seen:
+                continue
+            seen.add(v)
+            g.append(v)
+            todo.extend(adj[v])
+        groups.append(g)
+    assert all(len({worker[c] for c in g}) == 1 for g in groups)
+    load = [sum(cost[c] for c in range(len(calls)) if worker[c] == i) for i in range(n_workers)]
+    biggest = max((sum(cost[c] for c in g) for g in groups), default=0)
+    assert max(load) <= sum(cost) / n_workers + biggest
+    assert O.partition_workflow(calls, n_workers) == worker
+    assert set(O.partition_workflow(calls, 1)) <= {0}
+
+
+def test_oracle_partition_closed_forms():
+    """Equal groups go round the workers in turn; one heavy group and many light ones: the heavy one sits alone
+    until the others have caught up (the textbook behaviour of largest-first list scheduling)."""
+    w = wl.workflow_reflect(n_queries=6)
+    worker = O.partition_workflow(calls_of(w), 3)
+    assert [worker[3 * q] for q in range(6)] == [0, 1, 2, 0, 1, 2]
+    h = wl.Workflow("one_heavy")
+    big = h.add(h.fresh_tokens(1000), 10)                 # cost 10 * 1000 + 55
+    small = [h.add(h.fresh_tokens(100), 10) for _ in range(8)]      # cost 1055 each
+    worker = O.partition_workflow(calls_of(h), 2)
+    assert worker[big] == 0 and all(worker[c] == 1 for c in small)
+    with pytest.raises(ValueError):
+        O.partition_workflow(calls_of(h), 0)
+
+
+def test_oracle_nested_sequences_paper_figure():
+    """The paragraph below the scheduling algorithm: operators that share a static system prompt form one
+    inner sequence, inside which the calls run query by query (the question prompt stays cached between
+    operator 2 and operator 3 of a query); an operator-by-operator order alternates between the queries'
+    question prompts and prefills each of them once more.  Closed forms of the prefill usage of both orders."""
+    n_q, sys_len, q_len, len_out = 4, 32, 16, 8
+    w, ids = two_operator_example(n_q, sys_len, q_len, len_out)
+    t = O.build_trt(calls_of(w))
+    sigma, _, _, _ = O.cache_aware_schedule(t, 1, 1)      # short precedence delays: operator 1's outputs arrive in time
+    nested = O.nested_sequences(t, sigma)
+    fam_a = [i[0] for i in ids]
+    fam_b = [c for i in ids for c in (i[1], i[2])]
+    assert nested == [[fam_a, fam_b]], nested            # operator by operator across, query by query within
+    up = lambda seq: sum(O.prefill_usage(t, seq[j - 1] if j else -1, c) for j, c in enumerate(seq))
+    flat = fam_a + fam_b
+    opwise = [i[k] for k in range(3) for i in ids]
+    # family A: the system prompt once, a question per query; family B: the same plus operator 1's output
+    # (len_out tokens) per query, operator 3 of a query reusing the question operator 2 has just prefilled
+    assert up(flat) == (sys_len + n_q * q_len) + (sys_len + n_q * (q_len + len_out))
+    # operator by operator every operator-3 call follows another query's call and prefills its question again
+    assert up(opwise) == up(flat) + n_q * q_len
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_oracle_nested_sequences_invariants(seed):
+    """A regrouping of each worker's order: every call once, on its worker; an inner sequence holds calls of one
+    static prompt only, each static prompt of a worker appears in exactly one inner sequence, calls keep their
+    relative order inside it, and sequences are released in the order of their last call."""
+    w = wl.random_workflow(seed, n_calls=24, n_workers=2)
+    t = O.build_trt(calls_of(w))
+    sigma, _, _, _ = O.cache_aware_schedule(t, 2, 50)
+    nested = O.nested_sequences(t, sigma)
+    assert len(nested) == 2
+    for i, (seq, inner) in enumerate(zip(sigma, nested)):
+        assert sorted(c for s_ in inner for c in s_) == sorted(seq)
+        fams = [{O.static_prompt_node(t, c) for c in s_} for s_ in inner]
+        assert all(len(f) == 1 for f in fams)
+        assert len({next(iter(f)) for f in fams}) == len(inner)
+        pos = {c: j for j, c in enumerate(seq)}
+        for s_ in inner:
+            assert [pos[c] for c in s_] == sorted(pos[c] for c in s_)
+        last = [max(pos[c] for c in s_) for s_ in inner]
+        assert last == sorted(last)
+    # the static prompt is the first node below the root: the common prefix of a family is at least that node's segment
+    for c in range(w.n_calls):
+        v = O.static_prompt_node(t, c)
+        assert t.parent[v] == 0 and v in ([t.leaf_of_call[c]] + t.path(t.leaf_of_call[c]))
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_oracle_soft_execution_equals_the_evaluator_on_feasible_orders(seed):
+    """Where the priority order respects the dependencies, best-effort execution runs it as it stands, and the
+    evaluator (pinned above against longest paths) gives the same times."""
+    w = wl.random_workflow(seed, n_calls=14, n_workers=2)
+    t = O.build_trt(calls_of(w))
+    sigma, B, C, T = O.cache_aware_schedule(t, 2, 40)
+    assert O.run_soft_schedule(t, sigma, 40) == (sigma, B, C, T)
+
+
+@pytest.mark.parametrize("make", [lambda: wl.workflow_debate(3, 3, 2), lambda: wl.workflow_debate(4, 2, 3, n_workers=2),
+                                  lambda: wl.workflow_iterative(3, 4), lambda: wl.workflow_parallel(2, 3, 2),
+                                  lambda: wl.random_workflow(5, n_calls=20, n_workers=2)])
+def test_oracle_soft_execution_repairs_orders_the_dependencies_contradict(make):
+    """Debate: agent A's second round needs B's first and the other way round, so inner sequences per agent
+    cannot run back to back; the flattened nested order is infeasible as it stands (the evaluator rejects it or
+    not), best-effort execution still runs every call once, on its worker, never before its inputs are there,
+    one call at a time per worker, and what it reports agrees with the evaluator on the order it realised."""
+    w = make()
+    t = O.build_trt(calls_of(w))
+    n_workers = max(w.worker) + 1
+    sigma, _, _, _ = O.cache_aware_schedule(t, n_workers, 64)
+    nested = O.nested_sequences(t, sigma)
+    prio = [[c for seq in inner for c in seq] for inner in nested]
+    real, B, C, T = O.run_soft_schedule(t, prio, 64)
+    assert [sorted(s_) for s_ in real] == [sorted(s_) for s_ in prio]
+    for c in range(w.n_calls):
+        for x in t.deps[c]:
+            assert B[c] >= C[x] + 64 * t.len_out[x]
+    for seq in real:
+        for a, b in zip(seq, seq[1:]):
+            assert B[b] >= C[a]
+    assert (B, C, T) == O.evaluate_schedule(t, real, 64)
+    # a call is overtaken only by calls that could run: whenever a call ran before an earlier one of the
+    # priority order, that earlier one still missed an input at that moment
+    for i, seq in enumerate(real):
+        pos = {c: j for j, c in enumerate(prio[i])}
+        for j, c in enumerate(seq):
+            for d in seq[j + 1:]:
+                if pos[d] < pos[c]:
+                    assert any(x not in seq[:j] and w.worker[x] == i or w.worker[x] != i for x in t.deps[d])
+
+
+def test_oracle_soft_execution_worked_example():
+    """Two calls A, B and a third that reads both, priority order [third, A, B] on one worker: the third waits;
+    A and B run in order, then the third.  Times by hand (M = 10): A: 5 tokens, 2 out; B: 3 tokens, 1 out."""
+    calls = [O.Call([-2, -3], 1), O.Call([1, 2, 3, 4, 5], 2), O.Call([7, 8, 9], 1)]
+    t = O.build_trt(calls)
+    real, B, C, T = O.run_soft_schedule(t, [[0, 1, 2]], 10)
+    assert real == [[1, 2, 0]]
+    # A: U = 2 * 5 + 3 = 13 -> [0, 13]; B: U = 1 * 3 + 1 = 4 -> [13, 17]; third: inputs at 13 + 20 and 17 + 10,
+    # prompt = the two outputs (2 + 1 tokens), nothing shared with B: U = 1 * 3 + 1 = 4 -> [33, 37]
+    assert (B[1], C[1], B[2], C[2], B[0], C[0], T) == (0, 13, 13, 17, 33, 37, 37)
+
+
 # ------------------------------------------------------------------ library against the oracle
 
 @pytest.fixture(scope="module")
