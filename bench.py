@@ -248,6 +248,12 @@ def bench_workflow(runtime, hkv, wl, shape: str):
     elif shape == "debate":
         wf = wl.workflow_debate(n_queries=6, n_agents=3, rounds=3, sys_len=4096, q_len=2048, len_out=512)
         per_query = 9
+    elif shape == "iterative":
+        wf = wl.workflow_iterative(n_queries=8, n_chunks=6, sys_len=1024, chunk_len=4096, len_out=512)
+        per_query = 6
+    elif shape == "parallel":
+        wf = wl.workflow_parallel(n_queries=3, n_experts=7, n_chunks=6, sys_len=2048, chunk_len=4096, len_out=256)
+        per_query = 43
     else:
         wf = wl.workflow_reflect(n_queries=12, sys_len=4096, q_len=4096, len_out=512)
         per_query = 3
@@ -256,13 +262,18 @@ def bench_workflow(runtime, hkv, wl, shape: str):
     n = wf.n_calls
     longest_pages = max(len(runtime.workflow_prompt_tokens(wf, c)) for c in range(n)) // 16 + 1
     helium = hkv.trt_schedule(r.tree, 1, capacity)[0][0]
+    # the same schedule as nested sequences (one inner sequence per static prompt), run best-effort
+    nested = hkv.trt_nested(r.tree, [helium])[0]
+    soft = hkv.trt_run_soft(r.tree, [[c for seq in nested for c in seq]], capacity)[0][0]
     orders = {
         "cache_aware_schedule": (helium, True),
+        "nested_sequences_best_effort": (soft, True),
         "query_by_query": (list(range(n)), True),
         "operator_by_operator": ([q * per_query + o for o in range(per_query) for q in range(n // per_query)], True),
         "no_prefix_reuse": (helium, False),
     }
     res = {"workflow": wf.name, "calls": n, "tree_nodes": int(len(r.nodes["parent"])), "capacity_M": capacity,
+           "inner_sequences": len(nested),
            "layer": "32 q / 8 kv heads, head_dim 128, bf16", "orders": {}}
     for name, (seq, cache) in orders.items():
         usage = r.prepare(seq, cache)
@@ -592,7 +603,7 @@ def main() -> int:
     ap.add_argument("--profile-workload", choices=["c2", "c3", "c4", "c5", "c5_leaves", "c5_roots", "c3_leaves", "c3_shared"],
                     default=None,
                     help="run only this workload for a few steps and print its figures (for rocprofv3 runs; not the headline line)")
-    ap.add_argument("--workflow", choices=["map_reduce", "debate", "reflect"], default=None,
+    ap.add_argument("--workflow", choices=["map_reduce", "debate", "reflect", "iterative", "parallel"], default=None,
                     help="scheduling-layer experiment: run the prefill side of a synthetic workflow on one worker "
                          "under several call orders and print token steps beside measured GPU time (not the headline line)")
     ap.add_argument("--sweep-read-probe", action="store_true",

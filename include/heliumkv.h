@@ -602,6 +602,37 @@ int trt_evaluate(const hkv_trt *tree, const int32_t *sigma_indptr, const int32_t
 int trt_schedule(const hkv_trt *tree, int32_t n_workers, int64_t capacity, int32_t *sigma_indptr,
                  int32_t *sigma, int64_t *B, int64_t *C, int64_t *T);
 
+/* PartitionWorkflow (Section 5, first step of the scheduling algorithm: operators are partitioned across
+ * the workers and replicated per assignment to balance load).  The calls of a batch fall into groups
+ * connected by dependencies (one per input query); a group goes to one worker as a whole, so an operator is
+ * replicated on every worker that received one of its queries and no dependency crosses workers.  Groups are
+ * placed in order of decreasing estimated token usage (ties: smaller first call), each on the worker with
+ * the least usage so far (ties: lower number); usage of a call = len_out * omega(prompt) + len_out
+ * (len_out + 1) / 2 with a placeholder counted as the output length of its call.  Templates as for
+ * trt_build; worker: host [n_calls], out (feed it to trt_build).  EINVAL / ERANGE as trt_build. */
+int trt_partition(const int32_t *tmpl_indptr, const int32_t *tmpl_syms, const int32_t *len_out, int32_t n_calls,
+                  int32_t n_workers, int32_t *worker);
+/* Nested sequences (Section 5, paragraph below the scheduling algorithm): a worker's schedule as inner
+ * sequences of the calls that share their static prompt (the first node below the root on their path), in
+ * the order of sigma inside; the intermediate buffer releases an inner sequence when the last call of its
+ * family on that worker has been emitted, so inner sequences appear in the order of their last call.
+ * sigma as trt_schedule returns it.  Outputs (host): seq_indptr [n_workers + 1]: worker i owns the inner
+ * sequences seq_indptr[i] .. seq_indptr[i+1] - 1; seq_begin [n_calls + 1] (the first n_seq + 1 entries are
+ * written): sequence s is nested[seq_begin[s] .. seq_begin[s+1] - 1]; nested [n_calls].
+ * EINVAL / ERANGE if sigma is no partition of the calls. */
+int trt_nested(const hkv_trt *tree, const int32_t *sigma_indptr, const int32_t *sigma, int32_t n_workers,
+               int32_t *seq_indptr, int32_t *seq_begin, int32_t *nested);
+/* Best-effort execution of a soft schedule under the cost model of trt_evaluate (workers "execute
+ * best-effort, buffering and issuing ready LLM calls ... while preserving cache-friendly ordering"): order
+ * is one priority order per worker (e.g. the flattened nested sequences), which the dependencies may
+ * contradict.  Repeatedly, every worker with calls left names the first call of its order whose dependencies
+ * have all been issued; the worker whose candidate can start earliest (ties: lower number) issues it at that
+ * step.  Outputs: sigma [n_calls] (worker i's realised order in the slots of order_indptr), B, C (may be
+ * NULL), T.  On an order that respects the dependencies the result equals trt_evaluate's.  ETREE on a
+ * dependency cycle. */
+int trt_run_soft(const hkv_trt *tree, const int32_t *order_indptr, const int32_t *order, int32_t n_workers,
+                 int64_t capacity, int32_t *sigma, int64_t *B, int64_t *C, int64_t *T);
+
 #ifdef __cplusplus
 }
 #endif

@@ -38,7 +38,7 @@ EXPORTS = [
     "attn_prefill_workspace_bytes",
     "kv_cache_create", "kv_cache_destroy", "kv_cache_acquire", "kv_cache_release", "kv_cache_unpin", "kv_cache_stats",
     "trt_build", "trt_destroy", "trt_num_nodes", "trt_num_syms", "trt_num_calls", "trt_nodes", "trt_prefill_usage",
-    "trt_evaluate", "trt_schedule",
+    "trt_evaluate", "trt_schedule", "trt_partition", "trt_nested", "trt_run_soft",
 ]
 
 
@@ -550,6 +550,42 @@ def trt_schedule(tree, n_workers: int, capacity: int):
     _check(lib().trt_schedule(tree, C.c_int32(n_workers), C.c_int64(capacity), _hp(indptr), _hp(flat), _hp(B), _hp(Cc),
                               C.byref(T)))
     return [flat[indptr[i]:indptr[i + 1]].tolist() for i in range(n_workers)], B, Cc, int(T.value)
+
+
+def trt_partition(templates, len_out, n_workers: int) -> np.ndarray:
+    """Worker of every call (PartitionWorkflow)."""
+    indptr = np.zeros(len(templates) + 1, dtype=np.int32)
+    for i, t in enumerate(templates):
+        indptr[i + 1] = indptr[i] + len(t)
+    syms = _host_i32([s for t in templates for s in t])
+    lo = _host_i32(len_out)
+    worker = np.zeros(len(templates), dtype=np.int32)
+    _check(lib().trt_partition(_hp(indptr), _hp(syms), _hp(lo), C.c_int32(len(templates)), C.c_int32(n_workers),
+                               _hp(worker)))
+    return worker
+
+
+def trt_nested(tree, sigma):
+    """sigma: one list of calls per worker.  Returns per worker the list of inner sequences (lists of calls)."""
+    nc = _check(lib().trt_num_calls(tree))
+    indptr, flat = _sigma_arrays(sigma)
+    seq_indptr = np.zeros(len(sigma) + 1, dtype=np.int32)
+    seq_begin, nested = np.zeros(nc + 1, dtype=np.int32), np.zeros(nc, dtype=np.int32)
+    _check(lib().trt_nested(tree, _hp(indptr), _hp(flat), C.c_int32(len(sigma)), _hp(seq_indptr), _hp(seq_begin),
+                            _hp(nested)))
+    return [[nested[seq_begin[s]:seq_begin[s + 1]].tolist() for s in range(seq_indptr[i], seq_indptr[i + 1])]
+            for i in range(len(sigma))]
+
+
+def trt_run_soft(tree, order, capacity: int):
+    """order: one priority list of calls per worker.  Returns (realised sigma, B, C, T)."""
+    nc = _check(lib().trt_num_calls(tree))
+    indptr, flat = _sigma_arrays(order)
+    sigma = np.zeros(nc, dtype=np.int32)
+    B, Cc, T = _host_i64(nc), _host_i64(nc), C.c_int64(0)
+    _check(lib().trt_run_soft(tree, _hp(indptr), _hp(flat), C.c_int32(len(order)), C.c_int64(capacity), _hp(sigma),
+                              _hp(B), _hp(Cc), C.byref(T)))
+    return [sigma[indptr[i]:indptr[i + 1]].tolist() for i in range(len(order))], B, Cc, int(T.value)
 
 
 # ---------------------------------------------------------------------------------------------

@@ -396,3 +396,179 @@ extern "C" int trt_schedule(const hkv_trt *t, int32_t n_workers, int64_t capacit
     *T = mx;
     return HKV_OK;
 }
+
+// ---------------------------------------------------------------------------------------------
+// PartitionWorkflow, nested sequences, best-effort execution of a soft schedule (Section 5, the
+// scheduling algorithm and the paragraph below it; the paper names these steps and describes them in
+// prose, the rules taken here are stated at each function)
+
+// Groups of calls connected by dependencies (one per input query of a batch) go to one worker as a whole,
+// largest estimated token usage first, each to the worker with the least usage so far (ties: lower number).
+// Estimated usage of a call: len_out * omega(prompt) + len_out (len_out + 1) / 2, omega counting a static
+// token as 1 and a placeholder as the output length of the call it stands for.
+extern "C" int trt_partition(const int32_t *tmpl_indptr, const int32_t *tmpl_syms, const int32_t *len_out, int32_t n_calls,
+                             int32_t n_workers, int32_t *worker) {
+    if (n_calls < 0 || n_workers < 1 || (n_calls > 0 && (!tmpl_indptr || !len_out || !worker)))
+        return fail(HKV_EINVAL, "trt_partition: bad argument");
+    if (n_calls > 0 && tmpl_indptr[0] != 0) return fail(HKV_EINVAL, "trt_partition: tmpl_indptr[0] must be 0");
+    const int n = n_calls;
+    std::vector<int32_t> comp(n);
+    for (int c = 0; c < n; ++c) comp[c] = c;
+    auto find = [&](int x) {
+        while (comp[x] != x) x = comp[x];
+        return x;
+    };
+    std::vector<int64_t> cost(n, 0);
+    for (int c = 0; c < n; ++c) {
+        if (tmpl_indptr[c + 1] < tmpl_indptr[c]) return fail(HKV_EINVAL, "trt_partition: tmpl_indptr decreases at call %d", c);
+        if (len_out[c] < 0) return fail(HKV_ERANGE, "trt_partition: call %d has negative output length", c);
+        if (tmpl_indptr[c + 1] > tmpl_indptr[c] && !tmpl_syms) return fail(HKV_EINVAL, "trt_partition: null tmpl_syms");
+    }
+    for (int c = 0; c < n; ++c) {
+        int64_t omega = 0;
+        for (int k = tmpl_indptr[c]; k < tmpl_indptr[c + 1]; ++k) {
+            const int32_t s = tmpl_syms[k];
+            if (s >= 0) {
+                ++omega;
+                continue;
+            }
+            const int64_t x = -((int64_t)s + 1);
+            if (x >= n) return fail(HKV_ERANGE, "trt_partition: call %d reads the output of call %lld (of %d)", c, (long long)x, n);
+            omega += len_out[x];
+            const int a = find(c), b = find((int)x);
+            if (a != b) comp[std::max(a, b)] = std::min(a, b);
+        }
+        cost[c] = (int64_t)len_out[c] * omega + (int64_t)len_out[c] * (len_out[c] + 1) / 2;
+    }
+    std::vector<int64_t> group_cost(n, 0);
+    std::vector<int32_t> roots;
+    for (int c = 0; c < n; ++c) {
+        const int g = find(c);
+        if (g == c) roots.push_back(c);
+        group_cost[g] += cost[c];
+    }
+    std::stable_sort(roots.begin(), roots.end(), [&](int a, int b) { return group_cost[a] > group_cost[b]; });  // ties: smaller first call
+    std::vector<int64_t> load(n_workers, 0);
+    std::vector<int32_t> of_group(n, 0);
+    for (int g : roots) {
+        int w = 0;
+        for (int i = 1; i < n_workers; ++i)
+            if (load[i] < load[w]) w = i;
+        of_group[g] = w;
+        load[w] += group_cost[g];
+    }
+    for (int c = 0; c < n; ++c) worker[c] = of_group[find(c)];
+    return HKV_OK;
+}
+
+namespace {
+
+// first node below the root on the call's path (its leaf for an empty prompt): the static prompt its operator
+// family shares
+int static_prompt_node(const hkv_trt &t, int c) {
+    int v = t.leaf_of_call[c];
+    while (t.parent[v] > 0) v = t.parent[v];
+    return v;
+}
+
+int check_orders(const hkv_trt *t, const int32_t *indptr, const int32_t *calls, int32_t n_workers, const char *who) {
+    if (!t || !indptr || n_workers < 1) return fail(HKV_EINVAL, "%s: bad argument", who);
+    const int n = (int)t->len_out.size();
+    if (indptr[0] != 0 || indptr[n_workers] != n) return fail(HKV_EINVAL, "%s: the orders do not hold %d calls", who, n);
+    if (n > 0 && !calls) return fail(HKV_EINVAL, "%s: null order", who);
+    for (int i = 0; i < n_workers; ++i)
+        if (indptr[i + 1] < indptr[i]) return fail(HKV_EINVAL, "%s: indptr decreases", who);
+    std::vector<char> seen(n, 0);
+    for (int k = 0; k < n; ++k) {
+        if (calls[k] < 0 || calls[k] >= n || seen[calls[k]]) return fail(HKV_ERANGE, "%s: the orders are no partition of the calls (entry %d)", who, k);
+        seen[calls[k]] = 1;
+    }
+    return HKV_OK;
+}
+
+}  // namespace
+
+// A worker's final schedule as inner sequences: the calls under one static prompt, in the order of sigma,
+// released (appended to the worker's list) when the last of them has been emitted.
+extern "C" int trt_nested(const hkv_trt *t, const int32_t *sigma_indptr, const int32_t *sigma, int32_t n_workers,
+                          int32_t *seq_indptr, int32_t *seq_begin, int32_t *nested) {
+    if (int rc = check_orders(t, sigma_indptr, sigma, n_workers, "trt_nested")) return rc;
+    if (!seq_indptr || !seq_begin) return fail(HKV_EINVAL, "trt_nested: null output");
+    const int n = (int)t->len_out.size();
+    if (n > 0 && !nested) return fail(HKV_EINVAL, "trt_nested: null output");
+    const int n_nodes = (int)t->parent.size();
+    std::vector<int32_t> total(n_nodes), have(n_nodes);
+    std::vector<std::vector<int32_t>> buffer(n_nodes);
+    int n_seq = 0, pos = 0;
+    seq_indptr[0] = 0;
+    for (int i = 0; i < n_workers; ++i) {
+        std::fill(total.begin(), total.end(), 0);
+        for (int k = sigma_indptr[i]; k < sigma_indptr[i + 1]; ++k) ++total[static_prompt_node(*t, sigma[k])];
+        for (int k = sigma_indptr[i]; k < sigma_indptr[i + 1]; ++k) {
+            const int g = static_prompt_node(*t, sigma[k]);
+            buffer[g].push_back(sigma[k]);
+            if ((int)buffer[g].size() == total[g]) {  // the family is complete on this worker: release it
+                seq_begin[n_seq++] = pos;
+                for (int32_t c : buffer[g]) nested[pos++] = c;
+                buffer[g].clear();
+            }
+        }
+        seq_indptr[i + 1] = n_seq;
+    }
+    seq_begin[n_seq] = pos;
+    return HKV_OK;
+}
+
+// Best-effort execution of per-worker priority orders under the cost model: every worker with calls left
+// names the first call of its order whose dependencies have all been issued; the worker whose candidate can
+// start earliest (ties: lower number) issues it.
+extern "C" int trt_run_soft(const hkv_trt *t, const int32_t *order_indptr, const int32_t *order, int32_t n_workers,
+                            int64_t capacity, int32_t *sigma, int64_t *B, int64_t *C, int64_t *T) {
+    if (int rc = check_orders(t, order_indptr, order, n_workers, "trt_run_soft")) return rc;
+    if (!T || capacity < 1) return fail(HKV_EINVAL, "trt_run_soft: bad argument");
+    const int n = (int)t->len_out.size();
+    if (n > 0 && !sigma) return fail(HKV_EINVAL, "trt_run_soft: null sigma");
+    std::vector<char> issued(n, 0);
+    std::vector<int64_t> b(n, 0), cc(n, 0), free_at(n_workers, 0);
+    std::vector<std::vector<int32_t>> left(n_workers);
+    std::vector<int32_t> n_run(n_workers, 0), last(n_workers, -1);
+    for (int i = 0; i < n_workers; ++i) left[i].assign(order + order_indptr[i], order + order_indptr[i + 1]);
+    for (int step = 0; step < n; ++step) {
+        int best_w = -1, best_c = -1, best_k = -1;
+        int64_t best_b = 0;
+        for (int i = 0; i < n_workers; ++i) {
+            int cand = -1, at = -1;
+            for (int k = 0; k < (int)left[i].size() && cand < 0; ++k) {
+                bool ok = true;
+                for (int x : t->deps[left[i][k]]) ok = ok && issued[x];
+                if (ok) {
+                    cand = left[i][k];
+                    at = k;
+                }
+            }
+            if (cand < 0) continue;
+            int64_t start = free_at[i];
+            for (int x : t->deps[cand]) start = std::max(start, cc[x] + capacity * t->len_out[x]);
+            if (best_w < 0 || start < best_b) {
+                best_w = i;
+                best_c = cand;
+                best_k = at;
+                best_b = start;
+            }
+        }
+        if (best_w < 0) return fail(HKV_ETREE, "trt_run_soft: dependency cycle");
+        b[best_c] = best_b;
+        cc[best_c] = best_b + call_usage(*t, last[best_w], best_c);
+        free_at[best_w] = cc[best_c];
+        issued[best_c] = 1;
+        sigma[order_indptr[best_w] + n_run[best_w]++] = best_c;
+        last[best_w] = best_c;
+        left[best_w].erase(left[best_w].begin() + best_k);
+    }
+    int64_t mx = 0;
+    for (int c = 0; c < n; ++c) mx = std::max(mx, cc[c]);
+    if (B && n) memcpy(B, b.data(), n * sizeof(int64_t));
+    if (C && n) memcpy(C, cc.data(), n * sizeof(int64_t));
+    *T = mx;
+    return HKV_OK;
+}

@@ -413,6 +413,7 @@ def workflows():
     ws += [wl.random_workflow(100 + s, n_calls=40, vocab=3, max_len=14, n_workers=2) for s in range(4)]
     ws += [wl.workflow_map_reduce(n_workers=2), wl.workflow_debate(n_workers=2), wl.workflow_reflect(n_workers=1)]
     ws += [wl.workflow_debate(n_queries=5, n_agents=4, rounds=3, n_workers=3)]
+    ws += [wl.workflow_iterative(n_workers=2), wl.workflow_parallel(n_workers=2), wl.workflow_parallel(5, 7, 6, n_workers=3)]
     e = wl.Workflow("empty")
     ws.append(e)
     one = wl.Workflow("one_empty_template")
@@ -444,8 +445,39 @@ def test_library_tree_usage_evaluate_schedule_bit_exact(hkv, w):
             s, B, C, T = O.cache_aware_schedule(t, n_workers, cap)
             gs, gB, gC, gT = hkv.trt_schedule(h, n_workers, cap)
             assert gs == s and gB.tolist() == B and gC.tolist() == C and gT == T
+            # the nested form of that schedule and its best-effort execution
+            nested = O.nested_sequences(t, s)
+            assert hkv.trt_nested(h, s) == nested
+            prio = [[c for seq in inner for c in seq] for inner in nested]
+            rs, B, C, T = O.run_soft_schedule(t, prio, cap)
+            gs, gB, gC, gT = hkv.trt_run_soft(h, prio, cap)
+            assert gs == rs and gB.tolist() == B and gC.tolist() == C and gT == T
+        # a priority order that ignores the dependencies altogether
+        back = [[c for c in reversed(topo) if w.worker[c] == i] for i in range(n_workers)]
+        rs, B, C, T = O.run_soft_schedule(t, back, 9)
+        gs, gB, gC, gT = hkv.trt_run_soft(h, back, 9)
+        assert gs == rs and gB.tolist() == B and gC.tolist() == C and gT == T
+        for m in (1, 2, 3, 5):
+            assert hkv.trt_partition(w.templates, w.len_out, m).tolist() == O.partition_workflow(calls_of(w), m)
     finally:
         hkv.trt_destroy(h)
+
+
+def test_library_partition_then_schedule_end_to_end(hkv):
+    """The whole procedure of the scheduling algorithm through the library: partition, tree, recursion, nested
+    sequences, best-effort execution; two workers halve the total token step of a batch of independent queries
+    (up to the imbalance of one query)."""
+    w = wl.workflow_parallel(n_queries=6, n_experts=3, n_chunks=2)
+    T = {}
+    for m in (1, 2):
+        worker = hkv.trt_partition(w.templates, w.len_out, m)
+        h = hkv.trt_build(w.templates, w.len_out, worker)
+        sigma, _, _, _ = hkv.trt_schedule(h, m, 64)
+        prio = [[c for seq in inner for c in seq] for inner in hkv.trt_nested(h, sigma)]
+        real, B, C, T[m] = hkv.trt_run_soft(h, prio, 64)
+        assert sorted(c for s_ in real for c in s_) == list(range(w.n_calls))
+        hkv.trt_destroy(h)
+    assert T[2] < 0.62 * T[1]
 
 
 def test_library_scheduling_errors(hkv):
@@ -458,8 +490,20 @@ def test_library_scheduling_errors(hkv):
     with pytest.raises(hkv.HkvError) as e:
         hkv.trt_build([[1]], [-1])
     assert e.value.code == -2                                    # ERANGE
+    with pytest.raises(hkv.HkvError) as e:
+        hkv.trt_partition([[1], [-9]], [1, 1], 2)
+    assert e.value.code == -2                                    # ERANGE: output of a call outside the batch
+    with pytest.raises(hkv.HkvError) as e:
+        hkv.trt_partition([[1]], [1], 0)
+    assert e.value.code == -1
     h = hkv.trt_build([[1, 2], [3, -1]], [5, 1])
     try:
+        assert hkv.trt_run_soft(h, [[1, 0]], 10)[0] == [[0, 1]]      # the order is repaired, not rejected
+        for bad in ([[0]], [[0, 0]], [[0, 5]]):
+            with pytest.raises(hkv.HkvError):
+                hkv.trt_nested(h, bad)
+            with pytest.raises(hkv.HkvError):
+                hkv.trt_run_soft(h, bad, 10)
         with pytest.raises(hkv.HkvError) as e:
             hkv.trt_evaluate(h, [[1, 0]], 10)
         assert e.value.code == -4                                # contradicts the dependencies
