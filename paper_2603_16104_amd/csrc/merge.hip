@@ -56,6 +56,7 @@ __global__ __launch_bounds__(64 * kRowsPerBlock) void lse_merge_kernel(const flo
 // requested together, so a row costs one memory round trip after its count (kUnroll is 8, or 16 for
 // forests whose paths collect more than 8 partials).
 constexpr int kDenseRowsPerBlock = 8;
+constexpr int kManyRows = 16384;  // from here on a half wavefront merges four rows
 
 // four consecutive values of a partial, as floats
 template <bool PB16>
@@ -71,13 +72,11 @@ __device__ __forceinline__ f32x4 load_part4(const void *o_parts, size_t elem) {
 }
 
 template <int OUT_DT, int kUnroll, bool PB16>
-__global__ __launch_bounds__(32 * kDenseRowsPerBlock) void lse_merge_dense_kernel(
-    const void *__restrict__ o_parts, const float *__restrict__ lse_parts, const int32_t *__restrict__ part_count,
-    int32_t rows_per_count, int32_t max_parts, int32_t n_rows, void *__restrict__ out, float *__restrict__ lse_out,
-    const int32_t *__restrict__ out_rows, const float *__restrict__ down_parts) {
-    const int row = blockIdx.x * kDenseRowsPerBlock + (threadIdx.x >> 5);
-    const int l = threadIdx.x & 31;
-    if (row >= n_rows) return;
+__device__ __forceinline__ void merge_dense_row(const void *__restrict__ o_parts, const float *__restrict__ lse_parts,
+                                                const int32_t *__restrict__ part_count, int32_t rows_per_count,
+                                                int32_t max_parts, int row, int l, void *__restrict__ out,
+                                                float *__restrict__ lse_out, const int32_t *__restrict__ out_rows,
+                                                const float *__restrict__ down_parts) {
     const int cnt = min(part_count[row / rows_per_count], max_parts);
     const size_t base = (size_t)row * max_parts;
     const float *lp = lse_parts + base;
@@ -149,6 +148,24 @@ __global__ __launch_bounds__(32 * kDenseRowsPerBlock) void lse_merge_dense_kerne
     if (lse_out && l == 0) lse_out[dst] = (M == -INFINITY) ? -INFINITY : M + fast_log2(z) * kLn2;
 }
 
+// kRowsPerLane rows per half wavefront (rows row0, row0 + stride, ...): large batches run four, whose loads the
+// compiler issues together, on a quarter of the workgroups.
+template <int OUT_DT, int kUnroll, bool PB16, int kRowsPerLane>
+__global__ __launch_bounds__(32 * kDenseRowsPerBlock) void lse_merge_dense_kernel(
+    const void *__restrict__ o_parts, const float *__restrict__ lse_parts, const int32_t *__restrict__ part_count,
+    int32_t rows_per_count, int32_t max_parts, int32_t n_rows, void *__restrict__ out, float *__restrict__ lse_out,
+    const int32_t *__restrict__ out_rows, const float *__restrict__ down_parts) {
+    const int row0 = (blockIdx.x * kRowsPerLane) * kDenseRowsPerBlock + (threadIdx.x >> 5);
+    const int l = threadIdx.x & 31;
+#pragma unroll
+    for (int r = 0; r < kRowsPerLane; ++r) {
+        const int row = row0 + r * kDenseRowsPerBlock;
+        if (row < n_rows)
+            merge_dense_row<OUT_DT, kUnroll, PB16>(o_parts, lse_parts, part_count, rows_per_count, max_parts, row, l, out,
+                                                   lse_out, out_rows, down_parts);
+    }
+}
+
 }  // namespace
 
 hipError_t launch_lse_merge_dense(const void *o_parts, const float *lse_parts, const int32_t *part_count,
@@ -156,23 +173,35 @@ hipError_t launch_lse_merge_dense(const void *o_parts, const float *lse_parts, c
                                   int32_t out_dtype, float *lse_out, hipStream_t s, hipEvent_t ev_begin,
                                   hipEvent_t ev_end, const int32_t *out_rows, const float *down_parts) {
     if (n_rows <= 0) return hipSuccess;
-    dim3 grid((n_rows + kDenseRowsPerBlock - 1) / kDenseRowsPerBlock), block(32 * kDenseRowsPerBlock);
+    const bool many = n_rows >= kManyRows && max_parts <= 8;
+    const int per_block = kDenseRowsPerBlock * (many ? 4 : 1);
+    dim3 grid((n_rows + per_block - 1) / per_block), block(32 * kDenseRowsPerBlock);
     auto go = [&](auto kernel) {
         hipExtLaunchKernelGGL(kernel, grid, block, 0, s, ev_begin, ev_end, 0, o_parts, lse_parts, part_count,
                               rows_per_count, max_parts, n_rows, out, lse_out, out_rows, down_parts);
     };
     auto pick = [&](auto pb16) {
         constexpr bool PB = decltype(pb16)::value;
-        if (max_parts <= 8) {
+        if (many && max_parts <= 2) {
             if (out_dtype == 0)
-                go(lse_merge_dense_kernel<0, 8, PB>);
+                go(lse_merge_dense_kernel<0, 2, PB, 4>);
             else
-                go(lse_merge_dense_kernel<2, 8, PB>);
+                go(lse_merge_dense_kernel<2, 2, PB, 4>);
+        } else if (many) {
+            if (out_dtype == 0)
+                go(lse_merge_dense_kernel<0, 8, PB, 4>);
+            else
+                go(lse_merge_dense_kernel<2, 8, PB, 4>);
+        } else if (max_parts <= 8) {
+            if (out_dtype == 0)
+                go(lse_merge_dense_kernel<0, 8, PB, 1>);
+            else
+                go(lse_merge_dense_kernel<2, 8, PB, 1>);
         } else {
             if (out_dtype == 0)
-                go(lse_merge_dense_kernel<0, 16, PB>);
+                go(lse_merge_dense_kernel<0, 16, PB, 1>);
             else
-                go(lse_merge_dense_kernel<2, 16, PB>);
+                go(lse_merge_dense_kernel<2, 16, PB, 1>);
         }
     };
     if (down_parts)

@@ -250,13 +250,15 @@ def test_lse_merge_kernel(gpu, oracle):
         assert (got[3] == 0).all() and (got[7] == 0).all()
 
 
-@pytest.mark.parametrize("max_parts", [3, 8, 11, 16, 21])
-def test_lse_merge_dense_kernel(gpu, oracle, max_parts):
-    """Slot counts below, at and beyond the two unrolled depths of the kernel (8 and 16)."""
+@pytest.mark.parametrize("max_parts,n_groups", [(3, 37), (8, 37), (11, 37), (16, 37), (21, 37),
+                                                (1, 4200), (2, 4200), (3, 4200), (8, 4200), (11, 4200)])
+def test_lse_merge_dense_kernel(gpu, oracle, max_parts, n_groups):
+    """Slot counts below, at and beyond the unrolled depths of the kernel (2, 8 and 16), in a small batch and in one
+    beyond 16 384 rows, where a half wavefront merges four rows (the last workgroup's rows run out part-way)."""
     import torch
     from paper_2603_16104_amd import binding as hkv
     rng = np.random.default_rng(8)
-    rows_per_count, n_groups = 4, 37
+    rows_per_count = 4
     n_rows = rows_per_count * n_groups - 2                 # last group is ragged
     counts = rng.integers(0, max_parts + 1, size=n_groups).astype(np.int32)
     counts[0], counts[1] = 0, max_parts
