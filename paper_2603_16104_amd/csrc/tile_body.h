@@ -487,7 +487,9 @@ __device__ __forceinline__ void body(const TileArgs &a, char *lds, int first, in
     // complete before iteration j+1 and a request has two iterations to land; K stage (j-1) % 4 and
     // V stage (j-2) % 4 are free from the barrier at the end of iteration j-1 on, which is where
     // iteration j's requests go.  One barrier per iteration.
-    for (int j = 0; j < n_blk; ++j) {
+    // fp8: kq_now / vq_now hold {K(j+2), V(j+1)} on entry and {K(j+4), V(j+3)} on exit; the other pair of
+    // the register queue holds {K(j+3), V(j+2)} throughout (the two pairs swap roles every iteration).
+    auto iteration = [&](int j, u32x4 &kq_now, u32x4 &vq_now) {
         if constexpr (!FP8) {
             if (((j + 3) & 15) == 0) {
                 if ((j + 3) * 4 - id_base >= kIdSlots && (j + 3) * 4 <= last_page) {  // id slots exhausted (rare)
@@ -505,8 +507,8 @@ __device__ __forceinline__ void body(const TileArgs &a, char *lds, int first, in
         if (j > 0 && j * KB + 31 > wave_min_pos) mask_scores(sa, t);
         phase(sa, sb, wb, wa, t, k_tile(t + 1), k_tile(t + 2), v_tile(t > 0 ? t - 1 : 0), v_tile(t), [&]() {
             if constexpr (FP8) {  // widen {K(j+2), V(j+1)}: visible to everyone after this iteration's barrier
-                store_k_fp8(kq[0], (j + 2) % kStages);
-                store_v_fp8(vq[0], j + 1, (j + 1) % kStages);
+                store_k_fp8(kq_now, (j + 2) % kStages);
+                store_v_fp8(vq_now, j + 1, (j + 1) % kStages);
             } else {
                 issue_k_part(j + 3, 0);
                 issue_v_part(j + 2, 0);
@@ -514,11 +516,9 @@ __device__ __forceinline__ void body(const TileArgs &a, char *lds, int first, in
         });
         if (j * KB + 63 > wave_min_pos) mask_scores(sb, t + 1);
         phase(sb, sa, wa, wb, t + 1, k_tile(t + 2), k_tile(t + 3), v_tile(t), v_tile(t + 1), [&]() {
-            if constexpr (FP8) {  // the queue moves up; the request that takes the free place has two iterations to land
-                kq[0] = kq[1];
-                vq[0] = vq[1];
-                kq[1] = fetch_fp8(kbase, j + 4);
-                vq[1] = fetch_fp8(vbase, j + 3);
+            if constexpr (FP8) {  // the request that takes the free place has two iterations to land
+                kq_now = fetch_fp8(kbase, j + 4);
+                vq_now = fetch_fp8(vbase, j + 3);
             } else {
                 issue_k_part(j + 3, kParts - 1);
                 issue_v_part(j + 2, kParts - 1);
@@ -537,6 +537,14 @@ __device__ __forceinline__ void body(const TileArgs &a, char *lds, int first, in
                 __syncthreads();
             }
         }
+    };
+    if constexpr (FP8) {
+        for (int j = 0; j < n_blk; j += 2) {
+            iteration(j, kq[0], vq[0]);
+            if (j + 1 < n_blk) iteration(j + 1, kq[1], vq[1]);
+        }
+    } else {
+        for (int j = 0; j < n_blk; ++j) iteration(j, kq[0], vq[0]);
     }
     // drain: O^T += V^T P^T of the last step (vf holds its operands 0-3, wb its probabilities)
     {
