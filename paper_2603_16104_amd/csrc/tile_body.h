@@ -116,7 +116,7 @@ struct TileArgs {
 // FP8: the pool holds e4m3 codes with a scale per 16-token block and head (decode items only).
 // lds: kLdsBytes of the workgroup's LDS, 16-byte aligned.  The workgroup (kThreads threads, thread index
 // threadIdx.x) runs tiles first, first + stride, ... (prefill runs one: stride is not used).
-constexpr int kLdsBytes = 2 * kStages * kTileBytes + kIdSlots * 4 + 3 * kScaleSlots * 4 + 16;
+constexpr int kLdsBytes = 2 * kStages * kTileBytes + kIdSlots * 4 + kScaleSlots * 16 + 16;
 
 template <bool DECODE, bool FP8>
 __device__ __forceinline__ void body(const TileArgs &a, char *lds, int first, int stride) {
@@ -124,9 +124,11 @@ __device__ __forceinline__ void body(const TileArgs &a, char *lds, int first, in
     char(*sK)[kTileBytes] = reinterpret_cast<char(*)[kTileBytes]>(lds);
     char(*sV)[kTileBytes] = reinterpret_cast<char(*)[kTileBytes]>(lds + kStages * kTileBytes);
     int *sIds = reinterpret_cast<int *>(lds + 2 * kStages * kTileBytes);  // page ids of the keys in use (a window of the block table row)
-    // fp8: per page of the item c * K scale, log2(V scale), 1 / V scale
-    float *sCk = reinterpret_cast<float *>(sIds + kIdSlots), *sLv = sCk + kScaleSlots, *sIv = sLv + kScaleSlots;
-    int &sBail = *reinterpret_cast<int *>(sIv + kScaleSlots);
+    // fp8: per page of the item {c * K scale, log2(V scale), 1 / V scale, -}: one 16-byte read per page, and the
+    // two pages of a 32-token step sit side by side (entries behind the item's last page repeat it, so a step
+    // needs no clamp)
+    f32x4 *sScale = reinterpret_cast<f32x4 *>(sIds + kIdSlots);
+    int &sBail = *reinterpret_cast<int *>(sScale + kScaleSlots);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -338,10 +340,10 @@ __device__ __forceinline__ void body(const TileArgs &a, char *lds, int first, in
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             if constexpr (FP8) {
-                const int pg = min(2 * st + i, last_page);
-                r.ck[i] = sCk[pg];
-                r.lv[i] = sLv[pg];
-                r.iv[i] = sIv[pg];
+                const f32x4 e = sScale[2 * st + i];
+                r.ck[i] = e[0];
+                r.lv[i] = e[1];
+                r.iv[i] = e[2];
             } else {
                 r.ck[i] = c;
                 r.lv[i] = 0.f;
@@ -368,12 +370,10 @@ __device__ __forceinline__ void body(const TileArgs &a, char *lds, int first, in
     if (tid == 0) sBail = 0;
     fill_ids(0);
     if constexpr (FP8) {
-        for (int p = tid; p <= last_page; p += kThreads) {
-            const size_t id = (size_t)bt[p];
+        for (int p = tid; p < min(4 * n_blk, kScaleSlots); p += kThreads) {  // every page of every 64-token block
+            const size_t id = (size_t)bt[min(p, last_page)];
             const float vs = a.pool.v_scale[id * Hkv + kv_head];
-            sCk[p] = c * a.pool.k_scale[id * Hkv + kv_head];
-            sLv[p] = fast_log2(vs);
-            sIv[p] = 1.0f / vs;
+            sScale[p] = f32x4{c * a.pool.k_scale[id * Hkv + kv_head], fast_log2(vs), 1.0f / vs, 0.f};
         }
     }
     __syncthreads();
