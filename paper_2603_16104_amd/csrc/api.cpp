@@ -717,8 +717,9 @@ static void plan_items(hkv_decode_plan &pl) {
     pl.tile_items.clear();
     pl.tile_workgroups = 0;
     int tile_chunk = kMaxTileItemTokens;
+    double step_seconds = 0;  // what streaming all the bytes of the step takes
     {
-        double tile_flop = 0, other_bytes = 0;
+        double tile_flop = 0, other_bytes = 0, tile_bytes = 0;
         int64_t tile_units = 0, tile_tokens_max = 0;
         const double bytes_per_token = 2.0 * HKV_HEAD_DIM * (pl.pool->d.dtype == HKV_FP8_E4M3 ? 1 : 2);
         for (int v = 0; v < n_nodes; ++v) {
@@ -728,10 +729,12 @@ static void plan_items(hkv_decode_plan &pl) {
                 tile_flop += 4.0 * HKV_HEAD_DIM * pl.nodes[v].n_tokens * (double)R * pl.num_q_heads;
                 tile_units += (int64_t)((R + req_per_tile - 1) / req_per_tile) * Hkv;
                 tile_tokens_max = std::max<int64_t>(tile_tokens_max, pl.nodes[v].n_tokens);
+                tile_bytes += bytes_per_token * pl.nodes[v].n_tokens * Hkv;
             } else {
                 other_bytes += bytes_per_token * pl.nodes[v].n_tokens * Hkv;
             }
         }
+        step_seconds = (other_bytes + tile_bytes) / 5.6e12;
         if (tile_units > 0) {
             const int n_cu = chip.n_cu;
             int wgs = n_cu;
@@ -823,9 +826,19 @@ static void plan_items(hkv_decode_plan &pl) {
     }
     std::stable_sort(pl.tile_items.begin(), pl.tile_items.end(),
                      [](const DecodeItem &x, const DecodeItem &y) { return x.n_tokens > y.n_tokens; });
-    // a workgroup per item while that leaves a quarter of the chip to the other kernel's first workgroups
-    if (opt.tile_workgroups == 0 && (int)pl.tile_items.size() <= chip.n_cu - 64)
-        pl.tile_workgroups = (int32_t)pl.tile_items.size();
+    // While the items leave a quarter of the chip to the other items' first workgroups: as few persistent
+    // workgroups as finish their chain of items within the step (a tile item runs at about 5.5 TFLOP/s on its
+    // compute unit), in whole groups of 8 (one per XCD).  The items then hold few compute units for the whole
+    // step instead of many for a part of it, which the streaming items use better (c5: 64 workgroups of two
+    // items against 128 of one, step -2 %); a chain that outlasts the step would lengthen it, hence the margin.
+    if (opt.tile_workgroups == 0 && (int)pl.tile_items.size() <= chip.n_cu - 64) {
+        const int n_items = (int)pl.tile_items.size();
+        double item_seconds = 0;
+        for (const DecodeItem &it : pl.tile_items)
+            item_seconds = std::max(item_seconds, 4.0 * HKV_HEAD_DIM * it.n_tokens * (double)it.n_req * G / 5.5e12);
+        const int chain = std::max(1, (int)(step_seconds / item_seconds - 0.1));
+        pl.tile_workgroups = std::min(n_items, ((n_items + chain - 1) / chain + 7) / 8 * 8);
+    }
     pl.tile_workgroups = std::min<int32_t>(pl.tile_workgroups, (int32_t)pl.tile_items.size());
     pl.items.clear();
     pl.n_single = 0;

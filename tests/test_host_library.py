@@ -380,7 +380,8 @@ def test_many_row_and_few_row_items_are_dispatched_side_by_side():
 
 def test_large_many_row_share_goes_to_the_tile_kernel(oracle):
     """c5: the 16 roots (256 query rows per KV head, 137 GFLOP) become items of the 256-row tile: one request
-    group of 32 per root and KV head, the root's 8192 tokens in one item, a workgroup per item; the private
+    group of 32 per root and KV head, the root's 8192 tokens in one item, 64 persistent workgroups of two items
+    each (two items take about as long as streaming the step's bytes); the private
     leaves (8 rows each) are the other items, so both kinds go out as one launch unless the caller says
     otherwise.  c2 and c3 (2 and 9 GFLOP of such work) and plans with several query tokens per request have
     no tile items."""
@@ -393,7 +394,7 @@ def test_large_many_row_share_goes_to_the_tile_kernel(oracle):
     assert n_tile == 16 * 8 and len(items) == n_tile + 4096
     tiles = items[-n_tile:]
     assert (tiles[:, 4] == 32).all() and (tiles[:, 1] == 8192).all() and (tiles[:, 7] < 16).all()
-    assert hkv.hkv_decode_plan_tile_workgroups(plan) == 128 and hkv.hkv_decode_plan_is_fused(plan)
+    assert hkv.hkv_decode_plan_tile_workgroups(plan) == 64 and hkv.hkv_decode_plan_is_fused(plan)
     assert (items[:-n_tile, 4] == 1).all()
     hkv.hkv_decode_plan_destroy(plan)
     two = hkv.hkv_decode_plan_create_ex(pool, f.nodes, f.node_pages, f.req_leaf, w.num_q_heads, hkv.PLAN_HOST_ONLY, fused=-1,
