@@ -49,6 +49,8 @@
 #pragma once
 #include <hip/hip_ext.h>
 
+#include <type_traits>
+
 #include "hkv_device.h"
 
 namespace hkv {
@@ -240,15 +242,15 @@ __device__ __forceinline__ void body(const TileArgs &a, char *lds, int first, in
     // sequence are clamped: in bounds), so a request costs a lane read instead of a memory access.
     auto window = [&](int blk) { return sIds[min((blk & ~15) * 4 + lane, last_page) - id_base]; };
     int kwin = 0, vwin = 0;
-    auto issue_k_part = [&](int blk, int u) {  // K of block blk -> stage blk % kStages
+    auto issue_k_part = [&](int blk, int u, int st) {  // K of block blk -> stage st = blk % kStages
         const int pc = u * kWaves + wave, i = pc >> 2, cq = pc & 3;
         const int id = __builtin_amdgcn_readlane(kwin, (blk * 4 + i) & 63);
-        load_to_lds16(k_source(id, cq), lds_address(sK[blk % kStages] + i * 4096 + cq * 1024));
+        load_to_lds16(k_source(id, cq), lds_address(sK[st] + i * 4096 + cq * 1024));
     };
-    auto issue_v_part = [&](int blk, int u) {  // V of block blk -> stage blk % kStages
+    auto issue_v_part = [&](int blk, int u, int st) {  // V of block blk -> stage st = blk % kStages
         const int pc = u * kWaves + wave, i = pc >> 2, cq = pc & 3;
         const int id = __builtin_amdgcn_readlane(vwin, (blk * 4 + i) & 63);
-        load_to_lds16(v_source(id, cq), lds_address(sV[blk % kStages] + i * 4096 + cq * 1024));
+        load_to_lds16(v_source(id, cq), lds_address(sV[st] + i * 4096 + cq * 1024));
     };
     // Fallback path: K and V of block blk -> stage st, ids straight from LDS
     auto issue_block = [&](int blk, int st) {
@@ -396,16 +398,16 @@ __device__ __forceinline__ void body(const TileArgs &a, char *lds, int first, in
         kwin = window(0);
         vwin = kwin;
 #pragma unroll
-        for (int u = 0; u < kParts; ++u) issue_k_part(0, u);
+        for (int u = 0; u < kParts; ++u) issue_k_part(0, u, 0);
 #pragma unroll
         for (int u = 0; u < kParts; ++u) {
-            issue_k_part(1, u);
-            issue_v_part(0, u);
+            issue_k_part(1, u, 1);
+            issue_v_part(0, u, 0);
         }
 #pragma unroll
         for (int u = 0; u < kParts; ++u) {
-            issue_k_part(2, u);
-            issue_v_part(1, u);
+            issue_k_part(2, u, 2);
+            issue_v_part(1, u, 1);
         }
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(kLoadsPerBlock));  // all but the last group: K(0), K(1), V(0) are here
         __builtin_amdgcn_s_barrier();
@@ -489,7 +491,13 @@ __device__ __forceinline__ void body(const TileArgs &a, char *lds, int first, in
     // iteration j's requests go.  One barrier per iteration.
     // fp8: kq_now / vq_now hold {K(j+2), V(j+1)} on entry and {K(j+4), V(j+3)} on exit; the other pair of
     // the register queue holds {K(j+3), V(j+2)} throughout (the two pairs swap roles every iteration).
-    auto iteration = [&](int j, u32x4 &kq_now, u32x4 &vq_now) {
+    // The loop body exists four times, once per value of j % kStages, so that every LDS stage it touches is a
+    // compile-time offset of its reads and writes instead of an address computed per access.
+    auto iteration = [&](auto stage_tag, int j, u32x4 &kq_now, u32x4 &vq_now) {
+        constexpr int S = decltype(stage_tag)::value;  // j % kStages
+        // K resp. V tile of step 2j + c (c >= -1): block j + c / 2, half c % 2
+        auto kt = [&](int c) { return sK[(S + kStages + (c >> 1)) % kStages] + (c & 1) * 8192; };
+        auto vt = [&](int c) { return sV[(S + kStages + (c >> 1)) % kStages] + (c & 1) * 8192; };
         if constexpr (!FP8) {
             if (((j + 3) & 15) == 0) {
                 if ((j + 3) * 4 - id_base >= kIdSlots && (j + 3) * 4 <= last_page) {  // id slots exhausted (rare)
@@ -505,23 +513,23 @@ __device__ __forceinline__ void body(const TileArgs &a, char *lds, int first, in
         }
         const int t = 2 * j;
         if (j > 0 && j * KB + 31 > wave_min_pos) mask_scores(sa, t);
-        phase(sa, sb, wb, wa, t, k_tile(t + 1), k_tile(t + 2), v_tile(t > 0 ? t - 1 : 0), v_tile(t), [&]() {
+        phase(sa, sb, wb, wa, t, kt(1), kt(2), (S != 0 || j > 0) ? vt(-1) : vt(0), vt(0), [&]() {
             if constexpr (FP8) {  // widen {K(j+2), V(j+1)}: visible to everyone after this iteration's barrier
-                store_k_fp8(kq_now, (j + 2) % kStages);
-                store_v_fp8(vq_now, j + 1, (j + 1) % kStages);
+                store_k_fp8(kq_now, (S + 2) % kStages);
+                store_v_fp8(vq_now, j + 1, (S + 1) % kStages);
             } else {
-                issue_k_part(j + 3, 0);
-                issue_v_part(j + 2, 0);
+                issue_k_part(j + 3, 0, (S + 3) % kStages);
+                issue_v_part(j + 2, 0, (S + 2) % kStages);
             }
         });
         if (j * KB + 63 > wave_min_pos) mask_scores(sb, t + 1);
-        phase(sb, sa, wa, wb, t + 1, k_tile(t + 2), k_tile(t + 3), v_tile(t), v_tile(t + 1), [&]() {
+        phase(sb, sa, wa, wb, t + 1, kt(2), kt(3), vt(0), vt(1), [&]() {
             if constexpr (FP8) {  // the request that takes the free place has two iterations to land
                 kq_now = fetch_fp8(kbase, j + 4);
                 vq_now = fetch_fp8(vbase, j + 3);
             } else {
-                issue_k_part(j + 3, kParts - 1);
-                issue_v_part(j + 2, kParts - 1);
+                issue_k_part(j + 3, kParts - 1, (S + 3) % kStages);
+                issue_v_part(j + 2, kParts - 1, (S + 2) % kStages);
             }
         });
         // (after the last block the K operands come from stale stages: in bounds, never used)
@@ -533,18 +541,19 @@ __device__ __forceinline__ void body(const TileArgs &a, char *lds, int first, in
             __builtin_amdgcn_s_waitcnt(vmcnt_imm(kLoadsPerBlock));
             __syncthreads();
             if ((j + 1) * KB + KB > kv_len && (j + 1) * KB < kv_len) {  // V(j+1) holds the sequence end
-                zero_tail(j + 1, (j + 1) % kStages);
+                zero_tail(j + 1, (S + 1) % kStages);
                 __syncthreads();
             }
         }
     };
-    if constexpr (FP8) {
-        for (int j = 0; j < n_blk; j += 2) {
-            iteration(j, kq[0], vq[0]);
-            if (j + 1 < n_blk) iteration(j + 1, kq[1], vq[1]);
-        }
-    } else {
-        for (int j = 0; j < n_blk; ++j) iteration(j, kq[0], vq[0]);
+    for (int j = 0; j < n_blk; j += kStages) {
+        iteration(std::integral_constant<int, 0>{}, j, kq[0], vq[0]);
+        if (j + 1 >= n_blk) break;
+        iteration(std::integral_constant<int, 1>{}, j + 1, kq[1], vq[1]);
+        if (j + 2 >= n_blk) break;
+        iteration(std::integral_constant<int, 2>{}, j + 2, kq[0], vq[0]);
+        if (j + 3 >= n_blk) break;
+        iteration(std::integral_constant<int, 3>{}, j + 3, kq[1], vq[1]);
     }
     // drain: O^T += V^T P^T of the last step (vf holds its operands 0-3, wb its probabilities)
     {
