@@ -81,6 +81,13 @@ constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) |
 __device__ __forceinline__ void load_to_lds16(const void *gptr, uint32_t lds_base) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory");
 }
+// The same from a wavefront-uniform base plus a 32-bit offset per lane: the address arithmetic of the uniform
+// part stays on the scalar unit.
+__device__ __forceinline__ void load_to_lds16(const void *uniform_base, uint32_t lane_offset, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 ::"v"(lane_offset), "s"(uniform_base), "s"(lds_base)
+                 : "memory");
+}
 __device__ __forceinline__ uint32_t lds_address(const void *p) { return (uint32_t)(size_t)HKV_LDS_PTR(p); }
 
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
@@ -242,15 +249,19 @@ __device__ __forceinline__ void body(const TileArgs &a, char *lds, int first, in
     // sequence are clamped: in bounds), so a request costs a lane read instead of a memory access.
     auto window = [&](int blk) { return sIds[min((blk & ~15) * 4 + lane, last_page) - id_base]; };
     int kwin = 0, vwin = 0;
+    // (page and quarter are wavefront-uniform: only the lane's place inside the quarter is a vector operand)
+    const uint32_t v_in_quarter = (uint32_t)((lane >> 1) * 32 + ((v_unit ^ ((lane >> 4) & 1)) << 4));
     auto issue_k_part = [&](int blk, int u, int st) {  // K of block blk -> stage st = blk % kStages
         const int pc = u * kWaves + wave, i = pc >> 2, cq = pc & 3;
         const int id = __builtin_amdgcn_readlane(kwin, (blk * 4 + i) & 63);
-        load_to_lds16(k_source(id, cq), lds_address(sK[st] + i * 4096 + cq * 1024));
+        load_to_lds16(kbase + ((uint64_t)(uint32_t)id * page_stride + (uint32_t)(cq * 1024)), (uint32_t)k_in_quarter,
+                      lds_address(sK[st] + i * 4096 + cq * 1024));
     };
     auto issue_v_part = [&](int blk, int u, int st) {  // V of block blk -> stage st = blk % kStages
         const int pc = u * kWaves + wave, i = pc >> 2, cq = pc & 3;
         const int id = __builtin_amdgcn_readlane(vwin, (blk * 4 + i) & 63);
-        load_to_lds16(v_source(id, cq), lds_address(sV[st] + i * 4096 + cq * 1024));
+        load_to_lds16(vbase + ((uint64_t)(uint32_t)id * page_stride + (uint32_t)(cq * 1024)), v_in_quarter,
+                      lds_address(sV[st] + i * 4096 + cq * 1024));
     };
     // Fallback path: K and V of block blk -> stage st, ids straight from LDS
     auto issue_block = [&](int blk, int st) {
