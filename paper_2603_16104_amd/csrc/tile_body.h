@@ -297,7 +297,7 @@ __device__ __forceinline__ void body(const TileArgs &a, char *lds, int first, in
     // the bf16 image of stage st (V codes of slots past the item's end, which may be NaN, are cleared first)
     auto fetch_fp8 = [&](const char *base, int blk) {
         const int id = __builtin_amdgcn_readfirstlane(sIds[min(blk * 4 + f_i, last_page)]);  // (items never refill the window)
-        return ld16(base + ((uint64_t)(uint32_t)id * page_stride + (uint32_t)(f_q * 16)));
+        return ld16_stream(base + ((uint64_t)(uint32_t)id * page_stride + (uint32_t)(f_q * 16)));
     };
     auto store_k_fp8 = [&](u32x4 w, int st) {
         *reinterpret_cast<u32x4 *>(sK[st] + fk_dst0) = __builtin_bit_cast(u32x4, fp8x8_to_bf16x8(w[0], w[1]));
