@@ -831,7 +831,7 @@ static void plan_items(hkv_decode_plan &pl) {
     // compute unit), in whole groups of 8 (one per XCD).  The items then hold few compute units for the whole
     // step instead of many for a part of it, which the streaming items use better (c5: 64 workgroups of two
     // items against 128 of one, step -2 %); a chain that outlasts the step would lengthen it, hence the margin.
-    if (opt.tile_workgroups == 0 && (int)pl.tile_items.size() <= chip.n_cu - 64) {
+    if (opt.tile_workgroups == 0 && !pl.tile_items.empty() && (int)pl.tile_items.size() <= chip.n_cu - 64) {
         const int n_items = (int)pl.tile_items.size();
         double item_seconds = 0;
         for (const DecodeItem &it : pl.tile_items)
